@@ -1,0 +1,325 @@
+"""Plain CPU definition of MLMC gradient compression (Top-k ladder, fixed-point bit-wise ladder) and
+of the server aggregate.
+
+TEST INFRASTRUCTURE ONLY (see oracle/__init__.py): slow, written for checking by eye against the paper,
+never tuned, never used by the product path.
+
+What is computed, with the passages it follows:
+
+* Top-k compressor C_l = Top-k_l (Sec. 2.2 "Top-k"; Sec. 3.2): keep the k_l entries of largest
+  magnitude.  The order that decides "largest" is total: magnitude descending, ties (equal |g|,
+  including +0/-0) broken by the lower index.  It is realised by one full stable sort.
+* MLMC estimate (Eq. (5), Eq. (6), Alg. 2 worker steps): g~ = g^0 + (g^l - g^{l-1}) / p^l with l ~ p.
+  For a rank ladder k_0 < k_1 < ... < k_L the residual g^l - g^{l-1} is the band of entries with rank
+  in [k_{l-1}, k_l) (Sec. 3, remark after Alg. 2), and g^0 = C_0(g) is the band [0, k_0) (the paper's own
+  choice is k_0 = 0, i.e. g^0 = 0).
+* Adaptive probabilities (Lemma 3.4, Alg. 3): p^l = Delta^l / sum_l' Delta^l', Delta^l = ||g^l - g^{l-1}||_2.
+* Fixed probabilities of the geometric form of Lemma 3.3: p^l = 2^-l / (1 - 2^-L), l = 1..L.
+* Fixed-point bit-wise compressor (Sec. 2.2 "Fixed-point compressors", Sec. 3.1): entries are normalised
+  to magnitude < 1, written as sign + binary fraction, and C^F keeps the F most significant fraction bits.
+* Server aggregate (Alg. 2 / Alg. 3 "Server aggregates"): out = alpha * sum_i g~_i, alpha = 1/M for the mean.
+
+Readings where the paper is silent (each is also what the HIP library documents):
+
+* Norms: S_l = sum_{j in band l} g_j^2 is the exact real-number sum rounded once to fp64
+  (round-to-nearest-even); Delta^l = IEEE sqrt(S_l).  Exact sums do not depend on summation order.
+* Level draw: integer CDF thresholds T_l = floor(c_l * 2^32), c_l = p_1 + ... + p_l accumulated in fp64 in
+  level order, T_L = 2^32; x = one Philox4x32-10 word per (seed, step, worker); l = min{l : x < T_l}.
+* Weight: w = fp32(1.0 / p_l) (fp64 divide, then round to fp32); entry value = fp32(g_j * w), one multiply.
+  If p_l = 0 (reachable only through CDF rounding; the band is then the zero vector) w = 0.
+* All-zero residuals (sum of Delta = 0): uniform p_l = 1/L.
+* Bit-wise scale: power of two s = 2^e strictly above the row maximum, e = max(E_max, 1) - 126 with E_max the
+  largest biased exponent field in the row, so |g_j| / s < 1 and the fraction bits are exact.
+"""
+from __future__ import annotations
+
+import math
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+from .philox import level_uniform
+
+TWO32 = 4294967296.0
+
+
+# ----------------------------------------------------------------------------------------------
+# inputs
+# ----------------------------------------------------------------------------------------------
+def as_f32(row: np.ndarray) -> np.ndarray:
+    """A row as float32 values.  uint16 rows are bf16 bit patterns (exact upcast)."""
+    row = np.asarray(row)
+    if row.dtype == np.uint16:
+        return (row.astype(np.uint32) << np.uint32(16)).view(np.float32)
+    if row.dtype != np.float32:
+        raise TypeError("rows are float32 or uint16 (bf16 bits)")
+    return row
+
+
+def magnitude_keys(g32: np.ndarray) -> np.ndarray:
+    """|g| as an unsigned integer that orders like the magnitude: the fp32 bit pattern, sign cleared."""
+    return np.ascontiguousarray(g32).view(np.uint32) & np.uint32(0x7FFFFFFF)
+
+
+def magnitude_order(g32: np.ndarray) -> np.ndarray:
+    """Indices sorted by magnitude descending, equal magnitudes by index ascending (one stable sort)."""
+    inv = np.uint32(0x7FFFFFFF) - magnitude_keys(g32)
+    return np.argsort(inv, kind="stable")
+
+
+# ----------------------------------------------------------------------------------------------
+# level probabilities and the draw
+# ----------------------------------------------------------------------------------------------
+def geometric_p(L: int) -> List[float]:
+    """Lemma 3.3 form: p^l = 2^-l / (1 - 2^-L), l = 1..L (fp64)."""
+    return [math.ldexp(1.0, -l) / (1.0 - math.ldexp(1.0, -L)) for l in range(1, L + 1)]
+
+
+def adaptive_p(norms: Sequence[float]) -> List[float]:
+    """Lemma 3.4: p^l = Delta^l / sum Delta (sum in level order, fp64); uniform if every Delta is 0."""
+    total = 0.0
+    for x in norms:
+        total = total + float(x)
+    L = len(norms)
+    if total == 0.0:
+        return [1.0 / L] * L
+    return [float(x) / total for x in norms]
+
+
+def cdf_thresholds(p: Sequence[float]) -> List[int]:
+    L = len(p)
+    out, c = [], 0.0
+    for l in range(L):
+        c = c + float(p[l])
+        t = int(math.floor(c * TWO32))
+        out.append(min(max(t, 0), 1 << 32))
+    out[L - 1] = 1 << 32
+    return out
+
+
+def draw_level(p: Sequence[float], seed: int, step: int, worker: int) -> int:
+    """l in 1..L with probability p^l: inverse CDF of one 32-bit uniform (Alg. 2 "Sample l ~ p^l")."""
+    x = level_uniform(seed, step, worker)
+    for l, t in enumerate(cdf_thresholds(p), start=1):
+        if x < t:
+            return l
+    raise AssertionError("unreachable: T_L = 2^32")
+
+
+def level_weight(p_l: float) -> np.float32:
+    if p_l == 0.0:
+        return np.float32(0.0)
+    return np.float32(1.0 / float(p_l))
+
+
+# ----------------------------------------------------------------------------------------------
+# exact sums of squares
+# ----------------------------------------------------------------------------------------------
+SUMSQ_UNIT_LOG2 = -298  # squares are integer multiples of 2^-298 (smallest fp32 denormal squared)
+
+
+def exact_sumsq(g32: np.ndarray) -> int:
+    """sum_j g_j^2 as an exact integer count of 2^-298 units.
+
+    An fp32 magnitude is sig * 2^(E' - 150) with sig the 24-bit significand (no hidden bit for
+    denormals) and E' = max(E, 1), so g^2 = sig^2 * 2^(2(E' - 1)) units.  Entries are grouped by E' and the
+    integer squares (< 2^48) are summed in two 32-bit halves so that uint64 sums cannot overflow.
+    """
+    keys = magnitude_keys(g32)
+    if keys.size == 0:
+        return 0
+    E = (keys >> np.uint32(23)).astype(np.int64)
+    frac = (keys & np.uint32(0x7FFFFF)).astype(np.uint64)
+    sig = np.where(E > 0, frac | np.uint64(0x800000), frac)
+    Ep = np.maximum(E, 1)
+    sq = sig * sig
+    total = 0
+    for e in np.unique(Ep):
+        sel = sq[Ep == e]
+        lo = int(np.sum(sel & np.uint64(0xFFFFFFFF), dtype=np.uint64))
+        hi = int(np.sum(sel >> np.uint64(32), dtype=np.uint64))
+        total += ((hi << 32) + lo) << (2 * (int(e) - 1))
+    return total
+
+
+def units_to_f64(n_units: int) -> float:
+    """Exact integer count of 2^-298 units -> nearest fp64 (Python's int/int division is correctly rounded)."""
+    return n_units / (1 << 298)
+
+
+def level_norms_row(row: np.ndarray, ladder: Sequence[int]) -> Tuple[List[float], List[int]]:
+    """Delta^l = ||C_l(g) - C_{l-1}(g)||_2 for l = 1..L (Lemma 3.4), and the exact band sums S_0..S_L in units."""
+    g = as_f32(row)
+    order = magnitude_order(g)
+    L = len(ladder) - 1
+    units = [exact_sumsq(g[order[:ladder[0]]])]
+    for l in range(1, L + 1):
+        units.append(exact_sumsq(g[order[ladder[l - 1]:ladder[l]]]))
+    norms = [math.sqrt(units_to_f64(u)) for u in units[1:]]
+    return norms, units
+
+
+# ----------------------------------------------------------------------------------------------
+# Top-k MLMC
+# ----------------------------------------------------------------------------------------------
+def topk_dense(row: np.ndarray, k: int) -> np.ndarray:
+    """C(g) = Top-k(g) as a dense vector (Sec. 2.2)."""
+    g = as_f32(row)
+    out = np.zeros_like(g)
+    keep = magnitude_order(g)[:k]
+    out[keep] = g[keep]
+    return out
+
+
+def compress_topk_row(row: np.ndarray, ladder: Sequence[int], p: Optional[Sequence[float]],
+                      seed: int, step: int, worker: int, force_level: Optional[int] = None):
+    """One worker's MLMC Top-k message (Alg. 2 / Alg. 3 worker steps).
+
+    p = None selects the adaptive probabilities of Lemma 3.4 computed from this row.
+    Returns dict(level, weight, idx uint32 ascending, val float32, norms list[L], p list[L]).
+    """
+    g = as_f32(row)
+    d = g.size
+    L = len(ladder) - 1
+    assert 0 <= ladder[0] and all(ladder[i] < ladder[i + 1] for i in range(L)) and ladder[L] <= d
+    order = magnitude_order(g)
+    norms = None
+    if p is None:
+        norms, _ = level_norms_row(row, ladder)
+        p = adaptive_p(norms)
+    p = [float(x) for x in p]
+    level = draw_level(p, seed, step, worker) if force_level is None else int(force_level)
+    w = level_weight(p[level - 1])
+    base = order[:ladder[0]]
+    band = order[ladder[level - 1]:ladder[level]]
+    in_band = np.zeros(d, dtype=bool)
+    in_band[band] = True
+    idx = np.sort(np.concatenate([base, band])).astype(np.uint32)
+    val = g[idx].copy()
+    sel = in_band[idx]
+    val[sel] = val[sel] * w          # one fp32 multiply per band entry
+    return dict(level=level, weight=w, idx=idx, val=val.astype(np.float32), norms=norms, p=p)
+
+
+def compress_topk(G: np.ndarray, ladder, p, seed: int, step: int, norms_override=None):
+    """All M rows.  Row i is worker i.  p: list[L] shared by all rows, or None (adaptive).
+    norms_override[i] (optional) replaces the oracle's own Delta for row i in the adaptive case."""
+    msgs = []
+    for i in range(G.shape[0]):
+        pi = p
+        if p is None and norms_override is not None:
+            pi = adaptive_p(norms_override[i])
+        msgs.append(compress_topk_row(G[i], ladder, pi, seed, step, i))
+    return msgs
+
+
+def sparse_to_dense(idx: np.ndarray, val: np.ndarray, d: int) -> np.ndarray:
+    out = np.zeros(d, dtype=np.float32)
+    out[idx] = val
+    return out
+
+
+# ----------------------------------------------------------------------------------------------
+# fixed-point bit-wise MLMC
+# ----------------------------------------------------------------------------------------------
+def bits_scale_exponent(g32: np.ndarray) -> int:
+    """e with s = 2^e > max|g| and |g|/s < 1: e = max(E_max, 1) - 126 (E_max = largest exponent field)."""
+    keys = magnitude_keys(g32)
+    Emax = int(keys.max() >> np.uint32(23)) if keys.size else 0
+    return max(Emax, 1) - 126
+
+
+def fixed_point_digits(g32: np.ndarray, e: int, Q: int) -> np.ndarray:
+    """m_j = floor(|g_j| / 2^e * 2^Q): the first Q fraction bits of the normalised magnitude (Sec. 3.1)."""
+    a = np.abs(g32.astype(np.float64))
+    return np.floor(np.ldexp(a, Q - e)).astype(np.uint64)
+
+
+def bits_truncate_dense(row: np.ndarray, F: int, Q: int) -> np.ndarray:
+    """C^F(g): keep the F most significant fraction bits (out of the Q considered), as float64 values."""
+    g = as_f32(row)
+    e = bits_scale_exponent(g)
+    m = fixed_point_digits(g, e, Q)
+    kept = (m >> np.uint64(Q - F)).astype(np.float64)
+    return np.where(np.signbit(g), -1.0, 1.0) * np.ldexp(kept, e - F)
+
+
+def pack_plane(bits: np.ndarray) -> np.ndarray:
+    """bool[d] -> uint64[ceil(d/64)], word w bit b <-> element 64 w + b, pad bits zero."""
+    d = bits.size
+    nw = (d + 63) // 64
+    padded = np.zeros(nw * 64, dtype=np.uint8)
+    padded[:d] = bits
+    return np.packbits(padded, bitorder="little").view("<u8").astype(np.uint64)
+
+
+def unpack_plane(words: np.ndarray, d: int) -> np.ndarray:
+    return np.unpackbits(words.astype("<u8").view(np.uint8), bitorder="little")[:d].astype(bool)
+
+
+def compress_bits_row(row: np.ndarray, F: Sequence[int], p: Sequence[float], seed: int, step: int,
+                      worker: int, force_level: Optional[int] = None):
+    """One worker's fixed-point MLMC message: level, scale exponent, sign plane, base-field planes
+    (F_0 of them, LSB first), level-field planes (F_l - F_{l-1} of them, LSB first)."""
+    g = as_f32(row)
+    L = len(F) - 1
+    Q = F[L]
+    assert 0 <= F[0] and all(F[i] < F[i + 1] for i in range(L)) and Q <= 24
+    e = bits_scale_exponent(g)
+    m = fixed_point_digits(g, e, Q)
+    level = draw_level(p, seed, step, worker) if force_level is None else int(force_level)
+    width = F[level] - F[level - 1]
+    field = (m >> np.uint64(Q - F[level])) & np.uint64((1 << width) - 1)
+    base = (m >> np.uint64(Q - F[0])) if F[0] > 0 else np.zeros_like(m)
+    planes = [pack_plane(np.signbit(g))]
+    for b in range(F[0]):
+        planes.append(pack_plane(((base >> np.uint64(b)) & np.uint64(1)).astype(bool)))
+    for b in range(width):
+        planes.append(pack_plane(((field >> np.uint64(b)) & np.uint64(1)).astype(bool)))
+    return dict(level=level, scale_exp=e, planes=np.stack(planes), p_level=float(p[level - 1]))
+
+
+def decode_bits_row(msg, F: Sequence[int], d: int) -> np.ndarray:
+    """The fp32 vector g~ the server adds for this worker:
+    g~_j = sign_j * [ fp32(f0_j) * c_0 + fp32(f_j) * c_l ], c_0 = fp32(2^(e - F_0)),
+    c_l = fp32(2^(e - F_l) / p_l); products and the sum are single fp32 operations."""
+    level, e, planes = msg["level"], msg["scale_exp"], msg["planes"]
+    width = F[level] - F[level - 1]
+    sign = unpack_plane(planes[0], d)
+    f0 = np.zeros(d, dtype=np.uint32)
+    for b in range(F[0]):
+        f0 |= unpack_plane(planes[1 + b], d).astype(np.uint32) << np.uint32(b)
+    f = np.zeros(d, dtype=np.uint32)
+    for b in range(width):
+        f |= unpack_plane(planes[1 + F[0] + b], d).astype(np.uint32) << np.uint32(b)
+    p_l = msg["p_level"]
+    c_l = np.float32(math.ldexp(1.0, e - F[level]) / p_l) if p_l != 0.0 else np.float32(0.0)
+    v = f.astype(np.float32) * c_l
+    if F[0] > 0:
+        c_0 = np.float32(math.ldexp(1.0, e - F[0]))
+        v = f0.astype(np.float32) * c_0 + v
+    return np.where(sign, -v, v).astype(np.float32)
+
+
+def compress_bits(G: np.ndarray, F, p, seed: int, step: int):
+    return [compress_bits_row(G[i], F, p, seed, step, i) for i in range(G.shape[0])]
+
+
+# ----------------------------------------------------------------------------------------------
+# server aggregate
+# ----------------------------------------------------------------------------------------------
+def aggregate_sparse(msgs, d: int, alpha: float) -> np.ndarray:
+    """out_j = fp32(alpha * acc_j); acc_j = fp32 sum over workers in worker order of the entries at j
+    (a worker without an entry at j is skipped)."""
+    acc = np.zeros(d, dtype=np.float32)
+    for msg in msgs:
+        idx = msg["idx"].astype(np.int64)
+        acc[idx] = acc[idx] + msg["val"]
+    return (np.float32(alpha) * acc).astype(np.float32)
+
+
+def aggregate_bits(msgs, F, d: int, alpha: float) -> np.ndarray:
+    acc = np.zeros(d, dtype=np.float32)
+    for msg in msgs:
+        acc = acc + decode_bits_row(msg, F, d)
+    return (np.float32(alpha) * acc).astype(np.float32)

@@ -1,0 +1,426 @@
+"""Pins for the CPU oracle: every check compares the oracle with something that is not the oracle --
+a brute-force definition on tiny inputs, a closed form or identity from the paper, an exact rational
+computation, a library routine with a different algorithm, or published known-answer vectors.
+"""
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle import mlmc as O
+from oracle.philox import philox4x32_10, level_uniform
+import mlmc_workloads as W
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+# ----------------------------------------------------------------------------- helpers (independent)
+def brute_rank(g):
+    """rank(j) = #{i: |g_i| > |g_j|} + #{i < j: |g_i| == |g_j|}  -- O(d^2), float compares only."""
+    a = [abs(float(x)) for x in g]
+    d = len(a)
+    return [sum(1 for i in range(d) if a[i] > a[j]) + sum(1 for i in range(j) if a[i] == a[j]) for j in range(d)]
+
+
+def tiny_rows():
+    rng = np.random.default_rng(7)
+    rows = []
+    rows.append(rng.standard_normal(64).astype(np.float32))
+    rows.append(np.array([1, -1, 1, -1, 0.5, -0.0, 0.0, 2, 2, -2, 1e-40, -1e-40, 3e-41, 0, 7, -7], dtype=np.float32))
+    rows.append(np.full(33, -0.25, dtype=np.float32))
+    rows.append(np.zeros(17, dtype=np.float32))
+    rows.append((rng.integers(-2, 3, size=50)).astype(np.float32))
+    rows.append(rng.standard_normal(37).astype(np.float32) * np.float32(1e-3))
+    return rows
+
+
+# ----------------------------------------------------------------------------- Philox
+def test_philox_known_answers():
+    n = 0
+    with open(os.path.join(HERE, "golden", "philox4x32_10_kat.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            w = [int(x, 16) for x in line.split()]
+            assert list(philox4x32_10(w[0:4], w[4:6])) == w[6:10]
+            n += 1
+    assert n == 3
+
+
+def test_philox_counter_layout():
+    # key = (seed_lo, seed_hi); counter = (step_lo, step_hi, worker, 0); word 0 is used
+    seed, step, worker = 0x299f31d0a4093822, 0x85a308d3243f6a88, 0x13198a2e
+    assert level_uniform(seed, step, worker) == philox4x32_10(
+        (0x243f6a88, 0x85a308d3, 0x13198a2e, 0), (0xa4093822, 0x299f31d0))[0]
+    # uniformity of the word actually used: mean of 20000 draws within 5 sigma of 1/2
+    xs = [level_uniform(1, s, 0) / 2 ** 32 for s in range(20000)]
+    assert abs(sum(xs) / len(xs) - 0.5) < 5 * math.sqrt(1 / 12 / len(xs))
+
+
+# ----------------------------------------------------------------------------- ordering / Top-k
+@pytest.mark.parametrize("row_id", range(6))
+def test_order_matches_bruteforce_rank(row_id):
+    g = tiny_rows()[row_id]
+    order = O.magnitude_order(g)
+    rank = brute_rank(g)
+    assert [rank[j] for j in order] == list(range(len(g)))
+    for k in (0, 1, 2, len(g) // 2, len(g)):
+        want = np.array([g[j] if rank[j] < k else 0 for j in range(len(g))], dtype=np.float32)
+        assert np.array_equal(O.topk_dense(g, k).view(np.uint32), want.view(np.uint32))
+
+
+def test_bf16_rows_upcast_exactly():
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal(64).astype(np.float32)
+    b = W.f32_to_bf16_bits(x)
+    up = O.as_f32(b)
+    # bf16 RNE: error at most half a bf16 ulp (2^-9 relative), and the upcast has zero low mantissa bits
+    assert np.all(np.abs(up - x) <= np.abs(x) * 2.0 ** -8)
+    assert np.all((up.view(np.uint32) & 0xFFFF) == 0)
+    rank = brute_rank(up)
+    assert [rank[j] for j in O.magnitude_order(up)] == list(range(64))
+
+
+# ----------------------------------------------------------------------------- telescoping / unbiasedness
+@pytest.mark.parametrize("row_id", range(6))
+def test_telescoping_reproduces_top_level(row_id):
+    """App. A: g^0 + sum_l (g^l - g^{l-1}) = g^L.  With every weight 1 the bands tile C_L(g) exactly."""
+    g = tiny_rows()[row_id]
+    d = len(g)
+    ladder = sorted(set([0, 1, 2, d // 4, d // 2, d - 1])) if row_id % 2 else sorted(set([2, 3, d // 3, d - 2]))
+    ladder = [k for k in ladder if 0 <= k <= d]
+    L = len(ladder) - 1
+    ones = [1.0] * L   # not a distribution: forces weight 1 on every band
+    total = np.zeros(d, dtype=np.float32)
+    seen = np.zeros(d, dtype=int)
+    for l in range(1, L + 1):
+        m = O.compress_topk_row(g, ladder, ones, 0, 0, 0, force_level=l)
+        dense = O.sparse_to_dense(m["idx"], m["val"], d)
+        base = O.topk_dense(g, ladder[0])
+        total += dense - base
+        seen[m["idx"]] += 1
+        assert np.all(np.diff(m["idx"].astype(np.int64)) > 0)
+        assert len(m["idx"]) == ladder[0] + ladder[l] - ladder[l - 1]
+    total += O.topk_dense(g, ladder[0])
+    assert np.array_equal(total, O.topk_dense(g, ladder[L]))
+
+
+@pytest.mark.parametrize("adaptive", [False, True])
+def test_exact_expectation_is_top_level(adaptive):
+    """Lemma 3.2: sum_l p_l * g~(l) = C_L(g), checked in exact rational arithmetic up to the fp32 rounding
+    of the weight and product (relative 2^-22 per entry)."""
+    g = tiny_rows()[0]
+    d = len(g)
+    ladder = [4, 8, 16, 32, 64]
+    L = 4
+    p = None if adaptive else O.geometric_p(L)
+    exp = [Fraction(0)] * d
+    for l in range(1, L + 1):
+        m = O.compress_topk_row(g, ladder, p, 0, 0, 0, force_level=l)
+        pl = Fraction(m["p"][l - 1])
+        for j, v in zip(m["idx"], m["val"]):
+            exp[j] += pl * Fraction(float(v))
+    assert abs(sum(Fraction(x) for x in (m["p"])) - 1) < Fraction(1, 10 ** 12)
+    for j in range(d):
+        want = Fraction(float(g[j]))
+        assert abs(exp[j] - want) <= abs(want) * Fraction(1, 2 ** 21)
+
+
+def test_importance_sampling_special_case():
+    """Sec. 3.2: with the unit ladder k_l = l the message is the single rank-l entry scaled by 1/p_l."""
+    g = tiny_rows()[5]
+    d = len(g)
+    ladder = list(range(d + 1))
+    rank = brute_rank(g)
+    by_rank = {r: j for j, r in enumerate(rank)}
+    norms, _ = O.level_norms_row(g, ladder)
+    # Delta_l is the magnitude of the rank-(l-1) entry
+    for l in range(1, d + 1):
+        assert norms[l - 1] == abs(float(g[by_rank[l - 1]]))
+    for step in range(50):
+        m = O.compress_topk_row(g, ladder, None, 11, step, 2)
+        l = m["level"]
+        assert list(m["idx"]) == [by_rank[l - 1]]
+        pl = norms[l - 1] / math.fsum(norms)
+        assert m["val"][0] == np.float32(g[by_rank[l - 1]]) * np.float32(1.0 / m["p"][l - 1])
+        assert abs(m["p"][l - 1] - pl) < 1e-15
+
+
+def test_monte_carlo_unbiased_tiny_case():
+    """Lemma 3.2 by Monte Carlo over 10^5 frozen seeds on the tiny workload's ladder (reduced d): the
+    level frequencies match p within 3 sigma (binomial), which for rank bands is the whole statement
+    because g~ restricted to band l equals g * 1[level = l] / p_l."""
+    w = W.scaled(W.WORKLOADS["tiny_topk"], d=4096, M=1)
+    L = w.L
+    p = O.geometric_p(L)
+    N = 100_000
+    T = O.cdf_thresholds(p)
+    counts = [0] * (L + 1)
+    for seed in range(N):
+        x = level_uniform(seed, 0, 0)
+        l = next(i for i, t in enumerate(T, start=1) if x < t)
+        counts[l] += 1
+    for l in range(1, L + 1):
+        sd = math.sqrt(p[l - 1] * (1 - p[l - 1]) / N)
+        assert abs(counts[l] / N - p[l - 1]) <= 3 * sd + 1e-12, (l, counts[l] / N, p[l - 1])
+    # and the function the oracle actually calls agrees with that inverse-CDF on a few seeds
+    for seed in range(200):
+        x = level_uniform(seed, 0, 0)
+        assert O.draw_level(p, seed, 0, 0) == next(i for i, t in enumerate(T, start=1) if x < t)
+
+
+def test_monte_carlo_unbiased_per_coordinate_small():
+    """Per-coordinate 3-sigma check on d = 32 with frozen seeds (Lemma 3.2)."""
+    rng = np.random.default_rng(5)
+    g = rng.standard_normal(32).astype(np.float32)
+    ladder = [2, 4, 8, 16, 32]
+    L = 4
+    p = O.geometric_p(L)
+    N = 20000
+    s1 = np.zeros(32)
+    s2 = np.zeros(32)
+    for seed in range(N):
+        m = O.compress_topk_row(g, ladder, p, seed, 3, 1)
+        dense = O.sparse_to_dense(m["idx"], m["val"], 32).astype(np.float64)
+        s1 += dense
+        s2 += dense * dense
+    mean = s1 / N
+    var = np.maximum(s2 / N - mean ** 2, 0)
+    assert np.all(np.abs(mean - g) <= 3.2 * np.sqrt(var / N) + 1e-6 * np.abs(g))
+
+
+# ----------------------------------------------------------------------------- probabilities
+def test_geometric_p_is_lemma_3_3_form():
+    for L in (1, 5, 10, 63):
+        p = O.geometric_p(L)
+        assert abs(math.fsum(p) - 1.0) < 1e-15
+        for l in range(1, L):
+            assert p[l - 1] == 2 * p[l]
+        assert Fraction(p[0]) == Fraction(Fraction(1, 2) / (1 - Fraction(1, 2 ** L))) or \
+            abs(Fraction(p[0]) - Fraction(1, 2) / (1 - Fraction(1, 2 ** L))) < Fraction(1, 2 ** 53)
+
+
+def test_cdf_thresholds_integer_inverse_cdf():
+    p = [0.5, 0.25, 0.25]
+    assert O.cdf_thresholds(p) == [1 << 31, 3 << 30, 1 << 32]
+    p = [0.0, 1.0]
+    assert O.cdf_thresholds(p) == [0, 1 << 32]       # a zero-probability level is never drawn
+    assert all(O.draw_level(p, s, 0, 0) == 2 for s in range(100))
+    assert O.adaptive_p([0.0, 0.0, 0.0, 0.0]) == [0.25] * 4
+
+
+# ----------------------------------------------------------------------------- norms
+def test_exact_sumsq_against_rationals_and_fsum():
+    rng = np.random.default_rng(11)
+    for trial in range(5):
+        g = (rng.standard_normal(300) * 10.0 ** rng.uniform(-30, 30, size=300)).astype(np.float32)
+        g[::17] = np.float32(1e-42)  # denormals
+        exact = sum(Fraction(float(x)) ** 2 for x in g)
+        assert Fraction(O.exact_sumsq(g), 2 ** 298) == exact
+    # where no square underflows in fp64, fsum of the (exact) fp64 squares is the correctly rounded sum
+    g = rng.standard_normal(5000).astype(np.float32)
+    assert O.units_to_f64(O.exact_sumsq(g)) == math.fsum((g.astype(np.float64) ** 2).tolist())
+
+
+def test_level_norms_pythagoras_and_fsum():
+    """App. D: Delta_l^2 = ||g^l||^2 - ||g^{l-1}||^2, hence S_0 + sum_l S_l = ||C_L(g)||^2 (exactly, in units)."""
+    w = W.scaled(W.WORKLOADS["resnet50_adaptive_topk"], d=20000, M=2)
+    G = W.generate(w)
+    for i in range(2):
+        norms, units = O.level_norms_row(G[i], w.ladder)
+        assert sum(units) == O.exact_sumsq(G[i])
+        order = sorted(range(w.d), key=lambda j: (-abs(float(G[i][j])), j))
+        for l in (1, w.L // 2, w.L):
+            band = order[w.ladder[l - 1]:w.ladder[l]]
+            want = math.sqrt(math.fsum(float(G[i][j]) ** 2 for j in band))
+            assert norms[l - 1] == want
+
+
+def test_level_norms_exponential_decay_closed_form():
+    """Assumption 3.5 / App. E: |v(j)| = |v(0)| e^{-r j / 2} gives
+    Delta_l^2 = |v(0)|^2 e^{-r s (l-1)} (1 - e^{-r s}) / (1 - e^{-r}) for the ladder k_l = s l."""
+    d, s, r, v0 = 4096, 64, 0.01, 3.0
+    j = np.arange(d)
+    mags = (v0 * np.exp(-0.5 * r * j)).astype(np.float32)
+    rng = np.random.default_rng(2)
+    perm = rng.permutation(d)
+    g = np.empty(d, dtype=np.float32)
+    g[perm] = mags * rng.choice(np.array([-1.0, 1.0], dtype=np.float32), size=d)
+    ladder = [s * l for l in range(d // s + 1)]
+    norms, _ = O.level_norms_row(g, ladder)
+    for l in (1, 2, 10, d // s):
+        closed = v0 ** 2 * math.exp(-r * s * (l - 1)) * (1 - math.exp(-r * s)) / (1 - math.exp(-r))
+        assert abs(norms[l - 1] ** 2 - closed) <= 1e-6 * closed   # fp32 rounding of the inputs
+    # App. D: with the optimal p the second moment is (sum Delta)^2
+    p = O.adaptive_p(norms)
+    second = 0.0
+    for l in (1, 3, 17, d // s):
+        m = O.compress_topk_row(g, ladder, None, 0, 0, 0, force_level=l)
+        n2 = float(np.sum(m["val"].astype(np.float64) ** 2))
+        assert abs(n2 - norms[l - 1] ** 2 / p[l - 1] ** 2) <= 1e-5 * n2
+    assert abs(sum(x * x / q for x, q in zip(norms, p)) - math.fsum(norms) ** 2) <= 1e-9 * math.fsum(norms) ** 2
+
+
+@pytest.mark.parametrize("adaptive", [False, True])
+def test_second_moment_closed_forms(adaptive):
+    """App. D: E||g~||^2 = S_0 + sum_l S_l / p_l in general, = S_0 + (sum_l Delta_l)^2 for the adaptive p."""
+    w = W.scaled(W.WORKLOADS["resnet18_topk"], d=6000, M=1)
+    g = W.generate(w)[0]
+    p = None if adaptive else O.geometric_p(w.L)
+    norms, units = O.level_norms_row(g, w.ladder)
+    S0 = O.units_to_f64(units[0])
+    second = 0.0
+    for l in range(1, w.L + 1):
+        m = O.compress_topk_row(g, w.ladder, p, 0, 0, 0, force_level=l)
+        second += m["p"][l - 1] * float(np.sum(m["val"].astype(np.float64) ** 2))
+        pp = m["p"]
+    want = S0 + sum(x * x / q for x, q in zip(norms, pp) if q > 0)
+    assert abs(second - want) <= 1e-6 * want
+    if adaptive:
+        assert abs(want - (S0 + math.fsum(norms) ** 2)) <= 1e-9 * want
+
+
+# ----------------------------------------------------------------------------- bit-wise ladder
+def test_bits_digits_are_binary_expansion():
+    """Sec. 3.1: e = (-1)^{b_0} sum_j b_j 2^-j; the digits the oracle extracts re-assemble the truncation."""
+    rng = np.random.default_rng(9)
+    g = rng.standard_normal(200).astype(np.float32) * np.float32(0.37)
+    e = O.bits_scale_exponent(g)
+    s = math.ldexp(1.0, e)
+    assert float(np.abs(g).max()) < s <= 2 * float(np.abs(g).max())
+    Q = 16
+    m = O.fixed_point_digits(g, e, Q)
+    for j in range(200):
+        x = Fraction(abs(float(g[j]))) / Fraction(s)
+        assert 0 <= x < 1
+        assert int(m[j]) == int(x * 2 ** Q)             # floor of the exact rational
+        for F in (1, 2, 4, 8, 16):
+            t = O.bits_truncate_dense(g, F, Q)[j]
+            assert abs(Fraction(abs(float(t))) - x * Fraction(s)) < Fraction(s) / 2 ** F   # distortion < 2^-F (scaled)
+
+
+def test_bits_telescoping_and_constant_magnitude():
+    """Unit ladder F = 0..16 with p_l ∝ 2^-l: (1/p_l) b_l 2^-l = (1 - 2^-L) b_l, so every decoded entry is
+    0 or ±(1 - 2^-L) s; and sum_l p_l g~(l) = C^{F_L}(g) (Lemma 3.2 for this ladder)."""
+    rng = np.random.default_rng(4)
+    g = (rng.standard_normal(300) * 0.01).astype(np.float32)
+    d = 300
+    F = list(range(17))
+    L = 16
+    p = O.geometric_p(L)
+    e = O.bits_scale_exponent(g)
+    s = math.ldexp(1.0, e)
+    exp = np.zeros(d)
+    second = np.zeros(d)
+    for l in range(1, L + 1):
+        msg = O.compress_bits_row(g, F, p, 0, 0, 0, force_level=l)
+        assert msg["planes"].shape == (2, (d + 63) // 64)       # sign + one information bit per entry (Sec. 3.1)
+        dec = O.decode_bits_row(msg, F, d).astype(np.float64)
+        mags = np.unique(np.abs(dec))
+        assert set(mags.tolist()) <= {0.0, float(np.float32((1 - 2.0 ** -L) * s))}
+        exp += p[l - 1] * dec
+        second += p[l - 1] * dec * dec
+    trunc = O.bits_truncate_dense(g, 16, 16)
+    assert np.allclose(exp, trunc, rtol=1e-6, atol=0)
+    assert np.all(np.abs(trunc - g) < s * 2.0 ** -16)
+    # App. C: per-entry second moment (1 - 2^-L) |e| in normalised units
+    assert np.allclose(second / s ** 2, (1 - 2.0 ** -L) * np.abs(trunc) / s, rtol=1e-5, atol=0)
+
+
+def test_bits_general_ladder_expectation_and_layout():
+    w = W.scaled(W.WORKLOADS["resnet18_bits"], d=1000, M=1)
+    g = W.generate(w)[0]
+    d = w.d
+    for F in ([0, 1, 2, 4, 8, 16], [2, 3, 8, 12]):
+        L = len(F) - 1
+        p = O.geometric_p(L)
+        exp = np.zeros(d)
+        for l in range(1, L + 1):
+            msg = O.compress_bits_row(g, F, p, 0, 0, 0, force_level=l)
+            assert msg["planes"].shape[0] == 1 + F[0] + F[l] - F[l - 1]
+            # plane 0 is the sign, word w bit b <-> element 64 w + b
+            for j in (0, 1, 63, 64, 65, d - 1):
+                assert bool((int(msg["planes"][0][j // 64]) >> (j % 64)) & 1) == bool(np.signbit(g[j]))
+            exp += p[l - 1] * O.decode_bits_row(msg, F, d).astype(np.float64)
+        assert np.allclose(exp, O.bits_truncate_dense(g, F[L], F[L]), rtol=2e-6, atol=0)
+
+
+def test_bits_zero_and_denormal_rows():
+    F = [0, 1, 2, 4, 8, 16]
+    p = O.geometric_p(5)
+    z = np.zeros(130, dtype=np.float32)
+    msg = O.compress_bits_row(z, F, p, 0, 0, 0)
+    assert msg["scale_exp"] == -125 and not msg["planes"][1:].any()
+    assert not O.decode_bits_row(msg, F, 130).any()
+    den = np.array([1e-40, -3e-41, 0, 2e-45], dtype=np.float32)
+    e = O.bits_scale_exponent(den)
+    assert e == -125
+    m = O.fixed_point_digits(den, e, 16)
+    assert [int(x) for x in m] == [int(Fraction(abs(float(v))) / Fraction(2) ** e * 2 ** 16) for v in den]
+
+
+# ----------------------------------------------------------------------------- aggregate
+def test_aggregate_identity_special_case_is_alg1_mean():
+    """L = 1, k_0 = 0, k_1 = d, p_1 = 1: g~ = g and the aggregate with alpha = 1/M is Alg. 1's mean."""
+    rng = np.random.default_rng(1)
+    M, d = 4, 257
+    G = rng.standard_normal((M, d)).astype(np.float32)
+    msgs = O.compress_topk(G, [0, d], [1.0], 0, 0)
+    for i in range(M):
+        assert np.array_equal(msgs[i]["idx"], np.arange(d)) and np.array_equal(msgs[i]["val"], G[i])
+    out = O.aggregate_sparse(msgs, d, 1.0 / M)
+    acc = np.zeros(d, dtype=np.float32)
+    for i in range(M):
+        acc = acc + G[i]
+    assert np.array_equal(out, acc * np.float32(0.25))
+    assert np.allclose(out, G.astype(np.float64).mean(axis=0), rtol=1e-5, atol=1e-6)
+
+
+def test_aggregate_sparse_bruteforce():
+    rng = np.random.default_rng(8)
+    M, d = 5, 90
+    G = rng.standard_normal((M, d)).astype(np.float32)
+    ladder = [3, 7, 20, 90]
+    msgs = O.compress_topk(G, ladder, O.geometric_p(3), 5, 9)
+    out = O.aggregate_sparse(msgs, d, 0.5)
+    for j in range(d):
+        acc = np.float32(0)
+        for m in msgs:
+            hit = np.nonzero(m["idx"] == j)[0]
+            if hit.size:
+                acc = np.float32(acc + m["val"][hit[0]])
+        assert out[j] == np.float32(np.float32(0.5) * acc)
+    # different workers draw different levels across steps (the draw depends on the worker id)
+    levels = {(m["level"]) for s in range(20) for m in O.compress_topk(G, ladder, O.geometric_p(3), 5, s)}
+    assert len(levels) > 1
+
+
+def test_aggregate_bits_is_sum_of_decodes():
+    w = W.scaled(W.WORKLOADS["resnet18_bits"], d=500, M=3)
+    G = W.generate(w)
+    p = O.geometric_p(w.L)
+    msgs = O.compress_bits(G, w.ladder, p, 1, 2)
+    out = O.aggregate_bits(msgs, w.ladder, w.d, 1.0)
+    want = np.zeros(w.d, dtype=np.float32)
+    for m in msgs:
+        want = want + O.decode_bits_row(m, w.ladder, w.d)
+    assert np.array_equal(out, want)
+
+
+# ----------------------------------------------------------------------------- workloads
+def test_workload_generators_are_deterministic_and_shaped():
+    for name in ("tiny_topk", "resnet18_topk", "resnet50_adaptive_topk", "resnet18_bits", "bert_adaptive_topk_bf16"):
+        w = W.WORKLOADS[name]
+        assert w.ladder[-1] == (w.d if w.kind == "topk" else 16)
+        s = W.scaled(w, d=5000, M=2)
+        a, b = W.generate(s), W.generate(s)
+        assert a.shape == (2, 5000) and np.array_equal(a, b)
+        assert not np.array_equal(a[0], a[1])
+    assert W.WORKLOADS["resnet18_topk"].ladder[:3] == (11415, 22831, 45662)
+    assert W.WORKLOADS["resnet50_adaptive_topk"].ladder[0] == 6239
+    assert W.WORKLOADS["bert_adaptive_topk_bf16"].ladder[0] == 1898
+    lens, std = W.segment_layout(11_689_512, 62, 1e-4, 1e-1, 0)
+    assert lens.sum() == 11_689_512 and len(lens) == 62 and std.min() >= 1e-4 and std.max() <= 1e-1
