@@ -1,0 +1,151 @@
+/*
+ * mlmc.h -- C ABI of the MI355X (gfx950) library for the data-parallel hot path of Multilevel Monte
+ * Carlo (MLMC) gradient compression.
+ *
+ * Setting (paper, Sec. 2.1 "Problem Statement", Alg. 2, Alg. 3): M workers each hold a d-dimensional
+ * stochastic gradient.  Per step every worker draws a level l ~ p, sends the MLMC estimate
+ *     g~ = g^0 + (g^l - g^{l-1}) / p^l,   g^l = C^l(g)                          (Eq. (5), Eq. (6))
+ * and the server forms (1/M) sum_i g~_i.  Here the M workers are the M rows of one device matrix.
+ *
+ * Conventions that hold for every entry point
+ *   - "dev" pointers are device (HIP) memory owned by the caller; "host" pointers are host memory.  The
+ *     library never allocates, frees or retains device memory; the plan is a host object.
+ *   - All device work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = default stream) and
+ *     the call returns without synchronising.  The return value covers what the host can detect
+ *     (MLMC_EINVAL for bad arguments, MLMC_EHIP for a failed launch).  Conditions only the device can see
+ *     are OR-ed into *dev_status (MLMC_DEV_* bits), which the library clears at the start of the call.
+ *   - `ws` is a dev scratch buffer of at least the `workspace_bytes` reported by mlmc_plan, 256-byte aligned.
+ *     Calls that share a workspace must be ordered on one stream.
+ *   - Row i of g is worker i: element j of row i is g[i * ld + j], ld >= d, dtype as planned.
+ *   - Results are a pure function of (g, plan, p, seed, step): no atomics on floating point, no
+ *     dependence on scheduling.
+ *
+ * Orders and roundings (fixed so that an independent implementation can reproduce every bit)
+ *   - Magnitude order: key_j = bit pattern of |g_j| as fp32 (bf16 inputs are widened exactly);
+ *     rank(j) = #{i : key_i > key_j} + #{i < j : key_i == key_j}.  Top-k keeps rank < k.
+ *   - Band l (l = 1..L) = {j : k_{l-1} <= rank(j) < k_l}; base band = {j : rank(j) < k_0}.
+ *   - Delta_l = sqrt(S_l), S_l = exact sum of g_j^2 over band l rounded once to fp64 (Lemma 3.4).
+ *   - Adaptive p_l = Delta_l / (Delta_1 + ... + Delta_L) (fp64, sum in level order); all-zero -> 1/L.
+ *   - Draw: T_l = floor((p_1 + ... + p_l) * 2^32) (running fp64 sum), T_L = 2^32;
+ *     x = word 0 of Philox4x32-10 with key = (seed_lo, seed_hi), counter = (step_lo, step_hi, i, 0);
+ *     level = min{l : x < T_l}.
+ *   - Weight w = (float)(1.0 / p_level) (0 if p_level == 0); band values are the fp32 product g_j * w.
+ */
+#ifndef MLMC_H
+#define MLMC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct mlmc_plan_s mlmc_plan_t; /* opaque, host side, owned by the library */
+
+typedef enum {
+    MLMC_OK = 0,
+    MLMC_EINVAL = 1,   /* bad argument (ladder, probabilities, sizes, null pointers, alignment) */
+    MLMC_ENOMEM = 2,   /* host allocation failed */
+    MLMC_EHIP = 3      /* a HIP call or kernel launch failed */
+} mlmc_status;
+
+/* bits OR-ed into *dev_status by the kernels */
+#define MLMC_DEV_CAPACITY 1  /* row_off[M] > capacity: entries past capacity were not written */
+#define MLMC_DEV_NONFINITE 2 /* an Inf or NaN input was seen (it is ordered by its bit pattern) */
+#define MLMC_DEV_INTERNAL 4  /* an internal consistency check failed (counts do not add up) */
+
+typedef enum { MLMC_F32 = 0, MLMC_BF16 = 1 } mlmc_dtype;
+typedef enum { MLMC_TOPK = 0, MLMC_BITS = 1 } mlmc_kind;
+
+#define MLMC_MAX_LEVELS 32   /* L <= 32 */
+#define MLMC_MAX_WORKERS 1024 /* M <= 1024 */
+#define MLMC_TILE 4096       /* elements per tile of the per-row offset table */
+
+/*
+ * Plan: the inputs of Alg. 2 / Alg. 3 other than the gradients (multilevel compressor C^l, level
+ * probabilities) for M workers of dimension d (Sec. 2.1).
+ *   kind == MLMC_TOPK: ladder = ranks k_0..k_L, 0 <= k_0 < k_1 < ... < k_L <= d        (Sec. 3.2)
+ *   kind == MLMC_BITS: ladder = kept fraction bits F_0..F_L, 0 <= F_0 < ... < F_L <= 24 (Sec. 3.1)
+ *   p_fixed: host, L entries for levels 1..L, each > 0, summing to 1 within 1e-9; NULL selects the
+ *            adaptive probabilities of Lemma 3.4 (MLMC_TOPK only).
+ *   1 <= M <= MLMC_MAX_WORKERS, 1 <= d < 2^31, 1 <= L <= MLMC_MAX_LEVELS.
+ * Outputs (host): *plan; *workspace_bytes; *sparse_capacity_worst = M * (k_0 + widest band) entries
+ * (0 for MLMC_BITS).  Returns MLMC_EINVAL and leaves *plan NULL on a bad argument.
+ */
+mlmc_status mlmc_plan(mlmc_plan_t **plan, int kind, int M, int64_t d, int in_dtype, int L,
+                      const int64_t *ladder, const double *p_fixed, size_t *workspace_bytes,
+                      int64_t *sparse_capacity_worst);
+void mlmc_plan_destroy(mlmc_plan_t *plan);
+
+/* Tiles per row of the offset table: ceil(d / MLMC_TILE). */
+int64_t mlmc_plan_num_tiles(const mlmc_plan_t *plan);
+/* MLMC_BITS: planes per row of the packed message = 1 + F_0 + max_l (F_l - F_{l-1}); else 0. */
+int mlmc_plan_num_planes(const mlmc_plan_t *plan);
+
+/* Lemma 3.3 form: p[l-1] = 2^-l / (1 - 2^-L), l = 1..L (host array of L doubles). */
+mlmc_status mlmc_geometric_p(int L, double *p);
+
+const char *mlmc_status_string(int status);
+
+/*
+ * Per-level residual norms Delta_l = ||C_l(g) - C_{l-1}(g)||_2, l = 1..L, of every row (Lemma 3.4; for
+ * rank bands Delta_l^2 is the sum of squares over band l, App. D).  MLMC_TOPK plans only.
+ *   g: dev [M][ld];  norms: dev [M][L] fp64 (out);  dev_status: dev [1] int32 (out).
+ */
+mlmc_status mlmc_level_norms(const mlmc_plan_t *plan, const void *g, int64_t ld, double *norms,
+                             int32_t *dev_status, void *ws, void *hip_stream);
+
+/*
+ * Worker side of Alg. 2 (fixed p) / Alg. 3 (adaptive p) for the Top-k ladder: draw the level, emit
+ * C_0(g) + (C_l(g) - C_{l-1}(g)) / p_l as an index-sorted sparse band.
+ *   p: NULL -> the plan's p_fixed, or (adaptive plan) Lemma 3.4 probabilities computed here from g;
+ *      else dev [M][L] fp64: probabilities (p_is_norms == 0) or norms to be normalised (p_is_norms != 0).
+ *   seed, step: the draw of worker i depends on (seed, step, i) only.
+ *   level:   dev [M] int32 (out), drawn level in 1..L.
+ *   row_off: dev [M+1] int64 (out), exclusive prefix of nnz_i = k_0 + k_l - k_{l-1}.
+ *   idx/val: dev [capacity] uint32 / float (out); row i occupies [row_off[i], row_off[i+1]), ascending idx.
+ *            Base-band entries carry g_j, drawn-band entries carry fp32(g_j * w_i).
+ *   tile_off: dev [M][num_tiles + 1] uint32 (out) or NULL; tile_off[i][t] = number of entries of row i
+ *            with idx < t * MLMC_TILE (so tile_off[i][num_tiles] = nnz_i).  Lets mlmc_aggregate skip a search.
+ *   norms_out: dev [M][L] fp64 (out) or NULL; written only when p == NULL on an adaptive plan.
+ */
+mlmc_status mlmc_compress_topk(const mlmc_plan_t *plan, const void *g, int64_t ld, const double *p,
+                               int p_is_norms, uint64_t seed, uint64_t step, int32_t *level,
+                               int64_t *row_off, uint32_t *idx, float *val, int64_t capacity,
+                               uint32_t *tile_off, double *norms_out, int32_t *dev_status, void *ws,
+                               void *hip_stream);
+
+/*
+ * Worker side of Alg. 2 for the fixed-point bit-wise ladder (Sec. 3.1).  Per row: scale s = 2^e with
+ * e = max(E_max, 1) - 126 (E_max = largest fp32 exponent field in the row, so |g_j| / s < 1),
+ * m_j = floor(|g_j| / s * 2^{F_L}); drawn level l; message = sign plane, F_0 base-field planes
+ * (bits of m_j >> (F_L - F_0), LSB first), F_l - F_{l-1} level-field planes (bits of
+ * (m_j >> (F_L - F_l)) mod 2^{F_l - F_{l-1}}, LSB first).
+ *   level: dev [M] int32 (out);  scale_exp: dev [M] int32 (out), the exponent e.
+ *   planes: dev [M][num_planes][ceil(d/64)] uint64 (out); word w bit b <-> element 64 w + b, pad bits 0;
+ *           planes beyond 1 + F_0 + (F_l - F_{l-1}) of a row are left untouched.
+ */
+mlmc_status mlmc_compress_bits(const mlmc_plan_t *plan, const void *g, int64_t ld, uint64_t seed,
+                               uint64_t step, int32_t *level, int32_t *scale_exp, uint64_t *planes,
+                               int32_t *dev_status, void *ws, void *hip_stream);
+
+/*
+ * Server side (Alg. 2 / Alg. 3 "Server aggregates"): out[j] = fp32(alpha * acc_j), acc_j the fp32 sum over
+ * workers in worker order (alpha = 1/M gives the paper's mean).
+ *   MLMC_TOPK plan: row_off, idx, val as written by mlmc_compress_topk (level unused, may be NULL);
+ *     tile_off as written there, or NULL (then it is rebuilt by binary search into ws).  A worker without an
+ *     entry at j is skipped.
+ *   MLMC_BITS plan: level, scale_exp, planes as written by mlmc_compress_bits; the decoded value of
+ *     worker i at j is sign * [ fp32(f0) * fp32(2^(e - F_0)) + fp32(f) * fp32(2^(e - F_l) / p_l) ].
+ *   out: dev [d] fp32, fully overwritten.
+ */
+mlmc_status mlmc_aggregate(const mlmc_plan_t *plan, const int32_t *level, const int64_t *row_off,
+                           const uint32_t *idx, const float *val, const uint32_t *tile_off,
+                           const int32_t *scale_exp, const uint64_t *planes, float alpha, float *out,
+                           void *ws, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MLMC_H */

@@ -1,0 +1,308 @@
+// C ABI of libmlmc: plan construction / validation on the host and the entry points that enqueue the
+// kernels (see include/mlmc.h for the contract of every call).
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "mlmc_internal.h"
+
+namespace mlmc {
+mlmc_status topk_zero(const mlmc_plan_t* pl, void* ws, int32_t* dev_status, hipStream_t st);
+mlmc_status topk_draw(const DrawArgs& da, hipStream_t st);
+mlmc_status topk_select(const mlmc_plan_t* pl, const TopkArgs& a, bool sums, bool vec, hipStream_t st);
+mlmc_status topk_compact(const mlmc_plan_t* pl, const TopkArgs& a, bool vec, hipStream_t st);
+mlmc_status bits_compress(const mlmc_plan_t* pl, const BitsArgs& a, bool vec, hipStream_t st);
+mlmc_status agg_bits(const mlmc_plan_t* pl, const BitsArgs& b, const int32_t* level, const int32_t* scale_exp,
+                     const uint64_t* planes, float alpha, float* out, hipStream_t st);
+mlmc_status agg_sparse(const mlmc_plan_t* pl, const int64_t* row_off, const uint32_t* idx, const float* val,
+                       const uint32_t* tile_off, uint32_t* tile_off_ws, float alpha, float* out, hipStream_t st);
+
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// rows can be read with aligned 16-byte (fp32) / 8-byte (bf16) loads
+static bool vec_ok(const mlmc_plan_t* pl, const void* g, int64_t ld) {
+    if (pl->dtype == MLMC_F32) return ((uintptr_t)g % 16 == 0) && (ld % 4 == 0);
+    return ((uintptr_t)g % 8 == 0) && (ld % 4 == 0);
+}
+
+static void fill_topk_args(const mlmc_plan_t* pl, TopkArgs& a, const void* g, int64_t ld, void* ws, int32_t* dev_status) {
+    std::memset(&a, 0, sizeof(a));
+    char* w = (char*)ws;
+    a.g = g;
+    a.ld = ld;
+    a.d = pl->d;
+    a.M = pl->M;
+    a.L = pl->L;
+    for (int t = 0; t <= pl->L; ++t) a.k[t] = pl->ladder[t];
+    a.chunk = pl->chunk;
+    a.ntiles = pl->ntiles;
+    a.racc = (RowAcc*)(w + pl->off_racc);
+    a.hist1 = (uint32_t*)(w + pl->off_hist1);
+    a.rinfo = (RowInfo*)(w + pl->off_rinfo);
+    a.table = (uint16_t*)(w + pl->off_table);
+    a.tilecnt = (uint32_t*)(w + pl->off_tilecnt);
+    a.tiepre = (uint32_t*)(w + pl->off_tiepre);
+    a.tile_off = (uint32_t*)(w + pl->off_tileoff);
+    a.norms = (double*)(w + pl->off_norms);
+    a.cand = (uint32_t*)(w + pl->off_cand);
+    a.dev_status = dev_status;
+}
+
+static void fill_bits_args(const mlmc_plan_t* pl, BitsArgs& b, const void* g, int64_t ld, void* ws, int32_t* dev_status) {
+    std::memset(&b, 0, sizeof(b));
+    char* w = (char*)ws;
+    b.g = g;
+    b.ld = ld;
+    b.d = pl->d;
+    b.M = pl->M;
+    b.L = pl->L;
+    for (int t = 0; t <= pl->L; ++t) b.F[t] = (int32_t)pl->ladder[t];
+    for (int l = 0; l < pl->L; ++l) b.p_fixed[l] = pl->p[l];
+    b.nplanes = pl->nplanes;
+    b.nwords = (pl->d + 63) / 64;
+    b.chunk = pl->chunk;
+    b.rinfo = ws ? (RowInfo*)(w + pl->off_rinfo) : nullptr;
+    b.racc = ws ? (RowAcc*)(w + pl->off_racc) : nullptr;
+    b.dev_status = dev_status;
+}
+}  // namespace mlmc
+
+using namespace mlmc;
+
+extern "C" {
+
+const char* mlmc_status_string(int status) {
+    switch (status) {
+        case MLMC_OK: return "MLMC_OK";
+        case MLMC_EINVAL: return "MLMC_EINVAL: invalid argument";
+        case MLMC_ENOMEM: return "MLMC_ENOMEM: host allocation failed";
+        case MLMC_EHIP: return "MLMC_EHIP: HIP launch failed";
+        default: return "unknown mlmc status";
+    }
+}
+
+mlmc_status mlmc_geometric_p(int L, double* p) {
+    if (L < 1 || L > 1000 || !p) return MLMC_EINVAL;
+    const double norm = 1.0 - std::ldexp(1.0, -L);
+    for (int l = 1; l <= L; ++l) p[l - 1] = std::ldexp(1.0, -l) / norm;
+    return MLMC_OK;
+}
+
+mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dtype, int L, const int64_t* ladder,
+                      const double* p_fixed, size_t* workspace_bytes, int64_t* sparse_capacity_worst) {
+    if (plan) *plan = nullptr;
+    if (!plan || !ladder) return MLMC_EINVAL;
+    if (kind != MLMC_TOPK && kind != MLMC_BITS) return MLMC_EINVAL;
+    if (in_dtype != MLMC_F32 && in_dtype != MLMC_BF16) return MLMC_EINVAL;
+    if (M < 1 || M > MLMC_MAX_WORKERS || d < 1 || d >= ((int64_t)1 << 31) || L < 1 || L > MLMC_MAX_LEVELS) return MLMC_EINVAL;
+    if (ladder[0] < 0) return MLMC_EINVAL;
+    for (int t = 0; t < L; ++t)
+        if (ladder[t] >= ladder[t + 1]) return MLMC_EINVAL;
+    if (kind == MLMC_TOPK && ladder[L] > d) return MLMC_EINVAL;
+    if (kind == MLMC_BITS && ladder[L] > 24) return MLMC_EINVAL;
+    if (kind == MLMC_BITS && !p_fixed) return MLMC_EINVAL;  // Lemma 3.4 probabilities are built for rank bands only
+    if (p_fixed) {
+        double s = 0.0;
+        for (int l = 0; l < L; ++l) {
+            if (!(p_fixed[l] > 0.0) || !(p_fixed[l] <= 1.0)) return MLMC_EINVAL;
+            s += p_fixed[l];
+        }
+        if (std::fabs(s - 1.0) > 1e-9) return MLMC_EINVAL;
+    }
+    mlmc_plan_t* pl = new (std::nothrow) mlmc_plan_t;
+    if (!pl) return MLMC_ENOMEM;
+    std::memset(pl, 0, sizeof(*pl));
+    pl->kind = kind;
+    pl->M = M;
+    pl->dtype = in_dtype;
+    pl->L = L;
+    pl->d = d;
+    for (int t = 0; t <= L; ++t) pl->ladder[t] = ladder[t];
+    pl->adaptive = p_fixed == nullptr;
+    if (p_fixed)
+        for (int l = 0; l < L; ++l) pl->p[l] = p_fixed[l];
+    pl->ntiles = (d + TILE - 1) / TILE;
+    pl->nplanes = 0;
+    if (kind == MLMC_BITS) {
+        int maxw = 0;
+        for (int l = 1; l <= L; ++l) {
+            int w = (int)(ladder[l] - ladder[l - 1]);
+            if (w > maxw) maxw = w;
+        }
+        pl->nplanes = 1 + (int)ladder[0] + maxw;
+    }
+    // chunking of the streaming kernels: about 2048 workgroups over all rows, whole tiles, at most 2^18
+    // elements per workgroup (the LDS sum accumulators of the band-sum pass rely on that bound)
+    int64_t target_per_row = 2048 / M > 0 ? 2048 / M : 1;
+    int64_t chunk = (d + target_per_row - 1) / target_per_row;
+    chunk = (chunk + TILE - 1) / TILE * TILE;
+    if (chunk < 4 * TILE) chunk = 4 * TILE;
+    if (chunk > (1 << 18)) chunk = 1 << 18;
+    pl->chunk = (int)chunk;
+    pl->chunks_per_row = (int)((d + chunk - 1) / chunk);
+
+    size_t off = 0;
+    pl->off_racc = off;
+    off = align_up(off + sizeof(RowAcc) * (size_t)M, 256);
+    pl->off_hist1 = off;
+    if (kind == MLMC_TOPK) off = align_up(off + sizeof(uint32_t) * NB1 * (size_t)M, 256);
+    pl->zero_bytes = off;
+    pl->off_rinfo = off;
+    off = align_up(off + sizeof(RowInfo) * (size_t)M, 256);
+    if (kind == MLMC_TOPK) {
+        pl->off_table = off;
+        off = align_up(off + sizeof(uint16_t) * NB1 * (size_t)M, 256);
+        pl->off_tilecnt = off;
+        off = align_up(off + sizeof(uint32_t) * 6 * (size_t)pl->ntiles * M, 256);
+        pl->off_tiepre = off;
+        off = align_up(off + sizeof(uint32_t) * 3 * (size_t)pl->ntiles * M, 256);
+        pl->off_tileoff = off;
+        off = align_up(off + sizeof(uint32_t) * (size_t)(pl->ntiles + 1) * M, 256);
+        pl->off_norms = off;
+        off = align_up(off + sizeof(double) * (size_t)L * M, 256);
+        pl->off_cand = off;
+        off = align_up(off + sizeof(uint32_t) * (size_t)d * M, 256);
+    }
+    pl->ws_bytes = off;
+    if (workspace_bytes) *workspace_bytes = off;
+    if (sparse_capacity_worst) {
+        int64_t cap = 0;
+        if (kind == MLMC_TOPK) {
+            int64_t widest = 0;
+            for (int l = 1; l <= L; ++l)
+                if (ladder[l] - ladder[l - 1] > widest) widest = ladder[l] - ladder[l - 1];
+            cap = (int64_t)M * (ladder[0] + widest);
+        }
+        *sparse_capacity_worst = cap;
+    }
+    *plan = pl;
+    return MLMC_OK;
+}
+
+void mlmc_plan_destroy(mlmc_plan_t* plan) { delete plan; }
+
+int64_t mlmc_plan_num_tiles(const mlmc_plan_t* plan) { return plan ? plan->ntiles : 0; }
+int mlmc_plan_num_planes(const mlmc_plan_t* plan) { return plan ? plan->nplanes : 0; }
+
+mlmc_status mlmc_level_norms(const mlmc_plan_t* plan, const void* g, int64_t ld, double* norms, int32_t* dev_status,
+                             void* ws, void* hip_stream) {
+    if (!plan || plan->kind != MLMC_TOPK || !g || !norms || !dev_status || !ws || ld < plan->d) return MLMC_EINVAL;
+    if ((uintptr_t)ws % 256) return MLMC_EINVAL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    TopkArgs a;
+    fill_topk_args(plan, a, g, ld, ws, dev_status);
+    a.all_thresholds = 1;
+    a.norms_user = norms;
+    mlmc_status rc = topk_zero(plan, ws, dev_status, st);
+    if (rc != MLMC_OK) return rc;
+    return topk_select(plan, a, true, vec_ok(plan, g, ld), st);
+}
+
+mlmc_status mlmc_compress_topk(const mlmc_plan_t* plan, const void* g, int64_t ld, const double* p, int p_is_norms,
+                               uint64_t seed, uint64_t step, int32_t* level, int64_t* row_off, uint32_t* idx, float* val,
+                               int64_t capacity, uint32_t* tile_off, double* norms_out, int32_t* dev_status, void* ws,
+                               void* hip_stream) {
+    if (!plan || plan->kind != MLMC_TOPK || !g || !level || !row_off || !idx || !val || !dev_status || !ws) return MLMC_EINVAL;
+    if (ld < plan->d || capacity < 0 || (uintptr_t)ws % 256) return MLMC_EINVAL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const bool vec = vec_ok(plan, g, ld);
+    const bool internal_norms = plan->adaptive && p == nullptr;
+    TopkArgs a;
+    fill_topk_args(plan, a, g, ld, ws, dev_status);
+    a.level = level;
+    a.row_off = row_off;
+    a.idx = idx;
+    a.val = val;
+    a.capacity = capacity;
+    if (tile_off) a.tile_off = tile_off;
+    a.norms_user = internal_norms ? norms_out : nullptr;
+    a.all_thresholds = internal_norms ? 1 : 0;
+
+    DrawArgs da;
+    std::memset(&da, 0, sizeof(da));
+    da.M = plan->M;
+    da.L = plan->L;
+    for (int t = 0; t <= plan->L; ++t) da.k[t] = plan->ladder[t];
+    da.is_topk = 1;
+    da.seed = seed;
+    da.step = step;
+    da.rinfo = a.rinfo;
+    da.level = level;
+    da.row_off = row_off;
+    da.capacity = capacity;
+    da.dev_status = dev_status;
+    if (p) {
+        da.mode = p_is_norms ? 2 : 1;
+        da.p_dev = p;
+    } else if (!plan->adaptive) {
+        da.mode = 0;
+        for (int l = 0; l < plan->L; ++l) da.p_fixed[l] = plan->p[l];
+    } else {
+        da.mode = 2;
+        da.p_dev = a.norms;
+    }
+
+    mlmc_status rc = topk_zero(plan, ws, dev_status, st);
+    if (rc != MLMC_OK) return rc;
+    if (!internal_norms) {  // the level is known before the data is touched: only three thresholds are needed
+        rc = topk_draw(da, st);
+        if (rc != MLMC_OK) return rc;
+    }
+    rc = topk_select(plan, a, internal_norms, vec, st);
+    if (rc != MLMC_OK) return rc;
+    if (internal_norms) {
+        rc = topk_draw(da, st);
+        if (rc != MLMC_OK) return rc;
+    }
+    return topk_compact(plan, a, vec, st);
+}
+
+mlmc_status mlmc_compress_bits(const mlmc_plan_t* plan, const void* g, int64_t ld, uint64_t seed, uint64_t step,
+                               int32_t* level, int32_t* scale_exp, uint64_t* planes, int32_t* dev_status, void* ws,
+                               void* hip_stream) {
+    if (!plan || plan->kind != MLMC_BITS || !g || !level || !scale_exp || !planes || !dev_status || !ws) return MLMC_EINVAL;
+    if (ld < plan->d || (uintptr_t)ws % 256) return MLMC_EINVAL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    BitsArgs b;
+    fill_bits_args(plan, b, g, ld, ws, dev_status);
+    b.level = level;
+    b.scale_exp = scale_exp;
+    b.planes = planes;
+    DrawArgs da;
+    std::memset(&da, 0, sizeof(da));
+    da.M = plan->M;
+    da.L = plan->L;
+    da.mode = 0;
+    for (int l = 0; l < plan->L; ++l) da.p_fixed[l] = plan->p[l];
+    da.is_topk = 0;
+    da.seed = seed;
+    da.step = step;
+    da.rinfo = b.rinfo;
+    da.level = level;
+    da.dev_status = dev_status;
+    mlmc_status rc = topk_zero(plan, ws, dev_status, st);
+    if (rc != MLMC_OK) return rc;
+    rc = topk_draw(da, st);
+    if (rc != MLMC_OK) return rc;
+    return bits_compress(plan, b, vec_ok(plan, g, ld), st);
+}
+
+mlmc_status mlmc_aggregate(const mlmc_plan_t* plan, const int32_t* level, const int64_t* row_off, const uint32_t* idx,
+                           const float* val, const uint32_t* tile_off, const int32_t* scale_exp, const uint64_t* planes,
+                           float alpha, float* out, void* ws, void* hip_stream) {
+    if (!plan || !out) return MLMC_EINVAL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (plan->kind == MLMC_TOPK) {
+        if (!row_off || !idx || !val || scale_exp || planes) return MLMC_EINVAL;
+        if (!tile_off && (!ws || (uintptr_t)ws % 256)) return MLMC_EINVAL;
+        uint32_t* tws = ws ? (uint32_t*)((char*)ws + plan->off_tileoff) : nullptr;
+        return agg_sparse(plan, row_off, idx, val, tile_off, tws, alpha, out, st);
+    }
+    if (!level || !scale_exp || !planes || row_off || idx || val || tile_off) return MLMC_EINVAL;
+    BitsArgs b;
+    fill_bits_args(plan, b, nullptr, plan->d, nullptr, nullptr);
+    return agg_bits(plan, b, level, scale_exp, planes, alpha, out, st);
+}
+
+}  // extern "C"

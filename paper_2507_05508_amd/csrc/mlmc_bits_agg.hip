@@ -1,0 +1,278 @@
+// Fixed-point bit-wise MLMC (Sec. 3.1) and the server aggregate (Alg. 2 / Alg. 3) on gfx950.
+//
+//   k_bits_max      row maximum of the |g| keys (integer atomic max) -> power-of-two scale
+//   k_bits_extract  digits m_j = floor(|g_j| / s * 2^Q), sign plane + field planes packed by wave ballot
+//   k_agg_bits      out = alpha * sum_i decode_i, rows added in worker order
+//   k_tileoff       (fallback) per-tile offsets of index-sorted sparse rows by binary search
+//   k_agg_sparse    atomic-free segmented scatter-add: one workgroup owns one dense tile
+#include "mlmc_device.h"
+
+namespace mlmc {
+
+#define MLMC_LAUNCH_CHECK()                                    \
+    do {                                                       \
+        if (hipGetLastError() != hipSuccess) return MLMC_EHIP; \
+    } while (0)
+
+// ---------------------------------------------------------------------------------------------------
+template <int DT, bool VEC>
+__global__ __launch_bounds__(512) void k_bits_max(BitsArgs a) {
+    const int row = blockIdx.y;
+    const int64_t c0 = (int64_t)blockIdx.x * a.chunk;
+    const int64_t c1 = c0 + a.chunk < a.d ? c0 + a.chunk : a.d;
+    RowLoader<DT, VEC> ld(a.g, a.ld, a.d, row);
+    uint32_t maxkey = 0;
+#pragma unroll 4
+    for (int64_t j = c0 + (int64_t)threadIdx.x * 4; j < c1; j += 512 * 4) {
+        uint32_t b[4];
+        int nv = ld.load4(j, b);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            uint32_t key = c < nv ? key_of_bits(b[c]) : 0u;
+            maxkey = key > maxkey ? key : maxkey;
+        }
+    }
+    maxkey = wave_max(maxkey);
+    if (lane_id() == 0) {
+        atomicMax(&a.racc[row].rowmax_key, maxkey);
+        if (maxkey >= 0x7F800000u) atomicOr(a.dev_status, MLMC_DEV_NONFINITE);
+    }
+}
+
+// Per-row constants of the extraction / decode.
+struct BitsRow {
+    int level, Emax, Q, F0, Fl, width;
+};
+__device__ __forceinline__ BitsRow bits_row(const BitsArgs& a, int row) {
+    BitsRow r;
+    r.level = a.rinfo[row].level;
+    uint32_t E = a.racc[row].rowmax_key >> 23;
+    r.Emax = E ? (int)E : 1;
+    r.Q = a.F[a.L];
+    r.F0 = a.F[0];
+    r.Fl = a.F[r.level];
+    r.width = a.F[r.level] - a.F[r.level - 1];
+    return r;
+}
+
+// One wave packs one tile of 4096 elements: iteration i covers elements [64 i, 64 i + 64) of the tile, so a
+// ballot is the plane word of those 64 elements; lane i keeps word i and the 64 words go out in one store.
+template <int DT>
+__global__ __launch_bounds__(256) void k_bits_extract(BitsArgs a) {
+    const int row = blockIdx.y;
+    const uint32_t lane = lane_id(), wave = threadIdx.x >> 6;
+    const BitsRow br = bits_row(a, row);
+    const int np = 1 + br.F0 + br.width;  // planes written for this row
+    RowLoader<DT, false> ld(a.g, a.ld, a.d, row);
+    const int64_t ntiles = (a.d + TILE - 1) / TILE;
+    if (blockIdx.x == 0 && threadIdx.x == 0) a.scale_exp[row] = br.Emax - 126;
+    for (int64_t tile = (int64_t)blockIdx.x * 4 + wave; tile < ntiles; tile += (int64_t)gridDim.x * 4) {
+        const int64_t base = tile * TILE;
+        uint64_t words[MAX_PLANES];
+#pragma unroll
+        for (int p = 0; p < MAX_PLANES; ++p) words[p] = 0;
+#pragma unroll 8
+        for (int i = 0; i < 64; ++i) {
+            const int64_t j = base + i * 64 + lane;
+            uint32_t bits = j < a.d ? ld.load1(j) : 0u;
+            uint32_t key = key_of_bits(bits);
+            uint32_t E = key >> 23;
+            uint32_t sig = E ? ((key & 0x7FFFFFu) | 0x800000u) : (key & 0x7FFFFFu);
+            int shift = (24 - br.Q) + (br.Emax - (int)(E ? E : 1u));
+            uint32_t m = shift < 32 ? (sig >> shift) : 0u;   // floor(|g| / 2^e * 2^Q), e = Emax - 126
+            uint32_t f0 = br.F0 ? (m >> (br.Q - br.F0)) : 0u;
+            uint32_t f = (m >> (br.Q - br.Fl)) & ((1u << br.width) - 1u);
+            uint32_t packed = (bits >> 31) | (f0 << 1) | (f << (1 + br.F0));  // plane p <-> bit p
+#pragma unroll
+            for (int p = 0; p < MAX_PLANES; ++p) {
+                if (p < np) {
+                    uint64_t w = __ballot((packed >> p) & 1u);
+                    if (lane == (uint32_t)i) words[p] = w;
+                }
+            }
+        }
+        const int64_t w0 = tile * 64 + lane;
+        if (w0 < a.nwords) {
+            uint64_t* dst = a.planes + (size_t)row * a.nplanes * a.nwords + w0;
+#pragma unroll
+            for (int p = 0; p < MAX_PLANES; ++p)
+                if (p < np) dst[(size_t)p * a.nwords] = words[p];
+        }
+    }
+}
+
+struct AggBitsArgs {
+    BitsArgs b;
+    const int32_t* level;
+    const int32_t* scale_exp;
+    const uint64_t* planes;
+    float alpha;
+    float* out;
+};
+
+// out[j] = alpha * sum over rows (worker order) of sign * (f0 * c0 + f * cl): Alg. 2 "Server aggregates".
+__global__ __launch_bounds__(256) void k_agg_bits(AggBitsArgs a) {
+    __shared__ float s_c0[MLMC_MAX_WORKERS], s_cl[MLMC_MAX_WORKERS];
+    __shared__ uint8_t s_w[MLMC_MAX_WORKERS];
+    const BitsArgs& b = a.b;
+    const int F0 = b.F[0];
+    for (int r = threadIdx.x; r < b.M; r += 256) {
+        int lev = a.level[r];
+        int e = a.scale_exp[r];
+        double pl = b.p_fixed[lev - 1];
+        s_c0[r] = (float)ldexp(1.0, e - F0);
+        s_cl[r] = pl == 0.0 ? 0.0f : (float)__ddiv_rn(ldexp(1.0, e - b.F[lev]), pl);
+        s_w[r] = (uint8_t)(b.F[lev] - b.F[lev - 1]);
+    }
+    __syncthreads();
+    const uint32_t lane = lane_id();
+    const int64_t nw = b.nwords;
+    const int64_t wave_global = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 6;
+    const int64_t nwaves = ((int64_t)gridDim.x * 256) >> 6;
+    for (int64_t w = wave_global; w < nw; w += nwaves) {
+        float acc = 0.0f;
+        for (int r = 0; r < b.M; ++r) {
+            const uint64_t* pr = a.planes + (size_t)r * b.nplanes * nw + w;
+            uint32_t sign = (uint32_t)(pr[0] >> lane) & 1u;
+            uint32_t f0 = 0, f = 0;
+            for (int p = 0; p < F0; ++p) f0 |= ((uint32_t)(pr[(size_t)(1 + p) * nw] >> lane) & 1u) << p;
+            const int width = s_w[r];
+            for (int p = 0; p < width; ++p) f |= ((uint32_t)(pr[(size_t)(1 + F0 + p) * nw] >> lane) & 1u) << p;
+            float v = __fmul_rn((float)f, s_cl[r]);
+            if (F0 > 0) v = __fadd_rn(__fmul_rn((float)f0, s_c0[r]), v);
+            acc = __fadd_rn(acc, sign ? -v : v);
+        }
+        const int64_t j = w * 64 + lane;
+        if (j < b.d) a.out[j] = __fmul_rn(a.alpha, acc);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
+struct AggSparseArgs {
+    int32_t M;
+    int64_t d, ntiles;
+    const int64_t* row_off;
+    const uint32_t* idx;
+    const float* val;
+    const uint32_t* tile_off;  // [M][ntiles + 1]
+    uint32_t* tile_off_out;    // k_tileoff target
+    float alpha;
+    float* out;
+};
+
+__global__ __launch_bounds__(256) void k_tileoff(AggSparseArgs a) {
+    const int64_t n = (int64_t)a.M * (a.ntiles + 1);
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+        const int r = (int)(i / (a.ntiles + 1));
+        const int64_t t = i % (a.ntiles + 1);
+        const int64_t s = a.row_off[r], e = a.row_off[r + 1];
+        const uint64_t target = (uint64_t)t * TILE;
+        int64_t lo = s, hi = e;  // first position with idx >= target
+        while (lo < hi) {
+            int64_t mid = lo + ((hi - lo) >> 1);
+            if ((uint64_t)a.idx[mid] < target) lo = mid + 1; else hi = mid;
+        }
+        a.tile_off_out[i] = (uint32_t)(lo - s);
+    }
+}
+
+// One workgroup per dense tile: LDS accumulators, rows added one after the other (indices within a row are
+// distinct, so plain read-modify-write is race free), then one coalesced write of alpha * acc.
+__global__ __launch_bounds__(256) void k_agg_sparse(AggSparseArgs a) {
+    __shared__ float s_acc[TILE];
+    __shared__ int64_t s_beg[MLMC_MAX_WORKERS];
+    __shared__ uint32_t s_len[MLMC_MAX_WORKERS];
+    const int64_t tile = blockIdx.x;
+    const int64_t base = tile * TILE;
+    for (int i = threadIdx.x; i < TILE; i += 256) s_acc[i] = 0.0f;
+    for (int r = threadIdx.x; r < a.M; r += 256) {
+        const uint32_t* to = a.tile_off + (size_t)r * (a.ntiles + 1);
+        s_beg[r] = a.row_off[r] + to[tile];
+        s_len[r] = to[tile + 1] - to[tile];
+    }
+    __syncthreads();
+    for (int r = 0; r < a.M; ++r) {
+        const int64_t beg = s_beg[r];
+        const uint32_t len = s_len[r];
+        if (len) {  // uniform
+            for (uint32_t i = threadIdx.x; i < len; i += 256) {
+                uint32_t off = a.idx[beg + i] - (uint32_t)base;
+                if (off < (uint32_t)TILE) s_acc[off] = __fadd_rn(s_acc[off], a.val[beg + i]);
+            }
+            __syncthreads();
+        }
+    }
+    for (int i = threadIdx.x; i < TILE; i += 256) {
+        int64_t j = base + i;
+        if (j < a.d) a.out[j] = __fmul_rn(a.alpha, s_acc[i]);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
+mlmc_status bits_compress(const mlmc_plan_t* pl, const BitsArgs& a, bool vec, hipStream_t st) {
+    dim3 grid(pl->chunks_per_row, pl->M);
+    if (pl->dtype == MLMC_F32) {
+        if (vec) k_bits_max<MLMC_F32, true><<<grid, 512, 0, st>>>(a);
+        else k_bits_max<MLMC_F32, false><<<grid, 512, 0, st>>>(a);
+    } else {
+        if (vec) k_bits_max<MLMC_BF16, true><<<grid, 512, 0, st>>>(a);
+        else k_bits_max<MLMC_BF16, false><<<grid, 512, 0, st>>>(a);
+    }
+    MLMC_LAUNCH_CHECK();
+    int64_t ntiles = pl->ntiles;
+    int gx = (int)((ntiles + 3) / 4);
+    int cap = 4096 / pl->M > 0 ? 4096 / pl->M : 1;
+    if (gx > cap) gx = cap;
+    if (gx < 1) gx = 1;
+    dim3 egrid(gx, pl->M);
+    if (pl->dtype == MLMC_F32) k_bits_extract<MLMC_F32><<<egrid, 256, 0, st>>>(a);
+    else k_bits_extract<MLMC_BF16><<<egrid, 256, 0, st>>>(a);
+    MLMC_LAUNCH_CHECK();
+    return MLMC_OK;
+}
+
+mlmc_status agg_bits(const mlmc_plan_t* pl, const BitsArgs& b, const int32_t* level, const int32_t* scale_exp,
+                     const uint64_t* planes, float alpha, float* out, hipStream_t st) {
+    AggBitsArgs a;
+    a.b = b;
+    a.level = level;
+    a.scale_exp = scale_exp;
+    a.planes = planes;
+    a.alpha = alpha;
+    a.out = out;
+    int64_t waves = b.nwords;
+    int blocks = (int)((waves + 3) / 4);
+    if (blocks > 8192) blocks = 8192;
+    if (blocks < 1) blocks = 1;
+    k_agg_bits<<<blocks, 256, 0, st>>>(a);
+    MLMC_LAUNCH_CHECK();
+    return MLMC_OK;
+}
+
+mlmc_status agg_sparse(const mlmc_plan_t* pl, const int64_t* row_off, const uint32_t* idx, const float* val,
+                       const uint32_t* tile_off, uint32_t* tile_off_ws, float alpha, float* out, hipStream_t st) {
+    AggSparseArgs a;
+    a.M = pl->M;
+    a.d = pl->d;
+    a.ntiles = pl->ntiles;
+    a.row_off = row_off;
+    a.idx = idx;
+    a.val = val;
+    a.tile_off = tile_off;
+    a.tile_off_out = tile_off_ws;
+    a.alpha = alpha;
+    a.out = out;
+    if (!tile_off) {
+        int64_t n = (int64_t)pl->M * (pl->ntiles + 1);
+        int blocks = (int)((n + 255) / 256);
+        if (blocks > 4096) blocks = 4096;
+        k_tileoff<<<blocks, 256, 0, st>>>(a);
+        MLMC_LAUNCH_CHECK();
+        a.tile_off = tile_off_ws;
+    }
+    k_agg_sparse<<<(unsigned)pl->ntiles, 256, 0, st>>>(a);
+    MLMC_LAUNCH_CHECK();
+    return MLMC_OK;
+}
+
+}  // namespace mlmc

@@ -1,0 +1,74 @@
+"""GPU parity of the fixed-point bit-wise MLMC path and its aggregate against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import mlmc_workloads as W
+import paper_2507_05508_amd as P
+from oracle import mlmc as O
+from gpu_util import to_device
+
+pytestmark = pytest.mark.gpu
+
+
+def _check_bits(plan, G, F, p, seed, step, msg):
+    torch.cuda.synchronize()
+    M, d = G.shape
+    level = msg.level.cpu().numpy()
+    sexp = msg.scale_exp.cpu().numpy()
+    planes = msg.planes.cpu().numpy().view(np.uint64)
+    want = O.compress_bits(G, F, p, seed, step)
+    for i in range(M):
+        assert level[i] == want[i]["level"] and sexp[i] == want[i]["scale_exp"], (i, level[i], sexp[i], want[i]["level"], want[i]["scale_exp"])
+        n = want[i]["planes"].shape[0]
+        assert np.array_equal(planes[i, :n], want[i]["planes"]), f"row {i}: planes differ"
+    return want
+
+
+@pytest.mark.parametrize("F", [[0, 1, 2, 4, 8, 16], [2, 3, 8, 12], [0, 24], list(range(17))])
+@pytest.mark.parametrize("d", [3 * 4096 + 77, 64, 100_003])
+def test_bits_compress_and_aggregate(F, d):
+    w = W.scaled(W.WORKLOADS["resnet18_bits"], d=d, M=3)
+    G = W.generate(w)
+    L = len(F) - 1
+    p = O.geometric_p(L)
+    plan = P.Plan(P.MLMC_BITS, 3, d, P.MLMC_F32, F, p)
+    g = to_device(G)
+    for step in range(5):
+        print(f"bits F={F} d={d} step={step}", flush=True)
+        msg = P.mlmc_compress_bits(plan, g, seed=11, step=step)
+        want = _check_bits(plan, G, F, p, 11, step, msg)
+        assert plan.status() == 0
+        out = P.mlmc_aggregate(plan, msg, 1.0 / 3)
+        torch.cuda.synchronize()
+        ref = O.aggregate_bits(want, F, d, 1.0 / 3)
+        assert np.array_equal(out.cpu().numpy().view(np.uint32), ref.view(np.uint32))
+
+
+def test_bits_adversarial_and_padded_rows():
+    d = 2 * 4096 + 300
+    G = np.stack(W.adversarial_rows(d))
+    F = [0, 1, 2, 4, 8, 16]
+    p = O.geometric_p(5)
+    plan = P.Plan(P.MLMC_BITS, G.shape[0], d, P.MLMC_F32, F, p)
+    for ld in (d, d + 1, d + 6):
+        g = to_device(G, ld=ld)
+        for step in range(3):
+            print(f"bits adversarial ld={ld} step={step}", flush=True)
+            msg = P.mlmc_compress_bits(plan, g, seed=2, step=step)
+            want = _check_bits(plan, G, F, p, 2, step, msg)
+            out = P.mlmc_aggregate(plan, msg, 1.0)
+            torch.cuda.synchronize()
+            assert np.array_equal(out.cpu().numpy().view(np.uint32), O.aggregate_bits(want, F, d, 1.0).view(np.uint32))
+
+
+def test_bits_bf16_rows():
+    w = W.scaled(W.WORKLOADS["bert_adaptive_topk_bf16"], d=50_000, M=2)
+    G = W.generate(w)
+    F = [0, 1, 2, 4, 8]
+    p = O.geometric_p(4)
+    plan = P.Plan(P.MLMC_BITS, 2, w.d, P.MLMC_BF16, F, p)
+    g = to_device(G)
+    for step in range(3):
+        msg = P.mlmc_compress_bits(plan, g, seed=1, step=step)
+        _check_bits(plan, G, F, p, 1, step, msg)

@@ -1,0 +1,209 @@
+"""GPU parity of the Top-k MLMC path against the CPU oracle, element by element, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import mlmc_workloads as W
+import paper_2507_05508_amd as P
+from oracle import mlmc as O
+from gpu_util import check_topk_against_oracle, to_device, u32
+
+pytestmark = pytest.mark.gpu
+
+
+def _plan_for(w, p_fixed):
+    return P.Plan(P.MLMC_TOPK, w.M, w.d, P.MLMC_BF16 if w.dtype == "bf16" else P.MLMC_F32, w.ladder, p_fixed)
+
+
+@pytest.mark.parametrize("d", [65536, 5 * 4096 + 123, 1000])
+def test_fixed_p_tiny_workload(d):
+    w = W.scaled(W.WORKLOADS["tiny_topk"], d=d)
+    G = W.generate(w)
+    p = O.geometric_p(w.L)
+    plan = _plan_for(w, p)
+    g = to_device(G)
+    seen = set()
+    for step in range(12):
+        print(f"tiny_topk d={d} step={step}", flush=True)
+        msg = P.mlmc_compress_topk(plan, g, seed=0, step=step)
+        want = check_topk_against_oracle(plan, G, 0, step, msg, adaptive=False)
+        assert plan.status() == 0
+        seen |= {m["level"] for m in want}
+        out = P.mlmc_aggregate(plan, msg, 1.0 / w.M)
+        torch.cuda.synchronize()
+        ref = O.aggregate_sparse(want, w.d, 1.0 / w.M)
+        assert np.array_equal(out.cpu().numpy().view(np.uint32), ref.view(np.uint32))
+    assert len(seen) >= 3
+
+
+@pytest.mark.parametrize("name,d,M", [("resnet18_topk", 3 * 65536 + 4096 + 77, 3), ("resnet50_adaptive_topk", 300_001, 2)])
+def test_fixed_p_segmented(name, d, M):
+    w = W.scaled(W.WORKLOADS[name], d=d, M=M)
+    G = W.generate(w)
+    p = O.geometric_p(w.L)
+    plan = _plan_for(w, p)
+    g = to_device(G)
+    for step in (0, 1, 2, 7, 100, 2 ** 40 + 5):
+        print(f"{name} fixed d={d} step={step}", flush=True)
+        msg = P.mlmc_compress_topk(plan, g, seed=1234567890123, step=step)
+        want = check_topk_against_oracle(plan, G, 1234567890123, step, msg, adaptive=False)
+        assert plan.status() == 0
+        for use_tile in (True, False):
+            out = P.mlmc_aggregate(plan, msg, 0.5, use_tile_off=use_tile)
+            torch.cuda.synchronize()
+            ref = O.aggregate_sparse(want, w.d, 0.5)
+            assert np.array_equal(out.cpu().numpy().view(np.uint32), ref.view(np.uint32))
+
+
+@pytest.mark.parametrize("name,d,M", [("resnet50_adaptive_topk", 5 * 65536 + 999, 3), ("resnet18_topk", 70_000, 2),
+                                       ("tiny_topk", 20_000, 2)])
+def test_adaptive_norms_and_compress(name, d, M):
+    w = W.scaled(W.WORKLOADS[name], d=d, M=M)
+    G = W.generate(w)
+    plan = _plan_for(w, None)
+    g = to_device(G)
+    print(f"{name} adaptive norms d={d}", flush=True)
+    norms = P.mlmc_level_norms(plan, g)
+    torch.cuda.synchronize()
+    assert plan.status() == 0
+    got = norms.cpu().numpy()
+    for i in range(M):
+        want, _ = O.level_norms_row(G[i], w.ladder)
+        assert np.array_equal(got[i].view(np.uint64), np.array(want, dtype=np.float64).view(np.uint64)), (i, got[i], want)
+    for step in range(6):
+        print(f"{name} adaptive compress d={d} step={step}", flush=True)
+        msg = P.mlmc_compress_topk(plan, g, seed=42, step=step)
+        want = check_topk_against_oracle(plan, G, 42, step, msg, adaptive=True)
+        assert plan.status() == 0
+        assert np.array_equal(msg.norms.cpu().numpy().view(np.uint64), got.view(np.uint64))
+        out = P.mlmc_aggregate(plan, msg, 1.0)
+        torch.cuda.synchronize()
+        ref = O.aggregate_sparse(want, w.d, 1.0)
+        assert np.array_equal(out.cpu().numpy().view(np.uint32), ref.view(np.uint32))
+    # caller-supplied norms / probabilities take the three-threshold path and give the same message
+    msg2 = P.mlmc_compress_topk(plan, g, seed=42, step=3, p=norms, p_is_norms=True)
+    check_topk_against_oracle(plan, G, 42, 3, msg2, adaptive=True)
+    pt = torch.tensor([O.adaptive_p(list(got[i])) for i in range(M)], dtype=torch.float64, device=g.device)
+    msg3 = P.mlmc_compress_topk(plan, g, seed=42, step=4, p=pt, p_is_norms=False)
+    check_topk_against_oracle(plan, G, 42, 4, msg3, adaptive=True)
+
+
+def test_adversarial_rows_ties_zeros_denormals():
+    d = 3 * 4096 + 517
+    rows = W.adversarial_rows(d)
+    G = np.stack(rows)
+    M = G.shape[0]
+    ladder = [5, 100, 101, 1000, 4096, 9000, d - 1, d]
+    L = len(ladder) - 1
+    g = to_device(G)
+    plan_a = P.Plan(P.MLMC_TOPK, M, d, P.MLMC_F32, ladder, None)
+    print("adversarial norms", flush=True)
+    norms = P.mlmc_level_norms(plan_a, g).cpu().numpy()
+    for i in range(M):
+        want, _ = O.level_norms_row(G[i], ladder)
+        assert np.array_equal(norms[i].view(np.uint64), np.array(want).view(np.uint64)), (i, norms[i], want)
+    plan_f = P.Plan(P.MLMC_TOPK, M, d, P.MLMC_F32, ladder, O.geometric_p(L))
+    for step in range(10):
+        print(f"adversarial step={step}", flush=True)
+        msg = P.mlmc_compress_topk(plan_f, g, seed=9, step=step)
+        check_topk_against_oracle(plan_f, G, 9, step, msg, adaptive=False)
+        assert plan_f.status() == 0
+        msg = P.mlmc_compress_topk(plan_a, g, seed=9, step=step)
+        want = check_topk_against_oracle(plan_a, G, 9, step, msg, adaptive=True)
+        assert plan_a.status() == 0
+        out = P.mlmc_aggregate(plan_a, msg, 0.125)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy().view(np.uint32), O.aggregate_sparse(want, d, 0.125).view(np.uint32))
+
+
+@pytest.mark.parametrize("ld_pad", [1, 2, 3, 8])
+def test_padded_and_misaligned_rows(ld_pad):
+    w = W.scaled(W.WORKLOADS["resnet18_topk"], d=2 * 4096 + 1001, M=3)
+    G = W.generate(w)
+    g = to_device(G, ld=w.d + ld_pad)
+    plan = _plan_for(w, None)
+    for step in range(3):
+        print(f"padded ld=d+{ld_pad} step={step}", flush=True)
+        msg = P.mlmc_compress_topk(plan, g, seed=5, step=step)
+        check_topk_against_oracle(plan, G, 5, step, msg, adaptive=True)
+        assert plan.status() == 0
+
+
+def test_bf16_rows():
+    w = W.scaled(W.WORKLOADS["bert_adaptive_topk_bf16"], d=4 * 65536 + 4096 * 3 + 5, M=2)
+    G = W.generate(w)
+    assert G.dtype == np.uint16
+    g = to_device(G)
+    plan = _plan_for(w, None)
+    print("bf16 norms", flush=True)
+    norms = P.mlmc_level_norms(plan, g).cpu().numpy()
+    for i in range(w.M):
+        want, _ = O.level_norms_row(G[i], w.ladder)
+        assert np.array_equal(norms[i].view(np.uint64), np.array(want).view(np.uint64))
+    for step in range(6):
+        print(f"bf16 step={step}", flush=True)
+        msg = P.mlmc_compress_topk(plan, g, seed=77, step=step)
+        check_topk_against_oracle(plan, G, 77, step, msg, adaptive=True)
+        assert plan.status() == 0
+    g2 = to_device(G, ld=w.d + 3)
+    msg = P.mlmc_compress_topk(plan, g2, seed=77, step=1)
+    check_topk_against_oracle(plan, G, 77, 1, msg, adaptive=True)
+
+
+@pytest.mark.parametrize("d,ladder", [(1, [0, 1]), (5, [0, 2, 5]), (64, [0, 1, 2, 3, 64]), (4097, [0, 4097]),
+                                       (9000, [10, 20, 8000]), (4096, [4095, 4096])])
+def test_degenerate_shapes(d, ladder):
+    rng = np.random.default_rng(d)
+    G = rng.standard_normal((2, d)).astype(np.float32)
+    L = len(ladder) - 1
+    g = to_device(G)
+    for pf in (O.geometric_p(L), None):
+        plan = P.Plan(P.MLMC_TOPK, 2, d, P.MLMC_F32, ladder, pf)
+        for step in range(4):
+            print(f"degenerate d={d} ladder={ladder} adaptive={pf is None} step={step}", flush=True)
+            msg = P.mlmc_compress_topk(plan, g, seed=3, step=step)
+            want = check_topk_against_oracle(plan, G, 3, step, msg, adaptive=pf is None)
+            assert plan.status() == 0
+            out = P.mlmc_aggregate(plan, msg, 0.5)
+            torch.cuda.synchronize()
+            assert np.array_equal(out.cpu().numpy().view(np.uint32), O.aggregate_sparse(want, d, 0.5).view(np.uint32))
+
+
+def test_identity_ladder_is_dense_mean():
+    """L = 1, k_0 = 0, k_1 = d, p = 1: the message is the gradient and the aggregate is Alg. 1's mean."""
+    rng = np.random.default_rng(0)
+    M, d = 4, 10_000
+    G = rng.standard_normal((M, d)).astype(np.float32)
+    plan = P.Plan(P.MLMC_TOPK, M, d, P.MLMC_F32, [0, d], [1.0])
+    g = to_device(G)
+    msg = P.mlmc_compress_topk(plan, g, seed=0, step=0)
+    out = P.mlmc_aggregate(plan, msg, 0.25).cpu().numpy()
+    acc = np.zeros(d, dtype=np.float32)
+    for i in range(M):
+        acc = acc + G[i]
+    assert np.array_equal(out, acc * np.float32(0.25))
+
+
+def test_capacity_and_nonfinite_flags():
+    w = W.scaled(W.WORKLOADS["resnet18_topk"], d=20_000, M=2)
+    G = W.generate(w)
+    plan = _plan_for(w, O.geometric_p(w.L))
+    g = to_device(G)
+    small = P.SparseMessage(plan, capacity=10)
+    guard = torch.full_like(small.idx, -1)
+    P.mlmc_compress_topk(plan, g, seed=0, step=0, out=small)
+    assert plan.status() & P.MLMC_DEV_CAPACITY
+    want = O.compress_topk(G, w.ladder, plan.p_fixed, 0, 0)
+    assert np.array_equal(u32(small.idx)[:10], want[0]["idx"][:10])   # what fits is still correct
+    G2 = G.copy()
+    G2[1, 17] = np.inf
+    G2[0, 5] = np.nan
+    g2 = to_device(G2)
+    msg = P.mlmc_compress_topk(plan, g2, seed=0, step=1)
+    assert plan.status() & P.MLMC_DEV_NONFINITE
+    want = O.compress_topk(G2, w.ladder, plan.p_fixed, 0, 1)
+    off = 0
+    for i in range(2):
+        n = len(want[i]["idx"])
+        assert np.array_equal(u32(msg.idx)[off:off + n], want[i]["idx"])   # ordered by bit pattern
+        off += n
