@@ -1,0 +1,213 @@
+#!/usr/bin/env python3
+"""Benchmark of the MLMC compress + aggregate hot path on one MI355X.
+
+One "step" = one pass of the whole hot path over one batch of M synthetic gradient rows that are already
+resident in HBM: (adaptive: per-level norms +) level draw + compress + server aggregate.  The step index
+changes every step, so different levels (hence different message sizes) are drawn.
+
+Prints ONE JSON line: metric = GB/s of gradient input (M * d * sizeof(input) / step time), with
+  roofline     -- the dominant kernel's algorithmic bytes per launch / its HIP-event duration vs 8 TB/s HBM
+  cpu_baseline -- the CPU oracle timed on a bounded sample of the same workload (rows are independent)
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import mlmc_workloads as W  # noqa: E402
+
+HBM_PEAK_GBPS = 8000.0
+DEFAULT_WORKLOAD = "resnet50_adaptive_topk"
+
+
+def algorithmic_bytes(w, kernel, nnz_total, planes_bytes):
+    """Bytes the method itself has to move in one launch of `kernel` ('Kernels')."""
+    s_in = 2 if w.dtype == "bf16" else 4
+    in_bytes = w.M * w.d * s_in
+    if kernel in ("k_hist1", "k_pass2", "k_count", "k_bits_max"):
+        return in_bytes                                   # one read of every input element
+    if kernel == "k_write":
+        return in_bytes + 8 * nnz_total                   # read the rows, write (idx, val)
+    if kernel == "k_agg_sparse":
+        return 8 * nnz_total + 4 * w.d                    # read the messages, write the dense update
+    if kernel == "k_bits_extract":
+        return in_bytes + planes_bytes
+    if kernel == "k_agg_bits":
+        return planes_bytes + 4 * w.d
+    return 0
+
+
+def cpu_baseline(w, G, budget_s=25.0):
+    """The oracle as it stands, single thread, on the first rows of the same workload until ~budget_s."""
+    from oracle import mlmc as O
+    s_in = 2 if w.dtype == "bf16" else 4
+    t0 = time.perf_counter()
+    msgs, rows = [], 0
+    p = None if w.adaptive else O.geometric_p(w.L)
+    for i in range(w.M):
+        if w.kind == "topk":
+            msgs.append(O.compress_topk_row(G[i], w.ladder, p, w.seed, 0, i))
+        else:
+            msgs.append(O.compress_bits_row(G[i], w.ladder, p, w.seed, 0, i))
+        rows += 1
+        if time.perf_counter() - t0 > budget_s * 0.8:
+            break
+    if w.kind == "topk":
+        O.aggregate_sparse(msgs, w.d, 1.0 / w.M)
+    else:
+        O.aggregate_bits(msgs, w.ladder, w.d, 1.0 / w.M)
+    dt = time.perf_counter() - t0
+    return {"value": rows * w.d * s_in / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"{rows} of {w.M} rows of {w.name} (d={w.d}), one step: compress + aggregate, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD, choices=sorted(W.WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-budget", type=float, default=25.0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 1 GiB device copy (a known-size kernel to scale profiler byte counters by)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (M workers are M rows on one MI355X); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2507_05508_amd as P
+
+    w = W.WORKLOADS[args.workload]
+    t_gen = time.perf_counter()
+    G = W.generate(w)
+    print(f"[bench] generated {w.name}: M={w.M} d={w.d} {w.dtype} in {time.perf_counter() - t_gen:.1f} s", file=sys.stderr, flush=True)
+    dev = torch.device("cuda:0")
+    if w.dtype == "bf16":
+        g = torch.from_numpy(G.view(np.int16)).to(dev).view(torch.bfloat16)
+    else:
+        g = torch.from_numpy(G).to(dev)
+    s_in = 2 if w.dtype == "bf16" else 4
+    in_bytes = w.M * w.d * s_in
+    alpha = 1.0 / w.M
+
+    if w.kind == "topk":
+        plan = P.Plan(P.MLMC_TOPK, w.M, w.d, P.MLMC_BF16 if w.dtype == "bf16" else P.MLMC_F32, w.ladder,
+                      None if w.adaptive else P.mlmc_geometric_p(w.L))
+        msg = P.SparseMessage(plan, with_norms=w.adaptive)
+    else:
+        plan = P.Plan(P.MLMC_BITS, w.M, w.d, P.MLMC_F32, w.ladder, P.mlmc_geometric_p(w.L))
+        msg = P.BitsMessage(plan)
+    out = torch.empty(w.d, dtype=torch.float32, device=dev)
+
+    def step(i):
+        if w.kind == "topk":
+            P.mlmc_compress_topk(plan, g, seed=w.seed, step=i, out=msg)
+        else:
+            P.mlmc_compress_bits(plan, g, seed=w.seed, step=i, out=msg)
+        P.mlmc_aggregate(plan, msg, alpha, out=out)
+
+    if args.calibrate_copy:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    assert plan.status() == 0, f"device status {plan.status()}"
+
+    # timed region: K steps, whole-job wall clock between two synchronisations
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt * 1e3 / args.steps
+    assert plan.status() == 0, f"device status {plan.status()}"
+
+    # same K steps again with a HIP-event pair around every kernel (on the launch stream)
+    nnz_total, planes_bytes = 0, 0
+    P.mlmc_profile_reset()
+    P.mlmc_profile_enable(True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+        if w.kind == "topk":
+            pass
+    torch.cuda.synchronize()
+    dt_ev = time.perf_counter() - t1
+    P.mlmc_profile_enable(False)
+    prof = P.mlmc_profile_get()
+    # message sizes of those steps (needed for the algorithmic bytes): replay the draws, cheap
+    for i in range(args.steps):
+        if w.kind == "topk":
+            P.mlmc_compress_topk(plan, g, seed=w.seed, step=args.warmup + i, out=msg)
+            nnz_total += int(msg.row_off[-1].item())
+        else:
+            P.mlmc_compress_bits(plan, g, seed=w.seed, step=args.warmup + i, out=msg)
+            lv = msg.level.cpu().numpy()
+            widths = [w.ladder[l] - w.ladder[l - 1] for l in lv]
+            planes_bytes += sum((1 + w.ladder[0] + x) * ((w.d + 63) // 64) * 8 for x in widths)
+    nnz_avg = nnz_total / args.steps
+    planes_avg = planes_bytes / args.steps
+
+    kern = {k: {"avg_us": ms * 1e3 / n, "launches": n, "share": ms / sum(v[0] for v in prof.values())}
+            for k, (ms, n) in prof.items()}
+    dominant = max(prof, key=lambda k: prof[k][0])
+    dom_avg_s = prof[dominant][0] / prof[dominant][1] / 1e3
+    dom_bytes = algorithmic_bytes(w, dominant, nnz_avg, planes_avg)
+    achieved = dom_bytes / dom_avg_s / 1e9
+    if w.kind == "topk":
+        step_alg_bytes = in_bytes + 16 * nnz_avg + 4 * w.d
+    else:
+        step_alg_bytes = in_bytes + 2 * planes_avg + 4 * w.d
+
+    value = in_bytes / (ms_per_step * 1e-3) / 1e9
+    result = {
+        "metric": "mlmc_compress_aggregate_input_throughput",
+        "value": round(value, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32" if w.dtype == "f32" else "bf16",
+        "data": "synthetic",
+        "config": {"workload": w.name, "M": w.M, "d": w.d, "L": w.L, "kind": w.kind,
+                   "p": "adaptive" if w.adaptive else "fixed_geometric", "input_bytes": in_bytes,
+                   "avg_nnz_per_step": round(nnz_avg, 1), "alpha": alpha},
+        "hbm_peak_frac_input": round(value / HBM_PEAK_GBPS, 4),
+        "hbm_peak_frac_algorithmic": round(step_alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+        "ms_per_step_with_events": round(dt_ev * 1e3 / args.steps, 4),
+        "roofline": {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "avg_us": round(dom_avg_s * 1e6, 2), "algorithmic_bytes_per_launch": int(dom_bytes)},
+        "kernels": {k: {"avg_us": round(v["avg_us"], 2), "launches": v["launches"], "share": round(v["share"], 4)}
+                    for k, v in sorted(kern.items(), key=lambda kv: -kv[1]["share"])},
+    }
+    if not args.no_cpu_baseline:
+        del g
+        result["cpu_baseline"] = cpu_baseline(w, G, args.cpu_budget)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

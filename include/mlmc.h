@@ -145,6 +145,18 @@ mlmc_status mlmc_aggregate(const mlmc_plan_t *plan, const int32_t *level, const 
                            const int32_t *scale_exp, const uint64_t *planes, float alpha, float *out,
                            void *ws, void *hip_stream);
 
+/*
+ * Per-kernel timing for benchmarks (measurement aid, not part of the method).  While enabled, every kernel
+ * the library launches is bracketed by a pair of HIP events on the launch stream; mlmc_profile_get waits
+ * for the recorded events and returns the accumulated device time and launch count of kernel `id`
+ * (0 <= id < mlmc_profile_num_kernels()).  Host side, process wide, not thread safe; off by default.
+ */
+void mlmc_profile_enable(int on);
+void mlmc_profile_reset(void);
+int mlmc_profile_num_kernels(void);
+const char *mlmc_profile_kernel_name(int id);
+mlmc_status mlmc_profile_get(int id, double *total_ms, int64_t *launches);
+
 #ifdef __cplusplus
 }
 #endif

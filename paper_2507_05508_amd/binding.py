@@ -23,7 +23,9 @@ MLMC_TILE = 4096
 MLMC_MAX_LEVELS = 32
 
 EXPORTS = ["mlmc_plan", "mlmc_plan_destroy", "mlmc_plan_num_tiles", "mlmc_plan_num_planes", "mlmc_geometric_p",
-           "mlmc_status_string", "mlmc_level_norms", "mlmc_compress_topk", "mlmc_compress_bits", "mlmc_aggregate"]
+           "mlmc_status_string", "mlmc_level_norms", "mlmc_compress_topk", "mlmc_compress_bits", "mlmc_aggregate",
+           "mlmc_profile_enable", "mlmc_profile_reset", "mlmc_profile_num_kernels", "mlmc_profile_kernel_name",
+           "mlmc_profile_get"]
 
 _lib = None
 
@@ -61,8 +63,37 @@ def lib():
         L.mlmc_compress_bits.argtypes = [vp, vp, i64, u64, u64, vp, vp, vp, vp, vp, vp]
         L.mlmc_aggregate.restype = C.c_int
         L.mlmc_aggregate.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, C.c_float, vp, vp, vp]
+        L.mlmc_profile_enable.restype = None
+        L.mlmc_profile_enable.argtypes = [i32]
+        L.mlmc_profile_reset.restype = None
+        L.mlmc_profile_reset.argtypes = []
+        L.mlmc_profile_num_kernels.restype = i32
+        L.mlmc_profile_num_kernels.argtypes = []
+        L.mlmc_profile_kernel_name.restype = C.c_char_p
+        L.mlmc_profile_kernel_name.argtypes = [i32]
+        L.mlmc_profile_get.restype = C.c_int
+        L.mlmc_profile_get.argtypes = [i32, dbl_p, C.POINTER(i64)]
         _lib = L
     return _lib
+
+
+def mlmc_profile_enable(on: bool):
+    lib().mlmc_profile_enable(int(bool(on)))
+
+
+def mlmc_profile_reset():
+    lib().mlmc_profile_reset()
+
+
+def mlmc_profile_get():
+    """{kernel name: (total device ms, launches)} since the last reset (waits for the recorded events)."""
+    out = {}
+    for i in range(lib().mlmc_profile_num_kernels()):
+        ms, n = C.c_double(), C.c_int64()
+        _check(lib().mlmc_profile_get(i, C.byref(ms), C.byref(n)), "mlmc_profile_get")
+        if n.value:
+            out[lib().mlmc_profile_kernel_name(i).decode()] = (ms.value, n.value)
+    return out
 
 
 def _check(rc: int, what: str):

@@ -4,6 +4,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
+#include <vector>
 
 #include "mlmc_internal.h"
 
@@ -19,6 +20,48 @@ mlmc_status agg_sparse(const mlmc_plan_t* pl, const int64_t* row_off, const uint
                        const uint32_t* tile_off, uint32_t* tile_off_ws, float alpha, float* out, hipStream_t st);
 
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ---- per-kernel HIP-event timing (off by default; not thread safe) ---------------------------------
+bool g_prof_on = false;
+static const char* const k_names[K_NUM] = {
+    "k_zero", "k_hist1", "k_scan1", "k_pass2", "k_finish", "k_norms", "k_draw", "k_count", "k_tilescan", "k_write",
+    "k_bits_max", "k_bits_extract", "k_agg_bits", "k_tileoff", "k_agg_sparse"};
+struct ProfPair { int id; hipEvent_t e0, e1; };
+static std::vector<ProfPair> g_pending;
+static std::vector<ProfPair> g_free;
+static double g_total_ms[K_NUM];
+static int64_t g_launches[K_NUM];
+
+static void prof_drain() {
+    for (ProfPair& p : g_pending) {
+        float ms = 0.f;
+        if (hipEventSynchronize(p.e1) == hipSuccess && hipEventElapsedTime(&ms, p.e0, p.e1) == hipSuccess) {
+            g_total_ms[p.id] += ms;
+            g_launches[p.id] += 1;
+        }
+        g_free.push_back(p);
+    }
+    g_pending.clear();
+}
+
+void prof_begin(int id, hipStream_t st) {
+    if (g_pending.size() >= 8192) prof_drain();
+    ProfPair p;
+    if (!g_free.empty()) {
+        p = g_free.back();
+        g_free.pop_back();
+    } else {
+        if (hipEventCreate(&p.e0) != hipSuccess || hipEventCreate(&p.e1) != hipSuccess) return;
+    }
+    p.id = id;
+    (void)hipEventRecord(p.e0, st);
+    g_pending.push_back(p);
+}
+
+void prof_end(int id, hipStream_t st) {
+    if (g_pending.empty() || g_pending.back().id != id) return;
+    (void)hipEventRecord(g_pending.back().e1, st);
+}
 
 // rows can be read with aligned 16-byte (fp32) / 8-byte (bf16) loads
 static bool vec_ok(const mlmc_plan_t* pl, const void* g, int64_t ld) {
@@ -80,6 +123,28 @@ const char* mlmc_status_string(int status) {
         case MLMC_EHIP: return "MLMC_EHIP: HIP launch failed";
         default: return "unknown mlmc status";
     }
+}
+
+void mlmc_profile_enable(int on) {
+    if (!on) prof_drain();
+    g_prof_on = on != 0;
+}
+
+void mlmc_profile_reset(void) {
+    prof_drain();
+    for (int i = 0; i < K_NUM; ++i) { g_total_ms[i] = 0.0; g_launches[i] = 0; }
+}
+
+int mlmc_profile_num_kernels(void) { return K_NUM; }
+
+const char* mlmc_profile_kernel_name(int id) { return id >= 0 && id < K_NUM ? k_names[id] : ""; }
+
+mlmc_status mlmc_profile_get(int id, double* total_ms, int64_t* launches) {
+    if (id < 0 || id >= K_NUM || !total_ms || !launches) return MLMC_EINVAL;
+    prof_drain();
+    *total_ms = g_total_ms[id];
+    *launches = g_launches[id];
+    return MLMC_OK;
 }
 
 mlmc_status mlmc_geometric_p(int L, double* p) {

@@ -9,11 +9,6 @@
 
 namespace mlmc {
 
-#define MLMC_LAUNCH_CHECK()                                    \
-    do {                                                       \
-        if (hipGetLastError() != hipSuccess) return MLMC_EHIP; \
-    } while (0)
-
 // ---------------------------------------------------------------------------------------------------
 template <int DT, bool VEC>
 __global__ __launch_bounds__(512) void k_bits_max(BitsArgs a) {
@@ -212,22 +207,20 @@ __global__ __launch_bounds__(256) void k_agg_sparse(AggSparseArgs a) {
 mlmc_status bits_compress(const mlmc_plan_t* pl, const BitsArgs& a, bool vec, hipStream_t st) {
     dim3 grid(pl->chunks_per_row, pl->M);
     if (pl->dtype == MLMC_F32) {
-        if (vec) k_bits_max<MLMC_F32, true><<<grid, 512, 0, st>>>(a);
-        else k_bits_max<MLMC_F32, false><<<grid, 512, 0, st>>>(a);
+        if (vec) MLMC_LAUNCH(K_BITS_MAX, st, k_bits_max<MLMC_F32, true><<<grid, 512, 0, st>>>(a));
+        else MLMC_LAUNCH(K_BITS_MAX, st, k_bits_max<MLMC_F32, false><<<grid, 512, 0, st>>>(a));
     } else {
-        if (vec) k_bits_max<MLMC_BF16, true><<<grid, 512, 0, st>>>(a);
-        else k_bits_max<MLMC_BF16, false><<<grid, 512, 0, st>>>(a);
+        if (vec) MLMC_LAUNCH(K_BITS_MAX, st, k_bits_max<MLMC_BF16, true><<<grid, 512, 0, st>>>(a));
+        else MLMC_LAUNCH(K_BITS_MAX, st, k_bits_max<MLMC_BF16, false><<<grid, 512, 0, st>>>(a));
     }
-    MLMC_LAUNCH_CHECK();
     int64_t ntiles = pl->ntiles;
     int gx = (int)((ntiles + 3) / 4);
     int cap = 4096 / pl->M > 0 ? 4096 / pl->M : 1;
     if (gx > cap) gx = cap;
     if (gx < 1) gx = 1;
     dim3 egrid(gx, pl->M);
-    if (pl->dtype == MLMC_F32) k_bits_extract<MLMC_F32><<<egrid, 256, 0, st>>>(a);
-    else k_bits_extract<MLMC_BF16><<<egrid, 256, 0, st>>>(a);
-    MLMC_LAUNCH_CHECK();
+    if (pl->dtype == MLMC_F32) MLMC_LAUNCH(K_BITS_EXTRACT, st, k_bits_extract<MLMC_F32><<<egrid, 256, 0, st>>>(a));
+    else MLMC_LAUNCH(K_BITS_EXTRACT, st, k_bits_extract<MLMC_BF16><<<egrid, 256, 0, st>>>(a));
     return MLMC_OK;
 }
 
@@ -244,8 +237,7 @@ mlmc_status agg_bits(const mlmc_plan_t* pl, const BitsArgs& b, const int32_t* le
     int blocks = (int)((waves + 3) / 4);
     if (blocks > 8192) blocks = 8192;
     if (blocks < 1) blocks = 1;
-    k_agg_bits<<<blocks, 256, 0, st>>>(a);
-    MLMC_LAUNCH_CHECK();
+    MLMC_LAUNCH(K_AGG_BITS, st, k_agg_bits<<<blocks, 256, 0, st>>>(a));
     return MLMC_OK;
 }
 
@@ -266,12 +258,10 @@ mlmc_status agg_sparse(const mlmc_plan_t* pl, const int64_t* row_off, const uint
         int64_t n = (int64_t)pl->M * (pl->ntiles + 1);
         int blocks = (int)((n + 255) / 256);
         if (blocks > 4096) blocks = 4096;
-        k_tileoff<<<blocks, 256, 0, st>>>(a);
-        MLMC_LAUNCH_CHECK();
+        MLMC_LAUNCH(K_TILEOFF, st, k_tileoff<<<blocks, 256, 0, st>>>(a));
         a.tile_off = tile_off_ws;
     }
-    k_agg_sparse<<<(unsigned)pl->ntiles, 256, 0, st>>>(a);
-    MLMC_LAUNCH_CHECK();
+    MLMC_LAUNCH(K_AGG_SPARSE, st, k_agg_sparse<<<(unsigned)pl->ntiles, 256, 0, st>>>(a));
     return MLMC_OK;
 }
 

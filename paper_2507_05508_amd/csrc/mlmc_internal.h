@@ -108,6 +108,24 @@ struct BitsArgs {
     int32_t* dev_status;
 };
 
+// ---- optional per-kernel timing with HIP events (host side, see mlmc_profile_* in mlmc.h) ----------
+enum KernelId {
+    K_ZERO = 0, K_HIST1, K_SCAN1, K_PASS2, K_FINISH, K_NORMS, K_DRAW, K_COUNT, K_TILESCAN, K_WRITE,
+    K_BITS_MAX, K_BITS_EXTRACT, K_AGG_BITS, K_TILEOFF, K_AGG_SPARSE, K_NUM
+};
+extern bool g_prof_on;
+void prof_begin(int id, hipStream_t st);
+void prof_end(int id, hipStream_t st);
+
+// Launch statement wrapper: optional event pair around it, then the launch error check.
+#define MLMC_LAUNCH(id, st, ...)                                \
+    do {                                                        \
+        if (::mlmc::g_prof_on) ::mlmc::prof_begin(id, st);      \
+        __VA_ARGS__;                                            \
+        if (::mlmc::g_prof_on) ::mlmc::prof_end(id, st);        \
+        if (hipGetLastError() != hipSuccess) return MLMC_EHIP;  \
+    } while (0)
+
 }  // namespace mlmc
 
 struct mlmc_plan_s {

@@ -794,41 +794,26 @@ __global__ __launch_bounds__(256) void k_write(TopkArgs a) {
 
 // ---------------------------------------------------------------------------------------------------
 // host-side launchers
-#define MLMC_LAUNCH_CHECK()                                  \
-    do {                                                     \
-        if (hipGetLastError() != hipSuccess) return MLMC_EHIP; \
-    } while (0)
-
 template <int DT, bool VEC>
-static mlmc_status launch_stream_kernels_select(const mlmc_plan_t* pl, const TopkArgs& a, bool sums, hipStream_t st) {
+static mlmc_status launch_select(const mlmc_plan_t* pl, const TopkArgs& a, bool sums, hipStream_t st) {
     dim3 grid(pl->chunks_per_row, pl->M);
-    k_hist1<DT, VEC><<<grid, 512, 0, st>>>(a);
-    MLMC_LAUNCH_CHECK();
-    k_scan1<<<pl->M, 1024, 0, st>>>(a);
-    MLMC_LAUNCH_CHECK();
-    if (sums) k_pass2<DT, VEC, true><<<grid, P2_THREADS, 0, st>>>(a);
-    else k_pass2<DT, VEC, false><<<grid, P2_THREADS, 0, st>>>(a);
-    MLMC_LAUNCH_CHECK();
+    MLMC_LAUNCH(K_HIST1, st, k_hist1<DT, VEC><<<grid, 512, 0, st>>>(a));
+    MLMC_LAUNCH(K_SCAN1, st, k_scan1<<<pl->M, 1024, 0, st>>>(a));
+    if (sums) MLMC_LAUNCH(K_PASS2, st, k_pass2<DT, VEC, true><<<grid, P2_THREADS, 0, st>>>(a));
+    else MLMC_LAUNCH(K_PASS2, st, k_pass2<DT, VEC, false><<<grid, P2_THREADS, 0, st>>>(a));
     dim3 fgrid(pl->L + 1, pl->M);
-    if (sums) k_finish<true><<<fgrid, 256, 0, st>>>(a);
-    else k_finish<false><<<fgrid, 256, 0, st>>>(a);
-    MLMC_LAUNCH_CHECK();
-    if (sums) {
-        k_norms<<<pl->M, 64, 0, st>>>(a);
-        MLMC_LAUNCH_CHECK();
-    }
+    if (sums) MLMC_LAUNCH(K_FINISH, st, k_finish<true><<<fgrid, 256, 0, st>>>(a));
+    else MLMC_LAUNCH(K_FINISH, st, k_finish<false><<<fgrid, 256, 0, st>>>(a));
+    if (sums) MLMC_LAUNCH(K_NORMS, st, k_norms<<<pl->M, 64, 0, st>>>(a));
     return MLMC_OK;
 }
 
 template <int DT, bool VEC>
 static mlmc_status launch_compact(const mlmc_plan_t* pl, const TopkArgs& a, hipStream_t st) {
     dim3 grid(pl->chunks_per_row, pl->M);
-    k_count<DT, VEC><<<grid, 256, 0, st>>>(a);
-    MLMC_LAUNCH_CHECK();
-    k_tilescan<<<pl->M, 1024, 0, st>>>(a);
-    MLMC_LAUNCH_CHECK();
-    k_write<DT, VEC><<<grid, 256, 0, st>>>(a);
-    MLMC_LAUNCH_CHECK();
+    MLMC_LAUNCH(K_COUNT, st, k_count<DT, VEC><<<grid, 256, 0, st>>>(a));
+    MLMC_LAUNCH(K_TILESCAN, st, k_tilescan<<<pl->M, 1024, 0, st>>>(a));
+    MLMC_LAUNCH(K_WRITE, st, k_write<DT, VEC><<<grid, 256, 0, st>>>(a));
     return MLMC_OK;
 }
 
@@ -837,23 +822,19 @@ mlmc_status topk_zero(const mlmc_plan_t* pl, void* ws, int32_t* dev_status, hipS
     int blocks = (int)((n16 + 255) / 256);
     if (blocks > 2048) blocks = 2048;
     if (blocks < 1) blocks = 1;
-    k_zero<<<blocks, 256, 0, st>>>((uint4*)ws, n16, dev_status);
-    MLMC_LAUNCH_CHECK();
+    MLMC_LAUNCH(K_ZERO, st, k_zero<<<blocks, 256, 0, st>>>((uint4*)ws, n16, dev_status));
     return MLMC_OK;
 }
 
 mlmc_status topk_draw(const DrawArgs& da, hipStream_t st) {
-    k_draw<<<1, 1024, 0, st>>>(da);
-    MLMC_LAUNCH_CHECK();
+    MLMC_LAUNCH(K_DRAW, st, k_draw<<<1, 1024, 0, st>>>(da));
     return MLMC_OK;
 }
 
 mlmc_status topk_select(const mlmc_plan_t* pl, const TopkArgs& a, bool sums, bool vec, hipStream_t st) {
     if (pl->dtype == MLMC_F32)
-        return vec ? launch_stream_kernels_select<MLMC_F32, true>(pl, a, sums, st)
-                   : launch_stream_kernels_select<MLMC_F32, false>(pl, a, sums, st);
-    return vec ? launch_stream_kernels_select<MLMC_BF16, true>(pl, a, sums, st)
-               : launch_stream_kernels_select<MLMC_BF16, false>(pl, a, sums, st);
+        return vec ? launch_select<MLMC_F32, true>(pl, a, sums, st) : launch_select<MLMC_F32, false>(pl, a, sums, st);
+    return vec ? launch_select<MLMC_BF16, true>(pl, a, sums, st) : launch_select<MLMC_BF16, false>(pl, a, sums, st);
 }
 
 mlmc_status topk_compact(const mlmc_plan_t* pl, const TopkArgs& a, bool vec, hipStream_t st) {
