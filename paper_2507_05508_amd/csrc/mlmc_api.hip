@@ -24,7 +24,7 @@ static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // ---- per-kernel HIP-event timing (off by default; not thread safe) ---------------------------------
 bool g_prof_on = false;
 static const char* const k_names[K_NUM] = {
-    "k_zero", "k_hist1", "k_scan1", "k_pass2", "k_finish", "k_norms", "k_draw", "k_count", "k_tilescan", "k_write",
+    "k_zero", "k_hist1", "k_scan1", "k_pass2", "k_finish", "k_norms", "k_draw", "k_compact",
     "k_bits_max", "k_bits_extract", "k_agg_bits", "k_tileoff", "k_agg_sparse"};
 struct ProfPair { int id; hipEvent_t e0, e1; };
 static std::vector<ProfPair> g_pending;
@@ -84,8 +84,10 @@ static void fill_topk_args(const mlmc_plan_t* pl, TopkArgs& a, const void* g, in
     a.hist1 = (uint32_t*)(w + pl->off_hist1);
     a.rinfo = (RowInfo*)(w + pl->off_rinfo);
     a.table = (uint16_t*)(w + pl->off_table);
-    a.tilecnt = (uint32_t*)(w + pl->off_tilecnt);
-    a.tiepre = (uint32_t*)(w + pl->off_tiepre);
+    a.desc = (unsigned long long*)(w + pl->off_desc);
+    a.ticket = (uint32_t*)(w + pl->off_ticket);
+    a.units_per_row = pl->units_per_row;
+    a.cwaves = pl->cwaves;
     a.tile_off = (uint32_t*)(w + pl->off_tileoff);
     a.norms = (double*)(w + pl->off_norms);
     a.cand = (uint32_t*)(w + pl->off_cand);
@@ -212,16 +214,19 @@ mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dty
     off = align_up(off + sizeof(RowAcc) * (size_t)M, 256);
     pl->off_hist1 = off;
     if (kind == MLMC_TOPK) off = align_up(off + sizeof(uint32_t) * NB1 * (size_t)M, 256);
+    // compaction units: larger workgroups when few rows share the look-back chains
+    pl->cwaves = M >= 8 ? 8 : 16;
+    pl->units_per_row = (d + (int64_t)pl->cwaves * 1024 - 1) / ((int64_t)pl->cwaves * 1024);
+    pl->off_desc = off;
+    if (kind == MLMC_TOPK) off = align_up(off + sizeof(unsigned long long) * 4 * (size_t)pl->units_per_row * M, 256);
+    pl->off_ticket = off;
+    off = align_up(off + 256, 256);
     pl->zero_bytes = off;
     pl->off_rinfo = off;
     off = align_up(off + sizeof(RowInfo) * (size_t)M, 256);
     if (kind == MLMC_TOPK) {
         pl->off_table = off;
         off = align_up(off + sizeof(uint16_t) * NB1 * (size_t)M, 256);
-        pl->off_tilecnt = off;
-        off = align_up(off + sizeof(uint32_t) * 6 * (size_t)pl->ntiles * M, 256);
-        pl->off_tiepre = off;
-        off = align_up(off + sizeof(uint32_t) * 3 * (size_t)pl->ntiles * M, 256);
         pl->off_tileoff = off;
         off = align_up(off + sizeof(uint32_t) * (size_t)(pl->ntiles + 1) * M, 256);
         pl->off_norms = off;
@@ -258,6 +263,7 @@ mlmc_status mlmc_level_norms(const mlmc_plan_t* plan, const void* g, int64_t ld,
     TopkArgs a;
     fill_topk_args(plan, a, g, ld, ws, dev_status);
     a.all_thresholds = 1;
+    a.draw_mode = -1;  // norms only, no draw
     a.norms_user = norms;
     mlmc_status rc = topk_zero(plan, ws, dev_status, st);
     if (rc != MLMC_OK) return rc;
@@ -284,42 +290,23 @@ mlmc_status mlmc_compress_topk(const mlmc_plan_t* plan, const void* g, int64_t l
     a.norms_user = internal_norms ? norms_out : nullptr;
     a.all_thresholds = internal_norms ? 1 : 0;
 
-    DrawArgs da;
-    std::memset(&da, 0, sizeof(da));
-    da.M = plan->M;
-    da.L = plan->L;
-    for (int t = 0; t <= plan->L; ++t) da.k[t] = plan->ladder[t];
-    da.is_topk = 1;
-    da.seed = seed;
-    da.step = step;
-    da.rinfo = a.rinfo;
-    da.level = level;
-    da.row_off = row_off;
-    da.capacity = capacity;
-    da.dev_status = dev_status;
+    a.seed = seed;
+    a.step = step;
     if (p) {
-        da.mode = p_is_norms ? 2 : 1;
-        da.p_dev = p;
+        a.draw_mode = p_is_norms ? 2 : 1;
+        a.p_dev = p;
     } else if (!plan->adaptive) {
-        da.mode = 0;
-        for (int l = 0; l < plan->L; ++l) da.p_fixed[l] = plan->p[l];
+        a.draw_mode = 0;
+        for (int l = 0; l < plan->L; ++l) a.p_fixed[l] = plan->p[l];
     } else {
-        da.mode = 2;
-        da.p_dev = a.norms;
+        a.draw_mode = 3;
     }
-
     mlmc_status rc = topk_zero(plan, ws, dev_status, st);
     if (rc != MLMC_OK) return rc;
-    if (!internal_norms) {  // the level is known before the data is touched: only three thresholds are needed
-        rc = topk_draw(da, st);
-        if (rc != MLMC_OK) return rc;
-    }
+    // draw_mode < 3: the level is drawn before the data is touched (inside the threshold scan), so only
+    // three thresholds are resolved; draw_mode 3: all thresholds and band sums first, then the draw
     rc = topk_select(plan, a, internal_norms, vec, st);
     if (rc != MLMC_OK) return rc;
-    if (internal_norms) {
-        rc = topk_draw(da, st);
-        if (rc != MLMC_OK) return rc;
-    }
     return topk_compact(plan, a, vec, st);
 }
 

@@ -63,12 +63,19 @@ struct TopkArgs {
     RowInfo* rinfo;          // [M]
     RowAcc* racc;            // [M]
     uint32_t* cand;          // [M][d]
-    uint32_t* tilecnt;       // [M][6][ntiles]
-    uint32_t* tiepre;        // [M][3][ntiles]
+    unsigned long long* desc; // [M][units_per_row][4] look-back descriptors of the compaction (zeroed per call)
+    uint32_t* ticket;        // [1] work counter of the compaction (zeroed per call)
+    int64_t units_per_row;   // compaction units (cwaves * 1024 elements) per row
+    int32_t cwaves;          // waves per compaction workgroup
     uint32_t* tile_off;      // [M][ntiles + 1]
     double* norms;           // [M][L]
     double* norms_user;      // optional copy
     int32_t* dev_status;
+    // level draw (Alg. 2 / Alg. 3 "Sample l"): mode 0 p_fixed, 1 dev p, 2 dev norms, 3 norms computed by this call
+    int32_t draw_mode;
+    double p_fixed[LMAX];
+    const double* p_dev;     // [M][L]
+    uint64_t seed, step;
     // outputs of the compaction
     int32_t* level;
     int64_t* row_off;
@@ -110,7 +117,7 @@ struct BitsArgs {
 
 // ---- optional per-kernel timing with HIP events (host side, see mlmc_profile_* in mlmc.h) ----------
 enum KernelId {
-    K_ZERO = 0, K_HIST1, K_SCAN1, K_PASS2, K_FINISH, K_NORMS, K_DRAW, K_COUNT, K_TILESCAN, K_WRITE,
+    K_ZERO = 0, K_HIST1, K_SCAN1, K_PASS2, K_FINISH, K_NORMS, K_DRAW, K_COMPACT,
     K_BITS_MAX, K_BITS_EXTRACT, K_AGG_BITS, K_TILEOFF, K_AGG_SPARSE, K_NUM
 };
 extern bool g_prof_on;
@@ -140,6 +147,9 @@ struct mlmc_plan_s {
     int chunks_per_row;
     // workspace byte offsets
     size_t off_racc, off_hist1, zero_bytes;  // [0, zero_bytes) is cleared per call
-    size_t off_rinfo, off_table, off_tilecnt, off_tiepre, off_tileoff, off_norms, off_cand;
+    size_t off_desc, off_ticket;
+    int64_t units_per_row;
+    int cwaves;
+    size_t off_rinfo, off_table, off_tileoff, off_norms, off_cand;
     size_t ws_bytes;
 };

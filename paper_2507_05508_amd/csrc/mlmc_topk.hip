@@ -8,9 +8,10 @@
 //              boundary buckets are appended to per-slot candidate lists
 //   k_finish   per boundary bucket: remaining 17 key bits from the candidate list -> exact threshold key,
 //              tie quota, and the exact split of the bucket's sum between the bands it straddles
-//   k_norms    big-integer accumulation of the group sums -> correctly rounded fp64 S_l -> Delta_l (Lemma 3.4)
-//   k_draw     p_l, integer CDF, Philox draw, weight, row offsets (Alg. 2 / Alg. 3 "Sample l")
-//   k_count / k_tilescan / k_write   index-ordered compaction of base band + drawn band (Eq. (6))
+//   k_norms    big-integer accumulation of the group sums -> correctly rounded fp64 S_l -> Delta_l (Lemma 3.4),
+//              then the adaptive level draw (Alg. 3); with known p the draw happens at the start of k_scan1
+//   k_compact  index-ordered compaction of base band + drawn band (Eq. (6)) in one read of the rows:
+//              per-unit counts chained across workgroups by decoupled look-back
 #include "mlmc_device.h"
 
 namespace mlmc {
@@ -59,56 +60,97 @@ __global__ __launch_bounds__(512) void k_hist1(TopkArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------------
+// Level draw of one row (Alg. 2 / Alg. 3 "Sample l ~ p"), run by one thread.
+__device__ void draw_row(const TopkArgs& a, int row, const double* norms_row) {
+    double p[LMAX];
+    const int L = a.L;
+    if (a.draw_mode == 0) {
+        for (int l = 0; l < L; ++l) p[l] = a.p_fixed[l];
+    } else if (a.draw_mode == 1) {
+        for (int l = 0; l < L; ++l) p[l] = a.p_dev[(size_t)row * L + l];
+    } else {
+        const double* n = a.draw_mode == 2 ? a.p_dev + (size_t)row * L : norms_row;
+        double tot = 0.0;
+        for (int l = 0; l < L; ++l) tot = __dadd_rn(tot, n[l]);
+        for (int l = 0; l < L; ++l) p[l] = tot == 0.0 ? __ddiv_rn(1.0, (double)L) : __ddiv_rn(n[l], tot);
+    }
+    uint32_t x = philox_word0(a.seed, a.step, (uint32_t)row);
+    int level = draw_from_p(p, L, x);
+    double pl = p[level - 1];
+    RowInfo* ri = a.rinfo + row;
+    ri->level = level;
+    ri->weight = pl == 0.0 ? 0.0f : (float)__ddiv_rn(1.0, pl);
+    ri->draw_x = x;
+    a.level[row] = level;
+}
+
+// ---------------------------------------------------------------------------------------------------
 // Per row: locate thresholds at bucket resolution, assign candidate slots and sum groups, write the table.
 __global__ __launch_bounds__(1024) void k_scan1(TopkArgs a) {
     __shared__ uint32_t s_h[NB1];
     __shared__ uint32_t s_scan[17];
-    __shared__ uint32_t s_bmask[NB1 / 32];
+    __shared__ uint32_t s_bmask[NB1 / 32];   // bit per bucket: holds a threshold (boundary bucket)
+    __shared__ uint32_t s_pmask[NB1 / 32];   // bit per bucket: populated
     __shared__ int32_t s_active[TMAX];
-    __shared__ uint32_t s_tb[TMAX];      // bucket of threshold t; 0xFFFFFFFF none, 0xFFFFFFFE all
+    __shared__ int64_t s_k[TMAX];
+    __shared__ uint32_t s_tb[TMAX];          // bucket of threshold t; 0xFFFFFFFF none, 0xFFFFFFFE all
     __shared__ uint32_t s_tr[TMAX];
     __shared__ int32_t s_ng[256];
     __shared__ int32_t s_gbase[256];
-    __shared__ int32_t s_nslots;
+    __shared__ int32_t s_nslots, s_lev;
     __shared__ uint32_t s_slotb[SMAX];
 
     const int row = blockIdx.x, tid = threadIdx.x;
     RowInfo* ri = a.rinfo + row;
     const uint32_t* gh = a.hist1 + (size_t)row * NB1;
     const int L = a.L;
-    const int lev = ri->level;  // valid when !all_thresholds (draw ran first)
 
+    if (tid == 0) {
+        if (!a.all_thresholds) draw_row(a, row, nullptr);  // p is known up front: draw before anything else
+        s_lev = a.all_thresholds ? 0 : ri->level;
+    }
     for (int b = tid; b < NB1; b += 1024) s_h[b] = gh[b];
-    for (int w = tid; w < NB1 / 32; w += 1024) s_bmask[w] = 0;
+    for (int w = tid; w < NB1 / 32; w += 1024) { s_bmask[w] = 0; s_pmask[w] = 0; }
+    __syncthreads();
+    const int lev = s_lev;
     if (tid <= L) {
         bool act = a.all_thresholds || tid == 0 || tid == lev - 1 || tid == lev;
         s_active[tid] = act;
         int64_t kt = a.k[tid];
+        s_k[tid] = kt;
         s_tb[tid] = kt <= 0 ? 0xFFFFFFFFu : 0xFFFFFFFEu;  // overwritten below when 0 < k_t < d
         s_tr[tid] = 0;
     }
-    __syncthreads();
 
     // descending buckets: rb = tid*16 + i  <->  b = NB1 - 1 - rb
-    uint32_t sum = 0;
+    uint32_t hv[16];
+    uint32_t sum = 0, pbits = 0;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) sum += s_h[NB1 - 1 - (tid * 16 + i)];
+    for (int i = 0; i < 16; ++i) {
+        hv[i] = s_h[NB1 - 1 - (tid * 16 + i)];
+        sum += hv[i];
+        pbits |= (hv[i] ? 1u : 0u) << (15 - i);   // bit position = bucket offset inside the aligned 16-block
+    }
+    if (pbits) {
+        const int b0 = NB1 - 16 - tid * 16;        // lowest bucket of this thread's block (multiple of 16)
+        atomicOr(&s_pmask[b0 >> 5], pbits << (b0 & 31));
+    }
     uint32_t total;
-    uint32_t running = block_excl_scan<1024>(sum, s_scan, total);
+    const uint32_t before = block_excl_scan<1024>(sum, s_scan, total);   // also orders the LDS writes above
     if (tid == 0 && (int64_t)total != a.d) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
     if (sum) {
-        for (int i = 0; i < 16; ++i) {
-            int b = NB1 - 1 - (tid * 16 + i);
-            uint32_t hv = s_h[b];
-            if (hv) {
-                for (int t = 0; t <= L; ++t) {
-                    int64_t kt = a.k[t];
-                    if (s_active[t] && kt > 0 && kt < a.d && (int64_t)running < kt && kt <= (int64_t)running + hv) {
-                        s_tb[t] = (uint32_t)b;
-                        s_tr[t] = (uint32_t)(kt - running);
-                    }
+        for (int t = 0; t <= L; ++t) {
+            const int64_t kt = s_k[t];
+            if (!s_active[t] || kt <= 0 || kt >= a.d) continue;
+            if (kt <= (int64_t)before || kt > (int64_t)before + sum) continue;   // not in this thread's 16 buckets
+            uint32_t run = before;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                if ((int64_t)run < kt && kt <= (int64_t)run + hv[i]) {
+                    s_tb[t] = (uint32_t)(NB1 - 1 - (tid * 16 + i));
+                    s_tr[t] = (uint32_t)(kt - run);
                 }
-                running += hv;
+                run += hv[i];
             }
         }
     }
@@ -150,63 +192,109 @@ __global__ __launch_bounds__(1024) void k_scan1(TopkArgs a) {
     }
     __syncthreads();
 
-    // band of a bucket that is wholly inside one band: number of thresholds whose bucket lies above it
-    auto band_of = [&](int b) -> int {
-        int n = 0;
+    // One thread per exponent (64 buckets, bit i of the masks <-> bucket 64 E + i).  Boundary buckets cut the
+    // exponent into segments; a populated segment lies wholly inside one band and is one sum group:
+    // band = number of thresholds whose bucket lies above the segment ("none" thresholds always do).
+    const int E = tid;
+    uint64_t pm = 0, bm = 0;
+    int band_top = 0;
+    if (tid < 256) {
+        pm = (uint64_t)s_pmask[2 * E] | ((uint64_t)s_pmask[2 * E + 1] << 32);
+        bm = (uint64_t)s_bmask[2 * E] | ((uint64_t)s_bmask[2 * E + 1] << 32);
         for (int t = 0; t <= L; ++t) {
             uint32_t tb = s_tb[t];
-            bool above = tb == 0xFFFFFFFFu ? true : (tb == 0xFFFFFFFEu ? false : (int)tb > b);
-            n += above ? 1 : 0;
+            band_top += (tb == 0xFFFFFFFFu || (tb != 0xFFFFFFFEu && (int)tb > E * 64 + 63)) ? 1 : 0;
         }
-        return n;  // L + 1 = below the last threshold (k_L < d): in no band
+    }
+    auto thresholds_in = [&](int b) -> int {
+        int n = 0;
+        for (int t = 0; t <= L; ++t) n += s_tb[t] == (uint32_t)b ? 1 : 0;
+        return n;
     };
-
+    // walks the segments from the top; calls f(segment mask, band, boundary bit below it or -1)
+    auto walk = [&](auto&& f) {
+        uint64_t rem = bm;
+        int hi = 63, band = band_top;
+        while (hi >= 0) {
+            const int bpos = rem ? 63 - __builtin_clzll(rem) : -1;
+            const uint64_t upto_hi = hi == 63 ? ~0ull : ((1ull << (hi + 1)) - 1ull);
+            const uint64_t below = bpos < 0 ? 0ull : ((bpos == 63) ? ~0ull : ((1ull << (bpos + 1)) - 1ull));
+            f(upto_hi & ~below, band, bpos);
+            if (bpos < 0) break;
+            band += thresholds_in(E * 64 + bpos);
+            rem &= ~(1ull << bpos);
+            hi = bpos - 1;
+        }
+    };
     if (a.all_thresholds) {
         if (tid < 256) {
-            int ng = 0, prev = -1;
-            for (int i = 63; i >= 0; --i) {
-                int b = tid * 64 + i;
-                if (s_h[b] && !((s_bmask[b >> 5] >> (b & 31)) & 1u)) {
-                    int band = band_of(b);
-                    if (band != prev) { ++ng; prev = band; }
-                }
-            }
+            int ng = 0;
+            walk([&](uint64_t seg, int, int) { ng += (pm & ~bm & seg) ? 1 : 0; });
             s_ng[tid] = ng;
         }
         __syncthreads();
-        if (tid == 0) {
-            int run = 0;
-            for (int e = 255; e >= 0; --e) { s_gbase[e] = run; run += s_ng[e]; }
-            ri->n_groups = run;
-            int rs = run <= 32 ? 6 : run <= 64 ? 5 : run <= 128 ? 4 : run <= 256 ? 3 : 2;
-            ri->rep_shift = rs;
+        if (tid < 64) {  // exclusive scan over exponents, highest first: lane l owns exponents 255-4l .. 252-4l
+            int v[4], sum4 = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { v[i] = s_ng[255 - (tid * 4 + i)]; sum4 += v[i]; }
+            int inc = sum4;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                int u = __shfl_up(inc, o, 64);
+                if (tid >= o) inc += u;
+            }
+            int run = inc - sum4;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { s_gbase[255 - (tid * 4 + i)] = run; run += v[i]; }
+            if (tid == 63) {
+                ri->n_groups = run;
+                ri->rep_shift = run <= 32 ? 6 : run <= 64 ? 5 : run <= 128 ? 4 : run <= 256 ? 3 : 2;
+            }
         }
         __syncthreads();
     }
     if (tid < 256) {
-        uint16_t* tab = a.table + (size_t)row * NB1;
-        int gid = a.all_thresholds ? s_gbase[tid] - 1 : 0, prev = -1;
-        const int ns = s_nslots;
-        for (int i = 63; i >= 0; --i) {
-            int b = tid * 64 + i;
+        uint16_t* tab = a.table + (size_t)row * NB1 + E * 64;
+        if (bm == 0) {  // whole exponent in one band (or unpopulated / not needed)
             uint16_t code = CODE_IGNORE;
-            if ((s_bmask[b >> 5] >> (b & 31)) & 1u) {
-                int s = 0;
-                for (int u = 0; u < ns; ++u) if (s_slotb[u] == (uint32_t)b) s = u;
-                code = (uint16_t)(CODE_CAND | s);
-            } else if (a.all_thresholds && s_h[b]) {
-                int band = band_of(b);
-                if (band != prev) {
-                    ++gid;
-                    prev = band;
-                    if (gid < GMAX) {
-                        ri->g_exp[gid] = (uint16_t)(tid ? tid : 1);
-                        ri->g_band[gid] = (uint16_t)band;
-                    }
+            if (a.all_thresholds && pm) {
+                int gid = s_gbase[E];
+                if (gid < GMAX) {
+                    ri->g_exp[gid] = (uint16_t)(E ? E : 1);
+                    ri->g_band[gid] = (uint16_t)band_top;
+                    code = (uint16_t)gid;
                 }
-                code = gid < GMAX ? (uint16_t)gid : CODE_IGNORE;
             }
-            tab[b] = code;
+            uint32_t c2 = (uint32_t)code | ((uint32_t)code << 16);
+            uint4 v = make_uint4(c2, c2, c2, c2);
+            uint4* dst = (uint4*)tab;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) dst[i] = v;
+        } else {
+            int gid = a.all_thresholds ? s_gbase[E] : 0;
+            const int ns = s_nslots;
+            walk([&](uint64_t seg, int band, int bpos) {
+                uint16_t gcode = CODE_IGNORE;
+                if (a.all_thresholds && (pm & ~bm & seg)) {
+                    if (gid < GMAX) {
+                        ri->g_exp[gid] = (uint16_t)(E ? E : 1);
+                        ri->g_band[gid] = (uint16_t)band;
+                        gcode = (uint16_t)gid;
+                    }
+                    ++gid;
+                }
+                uint64_t sm = seg;
+                while (sm) {
+                    const int i = __builtin_ctzll(sm);
+                    sm &= sm - 1;
+                    tab[i] = ((pm >> i) & 1ull) ? gcode : CODE_IGNORE;
+                }
+                if (bpos >= 0) {
+                    int sl = 0;
+                    for (int u = 0; u < ns; ++u) if (s_slotb[u] == (uint32_t)(E * 64 + bpos)) sl = u;
+                    tab[bpos] = (uint16_t)(CODE_CAND | sl);
+                }
+            });
         }
     }
 }
@@ -316,8 +404,43 @@ __global__ __launch_bounds__(P2_THREADS) void k_pass2(TopkArgs a) {
 
 // ---------------------------------------------------------------------------------------------------
 // One workgroup per (boundary bucket, row): resolve the remaining 17 key bits on the candidate list.
+constexpr int FN_THREADS = 1024;
+
+// Descending search in a histogram held by one wave: lane l owns bins [BPL*l, BPL*l + BPL).  For the 1-based
+// rank r (counted from the top bin) returns the bin that contains it, the rank inside that bin, and the bin count.
+template <int BPL>
+__device__ __forceinline__ void wave_rank_search(const uint32_t* h, uint32_t r, int& bin, uint32_t& rin, uint32_t& cnt) {
+    const uint32_t lane = lane_id();
+    uint32_t v[BPL];
+    uint32_t sum = 0;
+#pragma unroll
+    for (int i = 0; i < BPL; ++i) { v[i] = h[BPL * lane + i]; sum += v[i]; }
+    // suffix sums: elements in bins above this lane's bins = total - inclusive prefix
+    uint32_t inc = sum;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        uint32_t u = __shfl_up(inc, o, 64);
+        if (lane >= (uint32_t)o) inc += u;
+    }
+    const uint32_t total = __shfl(inc, 63, 64);
+    uint32_t above = total - inc;  // count in bins of higher lanes
+    int fb = -1;
+    uint32_t fr = 0, fc = 0;
+#pragma unroll
+    for (int i = BPL - 1; i >= 0; --i) {
+        if (fb < 0 && above < r && r <= above + v[i]) { fb = BPL * (int)lane + i; fr = r - above; fc = v[i]; }
+        above += v[i];
+    }
+    uint64_t m = __ballot(fb >= 0);
+    int src = m ? (int)__builtin_ctzll(m) : 0;
+    bin = __shfl(fb, src, 64);
+    rin = __shfl(fr, src, 64);
+    cnt = __shfl(fc, src, 64);
+    if (!m) { bin = 0; rin = r; cnt = 0; }
+}
+
 template <bool SUMS>
-__global__ __launch_bounds__(256) void k_finish(TopkArgs a) {
+__global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a) {
     __shared__ uint32_t hA[512];
     __shared__ uint32_t hB[TMAX][256];
     __shared__ unsigned long long pacc[SUMS ? TMAX + 1 : 1][64][2];
@@ -328,6 +451,7 @@ __global__ __launch_bounds__(256) void k_finish(TopkArgs a) {
     __shared__ uint8_t s_sub_of_sb[512];
 
     const int s = blockIdx.x, row = blockIdx.y, tid = threadIdx.x;
+    const uint32_t lane = lane_id(), wave = tid >> 6;
     RowInfo* ri = a.rinfo + row;
     RowAcc* ra = a.racc + row;
     if (s >= ri->n_slots) return;
@@ -336,7 +460,9 @@ __global__ __launch_bounds__(256) void k_finish(TopkArgs a) {
     const uint32_t* list = a.cand + (size_t)row * (size_t)a.d + ri->slot_off[s];
     const int L = a.L;
 
-    for (int i = tid; i < 512; i += 256) { hA[i] = 0; s_sub_of_sb[i] = 0xFF; }
+    for (int i = tid; i < 512; i += FN_THREADS) { hA[i] = 0; s_sub_of_sb[i] = 0xFF; }
+    for (int i = tid; i < TMAX * 256; i += FN_THREADS) (&hB[0][0])[i] = 0;
+    if (SUMS) for (int i = tid; i < (TMAX + 1) * 64 * 2; i += FN_THREADS) (&pacc[0][0][0])[i] = 0ull;
     if (tid == 0) {
         int m = 0;
         for (int t = 0; t <= L; ++t)
@@ -348,62 +474,56 @@ __global__ __launch_bounds__(256) void k_finish(TopkArgs a) {
     const int nthr = s_n;
 
     // A: bits 16..8
-    for (uint32_t i = tid; i < n; i += 256) atomicAdd(&hA[(list[i] >> 8) & 511u], 1u);
+#pragma unroll 4
+    for (uint32_t i = tid; i < n; i += FN_THREADS) atomicAdd(&hA[(list[i] >> 8) & 511u], 1u);
     __syncthreads();
-    if (tid < nthr) {
-        uint32_t r = s_res[tid], cum = 0;
-        int sb = 511;
-        for (; sb > 0; --sb) {
-            uint32_t hv = hA[sb];
-            if (cum + hv >= r) break;
-            cum += hv;
-        }
-        s_sb[tid] = (uint32_t)sb;
-        s_res[tid] = r - cum;
-    }
-    __syncthreads();
-    if (tid == 0) {
-        int nsub = 0;
+    if (wave == 0) {
         for (int u = 0; u < nthr; ++u) {
-            if (u == 0 || s_sb[u] != s_sb[u - 1]) { s_sub_of_sb[s_sb[u]] = (uint8_t)nsub; ++nsub; }
-            s_sub[u] = nsub - 1;
+            int sb;
+            uint32_t rin, cnt;
+            wave_rank_search<8>(hA, s_res[u], sb, rin, cnt);
+            if (lane == 0) { s_sb[u] = (uint32_t)sb; s_res[u] = rin; }
+        }
+        wave_lds_sync();
+        if (lane == 0) {
+            int nsub = 0;
+            for (int u = 0; u < nthr; ++u) {
+                if (u == 0 || s_sb[u] != s_sb[u - 1]) { s_sub_of_sb[s_sb[u]] = (uint8_t)nsub; ++nsub; }
+                s_sub[u] = nsub - 1;
+            }
         }
     }
-    for (int i = tid; i < TMAX * 256; i += 256) (&hB[0][0])[i] = 0;
     __syncthreads();
 
     // B: bits 7..0 of the keys in the thresholds' sub-bins
-    for (uint32_t i = tid; i < n; i += 256) {
+#pragma unroll 4
+    for (uint32_t i = tid; i < n; i += FN_THREADS) {
         uint32_t key = list[i];
         uint32_t u = s_sub_of_sb[(key >> 8) & 511u];
         if (u != 0xFF) atomicAdd(&hB[u][key & 255u], 1u);
     }
     __syncthreads();
-    if (tid < nthr) {
-        const uint32_t* hb = hB[s_sub[tid]];
-        uint32_t r = s_res[tid], cum = 0;
-        int lb = 255;
-        for (; lb > 0; --lb) {
-            uint32_t hv = hb[lb];
-            if (cum + hv >= r) break;
-            cum += hv;
+    for (int u = wave; u < nthr; u += FN_THREADS / 64) {
+        int lb;
+        uint32_t rin, cnt;
+        wave_rank_search<4>(hB[s_sub[u]], s_res[u], lb, rin, cnt);
+        if (lane == 0) {
+            uint32_t tau = (bucket << B1_SHIFT) | (s_sb[u] << 8) | (uint32_t)lb;
+            s_tau[u] = tau;
+            s_q[u] = rin;
+            s_eq[u] = cnt;
+            ri->thr_tau[s_t[u]] = tau;
+            ri->thr_q[s_t[u]] = rin;
+            if (rin > cnt || rin == 0) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
         }
-        uint32_t tau = (bucket << B1_SHIFT) | (s_sb[tid] << 8) | (uint32_t)lb;
-        s_tau[tid] = tau;
-        s_q[tid] = r - cum;
-        s_eq[tid] = hb[lb];
-        ri->thr_tau[s_t[tid]] = tau;
-        ri->thr_q[s_t[tid]] = r - cum;
-        if (r - cum > hb[lb] || r - cum == 0) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
     }
     if (!SUMS) return;
+    __syncthreads();
 
     // C: exact sums of the parts the thresholds cut the bucket into (piece j: keys strictly between
     // threshold j-1 and threshold j; entries equal to a threshold key are added arithmetically)
-    for (int i = tid; i < (TMAX + 1) * 64 * 2; i += 256) (&pacc[0][0][0])[i] = 0ull;
-    __syncthreads();
-    const uint32_t lane = lane_id();
-    for (uint32_t i = tid; i < n; i += 256) {
+#pragma unroll 4
+    for (uint32_t i = tid; i < n; i += FN_THREADS) {
         uint32_t key = list[i];
         int j = 0;
         bool eq = false;
@@ -451,9 +571,10 @@ __global__ __launch_bounds__(256) void k_finish(TopkArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Delta_l (Lemma 3.4) from the exact group and piece sums.  One thread per (row, band).
+// Delta_l (Lemma 3.4) from the exact group and piece sums, then the adaptive draw.  One workgroup per row,
+// one thread per band; the 640-bit accumulators live in LDS.
 struct BigAcc {
-    uint32_t w[20];
+    uint32_t* w;  // 20 words
     __device__ void clear() { for (int i = 0; i < 20; ++i) w[i] = 0; }
     __device__ void add(uint64_t v, int shift) {  // += v << shift
         if (!v) return;
@@ -481,92 +602,96 @@ struct BigAcc {
         int top = -1;
         for (int i = 19; i >= 0; --i) if (w[i]) { top = i; break; }
         if (top < 0) return 0.0;
-        int P = top * 32 + 31 - __clz(w[top]);  // index of the most significant set bit
-        auto bit = [&](int i) -> uint32_t { return i < 0 ? 0u : (w[i >> 5] >> (i & 31)) & 1u; };
-        uint64_t mant = 0;
-        for (int i = 0; i < 53; ++i) mant = (mant << 1) | bit(P - i);
-        if (P >= 53) {
-            uint32_t guard = bit(P - 53);
-            bool sticky = false;
-            for (int i = P - 54; i >= 0 && !sticky; --i) sticky = bit(i) != 0;
-            if (guard && (sticky || (mant & 1ull))) ++mant;
-            return ldexp((double)mant, P - 52 - 298);
+        const int P = top * 32 + 31 - __clz(w[top]);  // index of the most significant set bit
+        auto word = [&](int i) -> uint64_t { return (i < 0 || i >= 20) ? 0ull : (uint64_t)w[i]; };
+        if (P <= 52) {  // fits the significand exactly
+            uint64_t v = word(0) | (word(1) << 32);
+            return ldexp((double)v, -298);
         }
-        return ldexp((double)(mant >> (52 - P)), -298);
+        // bits P .. P-52 as the significand, bit P-53 as guard, anything below as sticky
+        const int g = P - 53;                       // guard bit index (>= 0)
+        const int wi = g >> 5, bs = g & 31;         // window starting at the guard bit: 54 bits needed
+        uint64_t win = (word(wi) >> bs) | (word(wi + 1) << (32 - bs));
+        if (bs > 0) win |= word(wi + 2) << (64 - bs);
+        const uint32_t guard = (uint32_t)(win & 1ull);
+        uint64_t mant = (win >> 1) & ((1ull << 53) - 1ull);
+        bool sticky = bs ? (w[wi] & ((1u << bs) - 1u)) != 0 : false;
+        for (int i = wi - 1; i >= 0 && !sticky; --i) sticky = w[i] != 0;
+        if (guard && (sticky || (mant & 1ull))) ++mant;
+        return ldexp((double)mant, P - 52 - 298);
     }
 };
 
-__global__ __launch_bounds__(64) void k_norms(TopkArgs a) {
-    const int row = blockIdx.x, l = threadIdx.x;
-    if (l > a.L) return;
+__global__ __launch_bounds__(256) void k_norms(TopkArgs a) {
+    __shared__ uint32_t s_big[TMAX][20];
+    __shared__ unsigned long long s_glo[GMAX], s_ghi[GMAX];
+    __shared__ uint16_t s_gexp[GMAX], s_gband[GMAX];
+    __shared__ Piece s_pc[PMAX];
+    __shared__ double s_norm[LMAX];
+    const int row = blockIdx.x, tid = threadIdx.x;
     const RowInfo* ri = a.rinfo + row;
     const RowAcc* ra = a.racc + row;
-    BigAcc acc;
-    acc.clear();
     const int G = ri->n_groups;
-    for (int g = 0; g < G; ++g) {
-        if (ri->g_band[g] == l) {
-            int sh = 2 * ((int)ri->g_exp[g] - 1);
-            acc.add(ra->gsum[g][0], sh);
-            acc.add(ra->gsum[g][1], sh + 32);
-        }
+    for (int g = tid; g < G; g += 256) {
+        s_glo[g] = ra->gsum[g][0];
+        s_ghi[g] = ra->gsum[g][1];
+        s_gexp[g] = ri->g_exp[g];
+        s_gband[g] = ri->g_band[g];
     }
-    for (int p = 0; p < PMAX; ++p) {
-        const Piece& pc = ra->pieces[p];
-        if (pc.band_plus1 == l + 1) {
-            int sh = 2 * (pc.exp - 1);
-            acc.add(pc.lo, sh);
-            acc.add(pc.hi, sh + 32);
+    for (int p = tid; p < PMAX; p += 256) s_pc[p] = ra->pieces[p];
+    __syncthreads();
+    const int l = tid;
+    if (l >= 1 && l <= a.L) {
+        BigAcc acc;
+        acc.w = s_big[l];
+        acc.clear();
+        for (int g = 0; g < G; ++g) {
+            if (s_gband[g] == l) {
+                int sh = 2 * ((int)s_gexp[g] - 1);
+                acc.add(s_glo[g], sh);
+                acc.add(s_ghi[g], sh + 32);
+            }
         }
-    }
-    if (l >= 1) {
-        double S = acc.to_double();
-        double nrm = __dsqrt_rn(S);
+        for (int p = 0; p < PMAX; ++p) {
+            if (s_pc[p].band_plus1 == l + 1) {
+                int sh = 2 * (s_pc[p].exp - 1);
+                acc.add(s_pc[p].lo, sh);
+                acc.add(s_pc[p].hi, sh + 32);
+            }
+        }
+        double nrm = __dsqrt_rn(acc.to_double());
+        s_norm[l - 1] = nrm;
         a.norms[(size_t)row * a.L + (l - 1)] = nrm;
         if (a.norms_user) a.norms_user[(size_t)row * a.L + (l - 1)] = nrm;
     }
+    __syncthreads();
+    if (tid == 0 && a.draw_mode == 3) draw_row(a, row, s_norm);
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Level draw for all rows (one workgroup).
+// Level draw for all rows of the bit-wise path (one workgroup).
 __global__ __launch_bounds__(1024) void k_draw(DrawArgs a) {
-    __shared__ int64_t s_nnz[MLMC_MAX_WORKERS];
     const int r = threadIdx.x;
     if (r < a.M) {
         double p[LMAX];
         const int L = a.L;
-        if (a.mode == 0) {
-            for (int l = 0; l < L; ++l) p[l] = a.p_fixed[l];
-        } else if (a.mode == 1) {
-            for (int l = 0; l < L; ++l) p[l] = a.p_dev[(size_t)r * L + l];
-        } else {
-            double tot = 0.0;
-            for (int l = 0; l < L; ++l) tot = __dadd_rn(tot, a.p_dev[(size_t)r * L + l]);
-            for (int l = 0; l < L; ++l)
-                p[l] = tot == 0.0 ? __ddiv_rn(1.0, (double)L) : __ddiv_rn(a.p_dev[(size_t)r * L + l], tot);
-        }
+        for (int l = 0; l < L; ++l) p[l] = a.p_fixed[l];
         uint32_t x = philox_word0(a.seed, a.step, (uint32_t)r);
         int level = draw_from_p(p, L, x);
         double pl = p[level - 1];
-        float w = pl == 0.0 ? 0.0f : (float)__ddiv_rn(1.0, pl);
         RowInfo* ri = a.rinfo + r;
         ri->level = level;
-        ri->weight = w;
+        ri->weight = pl == 0.0 ? 0.0f : (float)__ddiv_rn(1.0, pl);
         ri->draw_x = x;
         a.level[r] = level;
-        s_nnz[r] = a.is_topk ? a.k[0] + a.k[level] - a.k[level - 1] : 0;
-    }
-    __syncthreads();
-    if (r == 0 && a.is_topk) {
-        int64_t run = 0;
-        for (int i = 0; i < a.M; ++i) { a.row_off[i] = run; run += s_nnz[i]; }
-        a.row_off[a.M] = run;
-        if (run > a.capacity) atomicOr(a.dev_status, MLMC_DEV_CAPACITY);
     }
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Compaction, pass 1: per tile, how many keys are above / equal to each of the three thresholds.
+// Compaction in one read.  A unit = CW waves x 1024 consecutive elements of one row.  Workgroups take units
+// from a ticket counter (rows interleaved, so every unit's predecessor in its row has an earlier ticket
+// and is already running); each unit publishes its counts (three tie counts, one output count) as
+// 64-bit descriptors and obtains its exclusive prefixes by decoupled look-back over its predecessors.
 struct Thr3 {
     uint32_t tau[3], q[3];
 };
@@ -579,126 +704,109 @@ __device__ __forceinline__ Thr3 load_thr3(const RowInfo* ri) {
     return t;
 }
 
-template <int DT, bool VEC>
-__global__ __launch_bounds__(256) void k_count(TopkArgs a) {
-    __shared__ uint32_t s_red[4][6];
-    const int row = blockIdx.y, tid = threadIdx.x;
-    const uint32_t lane = lane_id(), wave = tid >> 6;
-    const Thr3 th = load_thr3(a.rinfo + row);
-    RowLoader<DT, VEC> ld(a.g, a.ld, a.d, row);
-    const int64_t c0 = (int64_t)blockIdx.x * a.chunk;
-    const int64_t c1 = c0 + a.chunk < a.d ? c0 + a.chunk : a.d;
-    uint32_t* tc = a.tilecnt + (size_t)row * 6 * a.ntiles;
-    for (int64_t base = c0; base < c1; base += TILE) {
-        uint32_t cnt[6] = {0, 0, 0, 0, 0, 0};
-#pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            int64_t j = base + it * 1024 + tid * 4;
-            uint32_t b[4];
-            int nv = ld.load4(j, b);
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                if (c < nv) {
-                    uint32_t key = key_of_bits(b[c]);
-#pragma unroll
-                    for (int k = 0; k < 3; ++k) {
-                        cnt[2 * k] += key > th.tau[k] ? 1u : 0u;
-                        cnt[2 * k + 1] += key == th.tau[k] ? 1u : 0u;
-                    }
-                }
+constexpr unsigned long long DESC_AGG = 1ull << 62;   // value = this unit's own count
+constexpr unsigned long long DESC_PRE = 2ull << 62;   // value = inclusive prefix up to and including this unit
+constexpr unsigned long long DESC_VAL = 0xFFFFFFFFull;
+constexpr uint32_t LOOKBACK_SPIN_MAX = 1u << 22;      // bounded wait: about a second of polling
+
+__device__ __forceinline__ void desc_store(unsigned long long* p, unsigned long long v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned long long desc_load(const unsigned long long* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Run by one whole wave.  drow: descriptors of this row, [units][4]; chain c.  Publishes the unit's count,
+// returns the sum of the counts of units 0..unit-1, then publishes the inclusive prefix.
+__device__ uint32_t lookback(unsigned long long* drow, int c, int64_t unit, uint32_t agg, int32_t* dev_status) {
+    const uint32_t lane = lane_id();
+    unsigned long long* mine = drow + unit * 4 + c;
+    if (unit == 0) {
+        if (lane == 0) desc_store(mine, DESC_PRE | agg);
+        return 0;
+    }
+    if (lane == 0) desc_store(mine, DESC_AGG | agg);
+    uint32_t excl = 0;
+    int64_t pos = unit - 1;  // the window is units pos, pos-1, ..., pos-63 (lane 0 = nearest)
+    uint32_t spin = 0;
+    bool done = false;
+    while (!done) {
+        const int64_t u = pos - (int64_t)lane;
+        unsigned long long v = u >= 0 ? desc_load(drow + u * 4 + c) : DESC_PRE;
+        const uint32_t flag = (uint32_t)(v >> 62);
+        const uint64_t m_inv = __ballot(flag == 0);
+        const uint64_t m_pre = __ballot(flag == 2);
+        const int first_inv = m_inv ? (int)__builtin_ctzll(m_inv) : 64;
+        const int first_pre = m_pre ? (int)__builtin_ctzll(m_pre) : 64;
+        if (first_pre < first_inv) {          // a prefix is reachable through published counts
+            uint32_t part = (int)lane <= first_pre ? (uint32_t)(v & DESC_VAL) : 0u;
+            excl += wave_sum(part);
+            done = true;
+        } else if (first_inv == 64) {         // 64 published counts, no prefix yet: take them, look further back
+            excl += wave_sum((uint32_t)(v & DESC_VAL));
+            pos -= 64;
+        } else {                              // a predecessor has not published yet: poll again
+            __builtin_amdgcn_s_sleep(8);
+            if (++spin >= LOOKBACK_SPIN_MAX) {
+                if (lane == 0) atomicOr(dev_status, MLMC_DEV_INTERNAL);
+                done = true;
             }
         }
-#pragma unroll
-        for (int k = 0; k < 6; ++k) cnt[k] = wave_sum(cnt[k]);
-        __syncthreads();
-        if (lane == 0)
-            for (int k = 0; k < 6; ++k) s_red[wave][k] = cnt[k];
-        __syncthreads();
-        if (tid < 6) tc[(size_t)tid * a.ntiles + base / TILE] = s_red[0][tid] + s_red[1][tid] + s_red[2][tid] + s_red[3][tid];
     }
+    if (lane == 0) desc_store(mine, DESC_PRE | (unsigned long long)(excl + agg));
+    return excl;
 }
 
-// Compaction, pass 2: per row, tie prefixes and output offsets of every tile.
-__global__ __launch_bounds__(1024) void k_tilescan(TopkArgs a) {
-    __shared__ uint32_t s_scan[17];
-    const int row = blockIdx.x, tid = threadIdx.x;
-    const RowInfo* ri = a.rinfo + row;
-    const Thr3 th = load_thr3(ri);
+template <int DT, bool VEC, int CW>
+__global__ __launch_bounds__(CW * 64) void k_compact(TopkArgs a) {
+    constexpr int NT = CW * 64;
+    constexpr int UNIT = CW * 1024;
+    __shared__ int64_t s_rowoff[MLMC_MAX_WORKERS + 1];
+    __shared__ uint32_t s_ticket;
+    __shared__ uint32_t s_wtie[3][CW];
+    __shared__ uint32_t s_wemit[CW];
+    __shared__ uint32_t s_pre[4];
+    const int tid = threadIdx.x;
+    const uint32_t lane = lane_id(), wave = tid >> 6;
     const int64_t nt = a.ntiles;
-    const int64_t per = (nt + 1023) / 1024;
-    const int64_t t0 = (int64_t)tid * per, t1 = t0 + per < nt ? t0 + per : nt;
-    const uint32_t* tc = a.tilecnt + (size_t)row * 6 * nt;
-    uint32_t* tp = a.tiepre + (size_t)row * 3 * nt;
-    uint32_t* to = a.tile_off + (size_t)row * (nt + 1);
-    for (int k = 0; k < 3; ++k) {
-        uint32_t sum = 0;
-        for (int64_t t = t0; t < t1; ++t) sum += tc[(size_t)(2 * k + 1) * nt + t];
-        uint32_t total;
-        uint32_t run = block_excl_scan<1024>(sum, s_scan, total);
-        for (int64_t t = t0; t < t1; ++t) {
-            tp[(size_t)k * nt + t] = run;
-            run += tc[(size_t)(2 * k + 1) * nt + t];
-        }
+
+    // row offsets of the messages from the drawn levels (every workgroup keeps a copy; workgroup 0 writes them)
+    for (int i = tid; i < a.M; i += NT) {
+        const int lev = a.rinfo[i].level;
+        s_rowoff[i + 1] = a.k[0] + a.k[lev] - a.k[lev - 1];
     }
     __syncthreads();
-    auto emitted = [&](int64_t t) -> uint32_t {
-        uint32_t in[3];
-#pragma unroll
-        for (int k = 0; k < 3; ++k) {
-            uint64_t pre = tp[(size_t)k * nt + t], ce = tc[(size_t)(2 * k + 1) * nt + t];
-            uint64_t q = th.q[k];
-            uint64_t take = q > pre ? q - pre : 0;
-            if (take > ce) take = ce;
-            in[k] = tc[(size_t)(2 * k) * nt + t] + (uint32_t)take;
-        }
-        return in[0] + (in[2] - in[1]);
-    };
-    uint32_t sum = 0;
-    for (int64_t t = t0; t < t1; ++t) sum += emitted(t);
-    uint32_t total;
-    uint32_t run = block_excl_scan<1024>(sum, s_scan, total);
-    for (int64_t t = t0; t < t1; ++t) {
-        to[t] = run;
-        run += emitted(t);
-    }
     if (tid == 0) {
-        to[nt] = total;
-        const int lev = ri->level;
-        int64_t nnz = a.k[0] + a.k[lev] - a.k[lev - 1];
-        if ((int64_t)total != nnz) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
+        int64_t run = 0;
+        s_rowoff[0] = 0;
+        for (int i = 0; i < a.M; ++i) { int64_t n = s_rowoff[i + 1]; s_rowoff[i] = run; run += n; }
+        s_rowoff[a.M] = run;
+        if (blockIdx.x == 0 && run > a.capacity) atomicOr(a.dev_status, MLMC_DEV_CAPACITY);
     }
-}
+    __syncthreads();
+    if (blockIdx.x == 0)
+        for (int i = tid; i <= a.M; i += NT) a.row_off[i] = s_rowoff[i];
 
-// Compaction, pass 3: write (index, value) of base band and drawn band in index order.
-template <int DT, bool VEC>
-__global__ __launch_bounds__(256) void k_write(TopkArgs a) {
-    __shared__ uint32_t s_tie[3][4];
-    __shared__ uint32_t s_emit[4];
-    const int row = blockIdx.y, tid = threadIdx.x;
-    const uint32_t lane = lane_id(), wave = tid >> 6;
-    const RowInfo* ri = a.rinfo + row;
-    const Thr3 th = load_thr3(ri);
-    const float w = ri->weight;
-    RowLoader<DT, VEC> ld(a.g, a.ld, a.d, row);
-    const int64_t nt = a.ntiles;
-    const uint32_t* tc = a.tilecnt + (size_t)row * 6 * nt;
-    const uint32_t* tp = a.tiepre + (size_t)row * 3 * nt;
-    const uint32_t* to = a.tile_off + (size_t)row * (nt + 1);
-    const int64_t out_row = a.row_off[row];
-    const int64_t c0 = (int64_t)blockIdx.x * a.chunk;
-    const int64_t c1 = c0 + a.chunk < a.d ? c0 + a.chunk : a.d;
+    const uint32_t total_units = (uint32_t)(a.units_per_row * a.M);
+    while (true) {
+        if (tid == 0) s_ticket = atomicAdd(a.ticket, 1u);
+        __syncthreads();
+        const uint32_t ticket = s_ticket;
+        if (ticket >= total_units) break;
+        const int row = (int)(ticket % (uint32_t)a.M);
+        const int64_t unit = ticket / (uint32_t)a.M;
+        const RowInfo* ri = a.rinfo + row;
+        const Thr3 th = load_thr3(ri);
+        const float w = ri->weight;
+        RowLoader<DT, VEC> ld(a.g, a.ld, a.d, row);
+        const int64_t wbase = unit * UNIT + (int64_t)wave * 1024;  // this wave's 1024 elements
 
-    for (int64_t base = c0; base < c1; base += TILE) {
-        const int64_t tile = base / TILE;
-        if (to[tile + 1] == to[tile]) continue;  // nothing to emit here (uniform)
-        // this wave owns elements [base + wave*1024, +1024): 4 iterations of 64 lanes x 4
         uint32_t bits[16];
         uint32_t valid = 0;
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
-            int64_t j = base + wave * 1024 + it * 256 + lane * 4;
             uint32_t b[4];
-            int nv = ld.load4(j, b);
+            int nv = ld.load4(wbase + it * 256 + lane * 4, b);
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 bits[it * 4 + c] = b[c];
@@ -715,38 +823,42 @@ __global__ __launch_bounds__(256) void k_write(TopkArgs a) {
                 equal[k] |= (key == th.tau[k] ? 1u : 0u) << e;
             }
         }
-        uint32_t in[3];
-        bool any_tie = false;
 #pragma unroll
-        for (int k = 0; k < 3; ++k) {
-            above[k] &= valid;
-            equal[k] &= valid;
-            in[k] = above[k];
-            any_tie |= tc[(size_t)(2 * k + 1) * nt + tile] != 0;
+        for (int k = 0; k < 3; ++k) { above[k] &= valid; equal[k] &= valid; }
+        uint32_t in[3] = {above[0], above[1], above[2]};
+        {
+            uint32_t t0 = wave_sum(__popc(equal[0])), t1 = wave_sum(__popc(equal[1])), t2 = wave_sum(__popc(equal[2]));
+            uint32_t e0 = wave_sum(__popc(in[0] | (in[2] & ~in[1])));  // output count if the unit has no ties
+            if (lane == 0) { s_wtie[0][wave] = t0; s_wtie[1][wave] = t1; s_wtie[2][wave] = t2; s_wemit[wave] = e0; }
         }
-        if (any_tie) {  // uniform over the workgroup
-            uint32_t pre[3][4];
+        __syncthreads();
+        uint32_t ut[3];
+#pragma unroll
+        for (int k = 0; k < 3; ++k) ut[k] = wave_sum(lane < (uint32_t)CW ? s_wtie[k][lane] : 0u);
+        const bool any_tie = (ut[0] | ut[1] | ut[2]) != 0;  // uniform over the workgroup
+        unsigned long long* drow = a.desc + (size_t)row * (size_t)a.units_per_row * 4;
+        if (wave < 3) {
+            uint32_t ex = lookback(drow, (int)wave, unit, ut[wave], a.dev_status);
+            if (lane == 0) s_pre[wave] = ex;
+        } else if (wave == 3 && !any_tie) {
+            uint32_t agg = wave_sum(lane < (uint32_t)CW ? s_wemit[lane] : 0u);
+            uint32_t ex = lookback(drow, 3, unit, agg, a.dev_status);
+            if (lane == 0) s_pre[3] = ex;
+        }
+        __syncthreads();
+        if (any_tie) {
+            // rank the entries equal to a threshold key in index order; the first q_k of the row are inside
 #pragma unroll
             for (int k = 0; k < 3; ++k) {
-                uint32_t run = 0;
+                if (ut[k] == 0) continue;
+                uint64_t r0 = s_pre[k];
+                for (uint32_t w2 = 0; w2 < wave; ++w2) r0 += s_wtie[k][w2];
+                const uint64_t q = th.q[k];
 #pragma unroll
                 for (int it = 0; it < 4; ++it) {
                     uint32_t tot;
                     uint32_t ex = wave_excl_small(__popc((equal[k] >> (it * 4)) & 0xFu), tot);
-                    pre[k][it] = run + ex;
-                    run += tot;
-                }
-                if (lane == 0) s_tie[k][wave] = run;
-            }
-            __syncthreads();
-#pragma unroll
-            for (int k = 0; k < 3; ++k) {
-                uint64_t wbase = tp[(size_t)k * nt + tile];
-                for (uint32_t w2 = 0; w2 < wave; ++w2) wbase += s_tie[k][w2];
-                const uint64_t q = th.q[k];
-#pragma unroll
-                for (int it = 0; it < 4; ++it) {
-                    uint64_t r = wbase + pre[k][it];
+                    uint64_t r = r0 + ex;
 #pragma unroll
                     for (int c = 0; c < 4; ++c) {
                         const int e = it * 4 + c;
@@ -755,40 +867,53 @@ __global__ __launch_bounds__(256) void k_write(TopkArgs a) {
                             ++r;
                         }
                     }
+                    r0 += tot;
                 }
             }
+            uint32_t e1 = wave_sum(__popc(in[0] | (in[2] & ~in[1])));
+            __syncthreads();  // every wave has read the tentative s_wemit users (wave 3 did not use it)
+            if (lane == 0) s_wemit[wave] = e1;
+            __syncthreads();
+            if (wave == 3) {
+                uint32_t agg = wave_sum(lane < (uint32_t)CW ? s_wemit[lane] : 0u);
+                uint32_t ex = lookback(drow, 3, unit, agg, a.dev_status);
+                if (lane == 0) s_pre[3] = ex;
+            }
+            __syncthreads();
         }
         const uint32_t emit = in[0] | (in[2] & ~in[1]);
-        uint32_t epre[4];
-        uint32_t run = 0;
+        uint32_t wave_pre = s_pre[3];  // entries of this row before this wave's elements
+        for (uint32_t w2 = 0; w2 < wave; ++w2) wave_pre += s_wemit[w2];
+        if ((wave & 3u) == 0 && lane == 0) {
+            const int64_t tile = unit * (UNIT / TILE) + (wave >> 2);
+            if (tile < nt) a.tile_off[(size_t)row * (nt + 1) + tile] = wave_pre;
+        }
+        if (unit == a.units_per_row - 1 && wave == CW - 1 && lane == 0) {
+            const uint32_t total = wave_pre + s_wemit[wave];
+            a.tile_off[(size_t)row * (nt + 1) + nt] = total;
+            if ((int64_t)total != s_rowoff[row + 1] - s_rowoff[row]) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
+        }
+        int64_t pos0 = s_rowoff[row] + wave_pre;
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
             uint32_t tot;
             uint32_t ex = wave_excl_small(__popc((emit >> (it * 4)) & 0xFu), tot);
-            epre[it] = run + ex;
-            run += tot;
-        }
-        __syncthreads();  // s_emit (and s_tie) free for reuse
-        if (lane == 0) s_emit[wave] = run;
-        __syncthreads();
-        int64_t pos0 = out_row + to[tile];
-        for (uint32_t w2 = 0; w2 < wave; ++w2) pos0 += s_emit[w2];
-#pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            int64_t pos = pos0 + epre[it];
+            int64_t pos = pos0 + ex;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 const int e = it * 4 + c;
                 if ((emit >> e) & 1u) {
                     if (pos < a.capacity) {
                         float v = __uint_as_float(bits[e]);
-                        a.idx[pos] = (uint32_t)(base + wave * 1024 + it * 256 + lane * 4 + c);
+                        a.idx[pos] = (uint32_t)(wbase + it * 256 + lane * 4 + c);
                         a.val[pos] = ((in[0] >> e) & 1u) ? v : __fmul_rn(v, w);
                     }
                     ++pos;
                 }
             }
+            pos0 += tot;
         }
+        __syncthreads();  // LDS reuse by the next unit
     }
 }
 
@@ -802,18 +927,22 @@ static mlmc_status launch_select(const mlmc_plan_t* pl, const TopkArgs& a, bool 
     if (sums) MLMC_LAUNCH(K_PASS2, st, k_pass2<DT, VEC, true><<<grid, P2_THREADS, 0, st>>>(a));
     else MLMC_LAUNCH(K_PASS2, st, k_pass2<DT, VEC, false><<<grid, P2_THREADS, 0, st>>>(a));
     dim3 fgrid(pl->L + 1, pl->M);
-    if (sums) MLMC_LAUNCH(K_FINISH, st, k_finish<true><<<fgrid, 256, 0, st>>>(a));
-    else MLMC_LAUNCH(K_FINISH, st, k_finish<false><<<fgrid, 256, 0, st>>>(a));
-    if (sums) MLMC_LAUNCH(K_NORMS, st, k_norms<<<pl->M, 64, 0, st>>>(a));
+    if (sums) MLMC_LAUNCH(K_FINISH, st, k_finish<true><<<fgrid, FN_THREADS, 0, st>>>(a));
+    else MLMC_LAUNCH(K_FINISH, st, k_finish<false><<<fgrid, FN_THREADS, 0, st>>>(a));
+    if (sums) MLMC_LAUNCH(K_NORMS, st, k_norms<<<pl->M, 256, 0, st>>>(a));
     return MLMC_OK;
 }
 
 template <int DT, bool VEC>
 static mlmc_status launch_compact(const mlmc_plan_t* pl, const TopkArgs& a, hipStream_t st) {
-    dim3 grid(pl->chunks_per_row, pl->M);
-    MLMC_LAUNCH(K_COUNT, st, k_count<DT, VEC><<<grid, 256, 0, st>>>(a));
-    MLMC_LAUNCH(K_TILESCAN, st, k_tilescan<<<pl->M, 1024, 0, st>>>(a));
-    MLMC_LAUNCH(K_WRITE, st, k_write<DT, VEC><<<grid, 256, 0, st>>>(a));
+    const int64_t units = pl->units_per_row * pl->M;
+    if (pl->cwaves == 8) {
+        int grid = (int)(units < 1024 ? units : 1024);
+        MLMC_LAUNCH(K_COMPACT, st, k_compact<DT, VEC, 8><<<grid, 512, 0, st>>>(a));
+    } else {
+        int grid = (int)(units < 512 ? units : 512);
+        MLMC_LAUNCH(K_COMPACT, st, k_compact<DT, VEC, 16><<<grid, 1024, 0, st>>>(a));
+    }
     return MLMC_OK;
 }
 
