@@ -32,7 +32,7 @@ def algorithmic_bytes(w, kernel, nnz_total, planes_bytes):
     """Bytes the method itself has to move in one launch of `kernel` ('Kernels')."""
     s_in = 2 if w.dtype == "bf16" else 4
     in_bytes = w.M * w.d * s_in
-    if kernel in ("k_hist1", "k_pass2", "k_count", "k_bits_max"):
+    if kernel in ("k_main", "k_bits_max"):
         return in_bytes                                   # one read of every input element
     if kernel == "k_write":
         return in_bytes + 8 * nnz_total                   # read the rows, write (idx, val)

@@ -54,6 +54,7 @@ typedef enum {
 #define MLMC_DEV_CAPACITY 1  /* row_off[M] > capacity: entries past capacity were not written */
 #define MLMC_DEV_NONFINITE 2 /* an Inf or NaN input was seen (it is ordered by its bit pattern) */
 #define MLMC_DEV_INTERNAL 4  /* an internal consistency check failed (counts do not add up) */
+#define MLMC_DEV_REDONE 8    /* not an error: a row's sampled threshold search was refuted and the row was redone exactly */
 
 typedef enum { MLMC_F32 = 0, MLMC_BF16 = 1 } mlmc_dtype;
 typedef enum { MLMC_TOPK = 0, MLMC_BITS = 1 } mlmc_kind;
@@ -77,6 +78,15 @@ mlmc_status mlmc_plan(mlmc_plan_t **plan, int kind, int M, int64_t d, int in_dty
                       const int64_t *ladder, const double *p_fixed, size_t *workspace_bytes,
                       int64_t *sparse_capacity_worst);
 void mlmc_plan_destroy(mlmc_plan_t *plan);
+
+/*
+ * Tuning hook (MLMC_TOPK plans).  The rank thresholds of Top-k (Sec. 2.2, Sec. 3.2) are first located from a
+ * histogram of one 1024-element block out of 2^shift of every row, then proven or refuted by exact counts
+ * taken during the full read; a refuted row is redone from an exact histogram, so `shift` changes run time
+ * only, never a result.  mlmc_plan picks the shift from d (0 for short rows = exact histogram at once).
+ * 0 <= shift <= 12; MLMC_EINVAL otherwise.
+ */
+mlmc_status mlmc_plan_set_sampling(mlmc_plan_t *plan, int shift);
 
 /* Tiles per row of the offset table: ceil(d / MLMC_TILE). */
 int64_t mlmc_plan_num_tiles(const mlmc_plan_t *plan);

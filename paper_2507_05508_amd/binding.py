@@ -16,13 +16,13 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libmlmc.so")
 
 MLMC_OK, MLMC_EINVAL, MLMC_ENOMEM, MLMC_EHIP = 0, 1, 2, 3
-MLMC_DEV_CAPACITY, MLMC_DEV_NONFINITE, MLMC_DEV_INTERNAL = 1, 2, 4
+MLMC_DEV_CAPACITY, MLMC_DEV_NONFINITE, MLMC_DEV_INTERNAL, MLMC_DEV_REDONE = 1, 2, 4, 8
 MLMC_F32, MLMC_BF16 = 0, 1
 MLMC_TOPK, MLMC_BITS = 0, 1
 MLMC_TILE = 4096
 MLMC_MAX_LEVELS = 32
 
-EXPORTS = ["mlmc_plan", "mlmc_plan_destroy", "mlmc_plan_num_tiles", "mlmc_plan_num_planes", "mlmc_geometric_p",
+EXPORTS = ["mlmc_plan", "mlmc_plan_destroy", "mlmc_plan_set_sampling", "mlmc_plan_num_tiles", "mlmc_plan_num_planes", "mlmc_geometric_p",
            "mlmc_status_string", "mlmc_level_norms", "mlmc_compress_topk", "mlmc_compress_bits", "mlmc_aggregate",
            "mlmc_profile_enable", "mlmc_profile_reset", "mlmc_profile_num_kernels", "mlmc_profile_kernel_name",
            "mlmc_profile_get"]
@@ -47,6 +47,8 @@ def lib():
                                 C.POINTER(C.c_size_t), C.POINTER(i64)]
         L.mlmc_plan_destroy.restype = None
         L.mlmc_plan_destroy.argtypes = [vp]
+        L.mlmc_plan_set_sampling.restype = C.c_int
+        L.mlmc_plan_set_sampling.argtypes = [vp, i32]
         L.mlmc_plan_num_tiles.restype = i64
         L.mlmc_plan_num_tiles.argtypes = [vp]
         L.mlmc_plan_num_planes.restype = i32
@@ -153,9 +155,15 @@ class Plan:
         except Exception:
             pass
 
-    def status(self) -> int:
-        """Device status bits of the last call (synchronises)."""
-        return int(self.dev_status.item())
+    def set_sampling(self, shift: int):
+        """Histogram sampling of the threshold search: one block out of 2^shift (run time only, never results)."""
+        _check(lib().mlmc_plan_set_sampling(self.handle, int(shift)), "mlmc_plan_set_sampling")
+
+    def status(self, informational: bool = False) -> int:
+        """Device status bits of the last call (synchronises).  MLMC_DEV_REDONE is not an error and is only
+        reported when `informational` is set."""
+        s = int(self.dev_status.item())
+        return s if informational else s & ~MLMC_DEV_REDONE
 
 
 def mlmc_plan(kind, M, d, dtype, ladder, p_fixed=None, device="cuda:0", allocate=True) -> Plan:

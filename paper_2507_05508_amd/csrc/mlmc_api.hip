@@ -24,7 +24,7 @@ static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // ---- per-kernel HIP-event timing (off by default; not thread safe) ---------------------------------
 bool g_prof_on = false;
 static const char* const k_names[K_NUM] = {
-    "k_zero", "k_hist1", "k_scan1", "k_pass2", "k_finish", "k_norms", "k_draw", "k_compact",
+    "k_zero", "k_hist", "k_scan", "k_main", "k_finish", "k_norms", "k_draw", "k_emitcount", "k_write",
     "k_bits_max", "k_bits_extract", "k_agg_bits", "k_tileoff", "k_agg_sparse"};
 struct ProfPair { int id; hipEvent_t e0, e1; };
 static std::vector<ProfPair> g_pending;
@@ -79,18 +79,20 @@ static void fill_topk_args(const mlmc_plan_t* pl, TopkArgs& a, const void* g, in
     a.L = pl->L;
     for (int t = 0; t <= pl->L; ++t) a.k[t] = pl->ladder[t];
     a.chunk = pl->chunk;
+    a.chunks_per_row = pl->chunks_per_row;
+    a.sample_shift = pl->sample_shift;
     a.ntiles = pl->ntiles;
     a.racc = (RowAcc*)(w + pl->off_racc);
-    a.hist1 = (uint32_t*)(w + pl->off_hist1);
+    a.hist = (uint32_t*)(w + pl->off_hist);
+    a.hist2 = (uint32_t*)(w + pl->off_hist2);
+    a.chunk_emit = (uint32_t*)(w + pl->off_chunk_emit);
     a.rinfo = (RowInfo*)(w + pl->off_rinfo);
     a.table = (uint16_t*)(w + pl->off_table);
-    a.desc = (unsigned long long*)(w + pl->off_desc);
-    a.ticket = (uint32_t*)(w + pl->off_ticket);
-    a.units_per_row = pl->units_per_row;
-    a.cwaves = pl->cwaves;
+    a.chunk_cnt = (uint32_t*)(w + pl->off_chunk_cnt);
     a.tile_off = (uint32_t*)(w + pl->off_tileoff);
     a.norms = (double*)(w + pl->off_norms);
-    a.cand = (uint32_t*)(w + pl->off_cand);
+    a.cand_bits = (uint32_t*)(w + pl->off_cand_bits);
+    a.cand_idx = (uint32_t*)(w + pl->off_cand_idx);
     a.dev_status = dev_status;
 }
 
@@ -200,38 +202,43 @@ mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dty
         pl->nplanes = 1 + (int)ladder[0] + maxw;
     }
     // chunking of the streaming kernels: about 2048 workgroups over all rows, whole tiles, at most 2^18
-    // elements per workgroup (the LDS sum accumulators of the band-sum pass rely on that bound)
+    // elements per workgroup (the LDS accumulators and the packed candidate offsets rely on that bound)
     int64_t target_per_row = 2048 / M > 0 ? 2048 / M : 1;
     int64_t chunk = (d + target_per_row - 1) / target_per_row;
     chunk = (chunk + TILE - 1) / TILE * TILE;
     if (chunk < 4 * TILE) chunk = 4 * TILE;
-    if (chunk > (1 << 18)) chunk = 1 << 18;
+    if (chunk > CHUNK_MAX) chunk = CHUNK_MAX;
     pl->chunk = (int)chunk;
-    pl->chunks_per_row = (int)((d + chunk - 1) / chunk);
+    pl->chunks_per_row = (int)((d + chunk - 1) / chunk);   // <= 2^31 / 2^18 = CHUNKS_MAX
+    // rows long enough that a second full read matters get their thresholds from a sampled histogram
+    pl->sample_shift = d >= ((int64_t)1 << 23) ? 4 : d >= ((int64_t)1 << 21) ? 2 : 0;
 
     size_t off = 0;
     pl->off_racc = off;
     off = align_up(off + sizeof(RowAcc) * (size_t)M, 256);
-    pl->off_hist1 = off;
-    if (kind == MLMC_TOPK) off = align_up(off + sizeof(uint32_t) * NB1 * (size_t)M, 256);
-    // compaction units: larger workgroups when few rows share the look-back chains
-    pl->cwaves = M >= 8 ? 8 : 16;
-    pl->units_per_row = (d + (int64_t)pl->cwaves * 1024 - 1) / ((int64_t)pl->cwaves * 1024);
-    pl->off_desc = off;
-    if (kind == MLMC_TOPK) off = align_up(off + sizeof(unsigned long long) * 4 * (size_t)pl->units_per_row * M, 256);
-    pl->off_ticket = off;
-    off = align_up(off + 256, 256);
+    if (kind == MLMC_TOPK) {
+        pl->off_hist = off;
+        off = align_up(off + sizeof(uint32_t) * NB1 * (size_t)M, 256);
+        pl->off_hist2 = off;
+        off = align_up(off + sizeof(uint32_t) * NB1 * (size_t)M, 256);
+        pl->off_chunk_emit = off;
+        off = align_up(off + sizeof(uint32_t) * (size_t)pl->chunks_per_row * M, 256);
+    }
     pl->zero_bytes = off;
     pl->off_rinfo = off;
     off = align_up(off + sizeof(RowInfo) * (size_t)M, 256);
     if (kind == MLMC_TOPK) {
         pl->off_table = off;
         off = align_up(off + sizeof(uint16_t) * NB1 * (size_t)M, 256);
+        pl->off_chunk_cnt = off;
+        off = align_up(off + sizeof(uint32_t) * RMAX * (size_t)pl->chunks_per_row * M, 256);
         pl->off_tileoff = off;
         off = align_up(off + sizeof(uint32_t) * (size_t)(pl->ntiles + 1) * M, 256);
         pl->off_norms = off;
         off = align_up(off + sizeof(double) * (size_t)L * M, 256);
-        pl->off_cand = off;
+        pl->off_cand_bits = off;
+        off = align_up(off + sizeof(uint32_t) * (size_t)d * M, 256);
+        pl->off_cand_idx = off;
         off = align_up(off + sizeof(uint32_t) * (size_t)d * M, 256);
     }
     pl->ws_bytes = off;
@@ -251,6 +258,12 @@ mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dty
 }
 
 void mlmc_plan_destroy(mlmc_plan_t* plan) { delete plan; }
+
+mlmc_status mlmc_plan_set_sampling(mlmc_plan_t* plan, int shift) {
+    if (!plan || plan->kind != MLMC_TOPK || shift < 0 || shift > 12) return MLMC_EINVAL;
+    plan->sample_shift = shift;
+    return MLMC_OK;
+}
 
 int64_t mlmc_plan_num_tiles(const mlmc_plan_t* plan) { return plan ? plan->ntiles : 0; }
 int mlmc_plan_num_planes(const mlmc_plan_t* plan) { return plan ? plan->nplanes : 0; }
@@ -325,14 +338,11 @@ mlmc_status mlmc_compress_bits(const mlmc_plan_t* plan, const void* g, int64_t l
     std::memset(&da, 0, sizeof(da));
     da.M = plan->M;
     da.L = plan->L;
-    da.mode = 0;
     for (int l = 0; l < plan->L; ++l) da.p_fixed[l] = plan->p[l];
-    da.is_topk = 0;
     da.seed = seed;
     da.step = step;
     da.rinfo = b.rinfo;
     da.level = level;
-    da.dev_status = dev_status;
     mlmc_status rc = topk_zero(plan, ws, dev_status, st);
     if (rc != MLMC_OK) return rc;
     rc = topk_draw(da, st);

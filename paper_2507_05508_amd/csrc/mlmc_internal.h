@@ -9,42 +9,53 @@ namespace mlmc {
 
 constexpr int LMAX = MLMC_MAX_LEVELS;   // drawable levels 1..L
 constexpr int TMAX = LMAX + 1;          // rank thresholds t = 0..L (one per ladder entry)
-constexpr int SMAX = TMAX;              // distinct boundary buckets per row
+constexpr int ZMAX = TMAX;              // zones (key ranges that may hold a threshold) per row
+constexpr int RMAX = ZMAX + 1;          // regions per row: region i lies above zone i, region n_zones below the last zone
 constexpr int NB1 = 16384;              // first-digit buckets: 8 exponent bits + 6 mantissa bits of the key
 constexpr int B1_SHIFT = 17;            // key >> 17 = first digit
-constexpr int GMAX = 320;               // (exponent, band) sum groups per row: <= 255 + TMAX
-constexpr int PMAX = 2 * TMAX;          // boundary-bucket pieces per row
+constexpr int GMAX = 292;               // sum groups per row: id = (255 - exponent) + region index <= 255 + ZMAX
+constexpr int REP = 32;                 // lane-replicated LDS accumulators: slot = id * REP + (lane & 31)
+constexpr int PMAX = 192;               // exact partial sums ("pieces") that the zones of one row contribute
+constexpr int PIECE_CLASSES = 96;       // (parts of a zone) x (exponents of a zone) handled by one finish workgroup
 constexpr int TILE = MLMC_TILE;
-constexpr int ACC_SLOTS = 2048;         // LDS u64 accumulators of the band-sum pass
 constexpr int MAX_PLANES = 25;          // 1 sign + at most 24 field planes
+constexpr int CHUNK_MAX = 1 << 18;      // elements per workgroup chunk of the streaming kernels
+constexpr int CHUNKS_MAX = 8192;        // chunks per row
 
-constexpr uint16_t CODE_IGNORE = 0x7FFF;
-constexpr uint16_t CODE_CAND = 0x8000;
+constexpr uint16_t CODE_ZONE = 0x8000;  // table code of a zone bucket: CODE_ZONE | zone; else (region << 9) | group
 
 constexpr int THR_NONE = -1;      // k_t == 0: nothing is within the top k_t
 constexpr int THR_ALL = -2;       // k_t >= d: everything is
 constexpr int THR_INACTIVE = -3;  // not needed by this call
 
-struct Piece {          // exact sum of squared significands of one part of a boundary bucket
+constexpr uint32_t JX_ALL = 0x80000000u;  // every entry equal to the threshold key is inside (indices are < 2^31)
+
+struct Piece {          // exact sum of squared significands of one part of a zone
     int32_t band_plus1; // 0 = unused
     int32_t exp;        // max(exponent field, 1)
     uint64_t lo, hi;    // value = hi * 2^32 + lo, in units of 2^(2 (exp - 150))
 };
 
-struct RowInfo {  // per row, rewritten by every call
+// Per row, rewritten by every call.  Membership of entry (key, j) in the top k_t of its row:
+//     key > thr_tau[t]  ||  (key == thr_tau[t] && j < thr_jx[t])
+struct RowInfo {
     uint32_t thr_tau[TMAX];   // key at rank k_t - 1
-    uint32_t thr_q[TMAX];     // how many entries equal to thr_tau are within the top k_t
-    int32_t thr_slot[TMAX];   // boundary-bucket slot, or THR_*
-    uint32_t thr_resid[TMAX]; // rank of the threshold inside its bucket (1-based)
-    int32_t n_slots, n_groups, rep_shift, level;
+    uint32_t thr_jx[TMAX];    // entries equal to thr_tau with index below thr_jx are within the top k_t
+    int32_t thr_zone[TMAX];   // zone that holds the threshold, or THR_*
+    int32_t n_zones, level, respec, exact;
     float weight;
     uint32_t draw_x;
-    uint32_t slot_bucket[SMAX], slot_off[SMAX], slot_cnt[SMAX];
-    uint16_t g_exp[GMAX], g_band[GMAX];
+    uint32_t zone_top[ZMAX], zone_bot[ZMAX];   // first-digit buckets of the zone, top >= bot, both inclusive
+    uint32_t zone_off[ZMAX], zone_cap[ZMAX];   // its candidate list inside the row's candidate buffer
+    int32_t zone_t0[ZMAX], zone_t1[ZMAX];      // thresholds t0..t1 (those that are active) lie in the zone
+    int32_t region_label[RMAX];                // band of every element of the region (label L + 1: in no band)
+    uint16_t g_exp[GMAX], g_band[GMAX];        // sum group -> max(exponent, 1), band (0xFFFF unused)
 };
 
-struct RowAcc {  // per row, zeroed at the start of every call
-    uint32_t slot_fill[SMAX];
+struct RowAcc {  // per row, zeroed at the start of every call (and again before a row is redone exactly)
+    uint32_t zone_fill[ZMAX];
+    uint32_t region_cnt[RMAX];
+    uint32_t n_pieces;
     uint32_t rowmax_key;
     uint64_t gsum[GMAX][2];
     Piece pieces[PMAX];
@@ -56,17 +67,19 @@ struct TopkArgs {
     int32_t M, L;
     int64_t k[TMAX];
     int32_t all_thresholds;  // 1: every ladder threshold + band sums (adaptive); 0: thresholds 0, l-1, l only
-    int32_t chunk;           // elements per workgroup chunk (multiple of TILE)
+    int32_t chunk;           // elements per workgroup chunk (multiple of TILE, <= CHUNK_MAX)
+    int32_t chunks_per_row;
+    int32_t sample_shift;    // the first histogram reads one 1024-element block out of 2^sample_shift
     int64_t ntiles;
-    uint32_t* hist1;         // [M][NB1]
+    uint32_t* hist;          // [M][NB1] histogram of the sampled blocks
+    uint32_t* hist2;         // [M][NB1] full histogram of the rows that are redone exactly
     uint16_t* table;         // [M][NB1]
     RowInfo* rinfo;          // [M]
     RowAcc* racc;            // [M]
-    uint32_t* cand;          // [M][d]
-    unsigned long long* desc; // [M][units_per_row][4] look-back descriptors of the compaction (zeroed per call)
-    uint32_t* ticket;        // [1] work counter of the compaction (zeroed per call)
-    int64_t units_per_row;   // compaction units (cwaves * 1024 elements) per row
-    int32_t cwaves;          // waves per compaction workgroup
+    uint32_t* cand_bits;     // [M][d] candidate lists: fp32 bit patterns
+    uint32_t* cand_idx;      // [M][d]                  indices
+    uint32_t* chunk_cnt;     // [M][chunks_per_row][RMAX] elements of every region per chunk
+    uint32_t* chunk_emit;    // [M][chunks_per_row] message entries that come from the zones, per chunk
     uint32_t* tile_off;      // [M][ntiles + 1]
     double* norms;           // [M][L]
     double* norms_user;      // optional copy
@@ -85,17 +98,11 @@ struct TopkArgs {
 };
 
 struct DrawArgs {
-    int32_t M, L, mode;      // mode 0: p_fixed; 1: dev p; 2: dev norms
+    int32_t M, L;
     double p_fixed[LMAX];
-    const double* p_dev;     // [M][L]
-    int64_t k[TMAX];         // Top-k: ladder; bits: unused
-    int32_t is_topk;
     uint64_t seed, step;
     RowInfo* rinfo;
     int32_t* level;
-    int64_t* row_off;
-    int64_t capacity;
-    int32_t* dev_status;
 };
 
 struct BitsArgs {
@@ -117,7 +124,7 @@ struct BitsArgs {
 
 // ---- optional per-kernel timing with HIP events (host side, see mlmc_profile_* in mlmc.h) ----------
 enum KernelId {
-    K_ZERO = 0, K_HIST1, K_SCAN1, K_PASS2, K_FINISH, K_NORMS, K_DRAW, K_COMPACT,
+    K_ZERO = 0, K_HIST, K_SCAN, K_MAIN, K_FINISH, K_NORMS, K_DRAW, K_EMITCOUNT, K_WRITE,
     K_BITS_MAX, K_BITS_EXTRACT, K_AGG_BITS, K_TILEOFF, K_AGG_SPARSE, K_NUM
 };
 extern bool g_prof_on;
@@ -145,11 +152,9 @@ struct mlmc_plan_s {
     int nplanes;
     int chunk;
     int chunks_per_row;
+    int sample_shift;
     // workspace byte offsets
-    size_t off_racc, off_hist1, zero_bytes;  // [0, zero_bytes) is cleared per call
-    size_t off_desc, off_ticket;
-    int64_t units_per_row;
-    int cwaves;
-    size_t off_rinfo, off_table, off_tileoff, off_norms, off_cand;
+    size_t off_racc, off_hist, off_hist2, off_chunk_emit, zero_bytes;  // [0, zero_bytes) is cleared per call
+    size_t off_rinfo, off_table, off_chunk_cnt, off_tileoff, off_norms, off_cand_bits, off_cand_idx;
     size_t ws_bytes;
 };

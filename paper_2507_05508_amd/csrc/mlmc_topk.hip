@@ -1,17 +1,24 @@
-// Top-k MLMC on gfx950: exact multi-rank radix select on |g| keys, exact band sums of squares,
-// level draw, index-ordered band compaction.
+// Top-k MLMC on gfx950: exact multi-rank select on |g| keys, exact band sums of squares, level draw,
+// index-ordered band compaction.  The rows are read twice: once to select, once to write the message.
 //
-// Pipeline per call (all rows at once, one row per blockIdx.y or per workgroup):
-//   k_hist1    first-digit histogram of the keys (14 bits: exponent + 6 mantissa bits), LDS atomics
-//   k_scan1    per row: bucket of every needed rank threshold, class table bucket -> {sum group | candidate slot}
-//   k_pass2    second read: exact sums of squared significands per (exponent, band) group; keys of the
-//              boundary buckets are appended to per-slot candidate lists
-//   k_finish   per boundary bucket: remaining 17 key bits from the candidate list -> exact threshold key,
-//              tie quota, and the exact split of the bucket's sum between the bands it straddles
-//   k_norms    big-integer accumulation of the group sums -> correctly rounded fp64 S_l -> Delta_l (Lemma 3.4),
-//              then the adaptive level draw (Alg. 3); with known p the draw happens at the start of k_scan1
-//   k_compact  index-ordered compaction of base band + drawn band (Eq. (6)) in one read of the rows:
-//              per-unit counts chained across workgroups by decoupled look-back
+// Pipeline per call (all rows at once):
+//   k_hist       14-bit first-digit histogram (exponent + 6 mantissa bits) of a SAMPLE of every row: one
+//                1024-element block out of 2^s (s = 0 for short rows: then the histogram is exact)
+//   k_scan       per row: from the (scaled) sample histogram, a ZONE of buckets around every needed rank
+//                threshold that holds it with overwhelming probability; the buckets between zones are REGIONS whose
+//                elements lie wholly inside one band.  Writes the bucket -> {region, sum group | zone} table.
+//   k_main       the one full selection read: per region exact element counts (per chunk and per row) and exact
+//                sums of squared significands per (exponent, region); elements of zones are appended, with
+//                their index, to per-zone candidate lists
+//   k_finish     per zone: the exact counts above it prove (or refute) that its thresholds lie inside; radix select
+//                on the candidate list -> exact threshold key, index cut among equal keys, exact sums of the
+//                parts the thresholds cut the zone into.  A refuted row is flagged and redone with an exact
+//                histogram (k_hist / k_scan / k_main / k_finish once more, for flagged rows only).
+//   k_norms      big-integer accumulation of group and part sums -> correctly rounded fp64 S_l -> Delta_l
+//                (Lemma 3.4), then the adaptive level draw (Alg. 3); with known p the draw is done in k_scan
+//   k_emitcount  message entries that come from the zones of thresholds 0, l-1, l, per chunk
+//   k_write      second read: index-ordered compaction of base band + drawn band (Eq. (6)); a workgroup owns a
+//                chunk whose output offset follows from the per-chunk counts, so no look-back is needed
 #include "mlmc_device.h"
 
 namespace mlmc {
@@ -26,37 +33,52 @@ __global__ __launch_bounds__(256) void k_zero(uint4* p, size_t n16, int32_t* dev
 }
 
 // ---------------------------------------------------------------------------------------------------
-// First-digit histogram.  One workgroup = one contiguous chunk of one row.
+// First-digit histogram of the sampled blocks (block b of 1024 elements is sampled when b % S == S / 2).
+// exact_pass: only rows flagged for an exact redo are read, every block, into hist2.
+constexpr int HIST_THREADS = 512;
 template <int DT, bool VEC>
-__global__ __launch_bounds__(512) void k_hist1(TopkArgs a) {
+__global__ __launch_bounds__(HIST_THREADS) void k_hist(TopkArgs a, int exact_pass) {
     __shared__ uint32_t h[NB1];
     const int row = blockIdx.y;
-    const int64_t c0 = (int64_t)blockIdx.x * a.chunk;
-    const int64_t c1 = c0 + a.chunk < a.d ? c0 + a.chunk : a.d;
-    for (int b = threadIdx.x; b < NB1; b += 512) h[b] = 0;
+    if (exact_pass && !a.rinfo[row].respec) return;
+    const int shift = exact_pass ? 0 : a.sample_shift;
+    const int64_t S = (int64_t)1 << shift, first = S >> 1;
+    const int64_t nblk = (a.d + 1023) / 1024;
+    const int64_t ns = nblk > first ? (nblk - first + S - 1) / S : 0;   // sampled blocks of the row
+    const int64_t per = (ns + gridDim.x - 1) / gridDim.x;
+    const int64_t i0 = (int64_t)blockIdx.x * per;
+    const int64_t i1 = i0 + per < ns ? i0 + per : ns;
+    if (i0 >= i1) return;
+    for (int b = threadIdx.x; b < NB1; b += HIST_THREADS) h[b] = 0;
     __syncthreads();
     RowLoader<DT, VEC> ld(a.g, a.ld, a.d, row);
+    const uint32_t lane = lane_id(), wave = threadIdx.x >> 6;
     uint32_t maxkey = 0;
-#pragma unroll 4
-    for (int64_t j = c0 + (int64_t)threadIdx.x * 4; j < c1; j += 512 * 4) {
-        uint32_t b[4];
-        int nv = ld.load4(j, b);
+    for (int64_t i = i0 + wave; i < i1; i += HIST_THREADS / 64) {
+        const int64_t base = (first + i * S) * 1024 + lane * 4;
+        uint32_t b[4][4];
+        int nv[4];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            if (c < nv) {
-                uint32_t key = key_of_bits(b[c]);
-                atomicAdd(&h[key >> B1_SHIFT], 1u);
-                maxkey = key > maxkey ? key : maxkey;
+        for (int q = 0; q < 4; ++q) nv[q] = ld.load4(base + q * 256, b[q]);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                if (c < nv[q]) {
+                    uint32_t key = key_of_bits(b[q][c]);
+                    atomicAdd(&h[key >> B1_SHIFT], 1u);
+                    maxkey = key > maxkey ? key : maxkey;
+                }
             }
         }
     }
     __syncthreads();
-    uint32_t* gh = a.hist1 + (size_t)row * NB1;
-    for (int b = threadIdx.x; b < NB1; b += 512) {
+    uint32_t* gh = (exact_pass ? a.hist2 : a.hist) + (size_t)row * NB1;
+    for (int b = threadIdx.x; b < NB1; b += HIST_THREADS) {
         uint32_t v = h[b];
         if (v) atomicAdd(&gh[b], v);
     }
-    if (__ballot(maxkey >= 0x7F800000u) && lane_id() == 0) atomicOr(a.dev_status, MLMC_DEV_NONFINITE);
+    if (__ballot(maxkey >= 0x7F800000u) && lane == 0) atomicOr(a.dev_status, MLMC_DEV_NONFINITE);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -85,325 +107,348 @@ __device__ void draw_row(const TopkArgs& a, int row, const double* norms_row) {
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Per row: locate thresholds at bucket resolution, assign candidate slots and sum groups, write the table.
-__global__ __launch_bounds__(1024) void k_scan1(TopkArgs a) {
+// Per row: zones and regions from the histogram, candidate list layout, the class table.
+// How far (in standard deviations of the sampled count) a zone reaches on either side of the estimated rank.
+constexpr double ZONE_SIGMAS = 8.0;
+
+__global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
     __shared__ uint32_t s_h[NB1];
+    __shared__ uint32_t s_cum[NB1];          // sampled elements in buckets above b
     __shared__ uint32_t s_scan[17];
-    __shared__ uint32_t s_bmask[NB1 / 32];   // bit per bucket: holds a threshold (boundary bucket)
-    __shared__ uint32_t s_pmask[NB1 / 32];   // bit per bucket: populated
     __shared__ int32_t s_active[TMAX];
-    __shared__ int64_t s_k[TMAX];
-    __shared__ uint32_t s_tb[TMAX];          // bucket of threshold t; 0xFFFFFFFF none, 0xFFFFFFFE all
-    __shared__ uint32_t s_tr[TMAX];
-    __shared__ int32_t s_ng[256];
-    __shared__ int32_t s_gbase[256];
-    __shared__ int32_t s_nslots, s_lev;
-    __shared__ uint32_t s_slotb[SMAX];
+    __shared__ int64_t s_lo[TMAX], s_hi[TMAX];   // sample ranks (1-based) that bound the threshold's zone
+    __shared__ uint32_t s_top[TMAX], s_bot[TMAX];
+    __shared__ int32_t s_nz, s_lev;
+    __shared__ uint32_t s_ztop[ZMAX], s_zbot[ZMAX];
+    __shared__ int32_t s_label[RMAX];
 
     const int row = blockIdx.x, tid = threadIdx.x;
     RowInfo* ri = a.rinfo + row;
-    const uint32_t* gh = a.hist1 + (size_t)row * NB1;
+    RowAcc* ra = a.racc + row;
     const int L = a.L;
+    if (exact_pass) {
+        if (!ri->respec) return;
+        if (tid == 0) atomicOr(a.dev_status, MLMC_DEV_REDONE);
+        // the row starts over: clear what the first attempt accumulated
+        uint32_t* z = (uint32_t*)ra;
+        for (int i = tid; i < (int)(sizeof(RowAcc) / 4); i += 1024) z[i] = 0;
+    }
+    const bool exact = exact_pass || a.sample_shift == 0;
+    const uint32_t* gh = (exact_pass ? a.hist2 : a.hist) + (size_t)row * NB1;
 
     if (tid == 0) {
-        if (!a.all_thresholds) draw_row(a, row, nullptr);  // p is known up front: draw before anything else
+        if (!exact_pass) {
+            ri->respec = 0;
+            if (!a.all_thresholds) draw_row(a, row, nullptr);  // p is known up front: draw before anything else
+        }
+        ri->exact = exact ? 1 : 0;
         s_lev = a.all_thresholds ? 0 : ri->level;
     }
     for (int b = tid; b < NB1; b += 1024) s_h[b] = gh[b];
-    for (int w = tid; w < NB1 / 32; w += 1024) { s_bmask[w] = 0; s_pmask[w] = 0; }
+    for (int g = tid; g < GMAX; g += 1024) ri->g_band[g] = 0xFFFF;
     __syncthreads();
     const int lev = s_lev;
-    if (tid <= L) {
-        bool act = a.all_thresholds || tid == 0 || tid == lev - 1 || tid == lev;
-        s_active[tid] = act;
-        int64_t kt = a.k[tid];
-        s_k[tid] = kt;
-        s_tb[tid] = kt <= 0 ? 0xFFFFFFFFu : 0xFFFFFFFEu;  // overwritten below when 0 < k_t < d
-        s_tr[tid] = 0;
-    }
 
     // descending buckets: rb = tid*16 + i  <->  b = NB1 - 1 - rb
     uint32_t hv[16];
-    uint32_t sum = 0, pbits = 0;
+    uint32_t sum = 0;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         hv[i] = s_h[NB1 - 1 - (tid * 16 + i)];
         sum += hv[i];
-        pbits |= (hv[i] ? 1u : 0u) << (15 - i);   // bit position = bucket offset inside the aligned 16-block
-    }
-    if (pbits) {
-        const int b0 = NB1 - 16 - tid * 16;        // lowest bucket of this thread's block (multiple of 16)
-        atomicOr(&s_pmask[b0 >> 5], pbits << (b0 & 31));
     }
     uint32_t total;
-    const uint32_t before = block_excl_scan<1024>(sum, s_scan, total);   // also orders the LDS writes above
-    if (tid == 0 && (int64_t)total != a.d) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
+    const uint32_t before = block_excl_scan<1024>(sum, s_scan, total);
+    {
+        uint32_t run = before;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            s_cum[NB1 - 1 - (tid * 16 + i)] = run;
+            run += hv[i];
+        }
+    }
+    const int64_t ns = total;  // sampled elements
+    if (tid == 0 && exact && ns != a.d) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
+    if (tid <= L) {
+        const int t = tid;
+        const bool act = a.all_thresholds || t == 0 || t == lev - 1 || t == lev;
+        s_active[t] = act;
+        const int64_t kt = a.k[t];
+        int64_t lo = kt, hi = kt;
+        if (!exact) {
+            const double m = (double)kt * (double)ns / (double)a.d;
+            const double frac = 1.0 - (double)kt / (double)a.d;
+            const double sd = sqrt(m * (frac > 0.0 ? frac : 0.0));
+            lo = (int64_t)floor(m - ZONE_SIGMAS * sd) - 2;
+            hi = (int64_t)ceil(m + ZONE_SIGMAS * sd) + 2;
+        }
+        if (lo < 1) lo = 0;            // the zone starts at the highest bucket
+        if (hi > ns) hi = ns + 1;      // the zone reaches the lowest bucket
+        s_lo[t] = lo;
+        s_hi[t] = hi;
+        s_top[t] = NB1 - 1;
+        s_bot[t] = 0;
+    }
+    __syncthreads();
     if (sum) {
         for (int t = 0; t <= L; ++t) {
-            const int64_t kt = s_k[t];
-            if (!s_active[t] || kt <= 0 || kt >= a.d) continue;
-            if (kt <= (int64_t)before || kt > (int64_t)before + sum) continue;   // not in this thread's 16 buckets
-            uint32_t run = before;
+            if (!s_active[t]) continue;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                if ((int64_t)run < kt && kt <= (int64_t)run + hv[i]) {
-                    s_tb[t] = (uint32_t)(NB1 - 1 - (tid * 16 + i));
-                    s_tr[t] = (uint32_t)(kt - run);
+            for (int which = 0; which < 2; ++which) {
+                const int64_t r = which ? s_hi[t] : s_lo[t];
+                if (r <= (int64_t)before || r > (int64_t)before + sum) continue;   // not in this thread's 16 buckets
+                uint32_t run = before;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    if ((int64_t)run < r && r <= (int64_t)run + hv[i]) {
+                        if (which) s_bot[t] = (uint32_t)(NB1 - 1 - (tid * 16 + i));
+                        else s_top[t] = (uint32_t)(NB1 - 1 - (tid * 16 + i));
+                    }
+                    run += hv[i];
                 }
-                run += hv[i];
             }
         }
     }
     __syncthreads();
 
     if (tid == 0) {
-        int ns = 0;
-        uint32_t off = 0;
+        int nz = 0, lab = 0;
         for (int t = 0; t <= L; ++t) {
             if (!s_active[t]) {
-                ri->thr_slot[t] = THR_INACTIVE;
+                ri->thr_zone[t] = THR_INACTIVE;
                 continue;
             }
-            uint32_t b = s_tb[t];
-            if (b == 0xFFFFFFFFu) {
-                ri->thr_slot[t] = THR_NONE;
+            const int64_t kt = a.k[t];
+            if (kt <= 0) {
+                ri->thr_zone[t] = THR_NONE;
                 ri->thr_tau[t] = 0xFFFFFFFFu;
-                ri->thr_q[t] = 0;
-            } else if (b == 0xFFFFFFFEu) {
-                ri->thr_slot[t] = THR_ALL;
+                ri->thr_jx[t] = 0;
+                lab = t + 1;
+            } else if (kt >= a.d) {
+                ri->thr_zone[t] = THR_ALL;
                 ri->thr_tau[t] = 0;
-                ri->thr_q[t] = 0xFFFFFFFFu;
+                ri->thr_jx[t] = JX_ALL;
             } else {
-                if (ns == 0 || s_slotb[ns - 1] != b) {
-                    s_slotb[ns] = b;
-                    ri->slot_bucket[ns] = b;
-                    ri->slot_cnt[ns] = s_h[b];
-                    ri->slot_off[ns] = off;
-                    off += s_h[b];
-                    s_bmask[b >> 5] |= 1u << (b & 31);
-                    ++ns;
+                const uint32_t top = s_top[t], bot = s_bot[t] < s_top[t] ? s_bot[t] : s_top[t];
+                if (nz > 0 && top >= s_zbot[nz - 1]) {   // overlaps the previous zone: one zone for both
+                    if (top > s_ztop[nz - 1]) s_ztop[nz - 1] = top;
+                    if (bot < s_zbot[nz - 1]) s_zbot[nz - 1] = bot;
+                    ri->zone_t1[nz - 1] = t;
+                } else {
+                    s_ztop[nz] = top;
+                    s_zbot[nz] = bot;
+                    ri->zone_t0[nz] = t;
+                    ri->zone_t1[nz] = t;
+                    s_label[nz] = lab;
+                    ++nz;
                 }
-                ri->thr_slot[t] = ns - 1;
-                ri->thr_resid[t] = s_tr[t];
+                ri->thr_zone[t] = nz - 1;
+                lab = t + 1;
             }
         }
-        ri->n_slots = ns;
-        s_nslots = ns;
+        s_label[nz] = lab;
+        // candidate list layout
+        const uint64_t S = exact ? 1ull : (1ull << a.sample_shift);
+        uint64_t off = 0;
+        for (int z = 0; z < nz; ++z) {
+            const uint32_t top = s_ztop[z], bot = s_zbot[z];
+            const uint64_t c = (uint64_t)s_cum[bot] + s_h[bot] - s_cum[top];
+            uint64_t cap = c;
+            if (!exact) cap = S * (c + (uint64_t)(8.0 * sqrt((double)c)) + 16);
+            if (off + cap > (uint64_t)a.d) cap = (uint64_t)a.d - off;
+            ri->zone_top[z] = top;
+            ri->zone_bot[z] = bot;
+            ri->zone_off[z] = (uint32_t)off;
+            ri->zone_cap[z] = (uint32_t)cap;
+            off += cap;
+        }
+        for (int r = 0; r <= nz; ++r) ri->region_label[r] = s_label[r];
+        ri->n_zones = nz;
+        s_nz = nz;
     }
     __syncthreads();
 
-    // One thread per exponent (64 buckets, bit i of the masks <-> bucket 64 E + i).  Boundary buckets cut the
-    // exponent into segments; a populated segment lies wholly inside one band and is one sum group:
-    // band = number of thresholds whose bucket lies above the segment ("none" thresholds always do).
-    const int E = tid;
-    uint64_t pm = 0, bm = 0;
-    int band_top = 0;
-    if (tid < 256) {
-        pm = (uint64_t)s_pmask[2 * E] | ((uint64_t)s_pmask[2 * E + 1] << 32);
-        bm = (uint64_t)s_bmask[2 * E] | ((uint64_t)s_bmask[2 * E + 1] << 32);
-        for (int t = 0; t <= L; ++t) {
-            uint32_t tb = s_tb[t];
-            band_top += (tb == 0xFFFFFFFFu || (tb != 0xFFFFFFFEu && (int)tb > E * 64 + 63)) ? 1 : 0;
-        }
-    }
-    auto thresholds_in = [&](int b) -> int {
-        int n = 0;
-        for (int t = 0; t <= L; ++t) n += s_tb[t] == (uint32_t)b ? 1 : 0;
-        return n;
-    };
-    // walks the segments from the top; calls f(segment mask, band, boundary bit below it or -1)
-    auto walk = [&](auto&& f) {
-        uint64_t rem = bm;
-        int hi = 63, band = band_top;
-        while (hi >= 0) {
-            const int bpos = rem ? 63 - __builtin_clzll(rem) : -1;
-            const uint64_t upto_hi = hi == 63 ? ~0ull : ((1ull << (hi + 1)) - 1ull);
-            const uint64_t below = bpos < 0 ? 0ull : ((bpos == 63) ? ~0ull : ((1ull << (bpos + 1)) - 1ull));
-            f(upto_hi & ~below, band, bpos);
-            if (bpos < 0) break;
-            band += thresholds_in(E * 64 + bpos);
-            rem &= ~(1ull << bpos);
-            hi = bpos - 1;
-        }
-    };
-    if (a.all_thresholds) {
-        if (tid < 256) {
-            int ng = 0;
-            walk([&](uint64_t seg, int, int) { ng += (pm & ~bm & seg) ? 1 : 0; });
-            s_ng[tid] = ng;
-        }
-        __syncthreads();
-        if (tid < 64) {  // exclusive scan over exponents, highest first: lane l owns exponents 255-4l .. 252-4l
-            int v[4], sum4 = 0;
+    // class table: thread tid writes its 16 buckets (descending), 32 bytes
+    const int nz = s_nz;
+    uint16_t codes[16];
+    int zi = 0;   // zones wholly above the current bucket
 #pragma unroll
-            for (int i = 0; i < 4; ++i) { v[i] = s_ng[255 - (tid * 4 + i)]; sum4 += v[i]; }
-            int inc = sum4;
-#pragma unroll
-            for (int o = 1; o < 64; o <<= 1) {
-                int u = __shfl_up(inc, o, 64);
-                if (tid >= o) inc += u;
-            }
-            int run = inc - sum4;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) { s_gbase[255 - (tid * 4 + i)] = run; run += v[i]; }
-            if (tid == 63) {
-                ri->n_groups = run;
-                ri->rep_shift = run <= 32 ? 6 : run <= 64 ? 5 : run <= 128 ? 4 : run <= 256 ? 3 : 2;
-            }
-        }
-        __syncthreads();
-    }
-    if (tid < 256) {
-        uint16_t* tab = a.table + (size_t)row * NB1 + E * 64;
-        if (bm == 0) {  // whole exponent in one band (or unpopulated / not needed)
-            uint16_t code = CODE_IGNORE;
-            if (a.all_thresholds && pm) {
-                int gid = s_gbase[E];
-                if (gid < GMAX) {
-                    ri->g_exp[gid] = (uint16_t)(E ? E : 1);
-                    ri->g_band[gid] = (uint16_t)band_top;
-                    code = (uint16_t)gid;
-                }
-            }
-            uint32_t c2 = (uint32_t)code | ((uint32_t)code << 16);
-            uint4 v = make_uint4(c2, c2, c2, c2);
-            uint4* dst = (uint4*)tab;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) dst[i] = v;
+    for (int i = 0; i < 16; ++i) {
+        const uint32_t b = (uint32_t)(NB1 - 1 - (tid * 16 + i));
+        while (zi < nz && s_zbot[zi] > b) ++zi;
+        if (zi < nz && b <= s_ztop[zi]) {
+            codes[15 - i] = (uint16_t)(CODE_ZONE | zi);
         } else {
-            int gid = a.all_thresholds ? s_gbase[E] : 0;
-            const int ns = s_nslots;
-            walk([&](uint64_t seg, int band, int bpos) {
-                uint16_t gcode = CODE_IGNORE;
-                if (a.all_thresholds && (pm & ~bm & seg)) {
-                    if (gid < GMAX) {
-                        ri->g_exp[gid] = (uint16_t)(E ? E : 1);
-                        ri->g_band[gid] = (uint16_t)band;
-                        gcode = (uint16_t)gid;
-                    }
-                    ++gid;
-                }
-                uint64_t sm = seg;
-                while (sm) {
-                    const int i = __builtin_ctzll(sm);
-                    sm &= sm - 1;
-                    tab[i] = ((pm >> i) & 1ull) ? gcode : CODE_IGNORE;
-                }
-                if (bpos >= 0) {
-                    int sl = 0;
-                    for (int u = 0; u < ns; ++u) if (s_slotb[u] == (uint32_t)(E * 64 + bpos)) sl = u;
-                    tab[bpos] = (uint16_t)(CODE_CAND | sl);
-                }
-            });
+            const uint32_t E = b >> 6;
+            const int gid = (int)(255 - E) + zi;
+            codes[15 - i] = (uint16_t)((zi << 9) | gid);
+            ri->g_exp[gid] = (uint16_t)(E ? E : 1);
+            ri->g_band[gid] = (uint16_t)s_label[zi];
         }
+    }
+    {
+        uint32_t w[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) w[i] = (uint32_t)codes[2 * i] | ((uint32_t)codes[2 * i + 1] << 16);
+        uint4* dst = (uint4*)(a.table + (size_t)row * NB1 + (NB1 - 16 - tid * 16));
+        dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
+        dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
     }
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Second read of the rows: band sums (SUMS) and candidate extraction.
-constexpr int P2_THREADS = 1024;
-constexpr int P2_WAVES = P2_THREADS / 64;
-constexpr int P2_CAP = 512;  // staged candidates per wave
+// The selection read: region counts, group sums (SUMS), zone candidates.
+constexpr int MAIN_THREADS = 1024;
+constexpr int MAIN_WAVES = MAIN_THREADS / 64;
+constexpr int ST_CAP = 256;  // staged candidates per wave
 
 template <int DT, bool VEC, bool SUMS>
-__global__ __launch_bounds__(P2_THREADS) void k_pass2(TopkArgs a) {
+__global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pass) {
     __shared__ uint16_t s_tab[NB1];
-    __shared__ unsigned long long s_acc[SUMS ? ACC_SLOTS : 1];
-    __shared__ uint32_t s_key[P2_WAVES][P2_CAP];
-    __shared__ uint32_t s_meta[P2_WAVES][P2_CAP];
-    __shared__ uint32_t s_cnt[P2_WAVES][SMAX];
-    __shared__ uint32_t s_base[P2_WAVES][SMAX];
-    __shared__ uint32_t s_slot_off[SMAX];
+    __shared__ unsigned long long s_sum[SUMS ? GMAX * REP : 1];
+    __shared__ uint32_t s_cnt[RMAX * REP];
+    __shared__ uint32_t s_sbits[MAIN_WAVES][ST_CAP];
+    __shared__ uint32_t s_smeta[MAIN_WAVES][ST_CAP];   // (index - chunk start) << 14 | zone << 8 | rank in the wave's zone batch
+    __shared__ uint32_t s_zcnt[MAIN_WAVES][ZMAX];
+    __shared__ uint32_t s_zbase[MAIN_WAVES][ZMAX];
+    __shared__ uint32_t s_zoff[ZMAX], s_zcap[ZMAX];
 
     const int row = blockIdx.y, tid = threadIdx.x;
-    const uint32_t lane = lane_id(), wave = tid >> 6;
     const RowInfo* ri = a.rinfo + row;
+    if (exact_pass && !ri->respec) return;
+    const uint32_t lane = lane_id(), wave = tid >> 6, l31 = lane & 31u;
     RowAcc* ra = a.racc + row;
-    const int nslots = ri->n_slots;
-    const int rep_shift = SUMS ? ri->rep_shift : 0;
-    const int G = SUMS ? ri->n_groups : 0;
+    const int nz = ri->n_zones;
     {
         const uint4* src = (const uint4*)(a.table + (size_t)row * NB1);
         uint4* dst = (uint4*)s_tab;
-        for (int i = tid; i < NB1 * 2 / 16; i += P2_THREADS) dst[i] = src[i];
+        for (int i = tid; i < NB1 * 2 / 16; i += MAIN_THREADS) dst[i] = src[i];
     }
-    if (SUMS) for (int i = tid; i < ACC_SLOTS; i += P2_THREADS) s_acc[i] = 0ull;
-    if (tid < SMAX) s_slot_off[tid] = tid < nslots ? ri->slot_off[tid] : 0u;
-    if (lane < SMAX) s_cnt[wave][lane] = 0;
+    if (SUMS) for (int i = tid; i < GMAX * REP; i += MAIN_THREADS) s_sum[i] = 0ull;
+    for (int i = tid; i < RMAX * REP; i += MAIN_THREADS) s_cnt[i] = 0u;
+    if (tid < ZMAX) {
+        s_zoff[tid] = tid < nz ? ri->zone_off[tid] : 0u;
+        s_zcap[tid] = tid < nz ? ri->zone_cap[tid] : 0u;
+    }
+    if (lane < ZMAX) s_zcnt[wave][lane] = 0;
     __syncthreads();
 
     const int64_t c0 = (int64_t)blockIdx.x * a.chunk;
     const int64_t c1 = c0 + a.chunk < a.d ? c0 + a.chunk : a.d;
     RowLoader<DT, VEC> ld(a.g, a.ld, a.d, row);
-    uint32_t* cand_row = a.cand + (size_t)row * (size_t)a.d;
-    const uint32_t rep_mask = (1u << rep_shift) - 1u;
-    uint32_t nst = 0;  // wave-uniform: staged candidates
+    uint32_t* cb = a.cand_bits + (size_t)row * (size_t)a.d;
+    uint32_t* ci = a.cand_idx + (size_t)row * (size_t)a.d;
+    uint32_t nst = 0;      // wave-uniform: staged candidates
+    uint32_t maxkey = 0;
+    bool dropped = false;
 
     auto flush = [&]() {
         wave_lds_sync();
-        if ((int)lane < nslots) {
-            uint32_t n = s_cnt[wave][lane];
+        if ((int)lane < nz) {
+            uint32_t n = s_zcnt[wave][lane];
             uint32_t base = 0;
-            if (n) base = atomicAdd(&ra->slot_fill[lane], n);
-            s_base[wave][lane] = s_slot_off[lane] + base;
-            s_cnt[wave][lane] = 0;
+            if (n) base = atomicAdd(&ra->zone_fill[lane], n);
+            s_zbase[wave][lane] = base;
+            s_zcnt[wave][lane] = 0;
         }
         wave_lds_sync();
         for (uint32_t i = lane; i < nst; i += 64) {
-            uint32_t meta = s_meta[wave][i];
-            uint32_t pos = s_base[wave][meta >> 24] + (meta & 0xFFFFFFu);
-            if ((int64_t)pos < a.d) cand_row[pos] = s_key[wave][i];
-            else atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
+            const uint32_t meta = s_smeta[wave][i];
+            const uint32_t z = (meta >> 8) & 63u;
+            const uint32_t pos = s_zbase[wave][z] + (meta & 255u);
+            if (pos < s_zcap[z]) {
+                const size_t at = (size_t)s_zoff[z] + pos;
+                cb[at] = s_sbits[wave][i];
+                ci[at] = (uint32_t)c0 + (meta >> 14);
+            } else {
+                dropped = true;
+            }
         }
         wave_lds_sync();
         nst = 0;
     };
 
-    // every lane of a wave runs the same number of iterations (lanes past the chunk end load nothing)
-    for (int64_t jw = c0 + (int64_t)wave * 256; jw < c1; jw += P2_THREADS * 4) {
-        const int64_t j = jw + (int64_t)lane * 4;
-        uint32_t b[4];
-        int nv = j < c1 ? ld.load4(j, b) : 0;
+    // one 64-element slot: element c of load q of every lane
+    auto slot = [&](uint32_t bits, bool valid, uint32_t rel) {
+        const uint32_t key = key_of_bits(bits);
+        const uint16_t code = s_tab[key >> B1_SHIFT];
+        const bool zone = valid && (code & CODE_ZONE);
+        if (valid && !(code & CODE_ZONE)) {
+            if (SUMS) atomicAdd(&s_sum[(uint32_t)(code & 511u) * REP + l31], (unsigned long long)sig_square(key));
+            atomicAdd(&s_cnt[(uint32_t)(code >> 9) * REP + l31], 1u);
+        }
+        maxkey = key > maxkey ? key : maxkey;
+        const uint64_t m = __ballot(zone);
+        if (m) {
+            if (nst > ST_CAP - 64) flush();
+            if (zone) {
+                const uint32_t z = code & 63u;
+                const uint32_t pos = nst + mbcnt(m);
+                const uint32_t lr = atomicAdd(&s_zcnt[wave][z], 1u);
+                s_sbits[wave][pos] = bits;
+                s_smeta[wave][pos] = (rel << 14) | (z << 8) | lr;
+            }
+            nst += (uint32_t)__popcll(m);
+        }
+    };
+
+    // a wave covers 1024 consecutive elements per step, the workgroup 16384
+    for (int64_t jw = c0 + (int64_t)wave * 1024; jw < c1; jw += MAIN_THREADS * 16) {
+        uint32_t b[4][4];
+        int nv[4];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            uint32_t key = key_of_bits(b[c]);
-            uint16_t code = c < nv ? s_tab[key >> B1_SHIFT] : CODE_IGNORE;
-            if (SUMS && code < CODE_IGNORE)
-                atomicAdd(&s_acc[((uint32_t)code << rep_shift) + (lane & rep_mask)], (unsigned long long)sig_square(key));
-            bool is_cand = (code & CODE_CAND) != 0;
-            uint64_t m = __ballot(is_cand);
-            if (m) {
-                if (is_cand) {
-                    uint32_t s = code & 0xFFu;
-                    uint32_t pos = nst + mbcnt(m);
-                    uint32_t lr = atomicAdd(&s_cnt[wave][s], 1u);
-                    s_key[wave][pos] = key;
-                    s_meta[wave][pos] = (s << 24) | lr;
-                }
-                nst += (uint32_t)__popcll(m);
+        for (int q = 0; q < 4; ++q) {
+            const int64_t j = jw + q * 256 + (int64_t)lane * 4;
+            nv[q] = j < c1 ? ld.load4(j, b[q]) : 0;
+            if (nv[q] < 4) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) if (c >= nv[q]) b[q][c] = 0u;
             }
         }
-        if (nst > P2_CAP - 256) flush();
+        const uint32_t rel0 = (uint32_t)(jw - c0) + lane * 4;
+        if (jw + 1024 <= c1) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) slot(b[q][c], true, rel0 + q * 256 + c);
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) slot(b[q][c], c < nv[q], rel0 + q * 256 + c);
+        }
     }
     flush();
+    if (__ballot(maxkey >= 0x7F800000u) && lane == 0) atomicOr(a.dev_status, MLMC_DEV_NONFINITE);
+    if (__ballot(dropped) && lane == 0) {
+        // a candidate list overflowed its estimated capacity: redo the row exactly (exact capacities cannot overflow)
+        if (ri->exact) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
+        else atomicOr((int32_t*)&a.rinfo[row].respec, 1);
+    }
+    __syncthreads();
     if (SUMS) {
-        __syncthreads();
-        if (tid < G) {
+        for (int g = tid; g < GMAX; g += MAIN_THREADS) {
             unsigned long long lo = 0, hi = 0;
-            const int R = 1 << rep_shift;
-            for (int r = 0; r < R; ++r) {
-                unsigned long long v = s_acc[(tid << rep_shift) + r];
+#pragma unroll 8
+            for (int r = 0; r < REP; ++r) {
+                const unsigned long long v = s_sum[g * REP + ((r + tid) & (REP - 1))];
                 lo += v & 0xFFFFFFFFull;
                 hi += v >> 32;
             }
-            if (lo) atomicAdd((unsigned long long*)&ra->gsum[tid][0], lo);
-            if (hi) atomicAdd((unsigned long long*)&ra->gsum[tid][1], hi);
+            if (lo) atomicAdd((unsigned long long*)&ra->gsum[g][0], lo);
+            if (hi) atomicAdd((unsigned long long*)&ra->gsum[g][1], hi);
         }
+    }
+    if (tid < RMAX) {
+        uint32_t n = 0;
+        for (int r = 0; r < REP; ++r) n += s_cnt[tid * REP + ((r + tid) & (REP - 1))];
+        a.chunk_cnt[((size_t)row * a.chunks_per_row + blockIdx.x) * RMAX + tid] = n;
+        if (n) atomicAdd(&ra->region_cnt[tid], n);
     }
 }
 
 // ---------------------------------------------------------------------------------------------------
-// One workgroup per (boundary bucket, row): resolve the remaining 17 key bits on the candidate list.
+// One workgroup per (zone, row): resolve every threshold of the zone on its candidate list.
 constexpr int FN_THREADS = 1024;
 
 // Descending search in a histogram held by one wave: lane l owns bins [BPL*l, BPL*l + BPL).  For the 1-based
@@ -440,138 +485,236 @@ __device__ __forceinline__ void wave_rank_search(const uint32_t* h, uint32_t r, 
 }
 
 template <bool SUMS>
-__global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a) {
-    __shared__ uint32_t hA[512];
-    __shared__ uint32_t hB[TMAX][256];
-    __shared__ unsigned long long pacc[SUMS ? TMAX + 1 : 1][64][2];
-    __shared__ int32_t s_n;
-    __shared__ int32_t s_t[TMAX];
-    __shared__ uint32_t s_res[TMAX], s_sb[TMAX], s_tau[TMAX], s_q[TMAX], s_eq[TMAX];
-    __shared__ int32_t s_sub[TMAX];
-    __shared__ uint8_t s_sub_of_sb[512];
+__global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pass) {
+    __shared__ uint32_t s_hist[TMAX][256];
+    __shared__ unsigned long long s_pacc[SUMS ? PIECE_CLASSES * REP : 1][2];
+    __shared__ int32_t s_n, s_ok, s_nsub, s_any, s_elo, s_ehi;
+    __shared__ int32_t s_t[TMAX], s_sub[TMAX];
+    __shared__ uint32_t s_res[TMAX], s_pfx[TMAX], s_tau[TMAX], s_q[TMAX], s_eq[TMAX], s_jx[TMAX];
+    __shared__ uint32_t s_subpfx[TMAX], s_subtau[TMAX];
 
-    const int s = blockIdx.x, row = blockIdx.y, tid = threadIdx.x;
+    const int z = blockIdx.x, row = blockIdx.y, tid = threadIdx.x;
     const uint32_t lane = lane_id(), wave = tid >> 6;
     RowInfo* ri = a.rinfo + row;
     RowAcc* ra = a.racc + row;
-    if (s >= ri->n_slots) return;
-    const uint32_t n = ri->slot_cnt[s];
-    const uint32_t bucket = ri->slot_bucket[s];
-    const uint32_t* list = a.cand + (size_t)row * (size_t)a.d + ri->slot_off[s];
+    if (exact_pass && !ri->respec) return;
+    if (!exact_pass && ri->respec) return;   // already refuted (candidate overflow): the row is redone anyway
+    if (z >= ri->n_zones) return;
+    const uint32_t n = ra->zone_fill[z];
+    const uint32_t* kb = a.cand_bits + (size_t)row * (size_t)a.d + ri->zone_off[z];
+    const uint32_t* kj = a.cand_idx + (size_t)row * (size_t)a.d + ri->zone_off[z];
     const int L = a.L;
+    const int fail_bit = ri->exact ? 1 : 0;   // what a refuted check means: 1 internal error, 0 redo the row
 
-    for (int i = tid; i < 512; i += FN_THREADS) { hA[i] = 0; s_sub_of_sb[i] = 0xFF; }
-    for (int i = tid; i < TMAX * 256; i += FN_THREADS) (&hB[0][0])[i] = 0;
-    if (SUMS) for (int i = tid; i < (TMAX + 1) * 64 * 2; i += FN_THREADS) (&pacc[0][0][0])[i] = 0ull;
+    auto fail = [&]() {   // called by one thread
+        if (fail_bit) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
+        else atomicOr((int32_t*)&ri->respec, 1);
+    };
+
     if (tid == 0) {
+        // elements strictly above the zone: regions 0..z and zones 0..z-1
+        int64_t above = 0;
+        for (int i = 0; i <= z; ++i) above += ra->region_cnt[i];
+        for (int i = 0; i < z; ++i) above += ra->zone_fill[i];
+        bool ok = n <= ri->zone_cap[z];
         int m = 0;
-        for (int t = 0; t <= L; ++t)
-            if (ri->thr_slot[t] == s) { s_t[m] = t; s_res[m] = ri->thr_resid[t]; ++m; }
+        for (int t = ri->zone_t0[z]; t <= ri->zone_t1[z] && t <= L; ++t) {
+            if (ri->thr_zone[t] != z) continue;
+            const int64_t r = a.k[t] - above;
+            if (r < 1 || r > (int64_t)n) ok = false;
+            s_t[m] = t;
+            s_res[m] = (uint32_t)(r > 0 ? r : 1);
+            s_pfx[m] = 0;
+            ++m;
+        }
+        if (z == ri->n_zones - 1) {   // the last zone also checks that nothing was lost
+            int64_t tot = above + n + ra->region_cnt[z + 1];
+            if (tot != a.d) ok = false;
+        }
+        if (!ok) fail();
         s_n = m;
-        if (ra->slot_fill[s] != n) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
+        s_ok = ok ? 1 : 0;
     }
     __syncthreads();
+    if (!s_ok) return;
     const int nthr = s_n;
 
-    // A: bits 16..8
-#pragma unroll 4
-    for (uint32_t i = tid; i < n; i += FN_THREADS) atomicAdd(&hA[(list[i] >> 8) & 511u], 1u);
-    __syncthreads();
-    if (wave == 0) {
-        for (int u = 0; u < nthr; ++u) {
-            int sb;
-            uint32_t rin, cnt;
-            wave_rank_search<8>(hA, s_res[u], sb, rin, cnt);
-            if (lane == 0) { s_sb[u] = (uint32_t)sb; s_res[u] = rin; }
-        }
-        wave_lds_sync();
-        if (lane == 0) {
-            int nsub = 0;
+    // ---- radix select on the keys: digits of 8, 8, 8, 7 bits from the top ----
+    for (int pass = 0; pass < 4; ++pass) {
+        const int shift = pass == 0 ? 23 : pass == 1 ? 15 : pass == 2 ? 7 : 0;
+        const uint32_t mask = pass == 3 ? 127u : 255u;
+        const int hb = pass == 3 ? 7 : shift + 8;   // unresolved low bits before this pass (31 for pass 0)
+        if (tid == 0) {
+            int ns = 0;
             for (int u = 0; u < nthr; ++u) {
-                if (u == 0 || s_sb[u] != s_sb[u - 1]) { s_sub_of_sb[s_sb[u]] = (uint8_t)nsub; ++nsub; }
-                s_sub[u] = nsub - 1;
+                if (u == 0 || s_pfx[u] != s_pfx[u - 1]) { s_subpfx[ns] = s_pfx[u]; ++ns; }
+                s_sub[u] = ns - 1;
+            }
+            s_nsub = ns;
+        }
+        for (int i = tid; i < TMAX * 256; i += FN_THREADS) (&s_hist[0][0])[i] = 0;
+        __syncthreads();
+        const int nsub = s_nsub;
+        if (pass == 0) {
+#pragma unroll 4
+            for (uint32_t i = tid; i < n; i += FN_THREADS) atomicAdd(&s_hist[0][(key_of_bits(kb[i]) >> 23) & 255u], 1u);
+        } else if (nsub == 1) {
+            const uint32_t pf = s_subpfx[0] >> hb;
+#pragma unroll 4
+            for (uint32_t i = tid; i < n; i += FN_THREADS) {
+                const uint32_t key = key_of_bits(kb[i]);
+                if ((key >> hb) == pf) atomicAdd(&s_hist[0][(key >> shift) & mask], 1u);
+            }
+        } else {
+#pragma unroll 2
+            for (uint32_t i = tid; i < n; i += FN_THREADS) {
+                const uint32_t key = key_of_bits(kb[i]);
+                const uint32_t kp = key >> hb;
+                for (int s = 0; s < nsub; ++s)
+                    if (kp == (s_subpfx[s] >> hb)) atomicAdd(&s_hist[s][(key >> shift) & mask], 1u);
             }
         }
-    }
-    __syncthreads();
-
-    // B: bits 7..0 of the keys in the thresholds' sub-bins
-#pragma unroll 4
-    for (uint32_t i = tid; i < n; i += FN_THREADS) {
-        uint32_t key = list[i];
-        uint32_t u = s_sub_of_sb[(key >> 8) & 511u];
-        if (u != 0xFF) atomicAdd(&hB[u][key & 255u], 1u);
-    }
-    __syncthreads();
-    for (int u = wave; u < nthr; u += FN_THREADS / 64) {
-        int lb;
-        uint32_t rin, cnt;
-        wave_rank_search<4>(hB[s_sub[u]], s_res[u], lb, rin, cnt);
-        if (lane == 0) {
-            uint32_t tau = (bucket << B1_SHIFT) | (s_sb[u] << 8) | (uint32_t)lb;
-            s_tau[u] = tau;
-            s_q[u] = rin;
-            s_eq[u] = cnt;
-            ri->thr_tau[s_t[u]] = tau;
-            ri->thr_q[s_t[u]] = rin;
-            if (rin > cnt || rin == 0) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
+        __syncthreads();
+        if (pass == 0 && wave == FN_THREADS / 64 - 1) {   // exponent fields present in the list (lane l: bins 4l..4l+3)
+            uint32_t lo = 256, hi = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (s_hist[0][4 * lane + i]) { lo = lo < 4 * lane + i ? lo : 4 * lane + i; hi = 4 * lane + i; }
+#pragma unroll
+            for (int o = 32; o >= 1; o >>= 1) {
+                const uint32_t l2 = __shfl_xor(lo, o, 64), h2 = __shfl_xor(hi, o, 64);
+                lo = l2 < lo ? l2 : lo;
+                hi = h2 > hi ? h2 : hi;
+            }
+            if (lane == 0) { s_elo = (int32_t)lo; s_ehi = (int32_t)hi; }
         }
+        for (int u = wave; u < nthr; u += FN_THREADS / 64) {
+            int bin;
+            uint32_t rin, cnt;
+            wave_rank_search<4>(s_hist[s_sub[u]], s_res[u], bin, rin, cnt);
+            if (lane == 0) {
+                s_pfx[u] |= (uint32_t)bin << shift;
+                s_res[u] = rin;
+                if (pass == 3) { s_tau[u] = s_pfx[u]; s_q[u] = rin; s_eq[u] = cnt; }
+            }
+        }
+        __syncthreads();
+    }
+    // ---- index cut among the entries equal to the threshold key: the q-th smallest index + 1 ----
+    if (tid < nthr) {
+        s_jx[tid] = JX_ALL;
+        s_pfx[tid] = 0;
+        s_res[tid] = s_eq[tid] - s_q[tid] + 1;   // the q-th smallest is the (eq - q + 1)-th largest
+        if (s_q[tid] < 1 || s_q[tid] > s_eq[tid]) fail();
+    }
+    if (tid == 0) {
+        int any = 0;
+        for (int u = 0; u < nthr; ++u) any |= s_q[u] < s_eq[u] ? 1 : 0;
+        s_any = any;
+    }
+    __syncthreads();
+    if (s_any) {
+        for (int pass = 0; pass < 4; ++pass) {
+            const int shift = 24 - 8 * pass;
+            const int hb = shift + 8;   // 32 for pass 0: no prefix yet
+            if (tid == 0) {
+                int ns = 0;
+                for (int u = 0; u < nthr; ++u) {
+                    if (s_q[u] >= s_eq[u]) { s_sub[u] = -1; continue; }
+                    int found = -1;
+                    for (int s = 0; s < ns; ++s)
+                        if (s_subtau[s] == s_tau[u] && s_subpfx[s] == s_pfx[u]) found = s;
+                    if (found < 0) { s_subtau[ns] = s_tau[u]; s_subpfx[ns] = s_pfx[u]; found = ns++; }
+                    s_sub[u] = found;
+                }
+                s_nsub = ns;
+            }
+            for (int i = tid; i < TMAX * 256; i += FN_THREADS) (&s_hist[0][0])[i] = 0;
+            __syncthreads();
+            const int nsub = s_nsub;
+#pragma unroll 2
+            for (uint32_t i = tid; i < n; i += FN_THREADS) {
+                const uint32_t key = key_of_bits(kb[i]);
+                for (int s = 0; s < nsub; ++s) {
+                    if (key != s_subtau[s]) continue;
+                    const uint32_t j = kj[i];
+                    if (pass == 0 || (j >> hb) == (s_subpfx[s] >> hb)) atomicAdd(&s_hist[s][(j >> shift) & 255u], 1u);
+                }
+            }
+            __syncthreads();
+            for (int u = wave; u < nthr; u += FN_THREADS / 64) {
+                if (s_sub[u] < 0) continue;
+                int bin;
+                uint32_t rin, cnt;
+                wave_rank_search<4>(s_hist[s_sub[u]], s_res[u], bin, rin, cnt);
+                if (lane == 0) {
+                    s_pfx[u] |= (uint32_t)bin << shift;
+                    s_res[u] = rin;
+                    if (pass == 3) s_jx[u] = s_pfx[u] + 1u;
+                }
+            }
+            __syncthreads();
+        }
+    }
+    if (tid < nthr) {
+        ri->thr_tau[s_t[tid]] = s_tau[tid];
+        ri->thr_jx[s_t[tid]] = s_jx[tid];
     }
     if (!SUMS) return;
-    __syncthreads();
 
-    // C: exact sums of the parts the thresholds cut the bucket into (piece j: keys strictly between
-    // threshold j-1 and threshold j; entries equal to a threshold key are added arithmetically)
-#pragma unroll 4
+    // ---- exact sums of the parts the thresholds cut the zone into: part j = inside the top k of thresholds
+    //      j.. but of none before; one accumulator class per (part, exponent) ----
+    const int Ehi = s_ehi ? s_ehi : 1;   // n >= 1 here: the list holds a threshold
+    const int Elo = s_elo ? s_elo : 1;
+    const int span = Ehi - Elo + 1;
+    const int nclass = (nthr + 1) * span;
+    if (nclass > PIECE_CLASSES) {
+        if (tid == 0) fail();
+        return;
+    }
+    for (int i = tid; i < PIECE_CLASSES * REP * 2; i += FN_THREADS) (&s_pacc[0][0])[i] = 0ull;
+    __syncthreads();
+    const uint32_t l31 = lane & 31u;
+#pragma unroll 2
     for (uint32_t i = tid; i < n; i += FN_THREADS) {
-        uint32_t key = list[i];
-        int j = 0;
-        bool eq = false;
+        const uint32_t key = key_of_bits(kb[i]);
+        const uint32_t j = kj[i];
+        int part = 0;
         for (int u = 0; u < nthr; ++u) {
-            uint32_t tau = s_tau[u];
-            j += tau > key ? 1 : 0;
-            eq |= tau == key;
+            const uint32_t tau = s_tau[u];
+            const bool inside = key > tau || (key == tau && j < s_jx[u]);
+            part += inside ? 0 : 1;
         }
-        if (!eq) {
-            unsigned long long sq = sig_square(key);
-            atomicAdd(&pacc[j][lane][0], sq & 0xFFFFFFFFull);
-            atomicAdd(&pacc[j][lane][1], sq >> 32);
-        }
+        const int E = (int)(key >> 23) ? (int)(key >> 23) : 1;
+        const int cls = part * span + (E - Elo);
+        const unsigned long long sq = sig_square(key);
+        atomicAdd(&s_pacc[cls * REP + l31][0], sq & 0xFFFFFFFFull);
+        atomicAdd(&s_pacc[cls * REP + l31][1], sq >> 32);
     }
     __syncthreads();
-    if (tid <= nthr) {
-        const int j = tid;
+    if (tid < nclass) {
         unsigned long long lo = 0, hi = 0;
-        for (int l = 0; l < 64; ++l) { lo += pacc[j][l][0]; hi += pacc[j][l][1]; }
+        for (int r = 0; r < REP; ++r) { lo += s_pacc[tid * REP + r][0]; hi += s_pacc[tid * REP + r][1]; }
         hi += lo >> 32;
         lo &= 0xFFFFFFFFull;
-        // entries equal to threshold key tau_u: q_u of them are within the top k_{t_u}
-        auto add_ties = [&](uint32_t tau, unsigned long long cnt) {
-            unsigned long long sq = sig_square(tau);
-            lo += cnt * (sq & 0xFFFFFFFFull);
-            hi += cnt * (sq >> 32);
-            hi += lo >> 32;
-            lo &= 0xFFFFFFFFull;
-        };
-        if (j < nthr) {
-            unsigned long long prevq = (j > 0 && s_tau[j - 1] == s_tau[j]) ? s_q[j - 1] : 0ull;
-            add_ties(s_tau[j], (unsigned long long)s_q[j] - prevq);
+        if (lo | hi) {
+            const int part = tid / span, e = Elo + tid % span;
+            const uint32_t at = atomicAdd(&ra->n_pieces, 1u);
+            if (at >= (uint32_t)PMAX) {
+                fail();
+            } else {
+                Piece* pc = &ra->pieces[at];
+                pc->exp = e;
+                pc->lo = lo;
+                pc->hi = hi;
+                pc->band_plus1 = (part < nthr ? s_t[part] : s_t[nthr - 1] + 1) + 1;
+            }
         }
-        if (j > 0 && (j == nthr || s_tau[j] != s_tau[j - 1]))
-            add_ties(s_tau[j - 1], (unsigned long long)s_eq[j - 1] - s_q[j - 1]);
-        const int pidx = s_t[0] + s + j;
-        if (pidx >= PMAX) { atomicOr(a.dev_status, MLMC_DEV_INTERNAL); return; }
-        Piece* pc = &ra->pieces[pidx];
-        uint32_t E = bucket >> 6;
-        pc->exp = (int32_t)(E ? E : 1u);
-        pc->lo = lo;
-        pc->hi = hi;
-        pc->band_plus1 = (j < nthr ? s_t[j] : s_t[nthr - 1] + 1) + 1;
     }
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Delta_l (Lemma 3.4) from the exact group and piece sums, then the adaptive draw.  One workgroup per row,
+// Delta_l (Lemma 3.4) from the exact group and part sums, then the adaptive draw.  One workgroup per row,
 // one thread per band; the 640-bit accumulators live in LDS.
 struct BigAcc {
     uint32_t* w;  // 20 words
@@ -631,28 +774,28 @@ __global__ __launch_bounds__(256) void k_norms(TopkArgs a) {
     const int row = blockIdx.x, tid = threadIdx.x;
     const RowInfo* ri = a.rinfo + row;
     const RowAcc* ra = a.racc + row;
-    const int G = ri->n_groups;
-    for (int g = tid; g < G; g += 256) {
+    for (int g = tid; g < GMAX; g += 256) {
         s_glo[g] = ra->gsum[g][0];
         s_ghi[g] = ra->gsum[g][1];
         s_gexp[g] = ri->g_exp[g];
         s_gband[g] = ri->g_band[g];
     }
-    for (int p = tid; p < PMAX; p += 256) s_pc[p] = ra->pieces[p];
+    const int np = ra->n_pieces < (uint32_t)PMAX ? (int)ra->n_pieces : PMAX;
+    for (int p = tid; p < np; p += 256) s_pc[p] = ra->pieces[p];
     __syncthreads();
     const int l = tid;
     if (l >= 1 && l <= a.L) {
         BigAcc acc;
         acc.w = s_big[l];
         acc.clear();
-        for (int g = 0; g < G; ++g) {
-            if (s_gband[g] == l) {
+        for (int g = 0; g < GMAX; ++g) {
+            if (s_gband[g] == l && (s_glo[g] | s_ghi[g])) {
                 int sh = 2 * ((int)s_gexp[g] - 1);
                 acc.add(s_glo[g], sh);
                 acc.add(s_ghi[g], sh + 32);
             }
         }
-        for (int p = 0; p < PMAX; ++p) {
+        for (int p = 0; p < np; ++p) {
             if (s_pc[p].band_plus1 == l + 1) {
                 int sh = 2 * (s_pc[p].exp - 1);
                 acc.add(s_pc[p].lo, sh);
@@ -688,232 +831,227 @@ __global__ __launch_bounds__(1024) void k_draw(DrawArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Compaction in one read.  A unit = CW waves x 1024 consecutive elements of one row.  Workgroups take units
-// from a ticket counter (rows interleaved, so every unit's predecessor in its row has an earlier ticket
-// and is already running); each unit publishes its counts (three tie counts, one output count) as
-// 64-bit descriptors and obtains its exclusive prefixes by decoupled look-back over its predecessors.
+// Membership tests of the message (Eq. (6)): base band = top k_0; drawn band = top k_l without top k_{l-1}.
 struct Thr3 {
-    uint32_t tau[3], q[3];
+    uint32_t tau[3], jx[3];
 };
 __device__ __forceinline__ Thr3 load_thr3(const RowInfo* ri) {
     Thr3 t;
     const int lev = ri->level;
     const int ts[3] = {0, lev - 1, lev};
 #pragma unroll
-    for (int i = 0; i < 3; ++i) { t.tau[i] = ri->thr_tau[ts[i]]; t.q[i] = ri->thr_q[ts[i]]; }
+    for (int i = 0; i < 3; ++i) { t.tau[i] = ri->thr_tau[ts[i]]; t.jx[i] = ri->thr_jx[ts[i]]; }
     return t;
 }
-
-constexpr unsigned long long DESC_AGG = 1ull << 62;   // value = this unit's own count
-constexpr unsigned long long DESC_PRE = 2ull << 62;   // value = inclusive prefix up to and including this unit
-constexpr unsigned long long DESC_VAL = 0xFFFFFFFFull;
-constexpr uint32_t LOOKBACK_SPIN_MAX = 1u << 22;      // bounded wait: about a second of polling
-
-__device__ __forceinline__ void desc_store(unsigned long long* p, unsigned long long v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ unsigned long long desc_load(const unsigned long long* p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+__device__ __forceinline__ bool inside_top(const Thr3& th, int i, uint32_t key, uint32_t j) {
+    return key > th.tau[i] || (key == th.tau[i] && j < th.jx[i]);
 }
 
-// Run by one whole wave.  drow: descriptors of this row, [units][4]; chain c.  Publishes the unit's count,
-// returns the sum of the counts of units 0..unit-1, then publishes the inclusive prefix.
-__device__ uint32_t lookback(unsigned long long* drow, int c, int64_t unit, uint32_t agg, int32_t* dev_status) {
-    const uint32_t lane = lane_id();
-    unsigned long long* mine = drow + unit * 4 + c;
-    if (unit == 0) {
-        if (lane == 0) desc_store(mine, DESC_PRE | agg);
-        return 0;
+// Entries of the message that come from zone candidates, counted per chunk.  blockIdx.x = 0, 1, 2 <-> the zone
+// of threshold 0, l-1, l (a zone shared by two of them is counted once).
+__global__ __launch_bounds__(1024) void k_emitcount(TopkArgs a) {
+    __shared__ uint32_t s_c[CHUNKS_MAX];
+    const int s = blockIdx.x, row = blockIdx.y, tid = threadIdx.x;
+    const RowInfo* ri = a.rinfo + row;
+    const int lev = ri->level;
+    const int ts[3] = {0, lev - 1, lev};
+    const int z = ri->thr_zone[ts[s]];
+    if (z < 0) return;
+    for (int i = 0; i < s; ++i)
+        if (ri->thr_zone[ts[i]] == z) return;
+    const uint32_t n = a.racc[row].zone_fill[z];
+    const uint32_t* kb = a.cand_bits + (size_t)row * (size_t)a.d + ri->zone_off[z];
+    const uint32_t* kj = a.cand_idx + (size_t)row * (size_t)a.d + ri->zone_off[z];
+    const Thr3 th = load_thr3(ri);
+    const int nc = a.chunks_per_row;
+    for (int i = tid; i < nc; i += 1024) s_c[i] = 0;
+    __syncthreads();
+    const uint32_t chunk = (uint32_t)a.chunk;
+#pragma unroll 2
+    for (uint32_t i = tid; i < n; i += 1024) {
+        const uint32_t key = key_of_bits(kb[i]), j = kj[i];
+        const bool in0 = inside_top(th, 0, key, j);
+        const bool emit = in0 || (inside_top(th, 2, key, j) && !inside_top(th, 1, key, j));
+        if (emit) atomicAdd(&s_c[j / chunk], 1u);
     }
-    if (lane == 0) desc_store(mine, DESC_AGG | agg);
-    uint32_t excl = 0;
-    int64_t pos = unit - 1;  // the window is units pos, pos-1, ..., pos-63 (lane 0 = nearest)
-    uint32_t spin = 0;
-    bool done = false;
-    while (!done) {
-        const int64_t u = pos - (int64_t)lane;
-        unsigned long long v = u >= 0 ? desc_load(drow + u * 4 + c) : DESC_PRE;
-        const uint32_t flag = (uint32_t)(v >> 62);
-        const uint64_t m_inv = __ballot(flag == 0);
-        const uint64_t m_pre = __ballot(flag == 2);
-        const int first_inv = m_inv ? (int)__builtin_ctzll(m_inv) : 64;
-        const int first_pre = m_pre ? (int)__builtin_ctzll(m_pre) : 64;
-        if (first_pre < first_inv) {          // a prefix is reachable through published counts
-            uint32_t part = (int)lane <= first_pre ? (uint32_t)(v & DESC_VAL) : 0u;
-            excl += wave_sum(part);
-            done = true;
-        } else if (first_inv == 64) {         // 64 published counts, no prefix yet: take them, look further back
-            excl += wave_sum((uint32_t)(v & DESC_VAL));
-            pos -= 64;
-        } else {                              // a predecessor has not published yet: poll again
-            __builtin_amdgcn_s_sleep(8);
-            if (++spin >= LOOKBACK_SPIN_MAX) {
-                if (lane == 0) atomicOr(dev_status, MLMC_DEV_INTERNAL);
-                done = true;
+    __syncthreads();
+    uint32_t* ce = a.chunk_emit + (size_t)row * nc;
+    for (int i = tid; i < nc; i += 1024) {
+        uint32_t v = s_c[i];
+        if (v) atomicAdd(&ce[i], v);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// The message read.  One workgroup per (chunk, row); a wave covers 1024 consecutive elements per step.
+constexpr int WR_THREADS = 512;
+constexpr int WR_WAVES = WR_THREADS / 64;
+constexpr int WR_STEP = WR_WAVES * 1024;
+
+template <int DT, bool VEC>
+__global__ __launch_bounds__(WR_THREADS) void k_write(TopkArgs a) {
+    __shared__ unsigned long long s_red[WR_WAVES];
+    __shared__ int64_t s_rowstart, s_rownnz;
+    __shared__ uint32_t s_base;
+    __shared__ uint32_t s_wemit[2][WR_WAVES];
+    const int row = blockIdx.y, chunk_id = blockIdx.x, tid = threadIdx.x;
+    const uint32_t lane = lane_id(), wave = tid >> 6;
+    const RowInfo* ri = a.rinfo + row;
+    const int lev = ri->level;
+    const int nzn = ri->n_zones;
+    const int nc = a.chunks_per_row;
+    const int64_t nt = a.ntiles;
+
+    // start of this row's message: rows before it hold k_0 + k_l - k_{l-1} entries each
+    {
+        unsigned long long part = 0;
+        for (int i = tid; i < row; i += WR_THREADS) {
+            const int li = a.rinfo[i].level;
+            part += (unsigned long long)(a.k[0] + a.k[li] - a.k[li - 1]);
+        }
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) part += __shfl_xor(part, o, 64);
+        if (lane == 0) s_red[wave] = part;
+        __syncthreads();
+        if (tid == 0) {
+            unsigned long long t = 0;
+            for (int w = 0; w < WR_WAVES; ++w) t += s_red[w];
+            s_rowstart = (int64_t)t;
+            s_rownnz = a.k[0] + a.k[lev] - a.k[lev - 1];
+        }
+        __syncthreads();
+    }
+    // entries of this row before this chunk: regions of band 0 and band l, plus the zone entries
+    int r0 = -1, rl = -1;
+    for (int r = 0; r <= nzn; ++r) {
+        const int lab = ri->region_label[r];
+        if (lab == 0) r0 = r;
+        if (lab == lev) rl = r;
+    }
+    {
+        unsigned long long part = 0;
+        const uint32_t* cc = a.chunk_cnt + (size_t)row * nc * RMAX;
+        const uint32_t* ce = a.chunk_emit + (size_t)row * nc;
+        for (int c = tid; c < chunk_id; c += WR_THREADS) {
+            uint32_t v = ce[c];
+            if (r0 >= 0) v += cc[(size_t)c * RMAX + r0];
+            if (rl >= 0) v += cc[(size_t)c * RMAX + rl];
+            part += v;
+        }
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) part += __shfl_xor(part, o, 64);
+        if (lane == 0) s_red[wave] = part;
+        __syncthreads();
+        if (tid == 0) {
+            unsigned long long t = 0;
+            for (int w = 0; w < WR_WAVES; ++w) t += s_red[w];
+            s_base = (uint32_t)t;
+        }
+        __syncthreads();
+    }
+    const int64_t rowstart = s_rowstart;
+    if (chunk_id == 0) {
+        if (tid == 0) {
+            a.row_off[row] = rowstart;
+            if (row == a.M - 1) {
+                a.row_off[a.M] = rowstart + s_rownnz;
+                if (rowstart + s_rownnz > a.capacity) atomicOr(a.dev_status, MLMC_DEV_CAPACITY);
             }
         }
     }
-    if (lane == 0) desc_store(mine, DESC_PRE | (unsigned long long)(excl + agg));
-    return excl;
-}
+    const Thr3 th = load_thr3(ri);
+    const float w = ri->weight;
+    RowLoader<DT, VEC> ld(a.g, a.ld, a.d, row);
+    const int64_t c0 = (int64_t)chunk_id * a.chunk;
+    const int64_t c1 = c0 + a.chunk < a.d ? c0 + a.chunk : a.d;
+    uint32_t run = s_base;   // entries of this row before the current step
+    uint32_t par = 0;
 
-template <int DT, bool VEC, int CW>
-__global__ __launch_bounds__(CW * 64) void k_compact(TopkArgs a) {
-    constexpr int NT = CW * 64;
-    constexpr int UNIT = CW * 1024;
-    __shared__ int64_t s_rowoff[MLMC_MAX_WORKERS + 1];
-    __shared__ uint32_t s_ticket;
-    __shared__ uint32_t s_wtie[3][CW];
-    __shared__ uint32_t s_wemit[CW];
-    __shared__ uint32_t s_pre[4];
-    const int tid = threadIdx.x;
-    const uint32_t lane = lane_id(), wave = tid >> 6;
-    const int64_t nt = a.ntiles;
-
-    // row offsets of the messages from the drawn levels (every workgroup keeps a copy; workgroup 0 writes them)
-    for (int i = tid; i < a.M; i += NT) {
-        const int lev = a.rinfo[i].level;
-        s_rowoff[i + 1] = a.k[0] + a.k[lev] - a.k[lev - 1];
-    }
-    __syncthreads();
-    if (tid == 0) {
-        int64_t run = 0;
-        s_rowoff[0] = 0;
-        for (int i = 0; i < a.M; ++i) { int64_t n = s_rowoff[i + 1]; s_rowoff[i] = run; run += n; }
-        s_rowoff[a.M] = run;
-        if (blockIdx.x == 0 && run > a.capacity) atomicOr(a.dev_status, MLMC_DEV_CAPACITY);
-    }
-    __syncthreads();
-    if (blockIdx.x == 0)
-        for (int i = tid; i <= a.M; i += NT) a.row_off[i] = s_rowoff[i];
-
-    const uint32_t total_units = (uint32_t)(a.units_per_row * a.M);
-    while (true) {
-        if (tid == 0) s_ticket = atomicAdd(a.ticket, 1u);
-        __syncthreads();
-        const uint32_t ticket = s_ticket;
-        if (ticket >= total_units) break;
-        const int row = (int)(ticket % (uint32_t)a.M);
-        const int64_t unit = ticket / (uint32_t)a.M;
-        const RowInfo* ri = a.rinfo + row;
-        const Thr3 th = load_thr3(ri);
-        const float w = ri->weight;
-        RowLoader<DT, VEC> ld(a.g, a.ld, a.d, row);
-        const int64_t wbase = unit * UNIT + (int64_t)wave * 1024;  // this wave's 1024 elements
-
-        uint32_t bits[16];
-        uint32_t valid = 0;
+    auto load_step = [&](int64_t sb, uint32_t (&bits)[16], uint32_t& valid) {
+        const int64_t wbase = sb + (int64_t)wave * 1024;
+        valid = 0;
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
             uint32_t b[4];
-            int nv = ld.load4(wbase + it * 256 + lane * 4, b);
+            const int64_t j = wbase + it * 256 + lane * 4;
+            const int nv = j < c1 ? ld.load4(j, b) : 0;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 bits[it * 4 + c] = b[c];
                 if (c < nv) valid |= 1u << (it * 4 + c);
             }
         }
-        uint32_t above[3] = {0, 0, 0}, equal[3] = {0, 0, 0};
+    };
+
+    uint32_t bitsA[16], bitsB[16];
+    uint32_t validA = 0, validB = 0;
+    if (c0 < c1) load_step(c0, bitsA, validA);
+    for (int64_t sb = c0; sb < c1; sb += WR_STEP) {
+        if (sb + WR_STEP < c1) load_step(sb + WR_STEP, bitsB, validB);
+        const int64_t wbase = sb + (int64_t)wave * 1024;
+        uint32_t in0 = 0, emit = 0;
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-            uint32_t key = key_of_bits(bits[e]);
-#pragma unroll
-            for (int k = 0; k < 3; ++k) {
-                above[k] |= (key > th.tau[k] ? 1u : 0u) << e;
-                equal[k] |= (key == th.tau[k] ? 1u : 0u) << e;
-            }
+            const uint32_t key = key_of_bits(bitsA[e]);
+            const uint32_t j = (uint32_t)wbase + (uint32_t)(e >> 2) * 256u + lane * 4u + (uint32_t)(e & 3);
+            const bool i0 = inside_top(th, 0, key, j);
+            const bool em = i0 || (inside_top(th, 2, key, j) && !inside_top(th, 1, key, j));
+            in0 |= (i0 ? 1u : 0u) << e;
+            emit |= (em ? 1u : 0u) << e;
         }
-#pragma unroll
-        for (int k = 0; k < 3; ++k) { above[k] &= valid; equal[k] &= valid; }
-        uint32_t in[3] = {above[0], above[1], above[2]};
-        {
-            uint32_t t0 = wave_sum(__popc(equal[0])), t1 = wave_sum(__popc(equal[1])), t2 = wave_sum(__popc(equal[2]));
-            uint32_t e0 = wave_sum(__popc(in[0] | (in[2] & ~in[1])));  // output count if the unit has no ties
-            if (lane == 0) { s_wtie[0][wave] = t0; s_wtie[1][wave] = t1; s_wtie[2][wave] = t2; s_wemit[wave] = e0; }
-        }
+        in0 &= validA;
+        emit &= validA;
+        const uint32_t wcount = wave_sum(__popc(emit));
+        if (lane == 0) s_wemit[par][wave] = wcount;
         __syncthreads();
-        uint32_t ut[3];
+        uint32_t wave_pre = run, step_total = 0;
 #pragma unroll
-        for (int k = 0; k < 3; ++k) ut[k] = wave_sum(lane < (uint32_t)CW ? s_wtie[k][lane] : 0u);
-        const bool any_tie = (ut[0] | ut[1] | ut[2]) != 0;  // uniform over the workgroup
-        unsigned long long* drow = a.desc + (size_t)row * (size_t)a.units_per_row * 4;
-        if (wave < 3) {
-            uint32_t ex = lookback(drow, (int)wave, unit, ut[wave], a.dev_status);
-            if (lane == 0) s_pre[wave] = ex;
-        } else if (wave == 3 && !any_tie) {
-            uint32_t agg = wave_sum(lane < (uint32_t)CW ? s_wemit[lane] : 0u);
-            uint32_t ex = lookback(drow, 3, unit, agg, a.dev_status);
-            if (lane == 0) s_pre[3] = ex;
+        for (int w2 = 0; w2 < WR_WAVES; ++w2) {
+            const uint32_t v = s_wemit[par][w2];
+            if ((uint32_t)w2 < wave) wave_pre += v;
+            step_total += v;
         }
-        __syncthreads();
-        if (any_tie) {
-            // rank the entries equal to a threshold key in index order; the first q_k of the row are inside
-#pragma unroll
-            for (int k = 0; k < 3; ++k) {
-                if (ut[k] == 0) continue;
-                uint64_t r0 = s_pre[k];
-                for (uint32_t w2 = 0; w2 < wave; ++w2) r0 += s_wtie[k][w2];
-                const uint64_t q = th.q[k];
-#pragma unroll
-                for (int it = 0; it < 4; ++it) {
-                    uint32_t tot;
-                    uint32_t ex = wave_excl_small(__popc((equal[k] >> (it * 4)) & 0xFu), tot);
-                    uint64_t r = r0 + ex;
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) {
-                        const int e = it * 4 + c;
-                        if ((equal[k] >> e) & 1u) {
-                            if (r < q) in[k] |= 1u << e;
-                            ++r;
-                        }
-                    }
-                    r0 += tot;
-                }
-            }
-            uint32_t e1 = wave_sum(__popc(in[0] | (in[2] & ~in[1])));
-            __syncthreads();  // every wave has read the tentative s_wemit users (wave 3 did not use it)
-            if (lane == 0) s_wemit[wave] = e1;
-            __syncthreads();
-            if (wave == 3) {
-                uint32_t agg = wave_sum(lane < (uint32_t)CW ? s_wemit[lane] : 0u);
-                uint32_t ex = lookback(drow, 3, unit, agg, a.dev_status);
-                if (lane == 0) s_pre[3] = ex;
-            }
-            __syncthreads();
-        }
-        const uint32_t emit = in[0] | (in[2] & ~in[1]);
-        uint32_t wave_pre = s_pre[3];  // entries of this row before this wave's elements
-        for (uint32_t w2 = 0; w2 < wave; ++w2) wave_pre += s_wemit[w2];
-        if ((wave & 3u) == 0 && lane == 0) {
-            const int64_t tile = unit * (UNIT / TILE) + (wave >> 2);
+        if ((wave & 3u) == 0 && lane == 0 && wbase < c1) {
+            const int64_t tile = wbase / TILE;
             if (tile < nt) a.tile_off[(size_t)row * (nt + 1) + tile] = wave_pre;
         }
-        if (unit == a.units_per_row - 1 && wave == CW - 1 && lane == 0) {
-            const uint32_t total = wave_pre + s_wemit[wave];
-            a.tile_off[(size_t)row * (nt + 1) + nt] = total;
-            if ((int64_t)total != s_rowoff[row + 1] - s_rowoff[row]) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
-        }
-        int64_t pos0 = s_rowoff[row] + wave_pre;
+        int64_t pos0 = rowstart + wave_pre;
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
             uint32_t tot;
-            uint32_t ex = wave_excl_small(__popc((emit >> (it * 4)) & 0xFu), tot);
+            const uint32_t ex = wave_excl_small(__popc((emit >> (it * 4)) & 0xFu), tot);
             int64_t pos = pos0 + ex;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 const int e = it * 4 + c;
                 if ((emit >> e) & 1u) {
                     if (pos < a.capacity) {
-                        float v = __uint_as_float(bits[e]);
+                        const float v = __uint_as_float(bitsA[e]);
                         a.idx[pos] = (uint32_t)(wbase + it * 256 + lane * 4 + c);
-                        a.val[pos] = ((in[0] >> e) & 1u) ? v : __fmul_rn(v, w);
+                        a.val[pos] = ((in0 >> e) & 1u) ? v : __fmul_rn(v, w);
                     }
                     ++pos;
                 }
             }
             pos0 += tot;
         }
-        __syncthreads();  // LDS reuse by the next unit
+        run += step_total;
+        par ^= 1u;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) bitsA[e] = bitsB[e];
+        validA = validB;
+    }
+    // consistency: the chunk ends where the per-chunk counts say the next one starts
+    if (tid == 0) {
+        const uint32_t* cc = a.chunk_cnt + (size_t)row * nc * RMAX + (size_t)chunk_id * RMAX;
+        uint32_t expect = s_base + a.chunk_emit[(size_t)row * nc + chunk_id];
+        if (r0 >= 0) expect += cc[r0];
+        if (rl >= 0) expect += cc[rl];
+        if (expect != run) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
+        if (chunk_id == nc - 1) {
+            a.tile_off[(size_t)row * (nt + 1) + nt] = run;
+            if ((int64_t)run != s_rownnz) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
+        }
     }
 }
 
@@ -921,28 +1059,32 @@ __global__ __launch_bounds__(CW * 64) void k_compact(TopkArgs a) {
 // host-side launchers
 template <int DT, bool VEC>
 static mlmc_status launch_select(const mlmc_plan_t* pl, const TopkArgs& a, bool sums, hipStream_t st) {
-    dim3 grid(pl->chunks_per_row, pl->M);
-    MLMC_LAUNCH(K_HIST1, st, k_hist1<DT, VEC><<<grid, 512, 0, st>>>(a));
-    MLMC_LAUNCH(K_SCAN1, st, k_scan1<<<pl->M, 1024, 0, st>>>(a));
-    if (sums) MLMC_LAUNCH(K_PASS2, st, k_pass2<DT, VEC, true><<<grid, P2_THREADS, 0, st>>>(a));
-    else MLMC_LAUNCH(K_PASS2, st, k_pass2<DT, VEC, false><<<grid, P2_THREADS, 0, st>>>(a));
-    dim3 fgrid(pl->L + 1, pl->M);
-    if (sums) MLMC_LAUNCH(K_FINISH, st, k_finish<true><<<fgrid, FN_THREADS, 0, st>>>(a));
-    else MLMC_LAUNCH(K_FINISH, st, k_finish<false><<<fgrid, FN_THREADS, 0, st>>>(a));
+    const dim3 mgrid(pl->chunks_per_row, pl->M);
+    const dim3 fgrid(pl->L + 1, pl->M);
+    const int rounds = pl->sample_shift > 0 ? 2 : 1;   // second round: rows whose sampled zones were refuted
+    for (int exact_pass = 0; exact_pass < rounds; ++exact_pass) {
+        // histogram workgroups per row: enough to spread the row, few enough that the 64 KB flushes stay cheap
+        const int64_t nblk = (pl->d + 1023) / 1024;
+        const int64_t ns = exact_pass ? nblk : ((nblk >> pl->sample_shift) > 0 ? (nblk >> pl->sample_shift) : 1);
+        int64_t hw = ns / 32 > 0 ? ns / 32 : 1;
+        const int64_t hcap = 2048 / pl->M > 0 ? 2048 / pl->M : 1;
+        if (hw > hcap) hw = hcap;
+        const dim3 hgrid((unsigned)hw, pl->M);
+        MLMC_LAUNCH(K_HIST, st, k_hist<DT, VEC><<<hgrid, HIST_THREADS, 0, st>>>(a, exact_pass));
+        MLMC_LAUNCH(K_SCAN, st, k_scan<<<pl->M, 1024, 0, st>>>(a, exact_pass));
+        if (sums) MLMC_LAUNCH(K_MAIN, st, k_main<DT, VEC, true><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
+        else MLMC_LAUNCH(K_MAIN, st, k_main<DT, VEC, false><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
+        if (sums) MLMC_LAUNCH(K_FINISH, st, k_finish<true><<<fgrid, FN_THREADS, 0, st>>>(a, exact_pass));
+        else MLMC_LAUNCH(K_FINISH, st, k_finish<false><<<fgrid, FN_THREADS, 0, st>>>(a, exact_pass));
+    }
     if (sums) MLMC_LAUNCH(K_NORMS, st, k_norms<<<pl->M, 256, 0, st>>>(a));
     return MLMC_OK;
 }
 
 template <int DT, bool VEC>
 static mlmc_status launch_compact(const mlmc_plan_t* pl, const TopkArgs& a, hipStream_t st) {
-    const int64_t units = pl->units_per_row * pl->M;
-    if (pl->cwaves == 8) {
-        int grid = (int)(units < 1024 ? units : 1024);
-        MLMC_LAUNCH(K_COMPACT, st, k_compact<DT, VEC, 8><<<grid, 512, 0, st>>>(a));
-    } else {
-        int grid = (int)(units < 512 ? units : 512);
-        MLMC_LAUNCH(K_COMPACT, st, k_compact<DT, VEC, 16><<<grid, 1024, 0, st>>>(a));
-    }
+    MLMC_LAUNCH(K_EMITCOUNT, st, k_emitcount<<<dim3(3, pl->M), 1024, 0, st>>>(a));
+    MLMC_LAUNCH(K_WRITE, st, k_write<DT, VEC><<<dim3(pl->chunks_per_row, pl->M), WR_THREADS, 0, st>>>(a));
     return MLMC_OK;
 }
 

@@ -88,7 +88,42 @@ def test_adaptive_norms_and_compress(name, d, M):
     check_topk_against_oracle(plan, G, 42, 4, msg3, adaptive=True)
 
 
-def test_adversarial_rows_ties_zeros_denormals():
+@pytest.mark.parametrize("shift", [1, 3, 6])
+@pytest.mark.parametrize("name,d,M", [("resnet50_adaptive_topk", 9 * 65536 + 999, 3), ("tiny_topk", 150_000, 2),
+                                       ("bert_adaptive_topk_bf16", 6 * 65536 + 4096 + 5, 2)])
+def test_sampled_threshold_search_gives_the_same_message(name, d, M, shift):
+    """Thresholds located from a histogram of one block in 2^shift, proven by exact counts (or redone exactly when
+    the sample was too thin to bracket them): the message must not depend on the sampling."""
+    w = W.scaled(W.WORKLOADS[name], d=d, M=M)
+    G = W.generate(w)
+    g = to_device(G)
+    redone = set()
+    for pf in (None, O.geometric_p(w.L)):
+        plan = _plan_for(w, pf)
+        plan.set_sampling(shift)
+        if pf is None:
+            print(f"{name} sampled shift={shift} norms d={d}", flush=True)
+            norms = P.mlmc_level_norms(plan, g).cpu().numpy()
+            assert plan.status() == 0
+            for i in range(M):
+                want, _ = O.level_norms_row(G[i], w.ladder)
+                assert np.array_equal(norms[i].view(np.uint64), np.array(want, dtype=np.float64).view(np.uint64)), (i, norms[i], want)
+        for step in range(5):
+            print(f"{name} sampled shift={shift} adaptive={pf is None} d={d} step={step}", flush=True)
+            msg = P.mlmc_compress_topk(plan, g, seed=11, step=step)
+            want = check_topk_against_oracle(plan, G, 11, step, msg, adaptive=pf is None)
+            assert plan.status() == 0
+            redone.add(bool(plan.status(informational=True) & P.MLMC_DEV_REDONE))
+            out = P.mlmc_aggregate(plan, msg, 0.5)
+            torch.cuda.synchronize()
+            assert np.array_equal(out.cpu().numpy().view(np.uint32), O.aggregate_sparse(want, w.d, 0.5).view(np.uint32))
+    print(f"{name} shift={shift}: exact redo seen {sorted(redone)}", flush=True)
+    if shift <= 3:
+        assert redone == {False}    # an eighth of the blocks is plenty: the zones must hold
+
+
+@pytest.mark.parametrize("shift", [0, 2])
+def test_adversarial_rows_ties_zeros_denormals(shift):
     d = 3 * 4096 + 517
     rows = W.adversarial_rows(d)
     G = np.stack(rows)
@@ -97,12 +132,14 @@ def test_adversarial_rows_ties_zeros_denormals():
     L = len(ladder) - 1
     g = to_device(G)
     plan_a = P.Plan(P.MLMC_TOPK, M, d, P.MLMC_F32, ladder, None)
+    plan_a.set_sampling(shift)
     print("adversarial norms", flush=True)
     norms = P.mlmc_level_norms(plan_a, g).cpu().numpy()
     for i in range(M):
         want, _ = O.level_norms_row(G[i], ladder)
         assert np.array_equal(norms[i].view(np.uint64), np.array(want).view(np.uint64)), (i, norms[i], want)
     plan_f = P.Plan(P.MLMC_TOPK, M, d, P.MLMC_F32, ladder, O.geometric_p(L))
+    plan_f.set_sampling(shift)
     for step in range(10):
         print(f"adversarial step={step}", flush=True)
         msg = P.mlmc_compress_topk(plan_f, g, seed=9, step=step)
