@@ -136,6 +136,7 @@ def main():
         step(args.warmup + i)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    redone = bool(plan.status(informational=True) & P.MLMC_DEV_REDONE)   # of the last step
     ms_per_step = dt * 1e3 / args.steps
     assert plan.status() == 0, f"device status {plan.status()}"
 
@@ -197,6 +198,7 @@ def main():
         "hbm_peak_frac_input": round(value / HBM_PEAK_GBPS, 4),
         "hbm_peak_frac_algorithmic": round(step_alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
         "ms_per_step_with_events": round(dt_ev * 1e3 / args.steps, 4),
+        "exact_redo_in_last_step": redone,
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
                      "avg_us": round(dom_avg_s * 1e6, 2), "algorithmic_bytes_per_launch": int(dom_bytes)},

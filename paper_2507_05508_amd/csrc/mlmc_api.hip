@@ -24,7 +24,7 @@ static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // ---- per-kernel HIP-event timing (off by default; not thread safe) ---------------------------------
 bool g_prof_on = false;
 static const char* const k_names[K_NUM] = {
-    "k_zero", "k_hist", "k_scan", "k_main", "k_finish", "k_norms", "k_draw", "k_emitcount", "k_write",
+    "k_zero", "k_hist", "k_scan", "k_main", "k_finish", "redo_pass", "k_norms", "k_draw", "k_write",
     "k_bits_max", "k_bits_extract", "k_agg_bits", "k_tileoff", "k_agg_sparse"};
 struct ProfPair { int id; hipEvent_t e0, e1; };
 static std::vector<ProfPair> g_pending;
@@ -85,10 +85,10 @@ static void fill_topk_args(const mlmc_plan_t* pl, TopkArgs& a, const void* g, in
     a.racc = (RowAcc*)(w + pl->off_racc);
     a.hist = (uint32_t*)(w + pl->off_hist);
     a.hist2 = (uint32_t*)(w + pl->off_hist2);
-    a.chunk_emit = (uint32_t*)(w + pl->off_chunk_emit);
     a.rinfo = (RowInfo*)(w + pl->off_rinfo);
     a.table = (uint16_t*)(w + pl->off_table);
     a.chunk_cnt = (uint32_t*)(w + pl->off_chunk_cnt);
+    a.chunk_zcnt = (uint32_t*)(w + pl->off_chunk_zcnt);
     a.tile_off = (uint32_t*)(w + pl->off_tileoff);
     a.norms = (double*)(w + pl->off_norms);
     a.cand_bits = (uint32_t*)(w + pl->off_cand_bits);
@@ -221,8 +221,6 @@ mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dty
         off = align_up(off + sizeof(uint32_t) * NB1 * (size_t)M, 256);
         pl->off_hist2 = off;
         off = align_up(off + sizeof(uint32_t) * NB1 * (size_t)M, 256);
-        pl->off_chunk_emit = off;
-        off = align_up(off + sizeof(uint32_t) * (size_t)pl->chunks_per_row * M, 256);
     }
     pl->zero_bytes = off;
     pl->off_rinfo = off;
@@ -232,6 +230,8 @@ mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dty
         off = align_up(off + sizeof(uint16_t) * NB1 * (size_t)M, 256);
         pl->off_chunk_cnt = off;
         off = align_up(off + sizeof(uint32_t) * RMAX * (size_t)pl->chunks_per_row * M, 256);
+        pl->off_chunk_zcnt = off;
+        off = align_up(off + sizeof(uint32_t) * ZPMAX * (size_t)pl->chunks_per_row * M, 256);
         pl->off_tileoff = off;
         off = align_up(off + sizeof(uint32_t) * (size_t)(pl->ntiles + 1) * M, 256);
         pl->off_norms = off;

@@ -182,8 +182,13 @@ __global__ __launch_bounds__(256) void k_agg_sparse(AggSparseArgs a) {
     for (int i = threadIdx.x; i < TILE; i += 256) s_acc[i] = 0.0f;
     for (int r = threadIdx.x; r < a.M; r += 256) {
         const uint32_t* to = a.tile_off + (size_t)r * (a.ntiles + 1);
-        s_beg[r] = a.row_off[r] + to[tile];
-        s_len[r] = to[tile + 1] - to[tile];
+        // a tile holds at most TILE entries of a row and they lie inside the row's message: an offset table that
+        // says otherwise (a failed compress call, a caller's own table) must not steer reads out of bounds
+        const int64_t beg = a.row_off[r] + to[tile];
+        uint32_t len = to[tile + 1] - to[tile];
+        if (to[tile + 1] < to[tile] || len > (uint32_t)TILE || beg < a.row_off[r] || beg + len > a.row_off[r + 1]) len = 0;
+        s_beg[r] = beg;
+        s_len[r] = len;
     }
     __syncthreads();
     for (int r = 0; r < a.M; ++r) {

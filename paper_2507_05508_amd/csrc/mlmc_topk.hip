@@ -16,7 +16,6 @@
 //                histogram (k_hist / k_scan / k_main / k_finish once more, for flagged rows only).
 //   k_norms      big-integer accumulation of group and part sums -> correctly rounded fp64 S_l -> Delta_l
 //                (Lemma 3.4), then the adaptive level draw (Alg. 3); with known p the draw is done in k_scan
-//   k_emitcount  message entries that come from the zones of thresholds 0, l-1, l, per chunk
 //   k_write      second read: index-ordered compaction of base band + drawn band (Eq. (6)); a workgroup owns a
 //                chunk whose output offset follows from the per-chunk counts, so no look-back is needed
 #include "mlmc_device.h"
@@ -311,6 +310,7 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
     __shared__ uint32_t s_smeta[MAIN_WAVES][ST_CAP];   // (index - chunk start) << 14 | zone << 8 | rank in the wave's zone batch
     __shared__ uint32_t s_zcnt[MAIN_WAVES][ZMAX];
     __shared__ uint32_t s_zbase[MAIN_WAVES][ZMAX];
+    __shared__ uint32_t s_zmax[MAIN_WAVES][ZMAX], s_zmininv[MAIN_WAVES][ZMAX];
     __shared__ uint32_t s_zoff[ZMAX], s_zcap[ZMAX];
 
     const int row = blockIdx.y, tid = threadIdx.x;
@@ -330,7 +330,7 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
         s_zoff[tid] = tid < nz ? ri->zone_off[tid] : 0u;
         s_zcap[tid] = tid < nz ? ri->zone_cap[tid] : 0u;
     }
-    if (lane < ZMAX) s_zcnt[wave][lane] = 0;
+    if (lane < ZMAX) { s_zcnt[wave][lane] = 0; s_zmax[wave][lane] = 0; s_zmininv[wave][lane] = 0; }
     __syncthreads();
 
     const int64_t c0 = (int64_t)blockIdx.x * a.chunk;
@@ -342,17 +342,23 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
     uint32_t maxkey = 0;
     bool dropped = false;
 
+    // staged candidates of this wave -> the zones' lists (one global counter update per zone)
     auto flush = [&]() {
         wave_lds_sync();
         if ((int)lane < nz) {
             uint32_t n = s_zcnt[wave][lane];
             uint32_t base = 0;
-            if (n) base = atomicAdd(&ra->zone_fill[lane], n);
+            if (n) {
+                base = atomicAdd(&ra->zone_fill[lane], n);
+                atomicMax(&ra->zone_kmax[lane], s_zmax[wave][lane]);
+                atomicMax(&ra->zone_kmin_inv[lane], s_zmininv[wave][lane]);
+            }
             s_zbase[wave][lane] = base;
             s_zcnt[wave][lane] = 0;
         }
         wave_lds_sync();
-        for (uint32_t i = lane; i < nst; i += 64) {
+        const uint32_t ns = nst < (uint32_t)ST_CAP ? nst : (uint32_t)ST_CAP;
+        for (uint32_t i = lane; i < ns; i += 64) {
             const uint32_t meta = s_smeta[wave][i];
             const uint32_t z = (meta >> 8) & 63u;
             const uint32_t pos = s_zbase[wave][z] + (meta & 255u);
@@ -380,43 +386,66 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
         maxkey = key > maxkey ? key : maxkey;
         const uint64_t m = __ballot(zone);
         if (m) {
-            if (nst > ST_CAP - 64) flush();
             if (zone) {
                 const uint32_t z = code & 63u;
                 const uint32_t pos = nst + mbcnt(m);
-                const uint32_t lr = atomicAdd(&s_zcnt[wave][z], 1u);
-                s_sbits[wave][pos] = bits;
-                s_smeta[wave][pos] = (rel << 14) | (z << 8) | lr;
+                atomicMax(&s_zmax[wave][z], key);
+                atomicMax(&s_zmininv[wave][z], ~key);
+                if (pos < (uint32_t)ST_CAP) {
+                    const uint32_t lr = atomicAdd(&s_zcnt[wave][z], 1u);
+                    s_sbits[wave][pos] = bits;
+                    s_smeta[wave][pos] = (rel << 14) | (z << 8) | lr;
+                } else {   // the stage is full (a step made of candidates): append directly
+                    const uint32_t at = atomicAdd(&ra->zone_fill[z], 1u);
+                    atomicMax(&ra->zone_kmax[z], key);
+                    atomicMax(&ra->zone_kmin_inv[z], ~key);
+                    if (at < s_zcap[z]) {
+                        cb[(size_t)s_zoff[z] + at] = bits;
+                        ci[(size_t)s_zoff[z] + at] = (uint32_t)c0 + rel;
+                    } else {
+                        dropped = true;
+                    }
+                }
             }
             nst += (uint32_t)__popcll(m);
         }
     };
 
-    // a wave covers 1024 consecutive elements per step, the workgroup 16384
-    for (int64_t jw = c0 + (int64_t)wave * 1024; jw < c1; jw += MAIN_THREADS * 16) {
-        uint32_t b[4][4];
-        int nv[4];
+    // a wave covers 1024 consecutive elements per step, the workgroup 16384; the loads of the next step are
+    // issued before the current one is processed
+    auto load_step = [&](int64_t jw, uint32_t (&b)[16], uint32_t& valid) {
+        valid = 0;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int64_t j = jw + q * 256 + (int64_t)lane * 4;
-            nv[q] = j < c1 ? ld.load4(j, b[q]) : 0;
-            if (nv[q] < 4) {
+            uint32_t t[4];
+            const int nv = j < c1 ? ld.load4(j, t) : 0;
 #pragma unroll
-                for (int c = 0; c < 4; ++c) if (c >= nv[q]) b[q][c] = 0u;
+            for (int c = 0; c < 4; ++c) {
+                b[q * 4 + c] = t[c];
+                if (c < nv) valid |= 1u << (q * 4 + c);
             }
         }
+    };
+    uint32_t bA[16], bB[16];
+    uint32_t vA = 0, vB = 0;
+    const int64_t jw0 = c0 + (int64_t)wave * 1024;
+    if (jw0 < c1) load_step(jw0, bA, vA);
+    for (int64_t jw = jw0; jw < c1; jw += MAIN_THREADS * 16) {
+        const int64_t jn = jw + MAIN_THREADS * 16;
+        if (jn < c1) load_step(jn, bB, vB);
         const uint32_t rel0 = (uint32_t)(jw - c0) + lane * 4;
         if (jw + 1024 <= c1) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-#pragma unroll
-                for (int c = 0; c < 4; ++c) slot(b[q][c], true, rel0 + q * 256 + c);
+            for (int e = 0; e < 16; ++e) slot(bA[e], true, rel0 + (e >> 2) * 256 + (e & 3));
         } else {
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-#pragma unroll
-                for (int c = 0; c < 4; ++c) slot(b[q][c], c < nv[q], rel0 + q * 256 + c);
+            for (int e = 0; e < 16; ++e) slot(bA[e], (vA >> e) & 1u, rel0 + (e >> 2) * 256 + (e & 3));
         }
+        if (nst > ST_CAP / 2) flush();
+#pragma unroll
+        for (int e = 0; e < 16; ++e) bA[e] = bB[e];
+        vA = vB;
     }
     flush();
     if (__ballot(maxkey >= 0x7F800000u) && lane == 0) atomicOr(a.dev_status, MLMC_DEV_NONFINITE);
@@ -484,17 +513,30 @@ __device__ __forceinline__ void wave_rank_search(const uint32_t* h, uint32_t r, 
     if (!m) { bin = 0; rin = r; cnt = 0; }
 }
 
+constexpr int FH_BINS = 2048;        // bins of the zone-relative key histogram
+constexpr int COLLECT_CAP = 2048;    // candidates of the thresholds' bins that are ranked in LDS
+constexpr int ZC_CAP = 8192;         // (parts of the zone) x (chunks of the row) counters
+
 template <bool SUMS>
 __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pass) {
-    __shared__ uint32_t s_hist[TMAX][256];
+    __shared__ uint32_t s_un[TMAX * 256];   // slow path: digit histograms; fast path: candidates of the threshold bins
+    __shared__ uint32_t s_fh[FH_BINS];
+    __shared__ uint8_t s_bincls[FH_BINS];
+    __shared__ uint32_t s_zc[ZC_CAP];
     __shared__ unsigned long long s_pacc[SUMS ? PIECE_CLASSES * REP : 1][2];
-    __shared__ int32_t s_n, s_ok, s_nsub, s_any, s_elo, s_ehi;
+    __shared__ int32_t s_n, s_ok, s_nsub, s_any, s_fast;
+    __shared__ uint32_t s_ncol;
     __shared__ int32_t s_t[TMAX], s_sub[TMAX];
     __shared__ uint32_t s_res[TMAX], s_pfx[TMAX], s_tau[TMAX], s_q[TMAX], s_eq[TMAX], s_jx[TMAX];
     __shared__ uint32_t s_subpfx[TMAX], s_subtau[TMAX];
+    __shared__ uint32_t s_bin[TMAX], s_rin[TMAX], s_bcnt[TMAX], s_pos[TMAX];
+    uint32_t (*s_hist)[256] = (uint32_t(*)[256])s_un;
+    unsigned long long* s_col = (unsigned long long*)s_un;    // [COLLECT_CAP] as collected
+    unsigned long long* s_srt = s_col + COLLECT_CAP;          // [COLLECT_CAP] in descending order
+    static_assert(sizeof(s_un) >= 2 * COLLECT_CAP * sizeof(unsigned long long), "candidate buffers must fit");
 
     const int z = blockIdx.x, row = blockIdx.y, tid = threadIdx.x;
-    const uint32_t lane = lane_id(), wave = tid >> 6;
+    const uint32_t lane = lane_id(), wave = tid >> 6, l31 = lane & 31u;
     RowInfo* ri = a.rinfo + row;
     RowAcc* ra = a.racc + row;
     if (exact_pass && !ri->respec) return;
@@ -531,6 +573,7 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
             int64_t tot = above + n + ra->region_cnt[z + 1];
             if (tot != a.d) ok = false;
         }
+        if (m == 0) ok = false;
         if (!ok) fail();
         s_n = m;
         s_ok = ok ? 1 : 0;
@@ -538,160 +581,290 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
     __syncthreads();
     if (!s_ok) return;
     const int nthr = s_n;
+    const int nparts = nthr + 1;
+    const int nchunks = a.chunks_per_row;
+    const bool count_fits = nparts * nchunks <= ZC_CAP;
+    const uint32_t cmagic = (uint32_t)(0x100000000ull / (uint32_t)(a.chunk >> 12)) + 1u;   // chunk = multiple of 4096, >= 4 * 4096
+    auto chunk_of = [&](uint32_t j) -> uint32_t { return __umulhi(j >> 12, cmagic); };
 
-    // ---- radix select on the keys: digits of 8, 8, 8, 7 bits from the top ----
-    for (int pass = 0; pass < 4; ++pass) {
-        const int shift = pass == 0 ? 23 : pass == 1 ? 15 : pass == 2 ? 7 : 0;
-        const uint32_t mask = pass == 3 ? 127u : 255u;
-        const int hb = pass == 3 ? 7 : shift + 8;   // unresolved low bits before this pass (31 for pass 0)
-        if (tid == 0) {
-            int ns = 0;
-            for (int u = 0; u < nthr; ++u) {
-                if (u == 0 || s_pfx[u] != s_pfx[u - 1]) { s_subpfx[ns] = s_pfx[u]; ++ns; }
-                s_sub[u] = ns - 1;
-            }
-            s_nsub = ns;
-        }
-        for (int i = tid; i < TMAX * 256; i += FN_THREADS) (&s_hist[0][0])[i] = 0;
-        __syncthreads();
-        const int nsub = s_nsub;
-        if (pass == 0) {
-#pragma unroll 4
-            for (uint32_t i = tid; i < n; i += FN_THREADS) atomicAdd(&s_hist[0][(key_of_bits(kb[i]) >> 23) & 255u], 1u);
-        } else if (nsub == 1) {
-            const uint32_t pf = s_subpfx[0] >> hb;
-#pragma unroll 4
-            for (uint32_t i = tid; i < n; i += FN_THREADS) {
-                const uint32_t key = key_of_bits(kb[i]);
-                if ((key >> hb) == pf) atomicAdd(&s_hist[0][(key >> shift) & mask], 1u);
-            }
-        } else {
-#pragma unroll 2
-            for (uint32_t i = tid; i < n; i += FN_THREADS) {
-                const uint32_t key = key_of_bits(kb[i]);
-                const uint32_t kp = key >> hb;
-                for (int s = 0; s < nsub; ++s)
-                    if (kp == (s_subpfx[s] >> hb)) atomicAdd(&s_hist[s][(key >> shift) & mask], 1u);
-            }
-        }
-        __syncthreads();
-        if (pass == 0 && wave == FN_THREADS / 64 - 1) {   // exponent fields present in the list (lane l: bins 4l..4l+3)
-            uint32_t lo = 256, hi = 0;
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                if (s_hist[0][4 * lane + i]) { lo = lo < 4 * lane + i ? lo : 4 * lane + i; hi = 4 * lane + i; }
-#pragma unroll
-            for (int o = 32; o >= 1; o >>= 1) {
-                const uint32_t l2 = __shfl_xor(lo, o, 64), h2 = __shfl_xor(hi, o, 64);
-                lo = l2 < lo ? l2 : lo;
-                hi = h2 > hi ? h2 : hi;
-            }
-            if (lane == 0) { s_elo = (int32_t)lo; s_ehi = (int32_t)hi; }
-        }
-        for (int u = wave; u < nthr; u += FN_THREADS / 64) {
-            int bin;
-            uint32_t rin, cnt;
-            wave_rank_search<4>(s_hist[s_sub[u]], s_res[u], bin, rin, cnt);
-            if (lane == 0) {
-                s_pfx[u] |= (uint32_t)bin << shift;
-                s_res[u] = rin;
-                if (pass == 3) { s_tau[u] = s_pfx[u]; s_q[u] = rin; s_eq[u] = cnt; }
-            }
-        }
-        __syncthreads();
+    // range of the keys in the list (kept by the selection read), exponents for the part sums
+    const uint32_t kmin = ~ra->zone_kmin_inv[z], kmax = ra->zone_kmax[z];
+    const int Elo = (int)(kmin >> 23) ? (int)(kmin >> 23) : 1;
+    const int Ehi = (int)(kmax >> 23) ? (int)(kmax >> 23) : 1;
+    const int span = Ehi - Elo + 1;
+    const int nclass = nparts * span;
+    if (kmin > kmax || (SUMS && nclass > PIECE_CLASSES)) {
+        if (tid == 0) fail();
+        return;
     }
-    // ---- index cut among the entries equal to the threshold key: the q-th smallest index + 1 ----
-    if (tid < nthr) {
-        s_jx[tid] = JX_ALL;
-        s_pfx[tid] = 0;
-        s_res[tid] = s_eq[tid] - s_q[tid] + 1;   // the q-th smallest is the (eq - q + 1)-th largest
-        if (s_q[tid] < 1 || s_q[tid] > s_eq[tid]) fail();
-    }
-    if (tid == 0) {
-        int any = 0;
-        for (int u = 0; u < nthr; ++u) any |= s_q[u] < s_eq[u] ? 1 : 0;
-        s_any = any;
+    const uint32_t range = kmax - kmin;
+    const int sh = range < (uint32_t)FH_BINS ? 0 : (32 - __clz(range)) - 11;   // (range >> sh) < FH_BINS
+
+    for (int i = tid; i < FH_BINS; i += FN_THREADS) s_fh[i] = 0;
+    if (count_fits) for (int i = tid; i < nparts * nchunks; i += FN_THREADS) s_zc[i] = 0;
+    if (SUMS) for (int i = tid; i < PIECE_CLASSES * REP * 2; i += FN_THREADS) (&s_pacc[0][0])[i] = 0ull;
+    if (tid == 0) s_ncol = 0;
+    __syncthreads();
+
+    // what every candidate contributes once its part (number of the zone's thresholds it is NOT inside) is known
+    auto classify = [&](int part, uint32_t key, uint32_t j) {
+        if (count_fits) atomicAdd(&s_zc[part * nchunks + (int)chunk_of(j)], 1u);
+        if (SUMS) {
+            const int E = (int)(key >> 23) ? (int)(key >> 23) : 1;
+            const int cls = part * span + (E - Elo);
+            const unsigned long long sq = sig_square(key);
+            atomicAdd(&s_pacc[cls * REP + l31][0], sq & 0xFFFFFFFFull);
+            atomicAdd(&s_pacc[cls * REP + l31][1], sq >> 32);
+        }
+    };
+
+    // ---- fast path, read 1: histogram of (key - kmin) >> sh; the bin of every threshold ----
+#pragma unroll 8
+    for (uint32_t i = tid; i < n; i += FN_THREADS) {
+        const uint32_t key = key_of_bits(kb[i]);
+        const uint32_t b = (key - kmin) >> sh;
+        atomicAdd(&s_fh[b < (uint32_t)FH_BINS ? b : (uint32_t)FH_BINS - 1], 1u);
     }
     __syncthreads();
-    if (s_any) {
+    for (int u = wave; u < nthr; u += FN_THREADS / 64) {
+        int bin;
+        uint32_t rin, cnt;
+        wave_rank_search<FH_BINS / 64>(s_fh, s_res[u], bin, rin, cnt);
+        if (lane == 0) { s_bin[u] = (uint32_t)bin; s_rin[u] = rin; s_bcnt[u] = cnt; }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        // the candidates of the thresholds' bins, in descending key order, form segments (one per distinct bin)
+        uint32_t run = 0, seg = 0;
+        bool ok = true;
+        for (int u = 0; u < nthr; ++u) {
+            if (u == 0 || s_bin[u] != s_bin[u - 1]) { seg = run; run += s_bcnt[u]; }
+            if (s_rin[u] < 1 || s_rin[u] > s_bcnt[u]) ok = false;
+            s_pos[u] = seg + s_rin[u] - 1;
+        }
+        if (!ok) fail();
+        s_ok = ok ? 1 : 0;
+        s_fast = run <= (uint32_t)COLLECT_CAP ? 1 : 0;
+    }
+    __syncthreads();
+    if (!s_ok) return;
+
+    if (s_fast) {
+        for (int b = tid; b < FH_BINS; b += FN_THREADS) {
+            int part = 0;
+            bool isthr = false;
+            for (int u = 0; u < nthr; ++u) {
+                part += (uint32_t)b < s_bin[u] ? 1 : 0;
+                isthr |= (uint32_t)b == s_bin[u];
+            }
+            s_bincls[b] = isthr ? (uint8_t)0xFF : (uint8_t)part;
+        }
+        __syncthreads();
+        // ---- read 2: candidates of the thresholds' bins go to LDS, every other one is classified by its bin ----
+#pragma unroll 4
+        for (uint32_t i = tid; i < n; i += FN_THREADS) {
+            const uint32_t key = key_of_bits(kb[i]);
+            const uint32_t j = kj[i];
+            uint32_t b = (key - kmin) >> sh;
+            b = b < (uint32_t)FH_BINS ? b : (uint32_t)FH_BINS - 1;
+            const uint32_t cls = s_bincls[b];
+            if (cls == 0xFFu) {
+                const uint32_t at = atomicAdd(&s_ncol, 1u);
+                if (at < (uint32_t)COLLECT_CAP) s_col[at] = ((unsigned long long)key << 32) | (uint32_t)~j;
+            } else {
+                classify((int)cls, key, j);
+            }
+        }
+        __syncthreads();
+        const uint32_t ncol = s_ncol < (uint32_t)COLLECT_CAP ? s_ncol : (uint32_t)COLLECT_CAP;
+        // descending order of (key, lower index first) by counting: composites are distinct
+        for (uint32_t e = tid; e < ncol; e += FN_THREADS) {
+            const unsigned long long c = s_col[e];
+            uint32_t r = 0;
+            for (uint32_t f = 0; f < ncol; ++f) r += s_col[f] > c ? 1u : 0u;
+            s_srt[r] = c;
+        }
+        __syncthreads();
+        if (tid < nthr) {
+            if (s_pos[tid] < ncol) {
+                const unsigned long long c = s_srt[s_pos[tid]];
+                s_tau[tid] = (uint32_t)(c >> 32);
+                s_jx[tid] = ~(uint32_t)c + 1u;     // inside: equal key and index <= that of the threshold element
+            } else {
+                fail();
+            }
+        }
+        __syncthreads();
+        for (uint32_t e = tid; e < ncol; e += FN_THREADS) {
+            int part = 0;
+            for (int u = 0; u < nthr; ++u) part += e > s_pos[u] ? 1 : 0;
+            const unsigned long long c = s_srt[e];
+            classify(part, (uint32_t)(c >> 32), ~(uint32_t)c);
+        }
+    } else {
+        // ---- slow path (a threshold bin too full to rank in LDS, e.g. massive ties): radix select on the
+        //      keys, digits of 8, 8, 8, 7 bits from the top, then on the indices of the entries equal to the key ----
         for (int pass = 0; pass < 4; ++pass) {
-            const int shift = 24 - 8 * pass;
-            const int hb = shift + 8;   // 32 for pass 0: no prefix yet
+            const int shift = pass == 0 ? 23 : pass == 1 ? 15 : pass == 2 ? 7 : 0;
+            const uint32_t mask = pass == 3 ? 127u : 255u;
+            const int hb = pass == 3 ? 7 : shift + 8;   // unresolved low bits before this pass (31 for pass 0)
+            __syncthreads();
             if (tid == 0) {
                 int ns = 0;
                 for (int u = 0; u < nthr; ++u) {
-                    if (s_q[u] >= s_eq[u]) { s_sub[u] = -1; continue; }
-                    int found = -1;
-                    for (int s = 0; s < ns; ++s)
-                        if (s_subtau[s] == s_tau[u] && s_subpfx[s] == s_pfx[u]) found = s;
-                    if (found < 0) { s_subtau[ns] = s_tau[u]; s_subpfx[ns] = s_pfx[u]; found = ns++; }
-                    s_sub[u] = found;
+                    if (u == 0 || s_pfx[u] != s_pfx[u - 1]) { s_subpfx[ns] = s_pfx[u]; ++ns; }
+                    s_sub[u] = ns - 1;
                 }
                 s_nsub = ns;
             }
             for (int i = tid; i < TMAX * 256; i += FN_THREADS) (&s_hist[0][0])[i] = 0;
             __syncthreads();
             const int nsub = s_nsub;
+            if (pass == 0) {
+#pragma unroll 4
+                for (uint32_t i = tid; i < n; i += FN_THREADS) atomicAdd(&s_hist[0][(key_of_bits(kb[i]) >> 23) & 255u], 1u);
+            } else if (nsub == 1) {
+                const uint32_t pf = s_subpfx[0] >> hb;
+#pragma unroll 4
+                for (uint32_t i = tid; i < n; i += FN_THREADS) {
+                    const uint32_t key = key_of_bits(kb[i]);
+                    if ((key >> hb) == pf) atomicAdd(&s_hist[0][(key >> shift) & mask], 1u);
+                }
+            } else {
 #pragma unroll 2
-            for (uint32_t i = tid; i < n; i += FN_THREADS) {
-                const uint32_t key = key_of_bits(kb[i]);
-                for (int s = 0; s < nsub; ++s) {
-                    if (key != s_subtau[s]) continue;
-                    const uint32_t j = kj[i];
-                    if (pass == 0 || (j >> hb) == (s_subpfx[s] >> hb)) atomicAdd(&s_hist[s][(j >> shift) & 255u], 1u);
+                for (uint32_t i = tid; i < n; i += FN_THREADS) {
+                    const uint32_t key = key_of_bits(kb[i]);
+                    const uint32_t kp = key >> hb;
+                    for (int s2 = 0; s2 < nsub; ++s2)
+                        if (kp == (s_subpfx[s2] >> hb)) atomicAdd(&s_hist[s2][(key >> shift) & mask], 1u);
                 }
             }
             __syncthreads();
             for (int u = wave; u < nthr; u += FN_THREADS / 64) {
-                if (s_sub[u] < 0) continue;
                 int bin;
                 uint32_t rin, cnt;
                 wave_rank_search<4>(s_hist[s_sub[u]], s_res[u], bin, rin, cnt);
                 if (lane == 0) {
                     s_pfx[u] |= (uint32_t)bin << shift;
                     s_res[u] = rin;
-                    if (pass == 3) s_jx[u] = s_pfx[u] + 1u;
+                    if (pass == 3) { s_tau[u] = s_pfx[u]; s_q[u] = rin; s_eq[u] = cnt; }
                 }
             }
-            __syncthreads();
+        }
+        __syncthreads();
+        // index cut among the entries equal to the threshold key: the q-th smallest index + 1
+        if (tid < nthr) {
+            s_jx[tid] = JX_ALL;
+            s_pfx[tid] = 0;
+            s_res[tid] = s_eq[tid] - s_q[tid] + 1;   // the q-th smallest is the (eq - q + 1)-th largest
+            if (s_q[tid] < 1 || s_q[tid] > s_eq[tid]) fail();
+        }
+        if (tid == 0) {
+            int any = 0;
+            for (int u = 0; u < nthr; ++u) any |= s_q[u] < s_eq[u] ? 1 : 0;
+            s_any = any;
+        }
+        __syncthreads();
+        if (s_any) {
+            for (int pass = 0; pass < 4; ++pass) {
+                const int shift = 24 - 8 * pass;
+                const int hb = shift + 8;   // 32 for pass 0: no prefix yet
+                if (tid == 0) {
+                    int ns = 0;
+                    for (int u = 0; u < nthr; ++u) {
+                        if (s_q[u] >= s_eq[u]) { s_sub[u] = -1; continue; }
+                        int found = -1;
+                        for (int s2 = 0; s2 < ns; ++s2)
+                            if (s_subtau[s2] == s_tau[u] && s_subpfx[s2] == s_pfx[u]) found = s2;
+                        if (found < 0) { s_subtau[ns] = s_tau[u]; s_subpfx[ns] = s_pfx[u]; found = ns++; }
+                        s_sub[u] = found;
+                    }
+                    s_nsub = ns;
+                }
+                for (int i = tid; i < TMAX * 256; i += FN_THREADS) (&s_hist[0][0])[i] = 0;
+                __syncthreads();
+                const int nsub = s_nsub;
+#pragma unroll 2
+                for (uint32_t i = tid; i < n; i += FN_THREADS) {
+                    const uint32_t key = key_of_bits(kb[i]);
+                    for (int s2 = 0; s2 < nsub; ++s2) {
+                        if (key != s_subtau[s2]) continue;
+                        const uint32_t j = kj[i];
+                        if (pass == 0 || (j >> hb) == (s_subpfx[s2] >> hb)) atomicAdd(&s_hist[s2][(j >> shift) & 255u], 1u);
+                    }
+                }
+                __syncthreads();
+                for (int u = wave; u < nthr; u += FN_THREADS / 64) {
+                    if (s_sub[u] < 0) continue;
+                    int bin;
+                    uint32_t rin, cnt;
+                    wave_rank_search<4>(s_hist[s_sub[u]], s_res[u], bin, rin, cnt);
+                    if (lane == 0) {
+                        s_pfx[u] |= (uint32_t)bin << shift;
+                        s_res[u] = rin;
+                        if (pass == 3) s_jx[u] = s_pfx[u] + 1u;
+                    }
+                }
+                __syncthreads();
+            }
+        }
+        // every candidate's part from the exact thresholds
+        if (count_fits || SUMS) {
+#pragma unroll 2
+            for (uint32_t i = tid; i < n; i += FN_THREADS) {
+                const uint32_t key = key_of_bits(kb[i]);
+                const uint32_t j = kj[i];
+                int part = 0;
+                for (int u = 0; u < nthr; ++u) {
+                    const uint32_t tau = s_tau[u];
+                    part += (key > tau || (key == tau && j < s_jx[u])) ? 0 : 1;
+                }
+                classify(part, key, j);
+            }
         }
     }
+    __syncthreads();
     if (tid < nthr) {
         ri->thr_tau[s_t[tid]] = s_tau[tid];
         ri->thr_jx[s_t[tid]] = s_jx[tid];
     }
+    // ---- per-chunk counts of every part (the message read turns them into output offsets) ----
+    uint32_t* zc = a.chunk_zcnt + (size_t)row * nchunks * ZPMAX;
+    auto slot_of = [&](int part) -> int { return part < nthr ? s_t[part] : TMAX + z; };
+    if (count_fits) {
+        for (int i = tid; i < nparts * nchunks; i += FN_THREADS) {
+            const int part = i / nchunks, c = i - part * nchunks;
+            zc[(size_t)c * ZPMAX + slot_of(part)] = s_zc[i];
+        }
+    } else {
+        // long rows with many thresholds in one zone: a few parts at a time, one more read of the list each
+        const int ppp = ZC_CAP / nchunks;   // >= 1: a row has at most CHUNKS_MAX = ZC_CAP chunks
+        for (int p0 = 0; p0 < nparts; p0 += ppp) {
+            const int p1 = p0 + ppp < nparts ? p0 + ppp : nparts;
+            __syncthreads();
+            for (int i = tid; i < (p1 - p0) * nchunks; i += FN_THREADS) s_zc[i] = 0;
+            __syncthreads();
+#pragma unroll 2
+            for (uint32_t i = tid; i < n; i += FN_THREADS) {
+                const uint32_t key = key_of_bits(kb[i]);
+                const uint32_t j = kj[i];
+                int part = 0;
+                for (int u = 0; u < nthr; ++u) {
+                    const uint32_t tau = s_tau[u];
+                    part += (key > tau || (key == tau && j < s_jx[u])) ? 0 : 1;
+                }
+                if (part >= p0 && part < p1) atomicAdd(&s_zc[(part - p0) * nchunks + (int)chunk_of(j)], 1u);
+            }
+            __syncthreads();
+            for (int i = tid; i < (p1 - p0) * nchunks; i += FN_THREADS) {
+                const int part = p0 + i / nchunks, c = i % nchunks;
+                zc[(size_t)c * ZPMAX + slot_of(part)] = s_zc[i];
+            }
+        }
+    }
     if (!SUMS) return;
 
-    // ---- exact sums of the parts the thresholds cut the zone into: part j = inside the top k of thresholds
-    //      j.. but of none before; one accumulator class per (part, exponent) ----
-    const int Ehi = s_ehi ? s_ehi : 1;   // n >= 1 here: the list holds a threshold
-    const int Elo = s_elo ? s_elo : 1;
-    const int span = Ehi - Elo + 1;
-    const int nclass = (nthr + 1) * span;
-    if (nclass > PIECE_CLASSES) {
-        if (tid == 0) fail();
-        return;
-    }
-    for (int i = tid; i < PIECE_CLASSES * REP * 2; i += FN_THREADS) (&s_pacc[0][0])[i] = 0ull;
-    __syncthreads();
-    const uint32_t l31 = lane & 31u;
-#pragma unroll 2
-    for (uint32_t i = tid; i < n; i += FN_THREADS) {
-        const uint32_t key = key_of_bits(kb[i]);
-        const uint32_t j = kj[i];
-        int part = 0;
-        for (int u = 0; u < nthr; ++u) {
-            const uint32_t tau = s_tau[u];
-            const bool inside = key > tau || (key == tau && j < s_jx[u]);
-            part += inside ? 0 : 1;
-        }
-        const int E = (int)(key >> 23) ? (int)(key >> 23) : 1;
-        const int cls = part * span + (E - Elo);
-        const unsigned long long sq = sig_square(key);
-        atomicAdd(&s_pacc[cls * REP + l31][0], sq & 0xFFFFFFFFull);
-        atomicAdd(&s_pacc[cls * REP + l31][1], sq >> 32);
-    }
-    __syncthreads();
+    // ---- exact sums of the parts: one piece per (part, exponent) ----
     if (tid < nclass) {
         unsigned long long lo = 0, hi = 0;
         for (int r = 0; r < REP; ++r) { lo += s_pacc[tid * REP + r][0]; hi += s_pacc[tid * REP + r][1]; }
@@ -847,41 +1020,6 @@ __device__ __forceinline__ bool inside_top(const Thr3& th, int i, uint32_t key, 
     return key > th.tau[i] || (key == th.tau[i] && j < th.jx[i]);
 }
 
-// Entries of the message that come from zone candidates, counted per chunk.  blockIdx.x = 0, 1, 2 <-> the zone
-// of threshold 0, l-1, l (a zone shared by two of them is counted once).
-__global__ __launch_bounds__(1024) void k_emitcount(TopkArgs a) {
-    __shared__ uint32_t s_c[CHUNKS_MAX];
-    const int s = blockIdx.x, row = blockIdx.y, tid = threadIdx.x;
-    const RowInfo* ri = a.rinfo + row;
-    const int lev = ri->level;
-    const int ts[3] = {0, lev - 1, lev};
-    const int z = ri->thr_zone[ts[s]];
-    if (z < 0) return;
-    for (int i = 0; i < s; ++i)
-        if (ri->thr_zone[ts[i]] == z) return;
-    const uint32_t n = a.racc[row].zone_fill[z];
-    const uint32_t* kb = a.cand_bits + (size_t)row * (size_t)a.d + ri->zone_off[z];
-    const uint32_t* kj = a.cand_idx + (size_t)row * (size_t)a.d + ri->zone_off[z];
-    const Thr3 th = load_thr3(ri);
-    const int nc = a.chunks_per_row;
-    for (int i = tid; i < nc; i += 1024) s_c[i] = 0;
-    __syncthreads();
-    const uint32_t chunk = (uint32_t)a.chunk;
-#pragma unroll 2
-    for (uint32_t i = tid; i < n; i += 1024) {
-        const uint32_t key = key_of_bits(kb[i]), j = kj[i];
-        const bool in0 = inside_top(th, 0, key, j);
-        const bool emit = in0 || (inside_top(th, 2, key, j) && !inside_top(th, 1, key, j));
-        if (emit) atomicAdd(&s_c[j / chunk], 1u);
-    }
-    __syncthreads();
-    uint32_t* ce = a.chunk_emit + (size_t)row * nc;
-    for (int i = tid; i < nc; i += 1024) {
-        uint32_t v = s_c[i];
-        if (v) atomicAdd(&ce[i], v);
-    }
-}
-
 // ---------------------------------------------------------------------------------------------------
 // The message read.  One workgroup per (chunk, row); a wave covers 1024 consecutive elements per step.
 constexpr int WR_THREADS = 512;
@@ -921,23 +1059,35 @@ __global__ __launch_bounds__(WR_THREADS) void k_write(TopkArgs a) {
         }
         __syncthreads();
     }
-    // entries of this row before this chunk: regions of band 0 and band l, plus the zone entries
+    // entries of this row before this chunk: the regions of band 0 and band l, plus the parts of the zones of
+    // thresholds 0, l-1, l that belong to those bands
     int r0 = -1, rl = -1;
     for (int r = 0; r <= nzn; ++r) {
         const int lab = ri->region_label[r];
         if (lab == 0) r0 = r;
         if (lab == lev) rl = r;
     }
+    int zs[3] = {-1, -1, -1};
+    {
+        const int z0 = ri->thr_zone[0], za = ri->thr_zone[lev - 1], zb = ri->thr_zone[lev];
+        if (z0 >= 0) zs[0] = 0;                                   // inside the top k_0
+        if (za >= 0) zs[1] = zb == za ? lev : TMAX + za;          // just below threshold l-1, in its zone
+        if (zb >= 0 && zb != za) zs[2] = lev;                     // above threshold l, in a zone of its own
+    }
+    auto chunk_entries = [&](int c) -> uint32_t {
+        const uint32_t* cc = a.chunk_cnt + ((size_t)row * nc + c) * RMAX;
+        const uint32_t* zc = a.chunk_zcnt + ((size_t)row * nc + c) * ZPMAX;
+        uint32_t v = 0;
+        if (r0 >= 0) v += cc[r0];
+        if (rl >= 0) v += cc[rl];
+#pragma unroll
+        for (int i = 0; i < 3; ++i)
+            if (zs[i] >= 0) v += zc[zs[i]];
+        return v;
+    };
     {
         unsigned long long part = 0;
-        const uint32_t* cc = a.chunk_cnt + (size_t)row * nc * RMAX;
-        const uint32_t* ce = a.chunk_emit + (size_t)row * nc;
-        for (int c = tid; c < chunk_id; c += WR_THREADS) {
-            uint32_t v = ce[c];
-            if (r0 >= 0) v += cc[(size_t)c * RMAX + r0];
-            if (rl >= 0) v += cc[(size_t)c * RMAX + rl];
-            part += v;
-        }
+        for (int c = tid; c < chunk_id; c += WR_THREADS) part += chunk_entries(c);
 #pragma unroll
         for (int o = 32; o >= 1; o >>= 1) part += __shfl_xor(part, o, 64);
         if (lane == 0) s_red[wave] = part;
@@ -1043,10 +1193,7 @@ __global__ __launch_bounds__(WR_THREADS) void k_write(TopkArgs a) {
     }
     // consistency: the chunk ends where the per-chunk counts say the next one starts
     if (tid == 0) {
-        const uint32_t* cc = a.chunk_cnt + (size_t)row * nc * RMAX + (size_t)chunk_id * RMAX;
-        uint32_t expect = s_base + a.chunk_emit[(size_t)row * nc + chunk_id];
-        if (r0 >= 0) expect += cc[r0];
-        if (rl >= 0) expect += cc[rl];
+        const uint32_t expect = s_base + chunk_entries(chunk_id);
         if (expect != run) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
         if (chunk_id == nc - 1) {
             a.tile_off[(size_t)row * (nt + 1) + nt] = run;
@@ -1070,12 +1217,15 @@ static mlmc_status launch_select(const mlmc_plan_t* pl, const TopkArgs& a, bool 
         const int64_t hcap = 2048 / pl->M > 0 ? 2048 / pl->M : 1;
         if (hw > hcap) hw = hcap;
         const dim3 hgrid((unsigned)hw, pl->M);
-        MLMC_LAUNCH(K_HIST, st, k_hist<DT, VEC><<<hgrid, HIST_THREADS, 0, st>>>(a, exact_pass));
-        MLMC_LAUNCH(K_SCAN, st, k_scan<<<pl->M, 1024, 0, st>>>(a, exact_pass));
-        if (sums) MLMC_LAUNCH(K_MAIN, st, k_main<DT, VEC, true><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
-        else MLMC_LAUNCH(K_MAIN, st, k_main<DT, VEC, false><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
-        if (sums) MLMC_LAUNCH(K_FINISH, st, k_finish<true><<<fgrid, FN_THREADS, 0, st>>>(a, exact_pass));
-        else MLMC_LAUNCH(K_FINISH, st, k_finish<false><<<fgrid, FN_THREADS, 0, st>>>(a, exact_pass));
+        // the kernels of the redo round exit at once for rows that need none: they are timed as one entry
+        const int kh = exact_pass ? K_REDO : K_HIST, ks = exact_pass ? K_REDO : K_SCAN;
+        const int km = exact_pass ? K_REDO : K_MAIN, kf = exact_pass ? K_REDO : K_FINISH;
+        MLMC_LAUNCH(kh, st, k_hist<DT, VEC><<<hgrid, HIST_THREADS, 0, st>>>(a, exact_pass));
+        MLMC_LAUNCH(ks, st, k_scan<<<pl->M, 1024, 0, st>>>(a, exact_pass));
+        if (sums) MLMC_LAUNCH(km, st, k_main<DT, VEC, true><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
+        else MLMC_LAUNCH(km, st, k_main<DT, VEC, false><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
+        if (sums) MLMC_LAUNCH(kf, st, k_finish<true><<<fgrid, FN_THREADS, 0, st>>>(a, exact_pass));
+        else MLMC_LAUNCH(kf, st, k_finish<false><<<fgrid, FN_THREADS, 0, st>>>(a, exact_pass));
     }
     if (sums) MLMC_LAUNCH(K_NORMS, st, k_norms<<<pl->M, 256, 0, st>>>(a));
     return MLMC_OK;
@@ -1083,7 +1233,6 @@ static mlmc_status launch_select(const mlmc_plan_t* pl, const TopkArgs& a, bool 
 
 template <int DT, bool VEC>
 static mlmc_status launch_compact(const mlmc_plan_t* pl, const TopkArgs& a, hipStream_t st) {
-    MLMC_LAUNCH(K_EMITCOUNT, st, k_emitcount<<<dim3(3, pl->M), 1024, 0, st>>>(a));
     MLMC_LAUNCH(K_WRITE, st, k_write<DT, VEC><<<dim3(pl->chunks_per_row, pl->M), WR_THREADS, 0, st>>>(a));
     return MLMC_OK;
 }
