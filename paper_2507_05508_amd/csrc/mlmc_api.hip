@@ -93,6 +93,7 @@ static void fill_topk_args(const mlmc_plan_t* pl, TopkArgs& a, const void* g, in
     a.norms = (double*)(w + pl->off_norms);
     a.cand_bits = (uint32_t*)(w + pl->off_cand_bits);
     a.cand_idx = (uint32_t*)(w + pl->off_cand_idx);
+    a.cand_priv = (uint2*)(w + pl->off_cand_priv);
     a.dev_status = dev_status;
 }
 
@@ -240,6 +241,8 @@ mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dty
         off = align_up(off + sizeof(uint32_t) * (size_t)d * M, 256);
         pl->off_cand_idx = off;
         off = align_up(off + sizeof(uint32_t) * (size_t)d * M, 256);
+        pl->off_cand_priv = off;
+        off = align_up(off + sizeof(uint2) * (size_t)pl->chunk * pl->chunks_per_row * M, 256);
     }
     pl->ws_bytes = off;
     if (workspace_bytes) *workspace_bytes = off;

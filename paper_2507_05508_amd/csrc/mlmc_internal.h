@@ -25,7 +25,11 @@ constexpr int CHUNKS_MAX = 8192;        // chunks per row
 // top k of the zone's previous threshold has slot t; the part below every threshold of zone z has slot TMAX + z.
 constexpr int ZPMAX = 2 * TMAX;
 
-constexpr uint16_t CODE_ZONE = 0x8000;  // table code of a zone bucket: CODE_ZONE | zone; else (region << 9) | group
+// Class table code of a first-digit bucket: bits 0..8 sum group, bits 9..14 region (or zone), bit 15 set for a zone
+// bucket.  Zone buckets carry the group G_DUMMY, so the selection read needs no branch around its accumulators.
+constexpr uint16_t CODE_ZONE = 0x8000;
+constexpr int G_DUMMY = GMAX - 1;
+constexpr int REP_SUM = 16;             // replicas of the 64-bit group sum accumulators: slot = id * 16 + (lane & 15)
 
 constexpr int THR_NONE = -1;      // k_t == 0: nothing is within the top k_t
 constexpr int THR_ALL = -2;       // k_t >= d: everything is
@@ -82,6 +86,7 @@ struct TopkArgs {
     RowAcc* racc;            // [M]
     uint32_t* cand_bits;     // [M][d] candidate lists: fp32 bit patterns
     uint32_t* cand_idx;      // [M][d]                  indices
+    uint2* cand_priv;        // [M][chunks_per_row][chunk] candidates {bits, offset in chunk << 6 | zone} as the waves met them
     uint32_t* chunk_cnt;     // [M][chunks_per_row][RMAX] elements of every region per chunk
     uint32_t* chunk_zcnt;    // [M][chunks_per_row][ZPMAX] candidates of every part of every zone per chunk
     uint32_t* tile_off;      // [M][ntiles + 1]
@@ -159,6 +164,6 @@ struct mlmc_plan_s {
     int sample_shift;
     // workspace byte offsets
     size_t off_racc, off_hist, off_hist2, zero_bytes;  // [0, zero_bytes) is cleared per call
-    size_t off_rinfo, off_table, off_chunk_cnt, off_chunk_zcnt, off_tileoff, off_norms, off_cand_bits, off_cand_idx;
+    size_t off_rinfo, off_table, off_chunk_cnt, off_chunk_zcnt, off_tileoff, off_norms, off_cand_bits, off_cand_idx, off_cand_priv;
     size_t ws_bytes;
 };

@@ -276,7 +276,7 @@ __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
         const uint32_t b = (uint32_t)(NB1 - 1 - (tid * 16 + i));
         while (zi < nz && s_zbot[zi] > b) ++zi;
         if (zi < nz && b <= s_ztop[zi]) {
-            codes[15 - i] = (uint16_t)(CODE_ZONE | zi);
+            codes[15 - i] = (uint16_t)(CODE_ZONE | (zi << 9) | G_DUMMY);
         } else {
             const uint32_t E = b >> 6;
             const int gid = (int)(255 - E) + zi;
@@ -299,168 +299,198 @@ __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
 // The selection read: region counts, group sums (SUMS), zone candidates.
 constexpr int MAIN_THREADS = 1024;
 constexpr int MAIN_WAVES = MAIN_THREADS / 64;
-constexpr int ST_CAP = 256;  // staged candidates per wave
+constexpr int RING = 320;    // staged candidates per wave: one 64-entry batch + what one load can add
+
+// LDS layout (bytes).  The table, counters and stage sit below 64 KB so that their base folds into the
+// instruction's offset field.
+constexpr int LM_TAB = 0;                                   // uint16 [NB1]
+constexpr int LM_CNT = LM_TAB + NB1 * 2;                    // uint32 [128][REP]: regions 0..63, zones 64..127
+constexpr int LM_ZCUR = LM_CNT + 128 * REP * 4;             // uint32 [64] write cursor of every zone list
+constexpr int LM_ZMAX = LM_ZCUR + 64 * 4;                   // uint32 [64] largest candidate key of every zone
+constexpr int LM_ZMIN = LM_ZMAX + 64 * 4;                   // uint32 [64] largest ~key
+constexpr int LM_ZOFF = LM_ZMIN + 64 * 4;                   // uint32 [64]
+constexpr int LM_ZCAP = LM_ZOFF + 64 * 4;
+constexpr int LM_STAGE = LM_ZCAP + 64 * 4;                  // uint2 [MAIN_WAVES][RING]: {bits, rel << 6 | zone}
+constexpr int LM_SUM = LM_STAGE + MAIN_WAVES * RING * 8;    // uint64 [GMAX][REP_SUM]
+template <bool SUMS> constexpr int lm_total() { return LM_SUM + (SUMS ? GMAX * REP_SUM * 8 : 0); }
+static_assert(lm_total<true>() <= 160 * 1024, "LDS budget");
+static_assert(ZMAX <= 64 && RMAX <= 64 && GMAX <= 512, "field widths of the class code");
 
 template <int DT, bool VEC, bool SUMS>
 __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pass) {
-    __shared__ uint16_t s_tab[NB1];
-    __shared__ unsigned long long s_sum[SUMS ? GMAX * REP : 1];
-    __shared__ uint32_t s_cnt[RMAX * REP];
-    __shared__ uint32_t s_sbits[MAIN_WAVES][ST_CAP];
-    __shared__ uint32_t s_smeta[MAIN_WAVES][ST_CAP];   // (index - chunk start) << 14 | zone << 8 | rank in the wave's zone batch
-    __shared__ uint32_t s_zcnt[MAIN_WAVES][ZMAX];
-    __shared__ uint32_t s_zbase[MAIN_WAVES][ZMAX];
-    __shared__ uint32_t s_zmax[MAIN_WAVES][ZMAX], s_zmininv[MAIN_WAVES][ZMAX];
-    __shared__ uint32_t s_zoff[ZMAX], s_zcap[ZMAX];
+    __shared__ __align__(16) unsigned char lm[lm_total<SUMS>()];
+    uint32_t* s_cnt = (uint32_t*)(lm + LM_CNT);
+    uint32_t* s_zcur = (uint32_t*)(lm + LM_ZCUR);
+    uint32_t* s_zmax = (uint32_t*)(lm + LM_ZMAX);
+    uint32_t* s_zmin = (uint32_t*)(lm + LM_ZMIN);
+    uint32_t* s_zoff = (uint32_t*)(lm + LM_ZOFF);
+    uint32_t* s_zcap = (uint32_t*)(lm + LM_ZCAP);
 
     const int row = blockIdx.y, tid = threadIdx.x;
     const RowInfo* ri = a.rinfo + row;
     if (exact_pass && !ri->respec) return;
-    const uint32_t lane = lane_id(), wave = tid >> 6, l31 = lane & 31u;
+    const uint32_t lane = lane_id(), wave = tid >> 6;
     RowAcc* ra = a.racc + row;
     const int nz = ri->n_zones;
+    uint2* s_stage = (uint2*)(lm + LM_STAGE) + wave * RING;
     {
         const uint4* src = (const uint4*)(a.table + (size_t)row * NB1);
-        uint4* dst = (uint4*)s_tab;
+        uint4* dst = (uint4*)(lm + LM_TAB);
         for (int i = tid; i < NB1 * 2 / 16; i += MAIN_THREADS) dst[i] = src[i];
+        uint4* z = (uint4*)(lm + LM_CNT);
+        const uint4 zero = make_uint4(0, 0, 0, 0);
+        for (int i = tid; i < (LM_ZOFF - LM_CNT) / 16; i += MAIN_THREADS) z[i] = zero;
+        if (SUMS) {
+            z = (uint4*)(lm + LM_SUM);
+            for (int i = tid; i < GMAX * REP_SUM * 8 / 16; i += MAIN_THREADS) z[i] = zero;
+        }
     }
-    if (SUMS) for (int i = tid; i < GMAX * REP; i += MAIN_THREADS) s_sum[i] = 0ull;
-    for (int i = tid; i < RMAX * REP; i += MAIN_THREADS) s_cnt[i] = 0u;
-    if (tid < ZMAX) {
+    if (tid < 64) {
         s_zoff[tid] = tid < nz ? ri->zone_off[tid] : 0u;
         s_zcap[tid] = tid < nz ? ri->zone_cap[tid] : 0u;
     }
-    if (lane < ZMAX) { s_zcnt[wave][lane] = 0; s_zmax[wave][lane] = 0; s_zmininv[wave][lane] = 0; }
     __syncthreads();
 
     const int64_t c0 = (int64_t)blockIdx.x * a.chunk;
     const int64_t c1 = c0 + a.chunk < a.d ? c0 + a.chunk : a.d;
     RowLoader<DT, VEC> ld(a.g, a.ld, a.d, row);
-    uint32_t* cb = a.cand_bits + (size_t)row * (size_t)a.d;
-    uint32_t* ci = a.cand_idx + (size_t)row * (size_t)a.d;
-    uint32_t nst = 0;      // wave-uniform: staged candidates
+    // this wave's private, worst-case sized part of the scratch list: its candidates in the order met
+    uint2* priv = a.cand_priv + ((size_t)row * a.chunks_per_row + blockIdx.x) * (size_t)a.chunk + (size_t)wave * (a.chunk / MAIN_WAVES);
+    // per-lane byte addresses of the replicated accumulators
+    const uint32_t cnt_lane = (uint32_t)LM_CNT + (lane & 31u) * 4u;
+    const uint32_t sum_lane = (uint32_t)LM_SUM + (lane & 15u) * 8u;
+    uint32_t head = 0, tail = 0;   // wave-uniform: candidates staged / written out so far
     uint32_t maxkey = 0;
-    bool dropped = false;
 
-    // staged candidates of this wave -> the zones' lists (one global counter update per zone)
-    auto flush = [&]() {
+    // whole batches of 64 staged candidates -> the private list (dense stores, nothing to wait for)
+    auto drain = [&](bool all) {
         wave_lds_sync();
-        if ((int)lane < nz) {
-            uint32_t n = s_zcnt[wave][lane];
-            uint32_t base = 0;
-            if (n) {
-                base = atomicAdd(&ra->zone_fill[lane], n);
-                atomicMax(&ra->zone_kmax[lane], s_zmax[wave][lane]);
-                atomicMax(&ra->zone_kmin_inv[lane], s_zmininv[wave][lane]);
-            }
-            s_zbase[wave][lane] = base;
-            s_zcnt[wave][lane] = 0;
+        while (head - tail >= 64u || (all && head != tail)) {
+            const uint32_t i = tail + lane;
+            if (i < head) priv[i] = s_stage[i % (uint32_t)RING];
+            tail = head - tail >= 64u ? tail + 64u : head;
         }
         wave_lds_sync();
-        const uint32_t ns = nst < (uint32_t)ST_CAP ? nst : (uint32_t)ST_CAP;
-        for (uint32_t i = lane; i < ns; i += 64) {
-            const uint32_t meta = s_smeta[wave][i];
-            const uint32_t z = (meta >> 8) & 63u;
-            const uint32_t pos = s_zbase[wave][z] + (meta & 255u);
-            if (pos < s_zcap[z]) {
-                const size_t at = (size_t)s_zoff[z] + pos;
-                cb[at] = s_sbits[wave][i];
-                ci[at] = (uint32_t)c0 + (meta >> 14);
-            } else {
-                dropped = true;
-            }
-        }
-        wave_lds_sync();
-        nst = 0;
     };
 
-    // one 64-element slot: element c of load q of every lane
-    auto slot = [&](uint32_t bits, bool valid, uint32_t rel) {
-        const uint32_t key = key_of_bits(bits);
-        const uint16_t code = s_tab[key >> B1_SHIFT];
-        const bool zone = valid && (code & CODE_ZONE);
-        if (valid && !(code & CODE_ZONE)) {
-            if (SUMS) atomicAdd(&s_sum[(uint32_t)(code & 511u) * REP + l31], (unsigned long long)sig_square(key));
-            atomicAdd(&s_cnt[(uint32_t)(code >> 9) * REP + l31], 1u);
-        }
-        maxkey = key > maxkey ? key : maxkey;
-        const uint64_t m = __ballot(zone);
-        if (m) {
-            if (zone) {
-                const uint32_t z = code & 63u;
-                const uint32_t pos = nst + mbcnt(m);
-                atomicMax(&s_zmax[wave][z], key);
-                atomicMax(&s_zmininv[wave][z], ~key);
-                if (pos < (uint32_t)ST_CAP) {
-                    const uint32_t lr = atomicAdd(&s_zcnt[wave][z], 1u);
-                    s_sbits[wave][pos] = bits;
-                    s_smeta[wave][pos] = (rel << 14) | (z << 8) | lr;
-                } else {   // the stage is full (a step made of candidates): append directly
-                    const uint32_t at = atomicAdd(&ra->zone_fill[z], 1u);
-                    atomicMax(&ra->zone_kmax[z], key);
-                    atomicMax(&ra->zone_kmin_inv[z], ~key);
-                    if (at < s_zcap[z]) {
-                        cb[(size_t)s_zoff[z] + at] = bits;
-                        ci[(size_t)s_zoff[z] + at] = (uint32_t)c0 + rel;
-                    } else {
-                        dropped = true;
-                    }
-                }
-            }
-            nst += (uint32_t)__popcll(m);
-        }
-    };
-
-    // a wave covers 1024 consecutive elements per step, the workgroup 16384; the loads of the next step are
-    // issued before the current one is processed
-    auto load_step = [&](int64_t jw, uint32_t (&b)[16], uint32_t& valid) {
-        valid = 0;
+    // four consecutive elements of every lane (bit c of vmask: element c is inside the chunk): table look-ups
+    // first, then the accumulators (zone buckets carry a dummy group, elements past the end a dummy class, so
+    // there is no branch), then the candidates
+    auto process = [&](const uint32_t (&b)[4], uint32_t rel0, uint32_t vmask) {
+        uint32_t code[4];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int64_t j = jw + q * 256 + (int64_t)lane * 4;
-            uint32_t t[4];
-            const int nv = j < c1 ? ld.load4(j, t) : 0;
+        for (int c = 0; c < 4; ++c) code[c] = *(const uint16_t*)(lm + ((b[c] >> 16) & 0x7FFEu));
+        uint32_t anyz = 0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if (!((vmask >> c) & 1u)) code[c] = (63u << 9) | (uint32_t)G_DUMMY;
+            const uint32_t key = key_of_bits(b[c]);
+            if (SUMS) {
+                const uint32_t hid = (key & 0x7FFFFFu) | 0x800000u;
+                const uint32_t sig = key < hid ? key : hid;   // exponent field 0: no hidden bit, sig = key
+                atomicAdd((unsigned long long*)(lm + (((code[c] & 511u) << 7) + sum_lane)),
+                          (unsigned long long)sig * (unsigned long long)sig);
+            }
+            atomicAdd((uint32_t*)(lm + (((code[c] >> 9) << 7) + cnt_lane)), 1u);
+            maxkey = key > maxkey ? key : maxkey;
+            anyz |= code[c];
+        }
+        if (__ballot(anyz & CODE_ZONE)) {
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                b[q * 4 + c] = t[c];
-                if (c < nv) valid |= 1u << (q * 4 + c);
+                const bool zone = (code[c] & CODE_ZONE) != 0;
+                const uint64_t m = __ballot(zone);
+                if (zone) {
+                    const uint32_t pos = (head + mbcnt(m)) % (uint32_t)RING;
+                    s_stage[pos] = make_uint2(b[c], ((rel0 + c) << 6) | ((code[c] >> 9) & 63u));
+                }
+                head += (uint32_t)__popcll(m);
             }
+            if (head - tail >= 64u) drain(false);
         }
     };
-    uint32_t bA[16], bB[16];
-    uint32_t vA = 0, vB = 0;
-    const int64_t jw0 = c0 + (int64_t)wave * 1024;
-    if (jw0 < c1) load_step(jw0, bA, vA);
-    for (int64_t jw = jw0; jw < c1; jw += MAIN_THREADS * 16) {
-        const int64_t jn = jw + MAIN_THREADS * 16;
-        if (jn < c1) load_step(jn, bB, vB);
-        const uint32_t rel0 = (uint32_t)(jw - c0) + lane * 4;
-        if (jw + 1024 <= c1) {
+
+    // Load n of a wave covers the 256 elements at c0 + (16 n + wave) * 256: the 16 waves read 16 KB side by
+    // side.  Eight loads per lane stay in flight: a slot is refilled as soon as it has been processed.
+    const int64_t span = c1 - c0;
+    const int64_t woff = (int64_t)wave * 256;
+    const int64_t nfull = span >= woff + 256 ? (span - woff - 256) / 4096 + 1 : 0;   // loads with all 256 elements
+    auto issue = [&](int64_t n, uint32_t (&b)[4]) { ld.load4(c0 + (n * 16 + wave) * 256 + (int64_t)lane * 4, b); };
+    auto rel_of = [&](int64_t n) -> uint32_t { return (uint32_t)((n * 16 + wave) * 256) + lane * 4; };
+    uint32_t buf[8][4];
+    int64_t n = 0;
+    if (nfull >= 8) {
 #pragma unroll
-            for (int e = 0; e < 16; ++e) slot(bA[e], true, rel0 + (e >> 2) * 256 + (e & 3));
-        } else {
+        for (int q = 0; q < 8; ++q) issue(q, buf[q]);
+        for (; n + 16 <= nfull; n += 8) {
 #pragma unroll
-            for (int e = 0; e < 16; ++e) slot(bA[e], (vA >> e) & 1u, rel0 + (e >> 2) * 256 + (e & 3));
+            for (int q = 0; q < 8; ++q) {
+                process(buf[q], rel_of(n + q), 15u);
+                issue(n + q + 8, buf[q]);
+            }
         }
-        if (nst > ST_CAP / 2) flush();
 #pragma unroll
-        for (int e = 0; e < 16; ++e) bA[e] = bB[e];
-        vA = vB;
+        for (int q = 0; q < 8; ++q) process(buf[q], rel_of(n + q), 15u);
+        n += 8;
     }
-    flush();
+    for (; n < nfull; ++n) {
+        issue(n, buf[0]);
+        process(buf[0], rel_of(n), 15u);
+    }
+    if (c0 + (nfull * 16 + wave) * 256 < c1) {   // the ragged end of the chunk: at most one partial load per wave
+        const int64_t j = c0 + (nfull * 16 + wave) * 256 + (int64_t)lane * 4;
+        const int nv = j < c1 ? ld.load4(j, buf[0]) : 0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) if (c >= nv) buf[0][c] = 0u;
+        process(buf[0], rel_of(nfull), (1u << nv) - 1u);
+    }
+    drain(true);
     if (__ballot(maxkey >= 0x7F800000u) && lane == 0) atomicOr(a.dev_status, MLMC_DEV_NONFINITE);
+    __threadfence_block();
+    __syncthreads();
+
+    // ---- the workgroup's candidates move from the private lists to the zones' lists: one reservation per zone ----
+    if (tid < nz) {
+        uint32_t total = 0;
+        for (int r = 0; r < REP; ++r) total += s_cnt[(64 + tid) * REP + ((r + tid) & (REP - 1))];
+        s_zcur[tid] = total ? atomicAdd(&ra->zone_fill[tid], total) : 0u;
+    }
+    __syncthreads();
+    uint32_t* cb = a.cand_bits + (size_t)row * (size_t)a.d;
+    uint32_t* ci = a.cand_idx + (size_t)row * (size_t)a.d;
+    bool dropped = false;
+#pragma unroll 4
+    for (uint32_t i = lane; i < head; i += 64) {
+        const uint2 e = priv[i];
+        const uint32_t z = e.y & 63u, key = key_of_bits(e.x);
+        const uint32_t pos = atomicAdd(&s_zcur[z], 1u);
+        atomicMax(&s_zmax[z], key);
+        atomicMax(&s_zmin[z], ~key);
+        if (pos < s_zcap[z]) {
+            const size_t at = (size_t)s_zoff[z] + pos;
+            cb[at] = e.x;
+            ci[at] = (uint32_t)c0 + (e.y >> 6);
+        } else {
+            dropped = true;
+        }
+    }
     if (__ballot(dropped) && lane == 0) {
         // a candidate list overflowed its estimated capacity: redo the row exactly (exact capacities cannot overflow)
         if (ri->exact) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
         else atomicOr((int32_t*)&a.rinfo[row].respec, 1);
     }
     __syncthreads();
+    if (tid < nz && s_zmin[tid]) {   // the zone had candidates here (~key of a 31-bit key is never 0)
+        atomicMax(&ra->zone_kmax[tid], s_zmax[tid]);
+        atomicMax(&ra->zone_kmin_inv[tid], s_zmin[tid]);
+    }
     if (SUMS) {
-        for (int g = tid; g < GMAX; g += MAIN_THREADS) {
+        const unsigned long long* s_sum = (const unsigned long long*)(lm + LM_SUM);
+        for (int g = tid; g < G_DUMMY; g += MAIN_THREADS) {
             unsigned long long lo = 0, hi = 0;
-#pragma unroll 8
-            for (int r = 0; r < REP; ++r) {
-                const unsigned long long v = s_sum[g * REP + ((r + tid) & (REP - 1))];
+#pragma unroll
+            for (int r = 0; r < REP_SUM; ++r) {
+                const unsigned long long v = s_sum[g * REP_SUM + ((r + tid) & (REP_SUM - 1))];
                 lo += v & 0xFFFFFFFFull;
                 hi += v >> 32;
             }
@@ -469,10 +499,10 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
         }
     }
     if (tid < RMAX) {
-        uint32_t n = 0;
-        for (int r = 0; r < REP; ++r) n += s_cnt[tid * REP + ((r + tid) & (REP - 1))];
-        a.chunk_cnt[((size_t)row * a.chunks_per_row + blockIdx.x) * RMAX + tid] = n;
-        if (n) atomicAdd(&ra->region_cnt[tid], n);
+        uint32_t cnt = 0;
+        for (int r = 0; r < REP; ++r) cnt += s_cnt[tid * REP + ((r + tid) & (REP - 1))];
+        a.chunk_cnt[((size_t)row * a.chunks_per_row + blockIdx.x) * RMAX + tid] = cnt;
+        if (cnt) atomicAdd(&ra->region_cnt[tid], cnt);
     }
 }
 
