@@ -114,6 +114,29 @@ struct RowLoader {
         }
         return nv;
     }
+    // four consecutive elements that are all inside the row (j + 4 <= d): no branch, so that several of these
+    // loads can be in flight before the first result is needed
+    __device__ __forceinline__ void load4_full(int64_t j, uint32_t (&b)[4]) const {
+        if (DT == MLMC_F32) {
+            const uint32_t* p = (const uint32_t*)row + j;
+            if (VEC) {
+                uint4 v = *(const uint4*)p;
+                b[0] = v.x; b[1] = v.y; b[2] = v.z; b[3] = v.w;
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) b[c] = p[c];
+            }
+        } else {
+            const uint16_t* p = (const uint16_t*)row + j;
+            if (VEC) {
+                uint2 v = *(const uint2*)p;
+                b[0] = v.x << 16; b[1] = v.x & 0xFFFF0000u; b[2] = v.y << 16; b[3] = v.y & 0xFFFF0000u;
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) b[c] = (uint32_t)p[c] << 16;
+            }
+        }
+    }
     __device__ __forceinline__ uint32_t load1(int64_t j) const {
         if (DT == MLMC_F32) return ((const uint32_t*)row)[j];
         return (uint32_t)((const uint16_t*)row)[j] << 16;

@@ -18,6 +18,8 @@
 //                (Lemma 3.4), then the adaptive level draw (Alg. 3); with known p the draw is done in k_scan
 //   k_write      second read: index-ordered compaction of base band + drawn band (Eq. (6)); a workgroup owns a
 //                chunk whose output offset follows from the per-chunk counts, so no look-back is needed
+#include <type_traits>
+
 #include "mlmc_device.h"
 
 namespace mlmc {
@@ -415,7 +417,7 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
     const int64_t span = c1 - c0;
     const int64_t woff = (int64_t)wave * 256;
     const int64_t nfull = span >= woff + 256 ? (span - woff - 256) / 4096 + 1 : 0;   // loads with all 256 elements
-    auto issue = [&](int64_t n, uint32_t (&b)[4]) { ld.load4(c0 + (n * 16 + wave) * 256 + (int64_t)lane * 4, b); };
+    auto issue = [&](int64_t n, uint32_t (&b)[4]) { ld.load4_full(c0 + (n * 16 + wave) * 256 + (int64_t)lane * 4, b); };
     auto rel_of = [&](int64_t n) -> uint32_t { return (uint32_t)((n * 16 + wave) * 256) + lane * 4; };
     uint32_t buf[8][4];
     int64_t n = 0;
@@ -719,7 +721,10 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
             if (s_pos[tid] < ncol) {
                 const unsigned long long c = s_srt[s_pos[tid]];
                 s_tau[tid] = (uint32_t)(c >> 32);
-                s_jx[tid] = ~(uint32_t)c + 1u;     // inside: equal key and index <= that of the threshold element
+                // inside: equal key and index <= that of the threshold element; when it is the last of its key
+                // (every equal key sits in this bin, hence in this list) the index plays no part
+                const bool last = s_pos[tid] + 1 >= ncol || (uint32_t)(s_srt[s_pos[tid] + 1] >> 32) != s_tau[tid];
+                s_jx[tid] = last ? JX_ALL : ~(uint32_t)c + 1u;
             } else {
                 fail();
             }
@@ -1055,6 +1060,7 @@ __device__ __forceinline__ bool inside_top(const Thr3& th, int i, uint32_t key, 
 constexpr int WR_THREADS = 512;
 constexpr int WR_WAVES = WR_THREADS / 64;
 constexpr int WR_STEP = WR_WAVES * 1024;
+constexpr int WR_STAGE = 1024;   // entries of one step that are gathered in LDS and written densely
 
 template <int DT, bool VEC>
 __global__ __launch_bounds__(WR_THREADS) void k_write(TopkArgs a) {
@@ -1062,6 +1068,7 @@ __global__ __launch_bounds__(WR_THREADS) void k_write(TopkArgs a) {
     __shared__ int64_t s_rowstart, s_rownnz;
     __shared__ uint32_t s_base;
     __shared__ uint32_t s_wemit[2][WR_WAVES];
+    __shared__ uint2 s_out[2][WR_STAGE];
     const int row = blockIdx.y, chunk_id = blockIdx.x, tid = threadIdx.x;
     const uint32_t lane = lane_id(), wave = tid >> 6;
     const RowInfo* ri = a.rinfo + row;
@@ -1145,46 +1152,46 @@ __global__ __launch_bounds__(WR_THREADS) void k_write(TopkArgs a) {
     const int64_t c0 = (int64_t)chunk_id * a.chunk;
     const int64_t c1 = c0 + a.chunk < a.d ? c0 + a.chunk : a.d;
     uint32_t run = s_base;   // entries of this row before the current step
-    uint32_t par = 0;
 
-    auto load_step = [&](int64_t sb, uint32_t (&bits)[16], uint32_t& valid) {
-        const int64_t wbase = sb + (int64_t)wave * 1024;
-        valid = 0;
+    // Thresholds in the form "key > tau" wherever the index plays no part: all entries equal to the key inside
+    // (compare against tau - 1), or none; "cut" marks a threshold whose equal keys are split by index.
+    uint32_t tau[3];
+    bool cut[3], allin[3];
 #pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            uint32_t b[4];
-            const int64_t j = wbase + it * 256 + lane * 4;
-            const int nv = j < c1 ? ld.load4(j, b) : 0;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                bits[it * 4 + c] = b[c];
-                if (c < nv) valid |= 1u << (it * 4 + c);
-            }
-        }
-    };
+    for (int i = 0; i < 3; ++i) {
+        allin[i] = th.jx[i] == JX_ALL && th.tau[i] == 0u;
+        cut[i] = th.jx[i] != 0u && th.jx[i] != JX_ALL;
+        tau[i] = (th.jx[i] == JX_ALL && th.tau[i] != 0u) ? th.tau[i] - 1u : th.tau[i];
+    }
+    const bool any_cut = cut[0] || cut[1] || cut[2];
 
-    uint32_t bitsA[16], bitsB[16];
-    uint32_t validA = 0, validB = 0;
-    if (c0 < c1) load_step(c0, bitsA, validA);
-    for (int64_t sb = c0; sb < c1; sb += WR_STEP) {
-        if (sb + WR_STEP < c1) load_step(sb + WR_STEP, bitsB, validB);
+    // one step: bits of the wave's 1024 elements -> entries at their final positions.  Returns the step's total.
+    auto step = [&](auto with_cuts, const uint32_t (&bits)[16], uint32_t valid, int64_t sb, uint32_t par,
+                    bool& staged) -> uint32_t {
+        constexpr bool CUTS = decltype(with_cuts)::value;
         const int64_t wbase = sb + (int64_t)wave * 1024;
-        uint32_t in0 = 0, emit = 0;
+        bool in0[16], em[16];
+        uint32_t wcount = 0;
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-            const uint32_t key = key_of_bits(bitsA[e]);
-            const uint32_t j = (uint32_t)wbase + (uint32_t)(e >> 2) * 256u + lane * 4u + (uint32_t)(e & 3);
-            const bool i0 = inside_top(th, 0, key, j);
-            const bool em = i0 || (inside_top(th, 2, key, j) && !inside_top(th, 1, key, j));
-            in0 |= (i0 ? 1u : 0u) << e;
-            emit |= (em ? 1u : 0u) << e;
+            const uint32_t key = key_of_bits(bits[e]);
+            bool g[3];
+#pragma unroll
+            for (int i = 0; i < 3; ++i) {
+                g[i] = key > tau[i] || allin[i];
+                if (CUTS) {
+                    const uint32_t j = (uint32_t)wbase + (uint32_t)(e >> 2) * 256u + lane * 4u + (uint32_t)(e & 3);
+                    g[i] = g[i] || (cut[i] && key == th.tau[i] && j < th.jx[i]);
+                }
+            }
+            const bool v = (valid >> e) & 1u;
+            in0[e] = g[0] && v;
+            em[e] = (g[0] || (g[2] && !g[1])) && v;
+            wcount += (uint32_t)__popcll(__ballot(em[e]));
         }
-        in0 &= validA;
-        emit &= validA;
-        const uint32_t wcount = wave_sum(__popc(emit));
         if (lane == 0) s_wemit[par][wave] = wcount;
         __syncthreads();
-        uint32_t wave_pre = run, step_total = 0;
+        uint32_t wave_pre = 0, step_total = 0;
 #pragma unroll
         for (int w2 = 0; w2 < WR_WAVES; ++w2) {
             const uint32_t v = s_wemit[par][w2];
@@ -1193,34 +1200,108 @@ __global__ __launch_bounds__(WR_THREADS) void k_write(TopkArgs a) {
         }
         if ((wave & 3u) == 0 && lane == 0 && wbase < c1) {
             const int64_t tile = wbase / TILE;
-            if (tile < nt) a.tile_off[(size_t)row * (nt + 1) + tile] = wave_pre;
+            if (tile < nt) a.tile_off[(size_t)row * (nt + 1) + tile] = run + wave_pre;
         }
-        int64_t pos0 = rowstart + wave_pre;
+        staged = step_total <= (uint32_t)WR_STAGE;
+        uint32_t pos0 = wave_pre;   // position inside the step of the wave's next group of 256 elements
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
-            uint32_t tot;
-            const uint32_t ex = wave_excl_small(__popc((emit >> (it * 4)) & 0xFu), tot);
-            int64_t pos = pos0 + ex;
+            // entries of lower lanes in this group, then the lane's own entries in element order
+            uint32_t low = 0, tot = 0;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint64_t m = __ballot(em[it * 4 + c]);
+                low = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, low));
+                tot += (uint32_t)__popcll(m);
+            }
+            uint32_t pos = pos0 + low;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 const int e = it * 4 + c;
-                if ((emit >> e) & 1u) {
-                    if (pos < a.capacity) {
-                        const float v = __uint_as_float(bitsA[e]);
-                        a.idx[pos] = (uint32_t)(wbase + it * 256 + lane * 4 + c);
-                        a.val[pos] = ((in0 >> e) & 1u) ? v : __fmul_rn(v, w);
+                if (em[e]) {
+                    const float v = __uint_as_float(bits[e]);
+                    const uint32_t j = (uint32_t)(wbase + it * 256 + lane * 4 + c);
+                    const float out = in0[e] ? v : __fmul_rn(v, w);
+                    if (staged) {
+                        s_out[par][pos] = make_uint2(j, __float_as_uint(out));
+                    } else {
+                        const int64_t at = rowstart + run + pos;
+                        if (at < a.capacity) { a.idx[at] = j; a.val[at] = out; }
                     }
                     ++pos;
                 }
             }
             pos0 += tot;
         }
-        run += step_total;
-        par ^= 1u;
+        return step_total;
+    };
+    // staged entries of a finished step -> the message, dense
+    auto write_out = [&](uint32_t par, uint32_t first, uint32_t count) {
+        for (uint32_t i = tid; i < count; i += WR_THREADS) {
+            const uint2 e = s_out[par][i];
+            const int64_t at = rowstart + first + i;
+            if (at < a.capacity) { a.idx[at] = e.x; a.val[at] = __uint_as_float(e.y); }
+        }
+    };
+
+    uint32_t bitsA[16], bitsB[16];
+    uint32_t par = 0;
+    bool prev_staged = false;
+    uint32_t prev_first = 0, prev_count = 0;
+    auto load_full = [&](int64_t sb, uint32_t (&bits)[16]) {
+        const int64_t wbase = sb + (int64_t)wave * 1024 + lane * 4;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) bitsA[e] = bitsB[e];
-        validA = validB;
+        for (int it = 0; it < 4; ++it) {
+            uint32_t b[4];
+            ld.load4_full(wbase + it * 256, b);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) bits[it * 4 + c] = b[c];
+        }
+    };
+    int64_t sb = c0;
+    if (sb + WR_STEP <= c1) load_full(sb, bitsA);
+    for (; sb + WR_STEP <= c1; sb += WR_STEP) {   // full steps: every element inside the chunk
+        const bool more = sb + 2 * WR_STEP <= c1;
+        if (more) load_full(sb + WR_STEP, bitsB);
+        bool staged;
+        const uint32_t total = any_cut ? step(std::true_type{}, bitsA, 0xFFFFu, sb, par, staged)
+                                       : step(std::false_type{}, bitsA, 0xFFFFu, sb, par, staged);
+        if (prev_staged) write_out(par ^ 1u, prev_first, prev_count);
+        prev_staged = staged;
+        prev_first = run;
+        prev_count = total;
+        run += total;
+        par ^= 1u;
+        if (more) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) bitsA[e] = bitsB[e];
+        }
     }
+    if (sb < c1) {   // the ragged last step
+        const int64_t wbase = sb + (int64_t)wave * 1024;
+        uint32_t valid = 0;
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            uint32_t b[4];
+            const int64_t j = wbase + it * 256 + lane * 4;
+            const int nv = j < c1 ? ld.load4(j, b) : 0;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                bitsA[it * 4 + c] = c < nv ? b[c] : 0u;
+                if (c < nv) valid |= 1u << (it * 4 + c);
+            }
+        }
+        bool staged;
+        const uint32_t total = step(std::true_type{}, bitsA, valid, sb, par, staged);
+        if (prev_staged) write_out(par ^ 1u, prev_first, prev_count);
+        prev_staged = staged;
+        prev_first = run;
+        prev_count = total;
+        run += total;
+        par ^= 1u;
+    }
+    __syncthreads();
+    if (prev_staged) write_out(par ^ 1u, prev_first, prev_count);
     // consistency: the chunk ends where the per-chunk counts say the next one starts
     if (tid == 0) {
         const uint32_t expect = s_base + chunk_entries(chunk_id);
