@@ -1056,10 +1056,9 @@ __device__ __forceinline__ bool inside_top(const Thr3& th, int i, uint32_t key, 
 }
 
 // ---------------------------------------------------------------------------------------------------
-// The message read.  One workgroup per (chunk, row); a wave covers 1024 consecutive elements per step.
+// The message read.  One workgroup per (chunk, row), one tile per step.
 constexpr int WR_THREADS = 512;
 constexpr int WR_WAVES = WR_THREADS / 64;
-constexpr int WR_STEP = WR_WAVES * 1024;
 constexpr int WR_STAGE = 1024;   // entries of one step that are gathered in LDS and written densely
 
 template <int DT, bool VEC>
@@ -1165,16 +1164,18 @@ __global__ __launch_bounds__(WR_THREADS) void k_write(TopkArgs a) {
     }
     const bool any_cut = cut[0] || cut[1] || cut[2];
 
-    // one step: bits of the wave's 1024 elements -> entries at their final positions.  Returns the step's total.
-    auto step = [&](auto with_cuts, const uint32_t (&bits)[16], uint32_t valid, int64_t sb, uint32_t par,
-                    bool& staged) -> uint32_t {
+    // One step = one tile of 4096 elements: a wave covers 512 consecutive elements with two loads.  From the
+    // bits to entries at their final positions; returns the step's total.
+    auto step = [&](auto with_cuts, const uint32_t (&b0)[4], const uint32_t (&b1)[4], uint32_t valid, int64_t sb,
+                    uint32_t par, bool& staged) -> uint32_t {
         constexpr bool CUTS = decltype(with_cuts)::value;
-        const int64_t wbase = sb + (int64_t)wave * 1024;
-        bool in0[16], em[16];
+        const int64_t wbase = sb + (int64_t)wave * 512;
+        bool in0[8], em[8];
         uint32_t wcount = 0;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const uint32_t key = key_of_bits(bits[e]);
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t bits = e < 4 ? b0[e & 3] : b1[e & 3];
+            const uint32_t key = key_of_bits(bits);
             bool g[3];
 #pragma unroll
             for (int i = 0; i < 3; ++i) {
@@ -1198,14 +1199,11 @@ __global__ __launch_bounds__(WR_THREADS) void k_write(TopkArgs a) {
             if ((uint32_t)w2 < wave) wave_pre += v;
             step_total += v;
         }
-        if ((wave & 3u) == 0 && lane == 0 && wbase < c1) {
-            const int64_t tile = wbase / TILE;
-            if (tile < nt) a.tile_off[(size_t)row * (nt + 1) + tile] = run + wave_pre;
-        }
+        if (tid == 0) a.tile_off[(size_t)row * (nt + 1) + sb / TILE] = run;
         staged = step_total <= (uint32_t)WR_STAGE;
         uint32_t pos0 = wave_pre;   // position inside the step of the wave's next group of 256 elements
 #pragma unroll
-        for (int it = 0; it < 4; ++it) {
+        for (int it = 0; it < 2; ++it) {
             // entries of lower lanes in this group, then the lane's own entries in element order
             uint32_t low = 0, tot = 0;
 #pragma unroll
@@ -1219,7 +1217,7 @@ __global__ __launch_bounds__(WR_THREADS) void k_write(TopkArgs a) {
             for (int c = 0; c < 4; ++c) {
                 const int e = it * 4 + c;
                 if (em[e]) {
-                    const float v = __uint_as_float(bits[e]);
+                    const float v = __uint_as_float(it == 0 ? b0[c] : b1[c]);
                     const uint32_t j = (uint32_t)(wbase + it * 256 + lane * 4 + c);
                     const float out = in0[e] ? v : __fmul_rn(v, w);
                     if (staged) {
@@ -1244,61 +1242,62 @@ __global__ __launch_bounds__(WR_THREADS) void k_write(TopkArgs a) {
         }
     };
 
-    uint32_t bitsA[16], bitsB[16];
     uint32_t par = 0;
     bool prev_staged = false;
     uint32_t prev_first = 0, prev_count = 0;
-    auto load_full = [&](int64_t sb, uint32_t (&bits)[16]) {
-        const int64_t wbase = sb + (int64_t)wave * 1024 + lane * 4;
-#pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            uint32_t b[4];
-            ld.load4_full(wbase + it * 256, b);
-#pragma unroll
-            for (int c = 0; c < 4; ++c) bits[it * 4 + c] = b[c];
-        }
-    };
-    int64_t sb = c0;
-    if (sb + WR_STEP <= c1) load_full(sb, bitsA);
-    for (; sb + WR_STEP <= c1; sb += WR_STEP) {   // full steps: every element inside the chunk
-        const bool more = sb + 2 * WR_STEP <= c1;
-        if (more) load_full(sb + WR_STEP, bitsB);
+    // `general` is uniform over the workgroup (the two variants each hold a barrier)
+    auto run_step = [&](const uint32_t (&b0)[4], const uint32_t (&b1)[4], uint32_t valid, int64_t sb, bool general) {
         bool staged;
-        const uint32_t total = any_cut ? step(std::true_type{}, bitsA, 0xFFFFu, sb, par, staged)
-                                       : step(std::false_type{}, bitsA, 0xFFFFu, sb, par, staged);
-        if (prev_staged) write_out(par ^ 1u, prev_first, prev_count);
+        const uint32_t total = general ? step(std::true_type{}, b0, b1, valid, sb, par, staged)
+                                                           : step(std::false_type{}, b0, b1, valid, sb, par, staged);
+        if (prev_staged) write_out(par ^ 1u, prev_first, prev_count);   // the barrier inside step() covers it
         prev_staged = staged;
         prev_first = run;
         prev_count = total;
         run += total;
         par ^= 1u;
-        if (more) {
+    };
+    // four steps (eight loads per lane) are in flight: the loads of step s + 4 are issued as soon as step s is done
+    const int64_t nfull = (c1 - c0) / TILE;
+    auto issue = [&](int64_t s2, uint32_t (&b0)[4], uint32_t (&b1)[4]) {
+        const int64_t j = c0 + s2 * TILE + (int64_t)wave * 512 + lane * 4;
+        ld.load4_full(j, b0);
+        ld.load4_full(j + 256, b1);
+    };
+    uint32_t buf[8][4];
+    int64_t s2 = 0;
+    if (nfull >= 4) {
 #pragma unroll
-            for (int e = 0; e < 16; ++e) bitsA[e] = bitsB[e];
-        }
-    }
-    if (sb < c1) {   // the ragged last step
-        const int64_t wbase = sb + (int64_t)wave * 1024;
-        uint32_t valid = 0;
+        for (int u = 0; u < 4; ++u) issue(u, buf[2 * u], buf[2 * u + 1]);
+        for (; s2 + 8 <= nfull; s2 += 4) {
 #pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            uint32_t b[4];
-            const int64_t j = wbase + it * 256 + lane * 4;
-            const int nv = j < c1 ? ld.load4(j, b) : 0;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                bitsA[it * 4 + c] = c < nv ? b[c] : 0u;
-                if (c < nv) valid |= 1u << (it * 4 + c);
+            for (int u = 0; u < 4; ++u) {
+                run_step(buf[2 * u], buf[2 * u + 1], 0xFFu, c0 + (s2 + u) * TILE, any_cut);
+                issue(s2 + u + 4, buf[2 * u], buf[2 * u + 1]);
             }
         }
-        bool staged;
-        const uint32_t total = step(std::true_type{}, bitsA, valid, sb, par, staged);
-        if (prev_staged) write_out(par ^ 1u, prev_first, prev_count);
-        prev_staged = staged;
-        prev_first = run;
-        prev_count = total;
-        run += total;
-        par ^= 1u;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) run_step(buf[2 * u], buf[2 * u + 1], 0xFFu, c0 + (s2 + u) * TILE, any_cut);
+        s2 += 4;
+    }
+    for (; s2 < nfull; ++s2) {
+        issue(s2, buf[0], buf[1]);
+        run_step(buf[0], buf[1], 0xFFu, c0 + s2 * TILE, any_cut);
+    }
+    if (c0 + nfull * TILE < c1) {   // the ragged last tile of the row
+        const int64_t sb = c0 + nfull * TILE;
+        uint32_t valid = 0;
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int64_t j = sb + (int64_t)wave * 512 + it * 256 + lane * 4;
+            const int nv = j < c1 ? ld.load4(j, buf[it]) : 0;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                if (c >= nv) buf[it][c] = 0u;
+                else valid |= 1u << (it * 4 + c);
+            }
+        }
+        run_step(buf[0], buf[1], valid, sb, true);
     }
     __syncthreads();
     if (prev_staged) write_out(par ^ 1u, prev_first, prev_count);
