@@ -1059,10 +1059,11 @@ __device__ __forceinline__ bool inside_top(const Thr3& th, int i, uint32_t key, 
 // The message read.  One workgroup per (chunk, row), one tile per step.
 constexpr int WR_THREADS = 512;
 constexpr int WR_WAVES = WR_THREADS / 64;
+constexpr int WR_LINES = TILE / (WR_WAVES * 64);   // 64-element lines of a wave per step
 constexpr int WR_STAGE = 1024;   // entries of one step that are gathered in LDS and written densely
 
 template <int DT, bool VEC>
-__global__ __launch_bounds__(WR_THREADS) void k_write(TopkArgs a) {
+__global__ __launch_bounds__(WR_THREADS, 4) void k_write(TopkArgs a) {
     __shared__ unsigned long long s_red[WR_WAVES];
     __shared__ int64_t s_rowstart, s_rownnz;
     __shared__ uint32_t s_base;
@@ -1152,46 +1153,60 @@ __global__ __launch_bounds__(WR_THREADS) void k_write(TopkArgs a) {
     const int64_t c1 = c0 + a.chunk < a.d ? c0 + a.chunk : a.d;
     uint32_t run = s_base;   // entries of this row before the current step
 
-    // Thresholds in the form "key > tau" wherever the index plays no part: all entries equal to the key inside
-    // (compare against tau - 1), or none; "cut" marks a threshold whose equal keys are split by index.
-    uint32_t tau[3];
-    bool cut[3], allin[3];
+    // Thresholds as signed "key > tau" wherever the index plays no part (keys are 31-bit, so -1 admits every
+    // key and 0x7FFFFFFF none): all entries equal to the key inside -> tau - 1; none of them -> tau.  "cut"
+    // marks a threshold whose equal keys are split by index.
+    int32_t tau[3];
+    bool cut[3];
 #pragma unroll
     for (int i = 0; i < 3; ++i) {
-        allin[i] = th.jx[i] == JX_ALL && th.tau[i] == 0u;
+        const uint32_t t = th.tau[i] > 0x7FFFFFFFu ? 0x7FFFFFFFu : th.tau[i];
         cut[i] = th.jx[i] != 0u && th.jx[i] != JX_ALL;
-        tau[i] = (th.jx[i] == JX_ALL && th.tau[i] != 0u) ? th.tau[i] - 1u : th.tau[i];
+        tau[i] = th.jx[i] == JX_ALL ? (int32_t)t - 1 : (int32_t)t;
     }
     const bool any_cut = cut[0] || cut[1] || cut[2];
 
-    // One step = one tile of 4096 elements: a wave covers 512 consecutive elements with two loads.  From the
-    // bits to entries at their final positions; returns the step's total.
-    auto step = [&](auto with_cuts, const uint32_t (&b0)[4], const uint32_t (&b1)[4], uint32_t valid, int64_t sb,
-                    uint32_t par, bool& staged) -> uint32_t {
+    // One step = one tile of 4096 elements; a wave covers 512 consecutive elements as 8 lines of 64, one element
+    // per lane and load, so that the order of the lanes is the order of the indices.  Membership is one wave-wide
+    // mask per line, combined with scalar logic.  The step's entries are gathered in LDS (s_out[par]) and written
+    // densely: normally after the barrier of the next step, at once (window by window) when the step holds more
+    // than WR_STAGE entries.
+    uint32_t par = 0;
+    uint32_t prev_first = 0, prev_count = 0;   // a finished step whose entries still wait in s_out[par ^ 1]
+    // s_out holds {index, input bits}: the weight is applied here, once per entry
+    auto write_out = [&](uint32_t buf_id, uint32_t first, uint32_t count) {
+        for (uint32_t i = tid; i < count; i += WR_THREADS) {
+            const uint2 e = s_out[buf_id][i];
+            const int64_t at = rowstart + first + i;
+            const uint32_t key = key_of_bits(e.y);
+            const bool base = (int32_t)key > tau[0] || (cut[0] && key == th.tau[0] && e.x < th.jx[0]);
+            const float v = __uint_as_float(e.y);
+            if (at < a.capacity) { a.idx[at] = e.x; a.val[at] = base ? v : __fmul_rn(v, w); }
+        }
+    };
+    auto step = [&](auto with_cuts, auto is_ragged, const uint32_t (&b)[WR_LINES], int64_t sb) {
         constexpr bool CUTS = decltype(with_cuts)::value;
-        const int64_t wbase = sb + (int64_t)wave * 512;
-        bool in0[8], em[8];
+        constexpr bool RAGGED = decltype(is_ragged)::value;
+        const uint32_t jbase = (uint32_t)(sb + (int64_t)wave * (64 * WR_LINES)) + lane;
+        auto inside = [&](int i, uint32_t key, uint32_t j) -> bool {
+            bool g = (int32_t)key > tau[i];
+            if (CUTS) g = g || (cut[i] && key == th.tau[i] && j < th.jx[i]);
+            return g;
+        };
+        uint64_t em[WR_LINES];
         uint32_t wcount = 0;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const uint32_t bits = e < 4 ? b0[e & 3] : b1[e & 3];
-            const uint32_t key = key_of_bits(bits);
-            bool g[3];
-#pragma unroll
-            for (int i = 0; i < 3; ++i) {
-                g[i] = key > tau[i] || allin[i];
-                if (CUTS) {
-                    const uint32_t j = (uint32_t)wbase + (uint32_t)(e >> 2) * 256u + lane * 4u + (uint32_t)(e & 3);
-                    g[i] = g[i] || (cut[i] && key == th.tau[i] && j < th.jx[i]);
-                }
-            }
-            const bool v = (valid >> e) & 1u;
-            in0[e] = g[0] && v;
-            em[e] = (g[0] || (g[2] && !g[1])) && v;
-            wcount += (uint32_t)__popcll(__ballot(em[e]));
+        for (int q = 0; q < WR_LINES; ++q) {
+            const uint32_t key = key_of_bits(b[q]);
+            const uint32_t j = jbase + (uint32_t)q * 64u;
+            bool m = inside(0, key, j) || (inside(2, key, j) && !inside(1, key, j));
+            if (RAGGED) m = m && (int64_t)j < c1;
+            em[q] = __ballot(m);
+            wcount += (uint32_t)__popcll(em[q]);
         }
         if (lane == 0) s_wemit[par][wave] = wcount;
         __syncthreads();
+        if (prev_count) write_out(par ^ 1u, prev_first, prev_count);   // every wave is past its staging of that step
         uint32_t wave_pre = 0, step_total = 0;
 #pragma unroll
         for (int w2 = 0; w2 < WR_WAVES; ++w2) {
@@ -1200,107 +1215,73 @@ __global__ __launch_bounds__(WR_THREADS) void k_write(TopkArgs a) {
             step_total += v;
         }
         if (tid == 0) a.tile_off[(size_t)row * (nt + 1) + sb / TILE] = run;
-        staged = step_total <= (uint32_t)WR_STAGE;
-        uint32_t pos0 = wave_pre;   // position inside the step of the wave's next group of 256 elements
+        for (uint32_t wb = 0; wb < step_total; wb += (uint32_t)WR_STAGE) {
+            uint32_t pos0 = wave_pre - wb;   // may wrap: positions outside [0, WR_STAGE) are not in this window
 #pragma unroll
-        for (int it = 0; it < 2; ++it) {
-            // entries of lower lanes in this group, then the lane's own entries in element order
-            uint32_t low = 0, tot = 0;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const uint64_t m = __ballot(em[it * 4 + c]);
-                low = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, low));
-                tot += (uint32_t)__popcll(m);
+            for (int q = 0; q < WR_LINES; ++q) {
+                const uint64_t m = em[q];
+                if (m == 0) continue;   // uniform: nobody in the wave emits from this line
+                const uint32_t pos = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, pos0));
+                if (__builtin_amdgcn_inverse_ballot_w64(m) && pos < (uint32_t)WR_STAGE)
+                    s_out[par][pos] = make_uint2(jbase + (uint32_t)q * 64u, b[q]);
+                pos0 += (uint32_t)__popcll(m);
             }
-            uint32_t pos = pos0 + low;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const int e = it * 4 + c;
-                if (em[e]) {
-                    const float v = __uint_as_float(it == 0 ? b0[c] : b1[c]);
-                    const uint32_t j = (uint32_t)(wbase + it * 256 + lane * 4 + c);
-                    const float out = in0[e] ? v : __fmul_rn(v, w);
-                    if (staged) {
-                        s_out[par][pos] = make_uint2(j, __float_as_uint(out));
-                    } else {
-                        const int64_t at = rowstart + run + pos;
-                        if (at < a.capacity) { a.idx[at] = j; a.val[at] = out; }
-                    }
-                    ++pos;
-                }
+            if (step_total > (uint32_t)WR_STAGE) {   // a dense step: write this window now
+                __syncthreads();
+                const uint32_t cnt = step_total - wb < (uint32_t)WR_STAGE ? step_total - wb : (uint32_t)WR_STAGE;
+                write_out(par, run + wb, cnt);
+                __syncthreads();
             }
-            pos0 += tot;
         }
-        return step_total;
-    };
-    // staged entries of a finished step -> the message, dense
-    auto write_out = [&](uint32_t par, uint32_t first, uint32_t count) {
-        for (uint32_t i = tid; i < count; i += WR_THREADS) {
-            const uint2 e = s_out[par][i];
-            const int64_t at = rowstart + first + i;
-            if (at < a.capacity) { a.idx[at] = e.x; a.val[at] = __uint_as_float(e.y); }
-        }
-    };
-
-    uint32_t par = 0;
-    bool prev_staged = false;
-    uint32_t prev_first = 0, prev_count = 0;
-    // `general` is uniform over the workgroup (the two variants each hold a barrier)
-    auto run_step = [&](const uint32_t (&b0)[4], const uint32_t (&b1)[4], uint32_t valid, int64_t sb, bool general) {
-        bool staged;
-        const uint32_t total = general ? step(std::true_type{}, b0, b1, valid, sb, par, staged)
-                                                           : step(std::false_type{}, b0, b1, valid, sb, par, staged);
-        if (prev_staged) write_out(par ^ 1u, prev_first, prev_count);   // the barrier inside step() covers it
-        prev_staged = staged;
         prev_first = run;
-        prev_count = total;
-        run += total;
+        prev_count = step_total > (uint32_t)WR_STAGE ? 0u : step_total;
+        run += step_total;
         par ^= 1u;
     };
-    // four steps (eight loads per lane) are in flight: the loads of step s + 4 are issued as soon as step s is done
-    const int64_t nfull = (c1 - c0) / TILE;
-    auto issue = [&](int64_t s2, uint32_t (&b0)[4], uint32_t (&b1)[4]) {
-        const int64_t j = c0 + s2 * TILE + (int64_t)wave * 512 + lane * 4;
-        ld.load4_full(j, b0);
-        ld.load4_full(j + 256, b1);
+    // `ragged` and any_cut are uniform over the workgroup (every variant holds barriers)
+    auto run_step = [&](const uint32_t (&b)[WR_LINES], int64_t sb, bool ragged) {
+        if (ragged) step(std::true_type{}, std::true_type{}, b, sb);
+        else if (any_cut) step(std::true_type{}, std::false_type{}, b, sb);
+        else step(std::false_type{}, std::false_type{}, b, sb);
     };
-    uint32_t buf[8][4];
+    // two steps (sixteen loads per lane) are in flight: the loads of step s + 2 are issued as soon as step s is done
+    const int64_t nfull = (c1 - c0) / TILE;
+    auto issue = [&](int64_t s2, uint32_t (&b)[WR_LINES]) {
+        const int64_t j = c0 + s2 * TILE + (int64_t)wave * (64 * WR_LINES) + lane;
+#pragma unroll
+        for (int q = 0; q < WR_LINES; ++q) b[q] = ld.load1(j + q * 64);
+    };
+    uint32_t buf[2][WR_LINES];
     int64_t s2 = 0;
-    if (nfull >= 4) {
+    if (nfull >= 2) {
+        issue(0, buf[0]);
+        issue(1, buf[1]);
+        for (; s2 + 4 <= nfull; s2 += 2) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) issue(u, buf[2 * u], buf[2 * u + 1]);
-        for (; s2 + 8 <= nfull; s2 += 4) {
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                run_step(buf[2 * u], buf[2 * u + 1], 0xFFu, c0 + (s2 + u) * TILE, any_cut);
-                issue(s2 + u + 4, buf[2 * u], buf[2 * u + 1]);
+            for (int u = 0; u < 2; ++u) {
+                run_step(buf[u], c0 + (s2 + u) * TILE, false);
+                issue(s2 + u + 2, buf[u]);
             }
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) run_step(buf[2 * u], buf[2 * u + 1], 0xFFu, c0 + (s2 + u) * TILE, any_cut);
-        s2 += 4;
+        for (int u = 0; u < 2; ++u) run_step(buf[u], c0 + (s2 + u) * TILE, false);
+        s2 += 2;
     }
     for (; s2 < nfull; ++s2) {
-        issue(s2, buf[0], buf[1]);
-        run_step(buf[0], buf[1], 0xFFu, c0 + s2 * TILE, any_cut);
+        issue(s2, buf[0]);
+        run_step(buf[0], c0 + s2 * TILE, false);
     }
     if (c0 + nfull * TILE < c1) {   // the ragged last tile of the row
         const int64_t sb = c0 + nfull * TILE;
-        uint32_t valid = 0;
 #pragma unroll
-        for (int it = 0; it < 2; ++it) {
-            const int64_t j = sb + (int64_t)wave * 512 + it * 256 + lane * 4;
-            const int nv = j < c1 ? ld.load4(j, buf[it]) : 0;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                if (c >= nv) buf[it][c] = 0u;
-                else valid |= 1u << (it * 4 + c);
-            }
+        for (int q = 0; q < WR_LINES; ++q) {
+            const int64_t j = sb + (int64_t)wave * (64 * WR_LINES) + q * 64 + lane;
+            buf[0][q] = j < c1 ? ld.load1(j) : 0u;
         }
-        run_step(buf[0], buf[1], valid, sb, true);
+        run_step(buf[0], sb, true);
     }
     __syncthreads();
-    if (prev_staged) write_out(par ^ 1u, prev_first, prev_count);
+    if (prev_count) write_out(par ^ 1u, prev_first, prev_count);
     // consistency: the chunk ends where the per-chunk counts say the next one starts
     if (tid == 0) {
         const uint32_t expect = s_base + chunk_entries(chunk_id);
