@@ -24,7 +24,7 @@ static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // ---- per-kernel HIP-event timing (off by default; not thread safe) ---------------------------------
 bool g_prof_on = false;
 static const char* const k_names[K_NUM] = {
-    "k_zero", "k_hist", "k_scan", "k_main", "k_finish", "redo_pass", "k_norms", "k_draw", "k_write",
+    "k_zero", "k_hist", "k_scan", "k_main", "k_fhist", "k_finish", "redo_pass", "k_norms", "k_draw", "k_write",
     "k_bits_max", "k_bits_extract", "k_agg_bits", "k_tileoff", "k_agg_sparse"};
 struct ProfPair { int id; hipEvent_t e0, e1; };
 static std::vector<ProfPair> g_pending;
@@ -89,6 +89,9 @@ static void fill_topk_args(const mlmc_plan_t* pl, TopkArgs& a, const void* g, in
     a.table = (uint16_t*)(w + pl->off_table);
     a.chunk_cnt = (uint32_t*)(w + pl->off_chunk_cnt);
     a.chunk_zcnt = (uint32_t*)(w + pl->off_chunk_zcnt);
+    a.zhist = (uint32_t*)(w + pl->off_zhist);
+    a.zpacc = (unsigned long long*)(w + pl->off_zpacc);
+    a.zcol = (unsigned long long*)(w + pl->off_zcol);
     a.tile_off = (uint32_t*)(w + pl->off_tileoff);
     a.norms = (double*)(w + pl->off_norms);
     a.cand_bits = (uint32_t*)(w + pl->off_cand_bits);
@@ -222,6 +225,12 @@ mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dty
         off = align_up(off + sizeof(uint32_t) * NB1 * (size_t)M, 256);
         pl->off_hist2 = off;
         off = align_up(off + sizeof(uint32_t) * NB1 * (size_t)M, 256);
+        pl->off_chunk_zcnt = off;
+        off = align_up(off + sizeof(uint32_t) * ZPMAX * (size_t)pl->chunks_per_row * M, 256);
+        pl->off_zhist = off;
+        off = align_up(off + sizeof(uint32_t) * FH_BINS * ZMAX * (size_t)M, 256);
+        pl->off_zpacc = off;
+        off = align_up(off + sizeof(unsigned long long) * 2 * PIECE_CLASSES * ZMAX * (size_t)M, 256);
     }
     pl->zero_bytes = off;
     pl->off_rinfo = off;
@@ -231,8 +240,8 @@ mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dty
         off = align_up(off + sizeof(uint16_t) * NB1 * (size_t)M, 256);
         pl->off_chunk_cnt = off;
         off = align_up(off + sizeof(uint32_t) * RMAX * (size_t)pl->chunks_per_row * M, 256);
-        pl->off_chunk_zcnt = off;
-        off = align_up(off + sizeof(uint32_t) * ZPMAX * (size_t)pl->chunks_per_row * M, 256);
+        pl->off_zcol = off;
+        off = align_up(off + sizeof(unsigned long long) * COLLECT_CAP * ZMAX * (size_t)M, 256);
         pl->off_tileoff = off;
         off = align_up(off + sizeof(uint32_t) * (size_t)(pl->ntiles + 1) * M, 256);
         pl->off_norms = off;

@@ -21,6 +21,9 @@ constexpr int TILE = MLMC_TILE;
 constexpr int MAX_PLANES = 25;          // 1 sign + at most 24 field planes
 constexpr int CHUNK_MAX = 1 << 18;      // elements per workgroup chunk of the streaming kernels
 constexpr int CHUNKS_MAX = 8192;        // chunks per row
+constexpr int FH_BINS = 2048;           // bins of the zone-relative key histogram of the finish kernels
+constexpr int COLLECT_CAP = 2048;       // candidates of the thresholds' bins that are ranked in LDS
+constexpr int FIN_SLICES = 16;          // workgroups that share one zone's candidate list
 // Slot of a part of a zone in the per-chunk table of zone entries: the part inside the top k_t but outside the
 // top k of the zone's previous threshold has slot t; the part below every threshold of zone z has slot TMAX + z.
 constexpr int ZPMAX = 2 * TMAX;
@@ -61,6 +64,7 @@ struct RowInfo {
 
 struct RowAcc {  // per row, zeroed at the start of every call (and again before a row is redone exactly)
     uint32_t zone_fill[ZMAX];
+    uint32_t zone_colcnt[ZMAX], zone_ticket[ZMAX];   // finish kernel: gathered candidates, slices done
     uint32_t zone_kmax[ZMAX], zone_kmin_inv[ZMAX];   // largest key and largest ~key among the zone's candidates
     uint32_t region_cnt[RMAX];
     uint32_t n_pieces;
@@ -88,7 +92,10 @@ struct TopkArgs {
     uint32_t* cand_idx;      // [M][d]                  indices
     uint2* cand_priv;        // [M][chunks_per_row][chunk] candidates {bits, offset in chunk << 6 | zone} as the waves met them
     uint32_t* chunk_cnt;     // [M][chunks_per_row][RMAX] elements of every region per chunk
-    uint32_t* chunk_zcnt;    // [M][chunks_per_row][ZPMAX] candidates of every part of every zone per chunk
+    uint32_t* chunk_zcnt;    // [M][chunks_per_row][ZPMAX] candidates of every part of every zone per chunk (zeroed per call)
+    uint32_t* zhist;         // [M][ZMAX][FH_BINS] zone-relative key histograms (zeroed per call)
+    unsigned long long* zpacc; // [M][ZMAX][PIECE_CLASSES][2] sums of squared significands per (part, exponent) (zeroed per call)
+    unsigned long long* zcol;  // [M][ZMAX][COLLECT_CAP] candidates of the thresholds' bins
     uint32_t* tile_off;      // [M][ntiles + 1]
     double* norms;           // [M][L]
     double* norms_user;      // optional copy
@@ -133,7 +140,7 @@ struct BitsArgs {
 
 // ---- optional per-kernel timing with HIP events (host side, see mlmc_profile_* in mlmc.h) ----------
 enum KernelId {
-    K_ZERO = 0, K_HIST, K_SCAN, K_MAIN, K_FINISH, K_REDO, K_NORMS, K_DRAW, K_WRITE,
+    K_ZERO = 0, K_HIST, K_SCAN, K_MAIN, K_FHIST, K_FINISH, K_REDO, K_NORMS, K_DRAW, K_WRITE,
     K_BITS_MAX, K_BITS_EXTRACT, K_AGG_BITS, K_TILEOFF, K_AGG_SPARSE, K_NUM
 };
 extern bool g_prof_on;
@@ -163,7 +170,7 @@ struct mlmc_plan_s {
     int chunks_per_row;
     int sample_shift;
     // workspace byte offsets
-    size_t off_racc, off_hist, off_hist2, zero_bytes;  // [0, zero_bytes) is cleared per call
-    size_t off_rinfo, off_table, off_chunk_cnt, off_chunk_zcnt, off_tileoff, off_norms, off_cand_bits, off_cand_idx, off_cand_priv;
+    size_t off_racc, off_hist, off_hist2, off_chunk_zcnt, off_zhist, off_zpacc, zero_bytes;  // [0, zero_bytes) is cleared per call
+    size_t off_rinfo, off_table, off_chunk_cnt, off_zcol, off_tileoff, off_norms, off_cand_bits, off_cand_idx, off_cand_priv;
     size_t ws_bytes;
 };

@@ -133,6 +133,12 @@ __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
         // the row starts over: clear what the first attempt accumulated
         uint32_t* z = (uint32_t*)ra;
         for (int i = tid; i < (int)(sizeof(RowAcc) / 4); i += 1024) z[i] = 0;
+        z = a.zhist + (size_t)row * ZMAX * FH_BINS;
+        for (int i = tid; i < ZMAX * FH_BINS; i += 1024) z[i] = 0;
+        z = (uint32_t*)(a.zpacc + (size_t)row * ZMAX * PIECE_CLASSES * 2);
+        for (int i = tid; i < ZMAX * PIECE_CLASSES * 4; i += 1024) z[i] = 0;
+        z = a.chunk_zcnt + (size_t)row * a.chunks_per_row * ZPMAX;
+        for (int i = tid; i < a.chunks_per_row * ZPMAX; i += 1024) z[i] = 0;
     }
     const bool exact = exact_pass || a.sample_shift == 0;
     const uint32_t* gh = (exact_pass ? a.hist2 : a.hist) + (size_t)row * NB1;
@@ -545,29 +551,76 @@ __device__ __forceinline__ void wave_rank_search(const uint32_t* h, uint32_t r, 
     if (!m) { bin = 0; rin = r; cnt = 0; }
 }
 
-constexpr int FH_BINS = 2048;        // bins of the zone-relative key histogram
-constexpr int COLLECT_CAP = 2048;    // candidates of the thresholds' bins that are ranked in LDS
 constexpr int ZC_CAP = 8192;         // (parts of the zone) x (chunks of the row) counters
 
+// A zone's candidate list is split over up to FIN_SLICES workgroups.
+__device__ __forceinline__ int finish_slices(uint32_t n) {
+    const uint32_t s = (n + 8191u) / 8192u;
+    return s < 1u ? 1 : (s > (uint32_t)FIN_SLICES ? FIN_SLICES : (int)s);
+}
+// Key range of a zone's candidates (kept by the selection read) -> shift of the zone-relative histogram.
+__device__ __forceinline__ int finish_shift(uint32_t kmin, uint32_t kmax) {
+    const uint32_t range = kmax - kmin;
+    return range < (uint32_t)FH_BINS ? 0 : (32 - __clz(range)) - 11;   // (range >> shift) < FH_BINS
+}
+
+// Read 1 of a candidate list, one workgroup per (slice, zone, row): histogram of (key - kmin) >> shift.
+__global__ __launch_bounds__(FN_THREADS) void k_fhist(TopkArgs a, int exact_pass) {
+    __shared__ uint32_t s_fh[FH_BINS];
+    const int slice = blockIdx.x, z = blockIdx.y, row = blockIdx.z, tid = threadIdx.x;
+    const RowInfo* ri = a.rinfo + row;
+    const RowAcc* ra = a.racc + row;
+    if (exact_pass && !ri->respec) return;
+    if (!exact_pass && ri->respec) return;
+    if (z >= ri->n_zones) return;
+    const uint32_t n = ra->zone_fill[z];
+    if (n == 0 || n > ri->zone_cap[z]) return;   // the finish kernel reports it
+    const int S = finish_slices(n);
+    if (slice >= S) return;
+    const uint32_t kmin = ~ra->zone_kmin_inv[z], kmax = ra->zone_kmax[z];
+    if (kmin > kmax) return;
+    const int sh = finish_shift(kmin, kmax);
+    const uint32_t* kb = a.cand_bits + (size_t)row * (size_t)a.d + ri->zone_off[z];
+    const uint32_t per = (n + S - 1) / S;
+    const uint32_t i0 = (uint32_t)slice * per, i1 = i0 + per < n ? i0 + per : n;
+    for (int i = tid; i < FH_BINS; i += FN_THREADS) s_fh[i] = 0;
+    __syncthreads();
+#pragma unroll 8
+    for (uint32_t i = i0 + tid; i < i1; i += FN_THREADS) {
+        const uint32_t b = (key_of_bits(kb[i]) - kmin) >> sh;
+        atomicAdd(&s_fh[b < (uint32_t)FH_BINS ? b : (uint32_t)FH_BINS - 1], 1u);
+    }
+    __syncthreads();
+    uint32_t* zh = a.zhist + ((size_t)row * ZMAX + z) * FH_BINS;
+    for (int i = tid; i < FH_BINS; i += FN_THREADS) {
+        const uint32_t v = s_fh[i];
+        if (v) atomicAdd(&zh[i], v);
+    }
+}
+
+// Read 2, one workgroup per (slice, zone, row): from the zone's histogram the bin of every threshold; the
+// candidates of those bins are gathered (a few hundred) and ranked by the workgroup that finishes last, every other
+// candidate is classified by its bin: per-chunk counts of the zone's parts and exact sums per (part, exponent).
+// When a threshold bin is too full to rank in LDS (massive ties) slice 0 resolves the zone alone by radix select.
 template <bool SUMS>
-__global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pass) {
-    __shared__ uint32_t s_un[TMAX * 256];   // slow path: digit histograms; fast path: candidates of the threshold bins
+__global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pass, int phase) {
+    __shared__ uint32_t s_un[TMAX * 256];   // slow path: digit histograms; phase 1: candidates of the threshold bins
     __shared__ uint32_t s_fh[FH_BINS];
     __shared__ uint8_t s_bincls[FH_BINS];
     __shared__ uint32_t s_zc[ZC_CAP];
     __shared__ unsigned long long s_pacc[SUMS ? PIECE_CLASSES * REP : 1][2];
     __shared__ int32_t s_n, s_ok, s_nsub, s_any, s_fast;
-    __shared__ uint32_t s_ncol;
     __shared__ int32_t s_t[TMAX], s_sub[TMAX];
     __shared__ uint32_t s_res[TMAX], s_pfx[TMAX], s_tau[TMAX], s_q[TMAX], s_eq[TMAX], s_jx[TMAX];
     __shared__ uint32_t s_subpfx[TMAX], s_subtau[TMAX];
     __shared__ uint32_t s_bin[TMAX], s_rin[TMAX], s_bcnt[TMAX], s_pos[TMAX];
+    __shared__ uint32_t s_ncollect;
     uint32_t (*s_hist)[256] = (uint32_t(*)[256])s_un;
     unsigned long long* s_col = (unsigned long long*)s_un;    // [COLLECT_CAP] as collected
     unsigned long long* s_srt = s_col + COLLECT_CAP;          // [COLLECT_CAP] in descending order
     static_assert(sizeof(s_un) >= 2 * COLLECT_CAP * sizeof(unsigned long long), "candidate buffers must fit");
 
-    const int z = blockIdx.x, row = blockIdx.y, tid = threadIdx.x;
+    const int slice = blockIdx.x, z = blockIdx.y, row = blockIdx.z, tid = threadIdx.x;
     const uint32_t lane = lane_id(), wave = tid >> 6, l31 = lane & 31u;
     RowInfo* ri = a.rinfo + row;
     RowAcc* ra = a.racc + row;
@@ -575,6 +628,8 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
     if (!exact_pass && ri->respec) return;   // already refuted (candidate overflow): the row is redone anyway
     if (z >= ri->n_zones) return;
     const uint32_t n = ra->zone_fill[z];
+    const int S = finish_slices(n);
+    if (slice >= S) return;
     const uint32_t* kb = a.cand_bits + (size_t)row * (size_t)a.d + ri->zone_off[z];
     const uint32_t* kj = a.cand_idx + (size_t)row * (size_t)a.d + ri->zone_off[z];
     const int L = a.L;
@@ -606,7 +661,7 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
             if (tot != a.d) ok = false;
         }
         if (m == 0) ok = false;
-        if (!ok) fail();
+        if (!ok && slice == 0) fail();
         s_n = m;
         s_ok = ok ? 1 : 0;
     }
@@ -626,16 +681,21 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
     const int span = Ehi - Elo + 1;
     const int nclass = nparts * span;
     if (kmin > kmax || (SUMS && nclass > PIECE_CLASSES)) {
-        if (tid == 0) fail();
+        if (tid == 0 && slice == 0) fail();
         return;
     }
-    const uint32_t range = kmax - kmin;
-    const int sh = range < (uint32_t)FH_BINS ? 0 : (32 - __clz(range)) - 11;   // (range >> sh) < FH_BINS
+    const int sh = finish_shift(kmin, kmax);
+    uint32_t* zc = a.chunk_zcnt + (size_t)row * nchunks * ZPMAX;
+    unsigned long long* zp = a.zpacc + ((size_t)row * ZMAX + z) * (PIECE_CLASSES * 2);
+    unsigned long long* zcol = a.zcol + ((size_t)row * ZMAX + z) * COLLECT_CAP;
+    auto slot_of = [&](int part) -> int { return part < nthr ? s_t[part] : TMAX + z; };
 
-    for (int i = tid; i < FH_BINS; i += FN_THREADS) s_fh[i] = 0;
+    {
+        const uint32_t* zh = a.zhist + ((size_t)row * ZMAX + z) * FH_BINS;
+        for (int i = tid; i < FH_BINS; i += FN_THREADS) s_fh[i] = zh[i];
+    }
     if (count_fits) for (int i = tid; i < nparts * nchunks; i += FN_THREADS) s_zc[i] = 0;
     if (SUMS) for (int i = tid; i < PIECE_CLASSES * REP * 2; i += FN_THREADS) (&s_pacc[0][0])[i] = 0ull;
-    if (tid == 0) s_ncol = 0;
     __syncthreads();
 
     // what every candidate contributes once its part (number of the zone's thresholds it is NOT inside) is known
@@ -649,15 +709,26 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
             atomicAdd(&s_pacc[cls * REP + l31][1], sq >> 32);
         }
     };
+    // LDS counters and sums -> the zone's totals
+    auto flush_totals = [&](bool with_sums) {
+        __syncthreads();
+        if (count_fits) {
+            for (int i = tid; i < nparts * nchunks; i += FN_THREADS) {
+                const uint32_t v = s_zc[i];
+                if (v) {
+                    const int part = i / nchunks, c = i - part * nchunks;
+                    atomicAdd(&zc[(size_t)c * ZPMAX + slot_of(part)], v);
+                }
+            }
+        }
+        if (SUMS && with_sums && tid < nclass) {
+            unsigned long long lo = 0, hi = 0;
+            for (int r = 0; r < REP; ++r) { lo += s_pacc[tid * REP + r][0]; hi += s_pacc[tid * REP + r][1]; }
+            if (lo) atomicAdd(&zp[tid * 2], lo);
+            if (hi) atomicAdd(&zp[tid * 2 + 1], hi);
+        }
+    };
 
-    // ---- fast path, read 1: histogram of (key - kmin) >> sh; the bin of every threshold ----
-#pragma unroll 8
-    for (uint32_t i = tid; i < n; i += FN_THREADS) {
-        const uint32_t key = key_of_bits(kb[i]);
-        const uint32_t b = (key - kmin) >> sh;
-        atomicAdd(&s_fh[b < (uint32_t)FH_BINS ? b : (uint32_t)FH_BINS - 1], 1u);
-    }
-    __syncthreads();
     for (int u = wave; u < nthr; u += FN_THREADS / 64) {
         int bin;
         uint32_t rin, cnt;
@@ -674,14 +745,20 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
             if (s_rin[u] < 1 || s_rin[u] > s_bcnt[u]) ok = false;
             s_pos[u] = seg + s_rin[u] - 1;
         }
-        if (!ok) fail();
+        if (!ok && slice == 0) fail();
         s_ok = ok ? 1 : 0;
         s_fast = run <= (uint32_t)COLLECT_CAP ? 1 : 0;
+        s_ncollect = run;
     }
     __syncthreads();
     if (!s_ok) return;
+    const bool serial = !s_fast || !count_fits;   // one workgroup does the whole list
+    if (serial && slice != 0) return;
+    const int Seff = serial ? 1 : S;
+    const uint32_t per = (n + Seff - 1) / Seff;
+    const uint32_t i0 = (uint32_t)slice * per, i1 = i0 + per < n ? i0 + per : n;
 
-    if (s_fast) {
+    if (s_fast && phase == 0) {
         for (int b = tid; b < FH_BINS; b += FN_THREADS) {
             int part = 0;
             bool isthr = false;
@@ -692,23 +769,32 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
             s_bincls[b] = isthr ? (uint8_t)0xFF : (uint8_t)part;
         }
         __syncthreads();
-        // ---- read 2: candidates of the thresholds' bins go to LDS, every other one is classified by its bin ----
+        // ---- read 2 ----
 #pragma unroll 4
-        for (uint32_t i = tid; i < n; i += FN_THREADS) {
+        for (uint32_t i = i0 + tid; i < i1; i += FN_THREADS) {
             const uint32_t key = key_of_bits(kb[i]);
             const uint32_t j = kj[i];
             uint32_t b = (key - kmin) >> sh;
             b = b < (uint32_t)FH_BINS ? b : (uint32_t)FH_BINS - 1;
             const uint32_t cls = s_bincls[b];
             if (cls == 0xFFu) {
-                const uint32_t at = atomicAdd(&s_ncol, 1u);
-                if (at < (uint32_t)COLLECT_CAP) s_col[at] = ((unsigned long long)key << 32) | (uint32_t)~j;
+                const uint32_t at = atomicAdd(&ra->zone_colcnt[z], 1u);
+                if (at < (uint32_t)COLLECT_CAP) zcol[at] = ((unsigned long long)key << 32) | (uint32_t)~j;
             } else {
                 classify((int)cls, key, j);
             }
         }
+        flush_totals(true);
+        return;   // phase 1 (the next launch) ranks the gathered candidates
+    }
+    if (s_fast) {
+        const uint32_t ncol = s_ncollect;
+        if (ra->zone_colcnt[z] != ncol) {
+            if (tid == 0) fail();
+            return;
+        }
+        for (uint32_t e = tid; e < ncol; e += FN_THREADS) s_col[e] = zcol[e];
         __syncthreads();
-        const uint32_t ncol = s_ncol < (uint32_t)COLLECT_CAP ? s_ncol : (uint32_t)COLLECT_CAP;
         // descending order of (key, lower index first) by counting: composites are distinct
         for (uint32_t e = tid; e < ncol; e += FN_THREADS) {
             const unsigned long long c = s_col[e];
@@ -718,16 +804,12 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
         }
         __syncthreads();
         if (tid < nthr) {
-            if (s_pos[tid] < ncol) {
-                const unsigned long long c = s_srt[s_pos[tid]];
-                s_tau[tid] = (uint32_t)(c >> 32);
-                // inside: equal key and index <= that of the threshold element; when it is the last of its key
-                // (every equal key sits in this bin, hence in this list) the index plays no part
-                const bool last = s_pos[tid] + 1 >= ncol || (uint32_t)(s_srt[s_pos[tid] + 1] >> 32) != s_tau[tid];
-                s_jx[tid] = last ? JX_ALL : ~(uint32_t)c + 1u;
-            } else {
-                fail();
-            }
+            const unsigned long long c = s_srt[s_pos[tid]];
+            s_tau[tid] = (uint32_t)(c >> 32);
+            // inside: equal key and index <= that of the threshold element; when it is the last of its key
+            // (every equal key sits in this bin, hence in this list) the index plays no part
+            const bool last = s_pos[tid] + 1 >= ncol || (uint32_t)(s_srt[s_pos[tid] + 1] >> 32) != s_tau[tid];
+            s_jx[tid] = last ? JX_ALL : ~(uint32_t)c + 1u;
         }
         __syncthreads();
         for (uint32_t e = tid; e < ncol; e += FN_THREADS) {
@@ -736,7 +818,8 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
             const unsigned long long c = s_srt[e];
             classify(part, (uint32_t)(c >> 32), ~(uint32_t)c);
         }
-    } else {
+        flush_totals(false);   // their sums stay in LDS and are added to the zone's totals below
+    } else if (phase == 0) {
         // ---- slow path (a threshold bin too full to rank in LDS, e.g. massive ties): radix select on the
         //      keys, digits of 8, 8, 8, 7 bits from the top, then on the indices of the entries equal to the key ----
         for (int pass = 0; pass < 4; ++pass) {
@@ -857,21 +940,17 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
                 classify(part, key, j);
             }
         }
+        flush_totals(true);
+        __syncthreads();
+        if (SUMS) for (int i = tid; i < PIECE_CLASSES * REP * 2; i += FN_THREADS) (&s_pacc[0][0])[i] = 0ull;
     }
     __syncthreads();
-    if (tid < nthr) {
+    const bool resolved_here = s_fast ? phase == 1 : phase == 0;   // this launch found the zone's thresholds
+    if (resolved_here && tid < nthr) {
         ri->thr_tau[s_t[tid]] = s_tau[tid];
         ri->thr_jx[s_t[tid]] = s_jx[tid];
     }
-    // ---- per-chunk counts of every part (the message read turns them into output offsets) ----
-    uint32_t* zc = a.chunk_zcnt + (size_t)row * nchunks * ZPMAX;
-    auto slot_of = [&](int part) -> int { return part < nthr ? s_t[part] : TMAX + z; };
-    if (count_fits) {
-        for (int i = tid; i < nparts * nchunks; i += FN_THREADS) {
-            const int part = i / nchunks, c = i - part * nchunks;
-            zc[(size_t)c * ZPMAX + slot_of(part)] = s_zc[i];
-        }
-    } else {
+    if (resolved_here && !count_fits) {
         // long rows with many thresholds in one zone: a few parts at a time, one more read of the list each
         const int ppp = ZC_CAP / nchunks;   // >= 1: a row has at most CHUNKS_MAX = ZC_CAP chunks
         for (int p0 = 0; p0 < nparts; p0 += ppp) {
@@ -897,11 +976,13 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
             }
         }
     }
-    if (!SUMS) return;
+    if (!SUMS || phase == 0) return;
 
-    // ---- exact sums of the parts: one piece per (part, exponent) ----
+    // ---- exact sums of the parts: one piece per (part, exponent): the zone's totals of the earlier launch plus
+    //      what the ranked candidates added here ----
+    __syncthreads();
     if (tid < nclass) {
-        unsigned long long lo = 0, hi = 0;
+        unsigned long long lo = zp[tid * 2], hi = zp[tid * 2 + 1];
         for (int r = 0; r < REP; ++r) { lo += s_pacc[tid * REP + r][0]; hi += s_pacc[tid * REP + r][1]; }
         hi += lo >> 32;
         lo &= 0xFFFFFFFFull;
@@ -1298,7 +1379,7 @@ __global__ __launch_bounds__(WR_THREADS, 4) void k_write(TopkArgs a) {
 template <int DT, bool VEC>
 static mlmc_status launch_select(const mlmc_plan_t* pl, const TopkArgs& a, bool sums, hipStream_t st) {
     const dim3 mgrid(pl->chunks_per_row, pl->M);
-    const dim3 fgrid(pl->L + 1, pl->M);
+    const dim3 fgrid(FIN_SLICES, pl->L + 1, pl->M);
     const int rounds = pl->sample_shift > 0 ? 2 : 1;   // second round: rows whose sampled zones were refuted
     for (int exact_pass = 0; exact_pass < rounds; ++exact_pass) {
         // histogram workgroups per row: enough to spread the row, few enough that the 64 KB flushes stay cheap
@@ -1315,8 +1396,12 @@ static mlmc_status launch_select(const mlmc_plan_t* pl, const TopkArgs& a, bool 
         MLMC_LAUNCH(ks, st, k_scan<<<pl->M, 1024, 0, st>>>(a, exact_pass));
         if (sums) MLMC_LAUNCH(km, st, k_main<DT, VEC, true><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
         else MLMC_LAUNCH(km, st, k_main<DT, VEC, false><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
-        if (sums) MLMC_LAUNCH(kf, st, k_finish<true><<<fgrid, FN_THREADS, 0, st>>>(a, exact_pass));
-        else MLMC_LAUNCH(kf, st, k_finish<false><<<fgrid, FN_THREADS, 0, st>>>(a, exact_pass));
+        MLMC_LAUNCH(exact_pass ? K_REDO : K_FHIST, st, k_fhist<<<fgrid, FN_THREADS, 0, st>>>(a, exact_pass));
+        for (int phase = 0; phase < 2; ++phase) {
+            const dim3 g2 = phase == 0 ? fgrid : dim3(1, pl->L + 1, pl->M);
+            if (sums) MLMC_LAUNCH(kf, st, k_finish<true><<<g2, FN_THREADS, 0, st>>>(a, exact_pass, phase));
+            else MLMC_LAUNCH(kf, st, k_finish<false><<<g2, FN_THREADS, 0, st>>>(a, exact_pass, phase));
+        }
     }
     if (sums) MLMC_LAUNCH(K_NORMS, st, k_norms<<<pl->M, 256, 0, st>>>(a));
     return MLMC_OK;
