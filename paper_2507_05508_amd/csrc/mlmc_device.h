@@ -67,6 +67,25 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* lds, u
     return lds[wave] + inc - v;
 }
 
+// Strided loop over [i0, i1) for a group of NT threads (this thread starts at i0 + t): U loads are issued back to
+// back before the first is consumed.  A loop whose every load sits behind its own bounds check is compiled to one
+// load, one wait per iteration; here only whole batches take the fast path and the ragged rest is checked.
+template <int U, int NT, class Load, class Proc>
+__device__ __forceinline__ void batched_loop(uint32_t i0, uint32_t i1, uint32_t t, Load load, Proc proc) {
+    uint32_t i = i0 + t;
+    if (i1 >= (uint32_t)((U - 1) * NT)) {
+        const uint32_t lim = i1 - (uint32_t)((U - 1) * NT);   // i + (U-1)*NT < i1  <=>  i < lim
+        for (; i < lim; i += (uint32_t)(U * NT)) {
+            decltype(load(0u)) v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) v[u] = load(i + (uint32_t)(u * NT));
+#pragma unroll
+            for (int u = 0; u < U; ++u) proc(i + (uint32_t)(u * NT), v[u]);
+        }
+    }
+    for (; i < i1; i += (uint32_t)NT) proc(i, load(i));
+}
+
 // ---- keys ----------------------------------------------------------------------------------------
 __device__ __forceinline__ uint32_t key_of_bits(uint32_t fp32_bits) { return fp32_bits & 0x7FFFFFFFu; }
 

@@ -23,7 +23,9 @@ constexpr int CHUNK_MAX = 1 << 18;      // elements per workgroup chunk of the s
 constexpr int CHUNKS_MAX = 8192;        // chunks per row
 constexpr int FH_BINS = 2048;           // bins of the zone-relative key histogram of the finish kernels
 constexpr int COLLECT_CAP = 2048;       // candidates of the thresholds' bins that are ranked in LDS
-constexpr int FIN_SLICES = 16;          // workgroups that share one zone's candidate list
+constexpr int FIN_SLICES = 16;          // a zone's candidate list is worked on in up to this many slices ...
+constexpr int FIN_SLICE = 32768;        // ... of at least this many candidates
+constexpr int FIN_WGS = 32;             // workgroups per row that take the (zone, slice) items in turn
 // Slot of a part of a zone in the per-chunk table of zone entries: the part inside the top k_t but outside the
 // top k of the zone's previous threshold has slot t; the part below every threshold of zone z has slot TMAX + z.
 constexpr int ZPMAX = 2 * TMAX;
@@ -140,7 +142,7 @@ struct BitsArgs {
 
 // ---- optional per-kernel timing with HIP events (host side, see mlmc_profile_* in mlmc.h) ----------
 enum KernelId {
-    K_ZERO = 0, K_HIST, K_SCAN, K_MAIN, K_FHIST, K_FINISH, K_REDO, K_NORMS, K_DRAW, K_WRITE,
+    K_ZERO = 0, K_HIST, K_SCAN, K_MAIN, K_FHIST, K_FINISH, K_FINISH1, K_REDO, K_NORMS, K_DRAW, K_WRITE,
     K_BITS_MAX, K_BITS_EXTRACT, K_AGG_BITS, K_TILEOFF, K_AGG_SPARSE, K_NUM
 };
 extern bool g_prof_on;

@@ -55,21 +55,28 @@ __global__ __launch_bounds__(HIST_THREADS) void k_hist(TopkArgs a, int exact_pas
     RowLoader<DT, VEC> ld(a.g, a.ld, a.d, row);
     const uint32_t lane = lane_id(), wave = threadIdx.x >> 6;
     uint32_t maxkey = 0;
+    auto count4 = [&](const uint32_t (&b)[4], int nv) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if (c < nv) {
+                const uint32_t key = key_of_bits(b[c]);
+                atomicAdd(&h[key >> B1_SHIFT], 1u);
+                maxkey = key > maxkey ? key : maxkey;
+            }
+        }
+    };
     for (int64_t i = i0 + wave; i < i1; i += HIST_THREADS / 64) {
         const int64_t base = (first + i * S) * 1024 + lane * 4;
         uint32_t b[4][4];
-        int nv[4];
+        if ((first + i * S + 1) * 1024 <= a.d) {   // a whole block: four loads in flight
 #pragma unroll
-        for (int q = 0; q < 4; ++q) nv[q] = ld.load4(base + q * 256, b[q]);
+            for (int q = 0; q < 4; ++q) ld.load4_full(base + q * 256, b[q]);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                if (c < nv[q]) {
-                    uint32_t key = key_of_bits(b[q][c]);
-                    atomicAdd(&h[key >> B1_SHIFT], 1u);
-                    maxkey = key > maxkey ? key : maxkey;
-                }
+            for (int q = 0; q < 4; ++q) count4(b[q], 4);
+        } else {
+            for (int q = 0; q < 4; ++q) {
+                const int nv = ld.load4(base + q * 256, b[q]);
+                count4(b[q], nv);
             }
         }
     }
@@ -467,9 +474,7 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
     uint32_t* cb = a.cand_bits + (size_t)row * (size_t)a.d;
     uint32_t* ci = a.cand_idx + (size_t)row * (size_t)a.d;
     bool dropped = false;
-#pragma unroll 4
-    for (uint32_t i = lane; i < head; i += 64) {
-        const uint2 e = priv[i];
+    batched_loop<8, 64>(0u, head, lane, [&](uint32_t i) { return priv[i]; }, [&](uint32_t, uint2 e) {
         const uint32_t z = e.y & 63u, key = key_of_bits(e.x);
         const uint32_t pos = atomicAdd(&s_zcur[z], 1u);
         atomicMax(&s_zmax[z], key);
@@ -481,7 +486,7 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
         } else {
             dropped = true;
         }
-    }
+    });
     if (__ballot(dropped) && lane == 0) {
         // a candidate list overflowed its estimated capacity: redo the row exactly (exact capacities cannot overflow)
         if (ri->exact) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
@@ -555,7 +560,7 @@ constexpr int ZC_CAP = 8192;         // (parts of the zone) x (chunks of the row
 
 // A zone's candidate list is split over up to FIN_SLICES workgroups.
 __device__ __forceinline__ int finish_slices(uint32_t n) {
-    const uint32_t s = (n + 8191u) / 8192u;
+    const uint32_t s = (n + (uint32_t)FIN_SLICE - 1u) / (uint32_t)FIN_SLICE;
     return s < 1u ? 1 : (s > (uint32_t)FIN_SLICES ? FIN_SLICES : (int)s);
 }
 // Key range of a zone's candidates (kept by the selection read) -> shift of the zone-relative histogram.
@@ -564,37 +569,64 @@ __device__ __forceinline__ int finish_shift(uint32_t kmin, uint32_t kmax) {
     return range < (uint32_t)FH_BINS ? 0 : (32 - __clz(range)) - 11;   // (range >> shift) < FH_BINS
 }
 
-// Read 1 of a candidate list, one workgroup per (slice, zone, row): histogram of (key - kmin) >> shift.
+// The work of the finish kernels is a list of items (zone, slice) per row; the workgroups of a row take them in
+// turn.  Fills s_fill / s_rcnt (zone list lengths, region counts) and s_first (first item of every zone).
+__device__ __forceinline__ int finish_items(const RowInfo* ri, const RowAcc* ra, bool sliced, uint32_t* s_fill,
+                                            uint32_t* s_rcnt, int32_t* s_first) {
+    const int tid = threadIdx.x, nz = ri->n_zones;
+    if (tid < nz) s_fill[tid] = ra->zone_fill[tid];
+    if (tid >= 64 && tid - 64 <= nz) s_rcnt[tid - 64] = ra->region_cnt[tid - 64];
+    __syncthreads();
+    if (tid == 0) {
+        int run = 0;
+        for (int z = 0; z < nz; ++z) {
+            s_first[z] = run;
+            run += sliced ? finish_slices(s_fill[z]) : 1;
+        }
+        s_first[nz] = run;
+    }
+    __syncthreads();
+    return s_first[nz];
+}
+
+// Read 1 of a candidate list, one item per (zone, slice): histogram of (key - kmin) >> shift.
 __global__ __launch_bounds__(FN_THREADS) void k_fhist(TopkArgs a, int exact_pass) {
     __shared__ uint32_t s_fh[FH_BINS];
-    const int slice = blockIdx.x, z = blockIdx.y, row = blockIdx.z, tid = threadIdx.x;
+    __shared__ uint32_t s_fill[ZMAX], s_rcnt[RMAX];
+    __shared__ int32_t s_first[ZMAX + 1];
+    const int row = blockIdx.y, tid = threadIdx.x;
     const RowInfo* ri = a.rinfo + row;
     const RowAcc* ra = a.racc + row;
     if (exact_pass && !ri->respec) return;
     if (!exact_pass && ri->respec) return;
-    if (z >= ri->n_zones) return;
-    const uint32_t n = ra->zone_fill[z];
-    if (n == 0 || n > ri->zone_cap[z]) return;   // the finish kernel reports it
-    const int S = finish_slices(n);
-    if (slice >= S) return;
-    const uint32_t kmin = ~ra->zone_kmin_inv[z], kmax = ra->zone_kmax[z];
-    if (kmin > kmax) return;
-    const int sh = finish_shift(kmin, kmax);
-    const uint32_t* kb = a.cand_bits + (size_t)row * (size_t)a.d + ri->zone_off[z];
-    const uint32_t per = (n + S - 1) / S;
-    const uint32_t i0 = (uint32_t)slice * per, i1 = i0 + per < n ? i0 + per : n;
-    for (int i = tid; i < FH_BINS; i += FN_THREADS) s_fh[i] = 0;
-    __syncthreads();
-#pragma unroll 8
-    for (uint32_t i = i0 + tid; i < i1; i += FN_THREADS) {
-        const uint32_t b = (key_of_bits(kb[i]) - kmin) >> sh;
-        atomicAdd(&s_fh[b < (uint32_t)FH_BINS ? b : (uint32_t)FH_BINS - 1], 1u);
-    }
-    __syncthreads();
-    uint32_t* zh = a.zhist + ((size_t)row * ZMAX + z) * FH_BINS;
-    for (int i = tid; i < FH_BINS; i += FN_THREADS) {
-        const uint32_t v = s_fh[i];
-        if (v) atomicAdd(&zh[i], v);
+    const int nz = ri->n_zones;
+    const int nitems = finish_items(ri, ra, true, s_fill, s_rcnt, s_first);
+    for (int item = blockIdx.x; item < nitems; item += gridDim.x) {
+        int z = 0;
+        while (z + 1 < nz && s_first[z + 1] <= item) ++z;
+        const int slice = item - s_first[z];
+        const uint32_t n = s_fill[z];
+        if (n == 0 || n > ri->zone_cap[z]) continue;   // the finish kernel reports it
+        const int S = finish_slices(n);
+        const uint32_t kmin = ~ra->zone_kmin_inv[z], kmax = ra->zone_kmax[z];
+        if (kmin > kmax) continue;
+        const int sh = finish_shift(kmin, kmax);
+        const uint32_t* kb = a.cand_bits + (size_t)row * (size_t)a.d + ri->zone_off[z];
+        const uint32_t per = (n + S - 1) / S;
+        const uint32_t i0 = (uint32_t)slice * per, i1 = i0 + per < n ? i0 + per : n;
+        __syncthreads();
+        for (int i = tid; i < FH_BINS; i += FN_THREADS) s_fh[i] = 0;
+        __syncthreads();
+        batched_loop<8, FN_THREADS>(i0, i1, (uint32_t)tid, [&](uint32_t i) { return kb[i]; }, [&](uint32_t, uint32_t bits) {
+            const uint32_t b = (key_of_bits(bits) - kmin) >> sh;
+            atomicAdd(&s_fh[b < (uint32_t)FH_BINS ? b : (uint32_t)FH_BINS - 1], 1u);
+        });
+        __syncthreads();
+        uint32_t* zh = a.zhist + ((size_t)row * ZMAX + z) * FH_BINS;
+        for (int i = tid; i < FH_BINS; i += FN_THREADS) {
+            const uint32_t v = s_fh[i];
+            if (v) atomicAdd(&zh[i], v);
+        }
     }
 }
 
@@ -620,31 +652,34 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
     unsigned long long* s_srt = s_col + COLLECT_CAP;          // [COLLECT_CAP] in descending order
     static_assert(sizeof(s_un) >= 2 * COLLECT_CAP * sizeof(unsigned long long), "candidate buffers must fit");
 
-    const int slice = blockIdx.x, z = blockIdx.y, row = blockIdx.z, tid = threadIdx.x;
+    __shared__ uint32_t s_fill[ZMAX], s_rcnt[RMAX];
+    __shared__ int32_t s_first[ZMAX + 1];
+    const int row = blockIdx.y, tid = threadIdx.x;
     const uint32_t lane = lane_id(), wave = tid >> 6, l31 = lane & 31u;
     RowInfo* ri = a.rinfo + row;
     RowAcc* ra = a.racc + row;
     if (exact_pass && !ri->respec) return;
     if (!exact_pass && ri->respec) return;   // already refuted (candidate overflow): the row is redone anyway
-    if (z >= ri->n_zones) return;
-    const uint32_t n = ra->zone_fill[z];
-    const int S = finish_slices(n);
-    if (slice >= S) return;
-    const uint32_t* kb = a.cand_bits + (size_t)row * (size_t)a.d + ri->zone_off[z];
-    const uint32_t* kj = a.cand_idx + (size_t)row * (size_t)a.d + ri->zone_off[z];
     const int L = a.L;
+    const int nzones = ri->n_zones;
     const int fail_bit = ri->exact ? 1 : 0;   // what a refuted check means: 1 internal error, 0 redo the row
-
     auto fail = [&]() {   // called by one thread
         if (fail_bit) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
         else atomicOr((int32_t*)&ri->respec, 1);
     };
+    const int nitems = finish_items(ri, ra, phase == 0, s_fill, s_rcnt, s_first);
+
+    auto run_item = [&](const int z, const int slice) {
+    const uint32_t n = s_fill[z];
+    const int S = finish_slices(n);
+    const uint32_t* kb = a.cand_bits + (size_t)row * (size_t)a.d + ri->zone_off[z];
+    const uint32_t* kj = a.cand_idx + (size_t)row * (size_t)a.d + ri->zone_off[z];
 
     if (tid == 0) {
         // elements strictly above the zone: regions 0..z and zones 0..z-1
         int64_t above = 0;
-        for (int i = 0; i <= z; ++i) above += ra->region_cnt[i];
-        for (int i = 0; i < z; ++i) above += ra->zone_fill[i];
+        for (int i = 0; i <= z; ++i) above += s_rcnt[i];
+        for (int i = 0; i < z; ++i) above += s_fill[i];
         bool ok = n <= ri->zone_cap[z];
         int m = 0;
         for (int t = ri->zone_t0[z]; t <= ri->zone_t1[z] && t <= L; ++t) {
@@ -656,8 +691,8 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
             s_pfx[m] = 0;
             ++m;
         }
-        if (z == ri->n_zones - 1) {   // the last zone also checks that nothing was lost
-            int64_t tot = above + n + ra->region_cnt[z + 1];
+        if (z == nzones - 1) {   // the last zone also checks that nothing was lost
+            int64_t tot = above + n + s_rcnt[z + 1];
             if (tot != a.d) ok = false;
         }
         if (m == 0) ok = false;
@@ -758,7 +793,10 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
     const uint32_t per = (n + Seff - 1) / Seff;
     const uint32_t i0 = (uint32_t)slice * per, i1 = i0 + per < n ? i0 + per : n;
 
+    const uint32_t ncollect_zone = s_ncollect;   // candidates in the thresholds' bins, all slices together
+    __syncthreads();
     if (s_fast && phase == 0) {
+        if (tid == 0) s_ncollect = 0;
         for (int b = tid; b < FH_BINS; b += FN_THREADS) {
             int part = 0;
             bool isthr = false;
@@ -770,25 +808,33 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
         }
         __syncthreads();
         // ---- read 2 ----
-#pragma unroll 4
-        for (uint32_t i = i0 + tid; i < i1; i += FN_THREADS) {
-            const uint32_t key = key_of_bits(kb[i]);
-            const uint32_t j = kj[i];
+        batched_loop<8, FN_THREADS>(i0, i1, (uint32_t)tid, [&](uint32_t i) { return make_uint2(kb[i], kj[i]); },
+                                    [&](uint32_t, uint2 e) {
+            const uint32_t key = key_of_bits(e.x);
+            const uint32_t j = e.y;
             uint32_t b = (key - kmin) >> sh;
             b = b < (uint32_t)FH_BINS ? b : (uint32_t)FH_BINS - 1;
             const uint32_t cls = s_bincls[b];
-            if (cls == 0xFFu) {
-                const uint32_t at = atomicAdd(&ra->zone_colcnt[z], 1u);
-                if (at < (uint32_t)COLLECT_CAP) zcol[at] = ((unsigned long long)key << 32) | (uint32_t)~j;
+            if (cls == 0xFFu) {   // gathered in LDS first: one reservation in the zone's list per workgroup
+                const uint32_t at = atomicAdd(&s_ncollect, 1u);
+                if (at < (uint32_t)COLLECT_CAP) s_col[at] = ((unsigned long long)key << 32) | (uint32_t)~j;
             } else {
                 classify((int)cls, key, j);
             }
-        }
+        });
+        __syncthreads();
+        const uint32_t mine = s_ncollect;   // <= COLLECT_CAP: the zone's threshold bins hold no more
+        __syncthreads();
+        if (tid == 0) s_ncollect = mine ? atomicAdd(&ra->zone_colcnt[z], mine) : 0u;
+        __syncthreads();
+        const uint32_t at0 = s_ncollect;
+        for (uint32_t e = tid; e < mine; e += FN_THREADS)
+            if (at0 + e < (uint32_t)COLLECT_CAP) zcol[at0 + e] = s_col[e];
         flush_totals(true);
         return;   // phase 1 (the next launch) ranks the gathered candidates
     }
     if (s_fast) {
-        const uint32_t ncol = s_ncollect;
+        const uint32_t ncol = ncollect_zone;
         if (ra->zone_colcnt[z] != ncol) {
             if (tid == 0) fail();
             return;
@@ -839,23 +885,22 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
             __syncthreads();
             const int nsub = s_nsub;
             if (pass == 0) {
-#pragma unroll 4
-                for (uint32_t i = tid; i < n; i += FN_THREADS) atomicAdd(&s_hist[0][(key_of_bits(kb[i]) >> 23) & 255u], 1u);
+                batched_loop<8, FN_THREADS>(0u, n, (uint32_t)tid, [&](uint32_t i) { return kb[i]; }, [&](uint32_t, uint32_t bits) {
+                    atomicAdd(&s_hist[0][(key_of_bits(bits) >> 23) & 255u], 1u);
+                });
             } else if (nsub == 1) {
                 const uint32_t pf = s_subpfx[0] >> hb;
-#pragma unroll 4
-                for (uint32_t i = tid; i < n; i += FN_THREADS) {
-                    const uint32_t key = key_of_bits(kb[i]);
+                batched_loop<8, FN_THREADS>(0u, n, (uint32_t)tid, [&](uint32_t i) { return kb[i]; }, [&](uint32_t, uint32_t bits) {
+                    const uint32_t key = key_of_bits(bits);
                     if ((key >> hb) == pf) atomicAdd(&s_hist[0][(key >> shift) & mask], 1u);
-                }
+                });
             } else {
-#pragma unroll 2
-                for (uint32_t i = tid; i < n; i += FN_THREADS) {
-                    const uint32_t key = key_of_bits(kb[i]);
+                batched_loop<8, FN_THREADS>(0u, n, (uint32_t)tid, [&](uint32_t i) { return kb[i]; }, [&](uint32_t, uint32_t bits) {
+                    const uint32_t key = key_of_bits(bits);
                     const uint32_t kp = key >> hb;
                     for (int s2 = 0; s2 < nsub; ++s2)
                         if (kp == (s_subpfx[s2] >> hb)) atomicAdd(&s_hist[s2][(key >> shift) & mask], 1u);
-                }
+                });
             }
             __syncthreads();
             for (int u = wave; u < nthr; u += FN_THREADS / 64) {
@@ -902,15 +947,14 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
                 for (int i = tid; i < TMAX * 256; i += FN_THREADS) (&s_hist[0][0])[i] = 0;
                 __syncthreads();
                 const int nsub = s_nsub;
-#pragma unroll 2
-                for (uint32_t i = tid; i < n; i += FN_THREADS) {
-                    const uint32_t key = key_of_bits(kb[i]);
+                batched_loop<8, FN_THREADS>(0u, n, (uint32_t)tid, [&](uint32_t i) { return make_uint2(kb[i], kj[i]); },
+                                            [&](uint32_t, uint2 e) {
+                    const uint32_t key = key_of_bits(e.x), j = e.y;
                     for (int s2 = 0; s2 < nsub; ++s2) {
                         if (key != s_subtau[s2]) continue;
-                        const uint32_t j = kj[i];
                         if (pass == 0 || (j >> hb) == (s_subpfx[s2] >> hb)) atomicAdd(&s_hist[s2][(j >> shift) & 255u], 1u);
                     }
-                }
+                });
                 __syncthreads();
                 for (int u = wave; u < nthr; u += FN_THREADS / 64) {
                     if (s_sub[u] < 0) continue;
@@ -928,17 +972,16 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
         }
         // every candidate's part from the exact thresholds
         if (count_fits || SUMS) {
-#pragma unroll 2
-            for (uint32_t i = tid; i < n; i += FN_THREADS) {
-                const uint32_t key = key_of_bits(kb[i]);
-                const uint32_t j = kj[i];
+            batched_loop<8, FN_THREADS>(0u, n, (uint32_t)tid, [&](uint32_t i) { return make_uint2(kb[i], kj[i]); },
+                                        [&](uint32_t, uint2 e) {
+                const uint32_t key = key_of_bits(e.x), j = e.y;
                 int part = 0;
                 for (int u = 0; u < nthr; ++u) {
                     const uint32_t tau = s_tau[u];
                     part += (key > tau || (key == tau && j < s_jx[u])) ? 0 : 1;
                 }
                 classify(part, key, j);
-            }
+            });
         }
         flush_totals(true);
         __syncthreads();
@@ -958,17 +1001,16 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
             __syncthreads();
             for (int i = tid; i < (p1 - p0) * nchunks; i += FN_THREADS) s_zc[i] = 0;
             __syncthreads();
-#pragma unroll 2
-            for (uint32_t i = tid; i < n; i += FN_THREADS) {
-                const uint32_t key = key_of_bits(kb[i]);
-                const uint32_t j = kj[i];
+            batched_loop<8, FN_THREADS>(0u, n, (uint32_t)tid, [&](uint32_t i) { return make_uint2(kb[i], kj[i]); },
+                                        [&](uint32_t, uint2 e) {
+                const uint32_t key = key_of_bits(e.x), j = e.y;
                 int part = 0;
                 for (int u = 0; u < nthr; ++u) {
                     const uint32_t tau = s_tau[u];
                     part += (key > tau || (key == tau && j < s_jx[u])) ? 0 : 1;
                 }
                 if (part >= p0 && part < p1) atomicAdd(&s_zc[(part - p0) * nchunks + (int)chunk_of(j)], 1u);
-            }
+            });
             __syncthreads();
             for (int i = tid; i < (p1 - p0) * nchunks; i += FN_THREADS) {
                 const int part = p0 + i / nchunks, c = i % nchunks;
@@ -999,6 +1041,14 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
                 pc->band_plus1 = (part < nthr ? s_t[part] : s_t[nthr - 1] + 1) + 1;
             }
         }
+    }
+    };   // run_item
+
+    for (int item = blockIdx.x; item < nitems; item += gridDim.x) {
+        int z = 0;
+        while (z + 1 < nzones && s_first[z + 1] <= item) ++z;
+        __syncthreads();   // the previous item is done with the shared arrays
+        run_item(z, item - s_first[z]);
     }
 }
 
@@ -1379,7 +1429,7 @@ __global__ __launch_bounds__(WR_THREADS, 4) void k_write(TopkArgs a) {
 template <int DT, bool VEC>
 static mlmc_status launch_select(const mlmc_plan_t* pl, const TopkArgs& a, bool sums, hipStream_t st) {
     const dim3 mgrid(pl->chunks_per_row, pl->M);
-    const dim3 fgrid(FIN_SLICES, pl->L + 1, pl->M);
+    const dim3 fgrid(FIN_WGS, pl->M);
     const int rounds = pl->sample_shift > 0 ? 2 : 1;   // second round: rows whose sampled zones were refuted
     for (int exact_pass = 0; exact_pass < rounds; ++exact_pass) {
         // histogram workgroups per row: enough to spread the row, few enough that the 64 KB flushes stay cheap
@@ -1391,16 +1441,17 @@ static mlmc_status launch_select(const mlmc_plan_t* pl, const TopkArgs& a, bool 
         const dim3 hgrid((unsigned)hw, pl->M);
         // the kernels of the redo round exit at once for rows that need none: they are timed as one entry
         const int kh = exact_pass ? K_REDO : K_HIST, ks = exact_pass ? K_REDO : K_SCAN;
-        const int km = exact_pass ? K_REDO : K_MAIN, kf = exact_pass ? K_REDO : K_FINISH;
+        const int km = exact_pass ? K_REDO : K_MAIN;
         MLMC_LAUNCH(kh, st, k_hist<DT, VEC><<<hgrid, HIST_THREADS, 0, st>>>(a, exact_pass));
         MLMC_LAUNCH(ks, st, k_scan<<<pl->M, 1024, 0, st>>>(a, exact_pass));
         if (sums) MLMC_LAUNCH(km, st, k_main<DT, VEC, true><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
         else MLMC_LAUNCH(km, st, k_main<DT, VEC, false><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
         MLMC_LAUNCH(exact_pass ? K_REDO : K_FHIST, st, k_fhist<<<fgrid, FN_THREADS, 0, st>>>(a, exact_pass));
         for (int phase = 0; phase < 2; ++phase) {
-            const dim3 g2 = phase == 0 ? fgrid : dim3(1, pl->L + 1, pl->M);
-            if (sums) MLMC_LAUNCH(kf, st, k_finish<true><<<g2, FN_THREADS, 0, st>>>(a, exact_pass, phase));
-            else MLMC_LAUNCH(kf, st, k_finish<false><<<g2, FN_THREADS, 0, st>>>(a, exact_pass, phase));
+            const dim3 g2 = phase == 0 ? fgrid : dim3(pl->L + 1 < FIN_WGS ? pl->L + 1 : FIN_WGS, pl->M);
+            const int kid = exact_pass ? K_REDO : (phase ? K_FINISH1 : K_FINISH);
+            if (sums) MLMC_LAUNCH(kid, st, k_finish<true><<<g2, FN_THREADS, 0, st>>>(a, exact_pass, phase));
+            else MLMC_LAUNCH(kid, st, k_finish<false><<<g2, FN_THREADS, 0, st>>>(a, exact_pass, phase));
         }
     }
     if (sums) MLMC_LAUNCH(K_NORMS, st, k_norms<<<pl->M, 256, 0, st>>>(a));
