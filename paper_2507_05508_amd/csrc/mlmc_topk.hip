@@ -314,7 +314,7 @@ __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
 // The selection read: region counts, group sums (SUMS), zone candidates.
 constexpr int MAIN_THREADS = 1024;
 constexpr int MAIN_WAVES = MAIN_THREADS / 64;
-constexpr int RING = 320;    // staged candidates per wave: one 64-entry batch + what one load can add
+constexpr int RING = 512;    // staged candidates per wave (ring): at least one 64-entry batch + what one load can add
 
 // LDS layout (bytes).  The table, counters and stage sit below 64 KB so that their base folds into the
 // instruction's offset field.
