@@ -24,7 +24,7 @@ static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // ---- per-kernel HIP-event timing (off by default; not thread safe) ---------------------------------
 bool g_prof_on = false;
 static const char* const k_names[K_NUM] = {
-    "k_zero", "k_hist", "k_scan", "k_main", "k_fhist", "k_finish", "k_finish_rank", "redo_pass", "k_norms", "k_draw", "k_write",
+    "k_zero", "k_hist", "k_scan", "k_main", "k_fhist", "k_finish", "k_finish_rank", "redo_pass", "k_norms", "k_draw", "k_filter", "k_write",
     "k_bits_max", "k_bits_extract", "k_agg_bits", "k_tileoff", "k_agg_sparse"};
 struct ProfPair { int id; hipEvent_t e0, e1; };
 static std::vector<ProfPair> g_pending;
@@ -86,7 +86,7 @@ static void fill_topk_args(const mlmc_plan_t* pl, TopkArgs& a, const void* g, in
     a.hist = (uint32_t*)(w + pl->off_hist);
     a.hist2 = (uint32_t*)(w + pl->off_hist2);
     a.rinfo = (RowInfo*)(w + pl->off_rinfo);
-    a.table = (uint16_t*)(w + pl->off_table);
+    a.table = (uint32_t*)(w + pl->off_table);
     a.chunk_cnt = (uint32_t*)(w + pl->off_chunk_cnt);
     a.chunk_zcnt = (uint32_t*)(w + pl->off_chunk_zcnt);
     a.zhist = (uint32_t*)(w + pl->off_zhist);
@@ -97,6 +97,7 @@ static void fill_topk_args(const mlmc_plan_t* pl, TopkArgs& a, const void* g, in
     a.cand_bits = (uint32_t*)(w + pl->off_cand_bits);
     a.cand_idx = (uint32_t*)(w + pl->off_cand_idx);
     a.cand_priv = (uint2*)(w + pl->off_cand_priv);
+    a.priv_cnt = (uint32_t*)(w + pl->off_priv_cnt);
     a.dev_status = dev_status;
 }
 
@@ -237,7 +238,7 @@ mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dty
     off = align_up(off + sizeof(RowInfo) * (size_t)M, 256);
     if (kind == MLMC_TOPK) {
         pl->off_table = off;
-        off = align_up(off + sizeof(uint16_t) * NB1 * (size_t)M, 256);
+        off = align_up(off + sizeof(uint32_t) * NB1 * (size_t)M, 256);
         pl->off_chunk_cnt = off;
         off = align_up(off + sizeof(uint32_t) * RMAX * (size_t)pl->chunks_per_row * M, 256);
         pl->off_zcol = off;
@@ -252,6 +253,8 @@ mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dty
         off = align_up(off + sizeof(uint32_t) * (size_t)d * M, 256);
         pl->off_cand_priv = off;
         off = align_up(off + sizeof(uint2) * (size_t)pl->chunk * pl->chunks_per_row * M, 256);
+        pl->off_priv_cnt = off;
+        off = align_up(off + sizeof(uint32_t) * 16 * (size_t)pl->chunks_per_row * M, 256);
     }
     pl->ws_bytes = off;
     if (workspace_bytes) *workspace_bytes = off;

@@ -30,9 +30,13 @@ constexpr int FIN_WGS = 32;             // workgroups per row that take the (zon
 // top k of the zone's previous threshold has slot t; the part below every threshold of zone z has slot TMAX + z.
 constexpr int ZPMAX = 2 * TMAX;
 
-// Class table code of a first-digit bucket: bits 0..8 sum group, bits 9..14 region (or zone), bit 15 set for a zone
-// bucket.  Zone buckets carry the group G_DUMMY, so the selection read needs no branch around its accumulators.
-constexpr uint16_t CODE_ZONE = 0x8000;
+// Class table code of a first-digit bucket: bits 0..8 sum group; bits 9..15 counter (region 0..63, or 64 + zone);
+// bit 16 "stage this element" (zone candidate, or member of a band the message is expected to hold); bits 18..23
+// the tag it is staged under (zone, or TAG_MEMBER).  Zone buckets carry the group G_DUMMY, so the selection
+// read needs no branch around its accumulators.
+constexpr uint32_t CODE_ZONE = 0x8000;
+constexpr uint32_t CODE_STAGE = 0x10000;
+constexpr uint32_t TAG_MEMBER = 63;
 constexpr int G_DUMMY = GMAX - 1;
 constexpr int REP_SUM = 16;             // replicas of the 64-bit group sum accumulators: slot = id * 16 + (lane & 15)
 
@@ -55,6 +59,8 @@ struct RowInfo {
     uint32_t thr_jx[TMAX];    // entries equal to thr_tau with index below thr_jx are within the top k_t
     int32_t thr_zone[TMAX];   // zone that holds the threshold, or THR_*
     int32_t n_zones, level, respec, exact;
+    int32_t spec_level;       // level whose band the selection read staged for the message (0: none)
+    int32_t spec_ok;          // 1: the drawn level is spec_level, the message is assembled from the staged lists
     float weight;
     uint32_t draw_x;
     uint32_t zone_top[ZMAX], zone_bot[ZMAX];   // first-digit buckets of the zone, top >= bot, both inclusive
@@ -87,12 +93,13 @@ struct TopkArgs {
     int64_t ntiles;
     uint32_t* hist;          // [M][NB1] histogram of the sampled blocks
     uint32_t* hist2;         // [M][NB1] full histogram of the rows that are redone exactly
-    uint16_t* table;         // [M][NB1]
+    uint32_t* table;         // [M][NB1]
     RowInfo* rinfo;          // [M]
     RowAcc* racc;            // [M]
     uint32_t* cand_bits;     // [M][d] candidate lists: fp32 bit patterns
     uint32_t* cand_idx;      // [M][d]                  indices
-    uint2* cand_priv;        // [M][chunks_per_row][chunk] candidates {bits, offset in chunk << 6 | zone} as the waves met them
+    uint2* cand_priv;        // [M][chunks_per_row][chunk] staged {bits, offset in chunk << 6 | tag} as the waves met them
+    uint32_t* priv_cnt;      // [M][chunks_per_row][16] entries of every wave's private list
     uint32_t* chunk_cnt;     // [M][chunks_per_row][RMAX] elements of every region per chunk
     uint32_t* chunk_zcnt;    // [M][chunks_per_row][ZPMAX] candidates of every part of every zone per chunk (zeroed per call)
     uint32_t* zhist;         // [M][ZMAX][FH_BINS] zone-relative key histograms (zeroed per call)
@@ -142,7 +149,7 @@ struct BitsArgs {
 
 // ---- optional per-kernel timing with HIP events (host side, see mlmc_profile_* in mlmc.h) ----------
 enum KernelId {
-    K_ZERO = 0, K_HIST, K_SCAN, K_MAIN, K_FHIST, K_FINISH, K_FINISH1, K_REDO, K_NORMS, K_DRAW, K_WRITE,
+    K_ZERO = 0, K_HIST, K_SCAN, K_MAIN, K_FHIST, K_FINISH, K_FINISH1, K_REDO, K_NORMS, K_DRAW, K_FILTER, K_WRITE,
     K_BITS_MAX, K_BITS_EXTRACT, K_AGG_BITS, K_TILEOFF, K_AGG_SPARSE, K_NUM
 };
 extern bool g_prof_on;
@@ -173,6 +180,6 @@ struct mlmc_plan_s {
     int sample_shift;
     // workspace byte offsets
     size_t off_racc, off_hist, off_hist2, off_chunk_zcnt, off_zhist, off_zpacc, zero_bytes;  // [0, zero_bytes) is cleared per call
-    size_t off_rinfo, off_table, off_chunk_cnt, off_zcol, off_tileoff, off_norms, off_cand_bits, off_cand_idx, off_cand_priv;
+    size_t off_rinfo, off_table, off_chunk_cnt, off_zcol, off_tileoff, off_norms, off_cand_bits, off_cand_idx, off_cand_priv, off_priv_cnt;
     size_t ws_bytes;
 };

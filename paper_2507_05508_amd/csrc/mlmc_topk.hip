@@ -129,6 +129,7 @@ __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
     __shared__ int32_t s_nz, s_lev;
     __shared__ uint32_t s_ztop[ZMAX], s_zbot[ZMAX];
     __shared__ int32_t s_label[RMAX];
+    __shared__ double s_est[LMAX + 2];
 
     const int row = blockIdx.x, tid = threadIdx.x;
     RowInfo* ri = a.rinfo + row;
@@ -282,31 +283,82 @@ __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
     }
     __syncthreads();
 
-    // class table: thread tid writes its 16 buckets (descending), 32 bytes
+    // Which band will the message hold besides the base band?  With p known the level is already drawn.  With
+    // adaptive p it is predicted: band energies estimated from the histogram (bucket count x squared bucket
+    // midpoint), the same Philox word, the same inverse CDF.  The selection read stages the members of that band
+    // so that the message can be assembled without a second read of the row; a wrong prediction only costs
+    // that second read.  Bands above an eighth of the row are not staged (the second read is cheaper then).
     const int nz = s_nz;
-    uint16_t codes[16];
+    if (a.all_thresholds && a.draw_mode == 3) {
+        for (int l = tid; l < LMAX + 2; l += 1024) s_est[l] = 0.0;
+        __syncthreads();
+        if (sum) {
+            const double scale = (double)a.d / (double)(ns > 0 ? ns : 1);
+            int cur = -1;
+            double acc = 0.0;
+            uint32_t run = before;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                if (hv[i]) {
+                    const uint32_t b = (uint32_t)(NB1 - 1 - (tid * 16 + i));
+                    const double rank = ((double)run + 0.5 * (double)hv[i]) * scale;
+                    int band = 0;
+                    while (band <= L && rank >= (double)a.k[band]) ++band;   // first t with rank < k_t
+                    const double v = (double)__uint_as_float((b << B1_SHIFT) | 0x10000u);
+                    if (band != cur) {
+                        if (cur >= 0 && acc > 0.0) atomicAdd(&s_est[cur], acc);
+                        cur = band;
+                        acc = 0.0;
+                    }
+                    if ((b >> 6) < 255u) acc += (double)hv[i] * scale * v * v;
+                }
+                run += hv[i];
+            }
+            if (cur >= 0 && acc > 0.0) atomicAdd(&s_est[cur], acc);
+        }
+        __syncthreads();
+        if (tid == 0) {
+            double p[LMAX];
+            double tot = 0.0;
+            for (int l = 0; l < L; ++l) { p[l] = sqrt(s_est[l + 1]); tot += p[l]; }
+            for (int l = 0; l < L; ++l) p[l] = tot > 0.0 ? p[l] / tot : 1.0 / (double)L;
+            s_lev = draw_from_p(p, L, philox_word0(a.seed, a.step, (uint32_t)row));
+        }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        int sl = (a.all_thresholds && a.draw_mode != 3) ? 0 : s_lev;   // norms only: nothing to stage
+        if (sl > 0 && (a.k[sl] - a.k[sl - 1]) * 8 > a.d) sl = 0;
+        ri->spec_level = sl;
+        ri->spec_ok = (sl > 0 && !(a.all_thresholds && a.draw_mode == 3)) ? 1 : 0;   // adaptive: decided after the draw
+        s_lev = sl;
+    }
+    __syncthreads();
+    const int spec = s_lev;
+
+    // class table: thread tid writes its 16 buckets (descending), 64 bytes
+    uint32_t codes[16];
     int zi = 0;   // zones wholly above the current bucket
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         const uint32_t b = (uint32_t)(NB1 - 1 - (tid * 16 + i));
         while (zi < nz && s_zbot[zi] > b) ++zi;
         if (zi < nz && b <= s_ztop[zi]) {
-            codes[15 - i] = (uint16_t)(CODE_ZONE | (zi << 9) | G_DUMMY);
+            codes[15 - i] = CODE_STAGE | ((uint32_t)zi << 18) | CODE_ZONE | ((uint32_t)zi << 9) | (uint32_t)G_DUMMY;
         } else {
             const uint32_t E = b >> 6;
             const int gid = (int)(255 - E) + zi;
-            codes[15 - i] = (uint16_t)((zi << 9) | gid);
+            const int lab = s_label[zi];
+            const bool member = spec > 0 && (lab == 0 || lab == spec);
+            codes[15 - i] = (member ? (CODE_STAGE | (TAG_MEMBER << 18)) : 0u) | ((uint32_t)zi << 9) | (uint32_t)gid;
             ri->g_exp[gid] = (uint16_t)(E ? E : 1);
-            ri->g_band[gid] = (uint16_t)s_label[zi];
+            ri->g_band[gid] = (uint16_t)lab;
         }
     }
     {
-        uint32_t w[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) w[i] = (uint32_t)codes[2 * i] | ((uint32_t)codes[2 * i + 1] << 16);
         uint4* dst = (uint4*)(a.table + (size_t)row * NB1 + (NB1 - 16 - tid * 16));
-        dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
-        dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) dst[i] = make_uint4(codes[4 * i], codes[4 * i + 1], codes[4 * i + 2], codes[4 * i + 3]);
     }
 }
 
@@ -314,18 +366,17 @@ __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
 // The selection read: region counts, group sums (SUMS), zone candidates.
 constexpr int MAIN_THREADS = 1024;
 constexpr int MAIN_WAVES = MAIN_THREADS / 64;
-constexpr int RING = 512;    // staged candidates per wave (ring): at least one 64-entry batch + what one load can add
+constexpr int RING = 256;    // staged entries per wave (ring); at most 63 + 64 are pending at any time
 
-// LDS layout (bytes).  The table, counters and stage sit below 64 KB so that their base folds into the
-// instruction's offset field.
-constexpr int LM_TAB = 0;                                   // uint16 [NB1]
-constexpr int LM_CNT = LM_TAB + NB1 * 2;                    // uint32 [128][REP]: regions 0..63, zones 64..127
+// LDS layout (bytes).  The table sits at offset 0 so that the look-up needs no base.
+constexpr int LM_TAB = 0;                                   // uint32 [NB1]
+constexpr int LM_CNT = LM_TAB + NB1 * 4;                    // uint32 [128][REP]: regions 0..63, zones 64..127
 constexpr int LM_ZCUR = LM_CNT + 128 * REP * 4;             // uint32 [64] write cursor of every zone list
 constexpr int LM_ZMAX = LM_ZCUR + 64 * 4;                   // uint32 [64] largest candidate key of every zone
 constexpr int LM_ZMIN = LM_ZMAX + 64 * 4;                   // uint32 [64] largest ~key
 constexpr int LM_ZOFF = LM_ZMIN + 64 * 4;                   // uint32 [64]
 constexpr int LM_ZCAP = LM_ZOFF + 64 * 4;
-constexpr int LM_STAGE = LM_ZCAP + 64 * 4;                  // uint2 [MAIN_WAVES][RING]: {bits, rel << 6 | zone}
+constexpr int LM_STAGE = LM_ZCAP + 64 * 4;                  // uint2 [MAIN_WAVES][RING]: {bits, rel << 6 | tag}
 constexpr int LM_SUM = LM_STAGE + MAIN_WAVES * RING * 8;    // uint64 [GMAX][REP_SUM]
 template <bool SUMS> constexpr int lm_total() { return LM_SUM + (SUMS ? GMAX * REP_SUM * 8 : 0); }
 static_assert(lm_total<true>() <= 160 * 1024, "LDS budget");
@@ -351,7 +402,7 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
     {
         const uint4* src = (const uint4*)(a.table + (size_t)row * NB1);
         uint4* dst = (uint4*)(lm + LM_TAB);
-        for (int i = tid; i < NB1 * 2 / 16; i += MAIN_THREADS) dst[i] = src[i];
+        for (int i = tid; i < NB1 * 4 / 16; i += MAIN_THREADS) dst[i] = src[i];
         uint4* z = (uint4*)(lm + LM_CNT);
         const uint4 zero = make_uint4(0, 0, 0, 0);
         for (int i = tid; i < (LM_ZOFF - LM_CNT) / 16; i += MAIN_THREADS) z[i] = zero;
@@ -394,8 +445,8 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
     auto process = [&](const uint32_t (&b)[4], uint32_t rel0, uint32_t vmask) {
         uint32_t code[4];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) code[c] = *(const uint16_t*)(lm + ((b[c] >> 16) & 0x7FFEu));
-        uint32_t anyz = 0;
+        for (int c = 0; c < 4; ++c) code[c] = *(const uint32_t*)(lm + ((b[c] >> 15) & 0xFFFCu));
+        uint32_t anys = 0;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             if (!((vmask >> c) & 1u)) code[c] = (63u << 9) | (uint32_t)G_DUMMY;
@@ -406,22 +457,22 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
                 atomicAdd((unsigned long long*)(lm + (((code[c] & 511u) << 7) + sum_lane)),
                           (unsigned long long)sig * (unsigned long long)sig);
             }
-            atomicAdd((uint32_t*)(lm + (((code[c] >> 9) << 7) + cnt_lane)), 1u);
+            atomicAdd((uint32_t*)(lm + (((code[c] >> 2) & 0x3F80u) + cnt_lane)), 1u);
             maxkey = key > maxkey ? key : maxkey;
-            anyz |= code[c];
+            anys |= code[c];
         }
-        if (__ballot(anyz & CODE_ZONE)) {
+        if (__ballot(anys & CODE_STAGE)) {
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                const bool zone = (code[c] & CODE_ZONE) != 0;
-                const uint64_t m = __ballot(zone);
-                if (zone) {
+                const bool stage = (code[c] & CODE_STAGE) != 0;
+                const uint64_t m = __ballot(stage);
+                if (stage) {
                     const uint32_t pos = (head + mbcnt(m)) % (uint32_t)RING;
-                    s_stage[pos] = make_uint2(b[c], ((rel0 + c) << 6) | ((code[c] >> 9) & 63u));
+                    s_stage[pos] = make_uint2(b[c], ((rel0 + c) << 6) | ((code[c] >> 18) & 63u));
                 }
                 head += (uint32_t)__popcll(m);
+                if (head - tail >= 64u) drain(false);   // at most 63 + 64 entries are ever pending
             }
-            if (head - tail >= 64u) drain(false);
         }
     };
 
@@ -474,8 +525,10 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
     uint32_t* cb = a.cand_bits + (size_t)row * (size_t)a.d;
     uint32_t* ci = a.cand_idx + (size_t)row * (size_t)a.d;
     bool dropped = false;
+    if (lane == 0) a.priv_cnt[((size_t)row * a.chunks_per_row + blockIdx.x) * MAIN_WAVES + wave] = head;
     batched_loop<8, 64>(0u, head, lane, [&](uint32_t i) { return priv[i]; }, [&](uint32_t, uint2 e) {
         const uint32_t z = e.y & 63u, key = key_of_bits(e.x);
+        if (z == TAG_MEMBER) return;   // staged for the message only
         const uint32_t pos = atomicAdd(&s_zcur[z], 1u);
         atomicMax(&s_zmax[z], key);
         atomicMax(&s_zmin[z], ~key);
@@ -1147,7 +1200,11 @@ __global__ __launch_bounds__(256) void k_norms(TopkArgs a) {
         if (a.norms_user) a.norms_user[(size_t)row * a.L + (l - 1)] = nrm;
     }
     __syncthreads();
-    if (tid == 0 && a.draw_mode == 3) draw_row(a, row, s_norm);
+    if (tid == 0 && a.draw_mode == 3) {
+        draw_row(a, row, s_norm);
+        RowInfo* rw = a.rinfo + row;
+        rw->spec_ok = (rw->spec_level > 0 && rw->spec_level == rw->level) ? 1 : 0;
+    }
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -1203,6 +1260,7 @@ __global__ __launch_bounds__(WR_THREADS, 4) void k_write(TopkArgs a) {
     const int row = blockIdx.y, chunk_id = blockIdx.x, tid = threadIdx.x;
     const uint32_t lane = lane_id(), wave = tid >> 6;
     const RowInfo* ri = a.rinfo + row;
+    if (ri->spec_ok) return;   // the message of this row comes from the staged lists (k_filter)
     const int lev = ri->level;
     const int nzn = ri->n_zones;
     const int nc = a.chunks_per_row;
@@ -1425,6 +1483,151 @@ __global__ __launch_bounds__(WR_THREADS, 4) void k_write(TopkArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------------
+// The message without a second read of the row, for rows whose drawn band was staged by the selection read.
+// One workgroup per (chunk, row): the chunk's staged entries (16 private lists: zone candidates and band
+// members, in the order the waves met them) are tested against the exact thresholds; a bitmap over the chunk's
+// elements turns the members' offsets into ranks, i.e. into positions of the index-ordered message.
+constexpr int FL_THREADS = 1024;
+constexpr int FL_WORDS = CHUNK_MAX / 32;
+
+__global__ __launch_bounds__(FL_THREADS) void k_filter(TopkArgs a) {
+    __shared__ uint32_t s_bits[FL_WORDS];   // bit rel: element c0 + rel is in the message
+    __shared__ uint32_t s_pre[FL_WORDS];    // members in the words before
+    __shared__ unsigned long long s_red[FL_THREADS / 64];
+    __shared__ uint32_t s_scan[FL_THREADS / 64 + 1];
+    __shared__ int64_t s_rowstart, s_rownnz;
+    __shared__ uint32_t s_base;
+    const int row = blockIdx.y, chunk_id = blockIdx.x, tid = threadIdx.x;
+    const uint32_t lane = lane_id(), wave = tid >> 6;
+    const RowInfo* ri = a.rinfo + row;
+    if (!ri->spec_ok) return;   // k_write reads the row again
+    const int lev = ri->level;
+    const int nzn = ri->n_zones;
+    const int nc = a.chunks_per_row;
+    const int64_t nt = a.ntiles;
+    const int64_t c0 = (int64_t)chunk_id * a.chunk;
+    const int64_t c1 = c0 + a.chunk < a.d ? c0 + a.chunk : a.d;
+    const int nwords = (int)((c1 - c0 + 31) / 32);
+
+    for (int i = tid; i < nwords; i += FL_THREADS) s_bits[i] = 0;
+    // start of this row's message and entries of this row before this chunk (as in k_write)
+    {
+        unsigned long long part = 0;
+        for (int i = tid; i < row; i += FL_THREADS) {
+            const int li = a.rinfo[i].level;
+            part += (unsigned long long)(a.k[0] + a.k[li] - a.k[li - 1]);
+        }
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) part += __shfl_xor(part, o, 64);
+        if (lane == 0) s_red[wave] = part;
+        __syncthreads();
+        if (tid == 0) {
+            unsigned long long t = 0;
+            for (int w = 0; w < FL_THREADS / 64; ++w) t += s_red[w];
+            s_rowstart = (int64_t)t;
+            s_rownnz = a.k[0] + a.k[lev] - a.k[lev - 1];
+        }
+        __syncthreads();
+    }
+    int r0 = -1, rl = -1;
+    for (int r = 0; r <= nzn; ++r) {
+        const int lab = ri->region_label[r];
+        if (lab == 0) r0 = r;
+        if (lab == lev) rl = r;
+    }
+    int zs[3] = {-1, -1, -1};
+    {
+        const int z0 = ri->thr_zone[0], za = ri->thr_zone[lev - 1], zb = ri->thr_zone[lev];
+        if (z0 >= 0) zs[0] = 0;
+        if (za >= 0) zs[1] = zb == za ? lev : TMAX + za;
+        if (zb >= 0 && zb != za) zs[2] = lev;
+    }
+    auto chunk_entries = [&](int c) -> uint32_t {
+        const uint32_t* cc = a.chunk_cnt + ((size_t)row * nc + c) * RMAX;
+        const uint32_t* zc = a.chunk_zcnt + ((size_t)row * nc + c) * ZPMAX;
+        uint32_t v = 0;
+        if (r0 >= 0) v += cc[r0];
+        if (rl >= 0) v += cc[rl];
+#pragma unroll
+        for (int i = 0; i < 3; ++i)
+            if (zs[i] >= 0) v += zc[zs[i]];
+        return v;
+    };
+    {
+        unsigned long long part = 0;
+        for (int c = tid; c < chunk_id; c += FL_THREADS) part += chunk_entries(c);
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) part += __shfl_xor(part, o, 64);
+        if (lane == 0) s_red[wave] = part;
+        __syncthreads();
+        if (tid == 0) {
+            unsigned long long t = 0;
+            for (int w = 0; w < FL_THREADS / 64; ++w) t += s_red[w];
+            s_base = (uint32_t)t;
+        }
+        __syncthreads();
+    }
+    const int64_t rowstart = s_rowstart;
+    const uint32_t base = s_base;
+    if (chunk_id == 0 && tid == 0) {
+        a.row_off[row] = rowstart;
+        if (row == a.M - 1) {
+            a.row_off[a.M] = rowstart + s_rownnz;
+            if (rowstart + s_rownnz > a.capacity) atomicOr(a.dev_status, MLMC_DEV_CAPACITY);
+        }
+    }
+    const Thr3 th = load_thr3(ri);
+    const float w = ri->weight;
+    auto member = [&](uint32_t key, uint32_t j, bool& in0) -> bool {
+        in0 = inside_top(th, 0, key, j);
+        return in0 || (inside_top(th, 2, key, j) && !inside_top(th, 1, key, j));
+    };
+    // wave w of this workgroup reads the private list of wave w of the selection read
+    const uint2* priv = a.cand_priv + ((size_t)row * nc + chunk_id) * (size_t)a.chunk + (size_t)wave * (a.chunk / 16);
+    const uint32_t cnt = a.priv_cnt[((size_t)row * nc + chunk_id) * 16 + wave];
+    batched_loop<8, 64>(0u, cnt, lane, [&](uint32_t i) { return priv[i]; }, [&](uint32_t, uint2 e) {
+        const uint32_t rel = e.y >> 6;
+        bool in0;
+        if (member(key_of_bits(e.x), (uint32_t)c0 + rel, in0)) atomicOr(&s_bits[rel >> 5], 1u << (rel & 31u));
+    });
+    __syncthreads();
+    // exclusive prefix of the word popcounts
+    {
+        const int per = (nwords + FL_THREADS - 1) / FL_THREADS;
+        const int w0 = tid * per, w1 = w0 + per < nwords ? w0 + per : nwords;
+        uint32_t mysum = 0;
+        for (int i = w0; i < w1; ++i) mysum += (uint32_t)__popc(s_bits[i]);
+        uint32_t total;
+        uint32_t run = block_excl_scan<FL_THREADS>(mysum, s_scan, total);
+        for (int i = w0; i < w1; ++i) {
+            s_pre[i] = run;
+            run += (uint32_t)__popc(s_bits[i]);
+        }
+        if (tid == 0) {
+            if (total != chunk_entries(chunk_id)) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
+            if (chunk_id == nc - 1) {
+                a.tile_off[(size_t)row * (nt + 1) + nt] = base + total;
+                if ((int64_t)(base + total) != s_rownnz) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
+            }
+        }
+    }
+    __syncthreads();
+    for (int64_t t = c0 / TILE + tid; t * TILE < c1; t += FL_THREADS)
+        a.tile_off[(size_t)row * (nt + 1) + t] = base + s_pre[(t * TILE - c0) >> 5];
+    batched_loop<8, 64>(0u, cnt, lane, [&](uint32_t i) { return priv[i]; }, [&](uint32_t, uint2 e) {
+        const uint32_t rel = e.y >> 6, j = (uint32_t)c0 + rel;
+        bool in0;
+        if (member(key_of_bits(e.x), j, in0)) {
+            const uint32_t wd = rel >> 5;
+            const uint32_t rank = s_pre[wd] + (uint32_t)__popc(s_bits[wd] & ((1u << (rel & 31u)) - 1u));
+            const int64_t at = rowstart + base + rank;
+            const float v = __uint_as_float(e.x);
+            if (at < a.capacity) { a.idx[at] = j; a.val[at] = in0 ? v : __fmul_rn(v, w); }
+        }
+    });
+}
+
+// ---------------------------------------------------------------------------------------------------
 // host-side launchers
 template <int DT, bool VEC>
 static mlmc_status launch_select(const mlmc_plan_t* pl, const TopkArgs& a, bool sums, hipStream_t st) {
@@ -1460,7 +1663,10 @@ static mlmc_status launch_select(const mlmc_plan_t* pl, const TopkArgs& a, bool 
 
 template <int DT, bool VEC>
 static mlmc_status launch_compact(const mlmc_plan_t* pl, const TopkArgs& a, hipStream_t st) {
-    MLMC_LAUNCH(K_WRITE, st, k_write<DT, VEC><<<dim3(pl->chunks_per_row, pl->M), WR_THREADS, 0, st>>>(a));
+    const dim3 grid(pl->chunks_per_row, pl->M);
+    // rows whose drawn band was staged get their message from the staged lists, the others from a second read
+    MLMC_LAUNCH(K_FILTER, st, k_filter<<<grid, FL_THREADS, 0, st>>>(a));
+    MLMC_LAUNCH(K_WRITE, st, k_write<DT, VEC><<<grid, WR_THREADS, 0, st>>>(a));
     return MLMC_OK;
 }
 
