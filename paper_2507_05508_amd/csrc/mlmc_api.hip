@@ -24,7 +24,7 @@ static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // ---- per-kernel HIP-event timing (off by default; not thread safe) ---------------------------------
 bool g_prof_on = false;
 static const char* const k_names[K_NUM] = {
-    "k_zero", "k_hist", "k_scan", "k_main", "k_fhist", "k_finish", "k_finish_rank", "redo_pass", "k_norms", "k_draw", "k_filter", "k_write",
+    "k_zero", "k_hist", "k_scan", "k_main", "k_fhist", "k_finish", "k_finish_rank", "redo_pass", "k_norms", "k_draw", "k_msgplan", "k_filter", "k_write",
     "k_bits_max", "k_bits_extract", "k_agg_bits", "k_tileoff", "k_agg_sparse"};
 struct ProfPair { int id; hipEvent_t e0, e1; };
 static std::vector<ProfPair> g_pending;
@@ -98,6 +98,7 @@ static void fill_topk_args(const mlmc_plan_t* pl, TopkArgs& a, const void* g, in
     a.cand_idx = (uint32_t*)(w + pl->off_cand_idx);
     a.cand_priv = (uint2*)(w + pl->off_cand_priv);
     a.priv_cnt = (uint32_t*)(w + pl->off_priv_cnt);
+    a.chunk_base = (uint32_t*)(w + pl->off_chunk_base);
     a.dev_status = dev_status;
 }
 
@@ -255,6 +256,8 @@ mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dty
         off = align_up(off + sizeof(uint2) * (size_t)pl->chunk * pl->chunks_per_row * M, 256);
         pl->off_priv_cnt = off;
         off = align_up(off + sizeof(uint32_t) * 16 * (size_t)pl->chunks_per_row * M, 256);
+        pl->off_chunk_base = off;
+        off = align_up(off + sizeof(uint32_t) * (size_t)(pl->chunks_per_row + 1) * M, 256);
     }
     pl->ws_bytes = off;
     if (workspace_bytes) *workspace_bytes = off;

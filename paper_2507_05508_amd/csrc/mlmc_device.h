@@ -69,9 +69,11 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* lds, u
 
 // Strided loop over [i0, i1) for a group of NT threads (this thread starts at i0 + t): U loads are issued back to
 // back before the first is consumed.  A loop whose every load sits behind its own bounds check is compiled to one
-// load, one wait per iteration; here only whole batches take the fast path and the ragged rest is checked.
+// load, one wait per iteration; here whole batches take a branch-free path and the ragged rest is one more batch
+// whose out-of-range loads are redirected to the last element and discarded.
 template <int U, int NT, class Load, class Proc>
 __device__ __forceinline__ void batched_loop(uint32_t i0, uint32_t i1, uint32_t t, Load load, Proc proc) {
+    if (i1 <= i0) return;
     uint32_t i = i0 + t;
     if (i1 >= (uint32_t)((U - 1) * NT)) {
         const uint32_t lim = i1 - (uint32_t)((U - 1) * NT);   // i + (U-1)*NT < i1  <=>  i < lim
@@ -83,7 +85,19 @@ __device__ __forceinline__ void batched_loop(uint32_t i0, uint32_t i1, uint32_t 
             for (int u = 0; u < U; ++u) proc(i + (uint32_t)(u * NT), v[u]);
         }
     }
-    for (; i < i1; i += (uint32_t)NT) proc(i, load(i));
+    if (i < i1) {   // fewer than U strides are left for this thread
+        decltype(load(0u)) v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t k = i + (uint32_t)(u * NT);
+            v[u] = load(k < i1 ? k : i1 - 1u);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t k = i + (uint32_t)(u * NT);
+            if (k < i1) proc(k, v[u]);
+        }
+    }
 }
 
 // ---- keys ----------------------------------------------------------------------------------------

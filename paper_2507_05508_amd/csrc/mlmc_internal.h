@@ -52,6 +52,14 @@ struct Piece {          // exact sum of squared significands of one part of a zo
     uint64_t lo, hi;    // value = hi * 2^32 + lo, in units of 2^(2 (exp - 150))
 };
 
+// What the kernels that write a row's message need, gathered once per row by k_msgplan.
+struct MsgPlan {
+    int64_t rowstart, rownnz;   // position of the row's message in idx / val, its length k_0 + k_l - k_{l-1}
+    uint32_t tau[3], jx[3];     // thresholds 0, l-1, l
+    float weight;
+    int32_t level;
+};
+
 // Per row, rewritten by every call.  Membership of entry (key, j) in the top k_t of its row:
 //     key > thr_tau[t]  ||  (key == thr_tau[t] && j < thr_jx[t])
 struct RowInfo {
@@ -61,6 +69,7 @@ struct RowInfo {
     int32_t n_zones, level, respec, exact;
     int32_t spec_level;       // level whose band the selection read staged for the message (0: none)
     int32_t spec_ok;          // 1: the drawn level is spec_level, the message is assembled from the staged lists
+    MsgPlan msg;
     float weight;
     uint32_t draw_x;
     uint32_t zone_top[ZMAX], zone_bot[ZMAX];   // first-digit buckets of the zone, top >= bot, both inclusive
@@ -100,6 +109,7 @@ struct TopkArgs {
     uint32_t* cand_idx;      // [M][d]                  indices
     uint2* cand_priv;        // [M][chunks_per_row][chunk] staged {bits, offset in chunk << 6 | tag} as the waves met them
     uint32_t* priv_cnt;      // [M][chunks_per_row][16] entries of every wave's private list
+    uint32_t* chunk_base;    // [M][chunks_per_row + 1] message entries of the row before every chunk
     uint32_t* chunk_cnt;     // [M][chunks_per_row][RMAX] elements of every region per chunk
     uint32_t* chunk_zcnt;    // [M][chunks_per_row][ZPMAX] candidates of every part of every zone per chunk (zeroed per call)
     uint32_t* zhist;         // [M][ZMAX][FH_BINS] zone-relative key histograms (zeroed per call)
@@ -149,7 +159,7 @@ struct BitsArgs {
 
 // ---- optional per-kernel timing with HIP events (host side, see mlmc_profile_* in mlmc.h) ----------
 enum KernelId {
-    K_ZERO = 0, K_HIST, K_SCAN, K_MAIN, K_FHIST, K_FINISH, K_FINISH1, K_REDO, K_NORMS, K_DRAW, K_FILTER, K_WRITE,
+    K_ZERO = 0, K_HIST, K_SCAN, K_MAIN, K_FHIST, K_FINISH, K_FINISH1, K_REDO, K_NORMS, K_DRAW, K_MSGPLAN, K_FILTER, K_WRITE,
     K_BITS_MAX, K_BITS_EXTRACT, K_AGG_BITS, K_TILEOFF, K_AGG_SPARSE, K_NUM
 };
 extern bool g_prof_on;
@@ -180,6 +190,6 @@ struct mlmc_plan_s {
     int sample_shift;
     // workspace byte offsets
     size_t off_racc, off_hist, off_hist2, off_chunk_zcnt, off_zhist, off_zpacc, zero_bytes;  // [0, zero_bytes) is cleared per call
-    size_t off_rinfo, off_table, off_chunk_cnt, off_zcol, off_tileoff, off_norms, off_cand_bits, off_cand_idx, off_cand_priv, off_priv_cnt;
+    size_t off_rinfo, off_table, off_chunk_cnt, off_zcol, off_tileoff, off_norms, off_cand_bits, off_cand_idx, off_cand_priv, off_priv_cnt, off_chunk_base;
     size_t ws_bytes;
 };

@@ -287,7 +287,7 @@ __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
     // adaptive p it is predicted: band energies estimated from the histogram (bucket count x squared bucket
     // midpoint), the same Philox word, the same inverse CDF.  The selection read stages the members of that band
     // so that the message can be assembled without a second read of the row; a wrong prediction only costs
-    // that second read.  Bands above an eighth of the row are not staged (the second read is cheaper then).
+    // that second read.
     const int nz = s_nz;
     if (a.all_thresholds && a.draw_mode == 3) {
         for (int l = tid; l < LMAX + 2; l += 1024) s_est[l] = 0.0;
@@ -328,7 +328,6 @@ __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
     }
     if (tid == 0) {
         int sl = (a.all_thresholds && a.draw_mode != 3) ? 0 : s_lev;   // norms only: nothing to stage
-        if (sl > 0 && (a.k[sl] - a.k[sl - 1]) * 8 > a.d) sl = 0;
         ri->spec_level = sl;
         ri->spec_ok = (sl > 0 && !(a.all_thresholds && a.draw_mode == 3)) ? 1 : 0;   // adaptive: decided after the draw
         s_lev = sl;
@@ -1244,49 +1243,19 @@ __device__ __forceinline__ bool inside_top(const Thr3& th, int i, uint32_t key, 
 }
 
 // ---------------------------------------------------------------------------------------------------
-// The message read.  One workgroup per (chunk, row), one tile per step.
-constexpr int WR_THREADS = 512;
-constexpr int WR_WAVES = WR_THREADS / 64;
-constexpr int WR_LINES = TILE / (WR_WAVES * 64);   // 64-element lines of a wave per step
-constexpr int WR_STAGE = 1024;   // entries of one step that are gathered in LDS and written densely
-
-template <int DT, bool VEC>
-__global__ __launch_bounds__(WR_THREADS, 4) void k_write(TopkArgs a) {
-    __shared__ unsigned long long s_red[WR_WAVES];
-    __shared__ int64_t s_rowstart, s_rownnz;
-    __shared__ uint32_t s_base;
-    __shared__ uint32_t s_wemit[2][WR_WAVES];
-    __shared__ uint2 s_out[2][WR_STAGE];
-    const int row = blockIdx.y, chunk_id = blockIdx.x, tid = threadIdx.x;
-    const uint32_t lane = lane_id(), wave = tid >> 6;
-    const RowInfo* ri = a.rinfo + row;
-    if (ri->spec_ok) return;   // the message of this row comes from the staged lists (k_filter)
+// Per row, once the level is drawn and the thresholds are exact: where the row's message starts, how many of its
+// entries lie before every chunk (regions of band 0 and band l plus the parts of the zones of thresholds 0, l-1, l
+// that belong to those bands), and the three thresholds, so that the kernels that write the message start from
+// one small record.
+constexpr int MP_THREADS = 256;
+__global__ __launch_bounds__(MP_THREADS) void k_msgplan(TopkArgs a) {
+    __shared__ uint32_t s_scan[MP_THREADS / 64 + 1];
+    __shared__ uint32_t s_carry;
+    const int row = blockIdx.x, tid = threadIdx.x;
+    RowInfo* ri = a.rinfo + row;
     const int lev = ri->level;
     const int nzn = ri->n_zones;
     const int nc = a.chunks_per_row;
-    const int64_t nt = a.ntiles;
-
-    // start of this row's message: rows before it hold k_0 + k_l - k_{l-1} entries each
-    {
-        unsigned long long part = 0;
-        for (int i = tid; i < row; i += WR_THREADS) {
-            const int li = a.rinfo[i].level;
-            part += (unsigned long long)(a.k[0] + a.k[li] - a.k[li - 1]);
-        }
-#pragma unroll
-        for (int o = 32; o >= 1; o >>= 1) part += __shfl_xor(part, o, 64);
-        if (lane == 0) s_red[wave] = part;
-        __syncthreads();
-        if (tid == 0) {
-            unsigned long long t = 0;
-            for (int w = 0; w < WR_WAVES; ++w) t += s_red[w];
-            s_rowstart = (int64_t)t;
-            s_rownnz = a.k[0] + a.k[lev] - a.k[lev - 1];
-        }
-        __syncthreads();
-    }
-    // entries of this row before this chunk: the regions of band 0 and band l, plus the parts of the zones of
-    // thresholds 0, l-1, l that belong to those bands
     int r0 = -1, rl = -1;
     for (int r = 0; r <= nzn; ++r) {
         const int lab = ri->region_label[r];
@@ -1300,47 +1269,84 @@ __global__ __launch_bounds__(WR_THREADS, 4) void k_write(TopkArgs a) {
         if (za >= 0) zs[1] = zb == za ? lev : TMAX + za;          // just below threshold l-1, in its zone
         if (zb >= 0 && zb != za) zs[2] = lev;                     // above threshold l, in a zone of its own
     }
-    auto chunk_entries = [&](int c) -> uint32_t {
-        const uint32_t* cc = a.chunk_cnt + ((size_t)row * nc + c) * RMAX;
-        const uint32_t* zc = a.chunk_zcnt + ((size_t)row * nc + c) * ZPMAX;
+    if (tid == 0) s_carry = 0;
+    __syncthreads();
+    uint32_t* cbase = a.chunk_base + (size_t)row * (nc + 1);
+    for (int c0 = 0; c0 < nc; c0 += MP_THREADS) {
+        const int c = c0 + tid;
         uint32_t v = 0;
-        if (r0 >= 0) v += cc[r0];
-        if (rl >= 0) v += cc[rl];
+        if (c < nc) {
+            const uint32_t* cc = a.chunk_cnt + ((size_t)row * nc + c) * RMAX;
+            const uint32_t* zc = a.chunk_zcnt + ((size_t)row * nc + c) * ZPMAX;
+            if (r0 >= 0) v += cc[r0];
+            if (rl >= 0) v += cc[rl];
 #pragma unroll
-        for (int i = 0; i < 3; ++i)
-            if (zs[i] >= 0) v += zc[zs[i]];
-        return v;
-    };
-    {
-        unsigned long long part = 0;
-        for (int c = tid; c < chunk_id; c += WR_THREADS) part += chunk_entries(c);
-#pragma unroll
-        for (int o = 32; o >= 1; o >>= 1) part += __shfl_xor(part, o, 64);
-        if (lane == 0) s_red[wave] = part;
-        __syncthreads();
-        if (tid == 0) {
-            unsigned long long t = 0;
-            for (int w = 0; w < WR_WAVES; ++w) t += s_red[w];
-            s_base = (uint32_t)t;
+            for (int i = 0; i < 3; ++i)
+                if (zs[i] >= 0) v += zc[zs[i]];
         }
+        uint32_t total;
+        const uint32_t ex = block_excl_scan<MP_THREADS>(v, s_scan, total);
+        const uint32_t carry = s_carry;
+        if (c < nc) cbase[c] = carry + ex;
+        __syncthreads();
+        if (tid == 0) s_carry = carry + total;
         __syncthreads();
     }
-    const int64_t rowstart = s_rowstart;
-    if (chunk_id == 0) {
-        if (tid == 0) {
-            a.row_off[row] = rowstart;
-            if (row == a.M - 1) {
-                a.row_off[a.M] = rowstart + s_rownnz;
-                if (rowstart + s_rownnz > a.capacity) atomicOr(a.dev_status, MLMC_DEV_CAPACITY);
-            }
+    if (tid == 0) {
+        int64_t start = 0;
+        for (int i = 0; i < row; ++i) {
+            const int li = a.rinfo[i].level;
+            start += a.k[0] + a.k[li] - a.k[li - 1];
+        }
+        const int64_t nnz = a.k[0] + a.k[lev] - a.k[lev - 1];
+        cbase[nc] = s_carry;
+        if ((int64_t)s_carry != nnz) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
+        MsgPlan m;
+        m.rowstart = start;
+        m.rownnz = nnz;
+        const int ts[3] = {0, lev - 1, lev};
+        for (int i = 0; i < 3; ++i) { m.tau[i] = ri->thr_tau[ts[i]]; m.jx[i] = ri->thr_jx[ts[i]]; }
+        m.weight = ri->weight;
+        m.level = lev;
+        ri->msg = m;
+        a.row_off[row] = start;
+        a.tile_off[(size_t)row * (a.ntiles + 1) + a.ntiles] = (uint32_t)nnz;
+        if (row == a.M - 1) {
+            a.row_off[a.M] = start + nnz;
+            if (start + nnz > a.capacity) atomicOr(a.dev_status, MLMC_DEV_CAPACITY);
         }
     }
-    const Thr3 th = load_thr3(ri);
-    const float w = ri->weight;
+}
+
+// ---------------------------------------------------------------------------------------------------
+// The message read.  One workgroup per (chunk, row), one tile per step.
+constexpr int WR_THREADS = 512;
+constexpr int WR_WAVES = WR_THREADS / 64;
+constexpr int WR_LINES = TILE / (WR_WAVES * 64);   // 64-element lines of a wave per step
+constexpr int WR_STAGE = 1024;   // entries of one step that are gathered in LDS and written densely
+
+template <int DT, bool VEC>
+__global__ __launch_bounds__(WR_THREADS, 4) void k_write(TopkArgs a) {
+    __shared__ uint32_t s_wemit[2][WR_WAVES];
+    __shared__ uint2 s_out[2][WR_STAGE];
+    const int row = blockIdx.y, chunk_id = blockIdx.x, tid = threadIdx.x;
+    const uint32_t lane = lane_id(), wave = tid >> 6;
+    const RowInfo* ri = a.rinfo + row;
+    if (ri->spec_ok) return;   // the message of this row comes from the staged lists (k_filter)
+    const int nc = a.chunks_per_row;
+    const int64_t nt = a.ntiles;
+    const MsgPlan mp = ri->msg;
+    const int64_t rowstart = mp.rowstart;
+    Thr3 th;
+#pragma unroll
+    for (int i = 0; i < 3; ++i) { th.tau[i] = mp.tau[i]; th.jx[i] = mp.jx[i]; }
+    const float w = mp.weight;
     RowLoader<DT, VEC> ld(a.g, a.ld, a.d, row);
     const int64_t c0 = (int64_t)chunk_id * a.chunk;
     const int64_t c1 = c0 + a.chunk < a.d ? c0 + a.chunk : a.d;
-    uint32_t run = s_base;   // entries of this row before the current step
+    const uint32_t base = a.chunk_base[(size_t)row * (nc + 1) + chunk_id];
+    const uint32_t next_base = a.chunk_base[(size_t)row * (nc + 1) + chunk_id + 1];
+    uint32_t run = base;   // entries of this row before the current step
 
     // Thresholds as signed "key > tau" wherever the index plays no part (keys are 31-bit, so -1 admits every
     // key and 0x7FFFFFFF none): all entries equal to the key inside -> tau - 1; none of them -> tau.  "cut"
@@ -1472,14 +1478,7 @@ __global__ __launch_bounds__(WR_THREADS, 4) void k_write(TopkArgs a) {
     __syncthreads();
     if (prev_count) write_out(par ^ 1u, prev_first, prev_count);
     // consistency: the chunk ends where the per-chunk counts say the next one starts
-    if (tid == 0) {
-        const uint32_t expect = s_base + chunk_entries(chunk_id);
-        if (expect != run) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
-        if (chunk_id == nc - 1) {
-            a.tile_off[(size_t)row * (nt + 1) + nt] = run;
-            if ((int64_t)run != s_rownnz) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
-        }
-    }
+    if (tid == 0 && run != next_base) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -1488,96 +1487,31 @@ __global__ __launch_bounds__(WR_THREADS, 4) void k_write(TopkArgs a) {
 // members, in the order the waves met them) are tested against the exact thresholds; a bitmap over the chunk's
 // elements turns the members' offsets into ranks, i.e. into positions of the index-ordered message.
 constexpr int FL_THREADS = 1024;
-constexpr int FL_WORDS = CHUNK_MAX / 32;
 
 __global__ __launch_bounds__(FL_THREADS) void k_filter(TopkArgs a) {
-    __shared__ uint32_t s_bits[FL_WORDS];   // bit rel: element c0 + rel is in the message
-    __shared__ uint32_t s_pre[FL_WORDS];    // members in the words before
-    __shared__ unsigned long long s_red[FL_THREADS / 64];
+    extern __shared__ uint32_t s_dyn[];     // two arrays of chunk / 32 words
+    uint32_t* s_bits = s_dyn;               // bit rel: element c0 + rel is in the message
+    uint32_t* s_pre = s_dyn + a.chunk / 32; // members in the words before
     __shared__ uint32_t s_scan[FL_THREADS / 64 + 1];
-    __shared__ int64_t s_rowstart, s_rownnz;
-    __shared__ uint32_t s_base;
     const int row = blockIdx.y, chunk_id = blockIdx.x, tid = threadIdx.x;
     const uint32_t lane = lane_id(), wave = tid >> 6;
     const RowInfo* ri = a.rinfo + row;
     if (!ri->spec_ok) return;   // k_write reads the row again
-    const int lev = ri->level;
-    const int nzn = ri->n_zones;
     const int nc = a.chunks_per_row;
     const int64_t nt = a.ntiles;
     const int64_t c0 = (int64_t)chunk_id * a.chunk;
     const int64_t c1 = c0 + a.chunk < a.d ? c0 + a.chunk : a.d;
     const int nwords = (int)((c1 - c0 + 31) / 32);
-
     for (int i = tid; i < nwords; i += FL_THREADS) s_bits[i] = 0;
-    // start of this row's message and entries of this row before this chunk (as in k_write)
-    {
-        unsigned long long part = 0;
-        for (int i = tid; i < row; i += FL_THREADS) {
-            const int li = a.rinfo[i].level;
-            part += (unsigned long long)(a.k[0] + a.k[li] - a.k[li - 1]);
-        }
+    const MsgPlan mp = ri->msg;
+    const int64_t rowstart = mp.rowstart;
+    Thr3 th;
 #pragma unroll
-        for (int o = 32; o >= 1; o >>= 1) part += __shfl_xor(part, o, 64);
-        if (lane == 0) s_red[wave] = part;
-        __syncthreads();
-        if (tid == 0) {
-            unsigned long long t = 0;
-            for (int w = 0; w < FL_THREADS / 64; ++w) t += s_red[w];
-            s_rowstart = (int64_t)t;
-            s_rownnz = a.k[0] + a.k[lev] - a.k[lev - 1];
-        }
-        __syncthreads();
-    }
-    int r0 = -1, rl = -1;
-    for (int r = 0; r <= nzn; ++r) {
-        const int lab = ri->region_label[r];
-        if (lab == 0) r0 = r;
-        if (lab == lev) rl = r;
-    }
-    int zs[3] = {-1, -1, -1};
-    {
-        const int z0 = ri->thr_zone[0], za = ri->thr_zone[lev - 1], zb = ri->thr_zone[lev];
-        if (z0 >= 0) zs[0] = 0;
-        if (za >= 0) zs[1] = zb == za ? lev : TMAX + za;
-        if (zb >= 0 && zb != za) zs[2] = lev;
-    }
-    auto chunk_entries = [&](int c) -> uint32_t {
-        const uint32_t* cc = a.chunk_cnt + ((size_t)row * nc + c) * RMAX;
-        const uint32_t* zc = a.chunk_zcnt + ((size_t)row * nc + c) * ZPMAX;
-        uint32_t v = 0;
-        if (r0 >= 0) v += cc[r0];
-        if (rl >= 0) v += cc[rl];
-#pragma unroll
-        for (int i = 0; i < 3; ++i)
-            if (zs[i] >= 0) v += zc[zs[i]];
-        return v;
-    };
-    {
-        unsigned long long part = 0;
-        for (int c = tid; c < chunk_id; c += FL_THREADS) part += chunk_entries(c);
-#pragma unroll
-        for (int o = 32; o >= 1; o >>= 1) part += __shfl_xor(part, o, 64);
-        if (lane == 0) s_red[wave] = part;
-        __syncthreads();
-        if (tid == 0) {
-            unsigned long long t = 0;
-            for (int w = 0; w < FL_THREADS / 64; ++w) t += s_red[w];
-            s_base = (uint32_t)t;
-        }
-        __syncthreads();
-    }
-    const int64_t rowstart = s_rowstart;
-    const uint32_t base = s_base;
-    if (chunk_id == 0 && tid == 0) {
-        a.row_off[row] = rowstart;
-        if (row == a.M - 1) {
-            a.row_off[a.M] = rowstart + s_rownnz;
-            if (rowstart + s_rownnz > a.capacity) atomicOr(a.dev_status, MLMC_DEV_CAPACITY);
-        }
-    }
-    const Thr3 th = load_thr3(ri);
-    const float w = ri->weight;
+    for (int i = 0; i < 3; ++i) { th.tau[i] = mp.tau[i]; th.jx[i] = mp.jx[i]; }
+    const float w = mp.weight;
+    const uint32_t base = a.chunk_base[(size_t)row * (nc + 1) + chunk_id];
+    const uint32_t next_base = a.chunk_base[(size_t)row * (nc + 1) + chunk_id + 1];
+    __syncthreads();
     auto member = [&](uint32_t key, uint32_t j, bool& in0) -> bool {
         in0 = inside_top(th, 0, key, j);
         return in0 || (inside_top(th, 2, key, j) && !inside_top(th, 1, key, j));
@@ -1603,13 +1537,7 @@ __global__ __launch_bounds__(FL_THREADS) void k_filter(TopkArgs a) {
             s_pre[i] = run;
             run += (uint32_t)__popc(s_bits[i]);
         }
-        if (tid == 0) {
-            if (total != chunk_entries(chunk_id)) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
-            if (chunk_id == nc - 1) {
-                a.tile_off[(size_t)row * (nt + 1) + nt] = base + total;
-                if ((int64_t)(base + total) != s_rownnz) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
-            }
-        }
+        if (tid == 0 && base + total != next_base) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
     }
     __syncthreads();
     for (int64_t t = c0 / TILE + tid; t * TILE < c1; t += FL_THREADS)
@@ -1665,7 +1593,8 @@ template <int DT, bool VEC>
 static mlmc_status launch_compact(const mlmc_plan_t* pl, const TopkArgs& a, hipStream_t st) {
     const dim3 grid(pl->chunks_per_row, pl->M);
     // rows whose drawn band was staged get their message from the staged lists, the others from a second read
-    MLMC_LAUNCH(K_FILTER, st, k_filter<<<grid, FL_THREADS, 0, st>>>(a));
+    MLMC_LAUNCH(K_MSGPLAN, st, k_msgplan<<<pl->M, MP_THREADS, 0, st>>>(a));
+    MLMC_LAUNCH(K_FILTER, st, k_filter<<<grid, FL_THREADS, (size_t)pl->chunk / 32 * 8, st>>>(a));
     MLMC_LAUNCH(K_WRITE, st, k_write<DT, VEC><<<grid, WR_THREADS, 0, st>>>(a));
     return MLMC_OK;
 }
