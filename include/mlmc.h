@@ -88,6 +88,15 @@ void mlmc_plan_destroy(mlmc_plan_t *plan);
  */
 mlmc_status mlmc_plan_set_sampling(mlmc_plan_t *plan, int shift);
 
+/*
+ * Tuning hook (MLMC_TOPK plans).  With staging on (the default) the read that selects the thresholds also sets
+ * aside the members of the band the message will hold (Eq. (6)): the level is known before the read when p is
+ * given, and predicted from the sampled histogram when p is adaptive (Alg. 3); the message is then assembled
+ * from what was set aside and the rows are read once.  A wrong prediction, or staging switched off, makes the
+ * library read the row a second time.  Run time only, never a result.
+ */
+mlmc_status mlmc_plan_set_staging(mlmc_plan_t *plan, int enable);
+
 /* Tiles per row of the offset table: ceil(d / MLMC_TILE). */
 int64_t mlmc_plan_num_tiles(const mlmc_plan_t *plan);
 /* MLMC_BITS: planes per row of the packed message = 1 + F_0 + max_l (F_l - F_{l-1}); else 0. */

@@ -22,7 +22,7 @@ MLMC_TOPK, MLMC_BITS = 0, 1
 MLMC_TILE = 4096
 MLMC_MAX_LEVELS = 32
 
-EXPORTS = ["mlmc_plan", "mlmc_plan_destroy", "mlmc_plan_set_sampling", "mlmc_plan_num_tiles", "mlmc_plan_num_planes", "mlmc_geometric_p",
+EXPORTS = ["mlmc_plan", "mlmc_plan_destroy", "mlmc_plan_set_sampling", "mlmc_plan_set_staging", "mlmc_plan_num_tiles", "mlmc_plan_num_planes", "mlmc_geometric_p",
            "mlmc_status_string", "mlmc_level_norms", "mlmc_compress_topk", "mlmc_compress_bits", "mlmc_aggregate",
            "mlmc_profile_enable", "mlmc_profile_reset", "mlmc_profile_num_kernels", "mlmc_profile_kernel_name",
            "mlmc_profile_get"]
@@ -49,6 +49,8 @@ def lib():
         L.mlmc_plan_destroy.argtypes = [vp]
         L.mlmc_plan_set_sampling.restype = C.c_int
         L.mlmc_plan_set_sampling.argtypes = [vp, i32]
+        L.mlmc_plan_set_staging.restype = C.c_int
+        L.mlmc_plan_set_staging.argtypes = [vp, i32]
         L.mlmc_plan_num_tiles.restype = i64
         L.mlmc_plan_num_tiles.argtypes = [vp]
         L.mlmc_plan_num_planes.restype = i32
@@ -158,6 +160,10 @@ class Plan:
     def set_sampling(self, shift: int):
         """Histogram sampling of the threshold search: one block out of 2^shift (run time only, never results)."""
         _check(lib().mlmc_plan_set_sampling(self.handle, int(shift)), "mlmc_plan_set_sampling")
+
+    def set_staging(self, enable: bool):
+        """Stage the drawn band's members during the selection read (run time only, never results)."""
+        _check(lib().mlmc_plan_set_staging(self.handle, int(bool(enable))), "mlmc_plan_set_staging")
 
     def status(self, informational: bool = False) -> int:
         """Device status bits of the last call (synchronises).  MLMC_DEV_REDONE is not an error and is only

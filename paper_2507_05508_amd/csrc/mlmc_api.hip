@@ -81,6 +81,7 @@ static void fill_topk_args(const mlmc_plan_t* pl, TopkArgs& a, const void* g, in
     a.chunk = pl->chunk;
     a.chunks_per_row = pl->chunks_per_row;
     a.sample_shift = pl->sample_shift;
+    a.staging = pl->staging;
     a.ntiles = pl->ntiles;
     a.racc = (RowAcc*)(w + pl->off_racc);
     a.hist = (uint32_t*)(w + pl->off_hist);
@@ -218,6 +219,7 @@ mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dty
     pl->chunks_per_row = (int)((d + chunk - 1) / chunk);   // <= 2^31 / 2^18 = CHUNKS_MAX
     // rows long enough that a second full read matters get their thresholds from a sampled histogram
     pl->sample_shift = d >= ((int64_t)1 << 23) ? 4 : d >= ((int64_t)1 << 21) ? 2 : 0;
+    pl->staging = 1;
 
     size_t off = 0;
     pl->off_racc = off;
@@ -280,6 +282,12 @@ void mlmc_plan_destroy(mlmc_plan_t* plan) { delete plan; }
 mlmc_status mlmc_plan_set_sampling(mlmc_plan_t* plan, int shift) {
     if (!plan || plan->kind != MLMC_TOPK || shift < 0 || shift > 12) return MLMC_EINVAL;
     plan->sample_shift = shift;
+    return MLMC_OK;
+}
+
+mlmc_status mlmc_plan_set_staging(mlmc_plan_t* plan, int enable) {
+    if (!plan || plan->kind != MLMC_TOPK) return MLMC_EINVAL;
+    plan->staging = enable ? 1 : 0;
     return MLMC_OK;
 }
 

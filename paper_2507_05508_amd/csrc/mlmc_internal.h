@@ -99,6 +99,7 @@ struct TopkArgs {
     int32_t chunk;           // elements per workgroup chunk (multiple of TILE, <= CHUNK_MAX)
     int32_t chunks_per_row;
     int32_t sample_shift;    // the first histogram reads one 1024-element block out of 2^sample_shift
+    int32_t staging;         // 1: the selection read stages the members of the (predicted) drawn band
     int64_t ntiles;
     uint32_t* hist;          // [M][NB1] histogram of the sampled blocks
     uint32_t* hist2;         // [M][NB1] full histogram of the rows that are redone exactly
@@ -188,6 +189,7 @@ struct mlmc_plan_s {
     int chunk;
     int chunks_per_row;
     int sample_shift;
+    int staging;
     // workspace byte offsets
     size_t off_racc, off_hist, off_hist2, off_chunk_zcnt, off_zhist, off_zpacc, zero_bytes;  // [0, zero_bytes) is cleared per call
     size_t off_rinfo, off_table, off_chunk_cnt, off_zcol, off_tileoff, off_norms, off_cand_bits, off_cand_idx, off_cand_priv, off_priv_cnt, off_chunk_base;

@@ -327,7 +327,7 @@ __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
         __syncthreads();
     }
     if (tid == 0) {
-        int sl = (a.all_thresholds && a.draw_mode != 3) ? 0 : s_lev;   // norms only: nothing to stage
+        int sl = ((a.all_thresholds && a.draw_mode != 3) || !a.staging) ? 0 : s_lev;   // norms only: nothing to stage
         ri->spec_level = sl;
         ri->spec_ok = (sl > 0 && !(a.all_thresholds && a.draw_mode == 3)) ? 1 : 0;   // adaptive: decided after the draw
         s_lev = sl;

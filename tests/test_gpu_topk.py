@@ -122,6 +122,27 @@ def test_sampled_threshold_search_gives_the_same_message(name, d, M, shift):
         assert redone == {False}    # an eighth of the blocks is plenty: the zones must hold
 
 
+@pytest.mark.parametrize("name,d,M", [("resnet50_adaptive_topk", 7 * 65536 + 4096 + 17, 3), ("tiny_topk", 90_000, 2)])
+def test_message_from_second_read_equals_message_from_staged_lists(name, d, M):
+    """Staging off: every row's message is written by the second read of the row; staging on: from the lists the
+    selection read set aside (or, after a wrong level prediction, by the second read).  Same message either way."""
+    w = W.scaled(W.WORKLOADS[name], d=d, M=M)
+    G = W.generate(w)
+    g = to_device(G)
+    for pf in (None, O.geometric_p(w.L)):
+        for staging in (False, True):
+            plan = _plan_for(w, pf)
+            plan.set_staging(staging)
+            for step in range(8):
+                print(f"{name} staging={staging} adaptive={pf is None} d={d} step={step}", flush=True)
+                msg = P.mlmc_compress_topk(plan, g, seed=21, step=step)
+                want = check_topk_against_oracle(plan, G, 21, step, msg, adaptive=pf is None)
+                assert plan.status() == 0
+                out = P.mlmc_aggregate(plan, msg, 1.0 / M)
+                torch.cuda.synchronize()
+                assert np.array_equal(out.cpu().numpy().view(np.uint32), O.aggregate_sparse(want, w.d, 1.0 / M).view(np.uint32))
+
+
 @pytest.mark.parametrize("shift", [0, 2])
 def test_adversarial_rows_ties_zeros_denormals(shift):
     d = 3 * 4096 + 517
