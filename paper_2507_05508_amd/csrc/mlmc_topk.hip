@@ -1160,8 +1160,11 @@ __global__ __launch_bounds__(256) void k_norms(TopkArgs a) {
     __shared__ uint32_t s_big[TMAX][20];
     __shared__ unsigned long long s_glo[GMAX], s_ghi[GMAX];
     __shared__ uint16_t s_gexp[GMAX], s_gband[GMAX];
+    constexpr int NL_CAP = 96;
     __shared__ Piece s_pc[PMAX];
     __shared__ double s_norm[LMAX];
+    __shared__ int32_t s_nlist[TMAX];
+    __shared__ uint16_t s_list[TMAX][NL_CAP];
     const int row = blockIdx.x, tid = threadIdx.x;
     const RowInfo* ri = a.rinfo + row;
     const RowAcc* ra = a.racc + row;
@@ -1173,24 +1176,54 @@ __global__ __launch_bounds__(256) void k_norms(TopkArgs a) {
     }
     const int np = ra->n_pieces < (uint32_t)PMAX ? (int)ra->n_pieces : PMAX;
     for (int p = tid; p < np; p += 256) s_pc[p] = ra->pieces[p];
+    if (tid < TMAX) s_nlist[tid] = 0;
+    __syncthreads();
+    // the non-zero sums of every band, gathered so that a band's thread walks its own short list
+    for (int g = tid; g < GMAX + np; g += 256) {
+        int band;
+        bool nz;
+        if (g < GMAX) { band = s_gband[g]; nz = (s_glo[g] | s_ghi[g]) != 0; }
+        else { band = s_pc[g - GMAX].band_plus1 - 1; nz = (s_pc[g - GMAX].lo | s_pc[g - GMAX].hi) != 0; }
+        if (nz && band >= 1 && band <= a.L) {
+            const int at = atomicAdd(&s_nlist[band], 1);
+            if (at < NL_CAP) s_list[band][at] = (uint16_t)g;
+        }
+    }
     __syncthreads();
     const int l = tid;
     if (l >= 1 && l <= a.L) {
         BigAcc acc;
         acc.w = s_big[l];
         acc.clear();
-        for (int g = 0; g < GMAX; ++g) {
-            if (s_gband[g] == l && (s_glo[g] | s_ghi[g])) {
-                int sh = 2 * ((int)s_gexp[g] - 1);
-                acc.add(s_glo[g], sh);
-                acc.add(s_ghi[g], sh + 32);
+        const int n = s_nlist[l];
+        if (n <= NL_CAP) {
+            for (int i = 0; i < n; ++i) {
+                const int g = s_list[l][i];
+                if (g < GMAX) {
+                    const int sh = 2 * ((int)s_gexp[g] - 1);
+                    acc.add(s_glo[g], sh);
+                    acc.add(s_ghi[g], sh + 32);
+                } else {
+                    const Piece& pc = s_pc[g - GMAX];
+                    const int sh = 2 * (pc.exp - 1);
+                    acc.add(pc.lo, sh);
+                    acc.add(pc.hi, sh + 32);
+                }
             }
-        }
-        for (int p = 0; p < np; ++p) {
-            if (s_pc[p].band_plus1 == l + 1) {
-                int sh = 2 * (s_pc[p].exp - 1);
-                acc.add(s_pc[p].lo, sh);
-                acc.add(s_pc[p].hi, sh + 32);
+        } else {   // more sums than the list holds: walk everything
+            for (int g = 0; g < GMAX; ++g) {
+                if (s_gband[g] == l && (s_glo[g] | s_ghi[g])) {
+                    const int sh = 2 * ((int)s_gexp[g] - 1);
+                    acc.add(s_glo[g], sh);
+                    acc.add(s_ghi[g], sh + 32);
+                }
+            }
+            for (int p = 0; p < np; ++p) {
+                if (s_pc[p].band_plus1 == l + 1) {
+                    const int sh = 2 * (s_pc[p].exp - 1);
+                    acc.add(s_pc[p].lo, sh);
+                    acc.add(s_pc[p].hi, sh + 32);
+                }
             }
         }
         double nrm = __dsqrt_rn(acc.to_double());
