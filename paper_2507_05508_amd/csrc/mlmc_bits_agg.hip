@@ -191,15 +191,40 @@ __global__ __launch_bounds__(256) void k_agg_sparse(AggSparseArgs a) {
         s_len[r] = len;
     }
     __syncthreads();
-    for (int r = 0; r < a.M; ++r) {
-        const int64_t beg = s_beg[r];
-        const uint32_t len = s_len[r];
-        if (len) {  // uniform
-            for (uint32_t i = threadIdx.x; i < len; i += 256) {
-                uint32_t off = a.idx[beg + i] - (uint32_t)base;
-                if (off < (uint32_t)TILE) s_acc[off] = __fadd_rn(s_acc[off], a.val[beg + i]);
+    // rows in groups of eight: the first 256 entries of every row of the group are fetched back to back (a thread's
+    // entry, or the row's last one when it has fewer), then added in worker order
+    constexpr int RG = 8;
+    for (int r0 = 0; r0 < a.M; r0 += RG) {
+        uint32_t pidx[RG];
+        float pval[RG];
+#pragma unroll
+        for (int k = 0; k < RG; ++k) {
+            const int r = r0 + k;
+            const uint32_t len = r < a.M ? s_len[r] : 0u;
+            pidx[k] = 0xFFFFFFFFu;
+            pval[k] = 0.0f;
+            if (len) {  // uniform
+                const uint32_t e = threadIdx.x < len ? threadIdx.x : len - 1u;
+                pidx[k] = a.idx[s_beg[r] + e];
+                pval[k] = a.val[s_beg[r] + e];
             }
-            __syncthreads();
+        }
+#pragma unroll
+        for (int k = 0; k < RG; ++k) {
+            const int r = r0 + k;
+            const uint32_t len = r < a.M ? s_len[r] : 0u;
+            if (len) {  // uniform
+                const int64_t beg = s_beg[r];
+                if (threadIdx.x < len) {
+                    const uint32_t off = pidx[k] - (uint32_t)base;
+                    if (off < (uint32_t)TILE) s_acc[off] = __fadd_rn(s_acc[off], pval[k]);
+                }
+                for (uint32_t i = threadIdx.x + 256; i < len; i += 256) {
+                    const uint32_t off = a.idx[beg + i] - (uint32_t)base;
+                    if (off < (uint32_t)TILE) s_acc[off] = __fadd_rn(s_acc[off], a.val[beg + i]);
+                }
+                __syncthreads();
+            }
         }
     }
     for (int i = threadIdx.x; i < TILE; i += 256) {
