@@ -686,13 +686,19 @@ __global__ __launch_bounds__(FN_THREADS) void k_fhist(TopkArgs a, int exact_pass
 // candidates of those bins are gathered (a few hundred) and ranked by the workgroup that finishes last, every other
 // candidate is classified by its bin: per-chunk counts of the zone's parts and exact sums per (part, exponent).
 // When a threshold bin is too full to rank in LDS (massive ties) slice 0 resolves the zone alone by radix select.
-template <bool SUMS>
-__global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pass, int phase) {
-    __shared__ uint32_t s_un[TMAX * 256];   // slow path: digit histograms; phase 1: candidates of the threshold bins
+constexpr int ZC0_CAP = 4096;        // the sliced pass takes zones whose (parts x chunks) counters fit this
+
+template <bool SUMS, int PHASE>
+__global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pass) {
+    // phase 0 (many workgroups per zone) keeps its LDS small so that several workgroups share a CU
+    constexpr int UN_WORDS = PHASE == 0 ? COLLECT_CAP * 2 : TMAX * 256;
+    constexpr int ZC = PHASE == 0 ? ZC0_CAP : ZC_CAP;
+    constexpr int PREP = PHASE == 0 ? 8 : REP;   // lane replicas of the part sum accumulators
+    __shared__ uint32_t s_un[UN_WORDS];   // slow path: digit histograms; else: candidates of the threshold bins
     __shared__ uint32_t s_fh[FH_BINS];
     __shared__ uint8_t s_bincls[FH_BINS];
-    __shared__ uint32_t s_zc[ZC_CAP];
-    __shared__ unsigned long long s_pacc[SUMS ? PIECE_CLASSES * REP : 1][2];
+    __shared__ uint32_t s_zc[ZC];
+    __shared__ unsigned long long s_pacc[SUMS ? PIECE_CLASSES * PREP : 1][2];
     __shared__ int32_t s_n, s_ok, s_nsub, s_any, s_fast;
     __shared__ int32_t s_t[TMAX], s_sub[TMAX];
     __shared__ uint32_t s_res[TMAX], s_pfx[TMAX], s_tau[TMAX], s_q[TMAX], s_eq[TMAX], s_jx[TMAX];
@@ -701,13 +707,13 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
     __shared__ uint32_t s_ncollect;
     uint32_t (*s_hist)[256] = (uint32_t(*)[256])s_un;
     unsigned long long* s_col = (unsigned long long*)s_un;    // [COLLECT_CAP] as collected
-    unsigned long long* s_srt = s_col + COLLECT_CAP;          // [COLLECT_CAP] in descending order
-    static_assert(sizeof(s_un) >= 2 * COLLECT_CAP * sizeof(unsigned long long), "candidate buffers must fit");
+    unsigned long long* s_srt = s_col + COLLECT_CAP;          // [COLLECT_CAP] in descending order (phase 1)
+    static_assert(PHASE == 0 || sizeof(s_un) >= 2 * COLLECT_CAP * sizeof(unsigned long long), "candidate buffers must fit");
 
     __shared__ uint32_t s_fill[ZMAX], s_rcnt[RMAX];
     __shared__ int32_t s_first[ZMAX + 1];
     const int row = blockIdx.y, tid = threadIdx.x;
-    const uint32_t lane = lane_id(), wave = tid >> 6, l31 = lane & 31u;
+    const uint32_t lane = lane_id(), wave = tid >> 6, lrep = lane & (uint32_t)(PREP - 1);
     RowInfo* ri = a.rinfo + row;
     RowAcc* ra = a.racc + row;
     if (exact_pass && !ri->respec) return;
@@ -719,7 +725,7 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
         if (fail_bit) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
         else atomicOr((int32_t*)&ri->respec, 1);
     };
-    const int nitems = finish_items(ri, ra, phase == 0, s_fill, s_rcnt, s_first);
+    const int nitems = finish_items(ri, ra, PHASE == 0, s_fill, s_rcnt, s_first);
 
     auto run_item = [&](const int z, const int slice) {
     const uint32_t n = s_fill[z];
@@ -757,7 +763,7 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
     const int nthr = s_n;
     const int nparts = nthr + 1;
     const int nchunks = a.chunks_per_row;
-    const bool count_fits = nparts * nchunks <= ZC_CAP;
+    const bool count_fits = nparts * nchunks <= ZC;
     const uint32_t cmagic = (uint32_t)(0x100000000ull / (uint32_t)(a.chunk >> 12)) + 1u;   // chunk = multiple of 4096, >= 4 * 4096
     auto chunk_of = [&](uint32_t j) -> uint32_t { return __umulhi(j >> 12, cmagic); };
 
@@ -782,7 +788,7 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
         for (int i = tid; i < FH_BINS; i += FN_THREADS) s_fh[i] = zh[i];
     }
     if (count_fits) for (int i = tid; i < nparts * nchunks; i += FN_THREADS) s_zc[i] = 0;
-    if (SUMS) for (int i = tid; i < PIECE_CLASSES * REP * 2; i += FN_THREADS) (&s_pacc[0][0])[i] = 0ull;
+    if (SUMS) for (int i = tid; i < PIECE_CLASSES * PREP * 2; i += FN_THREADS) (&s_pacc[0][0])[i] = 0ull;
     __syncthreads();
 
     // what every candidate contributes once its part (number of the zone's thresholds it is NOT inside) is known
@@ -792,8 +798,8 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
             const int E = (int)(key >> 23) ? (int)(key >> 23) : 1;
             const int cls = part * span + (E - Elo);
             const unsigned long long sq = sig_square(key);
-            atomicAdd(&s_pacc[cls * REP + l31][0], sq & 0xFFFFFFFFull);
-            atomicAdd(&s_pacc[cls * REP + l31][1], sq >> 32);
+            atomicAdd(&s_pacc[cls * PREP + lrep][0], sq & 0xFFFFFFFFull);
+            atomicAdd(&s_pacc[cls * PREP + lrep][1], sq >> 32);
         }
     };
     // LDS counters and sums -> the zone's totals
@@ -810,7 +816,7 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
         }
         if (SUMS && with_sums && tid < nclass) {
             unsigned long long lo = 0, hi = 0;
-            for (int r = 0; r < REP; ++r) { lo += s_pacc[tid * REP + r][0]; hi += s_pacc[tid * REP + r][1]; }
+            for (int r = 0; r < PREP; ++r) { lo += s_pacc[tid * PREP + r][0]; hi += s_pacc[tid * PREP + r][1]; }
             if (lo) atomicAdd(&zp[tid * 2], lo);
             if (hi) atomicAdd(&zp[tid * 2 + 1], hi);
         }
@@ -839,15 +845,15 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
     }
     __syncthreads();
     if (!s_ok) return;
-    const bool serial = !s_fast || !count_fits;   // one workgroup does the whole list
-    if (serial && slice != 0) return;
-    const int Seff = serial ? 1 : S;
+    // zones that the sliced pass (phase 0) takes; every other zone is resolved by one workgroup in phase 1
+    const bool par_ok = s_fast && nparts * nchunks <= ZC0_CAP;
+    if (PHASE == 0 && !par_ok) return;
+    const int Seff = PHASE == 0 ? S : 1;
     const uint32_t per = (n + Seff - 1) / Seff;
     const uint32_t i0 = (uint32_t)slice * per, i1 = i0 + per < n ? i0 + per : n;
-
     const uint32_t ncollect_zone = s_ncollect;   // candidates in the thresholds' bins, all slices together
     __syncthreads();
-    if (s_fast && phase == 0) {
+    if (s_fast) {
         if (tid == 0) s_ncollect = 0;
         for (int b = tid; b < FH_BINS; b += FN_THREADS) {
             int part = 0;
@@ -859,39 +865,47 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
             s_bincls[b] = isthr ? (uint8_t)0xFF : (uint8_t)part;
         }
         __syncthreads();
-        // ---- read 2 ----
-        batched_loop<8, FN_THREADS>(i0, i1, (uint32_t)tid, [&](uint32_t i) { return make_uint2(kb[i], kj[i]); },
-                                    [&](uint32_t, uint2 e) {
-            const uint32_t key = key_of_bits(e.x);
-            const uint32_t j = e.y;
-            uint32_t b = (key - kmin) >> sh;
-            b = b < (uint32_t)FH_BINS ? b : (uint32_t)FH_BINS - 1;
-            const uint32_t cls = s_bincls[b];
-            if (cls == 0xFFu) {   // gathered in LDS first: one reservation in the zone's list per workgroup
-                const uint32_t at = atomicAdd(&s_ncollect, 1u);
-                if (at < (uint32_t)COLLECT_CAP) s_col[at] = ((unsigned long long)key << 32) | (uint32_t)~j;
-            } else {
-                classify((int)cls, key, j);
-            }
-        });
-        __syncthreads();
-        const uint32_t mine = s_ncollect;   // <= COLLECT_CAP: the zone's threshold bins hold no more
-        __syncthreads();
-        if (tid == 0) s_ncollect = mine ? atomicAdd(&ra->zone_colcnt[z], mine) : 0u;
-        __syncthreads();
-        const uint32_t at0 = s_ncollect;
-        for (uint32_t e = tid; e < mine; e += FN_THREADS)
-            if (at0 + e < (uint32_t)COLLECT_CAP) zcol[at0 + e] = s_col[e];
-        flush_totals(true);
-        return;   // phase 1 (the next launch) ranks the gathered candidates
-    }
-    if (s_fast) {
+        // ---- read 2: candidates of the thresholds' bins are gathered in LDS, every other one is classified ----
+        if (PHASE == 0 || !par_ok) {
+            batched_loop<8, FN_THREADS>(i0, i1, (uint32_t)tid, [&](uint32_t i) { return make_uint2(kb[i], kj[i]); },
+                                        [&](uint32_t, uint2 e) {
+                const uint32_t key = key_of_bits(e.x);
+                const uint32_t j = e.y;
+                uint32_t b = (key - kmin) >> sh;
+                b = b < (uint32_t)FH_BINS ? b : (uint32_t)FH_BINS - 1;
+                const uint32_t cls = s_bincls[b];
+                if (cls == 0xFFu) {
+                    const uint32_t at = atomicAdd(&s_ncollect, 1u);
+                    if (at < (uint32_t)COLLECT_CAP) s_col[at] = ((unsigned long long)key << 32) | (uint32_t)~j;
+                } else {
+                    classify((int)cls, key, j);
+                }
+            });
+            __syncthreads();
+        }
+        if constexpr (PHASE == 0) {
+            // one reservation in the zone's list per workgroup; phase 1 (the next launch) ranks the gathered candidates
+            const uint32_t mine = s_ncollect;   // <= COLLECT_CAP: the zone's threshold bins hold no more
+            __syncthreads();
+            if (tid == 0) s_ncollect = mine ? atomicAdd(&ra->zone_colcnt[z], mine) : 0u;
+            __syncthreads();
+            const uint32_t at0 = s_ncollect;
+            for (uint32_t e = tid; e < mine; e += FN_THREADS)
+                if (at0 + e < (uint32_t)COLLECT_CAP) zcol[at0 + e] = s_col[e];
+            flush_totals(true);
+            return;
+        }
         const uint32_t ncol = ncollect_zone;
-        if (ra->zone_colcnt[z] != ncol) {
+        if (par_ok) {
+            if (ra->zone_colcnt[z] != ncol) {
+                if (tid == 0) fail();
+                return;
+            }
+            for (uint32_t e = tid; e < ncol; e += FN_THREADS) s_col[e] = zcol[e];
+        } else if (s_ncollect != ncol) {
             if (tid == 0) fail();
             return;
         }
-        for (uint32_t e = tid; e < ncol; e += FN_THREADS) s_col[e] = zcol[e];
         __syncthreads();
         // descending order of (key, lower index first) by counting: composites are distinct
         for (uint32_t e = tid; e < ncol; e += FN_THREADS) {
@@ -916,8 +930,8 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
             const unsigned long long c = s_srt[e];
             classify(part, (uint32_t)(c >> 32), ~(uint32_t)c);
         }
-        flush_totals(false);   // their sums stay in LDS and are added to the zone's totals below
-    } else if (phase == 0) {
+        flush_totals(false);   // the sums stay in LDS and are added to the zone's totals below
+    } else if constexpr (PHASE == 1) {
         // ---- slow path (a threshold bin too full to rank in LDS, e.g. massive ties): radix select on the
         //      keys, digits of 8, 8, 8, 7 bits from the top, then on the indices of the entries equal to the key ----
         for (int pass = 0; pass < 4; ++pass) {
@@ -1037,15 +1051,15 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
         }
         flush_totals(true);
         __syncthreads();
-        if (SUMS) for (int i = tid; i < PIECE_CLASSES * REP * 2; i += FN_THREADS) (&s_pacc[0][0])[i] = 0ull;
+        if (SUMS) for (int i = tid; i < PIECE_CLASSES * PREP * 2; i += FN_THREADS) (&s_pacc[0][0])[i] = 0ull;
     }
     __syncthreads();
-    const bool resolved_here = s_fast ? phase == 1 : phase == 0;   // this launch found the zone's thresholds
-    if (resolved_here && tid < nthr) {
+    if (PHASE == 0) return;
+    if (tid < nthr) {
         ri->thr_tau[s_t[tid]] = s_tau[tid];
         ri->thr_jx[s_t[tid]] = s_jx[tid];
     }
-    if (resolved_here && !count_fits) {
+    if (!count_fits) {
         // long rows with many thresholds in one zone: a few parts at a time, one more read of the list each
         const int ppp = ZC_CAP / nchunks;   // >= 1: a row has at most CHUNKS_MAX = ZC_CAP chunks
         for (int p0 = 0; p0 < nparts; p0 += ppp) {
@@ -1070,14 +1084,14 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
             }
         }
     }
-    if (!SUMS || phase == 0) return;
+    if (!SUMS) return;
 
     // ---- exact sums of the parts: one piece per (part, exponent): the zone's totals of the earlier launch plus
     //      what the ranked candidates added here ----
     __syncthreads();
     if (tid < nclass) {
         unsigned long long lo = zp[tid * 2], hi = zp[tid * 2 + 1];
-        for (int r = 0; r < REP; ++r) { lo += s_pacc[tid * REP + r][0]; hi += s_pacc[tid * REP + r][1]; }
+        for (int r = 0; r < PREP; ++r) { lo += s_pacc[tid * PREP + r][0]; hi += s_pacc[tid * PREP + r][1]; }
         hi += lo >> 32;
         lo &= 0xFFFFFFFFull;
         if (lo | hi) {
@@ -1611,11 +1625,14 @@ static mlmc_status launch_select(const mlmc_plan_t* pl, const TopkArgs& a, bool 
         if (sums) MLMC_LAUNCH(km, st, k_main<DT, VEC, true><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
         else MLMC_LAUNCH(km, st, k_main<DT, VEC, false><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
         MLMC_LAUNCH(exact_pass ? K_REDO : K_FHIST, st, k_fhist<<<fgrid, FN_THREADS, 0, st>>>(a, exact_pass));
-        for (int phase = 0; phase < 2; ++phase) {
-            const dim3 g2 = phase == 0 ? fgrid : dim3(pl->L + 1 < FIN_WGS ? pl->L + 1 : FIN_WGS, pl->M);
-            const int kid = exact_pass ? K_REDO : (phase ? K_FINISH1 : K_FINISH);
-            if (sums) MLMC_LAUNCH(kid, st, k_finish<true><<<g2, FN_THREADS, 0, st>>>(a, exact_pass, phase));
-            else MLMC_LAUNCH(kid, st, k_finish<false><<<g2, FN_THREADS, 0, st>>>(a, exact_pass, phase));
+        const dim3 rgrid(pl->L + 1 < FIN_WGS ? pl->L + 1 : FIN_WGS, pl->M);
+        const int k0 = exact_pass ? K_REDO : K_FINISH, k1 = exact_pass ? K_REDO : K_FINISH1;
+        if (sums) {
+            MLMC_LAUNCH(k0, st, k_finish<true, 0><<<fgrid, FN_THREADS, 0, st>>>(a, exact_pass));
+            MLMC_LAUNCH(k1, st, k_finish<true, 1><<<rgrid, FN_THREADS, 0, st>>>(a, exact_pass));
+        } else {
+            MLMC_LAUNCH(k0, st, k_finish<false, 0><<<fgrid, FN_THREADS, 0, st>>>(a, exact_pass));
+            MLMC_LAUNCH(k1, st, k_finish<false, 1><<<rgrid, FN_THREADS, 0, st>>>(a, exact_pass));
         }
     }
     if (sums) MLMC_LAUNCH(K_NORMS, st, k_norms<<<pl->M, 256, 0, st>>>(a));
