@@ -30,15 +30,21 @@ constexpr int FIN_WGS = 48;             // workgroups per row that take the (zon
 // top k of the zone's previous threshold has slot t; the part below every threshold of zone z has slot TMAX + z.
 constexpr int ZPMAX = 2 * TMAX;
 
-// Class table code of a first-digit bucket: bits 0..8 sum group; bits 9..15 counter (region 0..63, or 64 + zone);
-// bit 16 "stage this element" (zone candidate, or member of a band the message is expected to hold); bits 18..23
-// the tag it is staged under (zone, or TAG_MEMBER).  Zone buckets carry the group G_DUMMY, so the selection
-// read needs no branch around its accumulators.
-constexpr uint32_t CODE_ZONE = 0x8000;
-constexpr uint32_t CODE_STAGE = 0x10000;
+// Class table code of a first-digit bucket, laid out so that the selection read forms its LDS addresses with
+// one or two instructions: bits 0..5 the tag an element is staged under (zone, or TAG_MEMBER); bits 6..12 the
+// counter (region 0..63, or 64 + zone), i.e. already multiplied by the 64 bytes of a counter's replicas;
+// bit 13 "stage this element" (zone candidate, or member of a band the message is expected to hold);
+// bits 23..31 the sum group (after >> 16: multiplied by the 128 bytes of a group's replicas).  Zone buckets
+// carry the group G_DUMMY, so the selection read needs no branch around its accumulators.
+constexpr uint32_t CODE_ZONE = 0x1000;
+constexpr uint32_t CODE_STAGE = 0x2000;
 constexpr uint32_t TAG_MEMBER = 63;
+__host__ __device__ constexpr uint32_t class_code(uint32_t group, uint32_t counter, uint32_t tag, bool stage) {
+    return (group << 23) | (counter << 6) | tag | (stage ? CODE_STAGE : 0u);
+}
 constexpr int G_DUMMY = GMAX - 1;
 constexpr int REP_SUM = 16;             // replicas of the 64-bit group sum accumulators: slot = id * 16 + (lane & 15)
+constexpr int REP_CNT = 16;             // replicas of the 32-bit region / zone counters
 
 constexpr int THR_NONE = -1;      // k_t == 0: nothing is within the top k_t
 constexpr int THR_ALL = -2;       // k_t >= d: everything is

@@ -343,13 +343,13 @@ __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
         const uint32_t b = (uint32_t)(NB1 - 1 - (tid * 16 + i));
         while (zi < nz && s_zbot[zi] > b) ++zi;
         if (zi < nz && b <= s_ztop[zi]) {
-            codes[15 - i] = CODE_STAGE | ((uint32_t)zi << 18) | CODE_ZONE | ((uint32_t)zi << 9) | (uint32_t)G_DUMMY;
+            codes[15 - i] = class_code((uint32_t)G_DUMMY, 64u + (uint32_t)zi, (uint32_t)zi, true);
         } else {
             const uint32_t E = b >> 6;
             const int gid = (int)(255 - E) + zi;
             const int lab = s_label[zi];
             const bool member = spec > 0 && (lab == 0 || lab == spec);
-            codes[15 - i] = (member ? (CODE_STAGE | (TAG_MEMBER << 18)) : 0u) | ((uint32_t)zi << 9) | (uint32_t)gid;
+            codes[15 - i] = class_code((uint32_t)gid, (uint32_t)zi, member ? TAG_MEMBER : 0u, member);
             ri->g_exp[gid] = (uint16_t)(E ? E : 1);
             ri->g_band[gid] = (uint16_t)lab;
         }
@@ -367,17 +367,21 @@ constexpr int MAIN_THREADS = 1024;
 constexpr int MAIN_WAVES = MAIN_THREADS / 64;
 constexpr int RING = 256;    // staged entries per wave (ring); at most 63 + 64 are pending at any time
 
-// LDS layout (bytes).  The table sits at offset 0 so that the look-up needs no base.
+// LDS layout (bytes).  The table sits at offset 0 so that the look-up needs no base; the sums at 64 KB and the
+// counters at a multiple of 8 KB so that their bases can be OR-ed with the fields of the class code.
 constexpr int LM_TAB = 0;                                   // uint32 [NB1]
-constexpr int LM_CNT = LM_TAB + NB1 * 4;                    // uint32 [128][REP]: regions 0..63, zones 64..127
-constexpr int LM_ZCUR = LM_CNT + 128 * REP * 4;             // uint32 [64] write cursor of every zone list
+constexpr int LM_SUM = NB1 * 4;                             // uint64 [GMAX][REP_SUM]
+constexpr int LM_CNT = 13 * 8192;                           // uint32 [128][REP_CNT]: regions 0..63, zones 64..127
+constexpr int LM_ZCUR = LM_CNT + 128 * REP_CNT * 4;         // uint32 [64] write cursor of every zone list
 constexpr int LM_ZMAX = LM_ZCUR + 64 * 4;                   // uint32 [64] largest candidate key of every zone
 constexpr int LM_ZMIN = LM_ZMAX + 64 * 4;                   // uint32 [64] largest ~key
 constexpr int LM_ZOFF = LM_ZMIN + 64 * 4;                   // uint32 [64]
 constexpr int LM_ZCAP = LM_ZOFF + 64 * 4;
 constexpr int LM_STAGE = LM_ZCAP + 64 * 4;                  // uint2 [MAIN_WAVES][RING]: {bits, rel << 6 | tag}
-constexpr int LM_SUM = LM_STAGE + MAIN_WAVES * RING * 8;    // uint64 [GMAX][REP_SUM]
-template <bool SUMS> constexpr int lm_total() { return LM_SUM + (SUMS ? GMAX * REP_SUM * 8 : 0); }
+constexpr int LM_END = LM_STAGE + MAIN_WAVES * RING * 8;
+static_assert(LM_SUM == 65536 && LM_SUM + GMAX * REP_SUM * 8 <= LM_CNT && LM_CNT % 8192 == 0, "LDS layout");
+static_assert(REP_SUM * 8 == 128 && REP_CNT * 4 == 64, "field scaling of the class code");
+template <bool SUMS> constexpr int lm_total() { return LM_END; }
 static_assert(lm_total<true>() <= 160 * 1024, "LDS budget");
 static_assert(ZMAX <= 64 && RMAX <= 64 && GMAX <= 512, "field widths of the class code");
 
@@ -422,7 +426,7 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
     // this wave's private, worst-case sized part of the scratch list: its candidates in the order met
     uint2* priv = a.cand_priv + ((size_t)row * a.chunks_per_row + blockIdx.x) * (size_t)a.chunk + (size_t)wave * (a.chunk / MAIN_WAVES);
     // per-lane byte addresses of the replicated accumulators
-    const uint32_t cnt_lane = (uint32_t)LM_CNT + (lane & 31u) * 4u;
+    const uint32_t cnt_lane = (uint32_t)LM_CNT + (lane & 15u) * 4u;
     const uint32_t sum_lane = (uint32_t)LM_SUM + (lane & 15u) * 8u;
     uint32_t head = 0, tail = 0;   // wave-uniform: candidates staged / written out so far
     uint32_t maxkey = 0;
@@ -448,26 +452,26 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
         uint32_t anys = 0;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            if (!((vmask >> c) & 1u)) code[c] = (63u << 9) | (uint32_t)G_DUMMY;
+            if (!((vmask >> c) & 1u)) code[c] = class_code((uint32_t)G_DUMMY, 63u, 0u, false);
             const uint32_t key = key_of_bits(b[c]);
             if (SUMS) {
                 const uint32_t hid = (key & 0x7FFFFFu) | 0x800000u;
                 const uint32_t sig = key < hid ? key : hid;   // exponent field 0: no hidden bit, sig = key
-                atomicAdd((unsigned long long*)(lm + (((code[c] & 511u) << 7) + sum_lane)),
+                atomicAdd((unsigned long long*)(lm + ((code[c] >> 16) | sum_lane)),
                           (unsigned long long)sig * (unsigned long long)sig);
             }
-            atomicAdd((uint32_t*)(lm + (((code[c] >> 2) & 0x3F80u) + cnt_lane)), 1u);
+            atomicAdd((uint32_t*)(lm + ((code[c] & 0x1FC0u) | cnt_lane)), 1u);
             maxkey = key > maxkey ? key : maxkey;
             anys |= code[c];
         }
         if (__ballot(anys & CODE_STAGE)) {
+            const uint32_t relc = rel0 << 6;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                const bool stage = (code[c] & CODE_STAGE) != 0;
-                const uint64_t m = __ballot(stage);
-                if (stage) {
+                const uint64_t m = __ballot(code[c] & CODE_STAGE);
+                if (__builtin_amdgcn_inverse_ballot_w64(m)) {
                     const uint32_t pos = (head + mbcnt(m)) % (uint32_t)RING;
-                    s_stage[pos] = make_uint2(b[c], ((rel0 + c) << 6) | ((code[c] >> 18) & 63u));
+                    s_stage[pos] = make_uint2(b[c], (relc + ((uint32_t)c << 6)) | (code[c] & 63u));
                 }
                 head += (uint32_t)__popcll(m);
                 if (head - tail >= 64u) drain(false);   // at most 63 + 64 entries are ever pending
@@ -517,7 +521,7 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
     // ---- the workgroup's candidates move from the private lists to the zones' lists: one reservation per zone ----
     if (tid < nz) {
         uint32_t total = 0;
-        for (int r = 0; r < REP; ++r) total += s_cnt[(64 + tid) * REP + ((r + tid) & (REP - 1))];
+        for (int r = 0; r < REP_CNT; ++r) total += s_cnt[(64 + tid) * REP_CNT + ((r + tid) & (REP_CNT - 1))];
         s_zcur[tid] = total ? atomicAdd(&ra->zone_fill[tid], total) : 0u;
     }
     __syncthreads();
@@ -565,7 +569,7 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
     }
     if (tid < RMAX) {
         uint32_t cnt = 0;
-        for (int r = 0; r < REP; ++r) cnt += s_cnt[tid * REP + ((r + tid) & (REP - 1))];
+        for (int r = 0; r < REP_CNT; ++r) cnt += s_cnt[tid * REP_CNT + ((r + tid) & (REP_CNT - 1))];
         a.chunk_cnt[((size_t)row * a.chunks_per_row + blockIdx.x) * RMAX + tid] = cnt;
         if (cnt) atomicAdd(&ra->region_cnt[tid], cnt);
     }
