@@ -17,10 +17,24 @@ __global__ __launch_bounds__(512) void k_bits_max(BitsArgs a) {
     const int64_t c1 = c0 + a.chunk < a.d ? c0 + a.chunk : a.d;
     RowLoader<DT, VEC> ld(a.g, a.ld, a.d, row);
     uint32_t maxkey = 0;
-#pragma unroll 4
-    for (int64_t j = c0 + (int64_t)threadIdx.x * 4; j < c1; j += 512 * 4) {
+    constexpr int64_t STEP = 512 * 4;
+    int64_t j = c0 + (int64_t)threadIdx.x * 4;
+    for (; j + 3 * STEP + 4 <= c1; j += 4 * STEP) {   // four loads in flight, no bounds checks inside
+        uint32_t b[4][4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) ld.load4_full(j + u * STEP, b[u]);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t key = key_of_bits(b[u][c]);
+                maxkey = key > maxkey ? key : maxkey;
+            }
+    }
+    for (; j < c1; j += STEP) {
         uint32_t b[4];
         int nv = ld.load4(j, b);
+        if (j + nv > c1) nv = (int)(c1 - j);
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             uint32_t key = c < nv ? key_of_bits(b[c]) : 0u;
@@ -66,10 +80,7 @@ __global__ __launch_bounds__(256) void k_bits_extract(BitsArgs a) {
         uint64_t words[MAX_PLANES];
 #pragma unroll
         for (int p = 0; p < MAX_PLANES; ++p) words[p] = 0;
-#pragma unroll 8
-        for (int i = 0; i < 64; ++i) {
-            const int64_t j = base + i * 64 + lane;
-            uint32_t bits = j < a.d ? ld.load1(j) : 0u;
+        auto digits = [&](uint32_t bits) -> uint32_t {
             uint32_t key = key_of_bits(bits);
             uint32_t E = key >> 23;
             uint32_t sig = E ? ((key & 0x7FFFFFu) | 0x800000u) : (key & 0x7FFFFFu);
@@ -77,13 +88,30 @@ __global__ __launch_bounds__(256) void k_bits_extract(BitsArgs a) {
             uint32_t m = shift < 32 ? (sig >> shift) : 0u;   // floor(|g| / 2^e * 2^Q), e = Emax - 126
             uint32_t f0 = br.F0 ? (m >> (br.Q - br.F0)) : 0u;
             uint32_t f = (m >> (br.Q - br.Fl)) & ((1u << br.width) - 1u);
-            uint32_t packed = (bits >> 31) | (f0 << 1) | (f << (1 + br.F0));  // plane p <-> bit p
+            return (bits >> 31) | (f0 << 1) | (f << (1 + br.F0));  // plane p <-> bit p
+        };
+        auto pack = [&](int i, uint32_t packed) {
 #pragma unroll
             for (int p = 0; p < MAX_PLANES; ++p) {
                 if (p < np) {
                     uint64_t w = __ballot((packed >> p) & 1u);
                     if (lane == (uint32_t)i) words[p] = w;
                 }
+            }
+        };
+        if (base + TILE <= a.d) {   // a whole tile: sixteen loads in flight, no bounds checks inside
+            for (int i0 = 0; i0 < 64; i0 += 16) {
+                uint32_t v[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) v[u] = ld.load1(base + (i0 + u) * 64 + lane);
+#pragma unroll
+                for (int u = 0; u < 16; ++u) pack(i0 + u, digits(v[u]));
+            }
+        } else {
+            for (int i = 0; i < 64; ++i) {
+                const int64_t j = base + i * 64 + lane;
+                const uint32_t bits = j < a.d ? ld.load1(j) : 0u;
+                pack(i, digits(bits));
             }
         }
         const int64_t w0 = tile * 64 + lane;
