@@ -849,15 +849,23 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
     }
     __syncthreads();
     if (!s_ok) return;
-    // zones that the sliced pass (phase 0) takes; every other zone is resolved by one workgroup in phase 1
-    const bool par_ok = s_fast && nparts * nchunks <= ZC0_CAP;
-    if (PHASE == 0 && !par_ok) return;
+    // Zones that the sliced pass (phase 0) takes: those whose per-chunk counters fit its LDS.  When the thresholds'
+    // bins hold few candidates (par_ok) they are gathered for ranking in LDS; when they hold many (massive ties,
+    // e.g. bf16 keys: par_big) they are moved to the zone's overflow list, on which phase 1 runs a radix select.
+    // Every other zone is resolved by one workgroup in phase 1.
+    const bool fits0 = nparts * nchunks <= ZC0_CAP;
+    const bool par_ok = s_fast && fits0;
+    const bool par_big = !s_fast && fits0;
+    if (PHASE == 0 && !par_ok && !par_big) return;
     const int Seff = PHASE == 0 ? S : 1;
     const uint32_t per = (n + Seff - 1) / Seff;
     const uint32_t i0 = (uint32_t)slice * per, i1 = i0 + per < n ? i0 + per : n;
     const uint32_t ncollect_zone = s_ncollect;   // candidates in the thresholds' bins, all slices together
+    uint32_t* c2b = a.cand2_bits + (size_t)row * (size_t)a.d + ri->zone_off[z];
+    uint32_t* c2j = a.cand2_idx + (size_t)row * (size_t)a.d + ri->zone_off[z];
+    const uint32_t zcap = ri->zone_cap[z];
     __syncthreads();
-    if (s_fast) {
+    if (s_fast || (PHASE == 0 && par_big)) {
         if (tid == 0) s_ncollect = 0;
         for (int b = tid; b < FH_BINS; b += FN_THREADS) {
             int part = 0;
@@ -869,6 +877,50 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
             s_bincls[b] = isthr ? (uint8_t)0xFF : (uint8_t)part;
         }
         __syncthreads();
+    }
+    if (PHASE == 0 && par_big) {
+        // ---- read 2, massive ties: the thresholds' bins go to the overflow list.  First everything else is
+        //      classified and the slice's share counted, then one reservation per workgroup, then the copy ----
+        auto bin_class = [&](uint32_t key) -> uint32_t {
+            uint32_t b = (key - kmin) >> sh;
+            b = b < (uint32_t)FH_BINS ? b : (uint32_t)FH_BINS - 1;
+            return s_bincls[b];
+        };
+        batched_loop<8, FN_THREADS>(i0, i1, (uint32_t)tid, [&](uint32_t i) { return make_uint2(kb[i], kj[i]); },
+                                    [&](uint32_t, uint2 e) {
+            const uint32_t key = key_of_bits(e.x);
+            const uint32_t cls = bin_class(key);
+            const bool col = cls == 0xFFu;
+            const uint64_t m = __ballot(col);
+            if (m && (int)lane == __builtin_ctzll(m)) atomicAdd(&s_ncollect, (uint32_t)__popcll(m));
+            if (!col) classify((int)cls, key, e.y);
+        });
+        __syncthreads();
+        const uint32_t mine = s_ncollect;
+        __syncthreads();
+        if (tid == 0) s_ncollect = mine ? atomicAdd(&ra->zone_colcnt[z], mine) : 0u;   // becomes the write cursor
+        __syncthreads();
+        if (mine) {
+            batched_loop<8, FN_THREADS>(i0, i1, (uint32_t)tid, [&](uint32_t i) { return make_uint2(kb[i], kj[i]); },
+                                        [&](uint32_t, uint2 e) {
+                const bool col = bin_class(key_of_bits(e.x)) == 0xFFu;
+                const uint64_t m = __ballot(col);
+                if (m) {
+                    const int first = __builtin_ctzll(m);
+                    uint32_t base = 0;
+                    if ((int)lane == first) base = atomicAdd(&s_ncollect, (uint32_t)__popcll(m));
+                    base = __shfl(base, first, 64);
+                    if (col) {
+                        const uint32_t pos = base + mbcnt(m);
+                        if (pos < zcap) { c2b[pos] = e.x; c2j[pos] = e.y; }
+                    }
+                }
+            });
+        }
+        flush_totals(true);
+        return;
+    }
+    if (s_fast) {
         // ---- read 2: candidates of the thresholds' bins are gathered in LDS, every other one is classified ----
         if (PHASE == 0 || !par_ok) {
             batched_loop<8, FN_THREADS>(i0, i1, (uint32_t)tid, [&](uint32_t i) { return make_uint2(kb[i], kj[i]); },
@@ -937,7 +989,18 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
         flush_totals(false);   // the sums stay in LDS and are added to the zone's totals below
     } else if constexpr (PHASE == 1) {
         // ---- slow path (a threshold bin too full to rank in LDS, e.g. massive ties): radix select on the
-        //      keys, digits of 8, 8, 8, 7 bits from the top, then on the indices of the entries equal to the key ----
+        //      keys, digits of 8, 8, 8, 7 bits from the top, then on the indices of the entries equal to the key.
+        //      It runs on the overflow list (the thresholds' bins only) when phase 0 built one, else on the whole list ----
+        const uint32_t* xb = par_big ? c2b : kb;
+        const uint32_t* xj = par_big ? c2j : kj;
+        const uint32_t xn = par_big ? ncollect_zone : n;
+        if (par_big) {
+            if (ra->zone_colcnt[z] != ncollect_zone || ncollect_zone > zcap) {
+                if (tid == 0) fail();
+                return;
+            }
+            if (tid < nthr) { s_res[tid] = s_pos[tid] + 1u; s_pfx[tid] = 0; }   // rank inside the overflow list
+        }
         for (int pass = 0; pass < 4; ++pass) {
             const int shift = pass == 0 ? 23 : pass == 1 ? 15 : pass == 2 ? 7 : 0;
             const uint32_t mask = pass == 3 ? 127u : 255u;
@@ -955,17 +1018,17 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
             __syncthreads();
             const int nsub = s_nsub;
             if (pass == 0) {
-                batched_loop<8, FN_THREADS>(0u, n, (uint32_t)tid, [&](uint32_t i) { return kb[i]; }, [&](uint32_t, uint32_t bits) {
+                batched_loop<8, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return xb[i]; }, [&](uint32_t, uint32_t bits) {
                     atomicAdd(&s_hist[0][(key_of_bits(bits) >> 23) & 255u], 1u);
                 });
             } else if (nsub == 1) {
                 const uint32_t pf = s_subpfx[0] >> hb;
-                batched_loop<8, FN_THREADS>(0u, n, (uint32_t)tid, [&](uint32_t i) { return kb[i]; }, [&](uint32_t, uint32_t bits) {
+                batched_loop<8, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return xb[i]; }, [&](uint32_t, uint32_t bits) {
                     const uint32_t key = key_of_bits(bits);
                     if ((key >> hb) == pf) atomicAdd(&s_hist[0][(key >> shift) & mask], 1u);
                 });
             } else {
-                batched_loop<8, FN_THREADS>(0u, n, (uint32_t)tid, [&](uint32_t i) { return kb[i]; }, [&](uint32_t, uint32_t bits) {
+                batched_loop<8, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return xb[i]; }, [&](uint32_t, uint32_t bits) {
                     const uint32_t key = key_of_bits(bits);
                     const uint32_t kp = key >> hb;
                     for (int s2 = 0; s2 < nsub; ++s2)
@@ -1017,7 +1080,7 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
                 for (int i = tid; i < TMAX * 256; i += FN_THREADS) (&s_hist[0][0])[i] = 0;
                 __syncthreads();
                 const int nsub = s_nsub;
-                batched_loop<8, FN_THREADS>(0u, n, (uint32_t)tid, [&](uint32_t i) { return make_uint2(kb[i], kj[i]); },
+                batched_loop<8, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return make_uint2(xb[i], xj[i]); },
                                             [&](uint32_t, uint2 e) {
                     const uint32_t key = key_of_bits(e.x), j = e.y;
                     for (int s2 = 0; s2 < nsub; ++s2) {
@@ -1042,7 +1105,7 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
         }
         // every candidate's part from the exact thresholds
         if (count_fits || SUMS) {
-            batched_loop<8, FN_THREADS>(0u, n, (uint32_t)tid, [&](uint32_t i) { return make_uint2(kb[i], kj[i]); },
+            batched_loop<8, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return make_uint2(xb[i], xj[i]); },
                                         [&](uint32_t, uint2 e) {
                 const uint32_t key = key_of_bits(e.x), j = e.y;
                 int part = 0;
