@@ -91,8 +91,8 @@ __global__ __launch_bounds__(HIST_THREADS) void k_hist(TopkArgs a, int exact_pas
 
 // ---------------------------------------------------------------------------------------------------
 // Level draw of one row (Alg. 2 / Alg. 3 "Sample l ~ p"), run by one thread.
-__device__ void draw_row(const TopkArgs& a, int row, const double* norms_row) {
-    double p[LMAX];
+// `p` is LMAX doubles of LDS scratch: a thread-local array indexed by a loop variable would live in scratch memory.
+__device__ void draw_row(const TopkArgs& a, int row, const double* norms_row, double* p) {
     const int L = a.L;
     if (a.draw_mode == 0) {
         for (int l = 0; l < L; ++l) p[l] = a.p_fixed[l];
@@ -129,7 +129,9 @@ __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
     __shared__ int32_t s_nz, s_lev;
     __shared__ uint32_t s_ztop[ZMAX], s_zbot[ZMAX];
     __shared__ int32_t s_label[RMAX];
-    __shared__ double s_est[LMAX + 2];
+    __shared__ float s_est[LMAX + 2];
+    __shared__ double s_p[LMAX];
+    __shared__ double s_kd[TMAX];
 
     const int row = blockIdx.x, tid = threadIdx.x;
     RowInfo* ri = a.rinfo + row;
@@ -154,7 +156,7 @@ __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
     if (tid == 0) {
         if (!exact_pass) {
             ri->respec = 0;
-            if (!a.all_thresholds) draw_row(a, row, nullptr);  // p is known up front: draw before anything else
+            if (!a.all_thresholds) draw_row(a, row, nullptr, s_p);  // p is known up front: draw before anything else
         }
         ri->exact = exact ? 1 : 0;
         s_lev = a.all_thresholds ? 0 : ri->level;
@@ -290,11 +292,12 @@ __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
     // that second read.
     const int nz = s_nz;
     if (a.all_thresholds && a.draw_mode == 3) {
-        for (int l = tid; l < LMAX + 2; l += 1024) s_est[l] = 0.0;
+        for (int l = tid; l < LMAX + 2; l += 1024) s_est[l] = 0.0f;
+        if (tid <= L) s_kd[tid] = (double)a.k[tid];   // per-lane indexed below: keep it out of the argument block
         __syncthreads();
         if (sum) {
             const double scale = (double)a.d / (double)(ns > 0 ? ns : 1);
-            int cur = -1;
+            int cur = -1, band = 0;
             double acc = 0.0;
             uint32_t run = before;
 #pragma unroll
@@ -302,11 +305,10 @@ __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
                 if (hv[i]) {
                     const uint32_t b = (uint32_t)(NB1 - 1 - (tid * 16 + i));
                     const double rank = ((double)run + 0.5 * (double)hv[i]) * scale;
-                    int band = 0;
-                    while (band <= L && rank >= (double)a.k[band]) ++band;   // first t with rank < k_t
+                    while (band <= L && rank >= s_kd[band]) ++band;   // first t with rank < k_t (ranks only grow)
                     const double v = (double)__uint_as_float((b << B1_SHIFT) | 0x10000u);
                     if (band != cur) {
-                        if (cur >= 0 && acc > 0.0) atomicAdd(&s_est[cur], acc);
+                        if (cur >= 0 && acc > 0.0) atomicAdd(&s_est[cur], (float)acc);
                         cur = band;
                         acc = 0.0;
                     }
@@ -314,13 +316,13 @@ __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
                 }
                 run += hv[i];
             }
-            if (cur >= 0 && acc > 0.0) atomicAdd(&s_est[cur], acc);
+            if (cur >= 0 && acc > 0.0) atomicAdd(&s_est[cur], (float)acc);   // fp32: a native LDS atomic, ample for a prediction
         }
         __syncthreads();
         if (tid == 0) {
-            double p[LMAX];
+            double* p = s_p;
             double tot = 0.0;
-            for (int l = 0; l < L; ++l) { p[l] = sqrt(s_est[l + 1]); tot += p[l]; }
+            for (int l = 0; l < L; ++l) { p[l] = sqrt((double)s_est[l + 1]); tot += p[l]; }
             for (int l = 0; l < L; ++l) p[l] = tot > 0.0 ? p[l] / tot : 1.0 / (double)L;
             s_lev = draw_from_p(p, L, philox_word0(a.seed, a.step, (uint32_t)row));
         }
@@ -1246,6 +1248,7 @@ __global__ __launch_bounds__(256) void k_norms(TopkArgs a) {
     __shared__ double s_norm[LMAX];
     __shared__ int32_t s_nlist[TMAX];
     __shared__ uint16_t s_list[TMAX][NL_CAP];
+    __shared__ double s_p[LMAX];
     const int row = blockIdx.x, tid = threadIdx.x;
     const RowInfo* ri = a.rinfo + row;
     const RowAcc* ra = a.racc + row;
@@ -1314,7 +1317,7 @@ __global__ __launch_bounds__(256) void k_norms(TopkArgs a) {
     }
     __syncthreads();
     if (tid == 0 && a.draw_mode == 3) {
-        draw_row(a, row, s_norm);
+        draw_row(a, row, s_norm, s_p);
         RowInfo* rw = a.rinfo + row;
         rw->spec_ok = (rw->spec_level > 0 && rw->spec_level == rw->level) ? 1 : 0;
     }
@@ -1323,14 +1326,15 @@ __global__ __launch_bounds__(256) void k_norms(TopkArgs a) {
 // ---------------------------------------------------------------------------------------------------
 // Level draw for all rows of the bit-wise path (one workgroup).
 __global__ __launch_bounds__(1024) void k_draw(DrawArgs a) {
+    __shared__ double s_p[LMAX];
     const int r = threadIdx.x;
+    if (r < a.L) s_p[r] = a.p_fixed[r];
+    __syncthreads();
     if (r < a.M) {
-        double p[LMAX];
         const int L = a.L;
-        for (int l = 0; l < L; ++l) p[l] = a.p_fixed[l];
         uint32_t x = philox_word0(a.seed, a.step, (uint32_t)r);
-        int level = draw_from_p(p, L, x);
-        double pl = p[level - 1];
+        int level = draw_from_p(s_p, L, x);
+        double pl = s_p[level - 1];
         RowInfo* ri = a.rinfo + r;
         ri->level = level;
         ri->weight = pl == 0.0 ? 0.0f : (float)__ddiv_rn(1.0, pl);
