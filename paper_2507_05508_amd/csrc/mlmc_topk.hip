@@ -1,23 +1,31 @@
 // Top-k MLMC on gfx950: exact multi-rank select on |g| keys, exact band sums of squares, level draw,
-// index-ordered band compaction.  The rows are read twice: once to select, once to write the message.
+// index-ordered band message.  A row is normally read once (plus a sample); a second read happens only when
+// the band that was set aside during the first read is not the band that is drawn.
 //
 // Pipeline per call (all rows at once):
 //   k_hist       14-bit first-digit histogram (exponent + 6 mantissa bits) of a SAMPLE of every row: one
 //                1024-element block out of 2^s (s = 0 for short rows: then the histogram is exact)
 //   k_scan       per row: from the (scaled) sample histogram, a ZONE of buckets around every needed rank
 //                threshold that holds it with overwhelming probability; the buckets between zones are REGIONS whose
-//                elements lie wholly inside one band.  Writes the bucket -> {region, sum group | zone} table.
-//   k_main       the one full selection read: per region exact element counts (per chunk and per row) and exact
-//                sums of squared significands per (exponent, region); elements of zones are appended, with
-//                their index, to per-zone candidate lists
-//   k_finish     per zone: the exact counts above it prove (or refute) that its thresholds lie inside; radix select
-//                on the candidate list -> exact threshold key, index cut among equal keys, exact sums of the
-//                parts the thresholds cut the zone into.  A refuted row is flagged and redone with an exact
-//                histogram (k_hist / k_scan / k_main / k_finish once more, for flagged rows only).
+//                elements lie wholly inside one band.  With known p the level is drawn here; with adaptive p it is
+//                predicted from the histogram.  Writes the class table: bucket -> {region, sum group, stage flag | zone}.
+//   k_main       the selection read: per region exact element counts (per chunk and per row) and exact sums of
+//                squared significands per (exponent, region); zone candidates and the members of the staged band
+//                go to per-wave private lists, the candidates from there to per-zone lists
+//   k_fhist      per (zone, slice): histogram of the candidates over the zone's own key range
+//   k_finish<0>  per (zone, slice): the exact counts above the zone prove (or refute) that its thresholds lie
+//                inside; candidates of the thresholds' bins are gathered, all others classified by their bin
+//                (per-chunk counts of the zone's parts, exact sums per part and exponent)
+//   k_finish<1>  per zone: gathered candidates ranked in LDS -> exact threshold key and index cut among equal keys
+//                (radix select on an overflow list when the bins hold many: massive ties).
+//                A refuted row is flagged and redone with an exact histogram (k_hist .. k_finish once more, for
+//                flagged rows only; these launches return at once otherwise).
 //   k_norms      big-integer accumulation of group and part sums -> correctly rounded fp64 S_l -> Delta_l
-//                (Lemma 3.4), then the adaptive level draw (Alg. 3); with known p the draw is done in k_scan
-//   k_write      second read: index-ordered compaction of base band + drawn band (Eq. (6)); a workgroup owns a
-//                chunk whose output offset follows from the per-chunk counts, so no look-back is needed
+//                (Lemma 3.4), then the adaptive level draw (Alg. 3)
+//   k_msgplan    per row: where its message starts, message entries before every chunk, the three thresholds
+//   k_filter     rows whose staged band is the drawn one: base band + drawn band (Eq. (6)) from the staged lists,
+//                ordered by index through a bitmap over the chunk
+//   k_write      the other rows: second read, a workgroup owns a chunk whose output offset is known
 #include <type_traits>
 
 #include "mlmc_device.h"
