@@ -45,6 +45,22 @@ def algorithmic_bytes(w, kernel, nnz_total, planes_bytes):
     return 0
 
 
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 summary of this workload (FETCH_SIZE +
+    WRITE_SIZE, scaled as the summary says), or None when no summary covers it."""
+    path = os.path.join(ROOT, "profiles", f"{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        f = line.split()
+        if f and f[0].split("<")[0] == kernel and len(f) >= 3:
+            try:
+                return int((float(f[-2]) + float(f[-1])) * 1e6)
+            except ValueError:
+                return None
+    return None
+
+
 def cpu_baseline(w, G, budget_s=25.0):
     """The oracle as it stands, single thread, on the first rows of the same workload until ~budget_s."""
     from oracle import mlmc as O
@@ -200,7 +216,8 @@ def main():
         "ms_per_step_with_events": round(dt_ev * 1e3 / args.steps, 4),
         "exact_redo_in_last_step": redone,
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "traffic": measured_traffic(w.name, dominant),
                      "avg_us": round(dom_avg_s * 1e6, 2), "algorithmic_bytes_per_launch": int(dom_bytes)},
         "kernels": {k: {"avg_us": round(v["avg_us"], 2), "launches": v["launches"], "share": round(v["share"], 4)}
                     for k, v in sorted(kern.items(), key=lambda kv: -kv[1]["share"])},

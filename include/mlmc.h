@@ -153,6 +153,8 @@ mlmc_status mlmc_compress_bits(const mlmc_plan_t *plan, const void *g, int64_t l
  * Server side (Alg. 2 / Alg. 3 "Server aggregates"): out[j] = fp32(alpha * acc_j), acc_j the fp32 sum over
  * workers in worker order (alpha = 1/M gives the paper's mean).
  *   MLMC_TOPK plan: row_off, idx, val as written by mlmc_compress_topk (level unused, may be NULL);
+ *     capacity = entries that idx / val hold (as passed to mlmc_compress_topk): entries at positions >= capacity
+ *     are never read, so a message that did not fit (MLMC_DEV_CAPACITY) cannot steer reads out of bounds;
  *     tile_off as written there, or NULL (then it is rebuilt by binary search into ws).  A worker without an
  *     entry at j is skipped.
  *   MLMC_BITS plan: level, scale_exp, planes as written by mlmc_compress_bits; the decoded value of
@@ -160,7 +162,7 @@ mlmc_status mlmc_compress_bits(const mlmc_plan_t *plan, const void *g, int64_t l
  *   out: dev [d] fp32, fully overwritten.
  */
 mlmc_status mlmc_aggregate(const mlmc_plan_t *plan, const int32_t *level, const int64_t *row_off,
-                           const uint32_t *idx, const float *val, const uint32_t *tile_off,
+                           const uint32_t *idx, const float *val, int64_t capacity, const uint32_t *tile_off,
                            const int32_t *scale_exp, const uint64_t *planes, float alpha, float *out,
                            void *ws, void *hip_stream);
 

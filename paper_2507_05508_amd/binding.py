@@ -66,7 +66,7 @@ def lib():
         L.mlmc_compress_bits.restype = C.c_int
         L.mlmc_compress_bits.argtypes = [vp, vp, i64, u64, u64, vp, vp, vp, vp, vp, vp]
         L.mlmc_aggregate.restype = C.c_int
-        L.mlmc_aggregate.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, C.c_float, vp, vp, vp]
+        L.mlmc_aggregate.argtypes = [vp, vp, vp, vp, vp, i64, vp, vp, vp, C.c_float, vp, vp, vp]
         L.mlmc_profile_enable.restype = None
         L.mlmc_profile_enable.argtypes = [i32]
         L.mlmc_profile_reset.restype = None
@@ -243,11 +243,11 @@ def mlmc_aggregate(plan: Plan, msg, alpha: float, out: Optional[torch.Tensor] = 
     if out is None:
         out = torch.empty(plan.d, dtype=torch.float32, device=plan.device)
     if plan.kind == MLMC_TOPK:
-        rc = lib().mlmc_aggregate(plan.handle, None, _ptr(msg.row_off), _ptr(msg.idx), _ptr(msg.val),
+        rc = lib().mlmc_aggregate(plan.handle, None, _ptr(msg.row_off), _ptr(msg.idx), _ptr(msg.val), msg.capacity,
                                   _ptr(msg.tile_off) if use_tile_off else None, None, None, float(alpha), _ptr(out),
                                   _ptr(plan.ws), _stream())
     else:
-        rc = lib().mlmc_aggregate(plan.handle, _ptr(msg.level), None, None, None, None, _ptr(msg.scale_exp),
+        rc = lib().mlmc_aggregate(plan.handle, _ptr(msg.level), None, None, None, 0, None, _ptr(msg.scale_exp),
                                   _ptr(msg.planes), float(alpha), _ptr(out), _ptr(plan.ws), _stream())
     _check(rc, "mlmc_aggregate")
     return out

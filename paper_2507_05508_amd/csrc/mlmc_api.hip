@@ -16,7 +16,7 @@ mlmc_status topk_compact(const mlmc_plan_t* pl, const TopkArgs& a, bool vec, hip
 mlmc_status bits_compress(const mlmc_plan_t* pl, const BitsArgs& a, bool vec, hipStream_t st);
 mlmc_status agg_bits(const mlmc_plan_t* pl, const BitsArgs& b, const int32_t* level, const int32_t* scale_exp,
                      const uint64_t* planes, float alpha, float* out, hipStream_t st);
-mlmc_status agg_sparse(const mlmc_plan_t* pl, const int64_t* row_off, const uint32_t* idx, const float* val,
+mlmc_status agg_sparse(const mlmc_plan_t* pl, const int64_t* row_off, const uint32_t* idx, const float* val, int64_t capacity,
                        const uint32_t* tile_off, uint32_t* tile_off_ws, float alpha, float* out, hipStream_t st);
 
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -383,15 +383,15 @@ mlmc_status mlmc_compress_bits(const mlmc_plan_t* plan, const void* g, int64_t l
 }
 
 mlmc_status mlmc_aggregate(const mlmc_plan_t* plan, const int32_t* level, const int64_t* row_off, const uint32_t* idx,
-                           const float* val, const uint32_t* tile_off, const int32_t* scale_exp, const uint64_t* planes,
+                           const float* val, int64_t capacity, const uint32_t* tile_off, const int32_t* scale_exp, const uint64_t* planes,
                            float alpha, float* out, void* ws, void* hip_stream) {
     if (!plan || !out) return MLMC_EINVAL;
     hipStream_t st = (hipStream_t)hip_stream;
     if (plan->kind == MLMC_TOPK) {
-        if (!row_off || !idx || !val || scale_exp || planes) return MLMC_EINVAL;
+        if (!row_off || !idx || !val || capacity < 0 || scale_exp || planes) return MLMC_EINVAL;
         if (!tile_off && (!ws || (uintptr_t)ws % 256)) return MLMC_EINVAL;
         uint32_t* tws = ws ? (uint32_t*)((char*)ws + plan->off_tileoff) : nullptr;
-        return agg_sparse(plan, row_off, idx, val, tile_off, tws, alpha, out, st);
+        return agg_sparse(plan, row_off, idx, val, capacity, tile_off, tws, alpha, out, st);
     }
     if (!level || !scale_exp || !planes || row_off || idx || val || tile_off) return MLMC_EINVAL;
     BitsArgs b;

@@ -177,6 +177,7 @@ struct AggSparseArgs {
     const int64_t* row_off;
     const uint32_t* idx;
     const float* val;
+    int64_t capacity;          // entries idx / val hold
     const uint32_t* tile_off;  // [M][ntiles + 1]
     uint32_t* tile_off_out;    // k_tileoff target
     float alpha;
@@ -188,7 +189,10 @@ __global__ __launch_bounds__(256) void k_tileoff(AggSparseArgs a) {
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
         const int r = (int)(i / (a.ntiles + 1));
         const int64_t t = i % (a.ntiles + 1);
-        const int64_t s = a.row_off[r], e = a.row_off[r + 1];
+        int64_t s = a.row_off[r], e = a.row_off[r + 1];   // entries past the capacity were never written
+        if (s > a.capacity) s = a.capacity;
+        if (e > a.capacity) e = a.capacity;
+        if (e < s) e = s;
         const uint64_t target = (uint64_t)t * TILE;
         int64_t lo = s, hi = e;  // first position with idx >= target
         while (lo < hi) {
@@ -214,7 +218,8 @@ __global__ __launch_bounds__(256) void k_agg_sparse(AggSparseArgs a) {
         // says otherwise (a failed compress call, a caller's own table) must not steer reads out of bounds
         const int64_t beg = a.row_off[r] + to[tile];
         uint32_t len = to[tile + 1] - to[tile];
-        if (to[tile + 1] < to[tile] || len > (uint32_t)TILE || beg < a.row_off[r] || beg + len > a.row_off[r + 1]) len = 0;
+        if (to[tile + 1] < to[tile] || len > (uint32_t)TILE || beg < a.row_off[r] || beg + len > a.row_off[r + 1] ||
+            beg + len > a.capacity) len = 0;
         s_beg[r] = beg;
         s_len[r] = len;
     }
@@ -299,7 +304,7 @@ mlmc_status agg_bits(const mlmc_plan_t* pl, const BitsArgs& b, const int32_t* le
     return MLMC_OK;
 }
 
-mlmc_status agg_sparse(const mlmc_plan_t* pl, const int64_t* row_off, const uint32_t* idx, const float* val,
+mlmc_status agg_sparse(const mlmc_plan_t* pl, const int64_t* row_off, const uint32_t* idx, const float* val, int64_t capacity,
                        const uint32_t* tile_off, uint32_t* tile_off_ws, float alpha, float* out, hipStream_t st) {
     AggSparseArgs a;
     a.M = pl->M;
@@ -308,6 +313,7 @@ mlmc_status agg_sparse(const mlmc_plan_t* pl, const int64_t* row_off, const uint
     a.row_off = row_off;
     a.idx = idx;
     a.val = val;
+    a.capacity = capacity;
     a.tile_off = tile_off;
     a.tile_off_out = tile_off_ws;
     a.alpha = alpha;

@@ -253,6 +253,10 @@ def test_capacity_and_nonfinite_flags():
     assert plan.status() & P.MLMC_DEV_CAPACITY
     want = O.compress_topk(G, w.ladder, plan.p_fixed, 0, 0)
     assert np.array_equal(u32(small.idx)[:10], want[0]["idx"][:10])   # what fits is still correct
+    for use_tile in (True, False):   # the aggregate must not follow the offsets past what the buffers hold
+        out = P.mlmc_aggregate(plan, small, 1.0, use_tile_off=use_tile)
+        torch.cuda.synchronize()
+        assert bool(torch.isfinite(out).all())
     G2 = G.copy()
     G2[1, 17] = np.inf
     G2[0, 5] = np.nan
