@@ -126,6 +126,7 @@ __device__ void draw_row(const TopkArgs& a, int row, const double* norms_row, do
 // Per row: zones and regions from the histogram, candidate list layout, the class table.
 // How far (in standard deviations of the sampled count) a zone reaches on either side of the estimated rank.
 constexpr double ZONE_SIGMAS = 8.0;
+constexpr int64_t STAGE_MAX_BAND_INV = 16;   // bands wider than d / 16 are not staged
 
 __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
     __shared__ uint32_t s_h[NB1];
@@ -338,6 +339,9 @@ __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
     }
     if (tid == 0) {
         int sl = ((a.all_thresholds && a.draw_mode != 3) || !a.staging) ? 0 : s_lev;   // norms only: nothing to stage
+        // a wide band is cheaper to collect by a second read: the staged lists of such a row would keep its few
+        // workgroups busy long after the other rows are done
+        if (sl > 0 && (a.k[sl] - a.k[sl - 1]) * STAGE_MAX_BAND_INV > a.d) sl = 0;
         ri->spec_level = sl;
         ri->spec_ok = (sl > 0 && !(a.all_thresholds && a.draw_mode == 3)) ? 1 : 0;   // adaptive: decided after the draw
         s_lev = sl;
