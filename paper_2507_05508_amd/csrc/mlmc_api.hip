@@ -80,6 +80,9 @@ static void fill_topk_args(const mlmc_plan_t* pl, TopkArgs& a, const void* g, in
     for (int t = 0; t <= pl->L; ++t) a.k[t] = pl->ladder[t];
     a.chunk = pl->chunk;
     a.chunks_per_row = pl->chunks_per_row;
+    a.cchunk = pl->cchunk;
+    a.csub = pl->csub;
+    a.cchunks_per_row = pl->cchunks_per_row;
     a.sample_shift = pl->sample_shift;
     a.staging = pl->staging;
     a.ntiles = pl->ntiles;
@@ -214,11 +217,16 @@ mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dty
     // elements per workgroup (the LDS accumulators and the packed candidate offsets rely on that bound)
     int64_t target_per_row = 2048 / M > 0 ? 2048 / M : 1;
     int64_t chunk = (d + target_per_row - 1) / target_per_row;
-    chunk = (chunk + TILE - 1) / TILE * TILE;
+    chunk = (chunk + 4 * TILE - 1) / (4 * TILE) * (4 * TILE);
     if (chunk < 4 * TILE) chunk = 4 * TILE;
     if (chunk > CHUNK_MAX) chunk = CHUNK_MAX;
     pl->chunk = (int)chunk;
     pl->chunks_per_row = (int)((d + chunk - 1) / chunk);   // <= 2^31 / 2^18 = CHUNKS_MAX
+    // message offsets are kept per count chunk, a quarter of a chunk (unless that would be too many per row):
+    // the second read of a row, when one is needed, then has four times as many workgroups
+    pl->csub = (pl->chunks_per_row * CSUB_MAX <= CHUNKS_MAX && chunk >= 16 * TILE) ? CSUB_MAX : 1;
+    pl->cchunk = (int)(chunk / pl->csub);
+    pl->cchunks_per_row = (int)((d + pl->cchunk - 1) / pl->cchunk);
     // rows long enough that a second full read matters get their thresholds from a sampled histogram
     pl->sample_shift = d >= ((int64_t)1 << 23) ? 4 : d >= ((int64_t)1 << 21) ? 2 : 0;
     pl->staging = 1;
@@ -232,7 +240,7 @@ mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dty
         pl->off_hist2 = off;
         off = align_up(off + sizeof(uint32_t) * NB1 * (size_t)M, 256);
         pl->off_chunk_zcnt = off;
-        off = align_up(off + sizeof(uint32_t) * ZPMAX * (size_t)pl->chunks_per_row * M, 256);
+        off = align_up(off + sizeof(uint32_t) * ZPMAX * (size_t)pl->cchunks_per_row * M, 256);
         pl->off_zhist = off;
         off = align_up(off + sizeof(uint32_t) * FH_BINS * ZMAX * (size_t)M, 256);
         pl->off_zpacc = off;
@@ -245,7 +253,7 @@ mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dty
         pl->off_table = off;
         off = align_up(off + sizeof(uint32_t) * NB1 * (size_t)M, 256);
         pl->off_chunk_cnt = off;
-        off = align_up(off + sizeof(uint32_t) * RMAX * (size_t)pl->chunks_per_row * M, 256);
+        off = align_up(off + sizeof(uint32_t) * RMAX * (size_t)pl->cchunks_per_row * M, 256);
         pl->off_zcol = off;
         off = align_up(off + sizeof(unsigned long long) * COLLECT_CAP * ZMAX * (size_t)M, 256);
         pl->off_tileoff = off;
@@ -265,7 +273,7 @@ mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dty
         pl->off_priv_cnt = off;
         off = align_up(off + sizeof(uint32_t) * 16 * (size_t)pl->chunks_per_row * M, 256);
         pl->off_chunk_base = off;
-        off = align_up(off + sizeof(uint32_t) * (size_t)(pl->chunks_per_row + 1) * M, 256);
+        off = align_up(off + sizeof(uint32_t) * (size_t)(pl->cchunks_per_row + 1) * M, 256);
     }
     pl->ws_bytes = off;
     if (workspace_bytes) *workspace_bytes = off;

@@ -45,6 +45,7 @@ __host__ __device__ constexpr uint32_t class_code(uint32_t group, uint32_t count
 constexpr int G_DUMMY = GMAX - 1;
 constexpr int REP_SUM = 16;             // replicas of the 64-bit group sum accumulators: slot = id * 16 + (lane & 15)
 constexpr int REP_CNT = 16;             // replicas of the 32-bit region / zone counters
+constexpr int CSUB_MAX = 4;             // count chunks per chunk of the selection read
 
 constexpr int THR_NONE = -1;      // k_t == 0: nothing is within the top k_t
 constexpr int THR_ALL = -2;       // k_t >= d: everything is
@@ -104,6 +105,9 @@ struct TopkArgs {
     int32_t all_thresholds;  // 1: every ladder threshold + band sums (adaptive); 0: thresholds 0, l-1, l only
     int32_t chunk;           // elements per workgroup chunk (multiple of TILE, <= CHUNK_MAX)
     int32_t chunks_per_row;
+    int32_t cchunk;          // elements per count chunk: chunk / csub (multiple of TILE); message offsets are kept per count chunk
+    int32_t csub;            // count chunks per chunk (1 or 4)
+    int32_t cchunks_per_row;
     int32_t sample_shift;    // the first histogram reads one 1024-element block out of 2^sample_shift
     int32_t staging;         // 1: the selection read stages the members of the (predicted) drawn band
     int64_t ntiles;
@@ -118,9 +122,9 @@ struct TopkArgs {
     uint32_t* cand2_idx;     // [M][d]
     uint2* cand_priv;        // [M][chunks_per_row][chunk] staged {bits, offset in chunk << 6 | tag} as the waves met them
     uint32_t* priv_cnt;      // [M][chunks_per_row][16] entries of every wave's private list
-    uint32_t* chunk_base;    // [M][chunks_per_row + 1] message entries of the row before every chunk
-    uint32_t* chunk_cnt;     // [M][chunks_per_row][RMAX] elements of every region per chunk
-    uint32_t* chunk_zcnt;    // [M][chunks_per_row][ZPMAX] candidates of every part of every zone per chunk (zeroed per call)
+    uint32_t* chunk_base;    // [M][cchunks_per_row + 1] message entries of the row before every count chunk
+    uint32_t* chunk_cnt;     // [M][cchunks_per_row][RMAX] elements of every region per count chunk
+    uint32_t* chunk_zcnt;    // [M][cchunks_per_row][ZPMAX] candidates of every part of every zone per count chunk (zeroed per call)
     uint32_t* zhist;         // [M][ZMAX][FH_BINS] zone-relative key histograms (zeroed per call)
     unsigned long long* zpacc; // [M][ZMAX][PIECE_CLASSES][2] sums of squared significands per (part, exponent) (zeroed per call)
     unsigned long long* zcol;  // [M][ZMAX][COLLECT_CAP] candidates of the thresholds' bins
@@ -196,6 +200,7 @@ struct mlmc_plan_s {
     int nplanes;
     int chunk;
     int chunks_per_row;
+    int cchunk, csub, cchunks_per_row;
     int sample_shift;
     int staging;
     // workspace byte offsets

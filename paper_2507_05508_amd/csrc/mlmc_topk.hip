@@ -156,8 +156,8 @@ __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
         for (int i = tid; i < ZMAX * FH_BINS; i += 1024) z[i] = 0;
         z = (uint32_t*)(a.zpacc + (size_t)row * ZMAX * PIECE_CLASSES * 2);
         for (int i = tid; i < ZMAX * PIECE_CLASSES * 4; i += 1024) z[i] = 0;
-        z = a.chunk_zcnt + (size_t)row * a.chunks_per_row * ZPMAX;
-        for (int i = tid; i < a.chunks_per_row * ZPMAX; i += 1024) z[i] = 0;
+        z = a.chunk_zcnt + (size_t)row * a.cchunks_per_row * ZPMAX;
+        for (int i = tid; i < a.cchunks_per_row * ZPMAX; i += 1024) z[i] = 0;
     }
     const bool exact = exact_pass || a.sample_shift == 0;
     const uint32_t* gh = (exact_pass ? a.hist2 : a.hist) + (size_t)row * NB1;
@@ -379,22 +379,23 @@ __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
 // The selection read: region counts, group sums (SUMS), zone candidates.
 constexpr int MAIN_THREADS = 1024;
 constexpr int MAIN_WAVES = MAIN_THREADS / 64;
-constexpr int RING = 256;    // staged entries per wave (ring); at most 63 + 64 are pending at any time
+constexpr int RING = 128;    // staged entries per wave (ring); at most 63 + 64 are pending at any time
 
-// LDS layout (bytes).  The table sits at offset 0 so that the look-up needs no base; the sums at 64 KB and the
-// counters at a multiple of 8 KB so that their bases can be OR-ed with the fields of the class code.
+// LDS layout (bytes), all of the 160 KB.  The table sits at offset 0 so that the look-up needs no base; the sums
+// at 64 KB and the counters at a multiple of 32 KB so that their bases can be OR-ed with the fields of the class
+// code.  The counters exist once per count chunk of the workgroup's chunk.
 constexpr int LM_TAB = 0;                                   // uint32 [NB1]
 constexpr int LM_SUM = NB1 * 4;                             // uint64 [GMAX][REP_SUM]
-constexpr int LM_CNT = 13 * 8192;                           // uint32 [128][REP_CNT]: regions 0..63, zones 64..127
-constexpr int LM_ZCUR = LM_CNT + 128 * REP_CNT * 4;         // uint32 [64] write cursor of every zone list
+constexpr int LM_ZCUR = LM_SUM + GMAX * REP_SUM * 8;        // uint32 [64] write cursor of every zone list
 constexpr int LM_ZMAX = LM_ZCUR + 64 * 4;                   // uint32 [64] largest candidate key of every zone
 constexpr int LM_ZMIN = LM_ZMAX + 64 * 4;                   // uint32 [64] largest ~key
 constexpr int LM_ZOFF = LM_ZMIN + 64 * 4;                   // uint32 [64]
 constexpr int LM_ZCAP = LM_ZOFF + 64 * 4;
 constexpr int LM_STAGE = LM_ZCAP + 64 * 4;                  // uint2 [MAIN_WAVES][RING]: {bits, rel << 6 | tag}
-constexpr int LM_END = LM_STAGE + MAIN_WAVES * RING * 8;
-static_assert(LM_SUM == 65536 && LM_SUM + GMAX * REP_SUM * 8 <= LM_CNT && LM_CNT % 8192 == 0, "LDS layout");
-static_assert(REP_SUM * 8 == 128 && REP_CNT * 4 == 64, "field scaling of the class code");
+constexpr int LM_CNT = 4 * 32768;                           // uint32 [CSUB_MAX][128][REP_CNT]: regions 0..63, zones 64..127
+constexpr int LM_END = LM_CNT + CSUB_MAX * 128 * REP_CNT * 4;
+static_assert(LM_SUM == 65536 && LM_STAGE + MAIN_WAVES * RING * 8 <= LM_CNT && LM_CNT % 32768 == 0, "LDS layout");
+static_assert(REP_SUM * 8 == 128 && REP_CNT * 4 == 64 && CSUB_MAX * 128 * REP_CNT * 4 == 32768, "field scaling of the class code");
 template <bool SUMS> constexpr int lm_total() { return LM_END; }
 static_assert(lm_total<true>() <= 160 * 1024, "LDS budget");
 static_assert(ZMAX <= 64 && RMAX <= 64 && GMAX <= 512, "field widths of the class code");
@@ -422,7 +423,9 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
         for (int i = tid; i < NB1 * 4 / 16; i += MAIN_THREADS) dst[i] = src[i];
         uint4* z = (uint4*)(lm + LM_CNT);
         const uint4 zero = make_uint4(0, 0, 0, 0);
-        for (int i = tid; i < (LM_ZOFF - LM_CNT) / 16; i += MAIN_THREADS) z[i] = zero;
+        for (int i = tid; i < (LM_END - LM_CNT) / 16; i += MAIN_THREADS) z[i] = zero;
+        z = (uint4*)(lm + LM_ZCUR);
+        for (int i = tid; i < (LM_ZOFF - LM_ZCUR) / 16; i += MAIN_THREADS) z[i] = zero;
         if (SUMS) {
             z = (uint4*)(lm + LM_SUM);
             for (int i = tid; i < GMAX * REP_SUM * 8 / 16; i += MAIN_THREADS) z[i] = zero;
@@ -459,7 +462,7 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
     // four consecutive elements of every lane (bit c of vmask: element c is inside the chunk): table look-ups
     // first, then the accumulators (zone buckets carry a dummy group, elements past the end a dummy class, so
     // there is no branch), then the candidates
-    auto process = [&](const uint32_t (&b)[4], uint32_t rel0, uint32_t vmask) {
+    auto process = [&](const uint32_t (&b)[4], uint32_t rel0, uint32_t vmask, uint32_t cnt_base) {
         uint32_t code[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) code[c] = *(const uint32_t*)(lm + ((b[c] >> 15) & 0xFFFCu));
@@ -474,7 +477,7 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
                 atomicAdd((unsigned long long*)(lm + ((code[c] >> 16) | sum_lane)),
                           (unsigned long long)sig * (unsigned long long)sig);
             }
-            atomicAdd((uint32_t*)(lm + ((code[c] & 0x1FC0u) | cnt_lane)), 1u);
+            atomicAdd((uint32_t*)(lm + ((code[c] & 0x1FC0u) | cnt_base)), 1u);
             maxkey = key > maxkey ? key : maxkey;
             anys |= code[c];
         }
@@ -500,6 +503,12 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
     const int64_t nfull = span >= woff + 256 ? (span - woff - 256) / 4096 + 1 : 0;   // loads with all 256 elements
     auto issue = [&](int64_t n, uint32_t (&b)[4]) { ld.load4_full(c0 + (n * 16 + wave) * 256 + (int64_t)lane * 4, b); };
     auto rel_of = [&](int64_t n) -> uint32_t { return (uint32_t)((n * 16 + wave) * 256) + lane * 4; };
+    // load round n covers tile n of the chunk: its counters are those of the count chunk the tile lies in
+    const int64_t tpc = a.cchunk / TILE;   // tiles per count chunk
+    auto cnt_of = [&](int64_t n) -> uint32_t {
+        const uint32_t sub = (n >= tpc ? 1u : 0u) + (n >= 2 * tpc ? 1u : 0u) + (n >= 3 * tpc ? 1u : 0u);
+        return cnt_lane + (a.csub > 1 ? sub : 0u) * (uint32_t)(128 * REP_CNT * 4);
+    };
     uint32_t buf[8][4];
     int64_t n = 0;
     if (nfull >= 8) {
@@ -508,24 +517,24 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
         for (; n + 16 <= nfull; n += 8) {
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
-                process(buf[q], rel_of(n + q), 15u);
+                process(buf[q], rel_of(n + q), 15u, cnt_of(n + q));
                 issue(n + q + 8, buf[q]);
             }
         }
 #pragma unroll
-        for (int q = 0; q < 8; ++q) process(buf[q], rel_of(n + q), 15u);
+        for (int q = 0; q < 8; ++q) process(buf[q], rel_of(n + q), 15u, cnt_of(n + q));
         n += 8;
     }
     for (; n < nfull; ++n) {
         issue(n, buf[0]);
-        process(buf[0], rel_of(n), 15u);
+        process(buf[0], rel_of(n), 15u, cnt_of(n));
     }
     if (c0 + (nfull * 16 + wave) * 256 < c1) {   // the ragged end of the chunk: at most one partial load per wave
         const int64_t j = c0 + (nfull * 16 + wave) * 256 + (int64_t)lane * 4;
         const int nv = j < c1 ? ld.load4(j, buf[0]) : 0;
 #pragma unroll
         for (int c = 0; c < 4; ++c) if (c >= nv) buf[0][c] = 0u;
-        process(buf[0], rel_of(nfull), (1u << nv) - 1u);
+        process(buf[0], rel_of(nfull), (1u << nv) - 1u, cnt_of(nfull));
     }
     drain(true);
     if (__ballot(maxkey >= 0x7F800000u) && lane == 0) atomicOr(a.dev_status, MLMC_DEV_NONFINITE);
@@ -535,7 +544,8 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
     // ---- the workgroup's candidates move from the private lists to the zones' lists: one reservation per zone ----
     if (tid < nz) {
         uint32_t total = 0;
-        for (int r = 0; r < REP_CNT; ++r) total += s_cnt[(64 + tid) * REP_CNT + ((r + tid) & (REP_CNT - 1))];
+        for (int r = 0; r < CSUB_MAX * REP_CNT; ++r)
+            total += s_cnt[(r / REP_CNT) * (128 * REP_CNT) + (64 + tid) * REP_CNT + ((r + tid) & (REP_CNT - 1))];
         s_zcur[tid] = total ? atomicAdd(&ra->zone_fill[tid], total) : 0u;
     }
     __syncthreads();
@@ -581,11 +591,13 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
             if (hi) atomicAdd((unsigned long long*)&ra->gsum[g][1], hi);
         }
     }
-    if (tid < RMAX) {
+    if (tid < RMAX * CSUB_MAX) {   // per count chunk: the counters of region tid % RMAX
+        const int r = tid % RMAX, sub = tid / RMAX;
         uint32_t cnt = 0;
-        for (int r = 0; r < REP_CNT; ++r) cnt += s_cnt[tid * REP_CNT + ((r + tid) & (REP_CNT - 1))];
-        a.chunk_cnt[((size_t)row * a.chunks_per_row + blockIdx.x) * RMAX + tid] = cnt;
-        if (cnt) atomicAdd(&ra->region_cnt[tid], cnt);
+        for (int k = 0; k < REP_CNT; ++k) cnt += s_cnt[sub * (128 * REP_CNT) + r * REP_CNT + ((k + tid) & (REP_CNT - 1))];
+        const int64_t cc = (int64_t)blockIdx.x * a.csub + sub;
+        if (sub < a.csub && cc < a.cchunks_per_row) a.chunk_cnt[((size_t)row * a.cchunks_per_row + cc) * RMAX + r] = cnt;
+        if (cnt) atomicAdd(&ra->region_cnt[r], cnt);
     }
 }
 
@@ -780,9 +792,9 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
     if (!s_ok) return;
     const int nthr = s_n;
     const int nparts = nthr + 1;
-    const int nchunks = a.chunks_per_row;
+    const int nchunks = a.cchunks_per_row;   // count chunks
     const bool count_fits = nparts * nchunks <= ZC;
-    const uint32_t cmagic = (uint32_t)(0x100000000ull / (uint32_t)(a.chunk >> 12)) + 1u;   // chunk = multiple of 4096, >= 4 * 4096
+    const uint32_t cmagic = (uint32_t)(0x100000000ull / (uint32_t)(a.cchunk >> 12)) + 1u;   // count chunk = multiple of 4096, >= 4 * 4096
     auto chunk_of = [&](uint32_t j) -> uint32_t { return __umulhi(j >> 12, cmagic); };
 
     // range of the keys in the list (kept by the selection read), exponents for the part sums
@@ -1385,7 +1397,7 @@ __global__ __launch_bounds__(MP_THREADS) void k_msgplan(TopkArgs a) {
     RowInfo* ri = a.rinfo + row;
     const int lev = ri->level;
     const int nzn = ri->n_zones;
-    const int nc = a.chunks_per_row;
+    const int nc = a.cchunks_per_row;   // count chunks
     int r0 = -1, rl = -1;
     for (int r = 0; r <= nzn; ++r) {
         const int lab = ri->region_label[r];
@@ -1463,7 +1475,7 @@ __global__ __launch_bounds__(WR_THREADS, 4) void k_write(TopkArgs a) {
     const uint32_t lane = lane_id(), wave = tid >> 6;
     const RowInfo* ri = a.rinfo + row;
     if (ri->spec_ok) return;   // the message of this row comes from the staged lists (k_filter)
-    const int nc = a.chunks_per_row;
+    const int nc = a.cchunks_per_row;   // one workgroup per count chunk
     const int64_t nt = a.ntiles;
     const MsgPlan mp = ri->msg;
     const int64_t rowstart = mp.rowstart;
@@ -1472,8 +1484,8 @@ __global__ __launch_bounds__(WR_THREADS, 4) void k_write(TopkArgs a) {
     for (int i = 0; i < 3; ++i) { th.tau[i] = mp.tau[i]; th.jx[i] = mp.jx[i]; }
     const float w = mp.weight;
     RowLoader<DT, VEC> ld(a.g, a.ld, a.d, row);
-    const int64_t c0 = (int64_t)chunk_id * a.chunk;
-    const int64_t c1 = c0 + a.chunk < a.d ? c0 + a.chunk : a.d;
+    const int64_t c0 = (int64_t)chunk_id * a.cchunk;
+    const int64_t c1 = c0 + a.cchunk < a.d ? c0 + a.cchunk : a.d;
     const uint32_t base = a.chunk_base[(size_t)row * (nc + 1) + chunk_id];
     const uint32_t next_base = a.chunk_base[(size_t)row * (nc + 1) + chunk_id + 1];
     uint32_t run = base;   // entries of this row before the current step
@@ -1639,8 +1651,10 @@ __global__ __launch_bounds__(FL_THREADS) void k_filter(TopkArgs a) {
 #pragma unroll
     for (int i = 0; i < 3; ++i) { th.tau[i] = mp.tau[i]; th.jx[i] = mp.jx[i]; }
     const float w = mp.weight;
-    const uint32_t base = a.chunk_base[(size_t)row * (nc + 1) + chunk_id];
-    const uint32_t next_base = a.chunk_base[(size_t)row * (nc + 1) + chunk_id + 1];
+    const int ncc = a.cchunks_per_row;
+    const int cc0 = chunk_id * a.csub, cc1 = cc0 + a.csub < ncc ? cc0 + a.csub : ncc;   // the chunk's count chunks
+    const uint32_t base = a.chunk_base[(size_t)row * (ncc + 1) + cc0];
+    const uint32_t next_base = a.chunk_base[(size_t)row * (ncc + 1) + cc1];
     __syncthreads();
     auto member = [&](uint32_t key, uint32_t j, bool& in0) -> bool {
         in0 = inside_top(th, 0, key, j);
@@ -1724,11 +1738,11 @@ static mlmc_status launch_select(const mlmc_plan_t* pl, const TopkArgs& a, bool 
 
 template <int DT, bool VEC>
 static mlmc_status launch_compact(const mlmc_plan_t* pl, const TopkArgs& a, hipStream_t st) {
-    const dim3 grid(pl->chunks_per_row, pl->M);
+    const dim3 grid(pl->chunks_per_row, pl->M), wgrid(pl->cchunks_per_row, pl->M);
     // rows whose drawn band was staged get their message from the staged lists, the others from a second read
     MLMC_LAUNCH(K_MSGPLAN, st, k_msgplan<<<pl->M, MP_THREADS, 0, st>>>(a));
     MLMC_LAUNCH(K_FILTER, st, k_filter<<<grid, FL_THREADS, (size_t)pl->chunk / 32 * 8, st>>>(a));
-    MLMC_LAUNCH(K_WRITE, st, k_write<DT, VEC><<<grid, WR_THREADS, 0, st>>>(a));
+    MLMC_LAUNCH(K_WRITE, st, k_write<DT, VEC><<<wgrid, WR_THREADS, 0, st>>>(a));
     return MLMC_OK;
 }
 
