@@ -36,7 +36,6 @@ constexpr int ZPMAX = 2 * TMAX;
 // bit 13 "stage this element" (zone candidate, or member of a band the message is expected to hold);
 // bits 23..31 the sum group (after >> 16: multiplied by the 128 bytes of a group's replicas).  Zone buckets
 // carry the group G_DUMMY, so the selection read needs no branch around its accumulators.
-constexpr uint32_t CODE_ZONE = 0x1000;
 constexpr uint32_t CODE_STAGE = 0x2000;
 constexpr uint32_t TAG_MEMBER = 63;
 __host__ __device__ constexpr uint32_t class_code(uint32_t group, uint32_t counter, uint32_t tag, bool stage) {
