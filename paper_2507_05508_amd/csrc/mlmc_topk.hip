@@ -462,10 +462,11 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
     // four consecutive elements of every lane (bit c of vmask: element c is inside the chunk): table look-ups
     // first, then the accumulators (zone buckets carry a dummy group, elements past the end a dummy class, so
     // there is no branch), then the candidates
-    auto process = [&](const uint32_t (&b)[4], uint32_t rel0, uint32_t vmask, uint32_t cnt_base) {
-        uint32_t code[4];
+    auto lookup = [&](const uint32_t (&b)[4], uint32_t (&code)[4]) {
 #pragma unroll
         for (int c = 0; c < 4; ++c) code[c] = *(const uint32_t*)(lm + ((b[c] >> 15) & 0xFFFCu));
+    };
+    auto process = [&](const uint32_t (&b)[4], uint32_t (&code)[4], uint32_t rel0, uint32_t vmask, uint32_t cnt_base) {
         uint32_t anys = 0;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
@@ -509,32 +510,46 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
         const uint32_t sub = (n >= tpc ? 1u : 0u) + (n >= 2 * tpc ? 1u : 0u) + (n >= 3 * tpc ? 1u : 0u);
         return cnt_lane + (a.csub > 1 ? sub : 0u) * (uint32_t)(128 * REP_CNT * 4);
     };
+    // The table look-ups of the next load are issued before the accumulators of the current one are updated, so
+    // that their latency is covered.
     uint32_t buf[8][4];
+    uint32_t cc[4], cn[4];
     int64_t n = 0;
     if (nfull >= 8) {
 #pragma unroll
         for (int q = 0; q < 8; ++q) issue(q, buf[q]);
+        lookup(buf[0], cn);
         for (; n + 16 <= nfull; n += 8) {
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
-                process(buf[q], rel_of(n + q), 15u, cnt_of(n + q));
+#pragma unroll
+                for (int c = 0; c < 4; ++c) cc[c] = cn[c];
+                lookup(buf[(q + 1) & 7], cn);   // q = 7: load n + 8, issued at q = 0 of this iteration
+                process(buf[q], cc, rel_of(n + q), 15u, cnt_of(n + q));
                 issue(n + q + 8, buf[q]);
             }
         }
 #pragma unroll
-        for (int q = 0; q < 8; ++q) process(buf[q], rel_of(n + q), 15u, cnt_of(n + q));
+        for (int q = 0; q < 8; ++q) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) cc[c] = cn[c];
+            if (q < 7) lookup(buf[q + 1], cn);
+            process(buf[q], cc, rel_of(n + q), 15u, cnt_of(n + q));
+        }
         n += 8;
     }
     for (; n < nfull; ++n) {
         issue(n, buf[0]);
-        process(buf[0], rel_of(n), 15u, cnt_of(n));
+        lookup(buf[0], cc);
+        process(buf[0], cc, rel_of(n), 15u, cnt_of(n));
     }
     if (c0 + (nfull * 16 + wave) * 256 < c1) {   // the ragged end of the chunk: at most one partial load per wave
         const int64_t j = c0 + (nfull * 16 + wave) * 256 + (int64_t)lane * 4;
         const int nv = j < c1 ? ld.load4(j, buf[0]) : 0;
 #pragma unroll
         for (int c = 0; c < 4; ++c) if (c >= nv) buf[0][c] = 0u;
-        process(buf[0], rel_of(nfull), (1u << nv) - 1u, cnt_of(nfull));
+        lookup(buf[0], cc);
+        process(buf[0], cc, rel_of(nfull), (1u << nv) - 1u, cnt_of(nfull));
     }
     drain(true);
     if (__ballot(maxkey >= 0x7F800000u) && lane == 0) atomicOr(a.dev_status, MLMC_DEV_NONFINITE);
