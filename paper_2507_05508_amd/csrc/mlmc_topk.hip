@@ -1042,106 +1042,167 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
             }
             if (tid < nthr) { s_res[tid] = s_pos[tid] + 1u; s_pfx[tid] = 0; }   // rank inside the overflow list
         }
-        for (int pass = 0; pass < 4; ++pass) {
-            const int shift = pass == 0 ? 23 : pass == 1 ? 15 : pass == 2 ? 7 : 0;
-            const uint32_t mask = pass == 3 ? 127u : 255u;
-            const int hb = pass == 3 ? 7 : shift + 8;   // unresolved low bits before this pass (31 for pass 0)
-            __syncthreads();
-            if (tid == 0) {
-                int ns = 0;
-                for (int u = 0; u < nthr; ++u) {
-                    if (u == 0 || s_pfx[u] != s_pfx[u - 1]) { s_subpfx[ns] = s_pfx[u]; ++ns; }
-                    s_sub[u] = ns - 1;
-                }
-                s_nsub = ns;
-            }
-            for (int i = tid; i < TMAX * 256; i += FN_THREADS) (&s_hist[0][0])[i] = 0;
-            __syncthreads();
-            const int nsub = s_nsub;
-            if (pass == 0) {
-                batched_loop<8, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return xb[i]; }, [&](uint32_t, uint32_t bits) {
-                    atomicAdd(&s_hist[0][(key_of_bits(bits) >> 23) & 255u], 1u);
-                });
-            } else if (nsub == 1) {
-                const uint32_t pf = s_subpfx[0] >> hb;
-                batched_loop<8, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return xb[i]; }, [&](uint32_t, uint32_t bits) {
-                    const uint32_t key = key_of_bits(bits);
-                    if ((key >> hb) == pf) atomicAdd(&s_hist[0][(key >> shift) & mask], 1u);
-                });
-            } else {
-                batched_loop<8, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return xb[i]; }, [&](uint32_t, uint32_t bits) {
-                    const uint32_t key = key_of_bits(bits);
-                    const uint32_t kp = key >> hb;
-                    for (int s2 = 0; s2 < nsub; ++s2)
-                        if (kp == (s_subpfx[s2] >> hb)) atomicAdd(&s_hist[s2][(key >> shift) & mask], 1u);
-                });
-            }
-            __syncthreads();
-            for (int u = wave; u < nthr; u += FN_THREADS / 64) {
-                int bin;
-                uint32_t rin, cnt;
-                wave_rank_search<4>(s_hist[s_sub[u]], s_res[u], bin, rin, cnt);
-                if (lane == 0) {
-                    s_pfx[u] |= (uint32_t)bin << shift;
-                    s_res[u] = rin;
-                    if (pass == 3) { s_tau[u] = s_pfx[u]; s_q[u] = rin; s_eq[u] = cnt; }
-                }
-            }
-        }
+        // One threshold and a single distinct key in the overflow list (the usual case for 16-bit inputs): the key is
+        // the threshold, only the index cut is left: histogram of the indices, then the one bin ranked in LDS.
+        if (tid == 0) { s_any = 0; s_nsub = 0; }
         __syncthreads();
-        // index cut among the entries equal to the threshold key: the q-th smallest index + 1
-        if (tid < nthr) {
-            s_jx[tid] = JX_ALL;
-            s_pfx[tid] = 0;
-            s_res[tid] = s_eq[tid] - s_q[tid] + 1;   // the q-th smallest is the (eq - q + 1)-th largest
-            if (s_q[tid] < 1 || s_q[tid] > s_eq[tid]) fail();
+        if (par_big && nthr == 1) {
+            for (int i = tid; i < FH_BINS; i += FN_THREADS) s_fh[i] = 0;
+            if (tid == 0) { s_q[0] = 0xFFFFFFFFu; s_eq[0] = 0u; s_ncollect = 0; }
+            __syncthreads();
+            batched_loop<8, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return xb[i]; }, [&](uint32_t, uint32_t bits) {
+                const uint32_t key = key_of_bits(bits);
+                if (key < s_q[0]) atomicMin(&s_q[0], key);   // s_q / s_eq: smallest / largest key (checked first: mostly no atomic)
+                if (key > s_eq[0]) atomicMax(&s_eq[0], key);
+            });
+            __syncthreads();
+            const uint32_t key1 = s_q[0];
+            const bool single = key1 == s_eq[0];
+            __syncthreads();
+            if (single) {
+                const uint32_t q = s_res[0];   // the threshold is the q-th entry of the list by ascending index
+                int ish = 0;
+                while (((uint32_t)(a.d - 1) >> ish) >= (uint32_t)FH_BINS) ++ish;
+                if (q < xn) {
+                    batched_loop<8, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return xj[i]; },
+                                                [&](uint32_t, uint32_t j) { atomicAdd(&s_fh[j >> ish], 1u); });
+                    __syncthreads();
+                    if (wave == 0) {
+                        int bin;
+                        uint32_t rin, cnt;
+                        wave_rank_search<FH_BINS / 64>(s_fh, xn - q + 1u, bin, rin, cnt);   // q-th smallest = (n - q + 1)-th largest
+                        if (lane == 0) { s_bin[0] = (uint32_t)bin; s_rin[0] = rin; s_bcnt[0] = cnt; }
+                    }
+                    __syncthreads();
+                    if (s_bcnt[0] <= (uint32_t)COLLECT_CAP && s_bcnt[0] > 0) {
+                        const uint32_t ibin = s_bin[0];
+                        batched_loop<8, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return xj[i]; }, [&](uint32_t, uint32_t j) {
+                            if ((j >> ish) == ibin) {
+                                const uint32_t at = atomicAdd(&s_ncollect, 1u);
+                                if (at < (uint32_t)COLLECT_CAP) s_col[at] = j;
+                            }
+                        });
+                        __syncthreads();
+                        const uint32_t nc2 = s_ncollect < (uint32_t)COLLECT_CAP ? s_ncollect : (uint32_t)COLLECT_CAP;
+                        for (uint32_t e = tid; e < nc2; e += FN_THREADS) {
+                            const uint32_t j = (uint32_t)s_col[e];
+                            uint32_t above = 0;
+                            for (uint32_t f = 0; f < nc2; ++f) above += (uint32_t)s_col[f] > j ? 1u : 0u;
+                            if (above + 1u == s_rin[0]) { s_tau[0] = key1; s_jx[0] = j + 1u; s_any = 1; }
+                        }
+                    }
+                } else if (tid == 0) {   // every entry of the list is inside
+                    s_tau[0] = key1;
+                    s_jx[0] = JX_ALL;
+                    s_any = 1;
+                }
+                __syncthreads();
+            }
         }
-        if (tid == 0) {
-            int any = 0;
-            for (int u = 0; u < nthr; ++u) any |= s_q[u] < s_eq[u] ? 1 : 0;
-            s_any = any;
-        }
+        const bool resolved = s_any != 0;
         __syncthreads();
-        if (s_any) {
+        if (!resolved) {
             for (int pass = 0; pass < 4; ++pass) {
-                const int shift = 24 - 8 * pass;
-                const int hb = shift + 8;   // 32 for pass 0: no prefix yet
+                const int shift = pass == 0 ? 23 : pass == 1 ? 15 : pass == 2 ? 7 : 0;
+                const uint32_t mask = pass == 3 ? 127u : 255u;
+                const int hb = pass == 3 ? 7 : shift + 8;   // unresolved low bits before this pass (31 for pass 0)
+                __syncthreads();
                 if (tid == 0) {
                     int ns = 0;
                     for (int u = 0; u < nthr; ++u) {
-                        if (s_q[u] >= s_eq[u]) { s_sub[u] = -1; continue; }
-                        int found = -1;
-                        for (int s2 = 0; s2 < ns; ++s2)
-                            if (s_subtau[s2] == s_tau[u] && s_subpfx[s2] == s_pfx[u]) found = s2;
-                        if (found < 0) { s_subtau[ns] = s_tau[u]; s_subpfx[ns] = s_pfx[u]; found = ns++; }
-                        s_sub[u] = found;
+                        if (u == 0 || s_pfx[u] != s_pfx[u - 1]) { s_subpfx[ns] = s_pfx[u]; ++ns; }
+                        s_sub[u] = ns - 1;
                     }
                     s_nsub = ns;
                 }
                 for (int i = tid; i < TMAX * 256; i += FN_THREADS) (&s_hist[0][0])[i] = 0;
                 __syncthreads();
                 const int nsub = s_nsub;
-                batched_loop<8, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return make_uint2(xb[i], xj[i]); },
-                                            [&](uint32_t, uint2 e) {
-                    const uint32_t key = key_of_bits(e.x), j = e.y;
-                    for (int s2 = 0; s2 < nsub; ++s2) {
-                        if (key != s_subtau[s2]) continue;
-                        if (pass == 0 || (j >> hb) == (s_subpfx[s2] >> hb)) atomicAdd(&s_hist[s2][(j >> shift) & 255u], 1u);
-                    }
-                });
+                if (pass == 0) {
+                    batched_loop<8, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return xb[i]; }, [&](uint32_t, uint32_t bits) {
+                        atomicAdd(&s_hist[0][(key_of_bits(bits) >> 23) & 255u], 1u);
+                    });
+                } else if (nsub == 1) {
+                    const uint32_t pf = s_subpfx[0] >> hb;
+                    batched_loop<8, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return xb[i]; }, [&](uint32_t, uint32_t bits) {
+                        const uint32_t key = key_of_bits(bits);
+                        if ((key >> hb) == pf) atomicAdd(&s_hist[0][(key >> shift) & mask], 1u);
+                    });
+                } else {
+                    batched_loop<8, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return xb[i]; }, [&](uint32_t, uint32_t bits) {
+                        const uint32_t key = key_of_bits(bits);
+                        const uint32_t kp = key >> hb;
+                        for (int s2 = 0; s2 < nsub; ++s2)
+                            if (kp == (s_subpfx[s2] >> hb)) atomicAdd(&s_hist[s2][(key >> shift) & mask], 1u);
+                    });
+                }
                 __syncthreads();
                 for (int u = wave; u < nthr; u += FN_THREADS / 64) {
-                    if (s_sub[u] < 0) continue;
                     int bin;
                     uint32_t rin, cnt;
                     wave_rank_search<4>(s_hist[s_sub[u]], s_res[u], bin, rin, cnt);
                     if (lane == 0) {
                         s_pfx[u] |= (uint32_t)bin << shift;
                         s_res[u] = rin;
-                        if (pass == 3) s_jx[u] = s_pfx[u] + 1u;
+                        if (pass == 3) { s_tau[u] = s_pfx[u]; s_q[u] = rin; s_eq[u] = cnt; }
                     }
                 }
-                __syncthreads();
+            }
+            __syncthreads();
+            // index cut among the entries equal to the threshold key: the q-th smallest index + 1
+            if (tid < nthr) {
+                s_jx[tid] = JX_ALL;
+                s_pfx[tid] = 0;
+                s_res[tid] = s_eq[tid] - s_q[tid] + 1;   // the q-th smallest is the (eq - q + 1)-th largest
+                if (s_q[tid] < 1 || s_q[tid] > s_eq[tid]) fail();
+            }
+            if (tid == 0) {
+                int any = 0;
+                for (int u = 0; u < nthr; ++u) any |= s_q[u] < s_eq[u] ? 1 : 0;
+                s_any = any;
+            }
+            __syncthreads();
+            if (s_any) {
+                for (int pass = 0; pass < 4; ++pass) {
+                    const int shift = 24 - 8 * pass;
+                    const int hb = shift + 8;   // 32 for pass 0: no prefix yet
+                    if (tid == 0) {
+                        int ns = 0;
+                        for (int u = 0; u < nthr; ++u) {
+                            if (s_q[u] >= s_eq[u]) { s_sub[u] = -1; continue; }
+                            int found = -1;
+                            for (int s2 = 0; s2 < ns; ++s2)
+                                if (s_subtau[s2] == s_tau[u] && s_subpfx[s2] == s_pfx[u]) found = s2;
+                            if (found < 0) { s_subtau[ns] = s_tau[u]; s_subpfx[ns] = s_pfx[u]; found = ns++; }
+                            s_sub[u] = found;
+                        }
+                        s_nsub = ns;
+                    }
+                    for (int i = tid; i < TMAX * 256; i += FN_THREADS) (&s_hist[0][0])[i] = 0;
+                    __syncthreads();
+                    const int nsub = s_nsub;
+                    batched_loop<8, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return make_uint2(xb[i], xj[i]); },
+                                                [&](uint32_t, uint2 e) {
+                        const uint32_t key = key_of_bits(e.x), j = e.y;
+                        for (int s2 = 0; s2 < nsub; ++s2) {
+                            if (key != s_subtau[s2]) continue;
+                            if (pass == 0 || (j >> hb) == (s_subpfx[s2] >> hb)) atomicAdd(&s_hist[s2][(j >> shift) & 255u], 1u);
+                        }
+                    });
+                    __syncthreads();
+                    for (int u = wave; u < nthr; u += FN_THREADS / 64) {
+                        if (s_sub[u] < 0) continue;
+                        int bin;
+                        uint32_t rin, cnt;
+                        wave_rank_search<4>(s_hist[s_sub[u]], s_res[u], bin, rin, cnt);
+                        if (lane == 0) {
+                            s_pfx[u] |= (uint32_t)bin << shift;
+                            s_res[u] = rin;
+                            if (pass == 3) s_jx[u] = s_pfx[u] + 1u;
+                        }
+                    }
+                    __syncthreads();
+                }
             }
         }
         // every candidate's part from the exact thresholds
