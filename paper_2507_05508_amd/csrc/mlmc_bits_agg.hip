@@ -10,11 +10,13 @@
 namespace mlmc {
 
 // ---------------------------------------------------------------------------------------------------
+constexpr int BITS_MAX_CHUNKS = 4;
 template <int DT, bool VEC>
 __global__ __launch_bounds__(512) void k_bits_max(BitsArgs a) {
     const int row = blockIdx.y;
-    const int64_t c0 = (int64_t)blockIdx.x * a.chunk;
-    const int64_t c1 = c0 + a.chunk < a.d ? c0 + a.chunk : a.d;
+    const int64_t span = (int64_t)a.chunk * BITS_MAX_CHUNKS;   // several chunks per workgroup: long unchecked runs
+    const int64_t c0 = (int64_t)blockIdx.x * span;
+    const int64_t c1 = c0 + span < a.d ? c0 + span : a.d;
     RowLoader<DT, VEC> ld(a.g, a.ld, a.d, row);
     uint32_t maxkey = 0;
     constexpr int64_t STEP = 512 * 4;
@@ -268,7 +270,7 @@ __global__ __launch_bounds__(256) void k_agg_sparse(AggSparseArgs a) {
 
 // ---------------------------------------------------------------------------------------------------
 mlmc_status bits_compress(const mlmc_plan_t* pl, const BitsArgs& a, bool vec, hipStream_t st) {
-    dim3 grid(pl->chunks_per_row, pl->M);
+    dim3 grid((pl->chunks_per_row + BITS_MAX_CHUNKS - 1) / BITS_MAX_CHUNKS, pl->M);
     if (pl->dtype == MLMC_F32) {
         if (vec) MLMC_LAUNCH(K_BITS_MAX, st, k_bits_max<MLMC_F32, true><<<grid, 512, 0, st>>>(a));
         else MLMC_LAUNCH(K_BITS_MAX, st, k_bits_max<MLMC_F32, false><<<grid, 512, 0, st>>>(a));
