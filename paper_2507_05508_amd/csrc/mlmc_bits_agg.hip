@@ -68,20 +68,18 @@ __device__ __forceinline__ BitsRow bits_row(const BitsArgs& a, int row) {
 
 // One wave packs one tile of 4096 elements: iteration i covers elements [64 i, 64 i + 64) of the tile, so a
 // ballot is the plane word of those 64 elements; lane i keeps word i and the 64 words go out in one store.
-template <int DT>
-__global__ __launch_bounds__(256) void k_bits_extract(BitsArgs a) {
-    const int row = blockIdx.y;
+// NPC: compile-time bound on the planes of the row (its actual count np <= NPC), so that the per-slot loop over
+// planes is as long as needed and no longer.
+template <int DT, int NPC>
+__device__ __forceinline__ void bits_extract_row(const BitsArgs& a, int row, const BitsRow& br, int np) {
     const uint32_t lane = lane_id(), wave = threadIdx.x >> 6;
-    const BitsRow br = bits_row(a, row);
-    const int np = 1 + br.F0 + br.width;  // planes written for this row
     RowLoader<DT, false> ld(a.g, a.ld, a.d, row);
     const int64_t ntiles = (a.d + TILE - 1) / TILE;
-    if (blockIdx.x == 0 && threadIdx.x == 0) a.scale_exp[row] = br.Emax - 126;
     for (int64_t tile = (int64_t)blockIdx.x * 4 + wave; tile < ntiles; tile += (int64_t)gridDim.x * 4) {
         const int64_t base = tile * TILE;
-        uint64_t words[MAX_PLANES];
+        uint64_t words[NPC];
 #pragma unroll
-        for (int p = 0; p < MAX_PLANES; ++p) words[p] = 0;
+        for (int p = 0; p < NPC; ++p) words[p] = 0;
         auto digits = [&](uint32_t bits) -> uint32_t {
             uint32_t key = key_of_bits(bits);
             uint32_t E = key >> 23;
@@ -94,7 +92,7 @@ __global__ __launch_bounds__(256) void k_bits_extract(BitsArgs a) {
         };
         auto pack = [&](int i, uint32_t packed) {
 #pragma unroll
-            for (int p = 0; p < MAX_PLANES; ++p) {
+            for (int p = 0; p < NPC; ++p) {
                 if (p < np) {
                     uint64_t w = __ballot((packed >> p) & 1u);
                     if (lane == (uint32_t)i) words[p] = w;
@@ -120,10 +118,25 @@ __global__ __launch_bounds__(256) void k_bits_extract(BitsArgs a) {
         if (w0 < a.nwords) {
             uint64_t* dst = a.planes + (size_t)row * a.nplanes * a.nwords + w0;
 #pragma unroll
-            for (int p = 0; p < MAX_PLANES; ++p)
+            for (int p = 0; p < NPC; ++p)
                 if (p < np) dst[(size_t)p * a.nwords] = words[p];
         }
     }
+}
+
+// One wave packs one tile of 4096 elements: iteration i covers elements [64 i, 64 i + 64) of the tile, so a
+// ballot is the plane word of those 64 elements; lane i keeps word i and the 64 words go out in one store.
+template <int DT>
+__global__ __launch_bounds__(256) void k_bits_extract(BitsArgs a) {
+    const int row = blockIdx.y;
+    const BitsRow br = bits_row(a, row);
+    const int np = 1 + br.F0 + br.width;  // planes written for this row
+    if (blockIdx.x == 0 && threadIdx.x == 0) a.scale_exp[row] = br.Emax - 126;
+    if (np <= 3) bits_extract_row<DT, 3>(a, row, br, np);
+    else if (np <= 5) bits_extract_row<DT, 5>(a, row, br, np);
+    else if (np <= 9) bits_extract_row<DT, 9>(a, row, br, np);
+    else if (np <= 17) bits_extract_row<DT, 17>(a, row, br, np);
+    else bits_extract_row<DT, MAX_PLANES>(a, row, br, np);
 }
 
 struct AggBitsArgs {
