@@ -149,6 +149,10 @@ struct AggBitsArgs {
 };
 
 // out[j] = alpha * sum over rows (worker order) of sign * (f0 * c0 + f * cl): Alg. 2 "Server aggregates".
+// A wave owns word w of every plane, i.e. elements 64 w .. 64 w + 63 (lane = element).  The words it needs (one
+// per row and plane) are fetched by different lanes in one load per group of rows; a word is then read from its
+// lane as a wave-wide mask whose bit `lane` is the element's bit.  NPC bounds the planes of any row.
+template <int NPC>
 __global__ __launch_bounds__(256) void k_agg_bits(AggBitsArgs a) {
     __shared__ float s_c0[MLMC_MAX_WORKERS], s_cl[MLMC_MAX_WORKERS];
     __shared__ uint8_t s_w[MLMC_MAX_WORKERS];
@@ -163,22 +167,45 @@ __global__ __launch_bounds__(256) void k_agg_bits(AggBitsArgs a) {
         s_w[r] = (uint8_t)(b.F[lev] - b.F[lev - 1]);
     }
     __syncthreads();
+    constexpr int RPG = 64 / NPC;   // rows whose words fit one register across the wave
     const uint32_t lane = lane_id();
+    const int rr_l = (int)lane / NPC, pp_l = (int)lane % NPC;
     const int64_t nw = b.nwords;
     const int64_t wave_global = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 6;
     const int64_t nwaves = ((int64_t)gridDim.x * 256) >> 6;
     for (int64_t w = wave_global; w < nw; w += nwaves) {
         float acc = 0.0f;
-        for (int r = 0; r < b.M; ++r) {
-            const uint64_t* pr = a.planes + (size_t)r * b.nplanes * nw + w;
-            uint32_t sign = (uint32_t)(pr[0] >> lane) & 1u;
-            uint32_t f0 = 0, f = 0;
-            for (int p = 0; p < F0; ++p) f0 |= ((uint32_t)(pr[(size_t)(1 + p) * nw] >> lane) & 1u) << p;
-            const int width = s_w[r];
-            for (int p = 0; p < width; ++p) f |= ((uint32_t)(pr[(size_t)(1 + F0 + p) * nw] >> lane) & 1u) << p;
-            float v = __fmul_rn((float)f, s_cl[r]);
-            if (F0 > 0) v = __fadd_rn(__fmul_rn((float)f0, s_c0[r]), v);
-            acc = __fadd_rn(acc, sign ? -v : v);
+        for (int r0 = 0; r0 < b.M; r0 += RPG) {
+            uint64_t mine = 0;
+            {
+                const int r = r0 + rr_l;
+                if (rr_l < RPG && r < b.M && pp_l < 1 + F0 + (int)s_w[r])
+                    mine = a.planes[((size_t)r * b.nplanes + pp_l) * nw + w];
+            }
+#pragma unroll
+            for (int rr = 0; rr < RPG; ++rr) {
+                const int r = r0 + rr;
+                if (r < b.M) {   // uniform
+                const int np = 1 + F0 + (int)s_w[r];
+                uint32_t f0 = 0, f = 0;
+#pragma unroll
+                for (int p = 1; p < NPC; ++p) {
+                    if (p < np) {   // uniform
+                        const uint64_t word = ((uint64_t)__builtin_amdgcn_readlane((uint32_t)(mine >> 32), rr * NPC + p) << 32) |
+                                              (uint32_t)__builtin_amdgcn_readlane((uint32_t)mine, rr * NPC + p);
+                        const bool bit = __builtin_amdgcn_inverse_ballot_w64(word);
+                        if (p <= F0) f0 |= bit ? 1u << (p - 1) : 0u;
+                        else f |= bit ? 1u << (p - 1 - F0) : 0u;
+                    }
+                }
+                const uint64_t sw = ((uint64_t)__builtin_amdgcn_readlane((uint32_t)(mine >> 32), rr * NPC) << 32) |
+                                    (uint32_t)__builtin_amdgcn_readlane((uint32_t)mine, rr * NPC);
+                const bool sign = __builtin_amdgcn_inverse_ballot_w64(sw);
+                float v = __fmul_rn((float)f, s_cl[r]);
+                if (F0 > 0) v = __fadd_rn(__fmul_rn((float)f0, s_c0[r]), v);
+                acc = __fadd_rn(acc, sign ? -v : v);
+                }
+            }
         }
         const int64_t j = w * 64 + lane;
         if (j < b.d) a.out[j] = __fmul_rn(a.alpha, acc);
@@ -315,7 +342,12 @@ mlmc_status agg_bits(const mlmc_plan_t* pl, const BitsArgs& b, const int32_t* le
     int blocks = (int)((waves + 3) / 4);
     if (blocks > 8192) blocks = 8192;
     if (blocks < 1) blocks = 1;
-    MLMC_LAUNCH(K_AGG_BITS, st, k_agg_bits<<<blocks, 256, 0, st>>>(a));
+    const int np = b.nplanes;   // 1 + F_0 + widest level field: bounds the planes of any row
+    if (np <= 3) MLMC_LAUNCH(K_AGG_BITS, st, k_agg_bits<3><<<blocks, 256, 0, st>>>(a));
+    else if (np <= 5) MLMC_LAUNCH(K_AGG_BITS, st, k_agg_bits<5><<<blocks, 256, 0, st>>>(a));
+    else if (np <= 9) MLMC_LAUNCH(K_AGG_BITS, st, k_agg_bits<9><<<blocks, 256, 0, st>>>(a));
+    else if (np <= 17) MLMC_LAUNCH(K_AGG_BITS, st, k_agg_bits<17><<<blocks, 256, 0, st>>>(a));
+    else MLMC_LAUNCH(K_AGG_BITS, st, k_agg_bits<MAX_PLANES><<<blocks, 256, 0, st>>>(a));
     return MLMC_OK;
 }
 
