@@ -227,6 +227,29 @@ def test_degenerate_shapes(d, ladder):
             assert np.array_equal(out.cpu().numpy().view(np.uint32), O.aggregate_sparse(want, d, 0.5).view(np.uint32))
 
 
+def test_many_levels_many_rows():
+    """The limits of the plan: L = 32 levels (33 thresholds, most of them crowded into a few buckets) and more rows
+    than any other test, sampled and exact threshold search, adaptive and fixed p."""
+    rng = np.random.default_rng(7)
+    M, d, L = 37, 3 * 16384 + 811, 32
+    G = (rng.standard_normal((M, d)) * np.exp(rng.uniform(-6, 2, size=(M, 1)))).astype(np.float32)
+    ladder = [3] + [10 + 37 * l + (l * l * l) // 2 for l in range(1, L)] + [d]
+    assert all(a < b for a, b in zip(ladder, ladder[1:]))
+    g = to_device(G)
+    for pf in (None, O.geometric_p(L)):
+        for shift in (0, 2):
+            plan = P.Plan(P.MLMC_TOPK, M, d, P.MLMC_F32, ladder, pf)
+            plan.set_sampling(shift)
+            for step in range(3):
+                print(f"L=32 M={M} adaptive={pf is None} shift={shift} step={step}", flush=True)
+                msg = P.mlmc_compress_topk(plan, g, seed=5, step=step)
+                want = check_topk_against_oracle(plan, G, 5, step, msg, adaptive=pf is None)
+                assert plan.status() == 0
+                out = P.mlmc_aggregate(plan, msg, 1.0 / M)
+                torch.cuda.synchronize()
+                assert np.array_equal(out.cpu().numpy().view(np.uint32), O.aggregate_sparse(want, d, 1.0 / M).view(np.uint32))
+
+
 def test_identity_ladder_is_dense_mean():
     """L = 1, k_0 = 0, k_1 = d, p = 1: the message is the gradient and the aggregate is Alg. 1's mean."""
     rng = np.random.default_rng(0)
