@@ -448,15 +448,31 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
     uint32_t head = 0, tail = 0;   // wave-uniform: candidates staged / written out so far
     uint32_t maxkey = 0;
 
-    // whole batches of 64 staged candidates -> the private list (dense stores, nothing to wait for)
+    // Whole batches of 64 staged entries -> the private list (dense stores).  The batch is read from LDS now and
+    // stored at the next call, so that the wave never waits for the LDS read (LDS serves a wave's accesses in
+    // order: the ring slots may be overwritten right away).
+    uint2 pend = make_uint2(0u, 0u);
+    uint32_t pend_at = 0;
+    bool pend_valid = false;   // wave-uniform
     auto drain = [&](bool all) {
-        wave_lds_sync();
-        while (head - tail >= 64u || (all && head != tail)) {
-            const uint32_t i = tail + lane;
-            if (i < head) priv[i] = s_stage[i % (uint32_t)RING];
-            tail = head - tail >= 64u ? tail + 64u : head;
+        if (pend_valid) priv[pend_at + lane] = pend;
+        pend_valid = false;
+        if (head - tail >= 64u) {
+            pend = s_stage[(tail + lane) % (uint32_t)RING];
+            pend_at = tail;
+            pend_valid = true;
+            tail += 64u;
         }
-        wave_lds_sync();
+        if (all) {
+            wave_lds_sync();
+            if (pend_valid) priv[pend_at + lane] = pend;
+            pend_valid = false;
+            while (head != tail) {
+                const uint32_t i = tail + lane;
+                if (i < head) priv[i] = s_stage[i % (uint32_t)RING];
+                tail = head - tail >= 64u ? tail + 64u : head;
+            }
+        }
     };
 
     // four consecutive elements of every lane (bit c of vmask: element c is inside the chunk): table look-ups
