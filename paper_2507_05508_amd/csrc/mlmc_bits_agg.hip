@@ -72,7 +72,7 @@ __device__ __forceinline__ BitsRow bits_row(const BitsArgs& a, int row) {
 // planes is as long as needed and no longer.
 template <int DT, int NPC>
 __device__ __forceinline__ void bits_extract_row(const BitsArgs& a, int row, const BitsRow& br, int np) {
-    const uint32_t lane = lane_id(), wave = threadIdx.x >> 6;
+    const uint32_t lane = lane_id(), wave = (uint32_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     RowLoader<DT, false> ld(a.g, a.ld, a.d, row);
     const int64_t ntiles = (a.d + TILE - 1) / TILE;
     for (int64_t tile = (int64_t)blockIdx.x * 4 + wave; tile < ntiles; tile += (int64_t)gridDim.x * 4) {

@@ -43,7 +43,7 @@ __device__ __forceinline__ uint32_t wave_excl_small(uint32_t c, uint32_t& total)
 // Exclusive scan over a workgroup of NT threads (NT multiple of 64, <= 1024). `lds` holds NT/64 + 1 words.
 template <int NT>
 __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* lds, uint32_t& total) {
-    const uint32_t lane = lane_id(), wave = threadIdx.x >> 6;
+    const uint32_t lane = lane_id(), wave = (uint32_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     uint32_t inc = v;
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {

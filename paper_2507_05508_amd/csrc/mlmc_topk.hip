@@ -61,7 +61,7 @@ __global__ __launch_bounds__(HIST_THREADS) void k_hist(TopkArgs a, int exact_pas
     for (int b = threadIdx.x; b < NB1; b += HIST_THREADS) h[b] = 0;
     __syncthreads();
     RowLoader<DT, VEC> ld(a.g, a.ld, a.d, row);
-    const uint32_t lane = lane_id(), wave = threadIdx.x >> 6;
+    const uint32_t lane = lane_id(), wave = (uint32_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     uint32_t maxkey = 0;
     auto count4 = [&](const uint32_t (&b)[4], int nv) {
 #pragma unroll
@@ -413,7 +413,8 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
     const int row = blockIdx.y, tid = threadIdx.x;
     const RowInfo* ri = a.rinfo + row;
     if (exact_pass && !ri->respec) return;
-    const uint32_t lane = lane_id(), wave = tid >> 6;
+    const uint32_t lane = lane_id();
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: loop bounds and offsets stay in SGPRs
     RowAcc* ra = a.racc + row;
     const int nz = ri->n_zones;
     uint2* s_stage = (uint2*)(lm + LM_STAGE) + wave * RING;
@@ -515,14 +516,14 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
 
     // Load n of a wave covers the 256 elements at c0 + (16 n + wave) * 256: the 16 waves read 16 KB side by
     // side.  Eight loads per lane stay in flight: a slot is refilled as soon as it has been processed.
-    const int64_t span = c1 - c0;
-    const int64_t woff = (int64_t)wave * 256;
-    const int64_t nfull = span >= woff + 256 ? (span - woff - 256) / 4096 + 1 : 0;   // loads with all 256 elements
-    auto issue = [&](int64_t n, uint32_t (&b)[4]) { ld.load4_full(c0 + (n * 16 + wave) * 256 + (int64_t)lane * 4, b); };
-    auto rel_of = [&](int64_t n) -> uint32_t { return (uint32_t)((n * 16 + wave) * 256) + lane * 4; };
+    const int span = (int)(c1 - c0);
+    const int woff = (int)wave * 256;
+    const int nfull = span >= woff + 256 ? (span - woff - 256) / 4096 + 1 : 0;   // loads with all 256 elements
+    auto issue = [&](int n, uint32_t (&b)[4]) { ld.load4_full(c0 + (int64_t)((n * 16 + (int)wave) * 256) + (int64_t)lane * 4, b); };
+    auto rel_of = [&](int n) -> uint32_t { return (uint32_t)((n * 16 + (int)wave) * 256) + lane * 4; };
     // load round n covers tile n of the chunk: its counters are those of the count chunk the tile lies in
-    const int64_t tpc = a.cchunk / TILE;   // tiles per count chunk
-    auto cnt_of = [&](int64_t n) -> uint32_t {
+    const int tpc = a.cchunk / TILE;   // tiles per count chunk
+    auto cnt_of = [&](int n) -> uint32_t {
         const uint32_t sub = (n >= tpc ? 1u : 0u) + (n >= 2 * tpc ? 1u : 0u) + (n >= 3 * tpc ? 1u : 0u);
         return cnt_lane + (a.csub > 1 ? sub : 0u) * (uint32_t)(128 * REP_CNT * 4);
     };
@@ -530,7 +531,7 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
     // that their latency is covered.
     uint32_t buf[8][4];
     uint32_t cc[4], cn[4];
-    int64_t n = 0;
+    int n = 0;
     if (nfull >= 8) {
 #pragma unroll
         for (int q = 0; q < 8; ++q) issue(q, buf[q]);
@@ -559,8 +560,8 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
         lookup(buf[0], cc);
         process(buf[0], cc, rel_of(n), 15u, cnt_of(n));
     }
-    if (c0 + (nfull * 16 + wave) * 256 < c1) {   // the ragged end of the chunk: at most one partial load per wave
-        const int64_t j = c0 + (nfull * 16 + wave) * 256 + (int64_t)lane * 4;
+    if (c0 + (int64_t)((nfull * 16 + (int)wave) * 256) < c1) {   // the ragged end of the chunk: at most one partial load per wave
+        const int64_t j = c0 + (int64_t)((nfull * 16 + (int)wave) * 256) + (int64_t)lane * 4;
         const int nv = j < c1 ? ld.load4(j, buf[0]) : 0;
 #pragma unroll
         for (int c = 0; c < 4; ++c) if (c >= nv) buf[0][c] = 0u;
@@ -774,7 +775,7 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
     __shared__ uint32_t s_fill[ZMAX], s_rcnt[RMAX];
     __shared__ int32_t s_first[ZMAX + 1];
     const int row = blockIdx.y, tid = threadIdx.x;
-    const uint32_t lane = lane_id(), wave = tid >> 6, lrep = lane & (uint32_t)(PREP - 1);
+    const uint32_t lane = lane_id(), wave = (uint32_t)__builtin_amdgcn_readfirstlane(tid >> 6), lrep = lane & (uint32_t)(PREP - 1);
     RowInfo* ri = a.rinfo + row;
     RowAcc* ra = a.racc + row;
     if (exact_pass && !ri->respec) return;
@@ -1564,7 +1565,7 @@ __global__ __launch_bounds__(WR_THREADS, 4) void k_write(TopkArgs a) {
     __shared__ uint32_t s_wemit[2][WR_WAVES];
     __shared__ uint2 s_out[2][WR_STAGE];
     const int row = blockIdx.y, chunk_id = blockIdx.x, tid = threadIdx.x;
-    const uint32_t lane = lane_id(), wave = tid >> 6;
+    const uint32_t lane = lane_id(), wave = (uint32_t)__builtin_amdgcn_readfirstlane(tid >> 6);
     const RowInfo* ri = a.rinfo + row;
     if (ri->spec_ok) return;   // the message of this row comes from the staged lists (k_filter)
     const int nc = a.cchunks_per_row;   // one workgroup per count chunk
@@ -1728,7 +1729,7 @@ __global__ __launch_bounds__(FL_THREADS) void k_filter(TopkArgs a) {
     uint32_t* s_pre = s_dyn + a.chunk / 32; // members in the words before
     __shared__ uint32_t s_scan[FL_THREADS / 64 + 1];
     const int row = blockIdx.y, chunk_id = blockIdx.x, tid = threadIdx.x;
-    const uint32_t lane = lane_id(), wave = tid >> 6;
+    const uint32_t lane = lane_id(), wave = (uint32_t)__builtin_amdgcn_readfirstlane(tid >> 6);
     const RowInfo* ri = a.rinfo + row;
     if (!ri->spec_ok) return;   // k_write reads the row again
     const int nc = a.chunks_per_row;
