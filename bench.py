@@ -92,6 +92,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD, choices=sorted(W.WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-staging", action="store_true",
+                    help="Top-k: write every message by a second read of the rows (tuning hook off; same results)")
     ap.add_argument("--cpu-budget", type=float, default=25.0)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device copy (a known-size kernel to scale profiler byte counters by)")
@@ -121,6 +123,8 @@ def main():
         plan = P.Plan(P.MLMC_TOPK, w.M, w.d, P.MLMC_BF16 if w.dtype == "bf16" else P.MLMC_F32, w.ladder,
                       None if w.adaptive else P.mlmc_geometric_p(w.L))
         msg = P.SparseMessage(plan, with_norms=w.adaptive)
+        if args.no_staging:
+            plan.set_staging(False)
     else:
         plan = P.Plan(P.MLMC_BITS, w.M, w.d, P.MLMC_F32, w.ladder, P.mlmc_geometric_p(w.L))
         msg = P.BitsMessage(plan)
