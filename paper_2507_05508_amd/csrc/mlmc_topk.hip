@@ -124,8 +124,13 @@ __device__ void draw_row(const TopkArgs& a, int row, const double* norms_row, do
 
 // ---------------------------------------------------------------------------------------------------
 // Per row: zones and regions from the histogram, candidate list layout, the class table.
-// How far (in standard deviations of the sampled count) a zone reaches on either side of the estimated rank.
+// How far (in standard deviations of the sampled count) a zone reaches on either side of the estimated rank.  The
+// binomial model fits when every homogeneous stretch of a row contributes many sampled blocks; a small sample of a
+// row made of segments with different scales is over-dispersed (whole blocks share a scale), hence the wide margin
+// there.  A zone that misses its threshold only costs the exact redo of that row.
 constexpr double ZONE_SIGMAS = 8.0;
+constexpr double ZONE_SIGMAS_BIG = 5.0;         // samples of at least ZONE_BIG_SAMPLE elements
+constexpr int64_t ZONE_BIG_SAMPLE = 1 << 20;
 constexpr int64_t STAGE_MAX_BAND_INV = 16;   // bands wider than d / 16 are not staged
 
 __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
@@ -205,8 +210,9 @@ __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
             const double m = (double)kt * (double)ns / (double)a.d;
             const double frac = 1.0 - (double)kt / (double)a.d;
             const double sd = sqrt(m * (frac > 0.0 ? frac : 0.0));
-            lo = (int64_t)floor(m - ZONE_SIGMAS * sd) - 2;
-            hi = (int64_t)ceil(m + ZONE_SIGMAS * sd) + 2;
+            const double zs = ns >= ZONE_BIG_SAMPLE ? ZONE_SIGMAS_BIG : ZONE_SIGMAS;
+            lo = (int64_t)floor(m - zs * sd) - 2;
+            hi = (int64_t)ceil(m + zs * sd) + 2;
         }
         if (lo < 1) lo = 0;            // the zone starts at the highest bucket
         if (hi > ns) hi = ns + 1;      // the zone reaches the lowest bucket
@@ -379,7 +385,6 @@ __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
 // The selection read: region counts, group sums (SUMS), zone candidates.
 constexpr int MAIN_THREADS = 1024;
 constexpr int MAIN_WAVES = MAIN_THREADS / 64;
-constexpr int RING = 128;    // staged entries per wave (ring); at most 63 + 64 are pending at any time
 
 // LDS layout (bytes), all of the 160 KB.  The table sits at offset 0 so that the look-up needs no base; the sums
 // at 64 KB and the counters at a multiple of 32 KB so that their bases can be OR-ed with the fields of the class
@@ -391,10 +396,10 @@ constexpr int LM_ZMAX = LM_ZCUR + 64 * 4;                   // uint32 [64] large
 constexpr int LM_ZMIN = LM_ZMAX + 64 * 4;                   // uint32 [64] largest ~key
 constexpr int LM_ZOFF = LM_ZMIN + 64 * 4;                   // uint32 [64]
 constexpr int LM_ZCAP = LM_ZOFF + 64 * 4;
-constexpr int LM_STAGE = LM_ZCAP + 64 * 4;                  // uint2 [MAIN_WAVES][RING]: {bits, rel << 6 | tag}
+constexpr int LM_MISC_END = LM_ZCAP + 64 * 4;
 constexpr int LM_CNT = 4 * 32768;                           // uint32 [CSUB_MAX][128][REP_CNT]: regions 0..63, zones 64..127
 constexpr int LM_END = LM_CNT + CSUB_MAX * 128 * REP_CNT * 4;
-static_assert(LM_SUM == 65536 && LM_STAGE + MAIN_WAVES * RING * 8 <= LM_CNT && LM_CNT % 32768 == 0, "LDS layout");
+static_assert(LM_SUM == 65536 && LM_MISC_END <= LM_CNT && LM_CNT % 32768 == 0, "LDS layout");
 static_assert(REP_SUM * 8 == 128 && REP_CNT * 4 == 64 && CSUB_MAX * 128 * REP_CNT * 4 == 32768, "field scaling of the class code");
 template <bool SUMS> constexpr int lm_total() { return LM_END; }
 static_assert(lm_total<true>() <= 160 * 1024, "LDS budget");
@@ -417,7 +422,6 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
     const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: loop bounds and offsets stay in SGPRs
     RowAcc* ra = a.racc + row;
     const int nz = ri->n_zones;
-    uint2* s_stage = (uint2*)(lm + LM_STAGE) + wave * RING;
     {
         const uint4* src = (const uint4*)(a.table + (size_t)row * NB1);
         uint4* dst = (uint4*)(lm + LM_TAB);
@@ -446,35 +450,8 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
     // per-lane byte addresses of the replicated accumulators
     const uint32_t cnt_lane = (uint32_t)LM_CNT + (lane & 15u) * 4u;
     const uint32_t sum_lane = (uint32_t)LM_SUM + (lane & 15u) * 8u;
-    uint32_t head = 0, tail = 0;   // wave-uniform: candidates staged / written out so far
+    uint32_t head = 0;   // wave-uniform: entries staged so far
     uint32_t maxkey = 0;
-
-    // Whole batches of 64 staged entries -> the private list (dense stores).  The batch is read from LDS now and
-    // stored at the next call, so that the wave never waits for the LDS read (LDS serves a wave's accesses in
-    // order: the ring slots may be overwritten right away).
-    uint2 pend = make_uint2(0u, 0u);
-    uint32_t pend_at = 0;
-    bool pend_valid = false;   // wave-uniform
-    auto drain = [&](bool all) {
-        if (pend_valid) priv[pend_at + lane] = pend;
-        pend_valid = false;
-        if (head - tail >= 64u) {
-            pend = s_stage[(tail + lane) % (uint32_t)RING];
-            pend_at = tail;
-            pend_valid = true;
-            tail += 64u;
-        }
-        if (all) {
-            wave_lds_sync();
-            if (pend_valid) priv[pend_at + lane] = pend;
-            pend_valid = false;
-            while (head != tail) {
-                const uint32_t i = tail + lane;
-                if (i < head) priv[i] = s_stage[i % (uint32_t)RING];
-                tail = head - tail >= 64u ? tail + 64u : head;
-            }
-        }
-    };
 
     // four consecutive elements of every lane (bit c of vmask: element c is inside the chunk): table look-ups
     // first, then the accumulators (zone buckets carry a dummy group, elements past the end a dummy class, so
@@ -504,12 +481,9 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 const uint64_t m = __ballot(code[c] & CODE_STAGE);
-                if (__builtin_amdgcn_inverse_ballot_w64(m)) {
-                    const uint32_t pos = (head + mbcnt(m)) % (uint32_t)RING;
-                    s_stage[pos] = make_uint2(b[c], (relc + ((uint32_t)c << 6)) | (code[c] & 63u));
-                }
+                if (__builtin_amdgcn_inverse_ballot_w64(m))
+                    priv[head + mbcnt(m)] = make_uint2(b[c], (relc + ((uint32_t)c << 6)) | (code[c] & 63u));
                 head += (uint32_t)__popcll(m);
-                if (head - tail >= 64u) drain(false);   // at most 63 + 64 entries are ever pending
             }
         }
     };
@@ -568,7 +542,6 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
         lookup(buf[0], cc);
         process(buf[0], cc, rel_of(nfull), (1u << nv) - 1u, cnt_of(nfull));
     }
-    drain(true);
     if (__ballot(maxkey >= 0x7F800000u) && lane == 0) atomicOr(a.dev_status, MLMC_DEV_NONFINITE);
     __threadfence_block();
     __syncthreads();
@@ -585,7 +558,7 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
     uint32_t* ci = a.cand_idx + (size_t)row * (size_t)a.d;
     bool dropped = false;
     if (lane == 0) a.priv_cnt[((size_t)row * a.chunks_per_row + blockIdx.x) * MAIN_WAVES + wave] = head;
-    batched_loop<8, 64>(0u, head, lane, [&](uint32_t i) { return priv[i]; }, [&](uint32_t, uint2 e) {
+    batched_loop<16, 64>(0u, head, lane, [&](uint32_t i) { return priv[i]; }, [&](uint32_t, uint2 e) {
         const uint32_t z = e.y & 63u, key = key_of_bits(e.x);
         if (z == TAG_MEMBER) return;   // staged for the message only
         const uint32_t pos = atomicAdd(&s_zcur[z], 1u);
