@@ -294,9 +294,22 @@ __global__ __launch_bounds__(256) void k_agg_sparse(AggSparseArgs a) {
                     const uint32_t off = pidx[k] - (uint32_t)base;
                     if (off < (uint32_t)TILE) s_acc[off] = __fadd_rn(s_acc[off], pval[k]);
                 }
-                for (uint32_t i = threadIdx.x + 256; i < len; i += 256) {
-                    const uint32_t off = a.idx[beg + i] - (uint32_t)base;
-                    if (off < (uint32_t)TILE) s_acc[off] = __fadd_rn(s_acc[off], a.val[beg + i]);
+                // the rest of a long row: four loads per thread in flight (past the end: the last entry, discarded)
+                for (uint32_t i0 = threadIdx.x + 256; i0 < len; i0 += 1024) {
+                    uint32_t qi[4];
+                    float qv[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const uint32_t i = i0 + (uint32_t)u * 256u;
+                        const uint32_t e = i < len ? i : len - 1u;
+                        qi[u] = a.idx[beg + e];
+                        qv[u] = a.val[beg + e];
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const uint32_t off = qi[u] - (uint32_t)base;
+                        if (i0 + (uint32_t)u * 256u < len && off < (uint32_t)TILE) s_acc[off] = __fadd_rn(s_acc[off], qv[u]);
+                    }
                 }
                 __syncthreads();
             }

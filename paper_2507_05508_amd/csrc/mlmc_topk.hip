@@ -1532,6 +1532,10 @@ constexpr int WR_THREADS = 512;
 constexpr int WR_WAVES = WR_THREADS / 64;
 constexpr int WR_LINES = TILE / (WR_WAVES * 64);   // 64-element lines of a wave per step
 constexpr int WR_STAGE = 1024;   // entries of one step that are gathered in LDS and written densely
+#ifndef WR_DIRECT_N
+#define WR_DIRECT_N 1024
+#endif
+constexpr int WR_DIRECT = WR_DIRECT_N;   // steps with more entries write them straight from the lanes (at most WR_STAGE)
 
 template <int DT, bool VEC>
 __global__ __launch_bounds__(WR_THREADS, 4) void k_write(TopkArgs a) {
@@ -1572,8 +1576,8 @@ __global__ __launch_bounds__(WR_THREADS, 4) void k_write(TopkArgs a) {
     // One step = one tile of 4096 elements; a wave covers 512 consecutive elements as 8 lines of 64, one element
     // per lane and load, so that the order of the lanes is the order of the indices.  Membership is one wave-wide
     // mask per line, combined with scalar logic.  The step's entries are gathered in LDS (s_out[par]) and written
-    // densely: normally after the barrier of the next step, at once (window by window) when the step holds more
-    // than WR_STAGE entries.
+    // densely after the barrier of the next step; a step with more than WR_STAGE entries writes them straight
+    // from the lanes that hold them.
     uint32_t par = 0;
     uint32_t prev_first = 0, prev_count = 0;   // a finished step whose entries still wait in s_out[par ^ 1]
     // s_out holds {index, input bits}: the weight is applied here, once per entry
@@ -1618,26 +1622,37 @@ __global__ __launch_bounds__(WR_THREADS, 4) void k_write(TopkArgs a) {
             step_total += v;
         }
         if (tid == 0) a.tile_off[(size_t)row * (nt + 1) + sb / TILE] = run;
-        for (uint32_t wb = 0; wb < step_total; wb += (uint32_t)WR_STAGE) {
-            uint32_t pos0 = wave_pre - wb;   // may wrap: positions outside [0, WR_STAGE) are not in this window
+        if (step_total > (uint32_t)WR_DIRECT) {
+            // a dense step: every lane writes its own entry (emitting neighbours write neighbouring positions)
+            uint32_t pos0 = run + wave_pre;
 #pragma unroll
             for (int q = 0; q < WR_LINES; ++q) {
                 const uint64_t m = em[q];
                 if (m == 0) continue;   // uniform: nobody in the wave emits from this line
                 const uint32_t pos = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, pos0));
-                if (__builtin_amdgcn_inverse_ballot_w64(m) && pos < (uint32_t)WR_STAGE)
-                    s_out[par][pos] = make_uint2(jbase + (uint32_t)q * 64u, b[q]);
+                if (__builtin_amdgcn_inverse_ballot_w64(m)) {
+                    const uint32_t j = jbase + (uint32_t)q * 64u;
+                    const uint32_t key = key_of_bits(b[q]);
+                    const int64_t at = rowstart + pos;
+                    const bool base = (int32_t)key > tau[0] || (cut[0] && key == th.tau[0] && j < th.jx[0]);
+                    const float v = __uint_as_float(b[q]);
+                    if (at < a.capacity) { a.idx[at] = j; a.val[at] = base ? v : __fmul_rn(v, w); }
+                }
                 pos0 += (uint32_t)__popcll(m);
             }
-            if (step_total > (uint32_t)WR_STAGE) {   // a dense step: write this window now
-                __syncthreads();
-                const uint32_t cnt = step_total - wb < (uint32_t)WR_STAGE ? step_total - wb : (uint32_t)WR_STAGE;
-                write_out(par, run + wb, cnt);
-                __syncthreads();
+        } else {
+            uint32_t pos0 = wave_pre;
+#pragma unroll
+            for (int q = 0; q < WR_LINES; ++q) {
+                const uint64_t m = em[q];
+                if (m == 0) continue;   // uniform: nobody in the wave emits from this line
+                const uint32_t pos = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, pos0));
+                if (__builtin_amdgcn_inverse_ballot_w64(m)) s_out[par][pos] = make_uint2(jbase + (uint32_t)q * 64u, b[q]);
+                pos0 += (uint32_t)__popcll(m);
             }
         }
         prev_first = run;
-        prev_count = step_total > (uint32_t)WR_STAGE ? 0u : step_total;
+        prev_count = step_total > (uint32_t)WR_DIRECT ? 0u : step_total;
         run += step_total;
         par ^= 1u;
     };
