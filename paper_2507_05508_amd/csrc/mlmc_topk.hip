@@ -222,81 +222,105 @@ __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
         s_bot[t] = 0;
     }
     __syncthreads();
-    if (sum) {
-        for (int t = 0; t <= L; ++t) {
-            if (!s_active[t]) continue;
-#pragma unroll
-            for (int which = 0; which < 2; ++which) {
-                const int64_t r = which ? s_hi[t] : s_lo[t];
-                if (r <= (int64_t)before || r > (int64_t)before + sum) continue;   // not in this thread's 16 buckets
-                uint32_t run = before;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    if ((int64_t)run < r && r <= (int64_t)run + hv[i]) {
-                        if (which) s_bot[t] = (uint32_t)(NB1 - 1 - (tid * 16 + i));
-                        else s_top[t] = (uint32_t)(NB1 - 1 - (tid * 16 + i));
-                    }
-                    run += hv[i];
-                }
+    // The bucket that holds sample rank r (counted from the top): the highest bucket b with at least r sampled
+    // elements in buckets >= b.  One thread per (threshold, end of its zone), bisection over the scanned histogram;
+    // r = 0 keeps the highest bucket, r > ns the lowest.
+    if (tid < 2 * (L + 1) && s_active[tid >> 1]) {
+        const int t = tid >> 1, which = tid & 1;
+        const int64_t r = which ? s_hi[t] : s_lo[t];
+        if (r >= 1 && r <= ns) {
+            int lo = 0, hi = NB1 - 1;   // (elements in buckets >= lo) >= r holds throughout
+            while (lo < hi) {
+                const int mid = (lo + hi + 1) >> 1;
+                if ((int64_t)s_cum[mid] + s_h[mid] >= r) lo = mid;
+                else hi = mid - 1;
             }
+            if (which) s_bot[t] = (uint32_t)lo;
+            else s_top[t] = (uint32_t)lo;
         }
     }
     __syncthreads();
 
-    if (tid == 0) {
+    // Zones in descending key order, by the first wave: lane t holds what threshold t found, the uniform loop
+    // fetches it with readlane, lane 0 writes.  Overlapping zones are merged.
+    if (tid < 64) {
+        const int tl = tid <= L ? tid : 0;
+        const int my_act = s_active[tl];
+        const uint32_t my_top = s_top[tl], my_bot0 = s_bot[tl];
+        const uint32_t my_bot = my_bot0 < my_top ? my_bot0 : my_top;
         int nz = 0, lab = 0;
+        uint32_t ztop = 0, zbot = 0;   // the open zone nz - 1
         for (int t = 0; t <= L; ++t) {
-            if (!s_active[t]) {
-                ri->thr_zone[t] = THR_INACTIVE;
-                continue;
-            }
+            const int act = __builtin_amdgcn_readlane(my_act, t);
+            const uint32_t top = (uint32_t)__builtin_amdgcn_readlane((int)my_top, t);
+            const uint32_t bot = (uint32_t)__builtin_amdgcn_readlane((int)my_bot, t);
             const int64_t kt = a.k[t];
-            if (kt <= 0) {
-                ri->thr_zone[t] = THR_NONE;
-                ri->thr_tau[t] = 0xFFFFFFFFu;
-                ri->thr_jx[t] = 0;
+            int tz;
+            uint32_t tau = 0, jx = 0;
+            bool set_thr = false;
+            if (!act) {
+                tz = THR_INACTIVE;
+            } else if (kt <= 0) {
+                tz = THR_NONE;
+                tau = 0xFFFFFFFFu; jx = 0; set_thr = true;
                 lab = t + 1;
             } else if (kt >= a.d) {
-                ri->thr_zone[t] = THR_ALL;
-                ri->thr_tau[t] = 0;
-                ri->thr_jx[t] = JX_ALL;
+                tz = THR_ALL;
+                tau = 0; jx = JX_ALL; set_thr = true;
             } else {
-                const uint32_t top = s_top[t], bot = s_bot[t] < s_top[t] ? s_bot[t] : s_top[t];
-                if (nz > 0 && top >= s_zbot[nz - 1]) {   // overlaps the previous zone: one zone for both
-                    if (top > s_ztop[nz - 1]) s_ztop[nz - 1] = top;
-                    if (bot < s_zbot[nz - 1]) s_zbot[nz - 1] = bot;
-                    ri->zone_t1[nz - 1] = t;
+                if (nz > 0 && top >= zbot) {   // overlaps the previous zone: one zone for both
+                    if (top > ztop) ztop = top;
+                    if (bot < zbot) zbot = bot;
+                    if (tid == 0) ri->zone_t1[nz - 1] = t;
                 } else {
-                    s_ztop[nz] = top;
-                    s_zbot[nz] = bot;
-                    ri->zone_t0[nz] = t;
-                    ri->zone_t1[nz] = t;
-                    s_label[nz] = lab;
+                    ztop = top;
+                    zbot = bot;
+                    if (tid == 0) {
+                        ri->zone_t0[nz] = t;
+                        ri->zone_t1[nz] = t;
+                        s_label[nz] = lab;
+                    }
                     ++nz;
                 }
-                ri->thr_zone[t] = nz - 1;
+                if (tid == 0) { s_ztop[nz - 1] = ztop; s_zbot[nz - 1] = zbot; }
+                tz = nz - 1;
                 lab = t + 1;
             }
+            if (tid == 0) {
+                ri->thr_zone[t] = tz;
+                if (set_thr) { ri->thr_tau[t] = tau; ri->thr_jx[t] = jx; }
+            }
         }
-        s_label[nz] = lab;
-        // candidate list layout
+        if (tid == 0) s_label[nz] = lab;
+        wave_lds_sync();
+        // candidate list layout: lane z sizes zone z, then the offsets in order
         const uint64_t S = exact ? 1ull : (1ull << a.sample_shift);
+        uint32_t ltop = 0, lbot = 0;
+        uint64_t mycap = 0;
+        if (tid < nz) {
+            ltop = s_ztop[tid];
+            lbot = s_zbot[tid];
+            const uint64_t c = (uint64_t)s_cum[lbot] + s_h[lbot] - s_cum[ltop];
+            mycap = exact ? c : S * (c + (uint64_t)(8.0 * sqrt((double)c)) + 16);
+        }
         uint64_t off = 0;
         for (int z = 0; z < nz; ++z) {
-            const uint32_t top = s_ztop[z], bot = s_zbot[z];
-            const uint64_t c = (uint64_t)s_cum[bot] + s_h[bot] - s_cum[top];
-            uint64_t cap = c;
-            if (!exact) cap = S * (c + (uint64_t)(8.0 * sqrt((double)c)) + 16);
+            uint64_t cap = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(mycap >> 32), z) << 32) |
+                           (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)mycap, z);
             if (off + cap > (uint64_t)a.d) cap = (uint64_t)a.d - off;
-            ri->zone_top[z] = top;
-            ri->zone_bot[z] = bot;
-            ri->zone_off[z] = (uint32_t)off;
-            ri->zone_cap[z] = (uint32_t)cap;
+            if (tid == z) {
+                ri->zone_top[z] = ltop;
+                ri->zone_bot[z] = lbot;
+                ri->zone_off[z] = (uint32_t)off;
+                ri->zone_cap[z] = (uint32_t)cap;
+            }
             off += cap;
         }
-        for (int r = 0; r <= nz; ++r) ri->region_label[r] = s_label[r];
-        ri->n_zones = nz;
-        s_nz = nz;
+        if (tid <= nz) ri->region_label[tid] = s_label[tid];
+        if (tid == 0) {
+            ri->n_zones = nz;
+            s_nz = nz;
+        }
     }
     __syncthreads();
 
@@ -310,28 +334,18 @@ __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
         for (int l = tid; l < LMAX + 2; l += 1024) s_est[l] = 0.0f;
         if (tid <= L) s_kd[tid] = (double)a.k[tid];   // per-lane indexed below: keep it out of the argument block
         __syncthreads();
-        if (sum) {
+        {
+            // strided over the buckets, so that the occupied ones (a few hundred in a row) spread over the threads
             const double scale = (double)a.d / (double)(ns > 0 ? ns : 1);
-            int cur = -1, band = 0;
-            double acc = 0.0;
-            uint32_t run = before;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                if (hv[i]) {
-                    const uint32_t b = (uint32_t)(NB1 - 1 - (tid * 16 + i));
-                    const double rank = ((double)run + 0.5 * (double)hv[i]) * scale;
-                    while (band <= L && rank >= s_kd[band]) ++band;   // first t with rank < k_t (ranks only grow)
-                    const double v = (double)__uint_as_float((b << B1_SHIFT) | 0x10000u);
-                    if (band != cur) {
-                        if (cur >= 0 && acc > 0.0) atomicAdd(&s_est[cur], (float)acc);
-                        cur = band;
-                        acc = 0.0;
-                    }
-                    if ((b >> 6) < 255u) acc += (double)hv[i] * scale * v * v;
-                }
-                run += hv[i];
+            for (int b = tid; b < NB1; b += 1024) {
+                const uint32_t h = s_h[b];
+                if (h == 0 || (b >> 6) >= 255) continue;
+                const double rank = ((double)s_cum[b] + 0.5 * (double)h) * scale;
+                int band = 0;
+                while (band <= L && rank >= s_kd[band]) ++band;   // first t with rank < k_t
+                const double v = (double)__uint_as_float(((uint32_t)b << B1_SHIFT) | 0x10000u);
+                atomicAdd(&s_est[band], (float)((double)h * scale * v * v));   // fp32: a native LDS atomic, ample for a prediction
             }
-            if (cur >= 0 && acc > 0.0) atomicAdd(&s_est[cur], (float)acc);   // fp32: a native LDS atomic, ample for a prediction
         }
         __syncthreads();
         if (tid == 0) {
