@@ -1345,75 +1345,63 @@ struct BigAcc {
 
 __global__ __launch_bounds__(256) void k_norms(TopkArgs a) {
     __shared__ uint32_t s_big[TMAX][20];
-    __shared__ unsigned long long s_glo[GMAX], s_ghi[GMAX];
-    __shared__ uint16_t s_gexp[GMAX], s_gband[GMAX];
-    constexpr int NL_CAP = 96;
-    __shared__ Piece s_pc[PMAX];
+    __shared__ unsigned long long s_wide[TMAX][20];   // per 32-bit word position: sum of the addends' words, carries not yet propagated
     __shared__ double s_norm[LMAX];
-    __shared__ int32_t s_nlist[TMAX];
-    __shared__ uint16_t s_list[TMAX][NL_CAP];
     __shared__ double s_p[LMAX];
     const int row = blockIdx.x, tid = threadIdx.x;
     const RowInfo* ri = a.rinfo + row;
     const RowAcc* ra = a.racc + row;
-    for (int g = tid; g < GMAX; g += 256) {
-        s_glo[g] = ra->gsum[g][0];
-        s_ghi[g] = ra->gsum[g][1];
-        s_gexp[g] = ri->g_exp[g];
-        s_gband[g] = ri->g_band[g];
-    }
-    const int np = ra->n_pieces < (uint32_t)PMAX ? (int)ra->n_pieces : PMAX;
-    for (int p = tid; p < np; p += 256) s_pc[p] = ra->pieces[p];
-    if (tid < TMAX) s_nlist[tid] = 0;
+    for (int i = tid; i < TMAX * 20; i += 256) (&s_wide[0][0])[i] = 0ull;
     __syncthreads();
-    // the non-zero sums of every band, gathered so that a band's thread walks its own short list
+    // Every non-zero group or part sum goes to its band: v << shift is split into three 32-bit words that are added
+    // (LDS atomics, any order) to 64-bit counters of their word positions; a few hundred addends cannot overflow them.
+    auto add = [&](int band, uint64_t v, int shift) {
+        if (!v) return;
+        const int wi = shift >> 5, bs = shift & 31;
+        uint32_t parts[3];
+        parts[0] = (uint32_t)(v << bs);
+        parts[1] = (uint32_t)(bs ? v >> (32 - bs) : v >> 32);
+        parts[2] = bs ? (uint32_t)(v >> (64 - bs)) : 0u;
+#pragma unroll
+        for (int i = 0; i < 3; ++i)
+            if (parts[i] && wi + i < 20) atomicAdd(&s_wide[band][wi + i], (unsigned long long)parts[i]);
+    };
+    const int np = ra->n_pieces < (uint32_t)PMAX ? (int)ra->n_pieces : PMAX;
     for (int g = tid; g < GMAX + np; g += 256) {
-        int band;
-        bool nz;
-        if (g < GMAX) { band = s_gband[g]; nz = (s_glo[g] | s_ghi[g]) != 0; }
-        else { band = s_pc[g - GMAX].band_plus1 - 1; nz = (s_pc[g - GMAX].lo | s_pc[g - GMAX].hi) != 0; }
-        if (nz && band >= 1 && band <= a.L) {
-            const int at = atomicAdd(&s_nlist[band], 1);
-            if (at < NL_CAP) s_list[band][at] = (uint16_t)g;
+        int band, sh;
+        uint64_t lo, hi;
+        if (g < GMAX) {
+            band = ri->g_band[g];
+            sh = 2 * ((int)ri->g_exp[g] - 1);
+            lo = ra->gsum[g][0];
+            hi = ra->gsum[g][1];
+        } else {
+            const Piece pc = ra->pieces[g - GMAX];
+            band = pc.band_plus1 - 1;
+            sh = 2 * (pc.exp - 1);
+            lo = pc.lo;
+            hi = pc.hi;
+        }
+        if (band >= 1 && band <= a.L && sh >= 0) {
+            add(band, lo, sh);
+            add(band, hi, sh + 32);
         }
     }
     __syncthreads();
     const int l = tid;
     if (l >= 1 && l <= a.L) {
+        uint64_t wide[20];
+#pragma unroll
+        for (int i = 0; i < 20; ++i) wide[i] = s_wide[l][i];
+        uint64_t carry = 0;
+#pragma unroll
+        for (int i = 0; i < 20; ++i) {
+            const uint64_t t = wide[i] + carry;
+            s_big[l][i] = (uint32_t)t;
+            carry = t >> 32;
+        }
         BigAcc acc;
         acc.w = s_big[l];
-        acc.clear();
-        const int n = s_nlist[l];
-        if (n <= NL_CAP) {
-            for (int i = 0; i < n; ++i) {
-                const int g = s_list[l][i];
-                if (g < GMAX) {
-                    const int sh = 2 * ((int)s_gexp[g] - 1);
-                    acc.add(s_glo[g], sh);
-                    acc.add(s_ghi[g], sh + 32);
-                } else {
-                    const Piece& pc = s_pc[g - GMAX];
-                    const int sh = 2 * (pc.exp - 1);
-                    acc.add(pc.lo, sh);
-                    acc.add(pc.hi, sh + 32);
-                }
-            }
-        } else {   // more sums than the list holds: walk everything
-            for (int g = 0; g < GMAX; ++g) {
-                if (s_gband[g] == l && (s_glo[g] | s_ghi[g])) {
-                    const int sh = 2 * ((int)s_gexp[g] - 1);
-                    acc.add(s_glo[g], sh);
-                    acc.add(s_ghi[g], sh + 32);
-                }
-            }
-            for (int p = 0; p < np; ++p) {
-                if (s_pc[p].band_plus1 == l + 1) {
-                    const int sh = 2 * (s_pc[p].exp - 1);
-                    acc.add(s_pc[p].lo, sh);
-                    acc.add(s_pc[p].hi, sh + 32);
-                }
-            }
-        }
         double nrm = __dsqrt_rn(acc.to_double());
         s_norm[l - 1] = nrm;
         a.norms[(size_t)row * a.L + (l - 1)] = nrm;
