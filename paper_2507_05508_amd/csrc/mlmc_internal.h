@@ -24,7 +24,7 @@ constexpr int CHUNKS_MAX = 8192;        // chunks per row
 constexpr int FH_BINS = 2048;           // bins of the zone-relative key histogram of the finish kernels
 constexpr int COLLECT_CAP = 2048;       // candidates of the thresholds' bins that are ranked in LDS
 constexpr int FIN_SLICES = 16;          // a zone's candidate list is worked on in up to this many slices ...
-constexpr int FIN_SLICE = 16384;        // ... of at least this many candidates
+constexpr int FIN_SLICE = 32768;        // ... of at least this many candidates
 constexpr int FIN_WGS = 32;             // workgroups per row that take the (zone, slice) items in turn
 // Slot of a part of a zone in the per-chunk table of zone entries: the part inside the top k_t but outside the
 // top k of the zone's previous threshold has slot t; the part below every threshold of zone z has slot TMAX + z.

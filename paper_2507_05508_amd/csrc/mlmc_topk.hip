@@ -1461,16 +1461,21 @@ constexpr int MP_THREADS = 256;
 __global__ __launch_bounds__(MP_THREADS) void k_msgplan(TopkArgs a) {
     __shared__ uint32_t s_scan[MP_THREADS / 64 + 1];
     __shared__ uint32_t s_carry;
+    __shared__ int64_t s_k[TMAX];   // the ladder, indexed per lane below
     const int row = blockIdx.x, tid = threadIdx.x;
+    if (tid < TMAX) s_k[tid] = tid <= a.L ? a.k[tid] : 0;
     RowInfo* ri = a.rinfo + row;
     const int lev = ri->level;
     const int nzn = ri->n_zones;
     const int nc = a.cchunks_per_row;   // count chunks
-    int r0 = -1, rl = -1;
-    for (int r = 0; r <= nzn; ++r) {
-        const int lab = ri->region_label[r];
-        if (lab == 0) r0 = r;
-        if (lab == lev) rl = r;
+    // the regions of band 0 and of band l (the last one with that label): lane r looks at region r
+    int r0, rl;
+    {
+        const uint32_t lane = lane_id();
+        const int lab = (int)lane <= nzn ? ri->region_label[lane] : -1;
+        const uint64_t m0 = __ballot(lab == 0), ml = __ballot(lab == lev);
+        r0 = m0 ? 63 - __builtin_clzll(m0) : -1;
+        rl = ml ? 63 - __builtin_clzll(ml) : -1;
     }
     int zs[3] = {-1, -1, -1};
     {
@@ -1502,12 +1507,20 @@ __global__ __launch_bounds__(MP_THREADS) void k_msgplan(TopkArgs a) {
         if (tid == 0) s_carry = carry + total;
         __syncthreads();
     }
-    if (tid == 0) {
-        int64_t start = 0;
-        for (int i = 0; i < row; ++i) {
+    // the messages of the rows before this one: lanes of the first wave take rows in turn
+    int64_t start = 0;
+    if (tid < 64) {
+        for (int i = tid; i < row; i += 64) {
             const int li = a.rinfo[i].level;
-            start += a.k[0] + a.k[li] - a.k[li - 1];
+            start += a.k[0] + s_k[li] - s_k[li - 1];
         }
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) {
+            const uint32_t lo = __shfl_xor((uint32_t)start, o, 64), hi = __shfl_xor((uint32_t)((uint64_t)start >> 32), o, 64);
+            start += (int64_t)(((uint64_t)hi << 32) | lo);
+        }
+    }
+    if (tid == 0) {
         const int64_t nnz = a.k[0] + a.k[lev] - a.k[lev - 1];
         cbase[nc] = s_carry;
         if ((int64_t)s_carry != nnz) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
