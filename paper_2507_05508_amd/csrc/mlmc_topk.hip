@@ -1740,6 +1740,17 @@ __global__ __launch_bounds__(FL_THREADS) void k_filter(TopkArgs a) {
     const int64_t c0 = (int64_t)chunk_id * a.chunk;
     const int64_t c1 = c0 + a.chunk < a.d ? c0 + a.chunk : a.d;
     const int nwords = (int)((c1 - c0 + 31) / 32);
+    // wave w of this workgroup reads the private list of wave w of the selection read
+    const uint2* priv = a.cand_priv + ((size_t)row * nc + chunk_id) * (size_t)a.chunk + (size_t)wave * (a.chunk / 16);
+    const uint32_t cnt = a.priv_cnt[((size_t)row * nc + chunk_id) * 16 + wave];
+    // The first FL_KEEP entries of every lane stay in registers for the second pass (a wave's list rarely holds
+    // more than 64 * FL_KEEP).  They are loaded without waiting for the list's length: the list's memory is there
+    // whatever it holds, and what lies past the end is ignored.
+    constexpr int FL_KEEP = 8;
+    uint2 ent[FL_KEEP];
+#pragma unroll
+    for (int u = 0; u < FL_KEEP; ++u) ent[u] = priv[lane + 64u * (uint32_t)u];
+    static_assert(64 * FL_KEEP <= 4 * TILE / MAIN_WAVES, "a wave's list has room for at least chunk / 16 >= 1024 entries");
     for (int i = tid; i < nwords; i += FL_THREADS) s_bits[i] = 0;
     const MsgPlan mp = ri->msg;
     const int64_t rowstart = mp.rowstart;
@@ -1756,14 +1767,17 @@ __global__ __launch_bounds__(FL_THREADS) void k_filter(TopkArgs a) {
         in0 = inside_top(th, 0, key, j);
         return in0 || (inside_top(th, 2, key, j) && !inside_top(th, 1, key, j));
     };
-    // wave w of this workgroup reads the private list of wave w of the selection read
-    const uint2* priv = a.cand_priv + ((size_t)row * nc + chunk_id) * (size_t)a.chunk + (size_t)wave * (a.chunk / 16);
-    const uint32_t cnt = a.priv_cnt[((size_t)row * nc + chunk_id) * 16 + wave];
-    batched_loop<8, 64>(0u, cnt, lane, [&](uint32_t i) { return priv[i]; }, [&](uint32_t, uint2 e) {
+    auto mark = [&](uint2 e) {
         const uint32_t rel = e.y >> 6;
         bool in0;
         if (member(key_of_bits(e.x), (uint32_t)c0 + rel, in0)) atomicOr(&s_bits[rel >> 5], 1u << (rel & 31u));
-    });
+    };
+    if (cnt) {
+#pragma unroll
+        for (int u = 0; u < FL_KEEP; ++u)
+            if (lane + 64u * (uint32_t)u < cnt) mark(ent[u]);
+    }
+    batched_loop<8, 64>(64u * FL_KEEP, cnt, lane, [&](uint32_t i) { return priv[i]; }, [&](uint32_t, uint2 e) { mark(e); });
     __syncthreads();
     // exclusive prefix of the word popcounts
     {
@@ -1782,7 +1796,7 @@ __global__ __launch_bounds__(FL_THREADS) void k_filter(TopkArgs a) {
     __syncthreads();
     for (int64_t t = c0 / TILE + tid; t * TILE < c1; t += FL_THREADS)
         a.tile_off[(size_t)row * (nt + 1) + t] = base + s_pre[(t * TILE - c0) >> 5];
-    batched_loop<8, 64>(0u, cnt, lane, [&](uint32_t i) { return priv[i]; }, [&](uint32_t, uint2 e) {
+    auto emit = [&](uint2 e) {
         const uint32_t rel = e.y >> 6, j = (uint32_t)c0 + rel;
         bool in0;
         if (member(key_of_bits(e.x), j, in0)) {
@@ -1792,7 +1806,13 @@ __global__ __launch_bounds__(FL_THREADS) void k_filter(TopkArgs a) {
             const float v = __uint_as_float(e.x);
             if (at < a.capacity) { a.idx[at] = j; a.val[at] = in0 ? v : __fmul_rn(v, w); }
         }
-    });
+    };
+    if (cnt) {
+#pragma unroll
+        for (int u = 0; u < FL_KEEP; ++u)
+            if (lane + 64u * (uint32_t)u < cnt) emit(ent[u]);
+    }
+    batched_loop<8, 64>(64u * FL_KEEP, cnt, lane, [&](uint32_t i) { return priv[i]; }, [&](uint32_t, uint2 e) { emit(e); });
 }
 
 // ---------------------------------------------------------------------------------------------------
