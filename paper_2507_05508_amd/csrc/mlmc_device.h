@@ -170,6 +170,25 @@ struct RowLoader {
             }
         }
     }
+    // load4_full for a row that is streamed through once: a non-temporal load, so that the row does not push
+    // what the kernel writes and reads back soon after (its staged lists) out of the L2
+    __device__ __forceinline__ void load4_stream(int64_t j, uint32_t (&b)[4]) const {
+        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+        typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+        if (DT == MLMC_F32 && VEC) {
+            const u32x4 v = __builtin_nontemporal_load((const u32x4*)((const uint32_t*)row + j));
+            b[0] = v.x; b[1] = v.y; b[2] = v.z; b[3] = v.w;
+        } else if (DT != MLMC_F32 && VEC) {
+            const u32x2 v = __builtin_nontemporal_load((const u32x2*)((const uint16_t*)row + j));
+            b[0] = v.x << 16; b[1] = v.x & 0xFFFF0000u; b[2] = v.y << 16; b[3] = v.y & 0xFFFF0000u;
+        } else {
+            load4_full(j, b);
+        }
+    }
+    __device__ __forceinline__ uint32_t load1_stream(int64_t j) const {
+        if (DT == MLMC_F32) return __builtin_nontemporal_load((const uint32_t*)row + j);
+        return (uint32_t)__builtin_nontemporal_load((const uint16_t*)row + j) << 16;
+    }
     __device__ __forceinline__ uint32_t load1(int64_t j) const {
         if (DT == MLMC_F32) return ((const uint32_t*)row)[j];
         return (uint32_t)((const uint16_t*)row)[j] << 16;

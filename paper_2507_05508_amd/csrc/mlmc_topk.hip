@@ -507,7 +507,7 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
     const int span = (int)(c1 - c0);
     const int woff = (int)wave * 256;
     const int nfull = span >= woff + 256 ? (span - woff - 256) / 4096 + 1 : 0;   // loads with all 256 elements
-    auto issue = [&](int n, uint32_t (&b)[4]) { ld.load4_full(c0 + (int64_t)((n * 16 + (int)wave) * 256) + (int64_t)lane * 4, b); };
+    auto issue = [&](int n, uint32_t (&b)[4]) { ld.load4_stream(c0 + (int64_t)((n * 16 + (int)wave) * 256) + (int64_t)lane * 4, b); };
     auto rel_of = [&](int n) -> uint32_t { return (uint32_t)((n * 16 + (int)wave) * 256) + lane * 4; };
     // load round n covers tile n of the chunk: its counters are those of the count chunk the tile lies in
     const int tpc = a.cchunk / TILE;   // tiles per count chunk
@@ -1682,7 +1682,7 @@ __global__ __launch_bounds__(WR_THREADS, 4) void k_write(TopkArgs a) {
     auto issue = [&](int64_t s2, uint32_t (&b)[WR_LINES]) {
         const int64_t j = c0 + s2 * TILE + (int64_t)wave * (64 * WR_LINES) + lane;
 #pragma unroll
-        for (int q = 0; q < WR_LINES; ++q) b[q] = ld.load1(j + q * 64);
+        for (int q = 0; q < WR_LINES; ++q) b[q] = ld.load1_stream(j + q * 64);
     };
     uint32_t buf[2][WR_LINES];
     int64_t s2 = 0;
