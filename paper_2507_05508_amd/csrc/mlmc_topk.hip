@@ -690,6 +690,33 @@ __device__ __forceinline__ int finish_items(const RowInfo* ri, const RowAcc* ra,
     return s_first[nz];
 }
 
+// Ranking by counting in LDS for a workgroup of FN_THREADS threads and n <= 2 * FN_THREADS distinct values v[0..n)
+// (16-byte aligned): r0 / r1 = how many values are greater than v[t] / v[t + FN_THREADS].  Every thread walks the
+// whole list once for both of its values, two list entries per (broadcast) LDS read.
+__device__ __forceinline__ void count_greater2(const unsigned long long* v, uint32_t n, uint32_t t, uint32_t& r0, uint32_t& r1) {
+    const unsigned long long c0 = t < n ? v[t] : ~0ull;
+    const unsigned long long c1 = t + (uint32_t)FN_THREADS < n ? v[t + (uint32_t)FN_THREADS] : ~0ull;
+    r0 = 0;
+    r1 = 0;
+    const ulonglong2* v2 = (const ulonglong2*)v;
+    const uint32_t n2 = n >> 1;
+    if (t >= n) return;   // waves past the end of the list do not load the LDS pipe
+    if (n <= (uint32_t)FN_THREADS) {   // uniform: one value per thread
+        for (uint32_t f = 0; f < n; ++f) r0 += v[f] > c0 ? 1u : 0u;
+        return;
+    }
+    for (uint32_t f = 0; f < n2; ++f) {
+        const ulonglong2 x = v2[f];
+        r0 += (x.x > c0 ? 1u : 0u) + (x.y > c0 ? 1u : 0u);
+        r1 += (x.x > c1 ? 1u : 0u) + (x.y > c1 ? 1u : 0u);
+    }
+    if (n & 1u) {
+        const unsigned long long x = v[n - 1u];
+        r0 += x > c0 ? 1u : 0u;
+        r1 += x > c1 ? 1u : 0u;
+    }
+}
+
 // Read 1 of a candidate list, one item per (zone, slice): histogram of (key - kmin) >> shift.
 __global__ __launch_bounds__(FN_THREADS) void k_fhist(TopkArgs a, int exact_pass) {
     __shared__ uint32_t s_fh[FH_BINS];
@@ -743,7 +770,7 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
     constexpr int UN_WORDS = PHASE == 0 ? COLLECT_CAP * 2 : TMAX * 256;
     constexpr int ZC = PHASE == 0 ? ZC0_CAP : ZC_CAP;
     constexpr int PREP = PHASE == 0 ? 8 : REP;   // lane replicas of the part sum accumulators
-    __shared__ uint32_t s_un[UN_WORDS];   // slow path: digit histograms; else: candidates of the threshold bins
+    __shared__ __align__(16) uint32_t s_un[UN_WORDS];   // slow path: digit histograms; else: candidates of the threshold bins
     __shared__ uint32_t s_fh[FH_BINS];
     __shared__ uint8_t s_bincls[FH_BINS];
     __shared__ uint32_t s_zc[ZC];
@@ -1009,11 +1036,11 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
         }
         __syncthreads();
         // descending order of (key, lower index first) by counting: composites are distinct
-        for (uint32_t e = tid; e < ncol; e += FN_THREADS) {
-            const unsigned long long c = s_col[e];
-            uint32_t r = 0;
-            for (uint32_t f = 0; f < ncol; ++f) r += s_col[f] > c ? 1u : 0u;
-            s_srt[r] = c;
+        {
+            uint32_t r0, r1;
+            count_greater2(s_col, ncol, (uint32_t)tid, r0, r1);
+            if ((uint32_t)tid < ncol) s_srt[r0] = s_col[tid];
+            if ((uint32_t)tid + FN_THREADS < ncol) s_srt[r1] = s_col[tid + FN_THREADS];
         }
         __syncthreads();
         if (tid < nthr) {
@@ -1054,10 +1081,15 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
             for (int i = tid; i < FH_BINS; i += FN_THREADS) s_fh[i] = 0;
             if (tid == 0) { s_q[0] = 0xFFFFFFFFu; s_eq[0] = 0u; s_ncollect = 0; }
             __syncthreads();
-            batched_loop<8, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return xb[i]; }, [&](uint32_t, uint32_t bits) {
-                const uint32_t key = key_of_bits(bits);
-                if (key < s_q[0]) atomicMin(&s_q[0], key);   // s_q / s_eq: smallest / largest key (checked first: mostly no atomic)
+            // one pass for both: smallest / largest key (checked first: mostly no atomic) and, for the case that they
+            // agree, the histogram of the indices.  One workgroup walks the list: many loads per thread in flight.
+            int ish = 0;
+            while (((uint32_t)(a.d - 1) >> ish) >= (uint32_t)FH_BINS) ++ish;
+            batched_loop<16, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return make_uint2(xb[i], xj[i]); }, [&](uint32_t, uint2 e) {
+                const uint32_t key = key_of_bits(e.x);
+                if (key < s_q[0]) atomicMin(&s_q[0], key);
                 if (key > s_eq[0]) atomicMax(&s_eq[0], key);
+                atomicAdd(&s_fh[e.y >> ish], 1u);
             });
             __syncthreads();
             const uint32_t key1 = s_q[0];
@@ -1065,12 +1097,7 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
             __syncthreads();
             if (single) {
                 const uint32_t q = s_res[0];   // the threshold is the q-th entry of the list by ascending index
-                int ish = 0;
-                while (((uint32_t)(a.d - 1) >> ish) >= (uint32_t)FH_BINS) ++ish;
                 if (q < xn) {
-                    batched_loop<8, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return xj[i]; },
-                                                [&](uint32_t, uint32_t j) { atomicAdd(&s_fh[j >> ish], 1u); });
-                    __syncthreads();
                     if (wave == 0) {
                         int bin;
                         uint32_t rin, cnt;
@@ -1080,7 +1107,7 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
                     __syncthreads();
                     if (s_bcnt[0] <= (uint32_t)COLLECT_CAP && s_bcnt[0] > 0) {
                         const uint32_t ibin = s_bin[0];
-                        batched_loop<8, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return xj[i]; }, [&](uint32_t, uint32_t j) {
+                        batched_loop<32, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return xj[i]; }, [&](uint32_t, uint32_t j) {
                             if ((j >> ish) == ibin) {
                                 const uint32_t at = atomicAdd(&s_ncollect, 1u);
                                 if (at < (uint32_t)COLLECT_CAP) s_col[at] = j;
@@ -1088,11 +1115,11 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
                         });
                         __syncthreads();
                         const uint32_t nc2 = s_ncollect < (uint32_t)COLLECT_CAP ? s_ncollect : (uint32_t)COLLECT_CAP;
-                        for (uint32_t e = tid; e < nc2; e += FN_THREADS) {
-                            const uint32_t j = (uint32_t)s_col[e];
-                            uint32_t above = 0;
-                            for (uint32_t f = 0; f < nc2; ++f) above += (uint32_t)s_col[f] > j ? 1u : 0u;
-                            if (above + 1u == s_rin[0]) { s_tau[0] = key1; s_jx[0] = j + 1u; s_any = 1; }
+                        {   // the entries are indices (distinct), held in 64-bit slots
+                            uint32_t r0, r1;
+                            count_greater2(s_col, nc2, (uint32_t)tid, r0, r1);
+                            if ((uint32_t)tid < nc2 && r0 + 1u == s_rin[0]) { s_tau[0] = key1; s_jx[0] = (uint32_t)s_col[tid] + 1u; s_any = 1; }
+                            if ((uint32_t)tid + FN_THREADS < nc2 && r1 + 1u == s_rin[0]) { s_tau[0] = key1; s_jx[0] = (uint32_t)s_col[tid + FN_THREADS] + 1u; s_any = 1; }
                         }
                     }
                 } else if (tid == 0) {   // every entry of the list is inside
