@@ -1078,7 +1078,10 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
         if (tid == 0) { s_any = 0; s_nsub = 0; }
         __syncthreads();
         if (par_big && nthr == 1) {
-            for (int i = tid; i < FH_BINS; i += FN_THREADS) s_fh[i] = 0;
+            // the index histogram in four lane-interleaved copies (in s_un, free until the gather below): neighbours in
+            // the list have neighbouring indices, and 64 lanes adding to one LDS word take 64 turns
+            static_assert(UN_WORDS >= 4 * FH_BINS, "room for the histogram copies");
+            for (int i = tid; i < 4 * FH_BINS; i += FN_THREADS) s_un[i] = 0;
             if (tid == 0) { s_q[0] = 0xFFFFFFFFu; s_eq[0] = 0u; s_ncollect = 0; }
             __syncthreads();
             // one pass for both: smallest / largest key (checked first: mostly no atomic) and, for the case that they
@@ -1089,9 +1092,10 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
                 const uint32_t key = key_of_bits(e.x);
                 if (key < s_q[0]) atomicMin(&s_q[0], key);
                 if (key > s_eq[0]) atomicMax(&s_eq[0], key);
-                atomicAdd(&s_fh[e.y >> ish], 1u);
+                atomicAdd(&s_un[((e.y >> ish) << 2) | (lane & 3u)], 1u);
             });
             __syncthreads();
+            for (int i = tid; i < FH_BINS; i += FN_THREADS) s_fh[i] = s_un[4 * i] + s_un[4 * i + 1] + s_un[4 * i + 2] + s_un[4 * i + 3];
             const uint32_t key1 = s_q[0];
             const bool single = key1 == s_eq[0];
             __syncthreads();
