@@ -105,6 +105,7 @@ static void fill_topk_args(const mlmc_plan_t* pl, TopkArgs& a, const void* g, in
     a.cand_priv = (uint2*)(w + pl->off_cand_priv);
     a.priv_cnt = (uint32_t*)(w + pl->off_priv_cnt);
     a.chunk_base = (uint32_t*)(w + pl->off_chunk_base);
+    a.row_order = (int32_t*)(w + pl->off_row_order);
     a.dev_status = dev_status;
 }
 
@@ -274,6 +275,8 @@ mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dty
         off = align_up(off + sizeof(uint32_t) * 16 * (size_t)pl->chunks_per_row * M, 256);
         pl->off_chunk_base = off;
         off = align_up(off + sizeof(uint32_t) * (size_t)(pl->cchunks_per_row + 1) * M, 256);
+        pl->off_row_order = off;
+        off = align_up(off + sizeof(int32_t) * (size_t)M, 256);
     }
     pl->ws_bytes = off;
     if (workspace_bytes) *workspace_bytes = off;

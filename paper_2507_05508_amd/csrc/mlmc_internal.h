@@ -122,6 +122,7 @@ struct TopkArgs {
     uint2* cand_priv;        // [M][chunks_per_row][chunk] staged {bits, offset in chunk << 6 | tag} as the waves met them
     uint32_t* priv_cnt;      // [M][chunks_per_row][16] entries of every wave's private list
     uint32_t* chunk_base;    // [M][cchunks_per_row + 1] message entries of the row before every count chunk
+    int32_t* row_order;      // [M] rows by descending message length: the order in which the message kernels take them
     uint32_t* chunk_cnt;     // [M][cchunks_per_row][RMAX] elements of every region per count chunk
     uint32_t* chunk_zcnt;    // [M][cchunks_per_row][ZPMAX] candidates of every part of every zone per count chunk (zeroed per call)
     uint32_t* zhist;         // [M][ZMAX][FH_BINS] zone-relative key histograms (zeroed per call)
@@ -204,6 +205,6 @@ struct mlmc_plan_s {
     int staging;
     // workspace byte offsets
     size_t off_racc, off_hist, off_hist2, off_chunk_zcnt, off_zhist, off_zpacc, zero_bytes;  // [0, zero_bytes) is cleared per call
-    size_t off_rinfo, off_table, off_chunk_cnt, off_zcol, off_tileoff, off_norms, off_cand_bits, off_cand_idx, off_cand2_bits, off_cand2_idx, off_cand_priv, off_priv_cnt, off_chunk_base;
+    size_t off_rinfo, off_table, off_chunk_cnt, off_zcol, off_tileoff, off_norms, off_cand_bits, off_cand_idx, off_cand2_bits, off_cand2_idx, off_cand_priv, off_priv_cnt, off_chunk_base, off_row_order;
     size_t ws_bytes;
 };

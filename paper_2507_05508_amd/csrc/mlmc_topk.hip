@@ -131,7 +131,7 @@ __device__ void draw_row(const TopkArgs& a, int row, const double* norms_row, do
 constexpr double ZONE_SIGMAS = 8.0;
 constexpr double ZONE_SIGMAS_BIG = 5.0;         // samples of at least ZONE_BIG_SAMPLE elements
 constexpr int64_t ZONE_BIG_SAMPLE = 1 << 20;
-constexpr int64_t STAGE_MAX_BAND_INV = 16;   // bands wider than d / 16 are not staged
+constexpr int64_t STAGE_MAX_BAND_INV = 8;   // bands wider than d / 8 are not staged
 
 __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
     __shared__ uint32_t s_h[NB1];
@@ -1538,18 +1538,26 @@ __global__ __launch_bounds__(MP_THREADS) void k_msgplan(TopkArgs a) {
         if (tid == 0) s_carry = carry + total;
         __syncthreads();
     }
-    // the messages of the rows before this one: lanes of the first wave take rows in turn
+    // The messages of the rows before this one, and this row's place among all rows by descending message length
+    // (the message kernels take the rows in that order, so that the long ones are not left for the end): lanes
+    // of the first wave take rows in turn.
     int64_t start = 0;
     if (tid < 64) {
-        for (int i = tid; i < row; i += 64) {
+        const int64_t mine = a.k[0] + s_k[lev] - s_k[lev - 1];
+        uint32_t ahead = 0;
+        for (int i = tid; i < a.M; i += 64) {
             const int li = a.rinfo[i].level;
-            start += a.k[0] + s_k[li] - s_k[li - 1];
+            const int64_t ni = a.k[0] + s_k[li] - s_k[li - 1];
+            if (i < row) start += ni;
+            ahead += (ni > mine || (ni == mine && i < row)) ? 1u : 0u;
         }
+        ahead = wave_sum(ahead);
 #pragma unroll
         for (int o = 32; o >= 1; o >>= 1) {
             const uint32_t lo = __shfl_xor((uint32_t)start, o, 64), hi = __shfl_xor((uint32_t)((uint64_t)start >> 32), o, 64);
             start += (int64_t)(((uint64_t)hi << 32) | lo);
         }
+        if (tid == 0) a.row_order[ahead] = row;
     }
     if (tid == 0) {
         const int64_t nnz = a.k[0] + a.k[lev] - a.k[lev - 1];
@@ -1587,7 +1595,7 @@ template <int DT, bool VEC>
 __global__ __launch_bounds__(WR_THREADS, 4) void k_write(TopkArgs a) {
     __shared__ uint32_t s_wemit[2][WR_WAVES];
     __shared__ uint2 s_out[2][WR_STAGE];
-    const int row = blockIdx.y, chunk_id = blockIdx.x, tid = threadIdx.x;
+    const int row = a.row_order[blockIdx.y], chunk_id = blockIdx.x, tid = threadIdx.x;
     const uint32_t lane = lane_id(), wave = (uint32_t)__builtin_amdgcn_readfirstlane(tid >> 6);
     const RowInfo* ri = a.rinfo + row;
     if (ri->spec_ok) return;   // the message of this row comes from the staged lists (k_filter)
@@ -1762,7 +1770,7 @@ __global__ __launch_bounds__(FL_THREADS) void k_filter(TopkArgs a) {
     uint32_t* s_bits = s_dyn;               // bit rel: element c0 + rel is in the message
     uint32_t* s_pre = s_dyn + a.chunk / 32; // members in the words before
     __shared__ uint32_t s_scan[FL_THREADS / 64 + 1];
-    const int row = blockIdx.y, chunk_id = blockIdx.x, tid = threadIdx.x;
+    const int row = a.row_order[blockIdx.y], chunk_id = blockIdx.x, tid = threadIdx.x;
     const uint32_t lane = lane_id(), wave = (uint32_t)__builtin_amdgcn_readfirstlane(tid >> 6);
     const RowInfo* ri = a.rinfo + row;
     if (!ri->spec_ok) return;   // k_write reads the row again
