@@ -103,7 +103,7 @@ __device__ __forceinline__ void bits_extract_row(const BitsArgs& a, int row, con
             for (int i0 = 0; i0 < 64; i0 += 16) {
                 uint32_t v[16];
 #pragma unroll
-                for (int u = 0; u < 16; ++u) v[u] = ld.load1(base + (i0 + u) * 64 + lane);
+                for (int u = 0; u < 16; ++u) v[u] = ld.load1_stream(base + (i0 + u) * 64 + lane);
 #pragma unroll
                 for (int u = 0; u < 16; ++u) pack(i0 + u, digits(v[u]));
             }
