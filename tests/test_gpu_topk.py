@@ -250,6 +250,28 @@ def test_many_levels_many_rows():
                 assert np.array_equal(out.cpu().numpy().view(np.uint32), O.aggregate_sparse(want, d, 1.0 / M).view(np.uint32))
 
 
+@pytest.mark.parametrize("M", [70, 300])
+def test_more_rows_than_a_wave_or_a_workgroup(M):
+    """Row counts beyond 64 and beyond 256: the per-row loops that lanes or threads share (message starts, the order in
+    which the message kernels take the rows, the aggregate's row table) wrap around."""
+    rng = np.random.default_rng(M)
+    d = 16384 + 77
+    G = (rng.standard_normal((M, d)) * np.exp(rng.uniform(-3, 3, size=(M, 1)))).astype(np.float32)
+    ladder = [5, 40, 300, 2000, d // 2, d]
+    L = len(ladder) - 1
+    g = to_device(G)
+    for pf in (None, O.geometric_p(L)):
+        plan = P.Plan(P.MLMC_TOPK, M, d, P.MLMC_F32, ladder, pf)
+        for step in range(2):
+            print(f"rows M={M} adaptive={pf is None} step={step}", flush=True)
+            msg = P.mlmc_compress_topk(plan, g, seed=11, step=step)
+            want = check_topk_against_oracle(plan, G, 11, step, msg, adaptive=pf is None)
+            assert plan.status() == 0
+            out = P.mlmc_aggregate(plan, msg, 1.0 / M)
+            torch.cuda.synchronize()
+            assert np.array_equal(out.cpu().numpy().view(np.uint32), O.aggregate_sparse(want, d, 1.0 / M).view(np.uint32))
+
+
 def test_identity_ladder_is_dense_mean():
     """L = 1, k_0 = 0, k_1 = d, p = 1: the message is the gradient and the aggregate is Alg. 1's mean."""
     rng = np.random.default_rng(0)
