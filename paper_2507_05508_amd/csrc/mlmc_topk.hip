@@ -557,22 +557,56 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
         process(buf[0], cc, rel_of(nfull), (1u << nv) - 1u, cnt_of(nfull));
     }
     if (__ballot(maxkey >= 0x7F800000u) && lane == 0) atomicOr(a.dev_status, MLMC_DEV_NONFINITE);
-    __threadfence_block();
-    __syncthreads();
 
-    // ---- the workgroup's candidates move from the private lists to the zones' lists: one reservation per zone ----
+    // ---- the workgroup's candidates move from the private lists to the zones' lists: one reservation per zone.
+    //      The wave's list comes back from memory while the reservations are made and the sums and counts, which
+    //      need nothing from it, go out. ----
+    constexpr int EP_KEEP = 16;
+    uint2 ent[EP_KEEP];
+    __threadfence_block();   // the wave reads back what it stored
+    if (head) {   // uniform
+#pragma unroll
+        for (int u = 0; u < EP_KEEP; ++u) {
+            const uint32_t i = lane + 64u * (uint32_t)u;
+            ent[u] = priv[i < head ? i : head - 1u];
+        }
+    }
+    if (lane == 0) a.priv_cnt[((size_t)row * a.chunks_per_row + blockIdx.x) * MAIN_WAVES + wave] = head;
+    __syncthreads();
     if (tid < nz) {
         uint32_t total = 0;
         for (int r = 0; r < CSUB_MAX * REP_CNT; ++r)
             total += s_cnt[(r / REP_CNT) * (128 * REP_CNT) + (64 + tid) * REP_CNT + ((r + tid) & (REP_CNT - 1))];
         s_zcur[tid] = total ? atomicAdd(&ra->zone_fill[tid], total) : 0u;
     }
+    if (SUMS && tid >= 64) {   // the waves after the first: the first is waiting for its reservations
+        const unsigned long long* s_sum = (const unsigned long long*)(lm + LM_SUM);
+        for (int g = tid - 64; g < G_DUMMY; g += MAIN_THREADS - 64) {
+            unsigned long long lo = 0, hi = 0;
+#pragma unroll
+            for (int r = 0; r < REP_SUM; ++r) {
+                const unsigned long long v = s_sum[g * REP_SUM + ((r + tid) & (REP_SUM - 1))];
+                lo += v & 0xFFFFFFFFull;
+                hi += v >> 32;
+            }
+            if (lo) atomicAdd((unsigned long long*)&ra->gsum[g][0], lo);
+            if (hi) atomicAdd((unsigned long long*)&ra->gsum[g][1], hi);
+        }
+    }
+    if (tid >= MAIN_THREADS - RMAX * CSUB_MAX) {   // per count chunk: the counters of region t % RMAX (the last waves)
+        const int t = tid - (MAIN_THREADS - RMAX * CSUB_MAX);
+        const int r = t % RMAX, sub = t / RMAX;
+        uint32_t cnt = 0;
+        for (int k = 0; k < REP_CNT; ++k) cnt += s_cnt[sub * (128 * REP_CNT) + r * REP_CNT + ((k + t) & (REP_CNT - 1))];
+        const int64_t cc = (int64_t)blockIdx.x * a.csub + sub;
+        if (sub < a.csub && cc < a.cchunks_per_row) a.chunk_cnt[((size_t)row * a.cchunks_per_row + cc) * RMAX + r] = cnt;
+        if (cnt) atomicAdd(&ra->region_cnt[r], cnt);
+    }
     __syncthreads();
     uint32_t* cb = a.cand_bits + (size_t)row * (size_t)a.d;
     uint32_t* ci = a.cand_idx + (size_t)row * (size_t)a.d;
     bool dropped = false;
-    if (lane == 0) a.priv_cnt[((size_t)row * a.chunks_per_row + blockIdx.x) * MAIN_WAVES + wave] = head;
-    batched_loop<16, 64>(0u, head, lane, [&](uint32_t i) { return priv[i]; }, [&](uint32_t, uint2 e) {
+    auto move = [&](uint2 e) {
         const uint32_t z = e.y & 63u, key = key_of_bits(e.x);
         if (z == TAG_MEMBER) return;   // staged for the message only
         const uint32_t pos = atomicAdd(&s_zcur[z], 1u);
@@ -585,7 +619,13 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
         } else {
             dropped = true;
         }
-    });
+    };
+    if (head) {
+#pragma unroll
+        for (int u = 0; u < EP_KEEP; ++u)
+            if (lane + 64u * (uint32_t)u < head) move(ent[u]);
+    }
+    batched_loop<16, 64>(64u * EP_KEEP, head, lane, [&](uint32_t i) { return priv[i]; }, [&](uint32_t, uint2 e) { move(e); });
     if (__ballot(dropped) && lane == 0) {
         // a candidate list overflowed its estimated capacity: redo the row exactly (exact capacities cannot overflow)
         if (ri->exact) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
@@ -595,28 +635,6 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
     if (tid < nz && s_zmin[tid]) {   // the zone had candidates here (~key of a 31-bit key is never 0)
         atomicMax(&ra->zone_kmax[tid], s_zmax[tid]);
         atomicMax(&ra->zone_kmin_inv[tid], s_zmin[tid]);
-    }
-    if (SUMS) {
-        const unsigned long long* s_sum = (const unsigned long long*)(lm + LM_SUM);
-        for (int g = tid; g < G_DUMMY; g += MAIN_THREADS) {
-            unsigned long long lo = 0, hi = 0;
-#pragma unroll
-            for (int r = 0; r < REP_SUM; ++r) {
-                const unsigned long long v = s_sum[g * REP_SUM + ((r + tid) & (REP_SUM - 1))];
-                lo += v & 0xFFFFFFFFull;
-                hi += v >> 32;
-            }
-            if (lo) atomicAdd((unsigned long long*)&ra->gsum[g][0], lo);
-            if (hi) atomicAdd((unsigned long long*)&ra->gsum[g][1], hi);
-        }
-    }
-    if (tid < RMAX * CSUB_MAX) {   // per count chunk: the counters of region tid % RMAX
-        const int r = tid % RMAX, sub = tid / RMAX;
-        uint32_t cnt = 0;
-        for (int k = 0; k < REP_CNT; ++k) cnt += s_cnt[sub * (128 * REP_CNT) + r * REP_CNT + ((k + tid) & (REP_CNT - 1))];
-        const int64_t cc = (int64_t)blockIdx.x * a.csub + sub;
-        if (sub < a.csub && cc < a.cchunks_per_row) a.chunk_cnt[((size_t)row * a.cchunks_per_row + cc) * RMAX + r] = cnt;
-        if (cnt) atomicAdd(&ra->region_cnt[r], cnt);
     }
 }
 
