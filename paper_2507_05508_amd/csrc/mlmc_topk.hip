@@ -783,7 +783,7 @@ __global__ __launch_bounds__(FN_THREADS) void k_fhist(TopkArgs a, int exact_pass
 constexpr int ZC0_CAP = 4096;        // the sliced pass takes zones whose (parts x chunks) counters fit this
 
 template <bool SUMS, int PHASE>
-__global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pass) {
+__global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkArgs a, int exact_pass) {
     // phase 0 (many workgroups per zone) keeps its LDS small so that several workgroups share a CU
     constexpr int UN_WORDS = PHASE == 0 ? COLLECT_CAP * 2 : TMAX * 256;
     constexpr int ZC = PHASE == 0 ? ZC0_CAP : ZC_CAP;
@@ -1103,10 +1103,10 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
             if (tid == 0) { s_q[0] = 0xFFFFFFFFu; s_eq[0] = 0u; s_ncollect = 0; }
             __syncthreads();
             // one pass for both: smallest / largest key (checked first: mostly no atomic) and, for the case that they
-            // agree, the histogram of the indices.  One workgroup walks the list: many loads per thread in flight.
+            // agree, the histogram of the indices.  One workgroup walks the list.
             int ish = 0;
             while (((uint32_t)(a.d - 1) >> ish) >= (uint32_t)FH_BINS) ++ish;
-            batched_loop<16, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return make_uint2(xb[i], xj[i]); }, [&](uint32_t, uint2 e) {
+            batched_loop<8, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return make_uint2(xb[i], xj[i]); }, [&](uint32_t, uint2 e) {
                 const uint32_t key = key_of_bits(e.x);
                 if (key < s_q[0]) atomicMin(&s_q[0], key);
                 if (key > s_eq[0]) atomicMax(&s_eq[0], key);
@@ -1129,7 +1129,7 @@ __global__ __launch_bounds__(FN_THREADS) void k_finish(TopkArgs a, int exact_pas
                     __syncthreads();
                     if (s_bcnt[0] <= (uint32_t)COLLECT_CAP && s_bcnt[0] > 0) {
                         const uint32_t ibin = s_bin[0];
-                        batched_loop<32, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return xj[i]; }, [&](uint32_t, uint32_t j) {
+                        batched_loop<16, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return xj[i]; }, [&](uint32_t, uint32_t j) {
                             if ((j >> ish) == ibin) {
                                 const uint32_t at = atomicAdd(&s_ncollect, 1u);
                                 if (at < (uint32_t)COLLECT_CAP) s_col[at] = j;
