@@ -88,7 +88,6 @@ struct RowInfo {
 struct RowAcc {  // per row, zeroed at the start of every call (and again before a row is redone exactly)
     uint32_t zone_fill[ZMAX];
     uint32_t zone_colcnt[ZMAX], zone_ticket[ZMAX];   // finish kernel: gathered candidates, slices done
-    uint32_t zone_kmax[ZMAX], zone_kmin_inv[ZMAX];   // largest key and largest ~key among the zone's candidates
     uint32_t region_cnt[RMAX];
     uint32_t n_pieces;
     uint32_t rowmax_key;

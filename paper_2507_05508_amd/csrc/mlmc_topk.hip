@@ -406,8 +406,8 @@ constexpr int MAIN_WAVES = MAIN_THREADS / 64;
 constexpr int LM_TAB = 0;                                   // uint32 [NB1]
 constexpr int LM_SUM = NB1 * 4;                             // uint64 [GMAX][REP_SUM]
 constexpr int LM_ZCUR = LM_SUM + GMAX * REP_SUM * 8;        // uint32 [64] write cursor of every zone list
-constexpr int LM_ZMAX = LM_ZCUR + 64 * 4;                   // uint32 [64] largest candidate key of every zone
-constexpr int LM_ZMIN = LM_ZMAX + 64 * 4;                   // uint32 [64] largest ~key
+constexpr int LM_ZMAX = LM_ZCUR + 64 * 4;                   // uint32 [64], word 0: largest key of the chunk
+constexpr int LM_ZMIN = LM_ZMAX + 64 * 4;                   // uint32 [64] spare
 constexpr int LM_ZOFF = LM_ZMIN + 64 * 4;                   // uint32 [64]
 constexpr int LM_ZCAP = LM_ZOFF + 64 * 4;
 constexpr int LM_MISC_END = LM_ZCAP + 64 * 4;
@@ -424,8 +424,7 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
     __shared__ __align__(16) unsigned char lm[lm_total<SUMS>()];
     uint32_t* s_cnt = (uint32_t*)(lm + LM_CNT);
     uint32_t* s_zcur = (uint32_t*)(lm + LM_ZCUR);
-    uint32_t* s_zmax = (uint32_t*)(lm + LM_ZMAX);
-    uint32_t* s_zmin = (uint32_t*)(lm + LM_ZMIN);
+    uint32_t* s_rowmax = (uint32_t*)(lm + LM_ZMAX);   // largest key the workgroup met
     uint32_t* s_zoff = (uint32_t*)(lm + LM_ZOFF);
     uint32_t* s_zcap = (uint32_t*)(lm + LM_ZCAP);
 
@@ -557,6 +556,8 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
         process(buf[0], cc, rel_of(nfull), (1u << nv) - 1u, cnt_of(nfull));
     }
     if (__ballot(maxkey >= 0x7F800000u) && lane == 0) atomicOr(a.dev_status, MLMC_DEV_NONFINITE);
+    maxkey = wave_max(maxkey);
+    if (lane == 0) atomicMax(s_rowmax, maxkey);
 
     // ---- the workgroup's candidates move from the private lists to the zones' lists: one reservation per zone.
     //      The wave's list comes back from memory while the reservations are made and the sums and counts, which
@@ -579,6 +580,7 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
             total += s_cnt[(r / REP_CNT) * (128 * REP_CNT) + (64 + tid) * REP_CNT + ((r + tid) & (REP_CNT - 1))];
         s_zcur[tid] = total ? atomicAdd(&ra->zone_fill[tid], total) : 0u;
     }
+    if (tid == 64) atomicMax(&ra->rowmax_key, s_rowmax[0]);
     if (SUMS && tid >= 64) {   // the waves after the first: the first is waiting for its reservations
         const unsigned long long* s_sum = (const unsigned long long*)(lm + LM_SUM);
         for (int g = tid - 64; g < G_DUMMY; g += MAIN_THREADS - 64) {
@@ -607,11 +609,9 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
     uint32_t* ci = a.cand_idx + (size_t)row * (size_t)a.d;
     bool dropped = false;
     auto move = [&](uint2 e) {
-        const uint32_t z = e.y & 63u, key = key_of_bits(e.x);
+        const uint32_t z = e.y & 63u;
         if (z == TAG_MEMBER) return;   // staged for the message only
         const uint32_t pos = atomicAdd(&s_zcur[z], 1u);
-        atomicMax(&s_zmax[z], key);
-        atomicMax(&s_zmin[z], ~key);
         if (pos < s_zcap[z]) {
             const size_t at = (size_t)s_zoff[z] + pos;
             cb[at] = e.x;
@@ -630,11 +630,6 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
         // a candidate list overflowed its estimated capacity: redo the row exactly (exact capacities cannot overflow)
         if (ri->exact) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
         else atomicOr((int32_t*)&a.rinfo[row].respec, 1);
-    }
-    __syncthreads();
-    if (tid < nz && s_zmin[tid]) {   // the zone had candidates here (~key of a 31-bit key is never 0)
-        atomicMax(&ra->zone_kmax[tid], s_zmax[tid]);
-        atomicMax(&ra->zone_kmin_inv[tid], s_zmin[tid]);
     }
 }
 
@@ -682,7 +677,15 @@ __device__ __forceinline__ int finish_slices(uint32_t n) {
     const uint32_t s = (n + (uint32_t)FIN_SLICE - 1u) / (uint32_t)FIN_SLICE;
     return s < 1u ? 1 : (s > (uint32_t)FIN_SLICES ? FIN_SLICES : (int)s);
 }
-// Key range of a zone's candidates (kept by the selection read) -> shift of the zone-relative histogram.
+// Key range of a zone: its buckets, cut at the largest key of the row (the top zone of a small sample reaches up to
+// the highest bucket, which would otherwise stretch the zone over every exponent above the data).
+__device__ __forceinline__ void zone_key_range(const RowInfo* ri, const RowAcc* ra, int z, uint32_t& kmin, uint32_t& kmax) {
+    kmin = ri->zone_bot[z] << B1_SHIFT;
+    kmax = ((ri->zone_top[z] + 1u) << B1_SHIFT) - 1u;
+    const uint32_t rmax = ra->rowmax_key;
+    if (kmax > rmax) kmax = rmax;
+}
+// Key range of a zone -> shift of the zone-relative histogram.
 __device__ __forceinline__ int finish_shift(uint32_t kmin, uint32_t kmax) {
     const uint32_t range = kmax - kmin;
     return range < (uint32_t)FH_BINS ? 0 : (32 - __clz(range)) - 11;   // (range >> shift) < FH_BINS
@@ -754,7 +757,8 @@ __global__ __launch_bounds__(FN_THREADS) void k_fhist(TopkArgs a, int exact_pass
         const uint32_t n = s_fill[z];
         if (n == 0 || n > ri->zone_cap[z]) continue;   // the finish kernel reports it
         const int S = finish_slices(n);
-        const uint32_t kmin = ~ra->zone_kmin_inv[z], kmax = ra->zone_kmax[z];
+        uint32_t kmin, kmax;
+        zone_key_range(ri, ra, z, kmin, kmax);
         if (kmin > kmax) continue;
         const int sh = finish_shift(kmin, kmax);
         const uint32_t* kb = a.cand_bits + (size_t)row * (size_t)a.d + ri->zone_off[z];
@@ -861,8 +865,9 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
     const uint32_t cmagic = (uint32_t)(0x100000000ull / (uint32_t)(a.cchunk >> 12)) + 1u;   // count chunk = multiple of 4096, >= 4 * 4096
     auto chunk_of = [&](uint32_t j) -> uint32_t { return __umulhi(j >> 12, cmagic); };
 
-    // range of the keys in the list (kept by the selection read), exponents for the part sums
-    const uint32_t kmin = ~ra->zone_kmin_inv[z], kmax = ra->zone_kmax[z];
+    // range of the keys in the list, exponents for the part sums
+    uint32_t kmin, kmax;
+    zone_key_range(ri, ra, z, kmin, kmax);
     const int Elo = (int)(kmin >> 23) ? (int)(kmin >> 23) : 1;
     const int Ehi = (int)(kmax >> 23) ? (int)(kmax >> 23) : 1;
     const int span = Ehi - Elo + 1;
