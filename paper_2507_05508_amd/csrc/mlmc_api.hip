@@ -98,10 +98,8 @@ static void fill_topk_args(const mlmc_plan_t* pl, TopkArgs& a, const void* g, in
     a.zcol = (unsigned long long*)(w + pl->off_zcol);
     a.tile_off = (uint32_t*)(w + pl->off_tileoff);
     a.norms = (double*)(w + pl->off_norms);
-    a.cand_bits = (uint32_t*)(w + pl->off_cand_bits);
-    a.cand_idx = (uint32_t*)(w + pl->off_cand_idx);
-    a.cand2_bits = (uint32_t*)(w + pl->off_cand2_bits);
-    a.cand2_idx = (uint32_t*)(w + pl->off_cand2_idx);
+    a.cand = (uint2*)(w + pl->off_cand);
+    a.cand2 = (uint2*)(w + pl->off_cand2);
     a.cand_priv = (uint2*)(w + pl->off_cand_priv);
     a.priv_cnt = (uint32_t*)(w + pl->off_priv_cnt);
     a.chunk_base = (uint32_t*)(w + pl->off_chunk_base);
@@ -261,14 +259,10 @@ mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dty
         off = align_up(off + sizeof(uint32_t) * (size_t)(pl->ntiles + 1) * M, 256);
         pl->off_norms = off;
         off = align_up(off + sizeof(double) * (size_t)L * M, 256);
-        pl->off_cand_bits = off;
-        off = align_up(off + sizeof(uint32_t) * (size_t)d * M, 256);
-        pl->off_cand_idx = off;
-        off = align_up(off + sizeof(uint32_t) * (size_t)d * M, 256);
-        pl->off_cand2_bits = off;
-        off = align_up(off + sizeof(uint32_t) * (size_t)d * M, 256);
-        pl->off_cand2_idx = off;
-        off = align_up(off + sizeof(uint32_t) * (size_t)d * M, 256);
+        pl->off_cand = off;
+        off = align_up(off + sizeof(uint2) * (size_t)d * M, 256);
+        pl->off_cand2 = off;
+        off = align_up(off + sizeof(uint2) * (size_t)d * M, 256);
         pl->off_cand_priv = off;
         off = align_up(off + sizeof(uint2) * (size_t)pl->chunk * pl->chunks_per_row * M, 256);
         pl->off_priv_cnt = off;

@@ -114,10 +114,8 @@ struct TopkArgs {
     uint32_t* table;         // [M][NB1]
     RowInfo* rinfo;          // [M]
     RowAcc* racc;            // [M]
-    uint32_t* cand_bits;     // [M][d] candidate lists: fp32 bit patterns
-    uint32_t* cand_idx;      // [M][d]                  indices
-    uint32_t* cand2_bits;    // [M][d] overflow lists: candidates of threshold bins too full to rank in LDS
-    uint32_t* cand2_idx;     // [M][d]
+    uint2* cand;             // [M][d] candidate lists of the zones: {fp32 bit pattern, index}
+    uint2* cand2;            // [M][d] overflow lists: candidates of threshold bins too full to rank in LDS
     uint2* cand_priv;        // [M][chunks_per_row][chunk] staged {bits, offset in chunk << 6 | tag} as the waves met them
     uint32_t* priv_cnt;      // [M][chunks_per_row][16] entries of every wave's private list
     uint32_t* chunk_base;    // [M][cchunks_per_row + 1] message entries of the row before every count chunk
@@ -204,6 +202,6 @@ struct mlmc_plan_s {
     int staging;
     // workspace byte offsets
     size_t off_racc, off_hist, off_hist2, off_chunk_zcnt, off_zhist, off_zpacc, zero_bytes;  // [0, zero_bytes) is cleared per call
-    size_t off_rinfo, off_table, off_chunk_cnt, off_zcol, off_tileoff, off_norms, off_cand_bits, off_cand_idx, off_cand2_bits, off_cand2_idx, off_cand_priv, off_priv_cnt, off_chunk_base, off_row_order;
+    size_t off_rinfo, off_table, off_chunk_cnt, off_zcol, off_tileoff, off_norms, off_cand, off_cand2, off_cand_priv, off_priv_cnt, off_chunk_base, off_row_order;
     size_t ws_bytes;
 };

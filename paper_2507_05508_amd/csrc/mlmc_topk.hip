@@ -605,17 +605,14 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
         if (cnt) atomicAdd(&ra->region_cnt[r], cnt);
     }
     __syncthreads();
-    uint32_t* cb = a.cand_bits + (size_t)row * (size_t)a.d;
-    uint32_t* ci = a.cand_idx + (size_t)row * (size_t)a.d;
+    uint2* cl = a.cand + (size_t)row * (size_t)a.d;
     bool dropped = false;
     auto move = [&](uint2 e) {
         const uint32_t z = e.y & 63u;
         if (z == TAG_MEMBER) return;   // staged for the message only
         const uint32_t pos = atomicAdd(&s_zcur[z], 1u);
         if (pos < s_zcap[z]) {
-            const size_t at = (size_t)s_zoff[z] + pos;
-            cb[at] = e.x;
-            ci[at] = (uint32_t)c0 + (e.y >> 6);
+            cl[(size_t)s_zoff[z] + pos] = make_uint2(e.x, (uint32_t)c0 + (e.y >> 6));
         } else {
             dropped = true;
         }
@@ -761,13 +758,13 @@ __global__ __launch_bounds__(FN_THREADS) void k_fhist(TopkArgs a, int exact_pass
         zone_key_range(ri, ra, z, kmin, kmax);
         if (kmin > kmax) continue;
         const int sh = finish_shift(kmin, kmax);
-        const uint32_t* kb = a.cand_bits + (size_t)row * (size_t)a.d + ri->zone_off[z];
+        const uint2* kl = a.cand + (size_t)row * (size_t)a.d + ri->zone_off[z];
         const uint32_t per = (n + S - 1) / S;
         const uint32_t i0 = (uint32_t)slice * per, i1 = i0 + per < n ? i0 + per : n;
         __syncthreads();
         for (int i = tid; i < FH_BINS; i += FN_THREADS) s_fh[i] = 0;
         __syncthreads();
-        batched_loop<8, FN_THREADS>(i0, i1, (uint32_t)tid, [&](uint32_t i) { return kb[i]; }, [&](uint32_t, uint32_t bits) {
+        batched_loop<8, FN_THREADS>(i0, i1, (uint32_t)tid, [&](uint32_t i) { return kl[i].x; }, [&](uint32_t, uint32_t bits) {
             const uint32_t b = (key_of_bits(bits) - kmin) >> sh;
             atomicAdd(&s_fh[b < (uint32_t)FH_BINS ? b : (uint32_t)FH_BINS - 1], 1u);
         });
@@ -828,8 +825,7 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
     auto run_item = [&](const int z, const int slice) {
     const uint32_t n = s_fill[z];
     const int S = finish_slices(n);
-    const uint32_t* kb = a.cand_bits + (size_t)row * (size_t)a.d + ri->zone_off[z];
-    const uint32_t* kj = a.cand_idx + (size_t)row * (size_t)a.d + ri->zone_off[z];
+    const uint2* kl = a.cand + (size_t)row * (size_t)a.d + ri->zone_off[z];   // {bits, index}
 
     if (tid == 0) {
         // elements strictly above the zone: regions 0..z and zones 0..z-1
@@ -956,8 +952,7 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
     const uint32_t per = (n + Seff - 1) / Seff;
     const uint32_t i0 = (uint32_t)slice * per, i1 = i0 + per < n ? i0 + per : n;
     const uint32_t ncollect_zone = s_ncollect;   // candidates in the thresholds' bins, all slices together
-    uint32_t* c2b = a.cand2_bits + (size_t)row * (size_t)a.d + ri->zone_off[z];
-    uint32_t* c2j = a.cand2_idx + (size_t)row * (size_t)a.d + ri->zone_off[z];
+    uint2* c2l = a.cand2 + (size_t)row * (size_t)a.d + ri->zone_off[z];
     const uint32_t zcap = ri->zone_cap[z];
     __syncthreads();
     if (s_fast || (PHASE == 0 && par_big)) {
@@ -981,7 +976,7 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
             b = b < (uint32_t)FH_BINS ? b : (uint32_t)FH_BINS - 1;
             return s_bincls[b];
         };
-        batched_loop<8, FN_THREADS>(i0, i1, (uint32_t)tid, [&](uint32_t i) { return make_uint2(kb[i], kj[i]); },
+        batched_loop<8, FN_THREADS>(i0, i1, (uint32_t)tid, [&](uint32_t i) { return kl[i]; },
                                     [&](uint32_t, uint2 e) {
             const uint32_t key = key_of_bits(e.x);
             const uint32_t cls = bin_class(key);
@@ -996,7 +991,7 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
         if (tid == 0) s_ncollect = mine ? atomicAdd(&ra->zone_colcnt[z], mine) : 0u;   // becomes the write cursor
         __syncthreads();
         if (mine) {
-            batched_loop<8, FN_THREADS>(i0, i1, (uint32_t)tid, [&](uint32_t i) { return make_uint2(kb[i], kj[i]); },
+            batched_loop<8, FN_THREADS>(i0, i1, (uint32_t)tid, [&](uint32_t i) { return kl[i]; },
                                         [&](uint32_t, uint2 e) {
                 const bool col = bin_class(key_of_bits(e.x)) == 0xFFu;
                 const uint64_t m = __ballot(col);
@@ -1007,7 +1002,7 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
                     base = __shfl(base, first, 64);
                     if (col) {
                         const uint32_t pos = base + mbcnt(m);
-                        if (pos < zcap) { c2b[pos] = e.x; c2j[pos] = e.y; }
+                        if (pos < zcap) c2l[pos] = e;
                     }
                 }
             });
@@ -1018,7 +1013,7 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
     if (s_fast) {
         // ---- read 2: candidates of the thresholds' bins are gathered in LDS, every other one is classified ----
         if (PHASE == 0 || !par_ok) {
-            batched_loop<8, FN_THREADS>(i0, i1, (uint32_t)tid, [&](uint32_t i) { return make_uint2(kb[i], kj[i]); },
+            batched_loop<8, FN_THREADS>(i0, i1, (uint32_t)tid, [&](uint32_t i) { return kl[i]; },
                                         [&](uint32_t, uint2 e) {
                 const uint32_t key = key_of_bits(e.x);
                 const uint32_t j = e.y;
@@ -1086,8 +1081,7 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
         // ---- slow path (a threshold bin too full to rank in LDS, e.g. massive ties): radix select on the
         //      keys, digits of 8, 8, 8, 7 bits from the top, then on the indices of the entries equal to the key.
         //      It runs on the overflow list (the thresholds' bins only) when phase 0 built one, else on the whole list ----
-        const uint32_t* xb = par_big ? c2b : kb;
-        const uint32_t* xj = par_big ? c2j : kj;
+        const uint2* xl = par_big ? c2l : kl;
         const uint32_t xn = par_big ? ncollect_zone : n;
         if (par_big) {
             if (ra->zone_colcnt[z] != ncollect_zone || ncollect_zone > zcap) {
@@ -1111,7 +1105,7 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
             // agree, the histogram of the indices.  One workgroup walks the list.
             int ish = 0;
             while (((uint32_t)(a.d - 1) >> ish) >= (uint32_t)FH_BINS) ++ish;
-            batched_loop<8, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return make_uint2(xb[i], xj[i]); }, [&](uint32_t, uint2 e) {
+            batched_loop<8, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return xl[i]; }, [&](uint32_t, uint2 e) {
                 const uint32_t key = key_of_bits(e.x);
                 if (key < s_q[0]) atomicMin(&s_q[0], key);
                 if (key > s_eq[0]) atomicMax(&s_eq[0], key);
@@ -1134,7 +1128,7 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
                     __syncthreads();
                     if (s_bcnt[0] <= (uint32_t)COLLECT_CAP && s_bcnt[0] > 0) {
                         const uint32_t ibin = s_bin[0];
-                        batched_loop<16, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return xj[i]; }, [&](uint32_t, uint32_t j) {
+                        batched_loop<16, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return xl[i].y; }, [&](uint32_t, uint32_t j) {
                             if ((j >> ish) == ibin) {
                                 const uint32_t at = atomicAdd(&s_ncollect, 1u);
                                 if (at < (uint32_t)COLLECT_CAP) s_col[at] = j;
@@ -1177,17 +1171,17 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
                 __syncthreads();
                 const int nsub = s_nsub;
                 if (pass == 0) {
-                    batched_loop<8, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return xb[i]; }, [&](uint32_t, uint32_t bits) {
+                    batched_loop<8, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return xl[i].x; }, [&](uint32_t, uint32_t bits) {
                         atomicAdd(&s_hist[0][(key_of_bits(bits) >> 23) & 255u], 1u);
                     });
                 } else if (nsub == 1) {
                     const uint32_t pf = s_subpfx[0] >> hb;
-                    batched_loop<8, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return xb[i]; }, [&](uint32_t, uint32_t bits) {
+                    batched_loop<8, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return xl[i].x; }, [&](uint32_t, uint32_t bits) {
                         const uint32_t key = key_of_bits(bits);
                         if ((key >> hb) == pf) atomicAdd(&s_hist[0][(key >> shift) & mask], 1u);
                     });
                 } else {
-                    batched_loop<8, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return xb[i]; }, [&](uint32_t, uint32_t bits) {
+                    batched_loop<8, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return xl[i].x; }, [&](uint32_t, uint32_t bits) {
                         const uint32_t key = key_of_bits(bits);
                         const uint32_t kp = key >> hb;
                         for (int s2 = 0; s2 < nsub; ++s2)
@@ -1239,7 +1233,7 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
                     for (int i = tid; i < TMAX * 256; i += FN_THREADS) (&s_hist[0][0])[i] = 0;
                     __syncthreads();
                     const int nsub = s_nsub;
-                    batched_loop<8, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return make_uint2(xb[i], xj[i]); },
+                    batched_loop<8, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return xl[i]; },
                                                 [&](uint32_t, uint2 e) {
                         const uint32_t key = key_of_bits(e.x), j = e.y;
                         for (int s2 = 0; s2 < nsub; ++s2) {
@@ -1265,7 +1259,7 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
         }
         // every candidate's part from the exact thresholds
         if (count_fits || SUMS) {
-            batched_loop<8, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return make_uint2(xb[i], xj[i]); },
+            batched_loop<8, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return xl[i]; },
                                         [&](uint32_t, uint2 e) {
                 const uint32_t key = key_of_bits(e.x), j = e.y;
                 int part = 0;
@@ -1294,7 +1288,7 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
             __syncthreads();
             for (int i = tid; i < (p1 - p0) * nchunks; i += FN_THREADS) s_zc[i] = 0;
             __syncthreads();
-            batched_loop<8, FN_THREADS>(0u, n, (uint32_t)tid, [&](uint32_t i) { return make_uint2(kb[i], kj[i]); },
+            batched_loop<8, FN_THREADS>(0u, n, (uint32_t)tid, [&](uint32_t i) { return kl[i]; },
                                         [&](uint32_t, uint2 e) {
                 const uint32_t key = key_of_bits(e.x), j = e.y;
                 int part = 0;
