@@ -878,7 +878,16 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
     unsigned long long* zcol = a.zcol + ((size_t)row * ZMAX + z) * COLLECT_CAP;
     auto slot_of = [&](int part) -> int { return part < nthr ? s_t[part] : TMAX + z; };
 
-    {
+    if (PHASE == 1 && exact_pass) {
+        // the redo round has no launches of its own for the histogram and the sliced pass: this workgroup makes the
+        // zone's histogram here (a zone of an exact histogram is one bucket) and resolves the zone alone
+        for (int i = tid; i < FH_BINS; i += FN_THREADS) s_fh[i] = 0;
+        __syncthreads();
+        batched_loop<8, FN_THREADS>(0u, n, (uint32_t)tid, [&](uint32_t i) { return kl[i].x; }, [&](uint32_t, uint32_t bits) {
+            const uint32_t b = (key_of_bits(bits) - kmin) >> sh;
+            atomicAdd(&s_fh[b < (uint32_t)FH_BINS ? b : (uint32_t)FH_BINS - 1], 1u);
+        });
+    } else {
         const uint32_t* zh = a.zhist + ((size_t)row * ZMAX + z) * FH_BINS;
         for (int i = tid; i < FH_BINS; i += FN_THREADS) s_fh[i] = zh[i];
     }
@@ -944,7 +953,7 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
     // bins hold few candidates (par_ok) they are gathered for ranking in LDS; when they hold many (massive ties,
     // e.g. bf16 keys: par_big) they are moved to the zone's overflow list, on which phase 1 runs a radix select.
     // Every other zone is resolved by one workgroup in phase 1.
-    const bool fits0 = nparts * nchunks <= ZC0_CAP;
+    const bool fits0 = !exact_pass && nparts * nchunks <= ZC0_CAP;   // the redo round: phase 1 only
     const bool par_ok = s_fast && fits0;
     const bool par_big = !s_fast && fits0;
     if (PHASE == 0 && !par_ok && !par_big) return;
@@ -1893,14 +1902,16 @@ static mlmc_status launch_select(const mlmc_plan_t* pl, const TopkArgs& a, bool 
         MLMC_LAUNCH(ks, st, k_scan<<<pl->M, 1024, 0, st>>>(a, exact_pass));
         if (sums) MLMC_LAUNCH(km, st, k_main<DT, VEC, true><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
         else MLMC_LAUNCH(km, st, k_main<DT, VEC, false><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
-        MLMC_LAUNCH(exact_pass ? K_REDO : K_FHIST, st, k_fhist<<<fgrid, FN_THREADS, 0, st>>>(a, exact_pass));
+        // the redo round resolves every zone in the ranking launch alone (two launches fewer to pay for when, as
+        // nearly always, no row needs it)
+        if (!exact_pass) MLMC_LAUNCH(K_FHIST, st, k_fhist<<<fgrid, FN_THREADS, 0, st>>>(a, exact_pass));
         const dim3 rgrid(pl->L + 1 < FIN_WGS ? pl->L + 1 : FIN_WGS, pl->M);
         const int k0 = exact_pass ? K_REDO : K_FINISH, k1 = exact_pass ? K_REDO : K_FINISH1;
         if (sums) {
-            MLMC_LAUNCH(k0, st, k_finish<true, 0><<<fgrid, FN_THREADS, 0, st>>>(a, exact_pass));
+            if (!exact_pass) MLMC_LAUNCH(k0, st, k_finish<true, 0><<<fgrid, FN_THREADS, 0, st>>>(a, exact_pass));
             MLMC_LAUNCH(k1, st, k_finish<true, 1><<<rgrid, FN_THREADS, 0, st>>>(a, exact_pass));
         } else {
-            MLMC_LAUNCH(k0, st, k_finish<false, 0><<<fgrid, FN_THREADS, 0, st>>>(a, exact_pass));
+            if (!exact_pass) MLMC_LAUNCH(k0, st, k_finish<false, 0><<<fgrid, FN_THREADS, 0, st>>>(a, exact_pass));
             MLMC_LAUNCH(k1, st, k_finish<false, 1><<<rgrid, FN_THREADS, 0, st>>>(a, exact_pass));
         }
     }
