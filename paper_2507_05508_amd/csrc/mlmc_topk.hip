@@ -12,17 +12,19 @@
 //   k_main       the selection read: per region exact element counts (per chunk and per row) and exact sums of
 //                squared significands per (exponent, region); zone candidates and the members of the staged band
 //                go to per-wave private lists, the candidates from there to per-zone lists
-//   k_fhist      per (zone, slice): histogram of the candidates over the zone's own key range
+//   k_fhist      per (zone, slice): histogram of the candidates over the zone's own key range (that of its buckets,
+//                cut at the largest key of the row)
 //   k_finish<0>  per (zone, slice): the exact counts above the zone prove (or refute) that its thresholds lie
 //                inside; candidates of the thresholds' bins are gathered, all others classified by their bin
 //                (per-chunk counts of the zone's parts, exact sums per part and exponent)
 //   k_finish<1>  per zone: gathered candidates ranked in LDS -> exact threshold key and index cut among equal keys
 //                (radix select on an overflow list when the bins hold many: massive ties).
-//                A refuted row is flagged and redone with an exact histogram (k_hist .. k_finish once more, for
-//                flagged rows only; these launches return at once otherwise).
+//                A refuted row is flagged and redone with an exact histogram (k_hist, k_scan, k_main, k_finish<1>
+//                once more, for flagged rows only; these launches return at once otherwise).
 //   k_norms      big-integer accumulation of group and part sums -> correctly rounded fp64 S_l -> Delta_l
 //                (Lemma 3.4), then the adaptive level draw (Alg. 3)
-//   k_msgplan    per row: where its message starts, message entries before every chunk, the three thresholds
+//   k_msgplan    per row: where its message starts, message entries before every chunk, the three thresholds,
+//                the row's place by message length (the two kernels below take the long rows first)
 //   k_filter     rows whose staged band is the drawn one: base band + drawn band (Eq. (6)) from the staged lists,
 //                ordered by index through a bitmap over the chunk
 //   k_write      the other rows: second read, a workgroup owns a chunk whose output offset is known
@@ -406,9 +408,8 @@ constexpr int MAIN_WAVES = MAIN_THREADS / 64;
 constexpr int LM_TAB = 0;                                   // uint32 [NB1]
 constexpr int LM_SUM = NB1 * 4;                             // uint64 [GMAX][REP_SUM]
 constexpr int LM_ZCUR = LM_SUM + GMAX * REP_SUM * 8;        // uint32 [64] write cursor of every zone list
-constexpr int LM_ZMAX = LM_ZCUR + 64 * 4;                   // uint32 [64], word 0: largest key of the chunk
-constexpr int LM_ZMIN = LM_ZMAX + 64 * 4;                   // uint32 [64] spare
-constexpr int LM_ZOFF = LM_ZMIN + 64 * 4;                   // uint32 [64]
+constexpr int LM_ROWMAX = LM_ZCUR + 64 * 4;                 // uint32 (16 bytes kept): largest key of the chunk
+constexpr int LM_ZOFF = LM_ROWMAX + 16;                     // uint32 [64]
 constexpr int LM_ZCAP = LM_ZOFF + 64 * 4;
 constexpr int LM_MISC_END = LM_ZCAP + 64 * 4;
 constexpr int LM_CNT = 4 * 32768;                           // uint32 [CSUB_MAX][128][REP_CNT]: regions 0..63, zones 64..127
@@ -424,7 +425,7 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
     __shared__ __align__(16) unsigned char lm[lm_total<SUMS>()];
     uint32_t* s_cnt = (uint32_t*)(lm + LM_CNT);
     uint32_t* s_zcur = (uint32_t*)(lm + LM_ZCUR);
-    uint32_t* s_rowmax = (uint32_t*)(lm + LM_ZMAX);   // largest key the workgroup met
+    uint32_t* s_rowmax = (uint32_t*)(lm + LM_ROWMAX);   // largest key the workgroup met
     uint32_t* s_zoff = (uint32_t*)(lm + LM_ZOFF);
     uint32_t* s_zcap = (uint32_t*)(lm + LM_ZCAP);
 
