@@ -75,7 +75,10 @@ __device__ __forceinline__ void bits_extract_row(const BitsArgs& a, int row, con
     const uint32_t lane = lane_id(), wave = (uint32_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     RowLoader<DT, false> ld(a.g, a.ld, a.d, row);
     const int64_t ntiles = (a.d + TILE - 1) / TILE;
-    for (int64_t tile = (int64_t)blockIdx.x * 4 + wave; tile < ntiles; tile += (int64_t)gridDim.x * 4) {
+    // tiles (and rows) are taken from the end: what the scale pass read last is the part of the input that the
+    // memory-side cache most likely still holds
+    for (int64_t rt = (int64_t)blockIdx.x * 4 + wave; rt < ntiles; rt += (int64_t)gridDim.x * 4) {
+        const int64_t tile = ntiles - 1 - rt;
         const int64_t base = tile * TILE;
         uint64_t words[NPC];
 #pragma unroll
@@ -128,7 +131,7 @@ __device__ __forceinline__ void bits_extract_row(const BitsArgs& a, int row, con
 // ballot is the plane word of those 64 elements; lane i keeps word i and the 64 words go out in one store.
 template <int DT>
 __global__ __launch_bounds__(256) void k_bits_extract(BitsArgs a) {
-    const int row = blockIdx.y;
+    const int row = a.M - 1 - (int)blockIdx.y;
     const BitsRow br = bits_row(a, row);
     const int np = 1 + br.F0 + br.width;  // planes written for this row
     if (blockIdx.x == 0 && threadIdx.x == 0) a.scale_exp[row] = br.Emax - 126;
