@@ -1515,7 +1515,7 @@ __device__ __forceinline__ bool inside_top(const Thr3& th, int i, uint32_t key, 
 // entries lie before every chunk (regions of band 0 and band l plus the parts of the zones of thresholds 0, l-1, l
 // that belong to those bands), and the three thresholds, so that the kernels that write the message start from
 // one small record.
-constexpr int MP_THREADS = 256;
+constexpr int MP_THREADS = 1024;
 __global__ __launch_bounds__(MP_THREADS) void k_msgplan(TopkArgs a) {
     __shared__ uint32_t s_scan[MP_THREADS / 64 + 1];
     __shared__ uint32_t s_carry;
