@@ -752,6 +752,10 @@ __global__ __launch_bounds__(FN_THREADS) void k_fhist(TopkArgs a, int exact_pass
         int z = 0;
         while (z + 1 < nz && s_first[z + 1] <= item) ++z;
         const int slice = item - s_first[z];
+        if (slice == 0) {   // what the sliced launch accumulates for a zone with massive ties: index histogram, key range
+            uint32_t* zi = (uint32_t*)(a.zcol + ((size_t)row * ZMAX + z) * COLLECT_CAP);
+            for (int i = tid; i < FH_BINS + 2; i += FN_THREADS) zi[i] = 0;
+        }
         const uint32_t n = s_fill[z];
         if (n == 0 || n > ri->zone_cap[z]) continue;   // the finish kernel reports it
         const int S = finish_slices(n);
@@ -1001,9 +1005,20 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
         if (tid == 0) s_ncollect = mine ? atomicAdd(&ra->zone_colcnt[z], mine) : 0u;   // becomes the write cursor
         __syncthreads();
         if (mine) {
+            // With the copy: the key range of what is copied and the histogram of its indices, for the zone as a whole
+            // (in the zone's gather buffer, unused on this path and cleared by the histogram launch).  When the range
+            // is a single key, the usual case, the ranking launch needs no pass of its own for them.
+            uint32_t* s_ih = s_un;   // FH_BINS words: free on this path
+            int ish = 0;
+            while (((uint32_t)(a.d - 1) >> ish) >= (uint32_t)FH_BINS) ++ish;
+            for (int i = tid; i < FH_BINS; i += FN_THREADS) s_ih[i] = 0;
+            if (tid == 0) { s_q[0] = 0u; s_eq[0] = 0u; }   // largest ~key, largest key
+            __syncthreads();
+            uint32_t kmx = 0, kmn_inv = 0;
             batched_loop<8, FN_THREADS>(i0, i1, (uint32_t)tid, [&](uint32_t i) { return kl[i]; },
                                         [&](uint32_t, uint2 e) {
-                const bool col = bin_class(key_of_bits(e.x)) == 0xFFu;
+                const uint32_t key = key_of_bits(e.x);
+                const bool col = bin_class(key) == 0xFFu;
                 const uint64_t m = __ballot(col);
                 if (m) {
                     const int first = __builtin_ctzll(m);
@@ -1013,9 +1028,22 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
                     if (col) {
                         const uint32_t pos = base + mbcnt(m);
                         if (pos < zcap) c2l[pos] = e;
+                        atomicAdd(&s_ih[e.y >> ish], 1u);
+                        kmx = key > kmx ? key : kmx;
+                        kmn_inv = ~key > kmn_inv ? ~key : kmn_inv;
                     }
                 }
             });
+            kmx = wave_max(kmx);
+            kmn_inv = wave_max(kmn_inv);
+            if (lane == 0 && kmn_inv) { atomicMax(&s_eq[0], kmx); atomicMax(&s_q[0], kmn_inv); }
+            __syncthreads();
+            uint32_t* zi = (uint32_t*)zcol;
+            for (int i = tid; i < FH_BINS; i += FN_THREADS) {
+                const uint32_t v = s_ih[i];
+                if (v) atomicAdd(&zi[i], v);
+            }
+            if (tid == 0 && s_q[0]) { atomicMax(&zi[FH_BINS], s_q[0]); atomicMax(&zi[FH_BINS + 1], s_eq[0]); }
         }
         flush_totals(true);
         return;
@@ -1105,24 +1133,13 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
         if (tid == 0) { s_any = 0; s_nsub = 0; }
         __syncthreads();
         if (par_big && nthr == 1) {
-            // the index histogram in four lane-interleaved copies (in s_un, free until the gather below): neighbours in
-            // the list have neighbouring indices, and 64 lanes adding to one LDS word take 64 turns
-            static_assert(UN_WORDS >= 4 * FH_BINS, "room for the histogram copies");
-            for (int i = tid; i < 4 * FH_BINS; i += FN_THREADS) s_un[i] = 0;
-            if (tid == 0) { s_q[0] = 0xFFFFFFFFu; s_eq[0] = 0u; s_ncollect = 0; }
-            __syncthreads();
-            // one pass for both: smallest / largest key (checked first: mostly no atomic) and, for the case that they
-            // agree, the histogram of the indices.  One workgroup walks the list.
+            // key range and index histogram of the overflow list: made by the sliced launch while it copied
+            const uint32_t* zi = (const uint32_t*)zcol;
             int ish = 0;
             while (((uint32_t)(a.d - 1) >> ish) >= (uint32_t)FH_BINS) ++ish;
-            batched_loop<8, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return xl[i]; }, [&](uint32_t, uint2 e) {
-                const uint32_t key = key_of_bits(e.x);
-                if (key < s_q[0]) atomicMin(&s_q[0], key);
-                if (key > s_eq[0]) atomicMax(&s_eq[0], key);
-                atomicAdd(&s_un[((e.y >> ish) << 2) | (lane & 3u)], 1u);
-            });
+            for (int i = tid; i < FH_BINS; i += FN_THREADS) s_fh[i] = zi[i];
+            if (tid == 0) { s_q[0] = ~zi[FH_BINS]; s_eq[0] = zi[FH_BINS + 1]; s_ncollect = 0; }
             __syncthreads();
-            for (int i = tid; i < FH_BINS; i += FN_THREADS) s_fh[i] = s_un[4 * i] + s_un[4 * i + 1] + s_un[4 * i + 2] + s_un[4 * i + 3];
             const uint32_t key1 = s_q[0];
             const bool single = key1 == s_eq[0];
             __syncthreads();
