@@ -211,7 +211,7 @@ __global__ __launch_bounds__(256) void k_agg_bits(AggBitsArgs a) {
             }
         }
         const int64_t j = w * 64 + lane;
-        if (j < b.d) a.out[j] = __fmul_rn(a.alpha, acc);
+        if (j < b.d) __builtin_nontemporal_store(__fmul_rn(a.alpha, acc), &a.out[j]);
     }
 }
 
@@ -320,7 +320,7 @@ __global__ __launch_bounds__(256) void k_agg_sparse(AggSparseArgs a) {
     }
     for (int i = threadIdx.x; i < TILE; i += 256) {
         int64_t j = base + i;
-        if (j < a.d) a.out[j] = __fmul_rn(a.alpha, s_acc[i]);
+        if (j < a.d) __builtin_nontemporal_store(__fmul_rn(a.alpha, s_acc[i]), &a.out[j]);   // written once, read by the caller later
     }
 }
 
