@@ -87,7 +87,7 @@ struct RowInfo {
 
 struct RowAcc {  // per row, zeroed at the start of every call (and again before a row is redone exactly)
     uint32_t zone_fill[ZMAX];
-    uint32_t zone_colcnt[ZMAX], zone_ticket[ZMAX];   // finish kernel: gathered candidates, slices done
+    uint32_t zone_colcnt[ZMAX];   // finish kernels: candidates of the thresholds' bins gathered (or moved to the overflow list) so far
     uint32_t region_cnt[RMAX];
     uint32_t n_pieces;
     uint32_t rowmax_key;

@@ -1367,32 +1367,10 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Delta_l (Lemma 3.4) from the exact group and part sums, then the adaptive draw.  One workgroup per row,
-// one thread per band; the 640-bit accumulators live in LDS.
+// Delta_l (Lemma 3.4) from the exact group and part sums, then the adaptive draw.  One workgroup per row; the
+// 640-bit sums live in LDS.
 struct BigAcc {
-    uint32_t* w;  // 20 words
-    __device__ void clear() { for (int i = 0; i < 20; ++i) w[i] = 0; }
-    __device__ void add(uint64_t v, int shift) {  // += v << shift
-        if (!v) return;
-        int wi = shift >> 5, bs = shift & 31;
-        uint32_t parts[3];
-        if (bs == 0) {
-            parts[0] = (uint32_t)v;
-            parts[1] = (uint32_t)(v >> 32);
-            parts[2] = 0;
-        } else {
-            parts[0] = (uint32_t)(v << bs);
-            parts[1] = (uint32_t)(v >> (32 - bs));
-            parts[2] = (uint32_t)(v >> (64 - bs));
-        }
-        uint64_t carry = 0;
-        for (int i = 0; i < 3 || carry; ++i) {
-            if (wi + i >= 20) break;
-            uint64_t sum = (uint64_t)w[wi + i] + (i < 3 ? parts[i] : 0u) + carry;
-            w[wi + i] = (uint32_t)sum;
-            carry = sum >> 32;
-        }
-    }
+    uint32_t* w;  // 20 words, least significant first
     // value * 2^-298 rounded to nearest-even fp64
     __device__ double to_double() const {
         int top = -1;
