@@ -212,9 +212,13 @@ mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dty
         }
         pl->nplanes = 1 + (int)ladder[0] + maxw;
     }
-    // chunking of the streaming kernels: about 2048 workgroups over all rows, whole tiles, at most 2^18
-    // elements per workgroup (the LDS accumulators and the packed candidate offsets rely on that bound)
+    // chunking of the streaming kernels: about 2048 workgroups over all rows, but chunks of at least some 96 K
+    // elements (a workgroup of the selection read loads a 64 KB table first), whole tiles, at most 2^18 elements
+    // per workgroup (the LDS accumulators and the packed candidate offsets rely on that bound)
     int64_t target_per_row = 2048 / M > 0 ? 2048 / M : 1;
+    int64_t by_size = (d + 98303) / 98304;
+    if (by_size < 4) by_size = 4;   // a short row still spreads over a few CUs
+    if (target_per_row > by_size) target_per_row = by_size;
     int64_t chunk = (d + target_per_row - 1) / target_per_row;
     chunk = (chunk + 4 * TILE - 1) / (4 * TILE) * (4 * TILE);
     if (chunk < 4 * TILE) chunk = 4 * TILE;
