@@ -272,6 +272,54 @@ def test_more_rows_than_a_wave_or_a_workgroup(M):
             assert np.array_equal(out.cpu().numpy().view(np.uint32), O.aggregate_sparse(want, d, 1.0 / M).view(np.uint32))
 
 
+@pytest.mark.parametrize("seed", [1, 2])
+def test_random_plans_and_inputs(seed):
+    """Randomised valid calls (row counts, lengths from 1 to 120 000, ladders, fp32 / bf16, padded rows, value
+    families with zeros, massive ties and heavy tails, sampled and exact threshold search, staging on and off)
+    against the oracle, bit for bit, aggregate included."""
+    rng = np.random.default_rng(seed)
+    for case in range(30):
+        M = int(rng.choice([1, 2, 3, 5, 9]))
+        d = int(rng.choice([rng.integers(1, 200), rng.integers(200, 20000), rng.integers(20000, 120000)]))
+        ladder = np.sort(rng.choice(np.arange(0, d + 1), size=min(int(rng.integers(2, 12)), d + 1), replace=False)).tolist()
+        if rng.random() < 0.5:
+            ladder[-1] = d
+        L = len(ladder) - 1
+        kind = int(rng.integers(0, 4))
+        if kind == 0:
+            G = rng.standard_normal((M, d)).astype(np.float32)
+        elif kind == 1:
+            G = (rng.standard_normal((M, d)) * np.exp(rng.uniform(-20, 10, size=(M, 1)))).astype(np.float32)
+            G[rng.random((M, d)) < 0.5] = 0.0
+        elif kind == 2:
+            G = rng.integers(-3, 4, size=(M, d)).astype(np.float32)
+        else:
+            G = (rng.standard_t(2, size=(M, d)) * np.exp(rng.uniform(-8, 2, size=(1, d)))).astype(np.float32)
+        bf16 = rng.random() < 0.3
+        if bf16:
+            Gb = (G.view(np.uint32) >> 16).astype(np.uint16)
+            G = (Gb.astype(np.uint32) << 16).view(np.float32)
+            g = to_device(Gb)
+        else:
+            g = to_device(G, ld=d + int(rng.integers(1, 4)) if rng.random() < 0.3 else None)
+        adaptive = rng.random() < 0.5
+        plan = P.Plan(P.MLMC_TOPK, M, d, P.MLMC_BF16 if bf16 else P.MLMC_F32, ladder, None if adaptive else O.geometric_p(L))
+        shift = int(rng.choice([0, 0, 1, 2, 4]))
+        plan.set_sampling(shift)
+        staging = rng.random() >= 0.25
+        plan.set_staging(staging)
+        call_seed = int(rng.integers(0, 2**40))
+        for step in range(2):
+            print(f"random case {case}: M={M} d={d} ladder={ladder} kind={kind} bf16={bf16} adaptive={adaptive} "
+                  f"shift={shift} staging={staging} step={step}", flush=True)
+            msg = P.mlmc_compress_topk(plan, g, seed=call_seed, step=step)
+            want = check_topk_against_oracle(plan, G, call_seed, step, msg, adaptive=adaptive)
+            assert plan.status() == 0
+            out = P.mlmc_aggregate(plan, msg, 0.5)
+            torch.cuda.synchronize()
+            assert np.array_equal(out.cpu().numpy().view(np.uint32), O.aggregate_sparse(want, d, 0.5).view(np.uint32))
+
+
 def test_identity_ladder_is_dense_mean():
     """L = 1, k_0 = 0, k_1 = d, p = 1: the message is the gradient and the aggregate is Alg. 1's mean."""
     rng = np.random.default_rng(0)
