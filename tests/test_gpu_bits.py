@@ -72,3 +72,38 @@ def test_bits_bf16_rows():
     for step in range(3):
         msg = P.mlmc_compress_bits(plan, g, seed=1, step=step)
         _check_bits(plan, G, F, p, 1, step, msg)
+
+
+@pytest.mark.parametrize("seed", [3, 4])
+def test_bits_random_plans_and_inputs(seed):
+    """Randomised valid calls of the bit-wise path (row counts, lengths, bit ladders up to 24 bits, value families
+    with zeros and very small or large scales, padded rows) against the oracle, bit for bit, aggregate included."""
+    rng = np.random.default_rng(seed)
+    for case in range(25):
+        M = int(rng.choice([1, 2, 3, 5, 9]))
+        d = int(rng.choice([rng.integers(1, 200), rng.integers(200, 20000), rng.integers(20000, 150000)]))
+        nF = int(rng.integers(2, 8))
+        F = np.sort(rng.choice(np.arange(0, 25), size=nF, replace=False)).tolist()
+        L = len(F) - 1
+        kind = int(rng.integers(0, 3))
+        if kind == 0:
+            G = rng.standard_normal((M, d)).astype(np.float32)
+        elif kind == 1:
+            G = (rng.standard_normal((M, d)) * np.exp(rng.uniform(-60, 40, size=(M, 1)))).astype(np.float32)
+            G[rng.random((M, d)) < 0.4] = 0.0
+        else:
+            G = rng.integers(-5, 6, size=(M, d)).astype(np.float32)
+            if M > 1:
+                G[0] = 0.0   # an all-zero row
+        p = O.geometric_p(L)
+        plan = P.Plan(P.MLMC_BITS, M, d, P.MLMC_F32, F, p)
+        g = to_device(G, ld=d + int(rng.integers(1, 4)) if rng.random() < 0.3 else None)
+        call_seed = int(rng.integers(0, 2**40))
+        for step in range(2):
+            print(f"bits random case {case}: M={M} d={d} F={F} kind={kind} step={step}", flush=True)
+            msg = P.mlmc_compress_bits(plan, g, seed=call_seed, step=step)
+            want = _check_bits(plan, G, F, p, call_seed, step, msg)
+            assert plan.status() == 0
+            out = P.mlmc_aggregate(plan, msg, 0.25)
+            torch.cuda.synchronize()
+            assert np.array_equal(out.cpu().numpy().view(np.uint32), O.aggregate_bits(want, F, d, 0.25).view(np.uint32))
