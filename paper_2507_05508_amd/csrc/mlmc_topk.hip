@@ -863,6 +863,10 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
     const int nparts = nthr + 1;
     const int nchunks = a.cchunks_per_row;   // count chunks
     const bool count_fits = nparts * nchunks <= ZC;
+    // Neighbours in a candidate list mostly come from the same chunk, and 64 lanes adding to one LDS word take 64
+    // turns: the counters are kept in as many lane-interleaved copies (1, 2 or 4) as the LDS array holds.
+    const int zrep_shift = nparts * nchunks * 4 <= ZC ? 2 : nparts * nchunks * 2 <= ZC ? 1 : 0;
+    const uint32_t zrep_lane = lane & ((1u << zrep_shift) - 1u);
     const uint32_t cmagic = (uint32_t)(0x100000000ull / (uint32_t)(a.cchunk >> 12)) + 1u;   // count chunk = multiple of 4096, >= 4 * 4096
     auto chunk_of = [&](uint32_t j) -> uint32_t { return __umulhi(j >> 12, cmagic); };
 
@@ -896,13 +900,13 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
         const uint32_t* zh = a.zhist + ((size_t)row * ZMAX + z) * FH_BINS;
         for (int i = tid; i < FH_BINS; i += FN_THREADS) s_fh[i] = zh[i];
     }
-    if (count_fits) for (int i = tid; i < nparts * nchunks; i += FN_THREADS) s_zc[i] = 0;
+    if (count_fits) for (int i = tid; i < (nparts * nchunks) << zrep_shift; i += FN_THREADS) s_zc[i] = 0;
     if (SUMS) for (int i = tid; i < PIECE_CLASSES * PREP * 2; i += FN_THREADS) (&s_pacc[0][0])[i] = 0ull;
     __syncthreads();
 
     // what every candidate contributes once its part (number of the zone's thresholds it is NOT inside) is known
     auto classify = [&](int part, uint32_t key, uint32_t j) {
-        if (count_fits) atomicAdd(&s_zc[part * nchunks + (int)chunk_of(j)], 1u);
+        if (count_fits) atomicAdd(&s_zc[(((uint32_t)(part * nchunks) + chunk_of(j)) << zrep_shift) | zrep_lane], 1u);
         if (SUMS) {
             const int E = (int)(key >> 23) ? (int)(key >> 23) : 1;
             const int cls = part * span + (E - Elo);
@@ -916,7 +920,8 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
         __syncthreads();
         if (count_fits) {
             for (int i = tid; i < nparts * nchunks; i += FN_THREADS) {
-                const uint32_t v = s_zc[i];
+                uint32_t v = 0;
+                for (int r = 0; r < (1 << zrep_shift); ++r) v += s_zc[(i << zrep_shift) + r];
                 if (v) {
                     const int part = i / nchunks, c = i - part * nchunks;
                     atomicAdd(&zc[(size_t)c * ZPMAX + slot_of(part)], v);
