@@ -905,14 +905,19 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
     __syncthreads();
 
     // what every candidate contributes once its part (number of the zone's thresholds it is NOT inside) is known
+    const bool whole_adds = (PHASE == 0 ? (n + (uint32_t)S - 1u) / (uint32_t)S : n) <= 32768u;   // candidates this workgroup classifies
     auto classify = [&](int part, uint32_t key, uint32_t j) {
         if (count_fits) atomicAdd(&s_zc[(((uint32_t)(part * nchunks) + chunk_of(j)) << zrep_shift) | zrep_lane], 1u);
         if (SUMS) {
             const int E = (int)(key >> 23) ? (int)(key >> 23) : 1;
             const int cls = part * span + (E - Elo);
             const unsigned long long sq = sig_square(key);
-            atomicAdd(&s_pacc[cls * PREP + lrep][0], sq & 0xFFFFFFFFull);
-            atomicAdd(&s_pacc[cls * PREP + lrep][1], sq >> 32);
+            if (whole_adds) {   // uniform: at most 2^15 squares below 2^48 cannot overflow one 64-bit accumulator
+                atomicAdd(&s_pacc[cls * PREP + lrep][0], sq);
+            } else {
+                atomicAdd(&s_pacc[cls * PREP + lrep][0], sq & 0xFFFFFFFFull);
+                atomicAdd(&s_pacc[cls * PREP + lrep][1], sq >> 32);
+            }
         }
     };
     // LDS counters and sums -> the zone's totals
@@ -930,7 +935,11 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
         }
         if (SUMS && with_sums && tid < nclass) {
             unsigned long long lo = 0, hi = 0;
-            for (int r = 0; r < PREP; ++r) { lo += s_pacc[tid * PREP + r][0]; hi += s_pacc[tid * PREP + r][1]; }
+            for (int r = 0; r < PREP; ++r) {
+                const unsigned long long v = s_pacc[tid * PREP + r][0];
+                lo += v & 0xFFFFFFFFull;
+                hi += (v >> 32) + s_pacc[tid * PREP + r][1];
+            }
             if (lo) atomicAdd(&zp[tid * 2], lo);
             if (hi) atomicAdd(&zp[tid * 2 + 1], hi);
         }
@@ -1344,7 +1353,11 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
     __syncthreads();
     if (tid < nclass) {
         unsigned long long lo = zp[tid * 2], hi = zp[tid * 2 + 1];
-        for (int r = 0; r < PREP; ++r) { lo += s_pacc[tid * PREP + r][0]; hi += s_pacc[tid * PREP + r][1]; }
+        for (int r = 0; r < PREP; ++r) {
+            const unsigned long long v = s_pacc[tid * PREP + r][0];
+            lo += v & 0xFFFFFFFFull;
+            hi += (v >> 32) + s_pacc[tid * PREP + r][1];
+        }
         hi += lo >> 32;
         lo &= 0xFFFFFFFFull;
         if (lo | hi) {
