@@ -120,8 +120,8 @@ struct TopkArgs {
     uint32_t* priv_cnt;      // [M][chunks_per_row][16] entries of every wave's private list
     uint32_t* chunk_base;    // [M][cchunks_per_row + 1] message entries of the row before every count chunk
     int32_t* row_order;      // [M] rows by descending message length: the order in which the message kernels take them
-    uint32_t* chunk_cnt;     // [M][cchunks_per_row][RMAX] elements of every region per count chunk
-    uint32_t* chunk_zcnt;    // [M][cchunks_per_row][ZPMAX] candidates of every part of every zone per count chunk (zeroed per call)
+    uint32_t* chunk_cnt;     // [M][RMAX][cchunks_per_row] elements of every region per count chunk
+    uint32_t* chunk_zcnt;    // [M][ZPMAX][cchunks_per_row] candidates of every part of every zone per count chunk (zeroed per call)
     uint32_t* zhist;         // [M][ZMAX][FH_BINS] zone-relative key histograms (zeroed per call)
     unsigned long long* zpacc; // [M][ZMAX][PIECE_CLASSES][2] sums of squared significands per (part, exponent) (zeroed per call)
     unsigned long long* zcol;  // [M][ZMAX][COLLECT_CAP] candidates of the thresholds' bins

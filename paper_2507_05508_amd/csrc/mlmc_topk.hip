@@ -602,7 +602,7 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
         uint32_t cnt = 0;
         for (int k = 0; k < REP_CNT; ++k) cnt += s_cnt[sub * (128 * REP_CNT) + r * REP_CNT + ((k + t) & (REP_CNT - 1))];
         const int64_t cc = (int64_t)blockIdx.x * a.csub + sub;
-        if (sub < a.csub && cc < a.cchunks_per_row) a.chunk_cnt[((size_t)row * a.cchunks_per_row + cc) * RMAX + r] = cnt;
+        if (sub < a.csub && cc < a.cchunks_per_row) a.chunk_cnt[((size_t)row * RMAX + r) * a.cchunks_per_row + cc] = cnt;
         if (cnt) atomicAdd(&ra->region_cnt[r], cnt);
     }
     __syncthreads();
@@ -929,7 +929,7 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
                 for (int r = 0; r < (1 << zrep_shift); ++r) v += s_zc[(i << zrep_shift) + r];
                 if (v) {
                     const int part = i / nchunks, c = i - part * nchunks;
-                    atomicAdd(&zc[(size_t)c * ZPMAX + slot_of(part)], v);
+                    atomicAdd(&zc[(size_t)slot_of(part) * nchunks + c], v);
                 }
             }
         }
@@ -1342,7 +1342,7 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
             __syncthreads();
             for (int i = tid; i < (p1 - p0) * nchunks; i += FN_THREADS) {
                 const int part = p0 + i / nchunks, c = i % nchunks;
-                zc[(size_t)c * ZPMAX + slot_of(part)] = s_zc[i];
+                zc[(size_t)slot_of(part) * nchunks + c] = s_zc[i];
             }
         }
     }
@@ -1555,29 +1555,39 @@ __global__ __launch_bounds__(MP_THREADS) void k_msgplan(TopkArgs a) {
         if (za >= 0) zs[1] = zb == za ? lev : TMAX + za;          // just below threshold l-1, in its zone
         if (zb >= 0 && zb != za) zs[2] = lev;                     // above threshold l, in a zone of its own
     }
-    if (tid == 0) s_carry = 0;
-    __syncthreads();
+    // message entries before every count chunk: a thread takes a run of consecutive count chunks (their counts are
+    // fetched together), one scan over the threads' sums
     uint32_t* cbase = a.chunk_base + (size_t)row * (nc + 1);
-    for (int c0 = 0; c0 < nc; c0 += MP_THREADS) {
-        const int c = c0 + tid;
-        uint32_t v = 0;
-        if (c < nc) {
-            const uint32_t* cc = a.chunk_cnt + ((size_t)row * nc + c) * RMAX;
-            const uint32_t* zc = a.chunk_zcnt + ((size_t)row * nc + c) * ZPMAX;
-            if (r0 >= 0) v += cc[r0];
-            if (rl >= 0) v += cc[rl];
+    constexpr int MP_RUN = CHUNKS_MAX / MP_THREADS;   // a row has at most CHUNKS_MAX count chunks
+    const int per = (nc + MP_THREADS - 1) / MP_THREADS;
+    uint32_t v[MP_RUN];
+    uint32_t mine = 0;
 #pragma unroll
-            for (int i = 0; i < 3; ++i)
-                if (zs[i] >= 0) v += zc[zs[i]];
+    for (int i = 0; i < MP_RUN; ++i) {
+        const int c = tid * per + i;
+        v[i] = 0;
+        if (i < per && c < nc) {
+            // both tables are laid out [region or part][count chunk]: a thread's run is contiguous
+            const uint32_t* cc = a.chunk_cnt + (size_t)row * RMAX * nc + c;
+            const uint32_t* zc = a.chunk_zcnt + (size_t)row * ZPMAX * nc + c;
+            if (r0 >= 0) v[i] += cc[(size_t)r0 * nc];
+            if (rl >= 0) v[i] += cc[(size_t)rl * nc];
+#pragma unroll
+            for (int q = 0; q < 3; ++q)
+                if (zs[q] >= 0) v[i] += zc[(size_t)zs[q] * nc];
         }
-        uint32_t total;
-        const uint32_t ex = block_excl_scan<MP_THREADS>(v, s_scan, total);
-        const uint32_t carry = s_carry;
-        if (c < nc) cbase[c] = carry + ex;
-        __syncthreads();
-        if (tid == 0) s_carry = carry + total;
-        __syncthreads();
+        mine += v[i];
     }
+    uint32_t total;
+    uint32_t run = block_excl_scan<MP_THREADS>(mine, s_scan, total);
+#pragma unroll
+    for (int i = 0; i < MP_RUN; ++i) {
+        const int c = tid * per + i;
+        if (i < per && c < nc) cbase[c] = run;
+        run += v[i];
+    }
+    if (tid == 0) s_carry = total;
+    __syncthreads();
     // The messages of the rows before this one, and this row's place among all rows by descending message length
     // (the message kernels take the rows in that order, so that the long ones are not left for the end): lanes
     // of the first wave take rows in turn.
