@@ -738,7 +738,9 @@ __device__ __forceinline__ void count_greater2(const unsigned long long* v, uint
 
 // Read 1 of a candidate list, one item per (zone, slice): histogram of (key - kmin) >> shift.
 __global__ __launch_bounds__(FN_THREADS) void k_fhist(TopkArgs a, int exact_pass) {
-    __shared__ uint32_t s_fh[FH_BINS];
+    // four lane-interleaved copies: keys with few distinct values (16-bit inputs) put many lanes on one bin, and LDS
+    // atomics of many lanes on one word take a turn each
+    __shared__ uint32_t s_fh[4 * FH_BINS];
     __shared__ uint32_t s_fill[ZMAX], s_rcnt[RMAX];
     __shared__ int32_t s_first[ZMAX + 1];
     const int row = blockIdx.y, tid = threadIdx.x;
@@ -767,16 +769,16 @@ __global__ __launch_bounds__(FN_THREADS) void k_fhist(TopkArgs a, int exact_pass
         const uint32_t per = (n + S - 1) / S;
         const uint32_t i0 = (uint32_t)slice * per, i1 = i0 + per < n ? i0 + per : n;
         __syncthreads();
-        for (int i = tid; i < FH_BINS; i += FN_THREADS) s_fh[i] = 0;
+        for (int i = tid; i < 4 * FH_BINS; i += FN_THREADS) s_fh[i] = 0;
         __syncthreads();
         batched_loop<8, FN_THREADS>(i0, i1, (uint32_t)tid, [&](uint32_t i) { return kl[i].x; }, [&](uint32_t, uint32_t bits) {
             const uint32_t b = (key_of_bits(bits) - kmin) >> sh;
-            atomicAdd(&s_fh[b < (uint32_t)FH_BINS ? b : (uint32_t)FH_BINS - 1], 1u);
+            atomicAdd(&s_fh[((b < (uint32_t)FH_BINS ? b : (uint32_t)FH_BINS - 1) << 2) | (lane_id() & 3u)], 1u);
         });
         __syncthreads();
         uint32_t* zh = a.zhist + ((size_t)row * ZMAX + z) * FH_BINS;
         for (int i = tid; i < FH_BINS; i += FN_THREADS) {
-            const uint32_t v = s_fh[i];
+            const uint32_t v = s_fh[4 * i] + s_fh[4 * i + 1] + s_fh[4 * i + 2] + s_fh[4 * i + 3];
             if (v) atomicAdd(&zh[i], v);
         }
     }
