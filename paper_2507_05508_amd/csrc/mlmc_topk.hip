@@ -788,7 +788,7 @@ __global__ __launch_bounds__(FN_THREADS) void k_fhist(TopkArgs a, int exact_pass
 // candidates of those bins are gathered (a few hundred) and ranked by the workgroup that finishes last, every other
 // candidate is classified by its bin: per-chunk counts of the zone's parts and exact sums per (part, exponent).
 // When a threshold bin is too full to rank in LDS (massive ties) slice 0 resolves the zone alone by radix select.
-constexpr int ZC0_CAP = 4096;        // the sliced pass takes zones whose (parts x chunks) counters fit this
+constexpr int ZC0_CAP = 8192;        // the sliced pass takes zones whose (parts x chunks) counters fit this
 
 template <bool SUMS, int PHASE>
 __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkArgs a, int exact_pass) {
@@ -866,8 +866,8 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
     const int nchunks = a.cchunks_per_row;   // count chunks
     const bool count_fits = nparts * nchunks <= ZC;
     // Neighbours in a candidate list mostly come from the same chunk, and 64 lanes adding to one LDS word take 64
-    // turns: the counters are kept in as many lane-interleaved copies (1, 2 or 4) as the LDS array holds.
-    const int zrep_shift = nparts * nchunks * 4 <= ZC ? 2 : nparts * nchunks * 2 <= ZC ? 1 : 0;
+    // turns: the counters are kept in as many lane-interleaved copies (1, 2, 4 or 8) as the LDS array holds.
+    const int zrep_shift = nparts * nchunks * 8 <= ZC ? 3 : nparts * nchunks * 4 <= ZC ? 2 : nparts * nchunks * 2 <= ZC ? 1 : 0;
     const uint32_t zrep_lane = lane & ((1u << zrep_shift) - 1u);
     const uint32_t cmagic = (uint32_t)(0x100000000ull / (uint32_t)(a.cchunk >> 12)) + 1u;   // count chunk = multiple of 4096, >= 4 * 4096
     auto chunk_of = [&](uint32_t j) -> uint32_t { return __umulhi(j >> 12, cmagic); };
