@@ -162,6 +162,7 @@ def main():
 
     # same K steps again with a HIP-event pair around every kernel (on the launch stream)
     nnz_total, planes_bytes = 0, 0
+    drawn = {}   # drawn level -> rows that drew it over the timed steps (the message size, hence the bytes, depends on it)
     P.mlmc_profile_reset()
     P.mlmc_profile_enable(True)
     torch.cuda.synchronize()
@@ -179,9 +180,13 @@ def main():
         if w.kind == "topk":
             P.mlmc_compress_topk(plan, g, seed=w.seed, step=args.warmup + i, out=msg)
             nnz_total += int(msg.row_off[-1].item())
+            for l in msg.level.cpu().numpy().tolist():
+                drawn[l] = drawn.get(l, 0) + 1
         else:
             P.mlmc_compress_bits(plan, g, seed=w.seed, step=args.warmup + i, out=msg)
             lv = msg.level.cpu().numpy()
+            for l in lv.tolist():
+                drawn[l] = drawn.get(l, 0) + 1
             widths = [w.ladder[l] - w.ladder[l - 1] for l in lv]
             planes_bytes += sum((1 + w.ladder[0] + x) * ((w.d + 63) // 64) * 8 for x in widths)
     nnz_avg = nnz_total / args.steps
@@ -219,6 +224,7 @@ def main():
         "hbm_peak_frac_algorithmic": round(step_alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
         "ms_per_step_with_events": round(dt_ev * 1e3 / args.steps, 4),
         "exact_redo_in_last_step": redone,
+        "drawn_levels": {str(l): n for l, n in sorted(drawn.items())},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": measured_traffic(w.name, dominant),
