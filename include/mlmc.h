@@ -92,8 +92,9 @@ mlmc_status mlmc_plan_set_sampling(mlmc_plan_t *plan, int shift);
  * Tuning hook (MLMC_TOPK plans).  With staging on (the default) the read that selects the thresholds also sets
  * aside the members of the band the message will hold (Eq. (6)): the level is known before the read when p is
  * given, and predicted from the sampled histogram when p is adaptive (Alg. 3); the message is then assembled
- * from what was set aside and the rows are read once.  A wrong prediction, or staging switched off, makes the
- * library read the row a second time.  Run time only, never a result.
+ * from what was set aside and the rows are read once.  A wrong prediction, a drawn band wider than an eighth of
+ * the row (cheaper to collect by reading again), or staging switched off, makes the library read the row a
+ * second time.  Run time only, never a result.
  */
 mlmc_status mlmc_plan_set_staging(mlmc_plan_t *plan, int enable);
 
