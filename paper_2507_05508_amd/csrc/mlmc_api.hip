@@ -29,6 +29,7 @@ static const char* const k_names[K_NUM] = {
 struct ProfPair { int id; hipEvent_t e0, e1; };
 static std::vector<ProfPair> g_pending;
 static std::vector<ProfPair> g_free;
+static bool g_open = false;   // the last entry of g_pending still waits for its end event
 static double g_total_ms[K_NUM];
 static int64_t g_launches[K_NUM];
 
@@ -47,20 +48,26 @@ static void prof_drain() {
 void prof_begin(int id, hipStream_t st) {
     if (g_pending.size() >= 8192) prof_drain();
     ProfPair p;
+    g_open = false;
     if (!g_free.empty()) {
         p = g_free.back();
         g_free.pop_back();
     } else {
-        if (hipEventCreate(&p.e0) != hipSuccess || hipEventCreate(&p.e1) != hipSuccess) return;
+        if (hipEventCreate(&p.e0) != hipSuccess) return;
+        if (hipEventCreate(&p.e1) != hipSuccess) { (void)hipEventDestroy(p.e0); return; }
     }
     p.id = id;
     (void)hipEventRecord(p.e0, st);
     g_pending.push_back(p);
+    g_open = true;
 }
 
+// Closes the pair that the matching prof_begin opened; when that call could not create its events there is no
+// open pair and nothing is recorded (an older pair of the same kernel is never touched).
 void prof_end(int id, hipStream_t st) {
-    if (g_pending.empty() || g_pending.back().id != id) return;
+    if (!g_open || g_pending.empty() || g_pending.back().id != id) return;
     (void)hipEventRecord(g_pending.back().e1, st);
+    g_open = false;
 }
 
 // rows can be read with aligned 16-byte (fp32) / 8-byte (bf16) loads

@@ -1638,10 +1638,7 @@ constexpr int WR_THREADS = 512;
 constexpr int WR_WAVES = WR_THREADS / 64;
 constexpr int WR_LINES = TILE / (WR_WAVES * 64);   // 64-element lines of a wave per step
 constexpr int WR_STAGE = 1024;   // entries of one step that are gathered in LDS and written densely
-#ifndef WR_DIRECT_N
-#define WR_DIRECT_N 1024
-#endif
-constexpr int WR_DIRECT = WR_DIRECT_N;   // steps with more entries write them straight from the lanes (at most WR_STAGE)
+constexpr int WR_DIRECT = 1024;  // steps with more entries write them straight from the lanes (at most WR_STAGE)
 
 template <int DT, bool VEC>
 __global__ __launch_bounds__(WR_THREADS, 4) void k_write(TopkArgs a) {
