@@ -19,17 +19,28 @@ HIPCC_FLAGS = [
 ]
 
 
-def build(verbose: bool = False) -> str:
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
-    cmd += [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB_PATH]
+def _run(cmd):
     proc = subprocess.run(cmd, capture_output=True, text=True)
-    out = "\n".join(l for l in (proc.stdout + proc.stderr).splitlines()
-                    if "packed-fp32-ops" not in l)
+    out = "\n".join(l for l in (proc.stdout + proc.stderr).splitlines() if "packed-fp32-ops" not in l)
     if proc.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + out)
-    if verbose and out.strip():
-        print(out)
+    return out
+
+
+def build(verbose: bool = False) -> str:
+    """Compiles every source (in parallel, one hipcc per file) and links libmlmc.so; always recompiles."""
+    from concurrent.futures import ThreadPoolExecutor
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    objdir = os.path.join(PKG_DIR, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    compile_flags = [f for f in HIPCC_FLAGS if f != "-shared"] + ["-c", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    objs = [os.path.join(objdir, s.replace(".hip", ".o")) for s in SOURCES]
+    cmds = [[hipcc] + compile_flags + [os.path.join(CSRC, s), "-o", o] for s, o in zip(SOURCES, objs)]
+    with ThreadPoolExecutor(max_workers=len(cmds)) as ex:
+        outs = list(ex.map(_run, cmds))
+    outs.append(_run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIB_PATH]))
+    if verbose and any(o.strip() for o in outs):
+        print("\n".join(o for o in outs if o.strip()))
     return LIB_PATH
 
 
