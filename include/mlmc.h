@@ -47,7 +47,8 @@ typedef enum {
     MLMC_OK = 0,
     MLMC_EINVAL = 1,   /* bad argument (ladder, probabilities, sizes, null pointers, alignment) */
     MLMC_ENOMEM = 2,   /* host allocation failed */
-    MLMC_EHIP = 3      /* a HIP call or kernel launch failed */
+    MLMC_EHIP = 3,     /* a HIP call or kernel launch failed */
+    MLMC_ELIMIT = 4    /* mlmc_compress_bits_static: the plan needs more scratch than MLMC_STATIC_SCRATCH_BYTES */
 } mlmc_status;
 
 /* bits OR-ed into *dev_status by the kernels */
@@ -149,6 +150,24 @@ mlmc_status mlmc_compress_topk(const mlmc_plan_t *plan, const void *g, int64_t l
 mlmc_status mlmc_compress_bits(const mlmc_plan_t *plan, const void *g, int64_t ld, uint64_t seed,
                                uint64_t step, int32_t *level, int32_t *scale_exp, uint64_t *planes,
                                int32_t *dev_status, void *ws, void *hip_stream);
+
+/*
+ * mlmc_compress_bits for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and kernels as
+ * mlmc_compress_bits, without `ws`: the scratch (per-row maxima and draw records) lives in a device array of
+ * MLMC_STATIC_SCRATCH_BYTES bytes inside the library, one copy per GPU, held until the process ends.  The call
+ * allocates nothing and frees nothing.  Its first call on a device looks the array's address up
+ * (hipGetSymbolAddress); make that call outside a graph capture.
+ *   Limit: the plan's workspace_bytes must not exceed MLMC_STATIC_SCRATCH_BYTES (M up to about 80 workers),
+ *   else MLMC_ELIMIT and nothing is enqueued.
+ *   All calls on one GPU share the array, on any stream and for any plan: calls that overlap on a GPU race.
+ *   Order them on one stream, or with events.  The array keeps the previous call's contents; the part that must
+ *   start at zero is cleared on the stream at the start of every call.
+ */
+#define MLMC_STATIC_SCRATCH_BYTES (1 << 20)
+mlmc_status mlmc_compress_bits_static(const mlmc_plan_t *plan, const void *g, int64_t ld, uint64_t seed,
+                                      uint64_t step, int32_t *level, int32_t *scale_exp, uint64_t *planes,
+                                      int32_t *dev_status, void *hip_stream);
 
 /*
  * Server side (Alg. 2 / Alg. 3 "Server aggregates"): out[j] = fp32(alpha * acc_j), acc_j the fp32 sum over

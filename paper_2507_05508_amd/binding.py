@@ -15,7 +15,8 @@ import torch
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libmlmc.so")
 
-MLMC_OK, MLMC_EINVAL, MLMC_ENOMEM, MLMC_EHIP = 0, 1, 2, 3
+MLMC_OK, MLMC_EINVAL, MLMC_ENOMEM, MLMC_EHIP, MLMC_ELIMIT = 0, 1, 2, 3, 4
+MLMC_STATIC_SCRATCH_BYTES = 1 << 20
 MLMC_DEV_CAPACITY, MLMC_DEV_NONFINITE, MLMC_DEV_INTERNAL, MLMC_DEV_REDONE = 1, 2, 4, 8
 MLMC_F32, MLMC_BF16 = 0, 1
 MLMC_TOPK, MLMC_BITS = 0, 1
@@ -23,7 +24,7 @@ MLMC_TILE = 4096
 MLMC_MAX_LEVELS = 32
 
 EXPORTS = ["mlmc_plan", "mlmc_plan_destroy", "mlmc_plan_set_sampling", "mlmc_plan_set_staging", "mlmc_plan_num_tiles", "mlmc_plan_num_planes", "mlmc_geometric_p",
-           "mlmc_status_string", "mlmc_level_norms", "mlmc_compress_topk", "mlmc_compress_bits", "mlmc_aggregate",
+           "mlmc_status_string", "mlmc_level_norms", "mlmc_compress_topk", "mlmc_compress_bits", "mlmc_compress_bits_static", "mlmc_aggregate",
            "mlmc_profile_enable", "mlmc_profile_reset", "mlmc_profile_num_kernels", "mlmc_profile_kernel_name",
            "mlmc_profile_get"]
 
@@ -65,6 +66,8 @@ def lib():
         L.mlmc_compress_topk.argtypes = [vp, vp, i64, vp, i32, u64, u64, vp, vp, vp, vp, i64, vp, vp, vp, vp, vp]
         L.mlmc_compress_bits.restype = C.c_int
         L.mlmc_compress_bits.argtypes = [vp, vp, i64, u64, u64, vp, vp, vp, vp, vp, vp]
+        L.mlmc_compress_bits_static.restype = C.c_int
+        L.mlmc_compress_bits_static.argtypes = [vp, vp, i64, u64, u64, vp, vp, vp, vp, vp]
         L.mlmc_aggregate.restype = C.c_int
         L.mlmc_aggregate.argtypes = [vp, vp, vp, vp, vp, i64, vp, vp, vp, C.c_float, vp, vp, vp]
         L.mlmc_profile_enable.restype = None
@@ -236,6 +239,17 @@ def mlmc_compress_bits(plan: Plan, g: torch.Tensor, seed: int, step: int, out: O
     rc = lib().mlmc_compress_bits(plan.handle, _ptr(g), ld, seed, step, _ptr(out.level), _ptr(out.scale_exp),
                                   _ptr(out.planes), _ptr(plan.dev_status), _ptr(plan.ws), _stream())
     _check(rc, "mlmc_compress_bits")
+    return out
+
+
+def mlmc_compress_bits_static(plan: Plan, g: torch.Tensor, seed: int, step: int, out: BitsMessage,
+                              dev_status: torch.Tensor) -> BitsMessage:
+    """mlmc_compress_bits without a workspace (the library's static device scratch).  `out` and `dev_status` are
+    the caller's: this call allocates nothing."""
+    ld = _check_g(plan, g)
+    rc = lib().mlmc_compress_bits_static(plan.handle, _ptr(g), ld, seed, step, _ptr(out.level), _ptr(out.scale_exp),
+                                         _ptr(out.planes), _ptr(dev_status), _stream())
+    _check(rc, "mlmc_compress_bits_static")
     return out
 
 

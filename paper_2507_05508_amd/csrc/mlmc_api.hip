@@ -3,6 +3,7 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -20,6 +21,28 @@ mlmc_status agg_sparse(const mlmc_plan_t* pl, const int64_t* row_off, const uint
                        const uint32_t* tile_off, uint32_t* tile_off_ws, float alpha, float* out, hipStream_t st);
 
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ---- static device scratch for mlmc_compress_bits_static --------------------------------------------
+// Every GPU that loads the library holds its own copy of this array until the process ends.  In host code the
+// array's name is only a handle for hipGetSymbolAddress: the device address is looked up once per device and
+// kept; kernels, like those of mlmc_compress_bits, take the address as an argument.
+static __device__ __align__(256) unsigned char scratch[MLMC_STATIC_SCRATCH_BYTES];
+constexpr int MAX_DEVICES = 64;
+static void* g_scratch_ptr[MAX_DEVICES];
+static std::mutex g_scratch_mutex;
+
+static mlmc_status static_scratch_of_current_device(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return MLMC_EHIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return MLMC_EHIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return MLMC_OK;
+}
 
 // ---- per-kernel HIP-event timing (off by default; not thread safe) ---------------------------------
 bool g_prof_on = false;
@@ -143,6 +166,7 @@ const char* mlmc_status_string(int status) {
         case MLMC_EINVAL: return "MLMC_EINVAL: invalid argument";
         case MLMC_ENOMEM: return "MLMC_ENOMEM: host allocation failed";
         case MLMC_EHIP: return "MLMC_EHIP: HIP launch failed";
+        case MLMC_ELIMIT: return "MLMC_ELIMIT: the plan needs more scratch than the static array holds";
         default: return "unknown mlmc status";
     }
 }
@@ -396,6 +420,18 @@ mlmc_status mlmc_compress_bits(const mlmc_plan_t* plan, const void* g, int64_t l
     rc = topk_draw(da, st);
     if (rc != MLMC_OK) return rc;
     return bits_compress(plan, b, vec_ok(plan, g, ld), st);
+}
+
+mlmc_status mlmc_compress_bits_static(const mlmc_plan_t* plan, const void* g, int64_t ld, uint64_t seed, uint64_t step,
+                                      int32_t* level, int32_t* scale_exp, uint64_t* planes, int32_t* dev_status,
+                                      void* hip_stream) {
+    if (!plan || plan->kind != MLMC_BITS) return MLMC_EINVAL;
+    if (plan->ws_bytes > (size_t)MLMC_STATIC_SCRATCH_BYTES) return MLMC_ELIMIT;   // before any HIP call
+    void* ws = nullptr;
+    const mlmc_status rc = static_scratch_of_current_device(&ws);
+    if (rc != MLMC_OK) return rc;
+    // same kernels as mlmc_compress_bits; the part of the scratch that must start at zero is cleared by the first of them
+    return mlmc_compress_bits(plan, g, ld, seed, step, level, scale_exp, planes, dev_status, ws, hip_stream);
 }
 
 mlmc_status mlmc_aggregate(const mlmc_plan_t* plan, const int32_t* level, const int64_t* row_off, const uint32_t* idx,
