@@ -45,44 +45,122 @@ def algorithmic_bytes(w, kernel, nnz_total, planes_bytes):
     return 0
 
 
+def kernel_sources_digest():
+    """sha256 over the kernel sources and the C header: names the code a profile was taken from."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2507_05508_amd", "csrc")
+    files = sorted(os.path.join(csrc, f) for f in os.listdir(csrc) if f.endswith((".hip", ".h")))
+    for path in files + [os.path.join(ROOT, "include", "mlmc.h")]:
+        h.update(os.path.basename(path).encode() + b"\0")
+        h.update(open(path, "rb").read())
+    return h.hexdigest()
+
+
 def measured_traffic(workload, kernel):
-    """HBM bytes per launch of `kernel` from the committed rocprofv3 summary of this workload (FETCH_SIZE +
-    WRITE_SIZE, scaled as the summary says), or None when no summary covers it."""
+    """(HBM bytes per launch of `kernel`, provenance) from the committed rocprofv3 summary of this workload
+    (FETCH_SIZE + WRITE_SIZE, scaled as the summary says).  The summary names the digest of the kernel sources it
+    was measured on; when the sources have changed since (or no summary covers the kernel) the bytes are None:
+    a stale counter reading is not reported."""
     path = os.path.join(ROOT, "profiles", f"{workload}.txt")
     if not os.path.exists(path):
-        return None
+        return None, {"profile": None, "reason": "no summary for this workload"}
+    digest_now, digest_prof, value = kernel_sources_digest(), None, None
     for line in open(path):
         f = line.split()
-        if f and f[0].split("<")[0] == kernel and len(f) >= 3:
+        if line.startswith("kernel sources sha256:"):
+            digest_prof = f[-1]
+        elif f and f[0].split("<")[0] == kernel and len(f) >= 3:
             try:
-                return int((float(f[-2]) + float(f[-1])) * 1e6)
+                value = int((float(f[-2]) + float(f[-1])) * 1e6)
             except ValueError:
-                return None
-    return None
+                value = None
+    prov = {"profile": f"profiles/{workload}.txt", "kernel_sources_sha256": digest_prof}
+    if digest_prof != digest_now:
+        prov["reason"] = "kernel sources changed since the profile was taken"
+        return None, prov
+    return value, prov
 
 
-def cpu_baseline(w, G, budget_s=25.0):
-    """The oracle as it stands, single thread, on the first rows of the same workload until ~budget_s."""
+def _oracle_row(w, row_data, i):
     from oracle import mlmc as O
-    s_in = 2 if w.dtype == "bf16" else 4
-    t0 = time.perf_counter()
-    msgs, rows = [], 0
     p = None if w.adaptive else O.geometric_p(w.L)
-    for i in range(w.M):
-        if w.kind == "topk":
-            msgs.append(O.compress_topk_row(G[i], w.ladder, p, w.seed, 0, i))
-        else:
-            msgs.append(O.compress_bits_row(G[i], w.ladder, p, w.seed, 0, i))
-        rows += 1
-        if time.perf_counter() - t0 > budget_s * 0.8:
-            break
     if w.kind == "topk":
-        O.aggregate_sparse(msgs, w.d, 1.0 / w.M)
-    else:
-        O.aggregate_bits(msgs, w.ladder, w.d, 1.0 / w.M)
-    dt = time.perf_counter() - t0
-    return {"value": rows * w.d * s_in / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": f"{rows} of {w.M} rows of {w.name} (d={w.d}), one step: compress + aggregate, {dt:.1f} s"}
+        return O.compress_topk_row(row_data, w.ladder, p, w.seed, 0, i)
+    return O.compress_bits_row(row_data, w.ladder, p, w.seed, 0, i)
+
+
+def _oracle_aggregate(w, msgs):
+    from oracle import mlmc as O
+    if w.kind == "topk":
+        return O.aggregate_sparse(msgs, w.d, 1.0 / w.M)
+    return O.aggregate_bits(msgs, w.ladder, w.d, 1.0 / w.M)
+
+
+def _cpu_child(w, G, rows, barrier, conn):
+    """One process of the all-cores leg: waits until every process is ready, then compresses its rows."""
+    try:
+        barrier.wait()
+        t0 = time.perf_counter()
+        msgs = [_oracle_row(w, G[i], i) for i in rows]
+        dt = time.perf_counter() - t0
+        keep = ("level", "idx", "val", "scale_exp", "planes", "p_level")
+        conn.send((dt, [{k: m[k] for k in keep if k in m} for m in msgs]))
+    finally:
+        conn.close()
+
+
+def cpu_baseline(w, G, budget_s=25.0, max_cores=16):
+    """The oracle as it stands on a bounded sample of the same workload, step 0: compress of every sampled row +
+    the aggregate of their messages.  Two legs: one thread, and one worker row per task over the host cores
+    (processes forked before anything touches the GPU; each times its own rows from a common start, the leg's time
+    is the slowest process + the single-threaded aggregate).  Must be called before the GPU is initialised."""
+    import multiprocessing as mp
+    s_in = 2 if w.dtype == "bf16" else 4
+    # leg 1: a single thread, first rows until about a third of the budget is spent
+    t0 = time.perf_counter()
+    msgs = []
+    for i in range(w.M):
+        msgs.append(_oracle_row(w, G[i], i))
+        if time.perf_counter() - t0 > budget_s / 3 * 0.8:
+            break
+    rows1 = len(msgs)
+    _oracle_aggregate(w, msgs)
+    dt1 = time.perf_counter() - t0
+    per_row = dt1 / rows1
+    single = {"value": rows1 * w.d * s_in / dt1 / 1e9, "unit": "GB/s", "cores": 1,
+              "sample": f"{rows1} of {w.M} rows of {w.name} (d={w.d}), step 0: compress + aggregate, {dt1:.1f} s"}
+    del msgs
+    # leg 2: rows over the cores; as many rows as fit the rest of the budget (a process slows down when all run)
+    cores = max(1, min(max_cores, os.cpu_count() or 1, w.M))
+    rounds = max(1, int((budget_s * 2 / 3) / (per_row * 1.6)))
+    rows2 = min(w.M, cores * rounds)
+    ctx = mp.get_context("fork")
+    barrier = ctx.Barrier(cores + 1)
+    procs, conns = [], []
+    for c in range(cores):
+        parent, child = ctx.Pipe(duplex=False)
+        pr = ctx.Process(target=_cpu_child, args=(w, G, list(range(c, rows2, cores)), barrier, child))
+        pr.start()
+        child.close()
+        procs.append(pr)
+        conns.append(parent)
+    barrier.wait()
+    results = [c.recv() for c in conns]
+    for pr in procs:
+        pr.join()
+    slowest = max(r[0] for r in results)
+    by_row = {}
+    for c, (_, ms) in enumerate(results):
+        for k, m in enumerate(ms):
+            by_row[c + k * cores] = m
+    t2 = time.perf_counter()
+    _oracle_aggregate(w, [by_row[i] for i in range(rows2)])
+    dt2 = slowest + time.perf_counter() - t2
+    return {"value": rows2 * w.d * s_in / dt2 / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "sample": f"{rows2} of {w.M} rows of {w.name} (d={w.d}), step 0, one row per task over {cores} processes: "
+                      f"compress {slowest:.1f} s (slowest process) + aggregate, {dt2:.1f} s",
+            "single_thread": single}
 
 
 def main():
@@ -95,6 +173,8 @@ def main():
     ap.add_argument("--no-staging", action="store_true",
                     help="Top-k: write every message by a second read of the rows (tuning hook off; same results)")
     ap.add_argument("--cpu-budget", type=float, default=25.0)
+    ap.add_argument("--print-kernel-digest", action="store_true",
+                    help="print the sha256 that names the kernel sources (profile summaries quote it) and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device copy (a known-size kernel to scale profiler byte counters by)")
     args = ap.parse_args()
@@ -103,13 +183,23 @@ def main():
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
-    import torch
-    import paper_2507_05508_amd as P
+    if args.print_kernel_digest:
+        print(kernel_sources_digest())
+        return
 
     w = W.WORKLOADS[args.workload]
     t_gen = time.perf_counter()
     G = W.generate(w)
     print(f"[bench] generated {w.name}: M={w.M} d={w.d} {w.dtype} in {time.perf_counter() - t_gen:.1f} s", file=sys.stderr, flush=True)
+    # the CPU baseline runs first: its worker processes are forked while this process holds no GPU state
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(w, G, args.cpu_budget)
+        print(f"[bench] cpu baseline: {cpu['value']:.4f} GB/s on {cpu['cores']} cores, "
+              f"{cpu['single_thread']['value']:.4f} GB/s on one", file=sys.stderr, flush=True)
+
+    import torch
+    import paper_2507_05508_amd as P
     dev = torch.device("cuda:0")
     if w.dtype == "bf16":
         g = torch.from_numpy(G.view(np.int16)).to(dev).view(torch.bfloat16)
@@ -204,6 +294,7 @@ def main():
         step_alg_bytes = in_bytes + 2 * planes_avg + 4 * w.d
 
     value = in_bytes / (ms_per_step * 1e-3) / 1e9
+    traffic, traffic_from = measured_traffic(w.name, dominant)
     result = {
         "metric": "mlmc_compress_aggregate_input_throughput",
         "value": round(value, 2),
@@ -227,14 +318,13 @@ def main():
         "drawn_levels": {str(l): n for l, n in sorted(drawn.items())},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": measured_traffic(w.name, dominant),
+                     "traffic": traffic, "traffic_from": traffic_from,
                      "avg_us": round(dom_avg_s * 1e6, 2), "algorithmic_bytes_per_launch": int(dom_bytes)},
         "kernels": {k: {"avg_us": round(v["avg_us"], 2), "launches": v["launches"], "share": round(v["share"], 4)}
                     for k, v in sorted(kern.items(), key=lambda kv: -kv[1]["share"])},
     }
-    if not args.no_cpu_baseline:
-        del g
-        result["cpu_baseline"] = cpu_baseline(w, G, args.cpu_budget)
+    if cpu is not None:
+        result["cpu_baseline"] = cpu
     print(json.dumps(result), flush=True)
 
 

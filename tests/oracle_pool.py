@@ -6,7 +6,7 @@ their row from (workload, row index), so no input crosses the process boundary. 
 """
 import multiprocessing as mp
 import os
-from concurrent.futures import ProcessPoolExecutor
+from concurrent.futures import ProcessPoolExecutor, as_completed
 
 import numpy as np
 
@@ -31,15 +31,32 @@ def _topk_row(args):
     return row, out
 
 
+class OracleTopkRows:
+    """O.compress_topk_row on rows of WORKLOADS[name] (or of its scaled version) for every step in `steps`, started
+    in `workers` processes (default min(rows, cores, 8)) when the object is made; result() waits and returns
+    {row: [message of every step]}, printing a line per finished row."""
+
+    def __init__(self, name, seed, steps, rows=None, p_fixed=None, d=None, M=None, workers=None):
+        w = W.WORKLOADS[name] if d is None else W.scaled(W.WORKLOADS[name], d=d, M=M)
+        rows = list(range(w.M)) if rows is None else list(rows)
+        if workers is None:
+            workers = max(1, min(len(rows), os.cpu_count() or 1, 8))
+        self.name = name
+        self.tasks = [(name, d, M, r, seed, tuple(steps), p_fixed) for r in rows]
+        self.ex = ProcessPoolExecutor(max_workers=workers, mp_context=mp.get_context("spawn"))
+        self.futures = [self.ex.submit(_topk_row, t) for t in self.tasks]
+
+    def result(self):
+        out = {}
+        try:
+            for f in as_completed(self.futures):
+                row, msgs = f.result()
+                out[row] = msgs
+                print(f"oracle: {self.name} row {row} done ({len(out)} of {len(self.futures)})", flush=True)
+        finally:
+            self.ex.shutdown(wait=True, cancel_futures=True)
+        return out
+
+
 def oracle_topk_rows(name, seed, steps, rows=None, p_fixed=None, d=None, M=None, workers=None):
-    """{row: [message of every step in `steps`]} from O.compress_topk_row, rows of WORKLOADS[name] (or of its
-    scaled version).  `workers` processes, default min(rows, cores, 8)."""
-    w = W.WORKLOADS[name] if d is None else W.scaled(W.WORKLOADS[name], d=d, M=M)
-    rows = list(range(w.M)) if rows is None else list(rows)
-    if workers is None:
-        workers = max(1, min(len(rows), os.cpu_count() or 1, 8))
-    tasks = [(name, d, M, r, seed, tuple(steps), p_fixed) for r in rows]
-    if workers == 1:
-        return dict(_topk_row(t) for t in tasks)
-    with ProcessPoolExecutor(max_workers=workers, mp_context=mp.get_context("spawn")) as ex:
-        return dict(ex.map(_topk_row, tasks))
+    return OracleTopkRows(name, seed, steps, rows, p_fixed, d, M, workers).result()

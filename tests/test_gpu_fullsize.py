@@ -1,8 +1,6 @@
-"""Parity at the full BASELINE sizes, in the launch configuration bench.py times: the oracle checks sampled
-rows element by element; every row is checked through properties that hold at any size, computed with torch
-library routines (sort, gather, indexed add) rather than with this library's kernels."""
-import math
-
+"""Parity at the full BASELINE sizes, in the launch configuration bench.py times: every row of every full-size
+workload is compared with the CPU oracle element by element (levels, norms, indices, values, offsets), and the dense
+update with the oracle's aggregate of its own messages.  The oracle runs in worker processes, one row per task."""
 import numpy as np
 import pytest
 import torch
@@ -10,8 +8,9 @@ import torch
 import mlmc_workloads as W
 import paper_2507_05508_amd as P
 from oracle import mlmc as O
+from oracle_pool import OracleTopkRows
 
-pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(1500)]
 
 
 def _upload(G):
@@ -20,84 +19,60 @@ def _upload(G):
     return torch.from_numpy(G).to("cuda:0")
 
 
-def _keys(grow: torch.Tensor) -> torch.Tensor:
-    return grow.float().view(torch.int32) & 0x7FFFFFFF
+def _compare_with_oracle(tag, w, plan, msg, out, want_rows, alpha):
+    """One compress + aggregate call against the oracle's messages of all rows (bit for bit)."""
+    level = msg.level.cpu().numpy()
+    row_off = msg.row_off.cpu().numpy()
+    idx = msg.idx.cpu().numpy().view(np.uint32)
+    val = msg.val.cpu().numpy().view(np.uint32)
+    norms = msg.norms.cpu().numpy() if w.adaptive else None
+    tile_off = msg.tile_off.cpu().numpy().view(np.uint32)
+    off = 0
+    for i in range(w.M):
+        m = want_rows[i]
+        assert level[i] == m["level"], (tag, i, level[i], m["level"])
+        if w.adaptive:
+            assert np.array_equal(norms[i].view(np.uint64), np.array(m["norms"], dtype=np.float64).view(np.uint64)), (tag, i)
+        n = len(m["idx"])
+        assert n == w.ladder[0] + w.ladder[m["level"]] - w.ladder[m["level"] - 1]
+        assert row_off[i] == off, (tag, i)
+        assert np.array_equal(idx[off:off + n], m["idx"]), f"{tag} row {i}: indices differ"
+        assert np.array_equal(val[off:off + n], m["val"].view(np.uint32)), f"{tag} row {i}: values differ"
+        bounds = np.searchsorted(m["idx"], np.arange(plan.num_tiles + 1, dtype=np.int64) * P.MLMC_TILE, side="left")
+        assert np.array_equal(tile_off[i], bounds.astype(np.uint32)), f"{tag} row {i}: tile offsets differ"
+        off += n
+    assert row_off[w.M] == off
+    ref = O.aggregate_sparse([want_rows[i] for i in range(w.M)], w.d, alpha)
+    assert np.array_equal(out.cpu().numpy().view(np.uint32), ref.view(np.uint32)), f"{tag}: dense update differs"
 
 
-def _topk_mask(keys, srt, kk):
-    """Boolean mask of the kk entries of largest key, equal keys by lower index (definition, via torch)."""
-    mask = torch.zeros_like(keys, dtype=torch.bool)
-    if kk <= 0:
-        return mask
-    tau = int(srt[kk - 1])
-    mask |= keys > tau
-    q = kk - int(mask.sum())
-    eq = torch.nonzero(keys == tau).flatten()[:q]
-    mask[eq] = True
-    return mask
-
-
-def _check_row_properties(w, g, msg, i, p_row):
-    """Row i of a Top-k message equals the definition evaluated with torch sort / nonzero / gather."""
-    level = int(msg.level[i])
-    s, e = int(msg.row_off[i]), int(msg.row_off[i + 1])
-    k = w.ladder
-    assert e - s == k[0] + k[level] - k[level - 1]
-    keys = _keys(g[i])
-    srt = torch.sort(keys, descending=True).values
-    base = _topk_mask(keys, srt, k[0])
-    band = _topk_mask(keys, srt, k[level]) & ~_topk_mask(keys, srt, k[level - 1])
-    want_idx = torch.nonzero(base | band).flatten()
-    assert torch.equal(msg.idx[s:e].long(), want_idx)
-    wgt = np.float32(1.0 / p_row[level - 1]) if p_row[level - 1] != 0 else np.float32(0)
-    gv = g[i].float()[want_idx]
-    want_val = torch.where(base[want_idx], gv, gv * torch.tensor(wgt, device=g.device))
-    assert torch.equal(msg.val[s:e].view(torch.int32), want_val.view(torch.int32))
-
-
-@pytest.mark.parametrize("name,sample_rows", [("resnet50_adaptive_topk", (0, 11)), ("resnet18_topk", (5,))])
-def test_topk_full_size(name, sample_rows):
+# steps: one ordinary step, and one in which (by the oracle's own draw) some row draws level 1 and some row level L
+@pytest.mark.parametrize("name,steps", [("resnet50_adaptive_topk", (3, 15)), ("resnet18_topk", (3, 266))])
+def test_topk_full_size(name, steps):
     w = W.WORKLOADS[name]
-    print(f"generating {name}", flush=True)
-    G = W.generate(w)
-    g = _upload(G)
     pf = None if w.adaptive else O.geometric_p(w.L)
+    print(f"{name}: oracle on all {w.M} rows, steps {steps} (worker processes)", flush=True)
+    pool = OracleTopkRows(name, w.seed, steps, p_fixed=pf)
+    print(f"{name}: generating the rows", flush=True)
+    g = _upload(W.generate(w))
+    want = pool.result()
+    drawn = {want[i][s]["level"] for i in range(w.M) for s in range(len(steps))}
+    assert 1 in drawn and w.L in drawn, drawn      # the narrowest and the widest band both reach full size
     plan = P.Plan(P.MLMC_TOPK, w.M, w.d, P.MLMC_F32, w.ladder, pf)
     msg = P.SparseMessage(plan, with_norms=w.adaptive)
-    seed, step = w.seed, 3
-    print(f"{name}: compress + aggregate on the GPU", flush=True)
-    P.mlmc_compress_topk(plan, g, seed=seed, step=step, out=msg)
-    out = P.mlmc_aggregate(plan, msg, 1.0 / w.M)
-    torch.cuda.synchronize()
-    assert plan.status() == 0
-    norms = msg.norms.cpu().numpy() if w.adaptive else None
-    # all rows: properties
-    for i in range(w.M):
-        print(f"{name}: properties of row {i}", flush=True)
-        p_row = O.adaptive_p(list(norms[i])) if w.adaptive else pf
-        if w.adaptive:   # Pythagoras: sum of squared norms + base = ||g||^2 (fp64 check of the exact sums)
-            tot = float((g[i].double() ** 2).sum())
-            base = float((torch.sort(g[i].abs(), descending=True).values[:w.ladder[0]].double() ** 2).sum())
-            assert abs(float((norms[i] ** 2).sum()) + base - tot) <= 1e-9 * tot
-        _check_row_properties(w, g, msg, i, p_row)
-    # aggregate: fp32 adds in worker order, recomputed with torch indexed adds
-    acc = torch.zeros(w.d, dtype=torch.float32, device=g.device)
-    for i in range(w.M):
-        s, e = int(msg.row_off[i]), int(msg.row_off[i + 1])
-        ii = msg.idx[s:e].long()
-        acc[ii] = acc[ii] + msg.val[s:e]
-    assert torch.equal((acc * (1.0 / w.M)).view(torch.int32), out.view(torch.int32))
-    # sampled rows: the oracle, element by element
-    row_off = msg.row_off.cpu().numpy()
-    for i in sample_rows:
-        print(f"{name}: oracle on row {i}", flush=True)
-        want = O.compress_topk_row(G[i], w.ladder, pf, seed, step, i)
-        s, e = row_off[i], row_off[i + 1]
-        assert int(msg.level[i]) == want["level"]
-        if w.adaptive:
-            assert np.array_equal(norms[i].view(np.uint64), np.array(want["norms"]).view(np.uint64))
-        assert np.array_equal(msg.idx[s:e].cpu().numpy().view(np.uint32), want["idx"])
-        assert np.array_equal(msg.val[s:e].cpu().numpy().view(np.uint32), want["val"].view(np.uint32))
+    alpha = 1.0 / w.M
+    for si, step in enumerate(steps):
+        for staging in (True, False):
+            tag = f"{name} step {step} staging {'on' if staging else 'off'}"
+            print(tag, flush=True)
+            plan.set_staging(staging)
+            msg.idx.fill_(-1)
+            msg.val.fill_(float("nan"))
+            P.mlmc_compress_topk(plan, g, seed=w.seed, step=step, out=msg)
+            out = P.mlmc_aggregate(plan, msg, alpha)
+            torch.cuda.synchronize()
+            assert plan.status() == 0
+            _compare_with_oracle(tag, w, plan, msg, out, {i: want[i][si] for i in range(w.M)}, alpha)
 
 
 def test_bits_full_size():
@@ -124,31 +99,15 @@ def test_bits_full_size():
 
 def test_topk_bf16_full_size():
     w = W.WORKLOADS["bert_adaptive_topk_bf16"]
-    print("generating bert_adaptive_topk_bf16 (4 x 1.2e8 Student-t entries)", flush=True)
-    G = W.generate(w)
-    g = _upload(G)
+    print("bert_adaptive_topk_bf16: oracle on all 4 rows of 1.2e8 entries (worker processes, a few minutes)", flush=True)
+    pool = OracleTopkRows(w.name, 0, (0,), workers=4)
+    print("bert_adaptive_topk_bf16: generating the rows", flush=True)
+    g = _upload(W.generate(w))
+    want = pool.result()
     plan = P.Plan(P.MLMC_TOPK, w.M, w.d, P.MLMC_BF16, w.ladder, None)
     msg = P.SparseMessage(plan, with_norms=True)
     P.mlmc_compress_topk(plan, g, seed=0, step=0, out=msg)
     out = P.mlmc_aggregate(plan, msg, 0.25)
     torch.cuda.synchronize()
     assert plan.status() == 0
-    norms = msg.norms.cpu().numpy()
-    for i in range(w.M):
-        print(f"bf16: properties of row {i}", flush=True)
-        _check_row_properties(w, g, msg, i, O.adaptive_p(list(norms[i])))
-    acc = torch.zeros(w.d, dtype=torch.float32, device=g.device)
-    for i in range(w.M):
-        s, e = int(msg.row_off[i]), int(msg.row_off[i + 1])
-        ii = msg.idx[s:e].long()
-        acc[ii] = acc[ii] + msg.val[s:e]
-    assert torch.equal((acc * 0.25).view(torch.int32), out.view(torch.int32))
-    i = 2
-    print("bf16: oracle on row 2 (about a minute)", flush=True)
-    want = O.compress_topk_row(G[i], w.ladder, None, 0, 0, i)
-    row_off = msg.row_off.cpu().numpy()
-    s, e = row_off[i], row_off[i + 1]
-    assert int(msg.level[i]) == want["level"]
-    assert np.array_equal(norms[i].view(np.uint64), np.array(want["norms"]).view(np.uint64))
-    assert np.array_equal(msg.idx[s:e].cpu().numpy().view(np.uint32), want["idx"])
-    assert np.array_equal(msg.val[s:e].cpu().numpy().view(np.uint32), want["val"].view(np.uint32))
+    _compare_with_oracle("bf16 step 0", w, plan, msg, out, {i: want[i][0] for i in range(w.M)}, 0.25)
