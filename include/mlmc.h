@@ -81,11 +81,13 @@ mlmc_status mlmc_plan(mlmc_plan_t **plan, int kind, int M, int64_t d, int in_dty
 void mlmc_plan_destroy(mlmc_plan_t *plan);
 
 /*
- * Tuning hook (MLMC_TOPK plans).  The rank thresholds of Top-k (Sec. 2.2, Sec. 3.2) are first located from a
+ * Tuning hook.  MLMC_TOPK plans: the rank thresholds of Top-k (Sec. 2.2, Sec. 3.2) are first located from a
  * histogram of one 1024-element block out of 2^shift of every row, then proven or refuted by exact counts
- * taken during the full read; a refuted row is redone from an exact histogram, so `shift` changes run time
- * only, never a result.  mlmc_plan picks the shift from d (0 for short rows = exact histogram at once).
- * 0 <= shift <= 12; MLMC_EINVAL otherwise.
+ * taken during the full read; a refuted row is redone from an exact histogram.  MLMC_BITS plans: the row scale
+ * (Sec. 3.1) is first taken from the largest entry of the same sample of blocks, the full read extracts the
+ * message under that scale and finds the true maximum; a row whose true maximum needs a larger scale is
+ * extracted again.  So `shift` changes run time only, never a result.  mlmc_plan picks the shift from d
+ * (0 for short rows = exact at once).  0 <= shift <= 12; MLMC_EINVAL otherwise.
  */
 mlmc_status mlmc_plan_set_sampling(mlmc_plan_t *plan, int shift);
 

@@ -33,7 +33,8 @@ def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objdir = os.path.join(PKG_DIR, "_build")
     os.makedirs(objdir, exist_ok=True)
-    compile_flags = [f for f in HIPCC_FLAGS if f != "-shared"] + ["-c", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    extra = os.environ.get("MLMC_EXTRA_HIPCC_FLAGS", "").split()   # development aid: extra -D switches for experiments
+    compile_flags = [f for f in HIPCC_FLAGS if f != "-shared"] + extra + ["-c", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
     objs = [os.path.join(objdir, s.replace(".hip", ".o")) for s in SOURCES]
     cmds = [[hipcc] + compile_flags + [os.path.join(CSRC, s), "-o", o] for s, o in zip(SOURCES, objs)]
     with ThreadPoolExecutor(max_workers=len(cmds)) as ex:

@@ -11,7 +11,6 @@
 
 namespace mlmc {
 mlmc_status topk_zero(const mlmc_plan_t* pl, void* ws, int32_t* dev_status, hipStream_t st);
-mlmc_status topk_draw(const DrawArgs& da, hipStream_t st);
 mlmc_status topk_select(const mlmc_plan_t* pl, const TopkArgs& a, bool sums, bool vec, hipStream_t st);
 mlmc_status topk_compact(const mlmc_plan_t* pl, const TopkArgs& a, bool vec, hipStream_t st);
 mlmc_status bits_compress(const mlmc_plan_t* pl, const BitsArgs& a, bool vec, hipStream_t st);
@@ -47,8 +46,8 @@ static mlmc_status static_scratch_of_current_device(void** out) {
 // ---- per-kernel HIP-event timing (off by default; not thread safe) ---------------------------------
 bool g_prof_on = false;
 static const char* const k_names[K_NUM] = {
-    "k_zero", "k_hist", "k_scan", "k_main", "k_fhist", "k_finish", "k_finish_rank", "redo_pass", "k_norms", "k_draw", "k_msgplan", "k_filter", "k_write",
-    "k_bits_max", "k_bits_extract", "k_agg_bits", "k_tileoff", "k_agg_sparse"};
+    "k_zero", "k_hist", "k_scan", "k_main", "k_fhist", "k_finish", "k_finish_rank", "redo_pass", "k_norms", "k_bits_prep", "k_msgplan", "k_filter", "k_write",
+    "k_bits_smax", "k_bits_extract", "k_bits_redo", "k_agg_bits", "k_tileoff", "k_agg_sparse"};
 struct ProfPair { int id; hipEvent_t e0, e1; };
 static std::vector<ProfPair> g_pending;
 static std::vector<ProfPair> g_free;
@@ -150,6 +149,7 @@ static void fill_bits_args(const mlmc_plan_t* pl, BitsArgs& b, const void* g, in
     b.nplanes = pl->nplanes;
     b.nwords = (pl->d + 63) / 64;
     b.chunk = pl->chunk;
+    b.sample_shift = pl->sample_shift;
     b.rinfo = ws ? (RowInfo*)(w + pl->off_rinfo) : nullptr;
     b.racc = ws ? (RowAcc*)(w + pl->off_racc) : nullptr;
     b.dev_status = dev_status;
@@ -326,7 +326,7 @@ mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dty
 void mlmc_plan_destroy(mlmc_plan_t* plan) { delete plan; }
 
 mlmc_status mlmc_plan_set_sampling(mlmc_plan_t* plan, int shift) {
-    if (!plan || plan->kind != MLMC_TOPK || shift < 0 || shift > 12) return MLMC_EINVAL;
+    if (!plan || shift < 0 || shift > 12) return MLMC_EINVAL;
     plan->sample_shift = shift;
     return MLMC_OK;
 }
@@ -406,19 +406,8 @@ mlmc_status mlmc_compress_bits(const mlmc_plan_t* plan, const void* g, int64_t l
     b.level = level;
     b.scale_exp = scale_exp;
     b.planes = planes;
-    DrawArgs da;
-    std::memset(&da, 0, sizeof(da));
-    da.M = plan->M;
-    da.L = plan->L;
-    for (int l = 0; l < plan->L; ++l) da.p_fixed[l] = plan->p[l];
-    da.seed = seed;
-    da.step = step;
-    da.rinfo = b.rinfo;
-    da.level = level;
-    mlmc_status rc = topk_zero(plan, ws, dev_status, st);
-    if (rc != MLMC_OK) return rc;
-    rc = topk_draw(da, st);
-    if (rc != MLMC_OK) return rc;
+    b.seed = seed;
+    b.step = step;
     return bits_compress(plan, b, vec_ok(plan, g, ld), st);
 }
 

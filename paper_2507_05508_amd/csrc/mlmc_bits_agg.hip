@@ -1,7 +1,10 @@
 // Fixed-point bit-wise MLMC (Sec. 3.1) and the server aggregate (Alg. 2 / Alg. 3) on gfx950.
 //
-//   k_bits_max      row maximum of the |g| keys (integer atomic max) -> power-of-two scale
-//   k_bits_extract  digits m_j = floor(|g_j| / s * 2^Q), sign plane + field planes packed by wave ballot
+//   k_bits_prep     level draw of every row
+//   k_bits_smax     largest |g| key of a sample of every row (integer atomic max) -> predicted power-of-two scale
+//   k_bits_extract  the one full read: digits floor(|g_j| / s * 2^F), sign plane + field planes packed by wave
+//                   ballot, and the true row maximum; a row whose true maximum has a larger exponent than the
+//                   sampled one is extracted again by a second launch (which returns at once for every other row)
 //   k_agg_bits      out = alpha * sum_i decode_i, rows added in worker order
 //   k_tileoff       (fallback) per-tile offsets of index-sorted sparse rows by binary search
 //   k_agg_sparse    atomic-free segmented scatter-add: one workgroup owns one dense tile
@@ -10,136 +13,267 @@
 namespace mlmc {
 
 // ---------------------------------------------------------------------------------------------------
-constexpr int BITS_MAX_CHUNKS = 4;
+// Level draw of every row (Alg. 2 "Sample l ~ p"), and the per-row state of the call set to its start values.
+__global__ __launch_bounds__(1024) void k_bits_prep(BitsArgs a) {
+    __shared__ double s_p[LMAX];
+    const int r = threadIdx.x;
+    if (r < a.L) s_p[r] = a.p_fixed[r];
+    if (r == 0) *a.dev_status = 0;
+    __syncthreads();
+    for (int row = r; row < a.M; row += 1024) {
+        const uint32_t x = philox_word0(a.seed, a.step, (uint32_t)row);
+        const int level = draw_from_p(s_p, a.L, x);
+        const double pl = s_p[level - 1];
+        RowInfo* ri = a.rinfo + row;
+        ri->level = level;
+        ri->weight = pl == 0.0 ? 0.0f : (float)__ddiv_rn(1.0, pl);
+        ri->draw_x = x;
+        a.level[row] = level;
+        a.racc[row].rowmax_key = 0u;
+        a.racc[row].smpmax_key = 0u;
+    }
+}
+
+// Largest |g| key of the sampled blocks of every row (block b of 1024 elements is sampled when b % S == S / 2,
+// S = 2^sample_shift; S = 1 reads the whole row and the result is the row maximum itself).
+constexpr int SMAX_THREADS = 512;
 template <int DT, bool VEC>
-__global__ __launch_bounds__(512) void k_bits_max(BitsArgs a) {
+__global__ __launch_bounds__(SMAX_THREADS) void k_bits_smax(BitsArgs a) {
     const int row = blockIdx.y;
-    const int64_t span = (int64_t)a.chunk * BITS_MAX_CHUNKS;   // several chunks per workgroup: long unchecked runs
-    const int64_t c0 = (int64_t)blockIdx.x * span;
-    const int64_t c1 = c0 + span < a.d ? c0 + span : a.d;
+    const int64_t S = (int64_t)1 << a.sample_shift, first = S >> 1;
+    const int64_t nblk = (a.d + 1023) / 1024;
+    const int64_t ns = nblk > first ? (nblk - first + S - 1) / S : 0;
     RowLoader<DT, VEC> ld(a.g, a.ld, a.d, row);
+    const uint32_t lane = lane_id(), wave = (uint32_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     uint32_t maxkey = 0;
-    constexpr int64_t STEP = 512 * 4;
-    int64_t j = c0 + (int64_t)threadIdx.x * 4;
-    for (; j + 3 * STEP + 4 <= c1; j += 4 * STEP) {   // four loads in flight, no bounds checks inside
+    for (int64_t i = (int64_t)blockIdx.x * (SMAX_THREADS / 64) + wave; i < ns; i += (int64_t)gridDim.x * (SMAX_THREADS / 64)) {
+        const int64_t blk = first + i * S;
+        const int64_t base = blk * 1024 + lane * 4;
         uint32_t b[4][4];
+        if ((blk + 1) * 1024 <= a.d) {   // a whole block: four loads in flight
 #pragma unroll
-        for (int u = 0; u < 4; ++u) ld.load4_full(j + u * STEP, b[u]);
+            for (int q = 0; q < 4; ++q) ld.load4_full(base + q * 256, b[q]);
+        } else {
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+            for (int q = 0; q < 4; ++q) ld.load4(base + q * 256, b[q]);   // past the end: +0
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                const uint32_t key = key_of_bits(b[u][c]);
+                const uint32_t key = key_of_bits(b[q][c]);
                 maxkey = key > maxkey ? key : maxkey;
             }
     }
-    for (; j < c1; j += STEP) {
-        uint32_t b[4];
-        int nv = ld.load4(j, b);
-        if (j + nv > c1) nv = (int)(c1 - j);
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            uint32_t key = c < nv ? key_of_bits(b[c]) : 0u;
-            maxkey = key > maxkey ? key : maxkey;
-        }
-    }
     maxkey = wave_max(maxkey);
-    if (lane_id() == 0) {
-        atomicMax(&a.racc[row].rowmax_key, maxkey);
+    if (lane == 0 && maxkey) {
+        atomicMax(&a.racc[row].smpmax_key, maxkey);
         if (maxkey >= 0x7F800000u) atomicOr(a.dev_status, MLMC_DEV_NONFINITE);
     }
 }
 
-// Per-row constants of the extraction / decode.
-struct BitsRow {
-    int level, Emax, Q, F0, Fl, width;
-};
-__device__ __forceinline__ BitsRow bits_row(const BitsArgs& a, int row) {
-    BitsRow r;
-    r.level = a.rinfo[row].level;
-    uint32_t E = a.racc[row].rowmax_key >> 23;
-    r.Emax = E ? (int)E : 1;
-    r.Q = a.F[a.L];
-    r.F0 = a.F[0];
-    r.Fl = a.F[r.level];
-    r.width = a.F[r.level] - a.F[r.level - 1];
-    return r;
+// v_writelane_b32 through its compiler intrinsic (this compiler has no builtin of that name): the result is `old`
+// with lane `lane` (uniform) replaced by the uniform value `sval`.  As an intrinsic, not inline assembly, so that
+// the compiler keeps the wait states the instruction needs after the compare that produced sval.
+extern "C" __device__ int mlmc_writelane_i32(int sval, int lane, int old) __asm("llvm.amdgcn.writelane.i32");
+__device__ __forceinline__ void put_lane(uint32_t& dst, uint32_t sval, int lane) {
+    dst = (uint32_t)mlmc_writelane_i32((int)sval, lane, (int)dst);
 }
 
 // One wave packs one tile of 4096 elements: iteration i covers elements [64 i, 64 i + 64) of the tile, so a
-// ballot is the plane word of those 64 elements; lane i keeps word i and the 64 words go out in one store.
-// NPC: compile-time bound on the planes of the row (its actual count np <= NPC), so that the per-slot loop over
-// planes is as long as needed and no longer.
-template <int DT, int NPC>
-__device__ __forceinline__ void bits_extract_row(const BitsArgs& a, int row, const BitsRow& br, int np) {
+// ballot is the plane word of those 64 elements; it is kept in lane i and the 64 words of a plane go out in one
+// store.  Emax is the exponent the scale is taken from.  NPC: compile-time bound on the planes of the row (np <= NPC);
+// BASE: the ladder has a base field (F_0 > 0).  Returns the largest key met, through maxkey.
+//
+// Digits (Sec. 3.1): |g| = sig * 2^(E' - 150), scale s = 2^(Emax - 126), so floor(|g| / s * 2^F) = sig >> (24 - F + Emax - E').
+// Bit b of (sig >> (24 - F_l + Emax - E')) for b < F_l - F_{l-1} is bit b of the level field.
+template <int DT, bool VEC, int NPC, bool BASE>
+__device__ __forceinline__ void bits_extract_tiles(const BitsArgs& a, int row, int Emax, int level, int np, uint32_t& maxkey,
+                                                   uint32_t* slds) {
     const uint32_t lane = lane_id(), wave = (uint32_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     RowLoader<DT, false> ld(a.g, a.ld, a.d, row);
+    RowLoader<DT, VEC> ld4(a.g, a.ld, a.d, row);
     const int64_t ntiles = (a.d + TILE - 1) / TILE;
-    // tiles (and rows) are taken from the end: what the scale pass read last is the part of the input that the
-    // memory-side cache most likely still holds
-    for (int64_t rt = (int64_t)blockIdx.x * 4 + wave; rt < ntiles; rt += (int64_t)gridDim.x * 4) {
-        const int64_t tile = ntiles - 1 - rt;
-        const int64_t base = tile * TILE;
-        uint64_t words[NPC];
+    const int64_t nwhole = a.d / TILE;   // tiles with all 4096 elements
+    const int F0 = a.F[0];
+    const uint32_t Cl = (uint32_t)(24 - a.F[level] + Emax), C0 = (uint32_t)(24 - F0 + Emax);
+    const uint32_t mask0 = BASE ? (1u << F0) - 1u : 0u;
+    uint32_t wlo[NPC], whi[NPC];   // lane i: word i of the tile's planes
 #pragma unroll
-        for (int p = 0; p < NPC; ++p) words[p] = 0;
-        auto digits = [&](uint32_t bits) -> uint32_t {
-            uint32_t key = key_of_bits(bits);
-            uint32_t E = key >> 23;
-            uint32_t sig = E ? ((key & 0x7FFFFFu) | 0x800000u) : (key & 0x7FFFFFu);
-            int shift = (24 - br.Q) + (br.Emax - (int)(E ? E : 1u));
-            uint32_t m = shift < 32 ? (sig >> shift) : 0u;   // floor(|g| / 2^e * 2^Q), e = Emax - 126
-            uint32_t f0 = br.F0 ? (m >> (br.Q - br.F0)) : 0u;
-            uint32_t f = (m >> (br.Q - br.Fl)) & ((1u << br.width) - 1u);
-            return (bits >> 31) | (f0 << 1) | (f << (1 + br.F0));  // plane p <-> bit p
-        };
-        auto pack = [&](int i, uint32_t packed) {
+    for (int p = 0; p < NPC; ++p) { wlo[p] = 0; whi[p] = 0; }
+    // plane p >= 1 <-> bit p - 1 of the value returned here (base field first, then the level field)
+    auto digits = [&](uint32_t bits) -> uint32_t {
+        const uint32_t key = key_of_bits(bits);
+        maxkey = key > maxkey ? key : maxkey;
+        const uint32_t E = key >> 23;
+        const uint32_t hid = (key & 0x7FFFFFu) | 0x800000u;
+        const uint32_t sig = key < hid ? key : hid;       // exponent field 0: no hidden bit
+        const uint32_t Ec = E > 1u ? E : 1u;
+        const uint32_t sl = Cl - Ec;                      // >= 32 (also "negative"): every digit is zero
+        const uint32_t x = sig >> (sl < 31u ? sl : 31u);
+        if (!BASE) return x;
+        const uint32_t s0 = C0 - Ec;
+        const uint32_t x0 = sig >> (s0 < 31u ? s0 : 31u);
+        return (x0 & mask0) | (x << F0);
+    };
+    // the ballots of iteration i (elements 64 i .. 64 i + 63 of the tile, one per lane) go to lane i of the tile's words
+    auto pack16 = [&](int g4, const uint32_t (&v)[16]) {
 #pragma unroll
-            for (int p = 0; p < NPC; ++p) {
-                if (p < np) {
-                    uint64_t w = __ballot((packed >> p) & 1u);
-                    if (lane == (uint32_t)i) words[p] = w;
+        for (int u = 0; u < 16; ++u) {
+            const int i = g4 * 16 + u;
+            const uint32_t bits = v[u];
+            const uint32_t x = digits(bits);
+            {
+                const uint64_t w = __ballot((int32_t)bits < 0);
+                put_lane(wlo[0], (uint32_t)w, i);
+                put_lane(whi[0], (uint32_t)(w >> 32), i);
+            }
+#pragma unroll
+            for (int p = 1; p < NPC; ++p) {
+                if (p < np) {   // uniform
+                    const uint64_t w = __ballot((x & (1u << (p - 1))) != 0u);
+                    put_lane(wlo[p], (uint32_t)w, i);
+                    put_lane(whi[p], (uint32_t)(w >> 32), i);
                 }
             }
-        };
-        if (base + TILE <= a.d) {   // a whole tile: sixteen loads in flight, no bounds checks inside
-            for (int i0 = 0; i0 < 64; i0 += 16) {
-                uint32_t v[16];
-#pragma unroll
-                for (int u = 0; u < 16; ++u) v[u] = ld.load1_stream(base + (i0 + u) * 64 + lane);
-#pragma unroll
-                for (int u = 0; u < 16; ++u) pack(i0 + u, digits(v[u]));
-            }
-        } else {
-            for (int i = 0; i < 64; ++i) {
-                const int64_t j = base + i * 64 + lane;
-                const uint32_t bits = j < a.d ? ld.load1(j) : 0u;
-                pack(i, digits(bits));
-            }
         }
+    };
+    auto store_words = [&](int64_t tile) {
         const int64_t w0 = tile * 64 + lane;
         if (w0 < a.nwords) {
             uint64_t* dst = a.planes + (size_t)row * a.nplanes * a.nwords + w0;
 #pragma unroll
             for (int p = 0; p < NPC; ++p)
-                if (p < np) dst[(size_t)p * a.nwords] = words[p];
+                if (p < np) dst[(size_t)p * a.nwords] = ((uint64_t)whi[p] << 32) | wlo[p];
         }
+    };
+    const int64_t first = (int64_t)blockIdx.x * 4 + wave, stride = (int64_t)gridDim.x * 4;
+    int64_t tile = first;
+    if (VEC) {
+        // Whole tiles of an aligned row: sixteen 16-byte loads per lane and tile (a load covers 256 consecutive
+        // elements, four per lane), eight in flight, also across the wave's tiles.  Four loads at a time pass
+        // through the wave's LDS buffer, written as loaded and read back one element per lane, so that a ballot
+        // is a plane word.
+        uint32_t bufA[4][4], bufB[4][4];
+        auto fetch4 = [&](int64_t t, int l0, uint32_t (&buf)[4][4]) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) ld4.load4_stream(t * TILE + (int64_t)((l0 + q) * 256) + (int64_t)lane * 4, buf[q]);
+        };
+        auto transpose16 = [&](const uint32_t (&buf)[4][4], uint32_t (&v)[16]) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                *(uint4*)(slds + q * 256 + lane * 4) = make_uint4(buf[q][0], buf[q][1], buf[q][2], buf[q][3]);
+            wave_lds_sync();
+#pragma unroll
+            for (int u = 0; u < 16; ++u) v[u] = slds[u * 64 + lane];
+            wave_lds_sync();   // the next writes come after these reads
+        };
+        if (tile < nwhole) {
+            fetch4(tile, 0, bufA);
+            fetch4(tile, 4, bufB);
+        }
+        for (; tile < nwhole; tile += stride) {
+            const bool more = tile + stride < nwhole;   // uniform
+            uint32_t v[16];
+            transpose16(bufA, v);
+            fetch4(tile, 8, bufA);
+            pack16(0, v);
+            transpose16(bufB, v);
+            fetch4(tile, 12, bufB);
+            pack16(1, v);
+            transpose16(bufA, v);
+            if (more) fetch4(tile + stride, 0, bufA);
+            pack16(2, v);
+            transpose16(bufB, v);
+            if (more) fetch4(tile + stride, 4, bufB);
+            pack16(3, v);
+            store_words(tile);
+        }
+    } else {
+        // a row that is not aligned for 16-byte loads: one element per lane and load, sixteen loads in flight
+        for (; tile < nwhole; tile += stride) {
+            for (int g4 = 0; g4 < 4; ++g4) {
+                uint32_t v[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) v[u] = ld.load1_stream(tile * TILE + (g4 * 16 + u) * 64 + lane);
+                pack16(g4, v);
+            }
+            store_words(tile);
+        }
+    }
+    if (tile < ntiles) {   // the ragged last tile of the row (one wave of the row gets here)
+        const int64_t base = tile * TILE;
+#pragma unroll
+        for (int p = 0; p < NPC; ++p) { wlo[p] = 0; whi[p] = 0; }
+        for (int i = 0; i < 64; ++i) {
+            const int64_t j = base + i * 64 + lane;
+            const uint32_t bits = j < a.d ? ld.load1(j) : 0u;
+            const uint32_t x = digits(bits);
+            const bool me = (int)lane == i;
+            {
+                const uint64_t w = __ballot((int32_t)bits < 0);
+                wlo[0] = me ? (uint32_t)w : wlo[0];
+                whi[0] = me ? (uint32_t)(w >> 32) : whi[0];
+            }
+#pragma unroll
+            for (int p = 1; p < NPC; ++p) {
+                if (p < np) {   // uniform
+                    const uint64_t w = __ballot((x & (1u << (p - 1))) != 0u);
+                    wlo[p] = me ? (uint32_t)w : wlo[p];
+                    whi[p] = me ? (uint32_t)(w >> 32) : whi[p];
+                }
+            }
+        }
+        store_words(tile);
     }
 }
 
-// One wave packs one tile of 4096 elements: iteration i covers elements [64 i, 64 i + 64) of the tile, so a
-// ballot is the plane word of those 64 elements; lane i keeps word i and the 64 words go out in one store.
-template <int DT>
+// The row's message under the scale taken from the sampled maximum; the true maximum of the row is tracked on the
+// way.  REDO (second launch, only when the maximum was sampled): rows whose true maximum has a larger exponent than
+// the sampled one are extracted again with the true one; every other row is already final and is skipped.
+// NPCMAX: bound on the planes of any row of the plan (the kernel holds only the variants it can need, so that a
+// plan with few planes is not charged the registers of the widest one).
+template <int DT, bool VEC, bool REDO, int NPCMAX>
 __global__ __launch_bounds__(256) void k_bits_extract(BitsArgs a) {
-    const int row = a.M - 1 - (int)blockIdx.y;
-    const BitsRow br = bits_row(a, row);
-    const int np = 1 + br.F0 + br.width;  // planes written for this row
-    if (blockIdx.x == 0 && threadIdx.x == 0) a.scale_exp[row] = br.Emax - 126;
-    if (np <= 3) bits_extract_row<DT, 3>(a, row, br, np);
-    else if (np <= 5) bits_extract_row<DT, 5>(a, row, br, np);
-    else if (np <= 9) bits_extract_row<DT, 9>(a, row, br, np);
-    else if (np <= 17) bits_extract_row<DT, 17>(a, row, br, np);
-    else bits_extract_row<DT, MAX_PLANES>(a, row, br, np);
+    __shared__ __align__(16) uint32_t s_tr[4][1024];   // per wave: four loads of 256 elements on their way from "four per lane" to "one per lane"
+    uint32_t* slds = s_tr[threadIdx.x >> 6];
+    const int row = blockIdx.y;
+    RowAcc* ra = a.racc + row;
+    const uint32_t Es = ra->smpmax_key >> 23;
+    uint32_t Ex = Es;
+    if (REDO) {
+        Ex = ra->rowmax_key >> 23;
+        if (Ex == Es) return;
+    }
+    const int Emax = Ex ? (int)Ex : 1;
+    const int level = a.rinfo[row].level;
+    const int F0 = a.F[0];
+    const int np = 1 + F0 + (a.F[level] - a.F[level - 1]);   // planes written for this row
+    if (blockIdx.x == 0 && threadIdx.x == 0) a.scale_exp[row] = Emax - 126;
+    uint32_t maxkey = 0;
+    if (F0 == 0) {
+        if (np <= 3) bits_extract_tiles<DT, VEC, 3, false>(a, row, Emax, level, np, maxkey, slds);
+        else if (np <= 5) bits_extract_tiles<DT, VEC, 5, false>(a, row, Emax, level, np, maxkey, slds);
+        else if (np <= 9) bits_extract_tiles<DT, VEC, 9, false>(a, row, Emax, level, np, maxkey, slds);
+        else if constexpr (NPCMAX > 9) {
+            if (np <= 17) bits_extract_tiles<DT, VEC, 17, false>(a, row, Emax, level, np, maxkey, slds);
+            else bits_extract_tiles<DT, VEC, MAX_PLANES, false>(a, row, Emax, level, np, maxkey, slds);
+        }
+    } else {
+        if (np <= 5) bits_extract_tiles<DT, VEC, 5, true>(a, row, Emax, level, np, maxkey, slds);
+        else if (np <= 9) bits_extract_tiles<DT, VEC, 9, true>(a, row, Emax, level, np, maxkey, slds);
+        else if constexpr (NPCMAX > 9) {
+            if (np <= 17) bits_extract_tiles<DT, VEC, 17, true>(a, row, Emax, level, np, maxkey, slds);
+            else bits_extract_tiles<DT, VEC, MAX_PLANES, true>(a, row, Emax, level, np, maxkey, slds);
+        }
+    }
+    if (!REDO) {
+        maxkey = wave_max(maxkey);
+        if (lane_id() == 0 && maxkey) {
+            atomicMax(&ra->rowmax_key, maxkey);
+            if (maxkey >= 0x7F800000u) atomicOr(a.dev_status, MLMC_DEV_NONFINITE);
+        }
+    }
 }
 
 struct AggBitsArgs {
@@ -152,9 +286,10 @@ struct AggBitsArgs {
 };
 
 // out[j] = alpha * sum over rows (worker order) of sign * (f0 * c0 + f * cl): Alg. 2 "Server aggregates".
-// A wave owns word w of every plane, i.e. elements 64 w .. 64 w + 63 (lane = element).  The words it needs (one
-// per row and plane) are fetched by different lanes in one load per group of rows; a word is then read from its
-// lane as a wave-wide mask whose bit `lane` is the element's bit.  NPC bounds the planes of any row.
+// A wave owns eight consecutive words of every plane, i.e. 512 consecutive elements; lane = element within a word.
+// The words are fetched 64 at a time, lane (q, k) = (lane / 8, lane % 8) taking word k of a row's plane q (so a
+// load instruction moves whole 64-byte sectors); a word is then read from its lane as a wave-wide mask whose bit
+// `lane` is the element's bit.  NPC bounds the planes of any row.
 template <int NPC>
 __global__ __launch_bounds__(256) void k_agg_bits(AggBitsArgs a) {
     __shared__ float s_c0[MLMC_MAX_WORKERS], s_cl[MLMC_MAX_WORKERS];
@@ -170,48 +305,63 @@ __global__ __launch_bounds__(256) void k_agg_bits(AggBitsArgs a) {
         s_w[r] = (uint8_t)(b.F[lev] - b.F[lev - 1]);
     }
     __syncthreads();
-    constexpr int RPG = 64 / NPC;   // rows whose words fit one register across the wave
+    constexpr int PL = (NPC + 7) / 8;   // load instructions per row
     const uint32_t lane = lane_id();
-    const int rr_l = (int)lane / NPC, pp_l = (int)lane % NPC;
+    const int q_l = (int)lane >> 3, k_l = (int)lane & 7;
     const int64_t nw = b.nwords;
+    const int64_t nblk = (nw + 7) / 8;
     const int64_t wave_global = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 6;
     const int64_t nwaves = ((int64_t)gridDim.x * 256) >> 6;
-    for (int64_t w = wave_global; w < nw; w += nwaves) {
-        float acc = 0.0f;
-        for (int r0 = 0; r0 < b.M; r0 += RPG) {
-            uint64_t mine = 0;
-            {
-                const int r = r0 + rr_l;
-                if (rr_l < RPG && r < b.M && pp_l < 1 + F0 + (int)s_w[r])
-                    mine = a.planes[((size_t)r * b.nplanes + pp_l) * nw + w];
-            }
+    for (int64_t blk = wave_global; blk < nblk; blk += nwaves) {
+        const int64_t w0 = blk * 8;
+        const bool wok = w0 + k_l < nw;
+        float acc[8];
 #pragma unroll
-            for (int rr = 0; rr < RPG; ++rr) {
-                const int r = r0 + rr;
-                if (r < b.M) {   // uniform
-                const int np = 1 + F0 + (int)s_w[r];
+        for (int k = 0; k < 8; ++k) acc[k] = 0.0f;
+        auto fetch = [&](int r, uint64_t (&m)[PL]) {
+            const int np = r < b.M ? 1 + F0 + (int)s_w[r] : 0;
+#pragma unroll
+            for (int u = 0; u < PL; ++u) {
+                const int p = u * 8 + q_l;
+                m[u] = (wok && p < np) ? a.planes[((size_t)r * b.nplanes + p) * nw + w0 + k_l] : 0ull;
+            }
+        };
+        uint64_t mine[PL], next[PL];
+        fetch(0, mine);
+        for (int r = 0; r < b.M; ++r) {   // rows in worker order; the next row's words are on their way meanwhile
+            fetch(r + 1, next);
+            const int np = 1 + F0 + (int)s_w[r];
+            const float c0 = s_c0[r], cl = s_cl[r];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
                 uint32_t f0 = 0, f = 0;
 #pragma unroll
                 for (int p = 1; p < NPC; ++p) {
                     if (p < np) {   // uniform
-                        const uint64_t word = ((uint64_t)__builtin_amdgcn_readlane((uint32_t)(mine >> 32), rr * NPC + p) << 32) |
-                                              (uint32_t)__builtin_amdgcn_readlane((uint32_t)mine, rr * NPC + p);
+                        const uint64_t m = mine[p >> 3];
+                        const uint64_t word = ((uint64_t)__builtin_amdgcn_readlane((uint32_t)(m >> 32), (p & 7) * 8 + k) << 32) |
+                                              (uint32_t)__builtin_amdgcn_readlane((uint32_t)m, (p & 7) * 8 + k);
                         const bool bit = __builtin_amdgcn_inverse_ballot_w64(word);
                         if (p <= F0) f0 |= bit ? 1u << (p - 1) : 0u;
                         else f |= bit ? 1u << (p - 1 - F0) : 0u;
                     }
                 }
-                const uint64_t sw = ((uint64_t)__builtin_amdgcn_readlane((uint32_t)(mine >> 32), rr * NPC) << 32) |
-                                    (uint32_t)__builtin_amdgcn_readlane((uint32_t)mine, rr * NPC);
+                const uint64_t m0 = mine[0];
+                const uint64_t sw = ((uint64_t)__builtin_amdgcn_readlane((uint32_t)(m0 >> 32), k) << 32) |
+                                    (uint32_t)__builtin_amdgcn_readlane((uint32_t)m0, k);
                 const bool sign = __builtin_amdgcn_inverse_ballot_w64(sw);
-                float v = __fmul_rn((float)f, s_cl[r]);
-                if (F0 > 0) v = __fadd_rn(__fmul_rn((float)f0, s_c0[r]), v);
-                acc = __fadd_rn(acc, sign ? -v : v);
-                }
+                float v = __fmul_rn((float)f, cl);
+                if (F0 > 0) v = __fadd_rn(__fmul_rn((float)f0, c0), v);
+                acc[k] = __fadd_rn(acc[k], sign ? -v : v);
             }
+#pragma unroll
+            for (int u = 0; u < PL; ++u) mine[u] = next[u];
         }
-        const int64_t j = w * 64 + lane;
-        if (j < b.d) __builtin_nontemporal_store(__fmul_rn(a.alpha, acc), &a.out[j]);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int64_t j = (w0 + k) * 64 + lane;
+            if (j < b.d) __builtin_nontemporal_store(__fmul_rn(a.alpha, acc[k]), &a.out[j]);
+        }
     }
 }
 
@@ -326,22 +476,50 @@ __global__ __launch_bounds__(256) void k_agg_sparse(AggSparseArgs a) {
 
 // ---------------------------------------------------------------------------------------------------
 mlmc_status bits_compress(const mlmc_plan_t* pl, const BitsArgs& a, bool vec, hipStream_t st) {
-    dim3 grid((pl->chunks_per_row + BITS_MAX_CHUNKS - 1) / BITS_MAX_CHUNKS, pl->M);
+    MLMC_LAUNCH(K_DRAW, st, k_bits_prep<<<1, 1024, 0, st>>>(a));
+    // sampled (or, for short rows, exact) row maxima
+    const int64_t nblk = (pl->d + 1023) / 1024;
+    const int64_t ns = (nblk >> a.sample_shift) > 0 ? (nblk >> a.sample_shift) : 1;
+    int64_t sw = (ns + 7) / 8;   // a block per wave
+    const int64_t scap = 4096 / pl->M > 0 ? 4096 / pl->M : 1;
+    if (sw > scap) sw = scap;
+    if (sw < 1) sw = 1;
+    const dim3 sgrid((unsigned)sw, pl->M);
     if (pl->dtype == MLMC_F32) {
-        if (vec) MLMC_LAUNCH(K_BITS_MAX, st, k_bits_max<MLMC_F32, true><<<grid, 512, 0, st>>>(a));
-        else MLMC_LAUNCH(K_BITS_MAX, st, k_bits_max<MLMC_F32, false><<<grid, 512, 0, st>>>(a));
+        if (vec) MLMC_LAUNCH(K_BITS_MAX, st, k_bits_smax<MLMC_F32, true><<<sgrid, SMAX_THREADS, 0, st>>>(a));
+        else MLMC_LAUNCH(K_BITS_MAX, st, k_bits_smax<MLMC_F32, false><<<sgrid, SMAX_THREADS, 0, st>>>(a));
     } else {
-        if (vec) MLMC_LAUNCH(K_BITS_MAX, st, k_bits_max<MLMC_BF16, true><<<grid, 512, 0, st>>>(a));
-        else MLMC_LAUNCH(K_BITS_MAX, st, k_bits_max<MLMC_BF16, false><<<grid, 512, 0, st>>>(a));
+        if (vec) MLMC_LAUNCH(K_BITS_MAX, st, k_bits_smax<MLMC_BF16, true><<<sgrid, SMAX_THREADS, 0, st>>>(a));
+        else MLMC_LAUNCH(K_BITS_MAX, st, k_bits_smax<MLMC_BF16, false><<<sgrid, SMAX_THREADS, 0, st>>>(a));
     }
+    // a wave takes about four tiles (its loads run ahead across tiles); at least some 2048 waves in all
     int64_t ntiles = pl->ntiles;
-    int gx = (int)((ntiles + 3) / 4);
+    int gx = (int)((ntiles + 15) / 16);
+    if ((int64_t)gx * pl->M < 512) gx = (int)((ntiles + 3) / 4);
     int cap = 4096 / pl->M > 0 ? 4096 / pl->M : 1;
     if (gx > cap) gx = cap;
     if (gx < 1) gx = 1;
     dim3 egrid(gx, pl->M);
-    if (pl->dtype == MLMC_F32) MLMC_LAUNCH(K_BITS_EXTRACT, st, k_bits_extract<MLMC_F32><<<egrid, 256, 0, st>>>(a));
-    else MLMC_LAUNCH(K_BITS_EXTRACT, st, k_bits_extract<MLMC_BF16><<<egrid, 256, 0, st>>>(a));
+    const bool small = pl->nplanes <= 9;
+#define MLMC_EXTRACT_V(ID, DT, VEC, REDO)                                                                               \
+    do {                                                                                                                \
+        if (small) MLMC_LAUNCH(ID, st, k_bits_extract<DT, VEC, REDO, 9><<<egrid, 256, 0, st>>>(a));                      \
+        else MLMC_LAUNCH(ID, st, k_bits_extract<DT, VEC, REDO, MAX_PLANES><<<egrid, 256, 0, st>>>(a));                   \
+    } while (0)
+#define MLMC_EXTRACT(ID, REDO)                                                                                          \
+    do {                                                                                                                \
+        if (pl->dtype == MLMC_F32) {                                                                                    \
+            if (vec) MLMC_EXTRACT_V(ID, MLMC_F32, true, REDO);                                                          \
+            else MLMC_EXTRACT_V(ID, MLMC_F32, false, REDO);                                                             \
+        } else {                                                                                                        \
+            if (vec) MLMC_EXTRACT_V(ID, MLMC_BF16, true, REDO);                                                         \
+            else MLMC_EXTRACT_V(ID, MLMC_BF16, false, REDO);                                                            \
+        }                                                                                                               \
+    } while (0)
+    MLMC_EXTRACT(K_BITS_EXTRACT, false);
+    if (a.sample_shift > 0) MLMC_EXTRACT(K_BITS_REDO, true);   // rows whose sampled maximum fell short (returns at once for the others)
+#undef MLMC_EXTRACT_V
+#undef MLMC_EXTRACT
     return MLMC_OK;
 }
 
@@ -354,7 +532,7 @@ mlmc_status agg_bits(const mlmc_plan_t* pl, const BitsArgs& b, const int32_t* le
     a.planes = planes;
     a.alpha = alpha;
     a.out = out;
-    int64_t waves = b.nwords;
+    int64_t waves = (b.nwords + 7) / 8;   // a wave takes eight words at a time
     int blocks = (int)((waves + 3) / 4);
     if (blocks > 8192) blocks = 8192;
     if (blocks < 1) blocks = 1;

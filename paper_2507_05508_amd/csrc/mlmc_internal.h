@@ -91,6 +91,8 @@ struct RowAcc {  // per row, zeroed at the start of every call (and again before
     uint32_t region_cnt[RMAX];
     uint32_t n_pieces;
     uint32_t rowmax_key;
+    uint32_t smpmax_key;          // bit-wise path: largest key of the sampled blocks (the scale is predicted from it)
+    uint32_t pad_;
     uint64_t gsum[GMAX][2];
     Piece pieces[PMAX];
 };
@@ -142,14 +144,6 @@ struct TopkArgs {
     int64_t capacity;
 };
 
-struct DrawArgs {
-    int32_t M, L;
-    double p_fixed[LMAX];
-    uint64_t seed, step;
-    RowInfo* rinfo;
-    int32_t* level;
-};
-
 struct BitsArgs {
     const void* g;
     int64_t ld, d;
@@ -159,6 +153,8 @@ struct BitsArgs {
     int32_t nplanes;         // planes per row in the message buffer
     int64_t nwords;          // ceil(d / 64)
     int32_t chunk;
+    int32_t sample_shift;    // the row maximum is first taken from one 1024-element block out of 2^sample_shift
+    uint64_t seed, step;
     RowInfo* rinfo;
     RowAcc* racc;
     int32_t* level;
@@ -170,7 +166,7 @@ struct BitsArgs {
 // ---- optional per-kernel timing with HIP events (host side, see mlmc_profile_* in mlmc.h) ----------
 enum KernelId {
     K_ZERO = 0, K_HIST, K_SCAN, K_MAIN, K_FHIST, K_FINISH, K_FINISH1, K_REDO, K_NORMS, K_DRAW, K_MSGPLAN, K_FILTER, K_WRITE,
-    K_BITS_MAX, K_BITS_EXTRACT, K_AGG_BITS, K_TILEOFF, K_AGG_SPARSE, K_NUM
+    K_BITS_MAX, K_BITS_EXTRACT, K_BITS_REDO, K_AGG_BITS, K_TILEOFF, K_AGG_SPARSE, K_NUM
 };
 extern bool g_prof_on;
 void prof_begin(int id, hipStream_t st);

@@ -1489,26 +1489,6 @@ __global__ __launch_bounds__(256) void k_norms(TopkArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Level draw for all rows of the bit-wise path (one workgroup).
-__global__ __launch_bounds__(1024) void k_draw(DrawArgs a) {
-    __shared__ double s_p[LMAX];
-    const int r = threadIdx.x;
-    if (r < a.L) s_p[r] = a.p_fixed[r];
-    __syncthreads();
-    if (r < a.M) {
-        const int L = a.L;
-        uint32_t x = philox_word0(a.seed, a.step, (uint32_t)r);
-        int level = draw_from_p(s_p, L, x);
-        double pl = s_p[level - 1];
-        RowInfo* ri = a.rinfo + r;
-        ri->level = level;
-        ri->weight = pl == 0.0 ? 0.0f : (float)__ddiv_rn(1.0, pl);
-        ri->draw_x = x;
-        a.level[r] = level;
-    }
-}
-
-// ---------------------------------------------------------------------------------------------------
 // Membership tests of the message (Eq. (6)): base band = top k_0; drawn band = top k_l without top k_{l-1}.
 struct Thr3 {
     uint32_t tau[3], jx[3];
@@ -1958,11 +1938,6 @@ mlmc_status topk_zero(const mlmc_plan_t* pl, void* ws, int32_t* dev_status, hipS
     if (blocks > 2048) blocks = 2048;
     if (blocks < 1) blocks = 1;
     MLMC_LAUNCH(K_ZERO, st, k_zero<<<blocks, 256, 0, st>>>((uint4*)ws, n16, dev_status));
-    return MLMC_OK;
-}
-
-mlmc_status topk_draw(const DrawArgs& da, hipStream_t st) {
-    MLMC_LAUNCH(K_DRAW, st, k_draw<<<1, 1024, 0, st>>>(da));
     return MLMC_OK;
 }
 

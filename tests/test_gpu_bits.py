@@ -97,6 +97,8 @@ def test_bits_random_plans_and_inputs(seed):
                 G[0] = 0.0   # an all-zero row
         p = O.geometric_p(L)
         plan = P.Plan(P.MLMC_BITS, M, d, P.MLMC_F32, F, p)
+        if case % 2:
+            plan.set_sampling(int(rng.integers(1, 5)))   # scale predicted from a sample of the blocks
         g = to_device(G, ld=d + int(rng.integers(1, 4)) if rng.random() < 0.3 else None)
         call_seed = int(rng.integers(0, 2**40))
         for step in range(2):
@@ -107,3 +109,36 @@ def test_bits_random_plans_and_inputs(seed):
             out = P.mlmc_aggregate(plan, msg, 0.25)
             torch.cuda.synchronize()
             assert np.array_equal(out.cpu().numpy().view(np.uint32), O.aggregate_bits(want, F, d, 0.25).view(np.uint32))
+
+
+@pytest.mark.parametrize("shift", [1, 2, 4])
+def test_bits_sampled_scale_is_proven_or_redone(shift):
+    """The row scale is predicted from a sample of the blocks and the message extracted under it in the one full
+    read; rows whose true maximum needs a larger scale are extracted again.  Rows are built so that the maximum
+    lies in a sampled block, in an unsampled block (larger exponent: redone), in an unsampled block with the same
+    exponent (not redone), and in the ragged last block; the result never depends on the sampling."""
+    S = 1 << shift
+    d = 40 * 1024 + 333
+    rng = np.random.default_rng(shift)
+    G = (rng.standard_normal((6, d)) * 0.01).astype(np.float32)
+    sampled_blk, unsampled_blk = (S >> 1) + S, (S >> 1) + S + 1
+    G[0, sampled_blk * 1024 + 5] = 3.0                      # maximum inside the sample
+    G[1, unsampled_blk * 1024 + 700] = -3.0                 # outside, several binades above the sample's maximum
+    G[2, unsampled_blk * 1024 + 1] = np.abs(G[2]).max() * np.float32(1.01)   # outside, (almost surely) same binade
+    G[3, d - 1] = 1e20                                      # last, partial block
+    G[4] = 0.0
+    G[4, unsampled_blk * 1024] = 1e-41                      # a denormal maximum outside the sample: scale exponent stays -125
+    F = [0, 1, 2, 4, 8, 16]
+    p = O.geometric_p(5)
+    for Fl, pl in ((F, p), ([2, 3, 8, 12], O.geometric_p(3))):
+        plan = P.Plan(P.MLMC_BITS, G.shape[0], d, P.MLMC_F32, Fl, pl)
+        plan.set_sampling(shift)
+        g = to_device(G)
+        for step in range(4):
+            print(f"bits sampled scale shift={shift} F={Fl} step={step}", flush=True)
+            msg = P.mlmc_compress_bits(plan, g, seed=5, step=step)
+            want = _check_bits(plan, G, Fl, pl, 5, step, msg)
+            assert plan.status() == 0
+            out = P.mlmc_aggregate(plan, msg, 0.5)
+            torch.cuda.synchronize()
+            assert np.array_equal(out.cpu().numpy().view(np.uint32), O.aggregate_bits(want, Fl, d, 0.5).view(np.uint32))
