@@ -280,18 +280,29 @@ struct AggBitsArgs {
     BitsArgs b;
     const int32_t* level;
     const int32_t* scale_exp;
-    const uint64_t* planes;
     float alpha;
-    float* out;
 };
 
 // out[j] = alpha * sum over rows (worker order) of sign * (f0 * c0 + f * cl): Alg. 2 "Server aggregates".
 // A wave owns eight consecutive words of every plane, i.e. 512 consecutive elements; lane = element within a word.
-// The words are fetched 64 at a time, lane (q, k) = (lane / 8, lane % 8) taking word k of a row's plane q (so a
-// load instruction moves whole 64-byte sectors); a word is then read from its lane as a wave-wide mask whose bit
-// `lane` is the element's bit.  NPC bounds the planes of any row.
-template <int NPC>
-__global__ __launch_bounds__(256) void k_agg_bits(AggBitsArgs a) {
+// The eight words of a (row, plane) are one 64-byte scalar load: a plane word is wave-uniform data, and as a
+// scalar register pair it is at once the lane mask "this element's bit is set".  A row whose level field is a
+// single bit (the most likely levels) costs two selects and one add per element.
+struct Words8 {
+    uint64_t w[8];
+};
+__device__ __forceinline__ Words8 load_words8(const uint64_t* __restrict__ p, int nvalid) {
+    Words8 r;
+    if (nvalid >= 8) {   // uniform
+        r = *(const Words8*)p;
+    } else {             // the last words of a plane: nothing is read past the plane's end
+#pragma unroll
+        for (int k = 0; k < 8; ++k) r.w[k] = k < nvalid ? p[k] : 0ull;
+    }
+    return r;
+}
+
+__global__ __launch_bounds__(256) void k_agg_bits(AggBitsArgs a, const uint64_t* __restrict__ planes, float* __restrict__ out) {
     __shared__ float s_c0[MLMC_MAX_WORKERS], s_cl[MLMC_MAX_WORKERS];
     __shared__ uint8_t s_w[MLMC_MAX_WORKERS];
     const BitsArgs& b = a.b;
@@ -305,62 +316,60 @@ __global__ __launch_bounds__(256) void k_agg_bits(AggBitsArgs a) {
         s_w[r] = (uint8_t)(b.F[lev] - b.F[lev - 1]);
     }
     __syncthreads();
-    constexpr int PL = (NPC + 7) / 8;   // load instructions per row
     const uint32_t lane = lane_id();
-    const int q_l = (int)lane >> 3, k_l = (int)lane & 7;
     const int64_t nw = b.nwords;
     const int64_t nblk = (nw + 7) / 8;
-    const int64_t wave_global = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 6;
+    const int64_t wave_global = __builtin_amdgcn_readfirstlane((int)(((int64_t)blockIdx.x * 256 + threadIdx.x) >> 6));
     const int64_t nwaves = ((int64_t)gridDim.x * 256) >> 6;
     for (int64_t blk = wave_global; blk < nblk; blk += nwaves) {
         const int64_t w0 = blk * 8;
-        const bool wok = w0 + k_l < nw;
+        const int nvalid = nw - w0 < 8 ? (int)(nw - w0) : 8;
         float acc[8];
 #pragma unroll
         for (int k = 0; k < 8; ++k) acc[k] = 0.0f;
-        auto fetch = [&](int r, uint64_t (&m)[PL]) {
-            const int np = r < b.M ? 1 + F0 + (int)s_w[r] : 0;
+        for (int r = 0; r < b.M; ++r) {   // rows in worker order
+            const int wd = __builtin_amdgcn_readfirstlane((int)s_w[r]);
+            const float cl = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(s_cl[r])));
+            const uint64_t* rp = planes + (size_t)r * b.nplanes * nw + w0;
+            const Words8 sg = load_words8(rp, nvalid);
+            if (F0 == 0 && wd == 1) {
+                // f is 0 or 1: the entry is +-cl or absent (adding +0 leaves the sum as it is)
+                const Words8 fw = load_words8(rp + nw, nvalid);
 #pragma unroll
-            for (int u = 0; u < PL; ++u) {
-                const int p = u * 8 + q_l;
-                m[u] = (wok && p < np) ? a.planes[((size_t)r * b.nplanes + p) * nw + w0 + k_l] : 0ull;
-            }
-        };
-        uint64_t mine[PL], next[PL];
-        fetch(0, mine);
-        for (int r = 0; r < b.M; ++r) {   // rows in worker order; the next row's words are on their way meanwhile
-            fetch(r + 1, next);
-            const int np = 1 + F0 + (int)s_w[r];
-            const float c0 = s_c0[r], cl = s_cl[r];
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                uint32_t f0 = 0, f = 0;
-#pragma unroll
-                for (int p = 1; p < NPC; ++p) {
-                    if (p < np) {   // uniform
-                        const uint64_t m = mine[p >> 3];
-                        const uint64_t word = ((uint64_t)__builtin_amdgcn_readlane((uint32_t)(m >> 32), (p & 7) * 8 + k) << 32) |
-                                              (uint32_t)__builtin_amdgcn_readlane((uint32_t)m, (p & 7) * 8 + k);
-                        const bool bit = __builtin_amdgcn_inverse_ballot_w64(word);
-                        if (p <= F0) f0 |= bit ? 1u << (p - 1) : 0u;
-                        else f |= bit ? 1u << (p - 1 - F0) : 0u;
-                    }
+                for (int k = 0; k < 8; ++k) {
+                    float v = __builtin_amdgcn_inverse_ballot_w64(fw.w[k] & ~sg.w[k]) ? cl : 0.0f;
+                    v = __builtin_amdgcn_inverse_ballot_w64(fw.w[k] & sg.w[k]) ? -cl : v;
+                    acc[k] = __fadd_rn(acc[k], v);
                 }
-                const uint64_t m0 = mine[0];
-                const uint64_t sw = ((uint64_t)__builtin_amdgcn_readlane((uint32_t)(m0 >> 32), k) << 32) |
-                                    (uint32_t)__builtin_amdgcn_readlane((uint32_t)m0, k);
-                const bool sign = __builtin_amdgcn_inverse_ballot_w64(sw);
-                float v = __fmul_rn((float)f, cl);
-                if (F0 > 0) v = __fadd_rn(__fmul_rn((float)f0, c0), v);
-                acc[k] = __fadd_rn(acc[k], sign ? -v : v);
-            }
+            } else {
+                const float c0 = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(s_c0[r])));
+                uint32_t f[8], f0[8];
 #pragma unroll
-            for (int u = 0; u < PL; ++u) mine[u] = next[u];
+                for (int k = 0; k < 8; ++k) { f[k] = 0; f0[k] = 0; }
+                for (int q = 0; q < F0; ++q) {
+                    const Words8 pw = load_words8(rp + (size_t)(1 + q) * nw, nvalid);
+                    const uint32_t bit = 1u << q;
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) f0[k] |= __builtin_amdgcn_inverse_ballot_w64(pw.w[k]) ? bit : 0u;
+                }
+                for (int q = 0; q < wd; ++q) {
+                    const Words8 pw = load_words8(rp + (size_t)(1 + F0 + q) * nw, nvalid);
+                    const uint32_t bit = 1u << q;
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) f[k] |= __builtin_amdgcn_inverse_ballot_w64(pw.w[k]) ? bit : 0u;
+                }
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    float v = __fmul_rn((float)f[k], cl);
+                    if (F0 > 0) v = __fadd_rn(__fmul_rn((float)f0[k], c0), v);
+                    acc[k] = __fadd_rn(acc[k], __builtin_amdgcn_inverse_ballot_w64(sg.w[k]) ? -v : v);
+                }
+            }
         }
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
             const int64_t j = (w0 + k) * 64 + lane;
-            if (j < b.d) __builtin_nontemporal_store(__fmul_rn(a.alpha, acc[k]), &a.out[j]);
+            if (j < b.d) __builtin_nontemporal_store(__fmul_rn(a.alpha, acc[k]), &out[j]);
         }
     }
 }
@@ -529,19 +538,12 @@ mlmc_status agg_bits(const mlmc_plan_t* pl, const BitsArgs& b, const int32_t* le
     a.b = b;
     a.level = level;
     a.scale_exp = scale_exp;
-    a.planes = planes;
     a.alpha = alpha;
-    a.out = out;
     int64_t waves = (b.nwords + 7) / 8;   // a wave takes eight words at a time
     int blocks = (int)((waves + 3) / 4);
     if (blocks > 8192) blocks = 8192;
     if (blocks < 1) blocks = 1;
-    const int np = b.nplanes;   // 1 + F_0 + widest level field: bounds the planes of any row
-    if (np <= 3) MLMC_LAUNCH(K_AGG_BITS, st, k_agg_bits<3><<<blocks, 256, 0, st>>>(a));
-    else if (np <= 5) MLMC_LAUNCH(K_AGG_BITS, st, k_agg_bits<5><<<blocks, 256, 0, st>>>(a));
-    else if (np <= 9) MLMC_LAUNCH(K_AGG_BITS, st, k_agg_bits<9><<<blocks, 256, 0, st>>>(a));
-    else if (np <= 17) MLMC_LAUNCH(K_AGG_BITS, st, k_agg_bits<17><<<blocks, 256, 0, st>>>(a));
-    else MLMC_LAUNCH(K_AGG_BITS, st, k_agg_bits<MAX_PLANES><<<blocks, 256, 0, st>>>(a));
+    MLMC_LAUNCH(K_AGG_BITS, st, k_agg_bits<<<blocks, 256, 0, st>>>(a, planes, out));
     return MLMC_OK;
 }
 
