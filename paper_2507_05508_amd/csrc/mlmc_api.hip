@@ -254,6 +254,23 @@ mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dty
     chunk = (chunk + 4 * TILE - 1) / (4 * TILE) * (4 * TILE);
     if (chunk < 4 * TILE) chunk = 4 * TILE;
     if (chunk > CHUNK_MAX) chunk = CHUNK_MAX;
+    // A workgroup of the selection read holds a whole CU, so its M * chunks workgroups run in rounds of one per
+    // CU: among the chunk sizes within a quarter of the one above, take the one whose last round is the fullest
+    // (rounds x chunk = the elements a CU streams through).
+    {
+        constexpr int64_t NUM_CUS = 256;   // MI355X
+        int64_t best = chunk, best_cost = -1;
+        for (int64_t c = chunk - chunk / 4; c <= chunk + chunk / 4; c += 4 * TILE) {
+            const int64_t cc = (c + 4 * TILE - 1) / (4 * TILE) * (4 * TILE);
+            if (cc < 4 * TILE || cc > CHUNK_MAX) continue;
+            const int64_t n = (d + cc - 1) / cc;
+            if (n > CHUNKS_MAX / CSUB_MAX) continue;
+            const int64_t rounds = ((int64_t)M * n + NUM_CUS - 1) / NUM_CUS;
+            const int64_t cost = rounds * (cc + 16384);   // + a workgroup's fixed part (table load, flush), in elements
+            if (best_cost < 0 || cost < best_cost || (cost == best_cost && cc == chunk)) { best = cc; best_cost = cost; }
+        }
+        chunk = best;
+    }
     pl->chunk = (int)chunk;
     pl->chunks_per_row = (int)((d + chunk - 1) / chunk);   // <= 2^31 / 2^18 = CHUNKS_MAX
     // message offsets are kept per count chunk, a quarter of a chunk (unless that would be too many per row):

@@ -148,6 +148,7 @@ __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
     __shared__ float s_est[LMAX + 2];
     __shared__ double s_p[LMAX];
     __shared__ double s_kd[TMAX];
+    __shared__ uint16_t s_gexp[GMAX], s_gband[GMAX];
 
     const int row = blockIdx.x, tid = threadIdx.x;
     RowInfo* ri = a.rinfo + row;
@@ -178,7 +179,7 @@ __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
         s_lev = a.all_thresholds ? 0 : ri->level;
     }
     for (int b = tid; b < NB1; b += 1024) s_h[b] = gh[b];
-    for (int g = tid; g < GMAX; g += 1024) ri->g_band[g] = 0xFFFF;
+    for (int g = tid; g < GMAX; g += 1024) { s_gband[g] = 0xFFFF; s_gexp[g] = 0; }
     __syncthreads();
     const int lev = s_lev;
 
@@ -386,14 +387,20 @@ __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
             const int lab = s_label[zi];
             const bool member = spec > 0 && (lab == 0 || lab == spec);
             codes[15 - i] = class_code((uint32_t)gid, (uint32_t)zi, member ? TAG_MEMBER : 0u, member);
-            ri->g_exp[gid] = (uint16_t)(E ? E : 1);
-            ri->g_band[gid] = (uint16_t)lab;
+            // every bucket of a group says the same: in LDS first (the buckets of a group are many), to memory once
+            s_gexp[gid] = (uint16_t)(E ? E : 1);
+            s_gband[gid] = (uint16_t)lab;
         }
     }
     {
         uint4* dst = (uint4*)(a.table + (size_t)row * NB1 + (NB1 - 16 - tid * 16));
 #pragma unroll
         for (int i = 0; i < 4; ++i) dst[i] = make_uint4(codes[4 * i], codes[4 * i + 1], codes[4 * i + 2], codes[4 * i + 3]);
+    }
+    __syncthreads();
+    for (int g = tid; g < GMAX; g += 1024) {
+        ri->g_exp[g] = s_gexp[g];
+        ri->g_band[g] = s_gband[g];
     }
 }
 
@@ -420,7 +427,10 @@ template <bool SUMS> constexpr int lm_total() { return LM_END; }
 static_assert(lm_total<true>() <= 160 * 1024, "LDS budget");
 static_assert(ZMAX <= 64 && RMAX <= 64 && GMAX <= 512, "field widths of the class code");
 
-template <int DT, bool VEC, bool SUMS>
+// LOOPED: a workgroup takes the chunks blockIdx.x, blockIdx.x + gridDim.x, ... of its row.  The redo round is launched
+// that way with a small grid, so that it costs little when, as nearly always, no row needs it; the first round has a
+// workgroup per chunk and no loop.
+template <int DT, bool VEC, bool SUMS, bool LOOPED>
 __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pass) {
     __shared__ __align__(16) unsigned char lm[lm_total<SUMS>()];
     uint32_t* s_cnt = (uint32_t*)(lm + LM_CNT);
@@ -436,6 +446,9 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
     const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: loop bounds and offsets stay in SGPRs
     RowAcc* ra = a.racc + row;
     const int nz = ri->n_zones;
+    int chunk_id = blockIdx.x;
+    do {
+    if (LOOPED && chunk_id != (int)blockIdx.x) __syncthreads();   // the previous chunk is done with the shared arrays
     {
         const uint4* src = (const uint4*)(a.table + (size_t)row * NB1);
         uint4* dst = (uint4*)(lm + LM_TAB);
@@ -456,11 +469,11 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
     }
     __syncthreads();
 
-    const int64_t c0 = (int64_t)blockIdx.x * a.chunk;
+    const int64_t c0 = (int64_t)chunk_id * a.chunk;
     const int64_t c1 = c0 + a.chunk < a.d ? c0 + a.chunk : a.d;
     RowLoader<DT, VEC> ld(a.g, a.ld, a.d, row);
     // this wave's private, worst-case sized part of the scratch list: its candidates in the order met
-    uint2* priv = a.cand_priv + ((size_t)row * a.chunks_per_row + blockIdx.x) * (size_t)a.chunk + (size_t)wave * (a.chunk / MAIN_WAVES);
+    uint2* priv = a.cand_priv + ((size_t)row * a.chunks_per_row + chunk_id) * (size_t)a.chunk + (size_t)wave * (a.chunk / MAIN_WAVES);
     // per-lane byte addresses of the replicated accumulators
     const uint32_t cnt_lane = (uint32_t)LM_CNT + (lane & 15u) * 4u;
     const uint32_t sum_lane = (uint32_t)LM_SUM + (lane & 15u) * 8u;
@@ -573,7 +586,7 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
             ent[u] = priv[i < head ? i : head - 1u];
         }
     }
-    if (lane == 0) a.priv_cnt[((size_t)row * a.chunks_per_row + blockIdx.x) * MAIN_WAVES + wave] = head;
+    if (lane == 0) a.priv_cnt[((size_t)row * a.chunks_per_row + chunk_id) * MAIN_WAVES + wave] = head;
     __syncthreads();
     if (tid < nz) {
         uint32_t total = 0;
@@ -601,7 +614,7 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
         const int r = t % RMAX, sub = t / RMAX;
         uint32_t cnt = 0;
         for (int k = 0; k < REP_CNT; ++k) cnt += s_cnt[sub * (128 * REP_CNT) + r * REP_CNT + ((k + t) & (REP_CNT - 1))];
-        const int64_t cc = (int64_t)blockIdx.x * a.csub + sub;
+        const int64_t cc = (int64_t)chunk_id * a.csub + sub;
         if (sub < a.csub && cc < a.cchunks_per_row) a.chunk_cnt[((size_t)row * RMAX + r) * a.cchunks_per_row + cc] = cnt;
         if (cnt) atomicAdd(&ra->region_cnt[r], cnt);
     }
@@ -629,6 +642,7 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
         if (ri->exact) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
         else atomicOr((int32_t*)&a.rinfo[row].respec, 1);
     }
+    } while (LOOPED && (chunk_id += (int)gridDim.x) < a.chunks_per_row);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -1887,7 +1901,6 @@ __global__ __launch_bounds__(FL_THREADS) void k_filter(TopkArgs a) {
 // host-side launchers
 template <int DT, bool VEC>
 static mlmc_status launch_select(const mlmc_plan_t* pl, const TopkArgs& a, bool sums, hipStream_t st) {
-    const dim3 mgrid(pl->chunks_per_row, pl->M);
     const dim3 fgrid(FIN_WGS, pl->M);
     const int rounds = pl->sample_shift > 0 ? 2 : 1;   // second round: rows whose sampled zones were refuted
     for (int exact_pass = 0; exact_pass < rounds; ++exact_pass) {
@@ -1895,16 +1908,24 @@ static mlmc_status launch_select(const mlmc_plan_t* pl, const TopkArgs& a, bool 
         const int64_t nblk = (pl->d + 1023) / 1024;
         const int64_t ns = exact_pass ? nblk : ((nblk >> pl->sample_shift) > 0 ? (nblk >> pl->sample_shift) : 1);
         int64_t hw = ns / 32 > 0 ? ns / 32 : 1;
-        const int64_t hcap = 2048 / pl->M > 0 ? 2048 / pl->M : 1;
+        // at most two workgroups per CU in all (what the 64 KB of LDS a workgroup holds allow at a time)
+        const int64_t hcap = 512 / pl->M > 0 ? 512 / pl->M : 1;
         if (hw > hcap) hw = hcap;
+        if (exact_pass && hw > 16) hw = 16;   // the redo round: small grids, they nearly always return at once
         const dim3 hgrid((unsigned)hw, pl->M);
+        const dim3 mgrid(exact_pass && pl->chunks_per_row > 32 ? 32 : pl->chunks_per_row, pl->M);
         // the kernels of the redo round exit at once for rows that need none: they are timed as one entry
         const int kh = exact_pass ? K_REDO : K_HIST, ks = exact_pass ? K_REDO : K_SCAN;
         const int km = exact_pass ? K_REDO : K_MAIN;
         MLMC_LAUNCH(kh, st, k_hist<DT, VEC><<<hgrid, HIST_THREADS, 0, st>>>(a, exact_pass));
         MLMC_LAUNCH(ks, st, k_scan<<<pl->M, 1024, 0, st>>>(a, exact_pass));
-        if (sums) MLMC_LAUNCH(km, st, k_main<DT, VEC, true><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
-        else MLMC_LAUNCH(km, st, k_main<DT, VEC, false><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
+        if (exact_pass) {
+            if (sums) MLMC_LAUNCH(km, st, k_main<DT, VEC, true, true><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
+            else MLMC_LAUNCH(km, st, k_main<DT, VEC, false, true><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
+        } else {
+            if (sums) MLMC_LAUNCH(km, st, k_main<DT, VEC, true, false><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
+            else MLMC_LAUNCH(km, st, k_main<DT, VEC, false, false><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
+        }
         // the redo round resolves every zone in the ranking launch alone (two launches fewer to pay for when, as
         // nearly always, no row needs it)
         if (!exact_pass) MLMC_LAUNCH(K_FHIST, st, k_fhist<<<fgrid, FN_THREADS, 0, st>>>(a, exact_pass));
