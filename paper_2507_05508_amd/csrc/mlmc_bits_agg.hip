@@ -410,9 +410,12 @@ __global__ __launch_bounds__(256) void k_tileoff(AggSparseArgs a) {
 // One workgroup per dense tile: LDS accumulators, rows added one after the other (indices within a row are
 // distinct, so plain read-modify-write is race free), then one coalesced write of alpha * acc.
 __global__ __launch_bounds__(256) void k_agg_sparse(AggSparseArgs a) {
-    __shared__ float s_acc[TILE];
-    __shared__ int64_t s_beg[MLMC_MAX_WORKERS];
-    __shared__ uint32_t s_len[MLMC_MAX_WORKERS];
+    // dynamic LDS, sized by the number of rows (M * 12 bytes), so that a CU holds as many workgroups as its wave
+    // slots allow: the tile's accumulators, then every row's start and length inside the tile
+    extern __shared__ __align__(16) unsigned char s_dyn_agg[];
+    float* s_acc = (float*)s_dyn_agg;
+    int64_t* s_beg = (int64_t*)(s_dyn_agg + TILE * sizeof(float));
+    uint32_t* s_len = (uint32_t*)(s_dyn_agg + TILE * sizeof(float) + (size_t)a.M * sizeof(int64_t));
     const int64_t tile = blockIdx.x;
     const int64_t base = tile * TILE;
     for (int i = threadIdx.x; i < TILE; i += 256) s_acc[i] = 0.0f;
@@ -568,7 +571,8 @@ mlmc_status agg_sparse(const mlmc_plan_t* pl, const int64_t* row_off, const uint
         MLMC_LAUNCH(K_TILEOFF, st, k_tileoff<<<blocks, 256, 0, st>>>(a));
         a.tile_off = tile_off_ws;
     }
-    MLMC_LAUNCH(K_AGG_SPARSE, st, k_agg_sparse<<<(unsigned)pl->ntiles, 256, 0, st>>>(a));
+    const size_t lds = TILE * sizeof(float) + (size_t)pl->M * (sizeof(int64_t) + sizeof(uint32_t));
+    MLMC_LAUNCH(K_AGG_SPARSE, st, k_agg_sparse<<<(unsigned)pl->ntiles, 256, lds, st>>>(a));
     return MLMC_OK;
 }
 

@@ -136,7 +136,7 @@ constexpr int64_t ZONE_BIG_SAMPLE = 1 << 20;
 constexpr int64_t STAGE_MAX_BAND_INV = 8;   // bands wider than d / 8 are not staged
 
 __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
-    __shared__ uint32_t s_h[NB1];
+    __shared__ __align__(16) uint32_t s_h[NB1];
     __shared__ uint32_t s_cum[NB1];          // sampled elements in buckets above b
     __shared__ uint32_t s_scan[17];
     __shared__ int32_t s_active[TMAX];
@@ -148,7 +148,9 @@ __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
     __shared__ float s_est[LMAX + 2];
     __shared__ double s_p[LMAX];
     __shared__ double s_kd[TMAX];
+    __shared__ int64_t s_k[TMAX];            // the ladder (indexed by loop variables below: kept out of the argument block)
     __shared__ uint16_t s_gexp[GMAX], s_gband[GMAX];
+    __shared__ uint32_t s_bmin, s_bmax;      // occupied buckets of the (sampled) histogram
 
     const int row = blockIdx.x, tid = threadIdx.x;
     RowInfo* ri = a.rinfo + row;
@@ -178,18 +180,33 @@ __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
         ri->exact = exact ? 1 : 0;
         s_lev = a.all_thresholds ? 0 : ri->level;
     }
-    for (int b = tid; b < NB1; b += 1024) s_h[b] = gh[b];
+    // descending buckets: rb = tid*16 + i  <->  b = NB1 - 1 - rb.  A thread fetches its sixteen buckets with four
+    // loads issued together (a loop over strided single loads waits for every one of them in turn).
+    uint32_t hv[16];
+    {
+        const uint4* src = (const uint4*)(gh + (NB1 - 16 - tid * 16));
+        uint4 q[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) q[i] = src[i];
+        uint4* dst = (uint4*)(s_h + (NB1 - 16 - tid * 16));
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            dst[i] = q[i];
+            hv[15 - 4 * i] = q[i].x; hv[14 - 4 * i] = q[i].y; hv[13 - 4 * i] = q[i].z; hv[12 - 4 * i] = q[i].w;
+        }
+    }
     for (int g = tid; g < GMAX; g += 1024) { s_gband[g] = 0xFFFF; s_gexp[g] = 0; }
+    if (tid <= L) { s_k[tid] = a.k[tid]; s_kd[tid] = (double)a.k[tid]; }
+    if (tid == 0) { s_bmin = NB1; s_bmax = 0; }
     __syncthreads();
     const int lev = s_lev;
 
-    // descending buckets: rb = tid*16 + i  <->  b = NB1 - 1 - rb
-    uint32_t hv[16];
     uint32_t sum = 0;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        hv[i] = s_h[NB1 - 1 - (tid * 16 + i)];
-        sum += hv[i];
+    for (int i = 0; i < 16; ++i) sum += hv[i];
+    if (sum) {   // range of the occupied buckets (the prediction below walks only that range)
+        atomicMin(&s_bmin, (uint32_t)(NB1 - 16 - tid * 16));
+        atomicMax(&s_bmax, (uint32_t)(NB1 - 1 - tid * 16));
     }
     uint32_t total;
     const uint32_t before = block_excl_scan<1024>(sum, s_scan, total);
@@ -207,7 +224,7 @@ __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
         const int t = tid;
         const bool act = a.all_thresholds || t == 0 || t == lev - 1 || t == lev;
         s_active[t] = act;
-        const int64_t kt = a.k[t];
+        const int64_t kt = s_k[t];
         int64_t lo = kt, hi = kt;
         if (!exact) {
             const double m = (double)kt * (double)ns / (double)a.d;
@@ -257,7 +274,7 @@ __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
             const int act = __builtin_amdgcn_readlane(my_act, t);
             const uint32_t top = (uint32_t)__builtin_amdgcn_readlane((int)my_top, t);
             const uint32_t bot = (uint32_t)__builtin_amdgcn_readlane((int)my_bot, t);
-            const int64_t kt = a.k[t];
+            const int64_t kt = s_k[t];
             int tz;
             uint32_t tau = 0, jx = 0;
             bool set_thr = false;
@@ -335,12 +352,13 @@ __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
     const int nz = s_nz;
     if (a.all_thresholds && a.draw_mode == 3) {
         for (int l = tid; l < LMAX + 2; l += 1024) s_est[l] = 0.0f;
-        if (tid <= L) s_kd[tid] = (double)a.k[tid];   // per-lane indexed below: keep it out of the argument block
         __syncthreads();
         {
-            // strided over the buckets, so that the occupied ones (a few hundred in a row) spread over the threads
+            // strided over the occupied range of buckets, so that the occupied ones (a few hundred in a row) spread
+            // over the threads
             const double scale = (double)a.d / (double)(ns > 0 ? ns : 1);
-            for (int b = tid; b < NB1; b += 1024) {
+            const int b1 = (int)s_bmax;
+            for (int b = (int)s_bmin + tid; b <= b1; b += 1024) {
                 const uint32_t h = s_h[b];
                 if (h == 0 || (b >> 6) >= 255) continue;
                 const double rank = ((double)s_cum[b] + 0.5 * (double)h) * scale;
@@ -351,10 +369,12 @@ __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
             }
         }
         __syncthreads();
+        if (tid < L) s_p[tid] = sqrt((double)s_est[tid + 1]);   // the square roots side by side, the rest in order
+        __syncthreads();
         if (tid == 0) {
             double* p = s_p;
             double tot = 0.0;
-            for (int l = 0; l < L; ++l) { p[l] = sqrt((double)s_est[l + 1]); tot += p[l]; }
+            for (int l = 0; l < L; ++l) tot += p[l];
             for (int l = 0; l < L; ++l) p[l] = tot > 0.0 ? p[l] / tot : 1.0 / (double)L;
             s_lev = draw_from_p(p, L, philox_word0(a.seed, a.step, (uint32_t)row));
         }
@@ -364,7 +384,7 @@ __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
         int sl = ((a.all_thresholds && a.draw_mode != 3) || !a.staging) ? 0 : s_lev;   // norms only: nothing to stage
         // a wide band is cheaper to collect by a second read: the staged lists of such a row would keep its few
         // workgroups busy long after the other rows are done
-        if (sl > 0 && (a.k[sl] - a.k[sl - 1]) * STAGE_MAX_BAND_INV > a.d) sl = 0;
+        if (sl > 0 && (s_k[sl] - s_k[sl - 1]) * STAGE_MAX_BAND_INV > a.d) sl = 0;
         ri->spec_level = sl;
         ri->spec_ok = (sl > 0 && !(a.all_thresholds && a.draw_mode == 3)) ? 1 : 0;   // adaptive: decided after the draw
         s_lev = sl;
@@ -372,24 +392,34 @@ __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
     __syncthreads();
     const int spec = s_lev;
 
-    // class table: thread tid writes its 16 buckets (descending), 64 bytes
+    // class table: thread tid writes its 16 buckets (descending), 64 bytes.  The zone bounds of the current zone
+    // index stay in registers; a thread's buckets share their exponent, so their group changes only with the zone
+    // index and the group tables are written once per change.
     uint32_t codes[16];
     int zi = 0;   // zones wholly above the current bucket
+    uint32_t ztop_c = nz > 0 ? s_ztop[0] : 0u, zbot_c = nz > 0 ? s_zbot[0] : 0u;
+    int lab_c = s_label[0];   // band of the region above zone zi (below the last zone when zi == nz)
+    int last_gid = -1;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         const uint32_t b = (uint32_t)(NB1 - 1 - (tid * 16 + i));
-        while (zi < nz && s_zbot[zi] > b) ++zi;
-        if (zi < nz && b <= s_ztop[zi]) {
+        while (zi < nz && zbot_c > b) {
+            ++zi;
+            lab_c = s_label[zi];
+            if (zi < nz) { ztop_c = s_ztop[zi]; zbot_c = s_zbot[zi]; }
+        }
+        if (zi < nz && b <= ztop_c) {
             codes[15 - i] = class_code((uint32_t)G_DUMMY, 64u + (uint32_t)zi, (uint32_t)zi, true);
         } else {
             const uint32_t E = b >> 6;
             const int gid = (int)(255 - E) + zi;
-            const int lab = s_label[zi];
-            const bool member = spec > 0 && (lab == 0 || lab == spec);
+            if (gid != last_gid) {
+                last_gid = gid;
+                s_gexp[gid] = (uint16_t)(E ? E : 1);
+                s_gband[gid] = (uint16_t)lab_c;
+            }
+            const bool member = spec > 0 && (lab_c == 0 || lab_c == spec);
             codes[15 - i] = class_code((uint32_t)gid, (uint32_t)zi, member ? TAG_MEMBER : 0u, member);
-            // every bucket of a group says the same: in LDS first (the buckets of a group are many), to memory once
-            s_gexp[gid] = (uint16_t)(E ? E : 1);
-            s_gband[gid] = (uint16_t)lab;
         }
     }
     {
