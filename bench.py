@@ -172,6 +172,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-staging", action="store_true",
                     help="Top-k: write every message by a second read of the rows (tuning hook off; same results)")
+    ap.add_argument("--fused-update", action="store_true",
+                    help="server side as mlmc_aggregate_update: x <- x - eta * g~ inside the aggregate, g~ itself not written")
     ap.add_argument("--cpu-budget", type=float, default=25.0)
     ap.add_argument("--print-kernel-digest", action="store_true",
                     help="print the sha256 that names the kernel sources (profile summaries quote it) and exit")
@@ -219,13 +221,17 @@ def main():
         plan = P.Plan(P.MLMC_BITS, w.M, w.d, P.MLMC_F32, w.ladder, P.mlmc_geometric_p(w.L))
         msg = P.BitsMessage(plan)
     out = torch.empty(w.d, dtype=torch.float32, device=dev)
+    x_model = torch.zeros(w.d, dtype=torch.float32, device=dev) if args.fused_update else None
 
     def step(i):
         if w.kind == "topk":
             P.mlmc_compress_topk(plan, g, seed=w.seed, step=i, out=msg)
         else:
             P.mlmc_compress_bits(plan, g, seed=w.seed, step=i, out=msg)
-        P.mlmc_aggregate(plan, msg, alpha, out=out)
+        if args.fused_update:
+            P.mlmc_aggregate_update(plan, msg, alpha, 0.01, x_model)
+        else:
+            P.mlmc_aggregate(plan, msg, alpha, out=out)
 
     if args.calibrate_copy:
         src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
@@ -310,7 +316,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "M": w.M, "d": w.d, "L": w.L, "kind": w.kind,
                    "p": "adaptive" if w.adaptive else "fixed_geometric", "input_bytes": in_bytes,
-                   "avg_nnz_per_step": round(nnz_avg, 1), "alpha": alpha},
+                   "avg_nnz_per_step": round(nnz_avg, 1), "alpha": alpha,
+                   "server": "aggregate + fused model update" if args.fused_update else "aggregate"},
         "hbm_peak_frac_input": round(value / HBM_PEAK_GBPS, 4),
         "hbm_peak_frac_algorithmic": round(step_alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
         "ms_per_step_with_events": round(dt_ev * 1e3 / args.steps, 4),

@@ -189,6 +189,29 @@ mlmc_status mlmc_aggregate(const mlmc_plan_t *plan, const int32_t *level, const 
                            void *ws, void *hip_stream);
 
 /*
+ * Server side with the model update fused in (Alg. 2 / Alg. 3 "Server aggregates" and "Server updates"):
+ * g~_j = fp32(alpha * acc_j) as in mlmc_aggregate, then x_j <- fp32(x_j - fp32(eta * g~_j)) (one multiply, one subtract),
+ * inside the same pass over the dense tiles, so that the update is not written and read again.
+ *   x:   dev [d] fp32, in and out (the model x_t -> x_{t+1}).
+ *   out: dev [d] fp32 (out) or NULL when g~ itself is not wanted; must not alias x.
+ *   Every other argument as in mlmc_aggregate.
+ */
+mlmc_status mlmc_aggregate_update(const mlmc_plan_t *plan, const int32_t *level, const int64_t *row_off,
+                                  const uint32_t *idx, const float *val, int64_t capacity,
+                                  const uint32_t *tile_off, const int32_t *scale_exp, const uint64_t *planes,
+                                  float alpha, float eta, float *x, float *out, void *ws, void *hip_stream);
+
+/*
+ * Bits every worker's message of this step takes on the wire (the "communicated bits" of Sec. 5), from the drawn levels:
+ *   MLMC_TOPK: nnz_i * (32 + ceil(log2 d)) + ceil(log2 L): every entry of the base band and of the drawn band as a
+ *     32-bit value and an index into d, plus the level (Sec. 3: the residual of Top-k is one rank band).
+ *   MLMC_BITS: d * (1 + F_0 + F_l - F_{l-1}) + 32 + ceil(log2 L): per entry the sign, the base bits and the level
+ *     field, plus the scale exponent and the level (Sec. 3.1; with F = 0..63 and a 64-bit scale: 2 d + 64 + 6).
+ *   level: dev [M] int32 as written by a compress call;  bits: dev [M] uint64 (out).
+ */
+mlmc_status mlmc_message_bits(const mlmc_plan_t *plan, const int32_t *level, uint64_t *bits, void *hip_stream);
+
+/*
  * Per-kernel timing for benchmarks (measurement aid, not part of the method).  While enabled, every kernel
  * the library launches is bracketed by a pair of HIP events on the launch stream; mlmc_profile_get waits
  * for the recorded events and returns the accumulated device time and launch count of kernel `id`

@@ -323,3 +323,36 @@ def aggregate_bits(msgs, F, d: int, alpha: float) -> np.ndarray:
     for msg in msgs:
         acc = acc + decode_bits_row(msg, F, d)
     return (np.float32(alpha) * acc).astype(np.float32)
+
+
+# ----------------------------------------------------------------------------------------------
+# server update and message sizes
+# ----------------------------------------------------------------------------------------------
+def server_update(x: np.ndarray, gtilde: np.ndarray, eta: float) -> np.ndarray:
+    """Alg. 2 / Alg. 3 "Server updates": x_{t+1} = x_t - eta * g~_t, per entry one fp32 multiply, then one fp32
+    subtract (two roundings, no fused multiply-add)."""
+    x = np.asarray(x, dtype=np.float32)
+    step = (np.float32(eta) * np.asarray(gtilde, dtype=np.float32)).astype(np.float32)
+    return (x - step).astype(np.float32)
+
+
+def _ceil_log2(n: int) -> int:
+    """Bits that name one of n alternatives: ceil(log2 n), 0 for n <= 1."""
+    return max(int(n) - 1, 0).bit_length()
+
+
+def message_bits_topk(ladder: Sequence[int], level: int, d: int, value_bits: int = 32) -> int:
+    """Bits one worker sends for a Top-k MLMC message (Sec. 3, Sec. 3.2: the residual is the entries of one rank
+    band): every entry as a value and an index into d, plus the level: nnz * (value_bits + ceil(log2 d)) + ceil(log2 L)."""
+    L = len(ladder) - 1
+    nnz = ladder[0] + ladder[level] - ladder[level - 1]
+    return nnz * (value_bits + _ceil_log2(d)) + _ceil_log2(L)
+
+
+def message_bits_fixed_point(F: Sequence[int], level: int, d: int, scale_bits: int = 32) -> int:
+    """Bits one worker sends for a fixed-point MLMC message (Sec. 3.1): per entry the sign, the F_0 base bits and the
+    F_l - F_{l-1} bits of the level field, plus the scale and the level.  With the unit ladder F = 0..63 and a 64-bit
+    scale this is the paper's 2 d + 64 + ceil(log2 63)."""
+    L = len(F) - 1
+    return d * (1 + F[0] + F[level] - F[level - 1]) + scale_bits + _ceil_log2(L)
+

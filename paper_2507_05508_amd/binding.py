@@ -24,7 +24,7 @@ MLMC_TILE = 4096
 MLMC_MAX_LEVELS = 32
 
 EXPORTS = ["mlmc_plan", "mlmc_plan_destroy", "mlmc_plan_set_sampling", "mlmc_plan_set_staging", "mlmc_plan_num_tiles", "mlmc_plan_num_planes", "mlmc_geometric_p",
-           "mlmc_status_string", "mlmc_level_norms", "mlmc_compress_topk", "mlmc_compress_bits", "mlmc_compress_bits_static", "mlmc_aggregate",
+           "mlmc_status_string", "mlmc_level_norms", "mlmc_compress_topk", "mlmc_compress_bits", "mlmc_compress_bits_static", "mlmc_aggregate", "mlmc_aggregate_update", "mlmc_message_bits",
            "mlmc_profile_enable", "mlmc_profile_reset", "mlmc_profile_num_kernels", "mlmc_profile_kernel_name",
            "mlmc_profile_get"]
 
@@ -70,6 +70,10 @@ def lib():
         L.mlmc_compress_bits_static.argtypes = [vp, vp, i64, u64, u64, vp, vp, vp, vp, vp]
         L.mlmc_aggregate.restype = C.c_int
         L.mlmc_aggregate.argtypes = [vp, vp, vp, vp, vp, i64, vp, vp, vp, C.c_float, vp, vp, vp]
+        L.mlmc_aggregate_update.restype = C.c_int
+        L.mlmc_aggregate_update.argtypes = [vp, vp, vp, vp, vp, i64, vp, vp, vp, C.c_float, C.c_float, vp, vp, vp, vp]
+        L.mlmc_message_bits.restype = C.c_int
+        L.mlmc_message_bits.argtypes = [vp, vp, vp, vp]
         L.mlmc_profile_enable.restype = None
         L.mlmc_profile_enable.argtypes = [i32]
         L.mlmc_profile_reset.restype = None
@@ -265,3 +269,28 @@ def mlmc_aggregate(plan: Plan, msg, alpha: float, out: Optional[torch.Tensor] = 
                                   _ptr(msg.planes), float(alpha), _ptr(out), _ptr(plan.ws), _stream())
     _check(rc, "mlmc_aggregate")
     return out
+
+
+def mlmc_aggregate_update(plan: Plan, msg, alpha: float, eta: float, x: torch.Tensor, out: Optional[torch.Tensor] = None,
+                          use_tile_off: bool = True) -> torch.Tensor:
+    """x <- x - eta * (alpha * sum of the workers' messages), in place; `out` (optional) also receives the update."""
+    if x.dtype != torch.float32 or x.numel() != plan.d or not x.is_contiguous() or not x.is_cuda:
+        raise MlmcError("x must be a contiguous float32 CUDA tensor [d]")
+    if plan.kind == MLMC_TOPK:
+        rc = lib().mlmc_aggregate_update(plan.handle, None, _ptr(msg.row_off), _ptr(msg.idx), _ptr(msg.val), msg.capacity,
+                                         _ptr(msg.tile_off) if use_tile_off else None, None, None, float(alpha), float(eta),
+                                         _ptr(x), _ptr(out), _ptr(plan.ws), _stream())
+    else:
+        rc = lib().mlmc_aggregate_update(plan.handle, _ptr(msg.level), None, None, None, 0, None, _ptr(msg.scale_exp),
+                                         _ptr(msg.planes), float(alpha), float(eta), _ptr(x), _ptr(out), _ptr(plan.ws), _stream())
+    _check(rc, "mlmc_aggregate_update")
+    return x
+
+
+def mlmc_message_bits(plan: Plan, msg, bits: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Bits per worker that the message `msg` of this plan takes on the wire (int64 tensor [M])."""
+    if bits is None:
+        bits = torch.empty(plan.M, dtype=torch.int64, device=plan.device)
+    _check(lib().mlmc_message_bits(plan.handle, _ptr(msg.level), _ptr(bits), _stream()), "mlmc_message_bits")
+    return bits
+

@@ -15,9 +15,11 @@ mlmc_status topk_select(const mlmc_plan_t* pl, const TopkArgs& a, bool sums, boo
 mlmc_status topk_compact(const mlmc_plan_t* pl, const TopkArgs& a, bool vec, hipStream_t st);
 mlmc_status bits_compress(const mlmc_plan_t* pl, const BitsArgs& a, bool vec, hipStream_t st);
 mlmc_status agg_bits(const mlmc_plan_t* pl, const BitsArgs& b, const int32_t* level, const int32_t* scale_exp,
-                     const uint64_t* planes, float alpha, float* out, hipStream_t st);
+                     const uint64_t* planes, float alpha, float* out, float eta, float* x, hipStream_t st);
 mlmc_status agg_sparse(const mlmc_plan_t* pl, const int64_t* row_off, const uint32_t* idx, const float* val, int64_t capacity,
-                       const uint32_t* tile_off, uint32_t* tile_off_ws, float alpha, float* out, hipStream_t st);
+                       const uint32_t* tile_off, uint32_t* tile_off_ws, float alpha, float* out, float eta, float* x,
+                       hipStream_t st);
+mlmc_status message_bits(const mlmc_plan_t* pl, const int32_t* level, unsigned long long* bits, hipStream_t st);
 
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -47,7 +49,7 @@ static mlmc_status static_scratch_of_current_device(void** out) {
 bool g_prof_on = false;
 static const char* const k_names[K_NUM] = {
     "k_zero", "k_hist", "k_scan", "k_main", "k_fhist", "k_finish", "k_finish_rank", "redo_pass", "k_norms", "k_bits_prep", "k_msgplan", "k_filter", "k_write",
-    "k_bits_smax", "k_bits_extract", "k_bits_redo", "k_agg_bits", "k_tileoff", "k_agg_sparse"};
+    "k_bits_smax", "k_bits_extract", "k_bits_redo", "k_agg_bits", "k_tileoff", "k_agg_sparse", "k_message_bits"};
 struct ProfPair { int id; hipEvent_t e0, e1; };
 static std::vector<ProfPair> g_pending;
 static std::vector<ProfPair> g_free;
@@ -440,21 +442,42 @@ mlmc_status mlmc_compress_bits_static(const mlmc_plan_t* plan, const void* g, in
     return mlmc_compress_bits(plan, g, ld, seed, step, level, scale_exp, planes, dev_status, ws, hip_stream);
 }
 
-mlmc_status mlmc_aggregate(const mlmc_plan_t* plan, const int32_t* level, const int64_t* row_off, const uint32_t* idx,
-                           const float* val, int64_t capacity, const uint32_t* tile_off, const int32_t* scale_exp, const uint64_t* planes,
-                           float alpha, float* out, void* ws, void* hip_stream) {
-    if (!plan || !out) return MLMC_EINVAL;
+static mlmc_status aggregate_impl(const mlmc_plan_t* plan, const int32_t* level, const int64_t* row_off, const uint32_t* idx,
+                                  const float* val, int64_t capacity, const uint32_t* tile_off, const int32_t* scale_exp,
+                                  const uint64_t* planes, float alpha, float* out, float eta, float* x, void* ws, void* hip_stream) {
+    if (!plan || (!out && !x)) return MLMC_EINVAL;
     hipStream_t st = (hipStream_t)hip_stream;
     if (plan->kind == MLMC_TOPK) {
         if (!row_off || !idx || !val || capacity < 0 || scale_exp || planes) return MLMC_EINVAL;
         if (!tile_off && (!ws || (uintptr_t)ws % 256)) return MLMC_EINVAL;
         uint32_t* tws = ws ? (uint32_t*)((char*)ws + plan->off_tileoff) : nullptr;
-        return agg_sparse(plan, row_off, idx, val, capacity, tile_off, tws, alpha, out, st);
+        return agg_sparse(plan, row_off, idx, val, capacity, tile_off, tws, alpha, out, eta, x, st);
     }
     if (!level || !scale_exp || !planes || row_off || idx || val || tile_off) return MLMC_EINVAL;
     BitsArgs b;
     fill_bits_args(plan, b, nullptr, plan->d, nullptr, nullptr);
-    return agg_bits(plan, b, level, scale_exp, planes, alpha, out, st);
+    return agg_bits(plan, b, level, scale_exp, planes, alpha, out, eta, x, st);
+}
+
+mlmc_status mlmc_aggregate(const mlmc_plan_t* plan, const int32_t* level, const int64_t* row_off, const uint32_t* idx,
+                           const float* val, int64_t capacity, const uint32_t* tile_off, const int32_t* scale_exp, const uint64_t* planes,
+                           float alpha, float* out, void* ws, void* hip_stream) {
+    if (!out) return MLMC_EINVAL;
+    return aggregate_impl(plan, level, row_off, idx, val, capacity, tile_off, scale_exp, planes, alpha, out, 0.0f, nullptr, ws,
+                          hip_stream);
+}
+
+mlmc_status mlmc_aggregate_update(const mlmc_plan_t* plan, const int32_t* level, const int64_t* row_off, const uint32_t* idx,
+                                  const float* val, int64_t capacity, const uint32_t* tile_off, const int32_t* scale_exp,
+                                  const uint64_t* planes, float alpha, float eta, float* x, float* out, void* ws,
+                                  void* hip_stream) {
+    if (!x || x == out) return MLMC_EINVAL;
+    return aggregate_impl(plan, level, row_off, idx, val, capacity, tile_off, scale_exp, planes, alpha, out, eta, x, ws, hip_stream);
+}
+
+mlmc_status mlmc_message_bits(const mlmc_plan_t* plan, const int32_t* level, uint64_t* bits, void* hip_stream) {
+    if (!plan || !level || !bits) return MLMC_EINVAL;
+    return message_bits(plan, level, (unsigned long long*)bits, (hipStream_t)hip_stream);
 }
 
 }  // extern "C"

@@ -276,11 +276,20 @@ __global__ __launch_bounds__(256) void k_bits_extract(BitsArgs a) {
     }
 }
 
+// What a kernel of the aggregate does with the finished sum of entry j: g~_j = alpha * acc (Alg. 2 "Server
+// aggregates"), written out and / or applied to the model, x_j <- x_j - eta * g~_j (Alg. 2 "Server updates": one
+// multiply, one subtract).
+__device__ __forceinline__ void finish_entry(float alpha, float acc, float* out, float eta, float* x, int64_t j) {
+    const float gt = __fmul_rn(alpha, acc);
+    if (out) __builtin_nontemporal_store(gt, &out[j]);   // written once, read by the caller later
+    if (x) x[j] = __fsub_rn(x[j], __fmul_rn(eta, gt));
+}
+
 struct AggBitsArgs {
     BitsArgs b;
     const int32_t* level;
     const int32_t* scale_exp;
-    float alpha;
+    float alpha, eta;
 };
 
 // out[j] = alpha * sum over rows (worker order) of sign * (f0 * c0 + f * cl): Alg. 2 "Server aggregates".
@@ -302,7 +311,8 @@ __device__ __forceinline__ Words8 load_words8(const uint64_t* __restrict__ p, in
     return r;
 }
 
-__global__ __launch_bounds__(256) void k_agg_bits(AggBitsArgs a, const uint64_t* __restrict__ planes, float* __restrict__ out) {
+__global__ __launch_bounds__(256) void k_agg_bits(AggBitsArgs a, const uint64_t* __restrict__ planes, float* __restrict__ out,
+                                                  float* __restrict__ x) {
     __shared__ float s_c0[MLMC_MAX_WORKERS], s_cl[MLMC_MAX_WORKERS];
     __shared__ uint8_t s_w[MLMC_MAX_WORKERS];
     const BitsArgs& b = a.b;
@@ -369,7 +379,7 @@ __global__ __launch_bounds__(256) void k_agg_bits(AggBitsArgs a, const uint64_t*
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
             const int64_t j = (w0 + k) * 64 + lane;
-            if (j < b.d) __builtin_nontemporal_store(__fmul_rn(a.alpha, acc[k]), &out[j]);
+            if (j < b.d) finish_entry(a.alpha, acc[k], out, a.eta, x, j);
         }
     }
 }
@@ -385,7 +395,9 @@ struct AggSparseArgs {
     const uint32_t* tile_off;  // [M][ntiles + 1]
     uint32_t* tile_off_out;    // k_tileoff target
     float alpha;
-    float* out;
+    float* out;                // the dense update g~ (may be null when only x is wanted)
+    float eta;
+    float* x;                  // server update x <- x - eta * g~ (null: no update)
 };
 
 __global__ __launch_bounds__(256) void k_tileoff(AggSparseArgs a) {
@@ -482,8 +494,49 @@ __global__ __launch_bounds__(256) void k_agg_sparse(AggSparseArgs a) {
     }
     for (int i = threadIdx.x; i < TILE; i += 256) {
         int64_t j = base + i;
-        if (j < a.d) __builtin_nontemporal_store(__fmul_rn(a.alpha, s_acc[i]), &a.out[j]);   // written once, read by the caller later
+        if (j < a.d) finish_entry(a.alpha, s_acc[i], a.out, a.eta, a.x, j);
     }
+}
+
+// Bits that name one of n alternatives.
+__device__ __forceinline__ int ceil_log2_dev(int64_t n) { return n <= 1 ? 0 : 64 - __clzll((unsigned long long)(n - 1)); }
+
+// Bits every worker's message takes on the wire.  Rank bands (Sec. 3, Sec. 3.2): every entry as a 32-bit value and an
+// index into d, plus the level.  Fixed-point ladder (Sec. 3.1): per entry the sign, the base bits and the bits of
+// the level field, plus the 32-bit scale exponent and the level.
+struct MsgBitsArgs {
+    int32_t kind, M, L;
+    int64_t d;
+    int64_t ladder[TMAX];
+    const int32_t* level;
+    unsigned long long* bits;
+};
+__global__ __launch_bounds__(256) void k_message_bits(MsgBitsArgs a) {
+    __shared__ int64_t s_lad[TMAX];
+    if ((int)threadIdx.x <= a.L) s_lad[threadIdx.x] = a.ladder[threadIdx.x];
+    __syncthreads();
+    const int r = blockIdx.x * 256 + threadIdx.x;
+    if (r >= a.M) return;
+    int lev = a.level[r];
+    lev = lev < 1 ? 1 : (lev > a.L ? a.L : lev);
+    const int64_t width = s_lad[lev] - s_lad[lev - 1];
+    unsigned long long n;
+    if (a.kind == MLMC_TOPK) n = (unsigned long long)(s_lad[0] + width) * (unsigned long long)(32 + ceil_log2_dev(a.d));
+    else n = (unsigned long long)a.d * (unsigned long long)(1 + s_lad[0] + width) + 32ull;
+    a.bits[r] = n + (unsigned long long)ceil_log2_dev(a.L);
+}
+
+mlmc_status message_bits(const mlmc_plan_t* pl, const int32_t* level, unsigned long long* bits, hipStream_t st) {
+    MsgBitsArgs a;
+    a.kind = pl->kind;
+    a.M = pl->M;
+    a.L = pl->L;
+    a.d = pl->d;
+    for (int t = 0; t <= pl->L; ++t) a.ladder[t] = pl->ladder[t];
+    a.level = level;
+    a.bits = bits;
+    MLMC_LAUNCH(K_MSGBITS, st, k_message_bits<<<(pl->M + 255) / 256, 256, 0, st>>>(a));
+    return MLMC_OK;
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -536,22 +589,24 @@ mlmc_status bits_compress(const mlmc_plan_t* pl, const BitsArgs& a, bool vec, hi
 }
 
 mlmc_status agg_bits(const mlmc_plan_t* pl, const BitsArgs& b, const int32_t* level, const int32_t* scale_exp,
-                     const uint64_t* planes, float alpha, float* out, hipStream_t st) {
+                     const uint64_t* planes, float alpha, float* out, float eta, float* x, hipStream_t st) {
     AggBitsArgs a;
     a.b = b;
     a.level = level;
     a.scale_exp = scale_exp;
     a.alpha = alpha;
+    a.eta = eta;
     int64_t waves = (b.nwords + 7) / 8;   // a wave takes eight words at a time
     int blocks = (int)((waves + 3) / 4);
     if (blocks > 8192) blocks = 8192;
     if (blocks < 1) blocks = 1;
-    MLMC_LAUNCH(K_AGG_BITS, st, k_agg_bits<<<blocks, 256, 0, st>>>(a, planes, out));
+    MLMC_LAUNCH(K_AGG_BITS, st, k_agg_bits<<<blocks, 256, 0, st>>>(a, planes, out, x));
     return MLMC_OK;
 }
 
 mlmc_status agg_sparse(const mlmc_plan_t* pl, const int64_t* row_off, const uint32_t* idx, const float* val, int64_t capacity,
-                       const uint32_t* tile_off, uint32_t* tile_off_ws, float alpha, float* out, hipStream_t st) {
+                       const uint32_t* tile_off, uint32_t* tile_off_ws, float alpha, float* out, float eta, float* x,
+                       hipStream_t st) {
     AggSparseArgs a;
     a.M = pl->M;
     a.d = pl->d;
@@ -564,6 +619,8 @@ mlmc_status agg_sparse(const mlmc_plan_t* pl, const int64_t* row_off, const uint
     a.tile_off_out = tile_off_ws;
     a.alpha = alpha;
     a.out = out;
+    a.eta = eta;
+    a.x = x;
     if (!tile_off) {
         int64_t n = (int64_t)pl->M * (pl->ntiles + 1);
         int blocks = (int)((n + 255) / 256);

@@ -166,7 +166,7 @@ struct BitsArgs {
 // ---- optional per-kernel timing with HIP events (host side, see mlmc_profile_* in mlmc.h) ----------
 enum KernelId {
     K_ZERO = 0, K_HIST, K_SCAN, K_MAIN, K_FHIST, K_FINISH, K_FINISH1, K_REDO, K_NORMS, K_DRAW, K_MSGPLAN, K_FILTER, K_WRITE,
-    K_BITS_MAX, K_BITS_EXTRACT, K_BITS_REDO, K_AGG_BITS, K_TILEOFF, K_AGG_SPARSE, K_NUM
+    K_BITS_MAX, K_BITS_EXTRACT, K_BITS_REDO, K_AGG_BITS, K_TILEOFF, K_AGG_SPARSE, K_MSGBITS, K_NUM
 };
 extern bool g_prof_on;
 void prof_begin(int id, hipStream_t st);

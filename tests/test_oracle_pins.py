@@ -550,6 +550,42 @@ def test_bits_pins_catch_planted_mistakes(monkeypatch):
     _check_aggregate_bits_bruteforce()
 
 
+# ----------------------------------------------------------------------------- server update, message sizes
+def test_server_update_is_alg1_sgd_step_in_the_identity_case():
+    """Alg. 2 "Server updates" x_{t+1} = x_t - eta g~_t: entry by entry with scalar fp32 operations; and with the
+    identity ladder (L = 1, k_1 = d, p_1 = 1) the step is Alg. 1's SGD step on the plain mean of the gradients."""
+    rng = np.random.default_rng(21)
+    M, d, eta = 4, 300, 0.0371
+    G = rng.standard_normal((M, d)).astype(np.float32)
+    x = rng.standard_normal(d).astype(np.float32)
+    gt = O.aggregate_sparse(O.compress_topk(G, [0, d], [1.0], 0, 0), d, 1.0 / M)
+    got = O.server_update(x, gt, eta)
+    for j in range(d):
+        assert got[j] == np.float32(x[j] - np.float32(np.float32(eta) * gt[j]))
+    want64 = x.astype(np.float64) - eta * G.astype(np.float64).mean(axis=0)
+    assert np.allclose(got, want64, rtol=1e-5, atol=1e-6)
+    # a planted fused multiply-add (one rounding) differs somewhere; so does a dropped eta
+    fused = (x.astype(np.float64) - np.float64(np.float32(eta)) * gt.astype(np.float64)).astype(np.float32)
+    assert np.any(fused != got) and np.any((x - gt) != got)
+
+
+def test_message_bits_match_the_papers_counts():
+    d = 1_000_003
+    # Sec. 3.1: unit fixed-point ladder of 63 bits, 64-bit scale: 2 d + 64 + ceil(log2 63)
+    F = list(range(64))
+    for l in (1, 17, 63):
+        assert O.message_bits_fixed_point(F, l, d, scale_bits=64) == 2 * d + 64 + 6
+    # the benchmark's ladder 1, 2, 4, 8, 16 bits with a 32-bit scale: sign + field width per entry
+    F = [0, 1, 2, 4, 8, 16]
+    assert [O.message_bits_fixed_point(F, l, d) for l in range(1, 6)] == [d * w + 32 + 3 for w in (2, 2, 3, 5, 9)]
+    # Sec. 3 / Sec. 3.2: Top-k with k_l = l sends one entry, s-Top-k sends s entries (value + index), plus the level
+    ladder = list(range(0, 101))
+    assert O.message_bits_topk(ladder, 37, d) == (32 + 20) + 7
+    s_ladder = [64 * l for l in range(0, 51)]
+    assert O.message_bits_topk(s_ladder, 50, d) == 64 * (32 + 20) + 6
+    assert O.message_bits_topk([10, 20, 40], 2, 1 << 20) == (10 + 20) * (32 + 20) + 1
+
+
 # ----------------------------------------------------------------------------- workloads
 def test_workload_generators_are_deterministic_and_shaped():
     for name in ("tiny_topk", "resnet18_topk", "resnet50_adaptive_topk", "resnet18_bits", "bert_adaptive_topk_bf16"):
