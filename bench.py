@@ -32,7 +32,7 @@ def algorithmic_bytes(w, kernel, nnz_total, planes_bytes):
     """Bytes the method itself has to move in one launch of `kernel` ('Kernels')."""
     s_in = 2 if w.dtype == "bf16" else 4
     in_bytes = w.M * w.d * s_in
-    if kernel in ("k_main", "k_bits_max"):
+    if kernel in ("k_main", "k_bits_max", "k_bits_smax"):
         return in_bytes                                   # one read of every input element
     if kernel == "k_write":
         return in_bytes + 8 * nnz_total                   # read the rows, write (idx, val)
@@ -87,6 +87,8 @@ def _oracle_row(w, row_data, i):
     p = None if w.adaptive else O.geometric_p(w.L)
     if w.kind == "topk":
         return O.compress_topk_row(row_data, w.ladder, p, w.seed, 0, i)
+    if w.kind == "fbits":
+        return O.compress_fbits_row(row_data, w.ladder, p, w.seed, 0, i)
     return O.compress_bits_row(row_data, w.ladder, p, w.seed, 0, i)
 
 
@@ -94,6 +96,8 @@ def _oracle_aggregate(w, msgs):
     from oracle import mlmc as O
     if w.kind == "topk":
         return O.aggregate_sparse(msgs, w.d, 1.0 / w.M)
+    if w.kind == "fbits":
+        return O.aggregate_fbits(msgs, w.ladder, w.d, 1.0 / w.M)
     return O.aggregate_bits(msgs, w.ladder, w.d, 1.0 / w.M)
 
 
@@ -218,7 +222,7 @@ def main():
         if args.no_staging:
             plan.set_staging(False)
     else:
-        plan = P.Plan(P.MLMC_BITS, w.M, w.d, P.MLMC_F32, w.ladder, P.mlmc_geometric_p(w.L))
+        plan = P.Plan(P.MLMC_FBITS if w.kind == "fbits" else P.MLMC_BITS, w.M, w.d, P.MLMC_F32, w.ladder, P.mlmc_geometric_p(w.L))
         msg = P.BitsMessage(plan)
     out = torch.empty(w.d, dtype=torch.float32, device=dev)
     x_model = torch.zeros(w.d, dtype=torch.float32, device=dev) if args.fused_update else None
@@ -284,7 +288,7 @@ def main():
             for l in lv.tolist():
                 drawn[l] = drawn.get(l, 0) + 1
             widths = [w.ladder[l] - w.ladder[l - 1] for l in lv]
-            planes_bytes += sum((1 + w.ladder[0] + x) * ((w.d + 63) // 64) * 8 for x in widths)
+            planes_bytes += sum(((9 if w.kind == "fbits" else 1) + w.ladder[0] + x) * ((w.d + 63) // 64) * 8 for x in widths)
     nnz_avg = nnz_total / args.steps
     planes_avg = planes_bytes / args.steps
 

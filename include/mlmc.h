@@ -58,7 +58,7 @@ typedef enum {
 #define MLMC_DEV_REDONE 8    /* not an error: a row's sampled threshold search was refuted and the row was redone exactly */
 
 typedef enum { MLMC_F32 = 0, MLMC_BF16 = 1 } mlmc_dtype;
-typedef enum { MLMC_TOPK = 0, MLMC_BITS = 1 } mlmc_kind;
+typedef enum { MLMC_TOPK = 0, MLMC_BITS = 1, MLMC_FBITS = 2 } mlmc_kind;
 
 #define MLMC_MAX_LEVELS 32   /* L <= 32 */
 #define MLMC_MAX_WORKERS 1024 /* M <= 1024 */
@@ -69,8 +69,11 @@ typedef enum { MLMC_TOPK = 0, MLMC_BITS = 1 } mlmc_kind;
  * probabilities) for M workers of dimension d (Sec. 2.1).
  *   kind == MLMC_TOPK: ladder = ranks k_0..k_L, 0 <= k_0 < k_1 < ... < k_L <= d        (Sec. 3.2)
  *   kind == MLMC_BITS: ladder = kept fraction bits F_0..F_L, 0 <= F_0 < ... < F_L <= 24 (Sec. 3.1)
+ *   kind == MLMC_FBITS: ladder = kept mantissa digits F_0..F_L, 0 <= F_0 < ... < F_L <= 23 (App. B: the
+ *            floating-point compressor C^F keeps sign, exponent and the first F mantissa digits of every entry;
+ *            the paper's ladder is F = 0, 1, ..., 52 for fp64, here 0..23 for fp32 inputs)
  *   p_fixed: host, L entries for levels 1..L, each > 0, summing to 1 within 1e-9; NULL selects the
- *            adaptive probabilities of Lemma 3.4 (MLMC_TOPK only).
+ *            adaptive probabilities of Lemma 3.4 (MLMC_TOPK only).  Lemma 3.3 / Lemma B.1: 2^-l / (1 - 2^-L).
  *   1 <= M <= MLMC_MAX_WORKERS, 1 <= d < 2^31, 1 <= L <= MLMC_MAX_LEVELS.
  * Outputs (host): *plan; *workspace_bytes; *sparse_capacity_worst = M * (k_0 + widest band) entries
  * (0 for MLMC_BITS).  Returns MLMC_EINVAL and leaves *plan NULL on a bad argument.
@@ -103,7 +106,8 @@ mlmc_status mlmc_plan_set_staging(mlmc_plan_t *plan, int enable);
 
 /* Tiles per row of the offset table: ceil(d / MLMC_TILE). */
 int64_t mlmc_plan_num_tiles(const mlmc_plan_t *plan);
-/* MLMC_BITS: planes per row of the packed message = 1 + F_0 + max_l (F_l - F_{l-1}); else 0. */
+/* Planes per row of the packed message: MLMC_BITS 1 + F_0 + max_l (F_l - F_{l-1}); MLMC_FBITS 9 + F_0 + max_l (F_l - F_{l-1});
+ * else 0. */
 int mlmc_plan_num_planes(const mlmc_plan_t *plan);
 
 /* Lemma 3.3 form: p[l-1] = 2^-l / (1 - 2^-L), l = 1..L (host array of L doubles). */
@@ -148,6 +152,11 @@ mlmc_status mlmc_compress_topk(const mlmc_plan_t *plan, const void *g, int64_t l
  *   level: dev [M] int32 (out);  scale_exp: dev [M] int32 (out), the exponent e.
  *   planes: dev [M][num_planes][ceil(d/64)] uint64 (out); word w bit b <-> element 64 w + b, pad bits 0;
  *           planes beyond 1 + F_0 + (F_l - F_{l-1}) of a row are left untouched.
+ *
+ * MLMC_FBITS plans (App. B, floating-point ladder): no scale; C^{F_0}(g) + (C^{F_l}(g) - C^{F_{l-1}}(g)) / p_l with
+ * C^F = mantissa truncated to F digits.  Message per row: sign plane, 8 planes of the exponent field (LSB first),
+ * F_0 planes of the first F_0 mantissa digits read as a number (LSB first), F_l - F_{l-1} planes of the digits
+ * F_{l-1}+1 .. F_l read as a number (LSB first).  scale_exp may be NULL (it is not written).  bf16 inputs are widened.
  */
 mlmc_status mlmc_compress_bits(const mlmc_plan_t *plan, const void *g, int64_t ld, uint64_t seed,
                                uint64_t step, int32_t *level, int32_t *scale_exp, uint64_t *planes,
@@ -181,6 +190,9 @@ mlmc_status mlmc_compress_bits_static(const mlmc_plan_t *plan, const void *g, in
  *     entry at j is skipped.
  *   MLMC_BITS plan: level, scale_exp, planes as written by mlmc_compress_bits; the decoded value of
  *     worker i at j is sign * [ fp32(f0) * fp32(2^(e - F_0)) + fp32(f) * fp32(2^(e - F_l) / p_l) ].
+ *   MLMC_FBITS plan: level, planes (scale_exp unused, may be NULL); with sign s, exponent field E, base digits f0 and
+ *     level digits f of worker i at j: base = float(s, E, f0 << (23 - F_0)), residual = float(s, E, f << (23 - F_l)) -
+ *     float(s, E, 0) (exact), decoded value = fp32(base + fp32(residual * fp32(1 / p_l))).
  *   out: dev [d] fp32, fully overwritten.
  */
 mlmc_status mlmc_aggregate(const mlmc_plan_t *plan, const int32_t *level, const int64_t *row_off,
@@ -207,6 +219,8 @@ mlmc_status mlmc_aggregate_update(const mlmc_plan_t *plan, const int32_t *level,
  *     32-bit value and an index into d, plus the level (Sec. 3: the residual of Top-k is one rank band).
  *   MLMC_BITS: d * (1 + F_0 + F_l - F_{l-1}) + 32 + ceil(log2 L): per entry the sign, the base bits and the level
  *     field, plus the scale exponent and the level (Sec. 3.1; with F = 0..63 and a 64-bit scale: 2 d + 64 + 6).
+ *   MLMC_FBITS: d * (9 + F_0 + F_l - F_{l-1}) + ceil(log2 L): per entry sign, 8 exponent bits, base and level digits
+ *     (App. B; for fp64 with one digit per level: 13 d + log2 52).
  *   level: dev [M] int32 as written by a compress call;  bits: dev [M] uint64 (out).
  */
 mlmc_status mlmc_message_bits(const mlmc_plan_t *plan, const int32_t *level, uint64_t *bits, void *hip_stream);

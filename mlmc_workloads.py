@@ -21,7 +21,7 @@ import numpy as np
 @dataclass(frozen=True)
 class Workload:
     name: str
-    kind: str                 # "topk" | "bits"
+    kind: str                 # "topk" | "bits" (fixed-point ladder) | "fbits" (floating-point ladder)
     M: int                    # workers (rows)
     d: int                    # gradient dimension
     dtype: str                # "f32" | "bf16"
@@ -59,6 +59,9 @@ WORKLOADS = {
     # bit-wise ladder at ResNet-18 scale
     "resnet18_bits": _mk("resnet18_bits", "bits", 8, 11_689_512, "f32", 5, [0, 1, 2, 4, 8, 16], False,
                          "segmented_normal", seed=0, steps=5, segments=62, std_lo=1e-4, std_hi=1e-1),
+    # floating-point bit-wise ladder (one mantissa digit per level) at ResNet-18 scale
+    "resnet18_fbits": _mk("resnet18_fbits", "fbits", 8, 11_689_512, "f32", 23, list(range(24)), False,
+                          "segmented_normal", seed=0, steps=5, segments=62, std_lo=1e-4, std_hi=1e-1),
     # BERT scale, bf16 inputs, heavy tails
     "bert_adaptive_topk_bf16": _mk("bert_adaptive_topk_bf16", "topk", 4, 124_439_808, "bf16", 16,
                                    geometric_rank_ladder(124_439_808, 16), True, "segmented_student_t",

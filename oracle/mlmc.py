@@ -43,6 +43,11 @@ from .philox import level_uniform
 TWO32 = 4294967296.0
 
 
+def _ceil_log2(n: int) -> int:
+    """Bits that name one of n alternatives: ceil(log2 n), 0 for n <= 1."""
+    return max(int(n) - 1, 0).bit_length()
+
+
 # ----------------------------------------------------------------------------------------------
 # inputs
 # ----------------------------------------------------------------------------------------------
@@ -306,6 +311,96 @@ def compress_bits(G: np.ndarray, F, p, seed: int, step: int):
 
 
 # ----------------------------------------------------------------------------------------------
+# floating-point bit-wise MLMC (App. B)
+# ----------------------------------------------------------------------------------------------
+MANT_BITS = 23   # fp32 inputs: the mantissa digits m_1..m_23 (the paper writes the fp64 case, 52 digits)
+
+
+def float_truncate(g32: np.ndarray, F: int) -> np.ndarray:
+    """Floating-point compressor C^F (App. B): sign and exponent kept, the mantissa sum truncated to its first F
+    digits.  On the fp32 bit pattern this clears the low 23 - F mantissa bits (also right for denormals and zero)."""
+    bits = np.ascontiguousarray(g32, dtype=np.float32).view(np.uint32)
+    keep = np.uint32((0xFFFFFFFF << (MANT_BITS - F)) & 0xFFFFFFFF)
+    return (bits & keep).view(np.float32)
+
+
+def fbits_estimate_dense(row: np.ndarray, F: Sequence[int], level: int, p_level: float) -> np.ndarray:
+    """g~ = C^{F_0}(g) + (C^{F_l}(g) - C^{F_{l-1}}(g)) / p_l (Eq. (5)) for the mantissa ladder F, as the fp32 vector the
+    server adds: the residual is exact in fp32 (both terms share sign and exponent), then one fp32 multiply by
+    w = fp32(1 / p_l) and one fp32 add."""
+    g = as_f32(row)
+    r = (float_truncate(g, F[level]) - float_truncate(g, F[level - 1])).astype(np.float32)
+    return (float_truncate(g, F[0]) + (r * level_weight(p_level)).astype(np.float32)).astype(np.float32)
+
+
+def compress_fbits_row(row: np.ndarray, F: Sequence[int], p: Sequence[float], seed: int, step: int, worker: int,
+                       force_level: Optional[int] = None):
+    """One worker's floating-point MLMC message: level; sign plane; 8 exponent planes (bits of the exponent field,
+    LSB first); F_0 base planes (bits of the first F_0 mantissa digits as a number, LSB first); F_l - F_{l-1} level
+    planes (bits of the mantissa digits F_{l-1}+1 .. F_l as a number, LSB first).  App. B: the residual keeps the sign
+    and the exponent of the entry and adds the level's mantissa digits."""
+    g = as_f32(row)
+    L = len(F) - 1
+    assert 0 <= F[0] and all(F[i] < F[i + 1] for i in range(L)) and F[L] <= MANT_BITS
+    bits = np.ascontiguousarray(g).view(np.uint32)
+    level = draw_level(p, seed, step, worker) if force_level is None else int(force_level)
+    width = F[level] - F[level - 1]
+    frac = bits & np.uint32(0x7FFFFF)
+    E = (bits >> np.uint32(23)) & np.uint32(0xFF)
+    base = frac >> np.uint32(MANT_BITS - F[0]) if F[0] > 0 else np.zeros_like(frac)
+    field = (frac >> np.uint32(MANT_BITS - F[level])) & np.uint32((1 << width) - 1)
+    planes = [pack_plane((bits >> np.uint32(31)).astype(bool))]
+    for b in range(8):
+        planes.append(pack_plane(((E >> np.uint32(b)) & np.uint32(1)).astype(bool)))
+    for b in range(F[0]):
+        planes.append(pack_plane(((base >> np.uint32(b)) & np.uint32(1)).astype(bool)))
+    for b in range(width):
+        planes.append(pack_plane(((field >> np.uint32(b)) & np.uint32(1)).astype(bool)))
+    return dict(level=level, planes=np.stack(planes), p_level=float(p[level - 1]))
+
+
+def decode_fbits_row(msg, F: Sequence[int], d: int) -> np.ndarray:
+    """The fp32 vector the server adds for a floating-point MLMC message: with sign s, exponent field E, base digits
+    f0 and level digits f, C^{F_0} = float(s, E, f0 << (23 - F_0)); the residual is float(s, E, f << (23 - F_l)) -
+    float(s, E, 0) (exact in fp32); g~ = fp32(C^{F_0} + fp32(residual * w))."""
+    level, planes = msg["level"], msg["planes"]
+    width = F[level] - F[level - 1]
+    sign = unpack_plane(planes[0], d).astype(np.uint32)
+    E = np.zeros(d, dtype=np.uint32)
+    for b in range(8):
+        E |= unpack_plane(planes[1 + b], d).astype(np.uint32) << np.uint32(b)
+    f0 = np.zeros(d, dtype=np.uint32)
+    for b in range(F[0]):
+        f0 |= unpack_plane(planes[9 + b], d).astype(np.uint32) << np.uint32(b)
+    f = np.zeros(d, dtype=np.uint32)
+    for b in range(width):
+        f |= unpack_plane(planes[9 + F[0] + b], d).astype(np.uint32) << np.uint32(b)
+    se = (sign << np.uint32(31)) | (E << np.uint32(23))
+    base_val = (se | (f0 << np.uint32(MANT_BITS - F[0]))).view(np.float32) if F[0] > 0 else se.view(np.float32)
+    r = ((se | (f << np.uint32(MANT_BITS - F[level]))).view(np.float32) - se.view(np.float32)).astype(np.float32)
+    return (base_val + (r * level_weight(msg["p_level"])).astype(np.float32)).astype(np.float32)
+
+
+def compress_fbits(G: np.ndarray, F, p, seed: int, step: int):
+    return [compress_fbits_row(G[i], F, p, seed, step, i) for i in range(G.shape[0])]
+
+
+def aggregate_fbits(msgs, F, d: int, alpha: float) -> np.ndarray:
+    acc = np.zeros(d, dtype=np.float32)
+    for msg in msgs:
+        acc = acc + decode_fbits_row(msg, F, d)
+    return (np.float32(alpha) * acc).astype(np.float32)
+
+
+def message_bits_floating_point(F: Sequence[int], level: int, d: int, exponent_bits: int = 8) -> int:
+    """Bits one worker sends for a floating-point MLMC message (App. B): per entry the sign, the exponent, the F_0 base
+    digits and the level's digits, plus the level.  For fp64 (11 exponent bits, unit ladder of 52 digits) this is the
+    paper's 13 d + log2(52), rounded up."""
+    L = len(F) - 1
+    return d * (1 + exponent_bits + F[0] + F[level] - F[level - 1]) + _ceil_log2(L)
+
+
+# ----------------------------------------------------------------------------------------------
 # server aggregate
 # ----------------------------------------------------------------------------------------------
 def aggregate_sparse(msgs, d: int, alpha: float) -> np.ndarray:
@@ -334,11 +429,6 @@ def server_update(x: np.ndarray, gtilde: np.ndarray, eta: float) -> np.ndarray:
     x = np.asarray(x, dtype=np.float32)
     step = (np.float32(eta) * np.asarray(gtilde, dtype=np.float32)).astype(np.float32)
     return (x - step).astype(np.float32)
-
-
-def _ceil_log2(n: int) -> int:
-    """Bits that name one of n alternatives: ceil(log2 n), 0 for n <= 1."""
-    return max(int(n) - 1, 0).bit_length()
 
 
 def message_bits_topk(ladder: Sequence[int], level: int, d: int, value_bits: int = 32) -> int:

@@ -148,6 +148,7 @@ static void fill_bits_args(const mlmc_plan_t* pl, BitsArgs& b, const void* g, in
     b.L = pl->L;
     for (int t = 0; t <= pl->L; ++t) b.F[t] = (int32_t)pl->ladder[t];
     for (int l = 0; l < pl->L; ++l) b.p_fixed[l] = pl->p[l];
+    b.flt = pl->kind == MLMC_FBITS ? 1 : 0;
     b.nplanes = pl->nplanes;
     b.nwords = (pl->d + 63) / 64;
     b.chunk = pl->chunk;
@@ -206,7 +207,7 @@ mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dty
                       const double* p_fixed, size_t* workspace_bytes, int64_t* sparse_capacity_worst) {
     if (plan) *plan = nullptr;
     if (!plan || !ladder) return MLMC_EINVAL;
-    if (kind != MLMC_TOPK && kind != MLMC_BITS) return MLMC_EINVAL;
+    if (kind != MLMC_TOPK && kind != MLMC_BITS && kind != MLMC_FBITS) return MLMC_EINVAL;
     if (in_dtype != MLMC_F32 && in_dtype != MLMC_BF16) return MLMC_EINVAL;
     if (M < 1 || M > MLMC_MAX_WORKERS || d < 1 || d >= ((int64_t)1 << 31) || L < 1 || L > MLMC_MAX_LEVELS) return MLMC_EINVAL;
     if (ladder[0] < 0) return MLMC_EINVAL;
@@ -214,7 +215,8 @@ mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dty
         if (ladder[t] >= ladder[t + 1]) return MLMC_EINVAL;
     if (kind == MLMC_TOPK && ladder[L] > d) return MLMC_EINVAL;
     if (kind == MLMC_BITS && ladder[L] > 24) return MLMC_EINVAL;
-    if (kind == MLMC_BITS && !p_fixed) return MLMC_EINVAL;  // Lemma 3.4 probabilities are built for rank bands only
+    if (kind == MLMC_FBITS && ladder[L] > 23) return MLMC_EINVAL;
+    if (kind != MLMC_TOPK && !p_fixed) return MLMC_EINVAL;  // Lemma 3.4 probabilities are built for rank bands only
     if (p_fixed) {
         double s = 0.0;
         for (int l = 0; l < L; ++l) {
@@ -237,13 +239,13 @@ mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dty
         for (int l = 0; l < L; ++l) pl->p[l] = p_fixed[l];
     pl->ntiles = (d + TILE - 1) / TILE;
     pl->nplanes = 0;
-    if (kind == MLMC_BITS) {
+    if (kind != MLMC_TOPK) {
         int maxw = 0;
         for (int l = 1; l <= L; ++l) {
             int w = (int)(ladder[l] - ladder[l - 1]);
             if (w > maxw) maxw = w;
         }
-        pl->nplanes = 1 + (int)ladder[0] + maxw;
+        pl->nplanes = (kind == MLMC_FBITS ? 9 : 1) + (int)ladder[0] + maxw;
     }
     // chunking of the streaming kernels: about 2048 workgroups over all rows, but chunks of at least some 96 K
     // elements (a workgroup of the selection read loads a 64 KB table first), whole tiles, at most 2^18 elements
@@ -417,7 +419,8 @@ mlmc_status mlmc_compress_topk(const mlmc_plan_t* plan, const void* g, int64_t l
 mlmc_status mlmc_compress_bits(const mlmc_plan_t* plan, const void* g, int64_t ld, uint64_t seed, uint64_t step,
                                int32_t* level, int32_t* scale_exp, uint64_t* planes, int32_t* dev_status, void* ws,
                                void* hip_stream) {
-    if (!plan || plan->kind != MLMC_BITS || !g || !level || !scale_exp || !planes || !dev_status || !ws) return MLMC_EINVAL;
+    if (!plan || plan->kind == MLMC_TOPK || !g || !level || !planes || !dev_status || !ws) return MLMC_EINVAL;
+    if (plan->kind == MLMC_BITS && !scale_exp) return MLMC_EINVAL;
     if (ld < plan->d || (uintptr_t)ws % 256) return MLMC_EINVAL;
     hipStream_t st = (hipStream_t)hip_stream;
     BitsArgs b;
@@ -433,7 +436,7 @@ mlmc_status mlmc_compress_bits(const mlmc_plan_t* plan, const void* g, int64_t l
 mlmc_status mlmc_compress_bits_static(const mlmc_plan_t* plan, const void* g, int64_t ld, uint64_t seed, uint64_t step,
                                       int32_t* level, int32_t* scale_exp, uint64_t* planes, int32_t* dev_status,
                                       void* hip_stream) {
-    if (!plan || plan->kind != MLMC_BITS) return MLMC_EINVAL;
+    if (!plan || plan->kind == MLMC_TOPK) return MLMC_EINVAL;
     if (plan->ws_bytes > (size_t)MLMC_STATIC_SCRATCH_BYTES) return MLMC_ELIMIT;   // before any HIP call
     void* ws = nullptr;
     const mlmc_status rc = static_scratch_of_current_device(&ws);
@@ -453,7 +456,8 @@ static mlmc_status aggregate_impl(const mlmc_plan_t* plan, const int32_t* level,
         uint32_t* tws = ws ? (uint32_t*)((char*)ws + plan->off_tileoff) : nullptr;
         return agg_sparse(plan, row_off, idx, val, capacity, tile_off, tws, alpha, out, eta, x, st);
     }
-    if (!level || !scale_exp || !planes || row_off || idx || val || tile_off) return MLMC_EINVAL;
+    if (!level || !planes || row_off || idx || val || tile_off) return MLMC_EINVAL;
+    if (plan->kind == MLMC_BITS && !scale_exp) return MLMC_EINVAL;
     BitsArgs b;
     fill_bits_args(plan, b, nullptr, plan->d, nullptr, nullptr);
     return agg_bits(plan, b, level, scale_exp, planes, alpha, out, eta, x, st);

@@ -87,7 +87,8 @@ __device__ __forceinline__ void put_lane(uint32_t& dst, uint32_t sval, int lane)
 //
 // Digits (Sec. 3.1): |g| = sig * 2^(E' - 150), scale s = 2^(Emax - 126), so floor(|g| / s * 2^F) = sig >> (24 - F + Emax - E').
 // Bit b of (sig >> (24 - F_l + Emax - E')) for b < F_l - F_{l-1} is bit b of the level field.
-template <int DT, bool VEC, int NPC, bool BASE>
+// MODE 0 / 1: fixed-point ladder without / with a base field (F_0 > 0); MODE 2: floating-point ladder (App. B).
+template <int DT, bool VEC, int NPC, int MODE>
 __device__ __forceinline__ void bits_extract_tiles(const BitsArgs& a, int row, int Emax, int level, int np, uint32_t& maxkey,
                                                    uint32_t* slds) {
     const uint32_t lane = lane_id(), wave = (uint32_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -96,16 +97,25 @@ __device__ __forceinline__ void bits_extract_tiles(const BitsArgs& a, int row, i
     const int64_t ntiles = (a.d + TILE - 1) / TILE;
     const int64_t nwhole = a.d / TILE;   // tiles with all 4096 elements
     const int F0 = a.F[0];
+    constexpr bool BASE = MODE == 1;
     const uint32_t Cl = (uint32_t)(24 - a.F[level] + Emax), C0 = (uint32_t)(24 - F0 + Emax);
     const uint32_t mask0 = BASE ? (1u << F0) - 1u : 0u;
+    const uint32_t fsl = (uint32_t)(23 - a.F[level]), fs0 = (uint32_t)(23 - F0);   // floating-point ladder: digit positions
     uint32_t wlo[NPC], whi[NPC];   // lane i: word i of the tile's planes
 #pragma unroll
     for (int p = 0; p < NPC; ++p) { wlo[p] = 0; whi[p] = 0; }
-    // plane p >= 1 <-> bit p - 1 of the value returned here (base field first, then the level field)
+    // plane p >= 1 <-> bit p - 1 of the value returned here (base field first, then the level field; for the
+    // floating-point ladder the eight exponent bits come first)
     auto digits = [&](uint32_t bits) -> uint32_t {
         const uint32_t key = key_of_bits(bits);
         maxkey = key > maxkey ? key : maxkey;
         const uint32_t E = key >> 23;
+        if (MODE == 2) {
+            // App. B: the digits m_1..m_F of the mantissa are the top F bits of the 23-bit fraction field
+            const uint32_t frac = key & 0x7FFFFFu;
+            const uint32_t base = F0 ? frac >> fs0 : 0u;
+            return E | ((base | ((frac >> fsl) << F0)) << 8);
+        }
         const uint32_t hid = (key & 0x7FFFFFu) | 0x800000u;
         const uint32_t sig = key < hid ? key : hid;       // exponent field 0: no hidden bit
         const uint32_t Ec = E > 1u ? E : 1u;
@@ -232,8 +242,8 @@ __device__ __forceinline__ void bits_extract_tiles(const BitsArgs& a, int row, i
 // way.  REDO (second launch, only when the maximum was sampled): rows whose true maximum has a larger exponent than
 // the sampled one are extracted again with the true one; every other row is already final and is skipped.
 // NPCMAX: bound on the planes of any row of the plan (the kernel holds only the variants it can need, so that a
-// plan with few planes is not charged the registers of the widest one).
-template <int DT, bool VEC, bool REDO, int NPCMAX>
+// plan with few planes is not charged the registers of the widest one).  FLT: floating-point ladder (no scale).
+template <int DT, bool VEC, bool REDO, int NPCMAX, bool FLT>
 __global__ __launch_bounds__(256) void k_bits_extract(BitsArgs a) {
     __shared__ __align__(16) uint32_t s_tr[4][1024];   // per wave: four loads of 256 elements on their way from "four per lane" to "one per lane"
     uint32_t* slds = s_tr[threadIdx.x >> 6];
@@ -248,23 +258,30 @@ __global__ __launch_bounds__(256) void k_bits_extract(BitsArgs a) {
     const int Emax = Ex ? (int)Ex : 1;
     const int level = a.rinfo[row].level;
     const int F0 = a.F[0];
-    const int np = 1 + F0 + (a.F[level] - a.F[level - 1]);   // planes written for this row
-    if (blockIdx.x == 0 && threadIdx.x == 0) a.scale_exp[row] = Emax - 126;
+    const int np = (FLT ? 9 : 1) + F0 + (a.F[level] - a.F[level - 1]);   // planes written for this row
+    if (!FLT && blockIdx.x == 0 && threadIdx.x == 0) a.scale_exp[row] = Emax - 126;
     uint32_t maxkey = 0;
-    if (F0 == 0) {
-        if (np <= 3) bits_extract_tiles<DT, VEC, 3, false>(a, row, Emax, level, np, maxkey, slds);
-        else if (np <= 5) bits_extract_tiles<DT, VEC, 5, false>(a, row, Emax, level, np, maxkey, slds);
-        else if (np <= 9) bits_extract_tiles<DT, VEC, 9, false>(a, row, Emax, level, np, maxkey, slds);
+    if constexpr (FLT) {
+        if (np <= 11) bits_extract_tiles<DT, VEC, 11, 2>(a, row, Emax, level, np, maxkey, slds);
+        else if constexpr (NPCMAX > 11) {
+            if (np <= 17) bits_extract_tiles<DT, VEC, 17, 2>(a, row, Emax, level, np, maxkey, slds);
+            else if (np <= 25) bits_extract_tiles<DT, VEC, 25, 2>(a, row, Emax, level, np, maxkey, slds);
+            else bits_extract_tiles<DT, VEC, MAX_FPLANES, 2>(a, row, Emax, level, np, maxkey, slds);
+        }
+    } else if (F0 == 0) {
+        if (np <= 3) bits_extract_tiles<DT, VEC, 3, 0>(a, row, Emax, level, np, maxkey, slds);
+        else if (np <= 5) bits_extract_tiles<DT, VEC, 5, 0>(a, row, Emax, level, np, maxkey, slds);
+        else if (np <= 9) bits_extract_tiles<DT, VEC, 9, 0>(a, row, Emax, level, np, maxkey, slds);
         else if constexpr (NPCMAX > 9) {
-            if (np <= 17) bits_extract_tiles<DT, VEC, 17, false>(a, row, Emax, level, np, maxkey, slds);
-            else bits_extract_tiles<DT, VEC, MAX_PLANES, false>(a, row, Emax, level, np, maxkey, slds);
+            if (np <= 17) bits_extract_tiles<DT, VEC, 17, 0>(a, row, Emax, level, np, maxkey, slds);
+            else bits_extract_tiles<DT, VEC, MAX_PLANES, 0>(a, row, Emax, level, np, maxkey, slds);
         }
     } else {
-        if (np <= 5) bits_extract_tiles<DT, VEC, 5, true>(a, row, Emax, level, np, maxkey, slds);
-        else if (np <= 9) bits_extract_tiles<DT, VEC, 9, true>(a, row, Emax, level, np, maxkey, slds);
+        if (np <= 5) bits_extract_tiles<DT, VEC, 5, 1>(a, row, Emax, level, np, maxkey, slds);
+        else if (np <= 9) bits_extract_tiles<DT, VEC, 9, 1>(a, row, Emax, level, np, maxkey, slds);
         else if constexpr (NPCMAX > 9) {
-            if (np <= 17) bits_extract_tiles<DT, VEC, 17, true>(a, row, Emax, level, np, maxkey, slds);
-            else bits_extract_tiles<DT, VEC, MAX_PLANES, true>(a, row, Emax, level, np, maxkey, slds);
+            if (np <= 17) bits_extract_tiles<DT, VEC, 17, 1>(a, row, Emax, level, np, maxkey, slds);
+            else bits_extract_tiles<DT, VEC, MAX_PLANES, 1>(a, row, Emax, level, np, maxkey, slds);
         }
     }
     if (!REDO) {
@@ -314,16 +331,22 @@ __device__ __forceinline__ Words8 load_words8(const uint64_t* __restrict__ p, in
 __global__ __launch_bounds__(256) void k_agg_bits(AggBitsArgs a, const uint64_t* __restrict__ planes, float* __restrict__ out,
                                                   float* __restrict__ x) {
     __shared__ float s_c0[MLMC_MAX_WORKERS], s_cl[MLMC_MAX_WORKERS];
-    __shared__ uint8_t s_w[MLMC_MAX_WORKERS];
+    __shared__ uint8_t s_w[MLMC_MAX_WORKERS], s_fl[MLMC_MAX_WORKERS];
     const BitsArgs& b = a.b;
     const int F0 = b.F[0];
     for (int r = threadIdx.x; r < b.M; r += 256) {
         int lev = a.level[r];
-        int e = a.scale_exp[r];
         double pl = b.p_fixed[lev - 1];
-        s_c0[r] = (float)ldexp(1.0, e - F0);
-        s_cl[r] = pl == 0.0 ? 0.0f : (float)__ddiv_rn(ldexp(1.0, e - b.F[lev]), pl);
+        if (b.flt) {   // the level's weight fp32(1 / p_l)
+            s_c0[r] = 0.0f;
+            s_cl[r] = pl == 0.0 ? 0.0f : (float)__ddiv_rn(1.0, pl);
+        } else {
+            int e = a.scale_exp[r];
+            s_c0[r] = (float)ldexp(1.0, e - F0);
+            s_cl[r] = pl == 0.0 ? 0.0f : (float)__ddiv_rn(ldexp(1.0, e - b.F[lev]), pl);
+        }
         s_w[r] = (uint8_t)(b.F[lev] - b.F[lev - 1]);
+        s_fl[r] = (uint8_t)b.F[lev];
     }
     __syncthreads();
     const uint32_t lane = lane_id();
@@ -342,7 +365,39 @@ __global__ __launch_bounds__(256) void k_agg_bits(AggBitsArgs a, const uint64_t*
             const float cl = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(s_cl[r])));
             const uint64_t* rp = planes + (size_t)r * b.nplanes * nw + w0;
             const Words8 sg = load_words8(rp, nvalid);
-            if (F0 == 0 && wd == 1) {
+            if (b.flt) {
+                // App. B: sign, exponent field and base digits give C^{F_0}; the level digits, placed under the same
+                // sign and exponent, minus the bare power of two give the residual (exact); weight, then one add
+                const int Fl = __builtin_amdgcn_readfirstlane((int)s_fl[r]);
+                uint32_t ev[8], f[8], f0[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) { ev[k] = 0; f[k] = 0; f0[k] = 0; }
+                for (int q = 0; q < 8; ++q) {
+                    const Words8 pw = load_words8(rp + (size_t)(1 + q) * nw, nvalid);
+                    const uint32_t bit = 1u << (23 + q);
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) ev[k] |= __builtin_amdgcn_inverse_ballot_w64(pw.w[k]) ? bit : 0u;
+                }
+                for (int q = 0; q < F0; ++q) {
+                    const Words8 pw = load_words8(rp + (size_t)(9 + q) * nw, nvalid);
+                    const uint32_t bit = 1u << (23 - F0 + q);
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) f0[k] |= __builtin_amdgcn_inverse_ballot_w64(pw.w[k]) ? bit : 0u;
+                }
+                for (int q = 0; q < wd; ++q) {
+                    const Words8 pw = load_words8(rp + (size_t)(9 + F0 + q) * nw, nvalid);
+                    const uint32_t bit = 1u << (23 - Fl + q);
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) f[k] |= __builtin_amdgcn_inverse_ballot_w64(pw.w[k]) ? bit : 0u;
+                }
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const uint32_t se = ev[k] | (__builtin_amdgcn_inverse_ballot_w64(sg.w[k]) ? 0x80000000u : 0u);
+                    const float res = __fsub_rn(__uint_as_float(se | f[k]), __uint_as_float(se));
+                    const float v = __fadd_rn(__uint_as_float(se | f0[k]), __fmul_rn(res, cl));
+                    acc[k] = __fadd_rn(acc[k], v);
+                }
+            } else if (F0 == 0 && wd == 1) {
                 // f is 0 or 1: the entry is +-cl or absent (adding +0 leaves the sum as it is)
                 const Words8 fw = load_words8(rp + nw, nvalid);
 #pragma unroll
@@ -522,6 +577,7 @@ __global__ __launch_bounds__(256) void k_message_bits(MsgBitsArgs a) {
     const int64_t width = s_lad[lev] - s_lad[lev - 1];
     unsigned long long n;
     if (a.kind == MLMC_TOPK) n = (unsigned long long)(s_lad[0] + width) * (unsigned long long)(32 + ceil_log2_dev(a.d));
+    else if (a.kind == MLMC_FBITS) n = (unsigned long long)a.d * (unsigned long long)(9 + s_lad[0] + width);
     else n = (unsigned long long)a.d * (unsigned long long)(1 + s_lad[0] + width) + 32ull;
     a.bits[r] = n + (unsigned long long)ceil_log2_dev(a.L);
 }
@@ -542,6 +598,35 @@ mlmc_status message_bits(const mlmc_plan_t* pl, const int32_t* level, unsigned l
 // ---------------------------------------------------------------------------------------------------
 mlmc_status bits_compress(const mlmc_plan_t* pl, const BitsArgs& a, bool vec, hipStream_t st) {
     MLMC_LAUNCH(K_DRAW, st, k_bits_prep<<<1, 1024, 0, st>>>(a));
+    // a wave takes about four tiles (its loads run ahead across tiles); at least some 2048 waves in all
+    int64_t ntiles = pl->ntiles;
+    int gx = (int)((ntiles + 15) / 16);
+    if ((int64_t)gx * pl->M < 512) gx = (int)((ntiles + 3) / 4);
+    int cap = 4096 / pl->M > 0 ? 4096 / pl->M : 1;
+    if (gx > cap) gx = cap;
+    if (gx < 1) gx = 1;
+    dim3 egrid(gx, pl->M);
+#define MLMC_EXTRACT_V(ID, DT, VEC, REDO, FLT, SMALL, BIG)                                                              \
+    do {                                                                                                                \
+        if (small) MLMC_LAUNCH(ID, st, k_bits_extract<DT, VEC, REDO, SMALL, FLT><<<egrid, 256, 0, st>>>(a));             \
+        else MLMC_LAUNCH(ID, st, k_bits_extract<DT, VEC, REDO, BIG, FLT><<<egrid, 256, 0, st>>>(a));                     \
+    } while (0)
+#define MLMC_EXTRACT(ID, REDO, FLT, SMALL, BIG)                                                                         \
+    do {                                                                                                                \
+        if (pl->dtype == MLMC_F32) {                                                                                    \
+            if (vec) MLMC_EXTRACT_V(ID, MLMC_F32, true, REDO, FLT, SMALL, BIG);                                         \
+            else MLMC_EXTRACT_V(ID, MLMC_F32, false, REDO, FLT, SMALL, BIG);                                            \
+        } else {                                                                                                        \
+            if (vec) MLMC_EXTRACT_V(ID, MLMC_BF16, true, REDO, FLT, SMALL, BIG);                                        \
+            else MLMC_EXTRACT_V(ID, MLMC_BF16, false, REDO, FLT, SMALL, BIG);                                           \
+        }                                                                                                               \
+    } while (0)
+    if (a.flt) {
+        // floating-point ladder (App. B): no scale, so nothing to find before the one read
+        const bool small = pl->nplanes <= 11;
+        MLMC_EXTRACT(K_BITS_EXTRACT, false, true, 11, MAX_FPLANES);
+        return MLMC_OK;
+    }
     // sampled (or, for short rows, exact) row maxima
     const int64_t nblk = (pl->d + 1023) / 1024;
     const int64_t ns = (nblk >> a.sample_shift) > 0 ? (nblk >> a.sample_shift) : 1;
@@ -557,32 +642,9 @@ mlmc_status bits_compress(const mlmc_plan_t* pl, const BitsArgs& a, bool vec, hi
         if (vec) MLMC_LAUNCH(K_BITS_MAX, st, k_bits_smax<MLMC_BF16, true><<<sgrid, SMAX_THREADS, 0, st>>>(a));
         else MLMC_LAUNCH(K_BITS_MAX, st, k_bits_smax<MLMC_BF16, false><<<sgrid, SMAX_THREADS, 0, st>>>(a));
     }
-    // a wave takes about four tiles (its loads run ahead across tiles); at least some 2048 waves in all
-    int64_t ntiles = pl->ntiles;
-    int gx = (int)((ntiles + 15) / 16);
-    if ((int64_t)gx * pl->M < 512) gx = (int)((ntiles + 3) / 4);
-    int cap = 4096 / pl->M > 0 ? 4096 / pl->M : 1;
-    if (gx > cap) gx = cap;
-    if (gx < 1) gx = 1;
-    dim3 egrid(gx, pl->M);
     const bool small = pl->nplanes <= 9;
-#define MLMC_EXTRACT_V(ID, DT, VEC, REDO)                                                                               \
-    do {                                                                                                                \
-        if (small) MLMC_LAUNCH(ID, st, k_bits_extract<DT, VEC, REDO, 9><<<egrid, 256, 0, st>>>(a));                      \
-        else MLMC_LAUNCH(ID, st, k_bits_extract<DT, VEC, REDO, MAX_PLANES><<<egrid, 256, 0, st>>>(a));                   \
-    } while (0)
-#define MLMC_EXTRACT(ID, REDO)                                                                                          \
-    do {                                                                                                                \
-        if (pl->dtype == MLMC_F32) {                                                                                    \
-            if (vec) MLMC_EXTRACT_V(ID, MLMC_F32, true, REDO);                                                          \
-            else MLMC_EXTRACT_V(ID, MLMC_F32, false, REDO);                                                             \
-        } else {                                                                                                        \
-            if (vec) MLMC_EXTRACT_V(ID, MLMC_BF16, true, REDO);                                                         \
-            else MLMC_EXTRACT_V(ID, MLMC_BF16, false, REDO);                                                            \
-        }                                                                                                               \
-    } while (0)
-    MLMC_EXTRACT(K_BITS_EXTRACT, false);
-    if (a.sample_shift > 0) MLMC_EXTRACT(K_BITS_REDO, true);   // rows whose sampled maximum fell short (returns at once for the others)
+    MLMC_EXTRACT(K_BITS_EXTRACT, false, false, 9, MAX_PLANES);
+    if (a.sample_shift > 0) MLMC_EXTRACT(K_BITS_REDO, true, false, 9, MAX_PLANES);   // rows whose sampled maximum fell short (returns at once for the others)
 #undef MLMC_EXTRACT_V
 #undef MLMC_EXTRACT
     return MLMC_OK;

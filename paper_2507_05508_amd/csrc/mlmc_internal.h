@@ -18,7 +18,8 @@ constexpr int REP = 32;                 // lane-replicated LDS accumulators: slo
 constexpr int PMAX = 192;               // exact partial sums ("pieces") that the zones of one row contribute
 constexpr int PIECE_CLASSES = 96;       // (parts of a zone) x (exponents of a zone) handled by one finish workgroup
 constexpr int TILE = MLMC_TILE;
-constexpr int MAX_PLANES = 25;          // 1 sign + at most 24 field planes
+constexpr int MAX_PLANES = 25;          // fixed-point messages: 1 sign + at most 24 field planes
+constexpr int MAX_FPLANES = 32;         // floating-point messages: 1 sign + 8 exponent + at most 23 mantissa planes
 constexpr int CHUNK_MAX = 1 << 18;      // elements per workgroup chunk of the streaming kernels
 constexpr int CHUNKS_MAX = 8192;        // chunks per row
 constexpr int FH_BINS = 2048;           // bins of the zone-relative key histogram of the finish kernels
@@ -150,6 +151,7 @@ struct BitsArgs {
     int32_t M, L;
     int32_t F[TMAX];
     double p_fixed[LMAX];
+    int32_t flt;             // 1: floating-point ladder (App. B): F are mantissa digits, no scale
     int32_t nplanes;         // planes per row in the message buffer
     int64_t nwords;          // ceil(d / 64)
     int32_t chunk;

@@ -364,6 +364,129 @@ def test_bits_zero_and_denormal_rows():
     assert [int(x) for x in m] == [int(Fraction(abs(float(v))) / Fraction(2) ** e * 2 ** 16) for v in den]
 
 
+# ----------------------------------------------------------------------------- floating-point bit-wise ladder (App. B)
+def _fp_rows():
+    rng = np.random.default_rng(31)
+    g = (rng.standard_normal(400) * 10.0 ** rng.uniform(-12, 6, size=400)).astype(np.float32)
+    g[::23] = 0.0
+    g[5] = -0.0
+    g[7:12] = np.array([1e-40, -3e-41, 2e-45, 1.1754944e-38, -1.17549421e-38], dtype=np.float32)   # denormals and the first normal
+    g[12:15] = np.array([1.0, -2.0, 1.0e30], dtype=np.float32)
+    return g
+
+
+def test_float_truncate_is_the_mantissa_truncation():
+    """App. B: e = (-1)^S 2^(E-127) (1 + sum_j m_j 2^-j); C^F keeps sign, exponent and the first F mantissa digits.
+    Checked with exact rationals built by math.frexp (not from the bit pattern); distortion below 2^(E-127) 2^-F."""
+    g = _fp_rows()
+    for F in (0, 1, 5, 11, 22, 23):
+        t = O.float_truncate(g, F)
+        for j in range(g.size):
+            x = float(g[j])
+            if x == 0.0:
+                assert t[j] == 0.0 and np.signbit(t[j]) == np.signbit(g[j])
+                continue
+            m, e = math.frexp(abs(x))                      # |x| = m 2^e, 0.5 <= m < 1
+            e_eff = max(e, -125)                           # denormals: fixed exponent 2^-126, no leading one
+            unit = Fraction(2) ** (e_eff - 1)              # 2^(E' - 127): the weight of the digit before the binary point
+            q = unit / 2 ** F                              # resolution of C^F
+            want = (Fraction(abs(x)) // q) * q             # truncation to a multiple of the resolution
+            assert Fraction(abs(float(t[j]))) == want, (F, j, x)
+            assert np.signbit(t[j]) == np.signbit(g[j])
+            assert Fraction(abs(x)) - want < q
+    assert np.array_equal(O.float_truncate(g, 23).view(np.uint32), g.view(np.uint32))
+
+
+def test_fbits_telescoping_unbiasedness_and_second_moment():
+    """Lemma 3.2 for the mantissa ladder: C^{F_0} + sum_l (C^{F_l} - C^{F_{l-1}}) = C^{F_L} (= g when F_L = 23), hence
+    sum_l p_l g~(l) = g; and App. B's closed form of the residual's second moment for the unit ladder with
+    p_l = 2^-l / (1 - 2^-23): 2^(E-127) (1 - 2^-23) (|e| - 2^(E-127)) per normal entry (exact rationals)."""
+    g = _fp_rows()
+    for F in (list(range(24)), [0, 1, 2, 4, 8, 16, 23], [3, 5, 12, 20]):
+        L = len(F) - 1
+        p = O.geometric_p(L)
+        tele = O.float_truncate(g, F[0]).astype(np.float64)
+        for l in range(1, L + 1):
+            tele += O.float_truncate(g, F[l]).astype(np.float64) - O.float_truncate(g, F[l - 1]).astype(np.float64)
+        assert np.array_equal(tele, O.float_truncate(g, F[L]).astype(np.float64))
+        exp = np.zeros(g.size)
+        for l in range(1, L + 1):
+            est = O.fbits_estimate_dense(g, F, l, p[l - 1])
+            msg = O.compress_fbits_row(g, F, p, 0, 0, 0, force_level=l)
+            assert msg["planes"].shape[0] == 9 + F[0] + F[l] - F[l - 1]
+            assert np.array_equal(O.decode_fbits_row(msg, F, g.size).view(np.uint32), est.view(np.uint32))   # wire -> same estimate
+            exp += p[l - 1] * est.astype(np.float64)
+        assert np.allclose(exp, O.float_truncate(g, F[L]).astype(np.float64), rtol=3e-7, atol=0)
+    # second moment, unit ladder, exact: sum_l (1/p_l) (m_l 2^-l 2^(E-127))^2
+    F = list(range(24))
+    pf = [Fraction(1, 2 ** l) / (1 - Fraction(1, 2 ** 23)) for l in range(1, 24)]
+    for j in (1, 2, 3, 12, 13, 30, 31, 77):
+        x = Fraction(abs(float(g[j])))
+        if x == 0:
+            continue
+        m, e = math.frexp(float(x))
+        if e < -125:
+            continue
+        unit = Fraction(2) ** (e - 1)
+        second = Fraction(0)
+        for l in range(1, 24):
+            r = Fraction(float(O.float_truncate(g[j:j + 1], l)[0])) - Fraction(float(O.float_truncate(g[j:j + 1], l - 1)[0]))
+            second += r * r / pf[l - 1]
+        assert second == unit * (1 - Fraction(1, 2 ** 23)) * (x - unit)
+
+
+def test_fbits_planes_bit_by_bit_and_message_bits():
+    """Wire layout from Python integers (struct, not numpy views): plane 0 sign, planes 1..8 the exponent field LSB
+    first, then the base digits and the level digits as numbers, LSB first; word w bit b <-> element 64 w + b."""
+    import struct
+    g = _fp_rows()[:64 * 3 + 9]
+    d = g.size
+    for F in (list(range(24)), [2, 3, 8, 12]):
+        L = len(F) - 1
+        p = O.geometric_p(L)
+        for l in (1, 2, L):
+            msg = O.compress_fbits_row(g, F, p, 0, 0, 0, force_level=l)
+            width = F[l] - F[l - 1]
+            for j in (0, 1, 5, 7, 9, 12, 14, 63, 64, 65, d - 1):
+                u = struct.unpack("<I", struct.pack("<f", float(g[j])))[0]
+                sign, E, frac = u >> 31, (u >> 23) & 0xFF, u & 0x7FFFFF
+                base = frac >> (23 - F[0]) if F[0] else 0
+                field = (frac >> (23 - F[l])) & ((1 << width) - 1)
+                bit = lambda plane: (int(msg["planes"][plane][j // 64]) >> (j % 64)) & 1
+                assert bit(0) == sign
+                assert [bit(1 + b) for b in range(8)] == [(E >> b) & 1 for b in range(8)]
+                assert [bit(9 + b) for b in range(F[0])] == [(base >> b) & 1 for b in range(F[0])]
+                assert [bit(9 + F[0] + b) for b in range(width)] == [(field >> b) & 1 for b in range(width)]
+            assert not (msg["planes"][:, -1] >> np.uint64(d % 64)).any()
+    # App. B: 13 d + log2(52) bits for fp64 (sign + 11 exponent bits + one mantissa digit), here with the level rounded up
+    assert O.message_bits_floating_point(list(range(53)), 17, 1000, exponent_bits=11) == 13 * 1000 + 6
+    assert O.message_bits_floating_point(list(range(24)), 5, 1000) == 10 * 1000 + 5
+
+
+def test_aggregate_fbits_bruteforce():
+    """Server aggregate of floating-point messages, one coordinate at a time from the definition (truncations of the
+    worker's entry, scalar fp32 operations, worker order, alpha once)."""
+    rng = np.random.default_rng(41)
+    M, d = 4, 130
+    G = (rng.standard_normal((M, d)) * np.array([[1.0], [3e6], [2e-3], [40.0]])).astype(np.float32)
+    for F, alpha in (([0, 1, 2, 4, 8, 16, 23], 0.37), ([3, 5, 12, 20], 1.0 / 3.0)):
+        L = len(F) - 1
+        p = O.geometric_p(L)
+        msgs = O.compress_fbits(G, F, p, 11, 5)
+        levels = [O.draw_level(p, 11, 5, i) for i in range(M)]
+        assert [m["level"] for m in msgs] == levels and len(set(levels)) > 1
+        out = O.aggregate_fbits(msgs, F, d, alpha)
+        for j in range(d):
+            acc = np.float32(0.0)
+            for i in range(M):
+                l = levels[i]
+                e = G[i, j:j + 1]
+                r = np.float32(O.float_truncate(e, F[l])[0] - O.float_truncate(e, F[l - 1])[0])
+                v = np.float32(O.float_truncate(e, F[0])[0] + np.float32(r * np.float32(1.0 / p[l - 1])))
+                acc = np.float32(acc + v)
+            assert out[j] == np.float32(np.float32(alpha) * acc), (F, j)
+
+
 # ----------------------------------------------------------------------------- aggregate
 def test_aggregate_identity_special_case_is_alg1_mean():
     """L = 1, k_0 = 0, k_1 = d, p_1 = 1: g~ = g and the aggregate with alpha = 1/M is Alg. 1's mean."""
