@@ -34,6 +34,10 @@ def algorithmic_bytes(w, kernel, nnz_total, planes_bytes):
     in_bytes = w.M * w.d * s_in
     if kernel in ("k_main", "k_bits_max", "k_bits_smax"):
         return in_bytes                                   # one read of every input element
+    if kernel == "k_rs_scatter":
+        return 16 * w.M * w.d                             # a sort pass: every {key, index} pair read and written
+    if kernel == "k_rs_hist":
+        return 8 * w.M * w.d
     if kernel == "k_write":
         return in_bytes + 8 * nnz_total                   # read the rows, write (idx, val)
     if kernel == "k_agg_sparse":
@@ -85,7 +89,7 @@ def measured_traffic(workload, kernel):
 def _oracle_row(w, row_data, i):
     from oracle import mlmc as O
     p = None if w.adaptive else O.geometric_p(w.L)
-    if w.kind == "topk":
+    if w.kind in ("topk", "stopk"):
         return O.compress_topk_row(row_data, w.ladder, p, w.seed, 0, i)
     if w.kind == "fbits":
         return O.compress_fbits_row(row_data, w.ladder, p, w.seed, 0, i)
@@ -94,7 +98,7 @@ def _oracle_row(w, row_data, i):
 
 def _oracle_aggregate(w, msgs):
     from oracle import mlmc as O
-    if w.kind == "topk":
+    if w.kind in ("topk", "stopk"):
         return O.aggregate_sparse(msgs, w.d, 1.0 / w.M)
     if w.kind == "fbits":
         return O.aggregate_fbits(msgs, w.ladder, w.d, 1.0 / w.M)
@@ -215,7 +219,11 @@ def main():
     in_bytes = w.M * w.d * s_in
     alpha = 1.0 / w.M
 
-    if w.kind == "topk":
+    sparse = w.kind in ("topk", "stopk")
+    if w.kind == "stopk":
+        plan = P.Plan(P.MLMC_STOPK, w.M, w.d, P.MLMC_BF16 if w.dtype == "bf16" else P.MLMC_F32, [w.extra["s"]], None)
+        msg = P.SparseMessage(plan, with_norms=True)
+    elif w.kind == "topk":
         plan = P.Plan(P.MLMC_TOPK, w.M, w.d, P.MLMC_BF16 if w.dtype == "bf16" else P.MLMC_F32, w.ladder,
                       None if w.adaptive else P.mlmc_geometric_p(w.L))
         msg = P.SparseMessage(plan, with_norms=w.adaptive)
@@ -228,7 +236,7 @@ def main():
     x_model = torch.zeros(w.d, dtype=torch.float32, device=dev) if args.fused_update else None
 
     def step(i):
-        if w.kind == "topk":
+        if sparse:
             P.mlmc_compress_topk(plan, g, seed=w.seed, step=i, out=msg)
         else:
             P.mlmc_compress_bits(plan, g, seed=w.seed, step=i, out=msg)
@@ -269,15 +277,13 @@ def main():
     t1 = time.perf_counter()
     for i in range(args.steps):
         step(args.warmup + i)
-        if w.kind == "topk":
-            pass
     torch.cuda.synchronize()
     dt_ev = time.perf_counter() - t1
     P.mlmc_profile_enable(False)
     prof = P.mlmc_profile_get()
     # message sizes of those steps (needed for the algorithmic bytes): replay the draws, cheap
     for i in range(args.steps):
-        if w.kind == "topk":
+        if sparse:
             P.mlmc_compress_topk(plan, g, seed=w.seed, step=args.warmup + i, out=msg)
             nnz_total += int(msg.row_off[-1].item())
             for l in msg.level.cpu().numpy().tolist():
@@ -298,7 +304,7 @@ def main():
     dom_avg_s = prof[dominant][0] / prof[dominant][1] / 1e3
     dom_bytes = algorithmic_bytes(w, dominant, nnz_avg, planes_avg)
     achieved = dom_bytes / dom_avg_s / 1e9
-    if w.kind == "topk":
+    if sparse:
         step_alg_bytes = in_bytes + 16 * nnz_avg + 4 * w.d
     else:
         step_alg_bytes = in_bytes + 2 * planes_avg + 4 * w.d

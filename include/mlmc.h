@@ -58,10 +58,11 @@ typedef enum {
 #define MLMC_DEV_REDONE 8    /* not an error: a row's sampled threshold search was refuted and the row was redone exactly */
 
 typedef enum { MLMC_F32 = 0, MLMC_BF16 = 1 } mlmc_dtype;
-typedef enum { MLMC_TOPK = 0, MLMC_BITS = 1, MLMC_FBITS = 2 } mlmc_kind;
+typedef enum { MLMC_TOPK = 0, MLMC_BITS = 1, MLMC_FBITS = 2, MLMC_STOPK = 3 } mlmc_kind;
 
 #define MLMC_MAX_LEVELS 32   /* L <= 32 */
 #define MLMC_MAX_WORKERS 1024 /* M <= 1024 */
+#define MLMC_MAX_SLEVELS 65536 /* MLMC_STOPK: L = ceil(d / s) <= 65536 */
 #define MLMC_TILE 4096       /* elements per tile of the per-row offset table */
 
 /*
@@ -72,11 +73,16 @@ typedef enum { MLMC_TOPK = 0, MLMC_BITS = 1, MLMC_FBITS = 2 } mlmc_kind;
  *   kind == MLMC_FBITS: ladder = kept mantissa digits F_0..F_L, 0 <= F_0 < ... < F_L <= 23 (App. B: the
  *            floating-point compressor C^F keeps sign, exponent and the first F mantissa digits of every entry;
  *            the paper's ladder is F = 0, 1, ..., 52 for fp64, here 0..23 for fp32 inputs)
+ *   kind == MLMC_STOPK: s-segmented Top-k (Sec. 2.2, Sec. 3.2): ladder = {s} (one entry, the segment length, s >= 1);
+ *            the row sorted by magnitude is cut into segments of s entries, C^l keeps the first l of them, so
+ *            k_l = min(s l, d), g^0 = 0, and L must be ceil(d / s) <= MLMC_MAX_SLEVELS.  p_fixed must be NULL: the
+ *            probabilities are Lemma 3.4's, over all L levels, from every row itself (Alg. 3).  The message of a
+ *            row is its drawn segment (s entries; the last segment may be shorter).
  *   p_fixed: host, L entries for levels 1..L, each > 0, summing to 1 within 1e-9; NULL selects the
  *            adaptive probabilities of Lemma 3.4 (MLMC_TOPK only).  Lemma 3.3 / Lemma B.1: 2^-l / (1 - 2^-L).
  *   1 <= M <= MLMC_MAX_WORKERS, 1 <= d < 2^31, 1 <= L <= MLMC_MAX_LEVELS.
  * Outputs (host): *plan; *workspace_bytes; *sparse_capacity_worst = M * (k_0 + widest band) entries
- * (0 for MLMC_BITS).  Returns MLMC_EINVAL and leaves *plan NULL on a bad argument.
+ * (0 for the bit-wise kinds; M * s for MLMC_STOPK).  Returns MLMC_EINVAL and leaves *plan NULL on a bad argument.
  */
 mlmc_status mlmc_plan(mlmc_plan_t **plan, int kind, int M, int64_t d, int in_dtype, int L,
                       const int64_t *ladder, const double *p_fixed, size_t *workspace_bytes,
@@ -117,7 +123,7 @@ const char *mlmc_status_string(int status);
 
 /*
  * Per-level residual norms Delta_l = ||C_l(g) - C_{l-1}(g)||_2, l = 1..L, of every row (Lemma 3.4; for
- * rank bands Delta_l^2 is the sum of squares over band l, App. D).  MLMC_TOPK plans only.
+ * rank bands Delta_l^2 is the sum of squares over band l, App. D).  MLMC_TOPK and MLMC_STOPK plans.
  *   g: dev [M][ld];  norms: dev [M][L] fp64 (out);  dev_status: dev [1] int32 (out).
  */
 mlmc_status mlmc_level_norms(const mlmc_plan_t *plan, const void *g, int64_t ld, double *norms,
@@ -136,6 +142,7 @@ mlmc_status mlmc_level_norms(const mlmc_plan_t *plan, const void *g, int64_t ld,
  *   tile_off: dev [M][num_tiles + 1] uint32 (out) or NULL; tile_off[i][t] = number of entries of row i
  *            with idx < t * MLMC_TILE (so tile_off[i][num_tiles] = nnz_i).  Lets mlmc_aggregate skip a search.
  *   norms_out: dev [M][L] fp64 (out) or NULL; written only when p == NULL on an adaptive plan.
+ * MLMC_STOPK plans: p must be NULL and p_is_norms 0; every other argument as above (level in 1..ceil(d / s)).
  */
 mlmc_status mlmc_compress_topk(const mlmc_plan_t *plan, const void *g, int64_t ld, const double *p,
                                int p_is_norms, uint64_t seed, uint64_t step, int32_t *level,
@@ -183,7 +190,7 @@ mlmc_status mlmc_compress_bits_static(const mlmc_plan_t *plan, const void *g, in
 /*
  * Server side (Alg. 2 / Alg. 3 "Server aggregates"): out[j] = fp32(alpha * acc_j), acc_j the fp32 sum over
  * workers in worker order (alpha = 1/M gives the paper's mean).
- *   MLMC_TOPK plan: row_off, idx, val as written by mlmc_compress_topk (level unused, may be NULL);
+ *   MLMC_TOPK / MLMC_STOPK plan: row_off, idx, val as written by mlmc_compress_topk (level unused, may be NULL);
  *     capacity = entries that idx / val hold (as passed to mlmc_compress_topk): entries at positions >= capacity
  *     are never read, so a message that did not fit (MLMC_DEV_CAPACITY) cannot steer reads out of bounds;
  *     tile_off as written there, or NULL (then it is rebuilt by binary search into ws).  A worker without an
@@ -215,7 +222,7 @@ mlmc_status mlmc_aggregate_update(const mlmc_plan_t *plan, const int32_t *level,
 
 /*
  * Bits every worker's message of this step takes on the wire (the "communicated bits" of Sec. 5), from the drawn levels:
- *   MLMC_TOPK: nnz_i * (32 + ceil(log2 d)) + ceil(log2 L): every entry of the base band and of the drawn band as a
+ *   MLMC_TOPK, MLMC_STOPK: nnz_i * (32 + ceil(log2 d)) + ceil(log2 L): every entry of the base band and of the drawn band as a
  *     32-bit value and an index into d, plus the level (Sec. 3: the residual of Top-k is one rank band).
  *   MLMC_BITS: d * (1 + F_0 + F_l - F_{l-1}) + 32 + ceil(log2 L): per entry the sign, the base bits and the level
  *     field, plus the scale exponent and the level (Sec. 3.1; with F = 0..63 and a 64-bit scale: 2 d + 64 + 6).

@@ -59,6 +59,10 @@ WORKLOADS = {
     # bit-wise ladder at ResNet-18 scale
     "resnet18_bits": _mk("resnet18_bits", "bits", 8, 11_689_512, "f32", 5, [0, 1, 2, 4, 8, 16], False,
                          "segmented_normal", seed=0, steps=5, segments=62, std_lo=1e-4, std_hi=1e-1),
+    # s-segmented Top-k at ResNet-18 scale: s = 0.001 n (the smallest k of App. G.1), 1000 levels, adaptive p over all of them
+    "resnet18_stopk": _mk("resnet18_stopk", "stopk", 8, 11_689_512, "f32", 1000,
+                          [min(11_690 * l, 11_689_512) for l in range(1001)], True, "segmented_normal",
+                          seed=0, steps=5, segments=62, std_lo=1e-4, std_hi=1e-1, s=11_690),
     # floating-point bit-wise ladder (one mantissa digit per level) at ResNet-18 scale
     "resnet18_fbits": _mk("resnet18_fbits", "fbits", 8, 11_689_512, "f32", 23, list(range(24)), False,
                           "segmented_normal", seed=0, steps=5, segments=62, std_lo=1e-4, std_hi=1e-1),
@@ -72,6 +76,12 @@ WORKLOADS = {
 def scaled(w: Workload, d: int, M: Optional[int] = None, name: Optional[str] = None) -> Workload:
     """Same recipe at another size (used by parity tests: same structure, oracle-sized)."""
     M = w.M if M is None else M
+    if w.kind == "stopk":
+        s_len = max(1, d // 1000)
+        L = -(-d // s_len)
+        extra = dict(w.extra, s=s_len)
+        return Workload(name or f"{w.name}@d{d}m{M}", w.kind, M, d, w.dtype, L, tuple(min(s_len * l, d) for l in range(L + 1)),
+                        w.adaptive, w.gen, w.seed, w.steps, extra)
     if w.kind == "topk":
         if w.gen == "iid_normal":
             ladder = tuple(min(d, k) for k in w.ladder)

@@ -206,6 +206,14 @@ def compress_topk_row(row: np.ndarray, ladder: Sequence[int], p: Optional[Sequen
     return dict(level=level, weight=w, idx=idx, val=val.astype(np.float32), norms=norms, p=p)
 
 
+def stopk_ladder(d: int, s: int) -> List[int]:
+    """The ladder of s-segmented Top-k (Sec. 2.2): the vector sorted by magnitude is cut into segments of length s
+    (the last one may be shorter); C^l keeps the first l segments, so k_l = min(s l, d), l = 0..ceil(d / s), and the
+    residual g^l - g^{l-1} is the l-th segment (Sec. 3.2)."""
+    L = -(-d // s)
+    return [min(s * l, d) for l in range(L + 1)]
+
+
 def compress_topk(G: np.ndarray, ladder, p, seed: int, step: int, norms_override=None):
     """All M rows.  Row i is worker i.  p: list[L] shared by all rows, or None (adaptive).
     norms_override[i] (optional) replaces the oracle's own Delta for row i in the adaptive case."""

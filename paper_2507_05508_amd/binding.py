@@ -19,7 +19,8 @@ MLMC_OK, MLMC_EINVAL, MLMC_ENOMEM, MLMC_EHIP, MLMC_ELIMIT = 0, 1, 2, 3, 4
 MLMC_STATIC_SCRATCH_BYTES = 1 << 20
 MLMC_DEV_CAPACITY, MLMC_DEV_NONFINITE, MLMC_DEV_INTERNAL, MLMC_DEV_REDONE = 1, 2, 4, 8
 MLMC_F32, MLMC_BF16 = 0, 1
-MLMC_TOPK, MLMC_BITS, MLMC_FBITS = 0, 1, 2
+MLMC_TOPK, MLMC_BITS, MLMC_FBITS, MLMC_STOPK = 0, 1, 2, 3
+MLMC_MAX_SLEVELS = 65536
 MLMC_TILE = 4096
 MLMC_MAX_LEVELS = 32
 
@@ -131,11 +132,17 @@ class Plan:
 
     def __init__(self, kind: int, M: int, d: int, dtype: int, ladder: Sequence[int],
                  p_fixed: Optional[Sequence[float]], device="cuda:0", allocate: bool = True):
-        L = len(ladder) - 1
+        if kind == MLMC_STOPK:   # ladder = [s]: segments of s entries of the sorted row, L = ceil(d / s) levels
+            self.s = int(ladder[0])
+            L = -(-d // self.s) if self.s >= 1 else 0
+            self.ladder = [min(self.s * l, d) for l in range(L + 1)] if 1 <= L <= MLMC_MAX_SLEVELS else [self.s]
+            lad = (C.c_int64 * 1)(self.s)
+        else:
+            L = len(ladder) - 1
+            self.ladder = [int(x) for x in ladder]
+            lad = (C.c_int64 * (L + 1))(*self.ladder)
         self.kind, self.M, self.d, self.dtype, self.L = kind, M, d, dtype, L
-        self.ladder = [int(x) for x in ladder]
         self.p_fixed = None if p_fixed is None else [float(x) for x in p_fixed]
-        lad = (C.c_int64 * (L + 1))(*self.ladder)
         pf = None if p_fixed is None else (C.c_double * L)(*self.p_fixed)
         handle, wsb, cap = C.c_void_p(), C.c_size_t(), C.c_int64()
         rc = lib().mlmc_plan(C.byref(handle), kind, M, d, dtype, L, lad, pf, C.byref(wsb), C.byref(cap))
@@ -260,7 +267,7 @@ def mlmc_compress_bits_static(plan: Plan, g: torch.Tensor, seed: int, step: int,
 def mlmc_aggregate(plan: Plan, msg, alpha: float, out: Optional[torch.Tensor] = None, use_tile_off: bool = True) -> torch.Tensor:
     if out is None:
         out = torch.empty(plan.d, dtype=torch.float32, device=plan.device)
-    if plan.kind == MLMC_TOPK:
+    if plan.kind in (MLMC_TOPK, MLMC_STOPK):
         rc = lib().mlmc_aggregate(plan.handle, None, _ptr(msg.row_off), _ptr(msg.idx), _ptr(msg.val), msg.capacity,
                                   _ptr(msg.tile_off) if use_tile_off else None, None, None, float(alpha), _ptr(out),
                                   _ptr(plan.ws), _stream())
@@ -276,7 +283,7 @@ def mlmc_aggregate_update(plan: Plan, msg, alpha: float, eta: float, x: torch.Te
     """x <- x - eta * (alpha * sum of the workers' messages), in place; `out` (optional) also receives the update."""
     if x.dtype != torch.float32 or x.numel() != plan.d or not x.is_contiguous() or not x.is_cuda:
         raise MlmcError("x must be a contiguous float32 CUDA tensor [d]")
-    if plan.kind == MLMC_TOPK:
+    if plan.kind in (MLMC_TOPK, MLMC_STOPK):
         rc = lib().mlmc_aggregate_update(plan.handle, None, _ptr(msg.row_off), _ptr(msg.idx), _ptr(msg.val), msg.capacity,
                                          _ptr(msg.tile_off) if use_tile_off else None, None, None, float(alpha), float(eta),
                                          _ptr(x), _ptr(out), _ptr(plan.ws), _stream())

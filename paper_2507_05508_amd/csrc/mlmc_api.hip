@@ -20,6 +20,7 @@ mlmc_status agg_sparse(const mlmc_plan_t* pl, const int64_t* row_off, const uint
                        const uint32_t* tile_off, uint32_t* tile_off_ws, float alpha, float* out, float eta, float* x,
                        hipStream_t st);
 mlmc_status message_bits(const mlmc_plan_t* pl, const int32_t* level, unsigned long long* bits, hipStream_t st);
+mlmc_status stopk_run(const mlmc_plan_t* pl, const StopkArgs& a, bool message, hipStream_t st);
 
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -49,7 +50,8 @@ static mlmc_status static_scratch_of_current_device(void** out) {
 bool g_prof_on = false;
 static const char* const k_names[K_NUM] = {
     "k_zero", "k_hist", "k_scan", "k_main", "k_fhist", "k_finish", "k_finish_rank", "redo_pass", "k_norms", "k_bits_prep", "k_msgplan", "k_filter", "k_write",
-    "k_bits_smax", "k_bits_extract", "k_bits_redo", "k_agg_bits", "k_tileoff", "k_agg_sparse", "k_message_bits"};
+    "k_bits_smax", "k_bits_extract", "k_bits_redo", "k_agg_bits", "k_tileoff", "k_agg_sparse", "k_message_bits",
+    "k_rs_hist", "k_rs_scan", "k_rs_scatter", "k_sb_norms", "k_sb_draw", "k_sb_mark", "k_sb_offsets", "k_sb_write"};
 struct ProfPair { int id; hipEvent_t e0, e1; };
 static std::vector<ProfPair> g_pending;
 static std::vector<ProfPair> g_free;
@@ -203,10 +205,75 @@ mlmc_status mlmc_geometric_p(int L, double* p) {
     return MLMC_OK;
 }
 
+// s-segmented Top-k (Sec. 2.2, Sec. 3.2): uniform ladder k_l = min(s l, d), L = ceil(d / s) levels, adaptive p only.
+static mlmc_status plan_stopk(mlmc_plan_t** plan, int M, int64_t d, int in_dtype, int L, int64_t s, const double* p_fixed,
+                              size_t* workspace_bytes, int64_t* sparse_capacity_worst) {
+    if (in_dtype != MLMC_F32 && in_dtype != MLMC_BF16) return MLMC_EINVAL;
+    if (M < 1 || M > MLMC_MAX_WORKERS || d < 1 || d >= ((int64_t)1 << 31) || s < 1 || p_fixed) return MLMC_EINVAL;
+    const int64_t Lw = (d + s - 1) / s;
+    if (Lw > MLMC_MAX_SLEVELS || (int64_t)L != Lw) return MLMC_EINVAL;
+    mlmc_plan_t* pl = new (std::nothrow) mlmc_plan_t;
+    if (!pl) return MLMC_ENOMEM;
+    std::memset(pl, 0, sizeof(*pl));
+    pl->kind = MLMC_STOPK;
+    pl->M = M;
+    pl->dtype = in_dtype;
+    pl->L = L;
+    pl->d = d;
+    pl->s = s;
+    pl->adaptive = true;
+    pl->ntiles = (d + TILE - 1) / TILE;
+    pl->nblk = (int)((d + 8192 - 1) / 8192);
+    pl->bm_words = (d + 31) / 32;
+    size_t off = 0;
+    pl->off_bitmap = off;
+    off = align_up(off + sizeof(uint32_t) * (size_t)pl->bm_words * M + 16, 256);
+    pl->off_srow = off;
+    off = align_up(off + sizeof(SRow) * (size_t)M, 256);
+    pl->off_counts = off;
+    off = align_up(off + sizeof(uint32_t) * 256 * (size_t)pl->nblk * M, 256);
+    pl->off_tileoff = off;
+    off = align_up(off + sizeof(uint32_t) * (size_t)(pl->ntiles + 1) * M, 256);
+    pl->off_norms = off;
+    off = align_up(off + sizeof(double) * (size_t)L * M, 256);
+    pl->off_pa = off;
+    off = align_up(off + sizeof(uint2) * (size_t)d * M, 256);
+    pl->off_pb = off;
+    off = align_up(off + sizeof(uint2) * (size_t)d * M, 256);
+    pl->ws_bytes = off;
+    if (workspace_bytes) *workspace_bytes = off;
+    if (sparse_capacity_worst) *sparse_capacity_worst = (int64_t)M * (s < d ? s : d);
+    *plan = pl;
+    return MLMC_OK;
+}
+
+static void fill_stopk_args(const mlmc_plan_t* pl, StopkArgs& a, const void* g, int64_t ld, void* ws, int32_t* dev_status) {
+    std::memset(&a, 0, sizeof(a));
+    char* w = (char*)ws;
+    a.g = g;
+    a.ld = ld;
+    a.d = pl->d;
+    a.M = pl->M;
+    a.L = pl->L;
+    a.s = pl->s;
+    a.nblk = pl->nblk;
+    a.ntiles = pl->ntiles;
+    a.bm_words = pl->bm_words;
+    a.pa = (uint2*)(w + pl->off_pa);
+    a.pb = (uint2*)(w + pl->off_pb);
+    a.counts = (uint32_t*)(w + pl->off_counts);
+    a.bitmap = (uint32_t*)(w + pl->off_bitmap);
+    a.tile_off = (uint32_t*)(w + pl->off_tileoff);
+    a.norms = (double*)(w + pl->off_norms);
+    a.srow = (SRow*)(w + pl->off_srow);
+    a.dev_status = dev_status;
+}
+
 mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dtype, int L, const int64_t* ladder,
                       const double* p_fixed, size_t* workspace_bytes, int64_t* sparse_capacity_worst) {
     if (plan) *plan = nullptr;
     if (!plan || !ladder) return MLMC_EINVAL;
+    if (kind == MLMC_STOPK) return plan_stopk(plan, M, d, in_dtype, L, ladder[0], p_fixed, workspace_bytes, sparse_capacity_worst);
     if (kind != MLMC_TOPK && kind != MLMC_BITS && kind != MLMC_FBITS) return MLMC_EINVAL;
     if (in_dtype != MLMC_F32 && in_dtype != MLMC_BF16) return MLMC_EINVAL;
     if (M < 1 || M > MLMC_MAX_WORKERS || d < 1 || d >= ((int64_t)1 << 31) || L < 1 || L > MLMC_MAX_LEVELS) return MLMC_EINVAL;
@@ -363,9 +430,15 @@ int mlmc_plan_num_planes(const mlmc_plan_t* plan) { return plan ? plan->nplanes 
 
 mlmc_status mlmc_level_norms(const mlmc_plan_t* plan, const void* g, int64_t ld, double* norms, int32_t* dev_status,
                              void* ws, void* hip_stream) {
-    if (!plan || plan->kind != MLMC_TOPK || !g || !norms || !dev_status || !ws || ld < plan->d) return MLMC_EINVAL;
+    if (!plan || (plan->kind != MLMC_TOPK && plan->kind != MLMC_STOPK) || !g || !norms || !dev_status || !ws || ld < plan->d) return MLMC_EINVAL;
     if ((uintptr_t)ws % 256) return MLMC_EINVAL;
     hipStream_t st = (hipStream_t)hip_stream;
+    if (plan->kind == MLMC_STOPK) {
+        StopkArgs sa;
+        fill_stopk_args(plan, sa, g, ld, ws, dev_status);
+        sa.norms_user = norms;
+        return stopk_run(plan, sa, false, st);
+    }
     TopkArgs a;
     fill_topk_args(plan, a, g, ld, ws, dev_status);
     a.all_thresholds = 1;
@@ -380,9 +453,24 @@ mlmc_status mlmc_compress_topk(const mlmc_plan_t* plan, const void* g, int64_t l
                                uint64_t seed, uint64_t step, int32_t* level, int64_t* row_off, uint32_t* idx, float* val,
                                int64_t capacity, uint32_t* tile_off, double* norms_out, int32_t* dev_status, void* ws,
                                void* hip_stream) {
-    if (!plan || plan->kind != MLMC_TOPK || !g || !level || !row_off || !idx || !val || !dev_status || !ws) return MLMC_EINVAL;
+    if (!plan || (plan->kind != MLMC_TOPK && plan->kind != MLMC_STOPK) || !g || !level || !row_off || !idx || !val || !dev_status || !ws) return MLMC_EINVAL;
     if (ld < plan->d || capacity < 0 || (uintptr_t)ws % 256) return MLMC_EINVAL;
     hipStream_t st = (hipStream_t)hip_stream;
+    if (plan->kind == MLMC_STOPK) {
+        if (p || p_is_norms) return MLMC_EINVAL;   // Lemma 3.4 probabilities from the row itself, nothing else
+        StopkArgs sa;
+        fill_stopk_args(plan, sa, g, ld, ws, dev_status);
+        sa.level = level;
+        sa.row_off = row_off;
+        sa.idx = idx;
+        sa.val = val;
+        sa.capacity = capacity;
+        if (tile_off) sa.tile_off = tile_off;
+        sa.norms_user = norms_out;
+        sa.seed = seed;
+        sa.step = step;
+        return stopk_run(plan, sa, true, st);
+    }
     const bool vec = vec_ok(plan, g, ld);
     const bool internal_norms = plan->adaptive && p == nullptr;
     TopkArgs a;
@@ -419,7 +507,7 @@ mlmc_status mlmc_compress_topk(const mlmc_plan_t* plan, const void* g, int64_t l
 mlmc_status mlmc_compress_bits(const mlmc_plan_t* plan, const void* g, int64_t ld, uint64_t seed, uint64_t step,
                                int32_t* level, int32_t* scale_exp, uint64_t* planes, int32_t* dev_status, void* ws,
                                void* hip_stream) {
-    if (!plan || plan->kind == MLMC_TOPK || !g || !level || !planes || !dev_status || !ws) return MLMC_EINVAL;
+    if (!plan || (plan->kind != MLMC_BITS && plan->kind != MLMC_FBITS) || !g || !level || !planes || !dev_status || !ws) return MLMC_EINVAL;
     if (plan->kind == MLMC_BITS && !scale_exp) return MLMC_EINVAL;
     if (ld < plan->d || (uintptr_t)ws % 256) return MLMC_EINVAL;
     hipStream_t st = (hipStream_t)hip_stream;
@@ -436,7 +524,7 @@ mlmc_status mlmc_compress_bits(const mlmc_plan_t* plan, const void* g, int64_t l
 mlmc_status mlmc_compress_bits_static(const mlmc_plan_t* plan, const void* g, int64_t ld, uint64_t seed, uint64_t step,
                                       int32_t* level, int32_t* scale_exp, uint64_t* planes, int32_t* dev_status,
                                       void* hip_stream) {
-    if (!plan || plan->kind == MLMC_TOPK) return MLMC_EINVAL;
+    if (!plan || (plan->kind != MLMC_BITS && plan->kind != MLMC_FBITS)) return MLMC_EINVAL;
     if (plan->ws_bytes > (size_t)MLMC_STATIC_SCRATCH_BYTES) return MLMC_ELIMIT;   // before any HIP call
     void* ws = nullptr;
     const mlmc_status rc = static_scratch_of_current_device(&ws);
@@ -450,7 +538,7 @@ static mlmc_status aggregate_impl(const mlmc_plan_t* plan, const int32_t* level,
                                   const uint64_t* planes, float alpha, float* out, float eta, float* x, void* ws, void* hip_stream) {
     if (!plan || (!out && !x)) return MLMC_EINVAL;
     hipStream_t st = (hipStream_t)hip_stream;
-    if (plan->kind == MLMC_TOPK) {
+    if (plan->kind == MLMC_TOPK || plan->kind == MLMC_STOPK) {
         if (!row_off || !idx || !val || capacity < 0 || scale_exp || planes) return MLMC_EINVAL;
         if (!tile_off && (!ws || (uintptr_t)ws % 256)) return MLMC_EINVAL;
         uint32_t* tws = ws ? (uint32_t*)((char*)ws + plan->off_tileoff) : nullptr;

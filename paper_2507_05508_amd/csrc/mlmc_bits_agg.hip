@@ -561,21 +561,27 @@ __device__ __forceinline__ int ceil_log2_dev(int64_t n) { return n <= 1 ? 0 : 64
 // the level field, plus the 32-bit scale exponent and the level.
 struct MsgBitsArgs {
     int32_t kind, M, L;
-    int64_t d;
+    int64_t d, s;
     int64_t ladder[TMAX];
     const int32_t* level;
     unsigned long long* bits;
 };
 __global__ __launch_bounds__(256) void k_message_bits(MsgBitsArgs a) {
     __shared__ int64_t s_lad[TMAX];
-    if ((int)threadIdx.x <= a.L) s_lad[threadIdx.x] = a.ladder[threadIdx.x];
+    if (a.kind != MLMC_STOPK && (int)threadIdx.x <= a.L) s_lad[threadIdx.x] = a.ladder[threadIdx.x];
     __syncthreads();
     const int r = blockIdx.x * 256 + threadIdx.x;
     if (r >= a.M) return;
     int lev = a.level[r];
     lev = lev < 1 ? 1 : (lev > a.L ? a.L : lev);
-    const int64_t width = s_lad[lev] - s_lad[lev - 1];
     unsigned long long n;
+    if (a.kind == MLMC_STOPK) {   // the drawn segment: s entries, the last one what is left
+        const int64_t lo = (int64_t)(lev - 1) * a.s;
+        const int64_t cnt = lo + a.s < a.d ? a.s : a.d - lo;
+        a.bits[r] = (unsigned long long)cnt * (unsigned long long)(32 + ceil_log2_dev(a.d)) + (unsigned long long)ceil_log2_dev(a.L);
+        return;
+    }
+    const int64_t width = s_lad[lev] - s_lad[lev - 1];
     if (a.kind == MLMC_TOPK) n = (unsigned long long)(s_lad[0] + width) * (unsigned long long)(32 + ceil_log2_dev(a.d));
     else if (a.kind == MLMC_FBITS) n = (unsigned long long)a.d * (unsigned long long)(9 + s_lad[0] + width);
     else n = (unsigned long long)a.d * (unsigned long long)(1 + s_lad[0] + width) + 32ull;
@@ -588,7 +594,9 @@ mlmc_status message_bits(const mlmc_plan_t* pl, const int32_t* level, unsigned l
     a.M = pl->M;
     a.L = pl->L;
     a.d = pl->d;
-    for (int t = 0; t <= pl->L; ++t) a.ladder[t] = pl->ladder[t];
+    a.s = pl->s;
+    if (pl->kind != MLMC_STOPK)
+        for (int t = 0; t <= pl->L; ++t) a.ladder[t] = pl->ladder[t];
     a.level = level;
     a.bits = bits;
     MLMC_LAUNCH(K_MSGBITS, st, k_message_bits<<<(pl->M + 255) / 256, 256, 0, st>>>(a));

@@ -165,10 +165,42 @@ struct BitsArgs {
     int32_t* dev_status;
 };
 
+// s-segmented Top-k (uniform ladder k_l = min(s l, d), thousands of levels)
+constexpr int SLMAX = MLMC_MAX_SLEVELS;
+struct SRow {           // per row: the drawn segment
+    int32_t level;
+    float weight;
+    int64_t lo, count;  // its positions in the sorted row: [lo, lo + count)
+};
+struct StopkArgs {
+    const void* g;
+    int64_t ld, d;
+    int32_t M, L;
+    int64_t s;
+    int32_t nblk;            // sort blocks per row
+    int64_t ntiles, bm_words;
+    uint2* pa;               // [M][d] {inverted key, index} pairs, ping
+    uint2* pb;               // pong
+    uint32_t* counts;        // [M][256][nblk] digit counts / offsets of a sort pass
+    uint32_t* bitmap;        // [M][bm_words] entries of the drawn segment
+    uint32_t* tile_off;      // [M][ntiles + 1]
+    double* norms;           // [M][L]
+    double* norms_user;
+    SRow* srow;              // [M]
+    int32_t* level;
+    int64_t* row_off;
+    uint32_t* idx;
+    float* val;
+    int64_t capacity;
+    int32_t* dev_status;
+    uint64_t seed, step;
+};
+
 // ---- optional per-kernel timing with HIP events (host side, see mlmc_profile_* in mlmc.h) ----------
 enum KernelId {
     K_ZERO = 0, K_HIST, K_SCAN, K_MAIN, K_FHIST, K_FINISH, K_FINISH1, K_REDO, K_NORMS, K_DRAW, K_MSGPLAN, K_FILTER, K_WRITE,
-    K_BITS_MAX, K_BITS_EXTRACT, K_BITS_REDO, K_AGG_BITS, K_TILEOFF, K_AGG_SPARSE, K_MSGBITS, K_NUM
+    K_BITS_MAX, K_BITS_EXTRACT, K_BITS_REDO, K_AGG_BITS, K_TILEOFF, K_AGG_SPARSE, K_MSGBITS,
+    K_RS_HIST, K_RS_SCAN, K_RS_SCATTER, K_SB_NORMS, K_SB_DRAW, K_SB_MARK, K_SB_OFFSETS, K_SB_WRITE, K_NUM
 };
 extern bool g_prof_on;
 void prof_begin(int id, hipStream_t st);
@@ -202,4 +234,9 @@ struct mlmc_plan_s {
     size_t off_racc, off_hist, off_hist2, off_chunk_zcnt, off_zhist, off_zpacc, zero_bytes;  // [0, zero_bytes) is cleared per call
     size_t off_rinfo, off_table, off_chunk_cnt, off_zcol, off_tileoff, off_norms, off_cand, off_cand2, off_cand_priv, off_priv_cnt, off_chunk_base, off_row_order;
     size_t ws_bytes;
+    // s-segmented Top-k plans
+    int64_t s;
+    int nblk;
+    int64_t bm_words;
+    size_t off_pa, off_pb, off_counts, off_bitmap, off_srow;
 };

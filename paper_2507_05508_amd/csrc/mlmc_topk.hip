@@ -1433,33 +1433,6 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
 // ---------------------------------------------------------------------------------------------------
 // Delta_l (Lemma 3.4) from the exact group and part sums, then the adaptive draw.  One workgroup per row; the
 // 640-bit sums live in LDS.
-struct BigAcc {
-    uint32_t* w;  // 20 words, least significant first
-    // value * 2^-298 rounded to nearest-even fp64
-    __device__ double to_double() const {
-        int top = -1;
-        for (int i = 19; i >= 0; --i) if (w[i]) { top = i; break; }
-        if (top < 0) return 0.0;
-        const int P = top * 32 + 31 - __clz(w[top]);  // index of the most significant set bit
-        auto word = [&](int i) -> uint64_t { return (i < 0 || i >= 20) ? 0ull : (uint64_t)w[i]; };
-        if (P <= 52) {  // fits the significand exactly
-            uint64_t v = word(0) | (word(1) << 32);
-            return ldexp((double)v, -298);
-        }
-        // bits P .. P-52 as the significand, bit P-53 as guard, anything below as sticky
-        const int g = P - 53;                       // guard bit index (>= 0)
-        const int wi = g >> 5, bs = g & 31;         // window starting at the guard bit: 54 bits needed
-        uint64_t win = (word(wi) >> bs) | (word(wi + 1) << (32 - bs));
-        if (bs > 0) win |= word(wi + 2) << (64 - bs);
-        const uint32_t guard = (uint32_t)(win & 1ull);
-        uint64_t mant = (win >> 1) & ((1ull << 53) - 1ull);
-        bool sticky = bs ? (w[wi] & ((1u << bs) - 1u)) != 0 : false;
-        for (int i = wi - 1; i >= 0 && !sticky; --i) sticky = w[i] != 0;
-        if (guard && (sticky || (mant & 1ull))) ++mant;
-        return ldexp((double)mant, P - 52 - 298);
-    }
-};
-
 __global__ __launch_bounds__(256) void k_norms(TopkArgs a) {
     __shared__ uint32_t s_big[TMAX][20];
     __shared__ unsigned long long s_wide[TMAX][20];   // per 32-bit word position: sum of the addends' words, carries not yet propagated

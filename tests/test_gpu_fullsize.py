@@ -75,6 +75,22 @@ def test_topk_full_size(name, steps):
             _compare_with_oracle(tag, w, plan, msg, out, {i: want[i][si] for i in range(w.M)}, alpha)
 
 
+def test_stopk_full_size():
+    """s-segmented Top-k at s = 0.001 n: 1000 levels, every row against the oracle (one step)."""
+    w = W.WORKLOADS["resnet18_stopk"]
+    pool = OracleTopkRows(w.name, w.seed, (2,))
+    g = _upload(W.generate(w))
+    want = pool.result()
+    plan = P.Plan(P.MLMC_STOPK, w.M, w.d, P.MLMC_F32, [w.extra["s"]], None)
+    assert tuple(plan.ladder) == w.ladder
+    msg = P.SparseMessage(plan, with_norms=True)
+    P.mlmc_compress_topk(plan, g, seed=w.seed, step=2, out=msg)
+    out = P.mlmc_aggregate(plan, msg, 1.0 / w.M)
+    torch.cuda.synchronize()
+    assert plan.status() == 0
+    _compare_with_oracle("stopk step 2", w, plan, msg, out, {i: want[i][0] for i in range(w.M)}, 1.0 / w.M)
+
+
 def test_bits_full_size():
     w = W.WORKLOADS["resnet18_bits"]
     G = W.generate(w)

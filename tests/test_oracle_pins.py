@@ -266,6 +266,52 @@ def test_level_norms_exponential_decay_closed_form():
     assert abs(sum(x * x / q for x, q in zip(norms, p)) - math.fsum(norms) ** 2) <= 1e-9 * math.fsum(norms) ** 2
 
 
+def test_stopk_thousands_of_levels():
+    """s-segmented Top-k (Sec. 2.2, Sec. 3.2) with thousands of levels: the ladder, Pythagoras over all bands (App. D),
+    the exponential-decay closed form (Assumption 3.5 / App. E) at L = 2048, and Lemma 3.4's s-Top-k form
+    p_l = sqrt(alpha_l - alpha_{l-1}) / sum_l' sqrt(alpha_l' - alpha_{l'-1}) with alpha_l = ||C^l(v)||^2 / ||v||^2."""
+    assert O.stopk_ladder(10, 3) == [0, 3, 6, 9, 10] and O.stopk_ladder(9, 3) == [0, 3, 6, 9] and O.stopk_ladder(5, 8) == [0, 5]
+    d, s, r, v0 = 2048 * 16 + 5, 16, 0.0007, 2.0
+    ladder = O.stopk_ladder(d, s)
+    L = len(ladder) - 1
+    assert L == 2049 and ladder[-1] == d and ladder[-2] == 2048 * 16
+    mags = (v0 * np.exp(-0.5 * r * np.arange(d))).astype(np.float32)
+    rng = np.random.default_rng(12)
+    g = np.empty(d, dtype=np.float32)
+    g[rng.permutation(d)] = mags * rng.choice(np.array([-1.0, 1.0], dtype=np.float32), size=d)
+    norms, units = O.level_norms_row(g, ladder)
+    assert units[0] == 0 and sum(units) == O.exact_sumsq(g)                       # Pythagoras, exactly
+    for l in (1, 2, 100, 1024, 2048):
+        closed = v0 ** 2 * math.exp(-r * s * (l - 1)) * (1 - math.exp(-r * s)) / (1 - math.exp(-r))
+        assert abs(norms[l - 1] ** 2 - closed) <= 2e-6 * closed
+    # the residual of level l is the l-th segment of the sorted vector: s entries (the last segment: 5)
+    for l in (1, 777, L):
+        m = O.compress_topk_row(g, ladder, None, 3, 4, 0, force_level=l)
+        want = np.sort(np.argsort(-np.abs(g.astype(np.float64)), kind="stable")[s * (l - 1):s * l])
+        assert np.array_equal(m["idx"], want.astype(np.uint32)) and len(m["idx"]) == (5 if l == L else s)
+    # Lemma 3.4, s-Top-k form, from the compressions themselves (dense, fp64)
+    total = float(np.sum(g.astype(np.float64) ** 2))
+    alpha = [float(np.sum(O.topk_dense(g, k).astype(np.float64) ** 2)) / total for k in (ladder[0], ladder[1], ladder[2], ladder[99], ladder[100])]
+    p = O.adaptive_p(norms)
+    root_sum = math.fsum(norms) / math.sqrt(total)
+    assert abs(p[0] - math.sqrt(alpha[1] - alpha[0]) / root_sum) <= 1e-9
+    assert abs(p[1] - math.sqrt(alpha[2] - alpha[1]) / root_sum) <= 1e-9
+    assert abs(p[99] - math.sqrt(alpha[4] - alpha[3]) / root_sum) <= 1e-7
+    # the draw from a long CDF: frequencies of coarse groups of levels match their probability mass (3 sigma)
+    N = 4000
+    groups = [(0, 64), (64, 512), (512, L)]
+    cnt = [0, 0, 0]
+    T = O.cdf_thresholds(p)
+    for seed in range(N):
+        l = O.draw_level(p, seed, 1, 2)
+        assert 1 <= l <= L and level_uniform(seed, 1, 2) < T[l - 1] and (l == 1 or level_uniform(seed, 1, 2) >= T[l - 2])
+        for gi, (a, b) in enumerate(groups):
+            cnt[gi] += a < l <= b
+    for gi, (a, b) in enumerate(groups):
+        q = math.fsum(p[a:b])
+        assert abs(cnt[gi] / N - q) <= 3 * math.sqrt(q * (1 - q) / N)
+
+
 @pytest.mark.parametrize("adaptive", [False, True])
 def test_second_moment_closed_forms(adaptive):
     """App. D: E||g~||^2 = S_0 + sum_l S_l / p_l in general, = S_0 + (sum_l Delta_l)^2 for the adaptive p."""
