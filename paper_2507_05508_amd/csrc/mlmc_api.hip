@@ -224,7 +224,7 @@ static mlmc_status plan_stopk(mlmc_plan_t** plan, int M, int64_t d, int in_dtype
     pl->adaptive = true;
     pl->ntiles = (d + TILE - 1) / TILE;
     pl->nblk = (int)((d + 8192 - 1) / 8192);
-    pl->bm_words = (d + 31) / 32;
+    pl->bm_words = ((d + 31) / 32 + 3) / 4 * 4;   // whole 16-byte groups per row
     size_t off = 0;
     pl->off_bitmap = off;
     off = align_up(off + sizeof(uint32_t) * (size_t)pl->bm_words * M + 16, 256);
@@ -232,6 +232,8 @@ static mlmc_status plan_stopk(mlmc_plan_t** plan, int M, int64_t d, int in_dtype
     off = align_up(off + sizeof(SRow) * (size_t)M, 256);
     pl->off_counts = off;
     off = align_up(off + sizeof(uint32_t) * 256 * (size_t)pl->nblk * M, 256);
+    pl->off_bintot = off;
+    off = align_up(off + sizeof(uint32_t) * 256 * (size_t)M, 256);
     pl->off_tileoff = off;
     off = align_up(off + sizeof(uint32_t) * (size_t)(pl->ntiles + 1) * M, 256);
     pl->off_norms = off;
@@ -262,6 +264,7 @@ static void fill_stopk_args(const mlmc_plan_t* pl, StopkArgs& a, const void* g, 
     a.pa = (uint2*)(w + pl->off_pa);
     a.pb = (uint2*)(w + pl->off_pb);
     a.counts = (uint32_t*)(w + pl->off_counts);
+    a.bin_total = (uint32_t*)(w + pl->off_bintot);
     a.bitmap = (uint32_t*)(w + pl->off_bitmap);
     a.tile_off = (uint32_t*)(w + pl->off_tileoff);
     a.norms = (double*)(w + pl->off_norms);

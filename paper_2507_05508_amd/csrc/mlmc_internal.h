@@ -182,6 +182,7 @@ struct StopkArgs {
     uint2* pa;               // [M][d] {inverted key, index} pairs, ping
     uint2* pb;               // pong
     uint32_t* counts;        // [M][256][nblk] digit counts / offsets of a sort pass
+    uint32_t* bin_total;     // [M][256] elements of every digit bin
     uint32_t* bitmap;        // [M][bm_words] entries of the drawn segment
     uint32_t* tile_off;      // [M][ntiles + 1]
     double* norms;           // [M][L]
@@ -238,5 +239,5 @@ struct mlmc_plan_s {
     int64_t s;
     int nblk;
     int64_t bm_words;
-    size_t off_pa, off_pb, off_counts, off_bitmap, off_srow;
+    size_t off_pa, off_pb, off_counts, off_bitmap, off_srow, off_bintot;
 };

@@ -50,38 +50,42 @@ __global__ __launch_bounds__(RS_THREADS) void k_rs_hist(StopkArgs a, const uint2
     a.counts[((size_t)row * 256 + tid) * a.nblk + blk] = s_h[tid];
 }
 
-// Exclusive prefix of counts[row][.][.] in (bin, block) order: where every block's share of every bin starts.
+// Exclusive prefix of counts[row][bin][.] over the blocks, one workgroup per (bin, row), and the bin's total; the
+// scatter adds the totals of the lower bins.
 __global__ __launch_bounds__(1024) void k_rs_scan(StopkArgs a) {
     __shared__ uint32_t s_scan[1024 / 64 + 1];
-    const int row = blockIdx.x, tid = threadIdx.x;
-    uint32_t* c = a.counts + (size_t)row * 256 * a.nblk;
-    const int64_t n = (int64_t)256 * a.nblk;
-    const int64_t per = (n + 1023) / 1024;
-    const int64_t j0 = (int64_t)tid * per, j1 = j0 + per < n ? j0 + per : n;
-    uint32_t sum = 0;
-    for (int64_t j = j0; j < j1; ++j) sum += c[j];
-    uint32_t total;
-    uint32_t run = block_excl_scan<1024>(sum, s_scan, total);
-    for (int64_t j = j0; j < j1; ++j) {
-        const uint32_t v = c[j];
-        c[j] = run;
-        run += v;
+    const int bin = blockIdx.x, row = blockIdx.y, tid = threadIdx.x;
+    uint32_t* c = a.counts + ((size_t)row * 256 + bin) * a.nblk;
+    uint32_t carry = 0;
+    for (int j0 = 0; j0 < a.nblk; j0 += 1024) {
+        const int j = j0 + tid;
+        const uint32_t v = j < a.nblk ? c[j] : 0u;
+        uint32_t total;
+        const uint32_t ex = block_excl_scan<1024>(v, s_scan, total);
+        if (j < a.nblk) c[j] = carry + ex;
+        carry += total;
     }
-    if (tid == 0 && (int64_t)total != a.d) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
+    if (tid == 0) a.bin_total[row * 256 + bin] = carry;
 }
 
 // Stable scatter of one pass.  Order is kept at every step: a wave walks its elements in order, lanes of a group
 // rank themselves among the lanes with the same digit below them, waves and blocks start where the prefixes say.
+// The block's pairs are first put in digit order in LDS, then written out: pairs of one digit go to consecutive
+// addresses, so the writes come in runs instead of single 8-byte stores.
 template <int DT, bool FIRST>
 __global__ __launch_bounds__(RS_THREADS) void k_rs_scatter(StopkArgs a, const uint2* src, uint2* dst, int shift) {
     __shared__ uint32_t s_hist[RS_THREADS / 64][256];
-    __shared__ uint32_t s_base[RS_THREADS / 64][256];
+    __shared__ uint32_t s_base[RS_THREADS / 64][256];   // slot in the block's digit-ordered staging area
+    __shared__ uint32_t s_gstart[256];                  // global position of the block's first pair of a digit minus its slot
+    __shared__ uint32_t s_scan[RS_THREADS / 64 + 1];
+    __shared__ uint2 s_stage[RS_TILE];
     const int row = blockIdx.y, blk = blockIdx.x, tid = threadIdx.x;
     const uint32_t lane = lane_id(), wave = (uint32_t)__builtin_amdgcn_readfirstlane(tid >> 6);
     for (int i = tid; i < (RS_THREADS / 64) * 256; i += RS_THREADS) (&s_hist[0][0])[i] = 0;
     __syncthreads();
     RowLoader<DT, false> ld(a.g, a.ld, a.d, row);
-    const int64_t w0 = (int64_t)blk * RS_TILE + (int64_t)wave * RS_PER_WAVE;
+    const int64_t b0 = (int64_t)blk * RS_TILE;
+    const int64_t w0 = b0 + (int64_t)wave * RS_PER_WAVE;
     uint2 e[RS_GROUPS];
 #pragma unroll
     for (int q = 0; q < RS_GROUPS; ++q) {
@@ -93,7 +97,16 @@ __global__ __launch_bounds__(RS_THREADS) void k_rs_scatter(StopkArgs a, const ui
         if (w0 + q * 64 + lane < a.d) atomicAdd(&s_hist[wave][(e[q].x >> shift) & 255u], 1u);
     __syncthreads();
     {
-        uint32_t run = a.counts[((size_t)row * 256 + tid) * a.nblk + blk];
+        // digit `tid`: its pairs of this block start at (lower bins of the row) + (earlier blocks of the bin) in the
+        // output, and at (lower digits of this block) in the staging area
+        uint32_t row_total, blk_total, mine = 0;
+#pragma unroll
+        for (int w = 0; w < RS_THREADS / 64; ++w) mine += s_hist[w][tid];
+        const uint32_t lower = block_excl_scan<RS_THREADS>(a.bin_total[row * 256 + tid], s_scan, row_total);
+        if (tid == 0 && (int64_t)row_total != a.d) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
+        const uint32_t slot0 = block_excl_scan<RS_THREADS>(mine, s_scan, blk_total);
+        s_gstart[tid] = lower + a.counts[((size_t)row * 256 + tid) * a.nblk + blk] - slot0;
+        uint32_t run = slot0;
 #pragma unroll
         for (int w = 0; w < RS_THREADS / 64; ++w) {
             s_base[w][tid] = run;
@@ -101,7 +114,6 @@ __global__ __launch_bounds__(RS_THREADS) void k_rs_scatter(StopkArgs a, const ui
         }
     }
     __syncthreads();
-    uint2* out = dst + (size_t)row * a.d;
     const uint64_t below = lane == 0 ? 0ull : (~0ull >> (64 - lane));
 #pragma unroll
     for (int q = 0; q < RS_GROUPS; ++q) {
@@ -118,7 +130,14 @@ __global__ __launch_bounds__(RS_THREADS) void k_rs_scatter(StopkArgs a, const ui
         wave_lds_sync();   // every lane has read its base before a leader moves it on
         if (valid && rank == 0) s_base[wave][digit] = base + (uint32_t)__popcll(peers);
         wave_lds_sync();
-        if (valid) out[base + rank] = e[q];
+        if (valid) s_stage[base + rank] = e[q];
+    }
+    __syncthreads();
+    uint2* out = dst + (size_t)row * a.d;
+    const int nvalid = (int)(a.d - b0 < RS_TILE ? a.d - b0 : RS_TILE);
+    for (int i = tid; i < nvalid; i += RS_THREADS) {
+        const uint2 p = s_stage[i];
+        out[s_gstart[(p.x >> shift) & 255u] + (uint32_t)i] = p;
     }
 }
 
@@ -136,21 +155,39 @@ __global__ __launch_bounds__(SN_WAVES * 64) void k_sb_norms(StopkArgs a, const u
         if (lane < 20) s_wide[wave][lane] = 0ull;
         wave_lds_sync();
         const int64_t lo = band * a.s, hi = lo + a.s < a.d ? lo + a.s : a.d;
-        for (int64_t i = lo + lane; i < hi; i += 64) {
-            const uint32_t key = 0x7FFFFFFFu - sp[i].x;
-            const uint64_t sq = sig_square(key);
-            if (sq) {
-                const uint32_t E = key >> 23;
-                const int shift = 2 * ((int)(E ? E : 1u) - 1);
-                const int wi = shift >> 5, bs = shift & 31;
-                const uint32_t p0 = (uint32_t)(sq << bs);
-                const uint32_t p1 = (uint32_t)(bs ? sq >> (32 - bs) : sq >> 32);
-                const uint32_t p2 = bs ? (uint32_t)(sq >> (64 - bs)) : 0u;
-                if (p0) atomicAdd(&s_wide[wave][wi], (unsigned long long)p0);
+        // A lane meets its keys in descending order, so their exponents come in runs: the squares of a run are summed in
+        // registers (low and high halves apart, no overflow for any segment length) and reach LDS once per run.
+        auto flush = [&](uint32_t E, uint64_t slo, uint64_t shi) {
+            const int shift = 2 * ((int)(E ? E : 1u) - 1);
+            auto add = [&](uint64_t v, int sh) {
+                if (!v) return;
+                const int wi = sh >> 5, bs = sh & 31;
+                const uint32_t p0 = (uint32_t)(v << bs);
+                const uint32_t p1 = (uint32_t)(bs ? v >> (32 - bs) : v >> 32);
+                const uint32_t p2 = bs ? (uint32_t)(v >> (64 - bs)) : 0u;
+                if (p0 && wi < 20) atomicAdd(&s_wide[wave][wi], (unsigned long long)p0);
                 if (p1 && wi + 1 < 20) atomicAdd(&s_wide[wave][wi + 1], (unsigned long long)p1);
                 if (p2 && wi + 2 < 20) atomicAdd(&s_wide[wave][wi + 2], (unsigned long long)p2);
+            };
+            add(slo, shift);
+            add(shi, shift + 32);
+        };
+        uint32_t curE = 0xFFFFFFFFu;
+        uint64_t slo = 0, shi = 0;
+        for (int64_t i = lo + lane; i < hi; i += 64) {
+            const uint32_t key = 0x7FFFFFFFu - sp[i].x;
+            const uint32_t E = key >> 23;
+            if (E != curE) {
+                if (curE != 0xFFFFFFFFu) flush(curE, slo, shi);
+                curE = E;
+                slo = 0;
+                shi = 0;
             }
+            const uint64_t sq = sig_square(key);
+            slo += sq & 0xFFFFFFFFull;
+            shi += sq >> 32;
         }
+        if (curE != 0xFFFFFFFFu) flush(curE, slo, shi);
         wave_lds_sync();
         if (lane == 0) {
             unsigned long long carry = 0;
@@ -248,25 +285,33 @@ __global__ __launch_bounds__(1024) void k_sb_offsets(StopkArgs a) {
     const int row = blockIdx.x, tid = threadIdx.x;
     const uint32_t* bm = a.bitmap + (size_t)row * a.bm_words;
     uint32_t* to = a.tile_off + (size_t)row * (a.ntiles + 1);
-    const int64_t per = (a.ntiles + 1023) / 1024;
-    const int64_t t0 = (int64_t)tid * per, t1 = t0 + per < a.ntiles ? t0 + per : a.ntiles;
-    uint32_t sum = 0;
-    for (int64_t t = t0; t < t1; ++t) {
+    // a thread counts one tile at a time (its 128 bitmap words with loads issued together), 1024 tiles per round
+    uint32_t carry = 0;
+    for (int64_t j0 = 0; j0 < a.ntiles; j0 += 1024) {
+        const int64_t t = j0 + tid;
         uint32_t c = 0;
-        for (int w = 0; w < TILE / 32; ++w) {
-            const int64_t wi = t * (TILE / 32) + w;
-            if (wi < a.bm_words) c += (uint32_t)__popc(bm[wi]);
+        if (t < a.ntiles) {
+            const int64_t wbase = t * (TILE / 32);
+            if (wbase + TILE / 32 <= a.bm_words && (a.bm_words % 4) == 0) {
+                const uint4* p4 = (const uint4*)(bm + wbase);
+                uint4 v[8];
+                for (int q0 = 0; q0 < TILE / 128; q0 += 8) {
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) v[q] = p4[q0 + q];
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) c += (uint32_t)(__popc(v[q].x) + __popc(v[q].y) + __popc(v[q].z) + __popc(v[q].w));
+                }
+            } else {
+                for (int w = 0; w < TILE / 32; ++w)
+                    if (wbase + w < a.bm_words) c += (uint32_t)__popc(bm[wbase + w]);
+            }
         }
-        to[t] = c;   // count for now, offset below
-        sum += c;
+        uint32_t round_total;
+        const uint32_t ex = block_excl_scan<1024>(c, s_scan, round_total);
+        if (t < a.ntiles) to[t] = carry + ex;
+        carry += round_total;
     }
-    uint32_t total;
-    uint32_t run = block_excl_scan<1024>(sum, s_scan, total);
-    for (int64_t t = t0; t < t1; ++t) {
-        const uint32_t c = to[t];
-        to[t] = run;
-        run += c;
-    }
+    const uint32_t total = carry;
     if (tid == 0) {
         to[a.ntiles] = total;
         if ((int64_t)total != a.srow[row].count) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
@@ -337,11 +382,11 @@ static mlmc_status launch_stopk(const mlmc_plan_t* pl, const StopkArgs& a, bool 
         const uint2* src = shift == first_shift ? nullptr : bufs[cur ^ 1];
         if (shift == first_shift) {
             MLMC_LAUNCH(K_RS_HIST, st, k_rs_hist<DT, true><<<sgrid, RS_THREADS, 0, st>>>(a, src, shift));
-            MLMC_LAUNCH(K_RS_SCAN, st, k_rs_scan<<<pl->M, 1024, 0, st>>>(a));
+            MLMC_LAUNCH(K_RS_SCAN, st, k_rs_scan<<<dim3(256, pl->M), 1024, 0, st>>>(a));
             MLMC_LAUNCH(K_RS_SCATTER, st, k_rs_scatter<DT, true><<<sgrid, RS_THREADS, 0, st>>>(a, src, bufs[cur], shift));
         } else {
             MLMC_LAUNCH(K_RS_HIST, st, k_rs_hist<DT, false><<<sgrid, RS_THREADS, 0, st>>>(a, src, shift));
-            MLMC_LAUNCH(K_RS_SCAN, st, k_rs_scan<<<pl->M, 1024, 0, st>>>(a));
+            MLMC_LAUNCH(K_RS_SCAN, st, k_rs_scan<<<dim3(256, pl->M), 1024, 0, st>>>(a));
             MLMC_LAUNCH(K_RS_SCATTER, st, k_rs_scatter<DT, false><<<sgrid, RS_THREADS, 0, st>>>(a, src, bufs[cur], shift));
         }
         cur ^= 1;
