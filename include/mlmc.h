@@ -110,6 +110,9 @@ mlmc_status mlmc_plan_set_sampling(mlmc_plan_t *plan, int shift);
  */
 mlmc_status mlmc_plan_set_staging(mlmc_plan_t *plan, int enable);
 
+/* MLMC_TOPK plans: elements of a row that one workgroup of the selection read takes (a multiple of MLMC_TILE, at most
+ * 2^18); 0 for other plans.  For tests and tuning: results never depend on it. */
+int64_t mlmc_plan_chunk(const mlmc_plan_t *plan);
 /* Tiles per row of the offset table: ceil(d / MLMC_TILE). */
 int64_t mlmc_plan_num_tiles(const mlmc_plan_t *plan);
 /* Planes per row of the packed message: MLMC_BITS 1 + F_0 + max_l (F_l - F_{l-1}); MLMC_FBITS 9 + F_0 + max_l (F_l - F_{l-1});

@@ -24,7 +24,7 @@ MLMC_MAX_SLEVELS = 65536
 MLMC_TILE = 4096
 MLMC_MAX_LEVELS = 32
 
-EXPORTS = ["mlmc_plan", "mlmc_plan_destroy", "mlmc_plan_set_sampling", "mlmc_plan_set_staging", "mlmc_plan_num_tiles", "mlmc_plan_num_planes", "mlmc_geometric_p",
+EXPORTS = ["mlmc_plan", "mlmc_plan_destroy", "mlmc_plan_set_sampling", "mlmc_plan_set_staging", "mlmc_plan_num_tiles", "mlmc_plan_chunk", "mlmc_plan_num_planes", "mlmc_geometric_p",
            "mlmc_status_string", "mlmc_level_norms", "mlmc_compress_topk", "mlmc_compress_bits", "mlmc_compress_bits_static", "mlmc_aggregate", "mlmc_aggregate_update", "mlmc_message_bits",
            "mlmc_profile_enable", "mlmc_profile_reset", "mlmc_profile_num_kernels", "mlmc_profile_kernel_name",
            "mlmc_profile_get"]
@@ -55,6 +55,8 @@ def lib():
         L.mlmc_plan_set_staging.argtypes = [vp, i32]
         L.mlmc_plan_num_tiles.restype = i64
         L.mlmc_plan_num_tiles.argtypes = [vp]
+        L.mlmc_plan_chunk.restype = i64
+        L.mlmc_plan_chunk.argtypes = [vp]
         L.mlmc_plan_num_planes.restype = i32
         L.mlmc_plan_num_planes.argtypes = [vp]
         L.mlmc_geometric_p.restype = C.c_int
@@ -152,6 +154,7 @@ class Plan:
         self.sparse_capacity_worst = cap.value
         self.num_tiles = lib().mlmc_plan_num_tiles(handle)
         self.num_planes = lib().mlmc_plan_num_planes(handle)
+        self.chunk = lib().mlmc_plan_chunk(handle)
         self.device = torch.device(device)
         self.ws = None
         self.dev_status = None

@@ -429,6 +429,7 @@ mlmc_status mlmc_plan_set_staging(mlmc_plan_t* plan, int enable) {
 }
 
 int64_t mlmc_plan_num_tiles(const mlmc_plan_t* plan) { return plan ? plan->ntiles : 0; }
+int64_t mlmc_plan_chunk(const mlmc_plan_t* plan) { return plan && plan->kind == MLMC_TOPK ? plan->chunk : 0; }
 int mlmc_plan_num_planes(const mlmc_plan_t* plan) { return plan ? plan->nplanes : 0; }
 
 mlmc_status mlmc_level_norms(const mlmc_plan_t* plan, const void* g, int64_t ld, double* norms, int32_t* dev_status,

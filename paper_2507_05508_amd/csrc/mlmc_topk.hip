@@ -1951,7 +1951,13 @@ static mlmc_status launch_compact(const mlmc_plan_t* pl, const TopkArgs& a, hipS
     const dim3 grid(pl->chunks_per_row, pl->M), wgrid(pl->cchunks_per_row, pl->M);
     // rows whose drawn band was staged get their message from the staged lists, the others from a second read
     MLMC_LAUNCH(K_MSGPLAN, st, k_msgplan<<<pl->M, MP_THREADS, 0, st>>>(a));
-    MLMC_LAUNCH(K_FILTER, st, k_filter<<<grid, FL_THREADS, (size_t)pl->chunk / 32 * 8, st>>>(a));
+    // the bitmap and its prefix: chunk / 32 words each, up to 64 KB for the largest chunk; a workgroup may need the
+    // limit on dynamic LDS raised for that (static arrays come on top)
+    const size_t fl_lds = (size_t)pl->chunk / 32 * 8;
+    if (fl_lds > 48 * 1024 &&
+        hipFuncSetAttribute((const void*)k_filter, hipFuncAttributeMaxDynamicSharedMemorySize, (int)fl_lds) != hipSuccess)
+        return MLMC_EHIP;
+    MLMC_LAUNCH(K_FILTER, st, k_filter<<<grid, FL_THREADS, fl_lds, st>>>(a));
     MLMC_LAUNCH(K_WRITE, st, k_write<DT, VEC><<<wgrid, WR_THREADS, 0, st>>>(a));
     return MLMC_OK;
 }

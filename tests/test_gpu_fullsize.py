@@ -75,6 +75,28 @@ def test_topk_full_size(name, steps):
             _compare_with_oracle(tag, w, plan, msg, out, {i: want[i][si] for i in range(w.M)}, alpha)
 
 
+def test_topk_largest_chunk():
+    """A shape whose plan takes the largest chunk (2^18 elements per workgroup of the selection read: the widest LDS
+    bitmap of the message kernel, eight count chunks per thread in the planner), every row against the oracle."""
+    name, d, M, step = "resnet50_adaptive_topk", 46_000_000, 16, 1
+    w = W.scaled(W.WORKLOADS[name], d=d, M=M)
+    pool = OracleTopkRows(name, w.seed, (step,), d=d, M=M)
+    print("largest chunk: generating the rows", flush=True)
+    g = _upload(W.generate(w))
+    plan = P.Plan(P.MLMC_TOPK, M, d, P.MLMC_F32, w.ladder, None)
+    assert plan.chunk == 1 << 18
+    want = pool.result()
+    msg = P.SparseMessage(plan, with_norms=True)
+    for staging in (True, False):
+        print(f"largest chunk: staging {staging}", flush=True)
+        plan.set_staging(staging)
+        P.mlmc_compress_topk(plan, g, seed=w.seed, step=step, out=msg)
+        out = P.mlmc_aggregate(plan, msg, 1.0 / M)
+        torch.cuda.synchronize()
+        assert plan.status() == 0
+        _compare_with_oracle(f"largest chunk staging {staging}", w, plan, msg, out, {i: want[i][0] for i in range(M)}, 1.0 / M)
+
+
 def test_stopk_full_size():
     """s-segmented Top-k at s = 0.001 n: 1000 levels, every row against the oracle (one step)."""
     w = W.WORKLOADS["resnet18_stopk"]
