@@ -17,6 +17,8 @@ What is computed, with the passages it follows:
 * Fixed probabilities of the geometric form of Lemma 3.3: p^l = 2^-l / (1 - 2^-L), l = 1..L.
 * Fixed-point bit-wise compressor (Sec. 2.2 "Fixed-point compressors", Sec. 3.1): entries are normalised
   to magnitude < 1, written as sign + binary fraction, and C^F keeps the F most significant fraction bits.
+* The same ladder with the entries divided by the largest entry itself, as Sec. 3.1 writes it (`vmax_digits` and the
+  `*_vbits*` functions): the digits of |g_j| / max|g|, capped at 2^Q - 1 for the entries of the largest magnitude.
 * Server aggregate (Alg. 2 / Alg. 3 "Server aggregates"): out = alpha * sum_i g~_i, alpha = 1/M for the mean.
 
 Readings where the paper is silent (each is also what the HIP library documents):
@@ -316,6 +318,86 @@ def decode_bits_row(msg, F: Sequence[int], d: int) -> np.ndarray:
 
 def compress_bits(G: np.ndarray, F, p, seed: int, step: int):
     return [compress_bits_row(G[i], F, p, seed, step, i) for i in range(G.shape[0])]
+
+
+# ----------------------------------------------------------------------------------------------
+# fixed-point bit-wise MLMC, entries divided by the largest entry itself (Sec. 3.1 as written)
+# ----------------------------------------------------------------------------------------------
+def vmax_digits(g32: np.ndarray, Q: int):
+    """Sec. 3.1 divides every entry by the largest entry v = max_j |g_j| and expands |g_j| / v in binary.  The first Q
+    digits as an integer: m_j = min(floor(|g_j| / v * 2^Q), 2^Q - 1); the cap is the reading for the entries with
+    |g_j| = v, whose quotient 1 has no expansion below 1.  Returns (m, v); a zero row gives m = 0, v = 0.
+    The quotient is taken in fp64: |g_j| 2^Q and v are exact there, the division is correctly rounded, and a quotient
+    that is not an integer lies at least 2^-24 away from the next one (its denominator divides v's 24-bit
+    significand), far more than the rounding error of a number below 2^24: so the floor is that of the exact ratio."""
+    a = np.abs(g32.astype(np.float64))
+    v = np.float32(np.abs(g32).max()) if g32.size else np.float32(0.0)
+    if v == 0.0:
+        return np.zeros(g32.shape, dtype=np.uint64), v
+    q = np.floor(np.ldexp(a, Q) / np.float64(v))
+    return np.minimum(q, float((1 << Q) - 1)).astype(np.uint64), v
+
+
+def vbits_truncate_dense(row: np.ndarray, F: int, Q: int) -> np.ndarray:
+    """C^F(g) of this ladder: sign_j * (m_j >> (Q - F)) * 2^-F * v, as float64 values."""
+    g = as_f32(row)
+    m, v = vmax_digits(g, Q)
+    kept = (m >> np.uint64(Q - F)).astype(np.float64)
+    return np.where(np.signbit(g), -1.0, 1.0) * np.ldexp(kept, -F) * np.float64(v)
+
+
+def compress_vbits_row(row: np.ndarray, F: Sequence[int], p: Sequence[float], seed: int, step: int,
+                       worker: int, force_level: Optional[int] = None):
+    """One worker's message: level, the largest entry v (an fp32 number, "transmitted" with the message, Sec. 3.1),
+    and the same planes as the power-of-two ladder: sign, F_0 base planes, F_l - F_{l-1} level planes, LSB first."""
+    g = as_f32(row)
+    L = len(F) - 1
+    Q = F[L]
+    assert 0 <= F[0] and all(F[i] < F[i + 1] for i in range(L)) and Q <= 24
+    m, v = vmax_digits(g, Q)
+    level = draw_level(p, seed, step, worker) if force_level is None else int(force_level)
+    width = F[level] - F[level - 1]
+    field = (m >> np.uint64(Q - F[level])) & np.uint64((1 << width) - 1)
+    base = (m >> np.uint64(Q - F[0])) if F[0] > 0 else np.zeros_like(m)
+    planes = [pack_plane(np.signbit(g))]
+    for b in range(F[0]):
+        planes.append(pack_plane(((base >> np.uint64(b)) & np.uint64(1)).astype(bool)))
+    for b in range(width):
+        planes.append(pack_plane(((field >> np.uint64(b)) & np.uint64(1)).astype(bool)))
+    return dict(level=level, vmax=np.float32(v), planes=np.stack(planes), p_level=float(p[level - 1]))
+
+
+def decode_vbits_row(msg, F: Sequence[int], d: int) -> np.ndarray:
+    """g~_j = sign_j * [ fp32(f0_j) * c_0 + fp32(f_j) * c_l ], c_0 = fp32(v 2^-F_0), c_l = fp32(v 2^-F_l / p_l)
+    (the constants in fp64, rounded once); products and the sum are single fp32 operations."""
+    level, planes = msg["level"], msg["planes"]
+    v = float(msg["vmax"])
+    width = F[level] - F[level - 1]
+    sign = unpack_plane(planes[0], d)
+    f0 = np.zeros(d, dtype=np.uint32)
+    for b in range(F[0]):
+        f0 |= unpack_plane(planes[1 + b], d).astype(np.uint32) << np.uint32(b)
+    f = np.zeros(d, dtype=np.uint32)
+    for b in range(width):
+        f |= unpack_plane(planes[1 + F[0] + b], d).astype(np.uint32) << np.uint32(b)
+    p_l = msg["p_level"]
+    c_l = np.float32(math.ldexp(v, -F[level]) / p_l) if p_l != 0.0 else np.float32(0.0)
+    val = f.astype(np.float32) * c_l
+    if F[0] > 0:
+        c_0 = np.float32(math.ldexp(v, -F[0]))
+        val = f0.astype(np.float32) * c_0 + val
+    return np.where(sign, -val, val).astype(np.float32)
+
+
+def compress_vbits(G: np.ndarray, F, p, seed: int, step: int):
+    return [compress_vbits_row(G[i], F, p, seed, step, i) for i in range(G.shape[0])]
+
+
+def aggregate_vbits(msgs, F, d: int, alpha: float) -> np.ndarray:
+    acc = np.zeros(d, dtype=np.float32)
+    for msg in msgs:
+        acc = acc + decode_vbits_row(msg, F, d)
+    return (np.float32(alpha) * acc).astype(np.float32)
 
 
 # ----------------------------------------------------------------------------------------------

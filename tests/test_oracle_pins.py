@@ -410,6 +410,95 @@ def test_bits_zero_and_denormal_rows():
     assert [int(x) for x in m] == [int(Fraction(abs(float(v))) / Fraction(2) ** e * 2 ** 16) for v in den]
 
 
+# ----------------------------------------------------------------------------- fixed point, divided by the largest entry (Sec. 3.1)
+def _vmax_rows():
+    rng = np.random.default_rng(77)
+    rows = [rng.standard_normal(300).astype(np.float32) * np.float32(0.37)]
+    r = (rng.standard_normal(200) * 10.0 ** rng.uniform(-20, 3, size=200)).astype(np.float32)
+    r[3] = -r[np.argmax(np.abs(r))]                       # the largest magnitude twice, with both signs
+    rows.append(r)
+    rows.append(np.array([3.0, -1.5, 0.75, 3.0, -3.0, 1e-40, 0.0, -0.0, 2.9999998], dtype=np.float32))
+    rows.append(np.array([1e-40, -3e-41, 0, 2e-45, 1.1754944e-38], dtype=np.float32))     # largest entry barely normal
+    rows.append(np.array([2e-45, -1e-45, 0], dtype=np.float32))                           # largest entry the 2nd denormal
+    return rows
+
+
+def _exact_vdigit(x: float, v: float, Q: int) -> int:
+    """min(floor(|x| / v 2^Q), 2^Q - 1) in exact rationals."""
+    return min(int(Fraction(abs(float(x))) / Fraction(float(v)) * 2 ** Q), 2 ** Q - 1)
+
+
+def test_vmax_digits_are_the_expansion_of_the_quotient():
+    """Sec. 3.1: entries divided by the largest entry, |e| <= 1, binary expansion: digits against exact rationals,
+    the distortion bound 2^-F of the truncations, the cap for |e| = 1."""
+    for g in _vmax_rows():
+        for Q in (1, 7, 16, 24):
+            m, v = O.vmax_digits(g, Q)
+            assert float(v) == max(abs(float(x)) for x in g)
+            assert [int(x) for x in m] == [_exact_vdigit(x, v, Q) for x in g]
+            assert int(m[int(np.argmax(np.abs(g)))]) == 2 ** Q - 1
+        for F in (1, 2, 4, 8, 16):
+            t = O.vbits_truncate_dense(g, F, 16)
+            v = Fraction(float(np.abs(g).max()))
+            for j in range(g.size):
+                err = abs(Fraction(abs(float(g[j]))) - Fraction(abs(float(t[j]))))
+                assert err <= v / 2 ** F and (np.signbit(t[j]) == np.signbit(g[j]) or t[j] == 0)
+    m, v = O.vmax_digits(np.zeros(70, dtype=np.float32), 16)
+    assert v == 0 and not m.any()
+
+
+def test_vbits_telescoping_expectation_layout_and_aggregate():
+    """Lemma 3.2 for this ladder (sum_l p_l g~(l) = C^{F_L}(g)); the wire layout bit by bit and the server's sum
+    coordinate by coordinate from exact-rational digits and scalar fp32 operations in worker order."""
+    w = W.scaled(W.WORKLOADS["resnet18_bits"], d=64 * 3 + 11, M=4)
+    G = W.generate(w)
+    G[1] *= np.float32(3.0e6)
+    G[2] *= np.float32(1.7e3)
+    G[3, ::2] *= np.float32(-1.0)
+    d, M = w.d, w.M
+    for F, alpha in (([0, 1, 2, 4, 8, 16], 1.0 / 3.0), ([3, 5, 8, 12, 19], 0.37)):
+        L, Q = len(F) - 1, F[-1]
+        p = O.geometric_p(L)
+        g = G[0]
+        v0 = float(np.abs(g).max())
+        exp = np.zeros(d)
+        for l in range(1, L + 1):
+            msg = O.compress_vbits_row(g, F, p, 0, 0, 0, force_level=l)
+            width = F[l] - F[l - 1]
+            assert msg["planes"].shape == (1 + F[0] + width, (d + 63) // 64) and float(msg["vmax"]) == v0
+            for j in (0, 1, 63, 64, 65, d - 2, d - 1, int(np.argmax(np.abs(g)))):
+                m = _exact_vdigit(g[j], v0, Q)
+                base = m >> (Q - F[0]) if F[0] else 0
+                field = (m >> (Q - F[l])) & ((1 << width) - 1)
+                bit = lambda plane: (int(msg["planes"][plane][j // 64]) >> (j % 64)) & 1
+                assert bit(0) == int(np.signbit(g[j]))
+                for b in range(F[0]):
+                    assert bit(1 + b) == (base >> b) & 1
+                for b in range(width):
+                    assert bit(1 + F[0] + b) == (field >> b) & 1
+            assert not (msg["planes"][:, -1] >> np.uint64(d % 64)).any()
+            exp += p[l - 1] * O.decode_vbits_row(msg, F, d).astype(np.float64)
+        assert np.allclose(exp, O.vbits_truncate_dense(g, Q, Q), rtol=2e-6, atol=0)
+        seed, step = 11, 5
+        msgs = O.compress_vbits(G, F, p, seed, step)
+        levels = [O.draw_level(p, seed, step, i) for i in range(M)]
+        assert len(set(levels)) > 1 and [m["level"] for m in msgs] == levels
+        out = O.aggregate_vbits(msgs, F, d, alpha)
+        for j in range(d):
+            acc = np.float32(0.0)
+            for i in range(M):
+                l = levels[i]
+                v = float(np.abs(G[i]).max())
+                m = _exact_vdigit(G[i, j], v, Q)
+                f0 = m >> (Q - F[0]) if F[0] else 0
+                f = (m >> (Q - F[l])) & ((1 << (F[l] - F[l - 1])) - 1)
+                val = np.float32(np.float32(f) * np.float32(math.ldexp(v, -F[l]) / p[l - 1]))
+                if F[0]:
+                    val = np.float32(np.float32(np.float32(f0) * np.float32(math.ldexp(v, -F[0]))) + val)
+                acc = np.float32(acc + (-val if np.signbit(G[i, j]) else val))
+            assert out[j] == np.float32(np.float32(alpha) * acc), (F, j)
+
+
 # ----------------------------------------------------------------------------- floating-point bit-wise ladder (App. B)
 def _fp_rows():
     rng = np.random.default_rng(31)
