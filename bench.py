@@ -93,6 +93,8 @@ def _oracle_row(w, row_data, i):
         return O.compress_topk_row(row_data, w.ladder, p, w.seed, 0, i)
     if w.kind == "fbits":
         return O.compress_fbits_row(row_data, w.ladder, p, w.seed, 0, i)
+    if w.kind == "vbits":
+        return O.compress_vbits_row(row_data, w.ladder, p, w.seed, 0, i)
     return O.compress_bits_row(row_data, w.ladder, p, w.seed, 0, i)
 
 
@@ -102,6 +104,8 @@ def _oracle_aggregate(w, msgs):
         return O.aggregate_sparse(msgs, w.d, 1.0 / w.M)
     if w.kind == "fbits":
         return O.aggregate_fbits(msgs, w.ladder, w.d, 1.0 / w.M)
+    if w.kind == "vbits":
+        return O.aggregate_vbits(msgs, w.ladder, w.d, 1.0 / w.M)
     return O.aggregate_bits(msgs, w.ladder, w.d, 1.0 / w.M)
 
 
@@ -230,7 +234,8 @@ def main():
         if args.no_staging:
             plan.set_staging(False)
     else:
-        plan = P.Plan(P.MLMC_FBITS if w.kind == "fbits" else P.MLMC_BITS, w.M, w.d, P.MLMC_F32, w.ladder, P.mlmc_geometric_p(w.L))
+        kind = {"bits": P.MLMC_BITS, "fbits": P.MLMC_FBITS, "vbits": P.MLMC_VBITS}[w.kind]
+        plan = P.Plan(kind, w.M, w.d, P.MLMC_F32, w.ladder, P.mlmc_geometric_p(w.L))
         msg = P.BitsMessage(plan)
     out = torch.empty(w.d, dtype=torch.float32, device=dev)
     x_model = torch.zeros(w.d, dtype=torch.float32, device=dev) if args.fused_update else None

@@ -58,7 +58,7 @@ typedef enum {
 #define MLMC_DEV_REDONE 8    /* not an error: a row's sampled threshold search was refuted and the row was redone exactly */
 
 typedef enum { MLMC_F32 = 0, MLMC_BF16 = 1 } mlmc_dtype;
-typedef enum { MLMC_TOPK = 0, MLMC_BITS = 1, MLMC_FBITS = 2, MLMC_STOPK = 3 } mlmc_kind;
+typedef enum { MLMC_TOPK = 0, MLMC_BITS = 1, MLMC_FBITS = 2, MLMC_STOPK = 3, MLMC_VBITS = 4 } mlmc_kind;
 
 #define MLMC_MAX_LEVELS 32   /* L <= 32 */
 #define MLMC_MAX_WORKERS 1024 /* M <= 1024 */
@@ -70,6 +70,11 @@ typedef enum { MLMC_TOPK = 0, MLMC_BITS = 1, MLMC_FBITS = 2, MLMC_STOPK = 3 } ml
  * probabilities) for M workers of dimension d (Sec. 2.1).
  *   kind == MLMC_TOPK: ladder = ranks k_0..k_L, 0 <= k_0 < k_1 < ... < k_L <= d        (Sec. 3.2)
  *   kind == MLMC_BITS: ladder = kept fraction bits F_0..F_L, 0 <= F_0 < ... < F_L <= 24 (Sec. 3.1)
+ *   kind == MLMC_VBITS: the same ladder of fraction bits, with the entries divided by the largest entry of the row itself
+ *            as Sec. 3.1 writes it (MLMC_BITS divides by the power of two above it): digits m_j = min(floor(|g_j| /
+ *            max|g| * 2^F_L), 2^F_L - 1) - the cap is for the entries of the largest magnitude, whose quotient 1 has no
+ *            binary expansion below 1; C^F keeps the first F of them.  The row maximum is read exactly before the
+ *            extraction (two reads of the input); mlmc_plan_set_sampling does not apply.
  *   kind == MLMC_FBITS: ladder = kept mantissa digits F_0..F_L, 0 <= F_0 < ... < F_L <= 23 (App. B: the
  *            floating-point compressor C^F keeps sign, exponent and the first F mantissa digits of every entry;
  *            the paper's ladder is F = 0, 1, ..., 52 for fp64, here 0..23 for fp32 inputs)
@@ -115,7 +120,7 @@ mlmc_status mlmc_plan_set_staging(mlmc_plan_t *plan, int enable);
 int64_t mlmc_plan_chunk(const mlmc_plan_t *plan);
 /* Tiles per row of the offset table: ceil(d / MLMC_TILE). */
 int64_t mlmc_plan_num_tiles(const mlmc_plan_t *plan);
-/* Planes per row of the packed message: MLMC_BITS 1 + F_0 + max_l (F_l - F_{l-1}); MLMC_FBITS 9 + F_0 + max_l (F_l - F_{l-1});
+/* Planes per row of the packed message: MLMC_BITS and MLMC_VBITS 1 + F_0 + max_l (F_l - F_{l-1}); MLMC_FBITS 9 + F_0 + max_l (F_l - F_{l-1});
  * else 0. */
 int mlmc_plan_num_planes(const mlmc_plan_t *plan);
 
@@ -162,6 +167,10 @@ mlmc_status mlmc_compress_topk(const mlmc_plan_t *plan, const void *g, int64_t l
  *   level: dev [M] int32 (out);  scale_exp: dev [M] int32 (out), the exponent e.
  *   planes: dev [M][num_planes][ceil(d/64)] uint64 (out); word w bit b <-> element 64 w + b, pad bits 0;
  *           planes beyond 1 + F_0 + (F_l - F_{l-1}) of a row are left untouched.
+ *
+ * MLMC_VBITS plans: the same message with the digits of |g_j| / max|g| (see mlmc_plan); scale_exp[i] receives the bit
+ * pattern of the fp32 number max_j |g_ij| (the largest entry, "transmitted" with the message, Sec. 3.1) instead of an
+ * exponent.  Decoded value: sign_j * [ fp32(f0_j) * fp32(v 2^-F_0) + fp32(f_j) * fp32(v 2^-F_l / p_l) ], v that number.
  *
  * MLMC_FBITS plans (App. B, floating-point ladder): no scale; C^{F_0}(g) + (C^{F_l}(g) - C^{F_{l-1}}(g)) / p_l with
  * C^F = mantissa truncated to F digits.  Message per row: sign plane, 8 planes of the exponent field (LSB first),

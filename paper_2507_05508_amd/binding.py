@@ -19,7 +19,7 @@ MLMC_OK, MLMC_EINVAL, MLMC_ENOMEM, MLMC_EHIP, MLMC_ELIMIT = 0, 1, 2, 3, 4
 MLMC_STATIC_SCRATCH_BYTES = 1 << 20
 MLMC_DEV_CAPACITY, MLMC_DEV_NONFINITE, MLMC_DEV_INTERNAL, MLMC_DEV_REDONE = 1, 2, 4, 8
 MLMC_F32, MLMC_BF16 = 0, 1
-MLMC_TOPK, MLMC_BITS, MLMC_FBITS, MLMC_STOPK = 0, 1, 2, 3
+MLMC_TOPK, MLMC_BITS, MLMC_FBITS, MLMC_STOPK, MLMC_VBITS = 0, 1, 2, 3, 4
 MLMC_MAX_SLEVELS = 65536
 MLMC_TILE = 4096
 MLMC_MAX_LEVELS = 32

@@ -151,6 +151,7 @@ static void fill_bits_args(const mlmc_plan_t* pl, BitsArgs& b, const void* g, in
     for (int t = 0; t <= pl->L; ++t) b.F[t] = (int32_t)pl->ladder[t];
     for (int l = 0; l < pl->L; ++l) b.p_fixed[l] = pl->p[l];
     b.flt = pl->kind == MLMC_FBITS ? 1 : 0;
+    b.vmx = pl->kind == MLMC_VBITS ? 1 : 0;
     b.nplanes = pl->nplanes;
     b.nwords = (pl->d + 63) / 64;
     b.chunk = pl->chunk;
@@ -277,14 +278,14 @@ mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dty
     if (plan) *plan = nullptr;
     if (!plan || !ladder) return MLMC_EINVAL;
     if (kind == MLMC_STOPK) return plan_stopk(plan, M, d, in_dtype, L, ladder[0], p_fixed, workspace_bytes, sparse_capacity_worst);
-    if (kind != MLMC_TOPK && kind != MLMC_BITS && kind != MLMC_FBITS) return MLMC_EINVAL;
+    if (kind != MLMC_TOPK && kind != MLMC_BITS && kind != MLMC_FBITS && kind != MLMC_VBITS) return MLMC_EINVAL;
     if (in_dtype != MLMC_F32 && in_dtype != MLMC_BF16) return MLMC_EINVAL;
     if (M < 1 || M > MLMC_MAX_WORKERS || d < 1 || d >= ((int64_t)1 << 31) || L < 1 || L > MLMC_MAX_LEVELS) return MLMC_EINVAL;
     if (ladder[0] < 0) return MLMC_EINVAL;
     for (int t = 0; t < L; ++t)
         if (ladder[t] >= ladder[t + 1]) return MLMC_EINVAL;
     if (kind == MLMC_TOPK && ladder[L] > d) return MLMC_EINVAL;
-    if (kind == MLMC_BITS && ladder[L] > 24) return MLMC_EINVAL;
+    if ((kind == MLMC_BITS || kind == MLMC_VBITS) && ladder[L] > 24) return MLMC_EINVAL;
     if (kind == MLMC_FBITS && ladder[L] > 23) return MLMC_EINVAL;
     if (kind != MLMC_TOPK && !p_fixed) return MLMC_EINVAL;  // Lemma 3.4 probabilities are built for rank bands only
     if (p_fixed) {
@@ -354,6 +355,7 @@ mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dty
     pl->cchunks_per_row = (int)((d + pl->cchunk - 1) / pl->cchunk);
     // rows long enough that a second full read matters get their thresholds from a sampled histogram
     pl->sample_shift = d >= ((int64_t)1 << 23) ? 4 : d >= ((int64_t)1 << 21) ? 2 : 0;
+    if (kind == MLMC_VBITS) pl->sample_shift = 0;   // the largest entry itself is needed, not its binade
     pl->staging = 1;
 
     size_t off = 0;
@@ -417,7 +419,7 @@ mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dty
 void mlmc_plan_destroy(mlmc_plan_t* plan) { delete plan; }
 
 mlmc_status mlmc_plan_set_sampling(mlmc_plan_t* plan, int shift) {
-    if (!plan || shift < 0 || shift > 12) return MLMC_EINVAL;
+    if (!plan || shift < 0 || shift > 12 || plan->kind == MLMC_VBITS) return MLMC_EINVAL;
     plan->sample_shift = shift;
     return MLMC_OK;
 }
@@ -511,8 +513,8 @@ mlmc_status mlmc_compress_topk(const mlmc_plan_t* plan, const void* g, int64_t l
 mlmc_status mlmc_compress_bits(const mlmc_plan_t* plan, const void* g, int64_t ld, uint64_t seed, uint64_t step,
                                int32_t* level, int32_t* scale_exp, uint64_t* planes, int32_t* dev_status, void* ws,
                                void* hip_stream) {
-    if (!plan || (plan->kind != MLMC_BITS && plan->kind != MLMC_FBITS) || !g || !level || !planes || !dev_status || !ws) return MLMC_EINVAL;
-    if (plan->kind == MLMC_BITS && !scale_exp) return MLMC_EINVAL;
+    if (!plan || (plan->kind != MLMC_BITS && plan->kind != MLMC_FBITS && plan->kind != MLMC_VBITS) || !g || !level || !planes || !dev_status || !ws) return MLMC_EINVAL;
+    if (plan->kind != MLMC_FBITS && !scale_exp) return MLMC_EINVAL;
     if (ld < plan->d || (uintptr_t)ws % 256) return MLMC_EINVAL;
     hipStream_t st = (hipStream_t)hip_stream;
     BitsArgs b;
@@ -528,7 +530,7 @@ mlmc_status mlmc_compress_bits(const mlmc_plan_t* plan, const void* g, int64_t l
 mlmc_status mlmc_compress_bits_static(const mlmc_plan_t* plan, const void* g, int64_t ld, uint64_t seed, uint64_t step,
                                       int32_t* level, int32_t* scale_exp, uint64_t* planes, int32_t* dev_status,
                                       void* hip_stream) {
-    if (!plan || (plan->kind != MLMC_BITS && plan->kind != MLMC_FBITS)) return MLMC_EINVAL;
+    if (!plan || (plan->kind != MLMC_BITS && plan->kind != MLMC_FBITS && plan->kind != MLMC_VBITS)) return MLMC_EINVAL;
     if (plan->ws_bytes > (size_t)MLMC_STATIC_SCRATCH_BYTES) return MLMC_ELIMIT;   // before any HIP call
     void* ws = nullptr;
     const mlmc_status rc = static_scratch_of_current_device(&ws);
@@ -549,7 +551,7 @@ static mlmc_status aggregate_impl(const mlmc_plan_t* plan, const int32_t* level,
         return agg_sparse(plan, row_off, idx, val, capacity, tile_off, tws, alpha, out, eta, x, st);
     }
     if (!level || !planes || row_off || idx || val || tile_off) return MLMC_EINVAL;
-    if (plan->kind == MLMC_BITS && !scale_exp) return MLMC_EINVAL;
+    if (plan->kind != MLMC_FBITS && !scale_exp) return MLMC_EINVAL;
     BitsArgs b;
     fill_bits_args(plan, b, nullptr, plan->d, nullptr, nullptr);
     return agg_bits(plan, b, level, scale_exp, planes, alpha, out, eta, x, st);

@@ -46,17 +46,20 @@ __global__ __launch_bounds__(SMAX_THREADS) void k_bits_smax(BitsArgs a) {
     RowLoader<DT, VEC> ld(a.g, a.ld, a.d, row);
     const uint32_t lane = lane_id(), wave = (uint32_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     uint32_t maxkey = 0;
-    for (int64_t i = (int64_t)blockIdx.x * (SMAX_THREADS / 64) + wave; i < ns; i += (int64_t)gridDim.x * (SMAX_THREADS / 64)) {
+    // a wave's blocks, the loads of the next one in flight while the current one is reduced
+    const int64_t i0 = (int64_t)blockIdx.x * (SMAX_THREADS / 64) + wave, istride = (int64_t)gridDim.x * (SMAX_THREADS / 64);
+    auto fetch = [&](int64_t i, uint32_t (&b)[4][4]) {
         const int64_t blk = first + i * S;
         const int64_t base = blk * 1024 + lane * 4;
-        uint32_t b[4][4];
         if ((blk + 1) * 1024 <= a.d) {   // a whole block: four loads in flight
 #pragma unroll
-            for (int q = 0; q < 4; ++q) ld.load4_full(base + q * 256, b[q]);
+            for (int q = 0; q < 4; ++q) ld.load4_stream(base + q * 256, b[q]);
         } else {
 #pragma unroll
             for (int q = 0; q < 4; ++q) ld.load4(base + q * 256, b[q]);   // past the end: +0
         }
+    };
+    auto reduce = [&](const uint32_t (&b)[4][4]) {
 #pragma unroll
         for (int q = 0; q < 4; ++q)
 #pragma unroll
@@ -64,6 +67,16 @@ __global__ __launch_bounds__(SMAX_THREADS) void k_bits_smax(BitsArgs a) {
                 const uint32_t key = key_of_bits(b[q][c]);
                 maxkey = key > maxkey ? key : maxkey;
             }
+    };
+    uint32_t b0[4][4], b1[4][4];
+    int64_t i = i0;
+    if (i < ns) fetch(i, b0);
+    for (; i < ns; i += 2 * istride) {
+        const bool more1 = i + istride < ns, more2 = i + 2 * istride < ns;   // uniform
+        if (more1) fetch(i + istride, b1);
+        reduce(b0);
+        if (more2) fetch(i + 2 * istride, b0);
+        if (more1) reduce(b1);
     }
     maxkey = wave_max(maxkey);
     if (lane == 0 && maxkey) {
@@ -87,17 +100,24 @@ __device__ __forceinline__ void put_lane(uint32_t& dst, uint32_t sval, int lane)
 //
 // Digits (Sec. 3.1): |g| = sig * 2^(E' - 150), scale s = 2^(Emax - 126), so floor(|g| / s * 2^F) = sig >> (24 - F + Emax - E').
 // Bit b of (sig >> (24 - F_l + Emax - E')) for b < F_l - F_{l-1} is bit b of the level field.
-// MODE 0 / 1: fixed-point ladder without / with a base field (F_0 > 0); MODE 2: floating-point ladder (App. B).
+// MODE 0 / 1: fixed-point ladder without / with a base field (F_0 > 0); MODE 2: floating-point ladder (App. B);
+// MODE 3 / 4: fixed-point ladder of |g| / v, v the largest entry of the row (vd, as a double; vr = 1 / vd), without /
+// with a base field.  Its digits: m = min(floor(|g| 2^Q / v), 2^Q - 1), Q = F_L.  |g| 2^Q and v are exact doubles;
+// n = trunc(|g| 2^Q * vr) is off by at most one, and the remainder |g| 2^Q - n v, exact in one fused multiply-add
+// (n v has at most 48 bits), says which way.
 template <int DT, bool VEC, int NPC, int MODE>
 __device__ __forceinline__ void bits_extract_tiles(const BitsArgs& a, int row, int Emax, int level, int np, uint32_t& maxkey,
-                                                   uint32_t* slds) {
+                                                   uint32_t* slds, double vd = 0.0, double vr = 0.0) {
     const uint32_t lane = lane_id(), wave = (uint32_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     RowLoader<DT, false> ld(a.g, a.ld, a.d, row);
     RowLoader<DT, VEC> ld4(a.g, a.ld, a.d, row);
     const int64_t ntiles = (a.d + TILE - 1) / TILE;
     const int64_t nwhole = a.d / TILE;   // tiles with all 4096 elements
     const int F0 = a.F[0];
-    constexpr bool BASE = MODE == 1;
+    constexpr bool BASE = MODE == 1 || MODE == 4;
+    const int Q = a.F[a.L];
+    const uint32_t vcap = vd > 0.0 ? (Q >= 32 ? 0xFFFFFFFFu : (1u << Q) - 1u) : 0u;   // a zero row has only zero digits
+    const uint32_t vsl = (uint32_t)(Q - a.F[level]), vs0 = (uint32_t)(Q - F0);
     const uint32_t Cl = (uint32_t)(24 - a.F[level] + Emax), C0 = (uint32_t)(24 - F0 + Emax);
     const uint32_t mask0 = BASE ? (1u << F0) - 1u : 0u;
     const uint32_t fsl = (uint32_t)(23 - a.F[level]), fs0 = (uint32_t)(23 - F0);   // floating-point ladder: digit positions
@@ -119,6 +139,17 @@ __device__ __forceinline__ void bits_extract_tiles(const BitsArgs& a, int row, i
         const uint32_t hid = (key & 0x7FFFFFu) | 0x800000u;
         const uint32_t sig = key < hid ? key : hid;       // exponent field 0: no hidden bit
         const uint32_t Ec = E > 1u ? E : 1u;
+        if (MODE >= 3) {
+            const double xg = ldexp((double)sig, (int)Ec - 150 + Q);   // |g| 2^Q
+            uint32_t n = (uint32_t)__dmul_rn(xg, vr);
+            const double rem = __fma_rn(-(double)n, vd, xg);
+            n += rem >= vd ? 1u : 0u;
+            n -= rem < 0.0 ? 1u : 0u;
+            n = n < vcap ? n : vcap;
+            const uint32_t xv = n >> vsl;
+            if (!BASE) return xv;
+            return ((n >> vs0) & mask0) | (xv << F0);
+        }
         const uint32_t sl = Cl - Ec;                      // >= 32 (also "negative"): every digit is zero
         const uint32_t x = sig >> (sl < 31u ? sl : 31u);
         if (!BASE) return x;
@@ -243,8 +274,10 @@ __device__ __forceinline__ void bits_extract_tiles(const BitsArgs& a, int row, i
 // the sampled one are extracted again with the true one; every other row is already final and is skipped.
 // NPCMAX: bound on the planes of any row of the plan (the kernel holds only the variants it can need, so that a
 // plan with few planes is not charged the registers of the widest one).  FLT: floating-point ladder (no scale).
-template <int DT, bool VEC, bool REDO, int NPCMAX, bool FLT>
+// KIND 2: fixed-point ladder of |g| / v: the row maximum was read exactly beforehand (sample of every block).
+template <int DT, bool VEC, bool REDO, int NPCMAX, int KIND>
 __global__ __launch_bounds__(256) void k_bits_extract(BitsArgs a) {
+    constexpr bool FLT = KIND == 1;
     __shared__ __align__(16) uint32_t s_tr[4][1024];   // per wave: four loads of 256 elements on their way from "four per lane" to "one per lane"
     uint32_t* slds = s_tr[threadIdx.x >> 6];
     const int row = blockIdx.y;
@@ -259,9 +292,22 @@ __global__ __launch_bounds__(256) void k_bits_extract(BitsArgs a) {
     const int level = a.rinfo[row].level;
     const int F0 = a.F[0];
     const int np = (FLT ? 9 : 1) + F0 + (a.F[level] - a.F[level - 1]);   // planes written for this row
-    if (!FLT && blockIdx.x == 0 && threadIdx.x == 0) a.scale_exp[row] = Emax - 126;
+    if (KIND == 0 && blockIdx.x == 0 && threadIdx.x == 0) a.scale_exp[row] = Emax - 126;
     uint32_t maxkey = 0;
-    if constexpr (FLT) {
+    if constexpr (KIND == 2) {
+        const uint32_t vkey = ra->smpmax_key;   // the largest |g| of the row
+        if (blockIdx.x == 0 && threadIdx.x == 0) a.scale_exp[row] = (int32_t)vkey;
+        const uint32_t vE = vkey >> 23;
+        const double vd = ldexp((double)(vE ? (vkey & 0x7FFFFFu) | 0x800000u : vkey), (int)(vE ? vE : 1u) - 150);
+        const double vr = vd > 0.0 ? __ddiv_rn(1.0, vd) : 0.0;
+        if (F0 == 0) {
+            if (np <= 9) bits_extract_tiles<DT, VEC, 9, 3>(a, row, Emax, level, np, maxkey, slds, vd, vr);
+            else if constexpr (NPCMAX > 9) bits_extract_tiles<DT, VEC, MAX_PLANES, 3>(a, row, Emax, level, np, maxkey, slds, vd, vr);
+        } else {
+            if (np <= 9) bits_extract_tiles<DT, VEC, 9, 4>(a, row, Emax, level, np, maxkey, slds, vd, vr);
+            else if constexpr (NPCMAX > 9) bits_extract_tiles<DT, VEC, MAX_PLANES, 4>(a, row, Emax, level, np, maxkey, slds, vd, vr);
+        }
+    } else if constexpr (FLT) {
         if (np <= 11) bits_extract_tiles<DT, VEC, 11, 2>(a, row, Emax, level, np, maxkey, slds);
         else if constexpr (NPCMAX > 11) {
             if (np <= 17) bits_extract_tiles<DT, VEC, 17, 2>(a, row, Emax, level, np, maxkey, slds);
@@ -340,6 +386,11 @@ __global__ __launch_bounds__(256) void k_agg_bits(AggBitsArgs a, const uint64_t*
         if (b.flt) {   // the level's weight fp32(1 / p_l)
             s_c0[r] = 0.0f;
             s_cl[r] = pl == 0.0 ? 0.0f : (float)__ddiv_rn(1.0, pl);
+        } else if (b.vmx) {   // the scale field carries the largest entry v: c_0 = fp32(v 2^-F_0), c_l = fp32(v 2^-F_l / p_l)
+            const uint32_t vkey = (uint32_t)a.scale_exp[r] & 0x7FFFFFFFu, vE = vkey >> 23;
+            const double vd = ldexp((double)(vE ? (vkey & 0x7FFFFFu) | 0x800000u : vkey), (int)(vE ? vE : 1u) - 150);
+            s_c0[r] = (float)ldexp(vd, -F0);
+            s_cl[r] = pl == 0.0 ? 0.0f : (float)__ddiv_rn(ldexp(vd, -b.F[lev]), pl);
         } else {
             int e = a.scale_exp[r];
             s_c0[r] = (float)ldexp(1.0, e - F0);
@@ -614,32 +665,32 @@ mlmc_status bits_compress(const mlmc_plan_t* pl, const BitsArgs& a, bool vec, hi
     if (gx > cap) gx = cap;
     if (gx < 1) gx = 1;
     dim3 egrid(gx, pl->M);
-#define MLMC_EXTRACT_V(ID, DT, VEC, REDO, FLT, SMALL, BIG)                                                              \
+#define MLMC_EXTRACT_V(ID, DT, VEC, REDO, KIND, SMALL, BIG)                                                              \
     do {                                                                                                                \
-        if (small) MLMC_LAUNCH(ID, st, k_bits_extract<DT, VEC, REDO, SMALL, FLT><<<egrid, 256, 0, st>>>(a));             \
-        else MLMC_LAUNCH(ID, st, k_bits_extract<DT, VEC, REDO, BIG, FLT><<<egrid, 256, 0, st>>>(a));                     \
+        if (small) MLMC_LAUNCH(ID, st, k_bits_extract<DT, VEC, REDO, SMALL, KIND><<<egrid, 256, 0, st>>>(a));            \
+        else MLMC_LAUNCH(ID, st, k_bits_extract<DT, VEC, REDO, BIG, KIND><<<egrid, 256, 0, st>>>(a));                    \
     } while (0)
-#define MLMC_EXTRACT(ID, REDO, FLT, SMALL, BIG)                                                                         \
+#define MLMC_EXTRACT(ID, REDO, KIND, SMALL, BIG)                                                                         \
     do {                                                                                                                \
         if (pl->dtype == MLMC_F32) {                                                                                    \
-            if (vec) MLMC_EXTRACT_V(ID, MLMC_F32, true, REDO, FLT, SMALL, BIG);                                         \
-            else MLMC_EXTRACT_V(ID, MLMC_F32, false, REDO, FLT, SMALL, BIG);                                            \
+            if (vec) MLMC_EXTRACT_V(ID, MLMC_F32, true, REDO, KIND, SMALL, BIG);                                         \
+            else MLMC_EXTRACT_V(ID, MLMC_F32, false, REDO, KIND, SMALL, BIG);                                            \
         } else {                                                                                                        \
-            if (vec) MLMC_EXTRACT_V(ID, MLMC_BF16, true, REDO, FLT, SMALL, BIG);                                        \
-            else MLMC_EXTRACT_V(ID, MLMC_BF16, false, REDO, FLT, SMALL, BIG);                                           \
+            if (vec) MLMC_EXTRACT_V(ID, MLMC_BF16, true, REDO, KIND, SMALL, BIG);                                        \
+            else MLMC_EXTRACT_V(ID, MLMC_BF16, false, REDO, KIND, SMALL, BIG);                                           \
         }                                                                                                               \
     } while (0)
     if (a.flt) {
         // floating-point ladder (App. B): no scale, so nothing to find before the one read
         const bool small = pl->nplanes <= 11;
-        MLMC_EXTRACT(K_BITS_EXTRACT, false, true, 11, MAX_FPLANES);
+        MLMC_EXTRACT(K_BITS_EXTRACT, false, 1, 11, MAX_FPLANES);
         return MLMC_OK;
     }
     // sampled (or, for short rows, exact) row maxima
     const int64_t nblk = (pl->d + 1023) / 1024;
     const int64_t ns = (nblk >> a.sample_shift) > 0 ? (nblk >> a.sample_shift) : 1;
-    int64_t sw = (ns + 7) / 8;   // a block per wave
-    const int64_t scap = 4096 / pl->M > 0 ? 4096 / pl->M : 1;
+    int64_t sw = (ns + 7) / 8;   // a block per wave, up to four workgroups of eight waves on every CU
+    const int64_t scap = 1024 / pl->M > 0 ? 1024 / pl->M : 1;
     if (sw > scap) sw = scap;
     if (sw < 1) sw = 1;
     const dim3 sgrid((unsigned)sw, pl->M);
@@ -651,8 +702,12 @@ mlmc_status bits_compress(const mlmc_plan_t* pl, const BitsArgs& a, bool vec, hi
         else MLMC_LAUNCH(K_BITS_MAX, st, k_bits_smax<MLMC_BF16, false><<<sgrid, SMAX_THREADS, 0, st>>>(a));
     }
     const bool small = pl->nplanes <= 9;
-    MLMC_EXTRACT(K_BITS_EXTRACT, false, false, 9, MAX_PLANES);
-    if (a.sample_shift > 0) MLMC_EXTRACT(K_BITS_REDO, true, false, 9, MAX_PLANES);   // rows whose sampled maximum fell short (returns at once for the others)
+    if (a.vmx) {   // the maxima above are exact (every block was read): one extraction
+        MLMC_EXTRACT(K_BITS_EXTRACT, false, 2, 9, MAX_PLANES);
+        return MLMC_OK;
+    }
+    MLMC_EXTRACT(K_BITS_EXTRACT, false, 0, 9, MAX_PLANES);
+    if (a.sample_shift > 0) MLMC_EXTRACT(K_BITS_REDO, true, 0, 9, MAX_PLANES);   // rows whose sampled maximum fell short (returns at once for the others)
 #undef MLMC_EXTRACT_V
 #undef MLMC_EXTRACT
     return MLMC_OK;

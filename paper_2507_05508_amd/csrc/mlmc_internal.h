@@ -152,6 +152,8 @@ struct BitsArgs {
     int32_t F[TMAX];
     double p_fixed[LMAX];
     int32_t flt;             // 1: floating-point ladder (App. B): F are mantissa digits, no scale
+    int32_t vmx;             // 1: fixed-point ladder of |g| / max|g| (the scale field carries the bits of max|g|)
+    int32_t pad_;
     int32_t nplanes;         // planes per row in the message buffer
     int64_t nwords;          // ceil(d / 64)
     int32_t chunk;

@@ -135,6 +135,29 @@ def test_bits_full_size():
         assert np.array_equal(out.cpu().numpy().view(np.uint32), ref.view(np.uint32))
 
 
+def test_vbits_full_size():
+    w = W.WORKLOADS["resnet18_vbits"]
+    G = W.generate(w)
+    g = _upload(G)
+    p = O.geometric_p(w.L)
+    plan = P.Plan(P.MLMC_VBITS, w.M, w.d, P.MLMC_F32, w.ladder, p)
+    for step in (0, 1):
+        print(f"largest-entry fixed point full size step {step}", flush=True)
+        msg = P.mlmc_compress_bits(plan, g, seed=w.seed, step=step)
+        out = P.mlmc_aggregate(plan, msg, 1.0 / w.M)
+        torch.cuda.synchronize()
+        assert plan.status() == 0
+        want = O.compress_vbits(G, w.ladder, p, w.seed, step)
+        planes = msg.planes.cpu().numpy().view(np.uint64)
+        vbits = msg.scale_exp.cpu().numpy().view(np.uint32)
+        for i in range(w.M):
+            assert int(msg.level[i]) == want[i]["level"] and vbits[i] == np.float32(want[i]["vmax"]).view(np.uint32)
+            n = want[i]["planes"].shape[0]
+            assert np.array_equal(planes[i, :n], want[i]["planes"])
+        ref = O.aggregate_vbits(want, w.ladder, w.d, 1.0 / w.M)
+        assert np.array_equal(out.cpu().numpy().view(np.uint32), ref.view(np.uint32))
+
+
 def test_fbits_full_size():
     w = W.WORKLOADS["resnet18_fbits"]
     G = W.generate(w)

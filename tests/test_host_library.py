@@ -48,6 +48,8 @@ def test_plan_validation():
         dict(kind=P.MLMC_TOPK, M=1, d=100, ladder=list(range(40)), p=None),   # L > MLMC_MAX_LEVELS
         dict(kind=P.MLMC_BITS, M=1, d=10, ladder=[0, 8, 25], p=[0.5, 0.5]),   # more than 24 bits
         dict(kind=P.MLMC_BITS, M=1, d=10, ladder=[0, 8, 16], p=None),         # adaptive bits not defined
+        dict(kind=P.MLMC_VBITS, M=1, d=10, ladder=[0, 8, 25], p=[0.5, 0.5]),  # more than 24 bits
+        dict(kind=P.MLMC_VBITS, M=1, d=10, ladder=[0, 8, 16], p=None),        # adaptive not defined
         dict(kind=P.MLMC_FBITS, M=1, d=10, ladder=[0, 8, 24], p=[0.5, 0.5]),  # more than 23 mantissa digits
         dict(kind=P.MLMC_FBITS, M=1, d=10, ladder=[0, 8, 16], p=None),        # adaptive not defined
         dict(kind=7, M=1, d=10, ladder=[0, 10], p=[1.0]),
@@ -59,5 +61,9 @@ def test_plan_validation():
     assert bits.num_planes == 9 and bits.sparse_capacity_worst == 0
     bits2 = P.Plan(P.MLMC_BITS, 8, 1000, P.MLMC_F32, [2, 3, 8, 12], P.mlmc_geometric_p(3), allocate=False)
     assert bits2.num_planes == 1 + 2 + 5
+    vb = P.Plan(P.MLMC_VBITS, 8, 1000, P.MLMC_F32, [2, 3, 8, 12], P.mlmc_geometric_p(3), allocate=False)
+    assert vb.num_planes == 1 + 2 + 5 and vb.sparse_capacity_worst == 0
+    with pytest.raises(P.MlmcError):
+        vb.set_sampling(2)   # the largest entry is read exactly
     fb = P.Plan(P.MLMC_FBITS, 8, 1000, P.MLMC_F32, list(range(24)), P.mlmc_geometric_p(23), allocate=False)
     assert fb.num_planes == 10 and fb.sparse_capacity_worst == 0   # sign + 8 exponent bits + one mantissa digit (App. B)
