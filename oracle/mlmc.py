@@ -19,6 +19,8 @@ What is computed, with the passages it follows:
   to magnitude < 1, written as sign + binary fraction, and C^F keeps the F most significant fraction bits.
 * The same ladder with the entries divided by the largest entry itself, as Sec. 3.1 writes it (`vmax_digits` and the
   `*_vbits*` functions): the digits of |g_j| / max|g|, capped at 2^Q - 1 for the entries of the largest magnitude.
+* Round-to-Nearest ladder (Sec. 3.3, App. G.2; the `rtn_*` functions): codes by exact rounding of v (2^b - 1) / (2c),
+  residual norms of Lemma 3.4 from exact integer sums, the message as the planes of the codes involved.
 * Server aggregate (Alg. 2 / Alg. 3 "Server aggregates"): out = alpha * sum_i g~_i, alpha = 1/M for the mean.
 
 Readings where the paper is silent (each is also what the HIP library documents):
@@ -488,6 +490,151 @@ def message_bits_floating_point(F: Sequence[int], level: int, d: int, exponent_b
     paper's 13 d + log2(52), rounded up."""
     L = len(F) - 1
     return d * (1 + exponent_bits + F[0] + F[level] - F[level - 1]) + _ceil_log2(L)
+
+
+# ----------------------------------------------------------------------------------------------
+# Round-to-Nearest MLMC (Sec. 3.3 "RTN", App. G.2): C^l(v) = delta^l clip(round(v / delta^l), -c, c), delta^l = 2c / (2^l - 1)
+# ----------------------------------------------------------------------------------------------
+# Readings (the paper gives the formula only): the clipping value c is the largest magnitude of the vector and is sent
+# with the message; "round" is round-half-to-even of the exact quotient (what torch.round and numpy.rint do); the clip
+# acts on the rounded integer and keeps it in the range of a symmetric l-bit code, |n| <= 2^(l-1) - 1 (so 2^l - 1
+# values, the count delta^l is built from); level 0 of a ladder that starts at 0 bits is the zero vector.  The ladder
+# holds bit widths b_0 < b_1 < ... < b_L <= 16; the top level is not the identity, the estimate is unbiased for
+# C^{b_L}(v), as for the fixed-point ladder.
+def rtn_codes(g32: np.ndarray, c: np.float32, b: int) -> np.ndarray:
+    """n_j = clamp(rne(v_j (2^b - 1) / (2c)), -(2^(b-1) - 1), 2^(b-1) - 1) as int64; b = 0 or c = 0 gives zeros.
+    The quotient is rounded from its fp64 value and then corrected with the exact remainder |v| D - n 2c (both
+    products have at most 41 significant bits and the remainder is exact in fp64), so the result is the rounding of
+    the exact real quotient, ties to even."""
+    if b == 0 or float(c) == 0.0:
+        return np.zeros(g32.shape, dtype=np.int64)
+    D = float((1 << b) - 1)
+    a = np.abs(g32.astype(np.float64))
+    num = a * D
+    den = 2.0 * float(c)
+    n = np.rint(num / den)
+    rem = num - n * den                       # exact
+    n = n + (rem > float(c)) - (rem < -float(c))
+    tie = np.abs(rem) == float(c)             # exactly between two integers: the even one
+    odd = np.fmod(n, 2.0) != 0.0
+    n = np.where(tie & odd, n + np.sign(rem), n)
+    n = np.minimum(n, float((1 << (b - 1)) - 1))
+    return np.where(np.signbit(g32), -n, n).astype(np.int64)
+
+
+def rtn_dense(row: np.ndarray, b: int) -> np.ndarray:
+    """C^b(v) as float64 values: n_j * 2c / (2^b - 1)."""
+    g = as_f32(row)
+    c = np.float32(np.abs(g).max()) if g.size else np.float32(0.0)
+    if b == 0 or c == 0:
+        return np.zeros(g.shape)
+    return rtn_codes(g, c, b).astype(np.float64) * (2.0 * float(c) / float((1 << b) - 1))
+
+
+def rtn_residual_ints(g32: np.ndarray, c: np.float32, b_prev: int, b_cur: int) -> np.ndarray:
+    """C^{b_cur} - C^{b_prev} = (2c / (D D')) k with the integers k_j = n_cur D' - n_prev D, D = 2^b_cur - 1,
+    D' = 2^b_prev - 1 (D' = 1 and n_prev = 0 when b_prev = 0)."""
+    D = (1 << b_cur) - 1
+    Dp = (1 << b_prev) - 1 if b_prev > 0 else 1
+    n_prev = rtn_codes(g32, c, b_prev) if b_prev > 0 else 0
+    return rtn_codes(g32, c, b_cur) * Dp - n_prev * D
+
+
+def rtn_level_norms_row(row: np.ndarray, B: Sequence[int]) -> List[float]:
+    """Delta_l = ||C^{b_l}(v) - C^{b_{l-1}}(v)||_2 (Lemma 3.4), l = 1..L: (2c / (D D')) sqrt(sum_j k_j^2) with the
+    integer sum exact, converted to fp64 once (round to nearest even), then one sqrt, one divide and one multiply."""
+    g = as_f32(row)
+    c = np.float32(np.abs(g).max()) if g.size else np.float32(0.0)
+    out = []
+    for l in range(1, len(B)):
+        k = rtn_residual_ints(g, c, B[l - 1], B[l])
+        kk = k.astype(np.int64)
+        assert kk.size * int(np.abs(kk).max(initial=0)) ** 2 < 2 ** 63     # the int64 dot product below is exact
+        S = int(np.dot(kk, kk))
+        D = (1 << B[l]) - 1
+        Dp = (1 << B[l - 1]) - 1 if B[l - 1] > 0 else 1
+        out.append((2.0 * float(c) / float(D * Dp)) * math.sqrt(float(S)))
+    return out
+
+
+def _rtn_code_planes(n: np.ndarray, b: int) -> List[np.ndarray]:
+    """The b planes of a code in two's complement truncated to b bits, least significant first."""
+    u = n.astype(np.int64) & np.int64((1 << b) - 1)
+    return [pack_plane(((u >> np.int64(q)) & np.int64(1)).astype(bool)) for q in range(b)]
+
+
+def compress_rtn_row(row: np.ndarray, B: Sequence[int], p: Optional[Sequence[float]], seed: int, step: int, worker: int,
+                     force_level: Optional[int] = None):
+    """One worker's RTN MLMC message (Alg. 3 when p is None: probabilities from this row's residual norms): level,
+    c, the coefficient fp32((2c / (D D')) / p_l) the server multiplies the residual integers with, and the planes of
+    the codes n_{b_0} (if b_0 > 0), n_{b_{l-1}} (if l > 1) and n_{b_l}, in that order."""
+    g = as_f32(row)
+    L = len(B) - 1
+    assert 0 <= B[0] and all(B[i] < B[i + 1] for i in range(L)) and B[L] <= 16
+    c = np.float32(np.abs(g).max()) if g.size else np.float32(0.0)
+    norms = rtn_level_norms_row(g, B)
+    probs = adaptive_p(norms) if p is None else list(p)
+    level = draw_level(probs, seed, step, worker) if force_level is None else int(force_level)
+    p_l = float(probs[level - 1])
+    planes = []
+    if B[0] > 0:
+        planes += _rtn_code_planes(rtn_codes(g, c, B[0]), B[0])
+    if level > 1:
+        planes += _rtn_code_planes(rtn_codes(g, c, B[level - 1]), B[level - 1])
+    planes += _rtn_code_planes(rtn_codes(g, c, B[level]), B[level])
+    D = (1 << B[level]) - 1
+    Dp = (1 << B[level - 1]) - 1 if B[level - 1] > 0 else 1
+    coef = np.float32((2.0 * float(c) / float(D * Dp)) / p_l) if p_l != 0.0 else np.float32(0.0)
+    return dict(level=level, c=c, coef=coef, planes=np.stack(planes), p_level=p_l, norms=norms)
+
+
+def _rtn_unpack_code(planes: np.ndarray, first: int, b: int, d: int) -> np.ndarray:
+    u = np.zeros(d, dtype=np.int64)
+    for q in range(b):
+        u |= unpack_plane(planes[first + q], d).astype(np.int64) << np.int64(q)
+    return np.where(u >= (1 << (b - 1)), u - (1 << b), u) if b > 0 else u
+
+
+def decode_rtn_row(msg, B: Sequence[int], d: int) -> np.ndarray:
+    """g~_j = fp32(n_{b_0}) * fp32(2c / D_0) + fp32(k_j) * coef with k_j = n_cur D' - n_prev D rebuilt from the codes;
+    products and the sum are single fp32 operations (the first term only when b_0 > 0)."""
+    level, planes = msg["level"], msg["planes"]
+    at = 0
+    n0 = None
+    if B[0] > 0:
+        n0 = _rtn_unpack_code(planes, 0, B[0], d)
+        at = B[0]
+    if level > 1:
+        n_prev = _rtn_unpack_code(planes, at, B[level - 1], d)
+        at += B[level - 1]
+    else:
+        n_prev = n0 if n0 is not None else np.zeros(d, dtype=np.int64)
+    n_cur = _rtn_unpack_code(planes, at, B[level], d)
+    D = (1 << B[level]) - 1
+    Dp = (1 << B[level - 1]) - 1 if B[level - 1] > 0 else 1
+    k = n_cur * Dp - n_prev * D
+    val = k.astype(np.float32) * np.float32(msg["coef"])
+    if n0 is not None:
+        c0 = np.float32(2.0 * float(msg["c"]) / float((1 << B[0]) - 1))
+        val = n0.astype(np.float32) * c0 + val
+    return val.astype(np.float32)
+
+
+def compress_rtn(G: np.ndarray, B, p, seed: int, step: int):
+    return [compress_rtn_row(G[i], B, p, seed, step, i) for i in range(G.shape[0])]
+
+
+def aggregate_rtn(msgs, B, d: int, alpha: float) -> np.ndarray:
+    acc = np.zeros(d, dtype=np.float32)
+    for msg in msgs:
+        acc = acc + decode_rtn_row(msg, B, d)
+    return (np.float32(alpha) * acc).astype(np.float32)
+
+
+def message_bits_rtn(B: Sequence[int], level: int, d: int) -> int:
+    """Bits of an RTN MLMC message: per entry the codes sent, plus c, the coefficient (32 bits each) and the level."""
+    per = B[0] + (B[level - 1] if level > 1 else 0) + B[level]
+    return d * per + 64 + _ceil_log2(len(B) - 1)
 
 
 # ----------------------------------------------------------------------------------------------

@@ -499,6 +499,131 @@ def test_vbits_telescoping_expectation_layout_and_aggregate():
             assert out[j] == np.float32(np.float32(alpha) * acc), (F, j)
 
 
+# ----------------------------------------------------------------------------- Round-to-Nearest ladder (Sec. 3.3, App. G.2)
+def _exact_rtn_code(x: float, c: float, b: int) -> int:
+    """clamp(rne(x (2^b - 1) / (2c))) in exact rationals, ties to even, |n| <= 2^(b-1) - 1."""
+    if b == 0 or c == 0:
+        return 0
+    t = Fraction(abs(float(x))) * ((1 << b) - 1) / (2 * Fraction(float(c)))
+    f = t.numerator // t.denominator
+    r = t - f
+    n = f + 1 if r > Fraction(1, 2) else f if r < Fraction(1, 2) else (f if f % 2 == 0 else f + 1)
+    n = min(n, (1 << (b - 1)) - 1)
+    return -n if np.signbit(np.float32(x)) else n
+
+
+def _rtn_rows():
+    rng = np.random.default_rng(5)
+    rows = [(rng.standard_normal(400) * 0.3).astype(np.float32)]
+    r = (rng.standard_normal(300) * 10.0 ** rng.uniform(-8, 2, size=300)).astype(np.float32)
+    r[7] = -np.abs(r).max()
+    rows.append(r)
+    # quotients exactly between two integers: c = 3.5 and b = 3 give v (2^b - 1) / (2c) = v
+    rows.append(np.array([3.5, 0.5, -0.5, 1.5, -1.5, 2.5, -2.5, -3.5, 0.0, -0.0, 0.49999997, 0.50000006, 2.4999998], dtype=np.float32))
+    rows.append(np.array([1e-40, -3e-41, 2e-45, 0.0], dtype=np.float32))
+    return rows
+
+
+def test_rtn_codes_round_the_exact_quotient_to_nearest_even():
+    """C^l(v) = delta^l clip(round(v / delta^l)), delta^l = 2c / (2^l - 1) (Sec. 3.3): codes against exact rationals
+    (ties included), the distortion bound delta^l / 2, zero rows."""
+    for g in _rtn_rows():
+        c = np.float32(np.abs(g).max())
+        for b in (1, 2, 3, 4, 8, 11, 16):
+            n = O.rtn_codes(g, c, b)
+            assert [int(x) for x in n] == [_exact_rtn_code(x, c, b) for x in g], b
+            dense = O.rtn_dense(g, b)
+            delta = 2 * Fraction(float(c)) / ((1 << b) - 1)
+            for j in range(g.size):
+                assert Fraction(float(dense[j])) == 0 or abs(Fraction(float(dense[j])) / delta - int(n[j])) < Fraction(1, 10 ** 9)
+                assert abs(int(n[j]) * delta - Fraction(float(g[j]))) <= delta / 2
+    tie = _rtn_rows()[2]
+    assert O.rtn_codes(tie, np.float32(3.5), 3).tolist() == [3, 0, 0, 2, -2, 2, -2, -3, 0, 0, 0, 1, 2]
+    assert not O.rtn_codes(np.zeros(9, dtype=np.float32), np.float32(0), 8).any()
+    assert not O.rtn_codes(tie, np.float32(3.5), 0).any()
+
+
+def test_rtn_norms_telescoping_and_second_moment():
+    """Lemma 3.4 for a ladder without rank or bit structure: Delta_l against the plain difference of the two dense
+    compressions and against an integer sum in Python ints; sum_l p_l g~(l) = C^{b_L}(v) (Lemma 3.2); with
+    p_l = Delta_l / sum Delta the second moment of the residual term is (sum Delta)^2."""
+    for B in ([0, 2, 4, 8, 16], [2, 3, 5, 9]):
+        for g in _rtn_rows()[:2]:
+            d = g.size
+            c = np.float32(np.abs(g).max())
+            norms = O.rtn_level_norms_row(g, B)
+            L = len(B) - 1
+            for l in range(1, L + 1):
+                diff = O.rtn_dense(g, B[l]) - O.rtn_dense(g, B[l - 1])
+                assert math.isclose(norms[l - 1], math.sqrt(math.fsum(diff * diff)), rel_tol=1e-12)
+                k = [_exact_rtn_code(x, c, B[l]) * (((1 << B[l - 1]) - 1) if B[l - 1] else 1) -
+                     _exact_rtn_code(x, c, B[l - 1]) * ((1 << B[l]) - 1) for x in g]
+                assert [int(x) for x in O.rtn_residual_ints(g, c, B[l - 1], B[l])] == k
+                DD = ((1 << B[l]) - 1) * (((1 << B[l - 1]) - 1) if B[l - 1] else 1)
+                assert norms[l - 1] == (2.0 * float(c) / float(DD)) * math.sqrt(float(sum(x * x for x in k)))
+            p = O.adaptive_p(norms)
+            exp = np.zeros(d)
+            second = 0.0
+            base = O.rtn_dense(g, B[0])
+            for l in range(1, L + 1):
+                msg = O.compress_rtn_row(g, B, None, 0, 0, 0, force_level=l)
+                assert msg["planes"].shape[0] == B[0] + (B[l - 1] if l > 1 else 0) + B[l] and msg["p_level"] == p[l - 1]
+                dec = O.decode_rtn_row(msg, B, d).astype(np.float64)
+                exp += p[l - 1] * dec
+                second += p[l - 1] * float(np.sum((dec - base) ** 2))
+            assert np.allclose(exp, O.rtn_dense(g, B[L]), rtol=3e-6, atol=float(c) * 1e-9)
+            assert math.isclose(second, sum(norms) ** 2, rel_tol=1e-5)
+
+
+def test_rtn_planes_bit_by_bit_aggregate_and_message_bits():
+    """The wire layout from exact-rational codes (two's complement, least significant plane first; base code,
+    previous level's code, drawn level's code), the server's sum coordinate by coordinate with scalar fp32
+    operations in worker order, and the message size."""
+    w = W.scaled(W.WORKLOADS["resnet18_bits"], d=64 * 2 + 9, M=4)
+    G = W.generate(w)
+    G[1] *= np.float32(3.0e5)
+    G[3, ::2] *= np.float32(-1.0)
+    d, M = w.d, w.M
+    for B, alpha in (([0, 2, 4, 8, 16], 1.0 / 3.0), ([2, 3, 5, 9], 0.37)):
+        L = len(B) - 1
+        seed, step = 3, 1
+        msgs = O.compress_rtn(G, B, None, seed, step)
+        levels = [m["level"] for m in msgs]
+        for i, m in enumerate(msgs):
+            p = O.adaptive_p(O.rtn_level_norms_row(G[i], B))
+            assert m["level"] == O.draw_level(p, seed, step, i) and m["p_level"] == p[m["level"] - 1]
+        assert len(set(levels)) > 1 or L == 1
+        for l in range(1, L + 1):
+            g = G[0]
+            c = float(np.abs(g).max())
+            msg = O.compress_rtn_row(g, B, None, 0, 0, 0, force_level=l)
+            fields = ([B[0]] if B[0] else []) + ([B[l - 1]] if l > 1 else []) + [B[l]]
+            for j in (0, 1, 63, 64, 65, d - 1, int(np.argmax(np.abs(g)))):
+                plane = 0
+                for b in fields:
+                    u = _exact_rtn_code(g[j], c, b) & ((1 << b) - 1)
+                    for q in range(b):
+                        assert (int(msg["planes"][plane][j // 64]) >> (j % 64)) & 1 == (u >> q) & 1, (B, l, j, b, q)
+                        plane += 1
+            assert not (msg["planes"][:, -1] >> np.uint64(d % 64)).any()
+            assert O.message_bits_rtn(B, l, d) == d * sum(fields) + 64 + (L - 1).bit_length()
+        out = O.aggregate_rtn(msgs, B, d, alpha)
+        for j in range(d):
+            acc = np.float32(0.0)
+            for i in range(M):
+                l = levels[i]
+                c = float(np.abs(G[i]).max())
+                D = (1 << B[l]) - 1
+                Dp = ((1 << B[l - 1]) - 1) if B[l - 1] else 1
+                k = _exact_rtn_code(G[i, j], c, B[l]) * Dp - _exact_rtn_code(G[i, j], c, B[l - 1]) * D
+                val = np.float32(np.float32(k) * np.float32((2.0 * c / float(D * Dp)) / msgs[i]["p_level"]))
+                if B[0]:
+                    c0 = np.float32(2.0 * c / float((1 << B[0]) - 1))
+                    val = np.float32(np.float32(np.float32(_exact_rtn_code(G[i, j], c, B[0])) * c0) + val)
+                acc = np.float32(acc + val)
+            assert out[j] == np.float32(np.float32(alpha) * acc), (B, j)
+
+
 # ----------------------------------------------------------------------------- floating-point bit-wise ladder (App. B)
 def _fp_rows():
     rng = np.random.default_rng(31)
