@@ -32,7 +32,7 @@ def algorithmic_bytes(w, kernel, nnz_total, planes_bytes):
     """Bytes the method itself has to move in one launch of `kernel` ('Kernels')."""
     s_in = 2 if w.dtype == "bf16" else 4
     in_bytes = w.M * w.d * s_in
-    if kernel in ("k_main", "k_bits_max", "k_bits_smax"):
+    if kernel in ("k_main", "k_bits_max", "k_bits_smax", "k_rtn_norms"):
         return in_bytes                                   # one read of every input element
     if kernel == "k_rs_scatter":
         return 16 * w.M * w.d                             # a sort pass: every {key, index} pair read and written
@@ -95,6 +95,8 @@ def _oracle_row(w, row_data, i):
         return O.compress_fbits_row(row_data, w.ladder, p, w.seed, 0, i)
     if w.kind == "vbits":
         return O.compress_vbits_row(row_data, w.ladder, p, w.seed, 0, i)
+    if w.kind == "rtn":
+        return O.compress_rtn_row(row_data, w.ladder, p, w.seed, 0, i)
     return O.compress_bits_row(row_data, w.ladder, p, w.seed, 0, i)
 
 
@@ -106,6 +108,8 @@ def _oracle_aggregate(w, msgs):
         return O.aggregate_fbits(msgs, w.ladder, w.d, 1.0 / w.M)
     if w.kind == "vbits":
         return O.aggregate_vbits(msgs, w.ladder, w.d, 1.0 / w.M)
+    if w.kind == "rtn":
+        return O.aggregate_rtn(msgs, w.ladder, w.d, 1.0 / w.M)
     return O.aggregate_bits(msgs, w.ladder, w.d, 1.0 / w.M)
 
 
@@ -234,8 +238,8 @@ def main():
         if args.no_staging:
             plan.set_staging(False)
     else:
-        kind = {"bits": P.MLMC_BITS, "fbits": P.MLMC_FBITS, "vbits": P.MLMC_VBITS}[w.kind]
-        plan = P.Plan(kind, w.M, w.d, P.MLMC_F32, w.ladder, P.mlmc_geometric_p(w.L))
+        kind = {"bits": P.MLMC_BITS, "fbits": P.MLMC_FBITS, "vbits": P.MLMC_VBITS, "rtn": P.MLMC_RTN}[w.kind]
+        plan = P.Plan(kind, w.M, w.d, P.MLMC_F32, w.ladder, None if w.adaptive else P.mlmc_geometric_p(w.L))
         msg = P.BitsMessage(plan)
     out = torch.empty(w.d, dtype=torch.float32, device=dev)
     x_model = torch.zeros(w.d, dtype=torch.float32, device=dev) if args.fused_update else None
@@ -244,7 +248,7 @@ def main():
         if sparse:
             P.mlmc_compress_topk(plan, g, seed=w.seed, step=i, out=msg)
         else:
-            P.mlmc_compress_bits(plan, g, seed=w.seed, step=i, out=msg)
+            (P.mlmc_compress_rtn if w.kind == "rtn" else P.mlmc_compress_bits)(plan, g, seed=w.seed, step=i, out=msg)
         if args.fused_update:
             P.mlmc_aggregate_update(plan, msg, alpha, 0.01, x_model)
         else:
@@ -294,12 +298,15 @@ def main():
             for l in msg.level.cpu().numpy().tolist():
                 drawn[l] = drawn.get(l, 0) + 1
         else:
-            P.mlmc_compress_bits(plan, g, seed=w.seed, step=args.warmup + i, out=msg)
+            (P.mlmc_compress_rtn if w.kind == "rtn" else P.mlmc_compress_bits)(plan, g, seed=w.seed, step=args.warmup + i, out=msg)
             lv = msg.level.cpu().numpy()
             for l in lv.tolist():
                 drawn[l] = drawn.get(l, 0) + 1
-            widths = [w.ladder[l] - w.ladder[l - 1] for l in lv]
-            planes_bytes += sum(((9 if w.kind == "fbits" else 1) + w.ladder[0] + x) * ((w.d + 63) // 64) * 8 for x in widths)
+            if w.kind == "rtn":     # the codes of the base, the previous and the drawn level
+                per_row = [w.ladder[0] + (w.ladder[l - 1] if l > 1 else 0) + w.ladder[l] for l in lv]
+            else:
+                per_row = [(9 if w.kind == "fbits" else 1) + w.ladder[0] + w.ladder[l] - w.ladder[l - 1] for l in lv]
+            planes_bytes += sum(n * ((w.d + 63) // 64) * 8 for n in per_row)
     nnz_avg = nnz_total / args.steps
     planes_avg = planes_bytes / args.steps
 

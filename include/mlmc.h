@@ -58,11 +58,12 @@ typedef enum {
 #define MLMC_DEV_REDONE 8    /* not an error: a row's sampled threshold search was refuted and the row was redone exactly */
 
 typedef enum { MLMC_F32 = 0, MLMC_BF16 = 1 } mlmc_dtype;
-typedef enum { MLMC_TOPK = 0, MLMC_BITS = 1, MLMC_FBITS = 2, MLMC_STOPK = 3, MLMC_VBITS = 4 } mlmc_kind;
+typedef enum { MLMC_TOPK = 0, MLMC_BITS = 1, MLMC_FBITS = 2, MLMC_STOPK = 3, MLMC_VBITS = 4, MLMC_RTN = 5 } mlmc_kind;
 
 #define MLMC_MAX_LEVELS 32   /* L <= 32 */
 #define MLMC_MAX_WORKERS 1024 /* M <= 1024 */
 #define MLMC_MAX_SLEVELS 65536 /* MLMC_STOPK: L = ceil(d / s) <= 65536 */
+#define MLMC_MAX_RTN_LEVELS 8  /* MLMC_RTN: L <= 8 */
 #define MLMC_TILE 4096       /* elements per tile of the per-row offset table */
 
 /*
@@ -78,6 +79,12 @@ typedef enum { MLMC_TOPK = 0, MLMC_BITS = 1, MLMC_FBITS = 2, MLMC_STOPK = 3, MLM
  *   kind == MLMC_FBITS: ladder = kept mantissa digits F_0..F_L, 0 <= F_0 < ... < F_L <= 23 (App. B: the
  *            floating-point compressor C^F keeps sign, exponent and the first F mantissa digits of every entry;
  *            the paper's ladder is F = 0, 1, ..., 52 for fp64, here 0..23 for fp32 inputs)
+ *   kind == MLMC_RTN: Round-to-Nearest ladder (Sec. 3.3, App. G.2): ladder = bit widths b_0..b_L, 0 <= b_0 < ... < b_L <= 16,
+ *            L <= MLMC_MAX_RTN_LEVELS.  C^b(v)_j = n_j * 2c / (2^b - 1) with c = max_j |v_j| (sent with the message) and
+ *            the code n_j = the exact quotient v_j (2^b - 1) / (2c) rounded to the nearest integer, ties to even,
+ *            kept within |n_j| <= 2^(b-1) - 1 (a symmetric b-bit code); b = 0 is the zero vector.  A message holds the
+ *            codes of the levels involved: b_0 + b_{l-1} + b_l planes at most 32.  p_fixed may be NULL: Lemma 3.4's
+ *            probabilities from every row's residual norms (Alg. 3).
  *   kind == MLMC_STOPK: s-segmented Top-k (Sec. 2.2, Sec. 3.2): ladder = {s} (one entry, the segment length, s >= 1);
  *            the row sorted by magnitude is cut into segments of s entries, C^l keeps the first l of them, so
  *            k_l = min(s l, d), g^0 = 0, and L must be ceil(d / s) <= MLMC_MAX_SLEVELS.  p_fixed must be NULL: the
@@ -121,7 +128,7 @@ int64_t mlmc_plan_chunk(const mlmc_plan_t *plan);
 /* Tiles per row of the offset table: ceil(d / MLMC_TILE). */
 int64_t mlmc_plan_num_tiles(const mlmc_plan_t *plan);
 /* Planes per row of the packed message: MLMC_BITS and MLMC_VBITS 1 + F_0 + max_l (F_l - F_{l-1}); MLMC_FBITS 9 + F_0 + max_l (F_l - F_{l-1});
- * else 0. */
+ * MLMC_RTN b_0 + max_l ((l > 1 ? b_{l-1} : 0) + b_l); else 0. */
 int mlmc_plan_num_planes(const mlmc_plan_t *plan);
 
 /* Lemma 3.3 form: p[l-1] = 2^-l / (1 - 2^-L), l = 1..L (host array of L doubles). */
@@ -182,6 +189,22 @@ mlmc_status mlmc_compress_bits(const mlmc_plan_t *plan, const void *g, int64_t l
                                int32_t *dev_status, void *ws, void *hip_stream);
 
 /*
+ * Worker side of Alg. 2 / Alg. 3 for the Round-to-Nearest ladder (MLMC_RTN plans; Sec. 3.3, App. G.2).  The residual of
+ * level l is C^{b_l}(v) - C^{b_{l-1}}(v) = (2c / (D D')) k with the integers k_j = n_{b_l} D' - n_{b_{l-1}} D,
+ * D = 2^{b_l} - 1, D' = 2^{b_{l-1}} - 1 (D' = 1, n = 0 for b_{l-1} = 0); Delta_l = (2c / (D D')) sqrt(sum_j k_j^2) with
+ * the integer sum exact and rounded once to fp64 (Lemma 3.4).  Three reads of the input: largest entry, norms, codes.
+ *   level: dev [M] int32 (out);  scale: dev [M][2] int32 (out): the bit patterns of c and of the coefficient
+ *   fp32((2c / (D D')) / p_l) that the server multiplies k with;  planes: dev [M][num_planes][ceil(d/64)] uint64 (out):
+ *   per row the planes of the codes n_{b_0} (b_0 of them, if b_0 > 0), n_{b_{l-1}} (if l > 1) and n_{b_l}, each code
+ *   in two's complement cut to its width, least significant plane first; word w bit k <-> element 64 w + k; pad bits
+ *   zero; planes past those are not written.  norms_out: dev [M][L] fp64 or NULL.
+ *   Decoded value (mlmc_aggregate): fp32(n_{b_0}) * fp32(2c / D_0) + fp32(k_j) * coefficient, single fp32 operations.
+ */
+mlmc_status mlmc_compress_rtn(const mlmc_plan_t *plan, const void *g, int64_t ld, uint64_t seed, uint64_t step,
+                              int32_t *level, int32_t *scale, uint64_t *planes, double *norms_out,
+                              int32_t *dev_status, void *ws, void *hip_stream);
+
+/*
  * mlmc_compress_bits for callers that cannot allocate device memory or pass a workspace: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and kernels as
  * mlmc_compress_bits, without `ws`: the scratch (per-row maxima and draw records) lives in a device array of
@@ -209,6 +232,7 @@ mlmc_status mlmc_compress_bits_static(const mlmc_plan_t *plan, const void *g, in
  *     entry at j is skipped.
  *   MLMC_BITS plan: level, scale_exp, planes as written by mlmc_compress_bits; the decoded value of
  *     worker i at j is sign * [ fp32(f0) * fp32(2^(e - F_0)) + fp32(f) * fp32(2^(e - F_l) / p_l) ].
+ *   MLMC_RTN plan: level, scale_exp = the [M][2] `scale` of mlmc_compress_rtn, planes; decoded as stated there.
  *   MLMC_FBITS plan: level, planes (scale_exp unused, may be NULL); with sign s, exponent field E, base digits f0 and
  *     level digits f of worker i at j: base = float(s, E, f0 << (23 - F_0)), residual = float(s, E, f << (23 - F_l)) -
  *     float(s, E, 0) (exact), decoded value = fp32(base + fp32(residual * fp32(1 / p_l))).

@@ -21,7 +21,7 @@ import numpy as np
 @dataclass(frozen=True)
 class Workload:
     name: str
-    kind: str                 # "topk" | "stopk" | "bits" (fixed-point ladder) | "vbits" (the same, divided by the largest entry) | "fbits" (floating-point ladder)
+    kind: str                 # "topk" | "stopk" | "bits" (fixed-point ladder) | "vbits" (the same, divided by the largest entry) | "fbits" (floating-point ladder) | "rtn" (Round-to-Nearest ladder)
     M: int                    # workers (rows)
     d: int                    # gradient dimension
     dtype: str                # "f32" | "bf16"
@@ -62,6 +62,9 @@ WORKLOADS = {
     # the same ladder with entries divided by the largest entry itself (Sec. 3.1 as written)
     "resnet18_vbits": _mk("resnet18_vbits", "vbits", 8, 11_689_512, "f32", 5, [0, 1, 2, 4, 8, 16], False,
                           "segmented_normal", seed=0, steps=5, segments=62, std_lo=1e-4, std_hi=1e-1),
+    # Round-to-Nearest ladder at the widths the paper's plain RTN runs use (App. G.2: l in {2, 4, 8, 16}), adaptive p
+    "resnet18_rtn": _mk("resnet18_rtn", "rtn", 8, 11_689_512, "f32", 4, [0, 2, 4, 8, 16], True,
+                        "segmented_normal", seed=0, steps=5, segments=62, std_lo=1e-4, std_hi=1e-1),
     # s-segmented Top-k at ResNet-18 scale: s = 0.001 n (the smallest k of App. G.1), 1000 levels, adaptive p over all of them
     "resnet18_stopk": _mk("resnet18_stopk", "stopk", 8, 11_689_512, "f32", 1000,
                           [min(11_690 * l, 11_689_512) for l in range(1001)], True, "segmented_normal",

@@ -19,13 +19,13 @@ MLMC_OK, MLMC_EINVAL, MLMC_ENOMEM, MLMC_EHIP, MLMC_ELIMIT = 0, 1, 2, 3, 4
 MLMC_STATIC_SCRATCH_BYTES = 1 << 20
 MLMC_DEV_CAPACITY, MLMC_DEV_NONFINITE, MLMC_DEV_INTERNAL, MLMC_DEV_REDONE = 1, 2, 4, 8
 MLMC_F32, MLMC_BF16 = 0, 1
-MLMC_TOPK, MLMC_BITS, MLMC_FBITS, MLMC_STOPK, MLMC_VBITS = 0, 1, 2, 3, 4
+MLMC_TOPK, MLMC_BITS, MLMC_FBITS, MLMC_STOPK, MLMC_VBITS, MLMC_RTN = 0, 1, 2, 3, 4, 5
 MLMC_MAX_SLEVELS = 65536
 MLMC_TILE = 4096
 MLMC_MAX_LEVELS = 32
 
 EXPORTS = ["mlmc_plan", "mlmc_plan_destroy", "mlmc_plan_set_sampling", "mlmc_plan_set_staging", "mlmc_plan_num_tiles", "mlmc_plan_chunk", "mlmc_plan_num_planes", "mlmc_geometric_p",
-           "mlmc_status_string", "mlmc_level_norms", "mlmc_compress_topk", "mlmc_compress_bits", "mlmc_compress_bits_static", "mlmc_aggregate", "mlmc_aggregate_update", "mlmc_message_bits",
+           "mlmc_status_string", "mlmc_level_norms", "mlmc_compress_topk", "mlmc_compress_bits", "mlmc_compress_bits_static", "mlmc_compress_rtn", "mlmc_aggregate", "mlmc_aggregate_update", "mlmc_message_bits",
            "mlmc_profile_enable", "mlmc_profile_reset", "mlmc_profile_num_kernels", "mlmc_profile_kernel_name",
            "mlmc_profile_get"]
 
@@ -69,6 +69,8 @@ def lib():
         L.mlmc_compress_topk.argtypes = [vp, vp, i64, vp, i32, u64, u64, vp, vp, vp, vp, i64, vp, vp, vp, vp, vp]
         L.mlmc_compress_bits.restype = C.c_int
         L.mlmc_compress_bits.argtypes = [vp, vp, i64, u64, u64, vp, vp, vp, vp, vp, vp]
+        L.mlmc_compress_rtn.restype = C.c_int
+        L.mlmc_compress_rtn.argtypes = [vp, vp, i64, u64, u64, vp, vp, vp, vp, vp, vp, vp]
         L.mlmc_compress_bits_static.restype = C.c_int
         L.mlmc_compress_bits_static.argtypes = [vp, vp, i64, u64, u64, vp, vp, vp, vp, vp]
         L.mlmc_aggregate.restype = C.c_int
@@ -242,7 +244,10 @@ class BitsMessage:
         dev = plan.device
         self.nwords = (plan.d + 63) // 64
         self.level = torch.empty(plan.M, dtype=torch.int32, device=dev)
-        self.scale_exp = torch.empty(plan.M, dtype=torch.int32, device=dev)
+        # per row: the scale exponent (MLMC_BITS), the bits of the largest entry (MLMC_VBITS), or, for MLMC_RTN, two
+        # words: the bits of c and of the coefficient
+        self.scale_exp = torch.empty((plan.M, 2) if plan.kind == MLMC_RTN else (plan.M,), dtype=torch.int32, device=dev)
+        self.norms = torch.empty((plan.M, plan.L), dtype=torch.float64, device=dev) if plan.kind == MLMC_RTN else None
         self.planes = torch.zeros((plan.M, plan.num_planes, self.nwords), dtype=torch.int64, device=dev)  # uint64 payload
 
 
@@ -253,6 +258,16 @@ def mlmc_compress_bits(plan: Plan, g: torch.Tensor, seed: int, step: int, out: O
     rc = lib().mlmc_compress_bits(plan.handle, _ptr(g), ld, seed, step, _ptr(out.level), _ptr(out.scale_exp),
                                   _ptr(out.planes), _ptr(plan.dev_status), _ptr(plan.ws), _stream())
     _check(rc, "mlmc_compress_bits")
+    return out
+
+
+def mlmc_compress_rtn(plan: Plan, g: torch.Tensor, seed: int, step: int, out: Optional[BitsMessage] = None) -> BitsMessage:
+    ld = _check_g(plan, g)
+    if out is None:
+        out = BitsMessage(plan)
+    rc = lib().mlmc_compress_rtn(plan.handle, _ptr(g), ld, seed, step, _ptr(out.level), _ptr(out.scale_exp), _ptr(out.planes),
+                                 _ptr(out.norms), _ptr(plan.dev_status), _ptr(plan.ws), _stream())
+    _check(rc, "mlmc_compress_rtn")
     return out
 
 

@@ -9,7 +9,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libmlmc.so")
-SOURCES = ["mlmc_api.hip", "mlmc_topk.hip", "mlmc_bits_agg.hip", "mlmc_stopk.hip"]
+SOURCES = ["mlmc_api.hip", "mlmc_topk.hip", "mlmc_bits_agg.hip", "mlmc_vrtn.hip", "mlmc_stopk.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -14,6 +14,7 @@ mlmc_status topk_zero(const mlmc_plan_t* pl, void* ws, int32_t* dev_status, hipS
 mlmc_status topk_select(const mlmc_plan_t* pl, const TopkArgs& a, bool sums, bool vec, hipStream_t st);
 mlmc_status topk_compact(const mlmc_plan_t* pl, const TopkArgs& a, bool vec, hipStream_t st);
 mlmc_status bits_compress(const mlmc_plan_t* pl, const BitsArgs& a, bool vec, hipStream_t st);
+mlmc_status rtn_compress(const mlmc_plan_t* pl, const BitsArgs& a, bool vec, bool message, hipStream_t st);
 mlmc_status agg_bits(const mlmc_plan_t* pl, const BitsArgs& b, const int32_t* level, const int32_t* scale_exp,
                      const uint64_t* planes, float alpha, float* out, float eta, float* x, hipStream_t st);
 mlmc_status agg_sparse(const mlmc_plan_t* pl, const int64_t* row_off, const uint32_t* idx, const float* val, int64_t capacity,
@@ -50,7 +51,7 @@ static mlmc_status static_scratch_of_current_device(void** out) {
 bool g_prof_on = false;
 static const char* const k_names[K_NUM] = {
     "k_zero", "k_hist", "k_scan", "k_main", "k_fhist", "k_finish", "k_finish_rank", "redo_pass", "k_norms", "k_bits_prep", "k_msgplan", "k_filter", "k_write",
-    "k_bits_smax", "k_bits_extract", "k_bits_redo", "k_agg_bits", "k_tileoff", "k_agg_sparse", "k_message_bits",
+    "k_bits_smax", "k_bits_extract", "k_bits_redo", "k_agg_bits", "k_tileoff", "k_agg_sparse", "k_message_bits", "k_rtn_norms", "k_rtn_draw",
     "k_rs_hist", "k_rs_scan", "k_rs_scatter", "k_sb_norms", "k_sb_draw", "k_sb_mark", "k_sb_offsets", "k_sb_write"};
 struct ProfPair { int id; hipEvent_t e0, e1; };
 static std::vector<ProfPair> g_pending;
@@ -152,6 +153,12 @@ static void fill_bits_args(const mlmc_plan_t* pl, BitsArgs& b, const void* g, in
     for (int l = 0; l < pl->L; ++l) b.p_fixed[l] = pl->p[l];
     b.flt = pl->kind == MLMC_FBITS ? 1 : 0;
     b.vmx = pl->kind == MLMC_VBITS ? 1 : 0;
+    b.rtn = pl->kind == MLMC_RTN ? 1 : 0;
+    b.adaptive = pl->adaptive ? 1 : 0;
+    if (pl->kind == MLMC_RTN && ws) {
+        b.rtn_sums = (unsigned long long*)(w + pl->off_rtn_sums);
+        b.norms = (double*)(w + pl->off_norms);
+    }
     b.nplanes = pl->nplanes;
     b.nwords = (pl->d + 63) / 64;
     b.chunk = pl->chunk;
@@ -278,7 +285,7 @@ mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dty
     if (plan) *plan = nullptr;
     if (!plan || !ladder) return MLMC_EINVAL;
     if (kind == MLMC_STOPK) return plan_stopk(plan, M, d, in_dtype, L, ladder[0], p_fixed, workspace_bytes, sparse_capacity_worst);
-    if (kind != MLMC_TOPK && kind != MLMC_BITS && kind != MLMC_FBITS && kind != MLMC_VBITS) return MLMC_EINVAL;
+    if (kind != MLMC_TOPK && kind != MLMC_BITS && kind != MLMC_FBITS && kind != MLMC_VBITS && kind != MLMC_RTN) return MLMC_EINVAL;
     if (in_dtype != MLMC_F32 && in_dtype != MLMC_BF16) return MLMC_EINVAL;
     if (M < 1 || M > MLMC_MAX_WORKERS || d < 1 || d >= ((int64_t)1 << 31) || L < 1 || L > MLMC_MAX_LEVELS) return MLMC_EINVAL;
     if (ladder[0] < 0) return MLMC_EINVAL;
@@ -287,7 +294,8 @@ mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dty
     if (kind == MLMC_TOPK && ladder[L] > d) return MLMC_EINVAL;
     if ((kind == MLMC_BITS || kind == MLMC_VBITS) && ladder[L] > 24) return MLMC_EINVAL;
     if (kind == MLMC_FBITS && ladder[L] > 23) return MLMC_EINVAL;
-    if (kind != MLMC_TOPK && !p_fixed) return MLMC_EINVAL;  // Lemma 3.4 probabilities are built for rank bands only
+    if (kind == MLMC_RTN && (ladder[L] > 16 || L > MLMC_MAX_RTN_LEVELS)) return MLMC_EINVAL;
+    if (kind != MLMC_TOPK && kind != MLMC_RTN && !p_fixed) return MLMC_EINVAL;  // Lemma 3.4 probabilities: rank bands and the Round-to-Nearest ladder
     if (p_fixed) {
         double s = 0.0;
         for (int l = 0; l < L; ++l) {
@@ -317,6 +325,15 @@ mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dty
             if (w > maxw) maxw = w;
         }
         pl->nplanes = (kind == MLMC_FBITS ? 9 : 1) + (int)ladder[0] + maxw;
+        if (kind == MLMC_RTN) {   // the codes of the base, the previous and the drawn level
+            int most = 0;
+            for (int l = 1; l <= L; ++l) {
+                const int n = (int)ladder[0] + (l > 1 ? (int)ladder[l - 1] : 0) + (int)ladder[l];
+                if (n > most) most = n;
+            }
+            if (most > MAX_FPLANES) { delete pl; return MLMC_EINVAL; }
+            pl->nplanes = most;
+        }
     }
     // chunking of the streaming kernels: about 2048 workgroups over all rows, but chunks of at least some 96 K
     // elements (a workgroup of the selection read loads a 64 KB table first), whole tiles, at most 2^18 elements
@@ -355,7 +372,7 @@ mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dty
     pl->cchunks_per_row = (int)((d + pl->cchunk - 1) / pl->cchunk);
     // rows long enough that a second full read matters get their thresholds from a sampled histogram
     pl->sample_shift = d >= ((int64_t)1 << 23) ? 4 : d >= ((int64_t)1 << 21) ? 2 : 0;
-    if (kind == MLMC_VBITS) pl->sample_shift = 0;   // the largest entry itself is needed, not its binade
+    if (kind == MLMC_VBITS || kind == MLMC_RTN) pl->sample_shift = 0;   // the largest entry itself is needed, not its binade
     pl->staging = 1;
 
     size_t off = 0;
@@ -376,6 +393,12 @@ mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dty
     pl->zero_bytes = off;
     pl->off_rinfo = off;
     off = align_up(off + sizeof(RowInfo) * (size_t)M, 256);
+    if (kind == MLMC_RTN) {
+        pl->off_rtn_sums = off;
+        off = align_up(off + sizeof(unsigned long long) * 2 * (size_t)L * M, 256);
+        pl->off_norms = off;
+        off = align_up(off + sizeof(double) * (size_t)L * M, 256);
+    }
     if (kind == MLMC_TOPK) {
         pl->off_table = off;
         off = align_up(off + sizeof(uint32_t) * NB1 * (size_t)M, 256);
@@ -419,7 +442,7 @@ mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dty
 void mlmc_plan_destroy(mlmc_plan_t* plan) { delete plan; }
 
 mlmc_status mlmc_plan_set_sampling(mlmc_plan_t* plan, int shift) {
-    if (!plan || shift < 0 || shift > 12 || plan->kind == MLMC_VBITS) return MLMC_EINVAL;
+    if (!plan || shift < 0 || shift > 12 || plan->kind == MLMC_VBITS || plan->kind == MLMC_RTN) return MLMC_EINVAL;
     plan->sample_shift = shift;
     return MLMC_OK;
 }
@@ -436,9 +459,15 @@ int mlmc_plan_num_planes(const mlmc_plan_t* plan) { return plan ? plan->nplanes 
 
 mlmc_status mlmc_level_norms(const mlmc_plan_t* plan, const void* g, int64_t ld, double* norms, int32_t* dev_status,
                              void* ws, void* hip_stream) {
-    if (!plan || (plan->kind != MLMC_TOPK && plan->kind != MLMC_STOPK) || !g || !norms || !dev_status || !ws || ld < plan->d) return MLMC_EINVAL;
+    if (!plan || (plan->kind != MLMC_TOPK && plan->kind != MLMC_STOPK && plan->kind != MLMC_RTN) || !g || !norms || !dev_status || !ws || ld < plan->d) return MLMC_EINVAL;
     if ((uintptr_t)ws % 256) return MLMC_EINVAL;
     hipStream_t st = (hipStream_t)hip_stream;
+    if (plan->kind == MLMC_RTN) {
+        BitsArgs b;
+        fill_bits_args(plan, b, g, ld, ws, dev_status);
+        b.norms_user = norms;
+        return rtn_compress(plan, b, vec_ok(plan, g, ld), false, st);
+    }
     if (plan->kind == MLMC_STOPK) {
         StopkArgs sa;
         fill_stopk_args(plan, sa, g, ld, ws, dev_status);
@@ -525,6 +554,21 @@ mlmc_status mlmc_compress_bits(const mlmc_plan_t* plan, const void* g, int64_t l
     b.seed = seed;
     b.step = step;
     return bits_compress(plan, b, vec_ok(plan, g, ld), st);
+}
+
+mlmc_status mlmc_compress_rtn(const mlmc_plan_t* plan, const void* g, int64_t ld, uint64_t seed, uint64_t step, int32_t* level,
+                              int32_t* scale, uint64_t* planes, double* norms_out, int32_t* dev_status, void* ws, void* hip_stream) {
+    if (!plan || plan->kind != MLMC_RTN || !g || !level || !scale || !planes || !dev_status || !ws) return MLMC_EINVAL;
+    if (ld < plan->d || (uintptr_t)ws % 256) return MLMC_EINVAL;
+    BitsArgs b;
+    fill_bits_args(plan, b, g, ld, ws, dev_status);
+    b.level = level;
+    b.scale_exp = scale;
+    b.planes = planes;
+    b.norms_user = norms_out;
+    b.seed = seed;
+    b.step = step;
+    return rtn_compress(plan, b, vec_ok(plan, g, ld), true, (hipStream_t)hip_stream);
 }
 
 mlmc_status mlmc_compress_bits_static(const mlmc_plan_t* plan, const void* g, int64_t ld, uint64_t seed, uint64_t step,

@@ -1,14 +1,16 @@
-// Fixed-point bit-wise MLMC (Sec. 3.1) and the server aggregate (Alg. 2 / Alg. 3) on gfx950.
+// Bit-wise MLMC (Sec. 3.1 fixed point, App. B floating point) and the server aggregate (Alg. 2 / Alg. 3) on gfx950.
 //
 //   k_bits_prep     level draw of every row
-//   k_bits_smax     largest |g| key of a sample of every row (integer atomic max) -> predicted power-of-two scale
-//   k_bits_extract  the one full read: digits floor(|g_j| / s * 2^F), sign plane + field planes packed by wave
+//   k_bits_smax     largest |g| key of a sample of every row (integer atomic max) -> predicted power-of-two scale   [mlmc_extract.h]
+//   k_bits_extract  the one full read: digits floor(|g_j| / s * 2^F), sign plane + field planes packed by wave      [mlmc_extract.h]
 //                   ballot, and the true row maximum; a row whose true maximum has a larger exponent than the
 //                   sampled one is extracted again by a second launch (which returns at once for every other row)
-//   k_agg_bits      out = alpha * sum_i decode_i, rows added in worker order
+//   k_agg_bits      out = alpha * sum_i decode_i, rows added in worker order (all plane messages, Round-to-Nearest included)
 //   k_tileoff       (fallback) per-tile offsets of index-sorted sparse rows by binary search
 //   k_agg_sparse    atomic-free segmented scatter-add: one workgroup owns one dense tile
-#include "mlmc_device.h"
+//   k_message_bits  bits on the wire of every row's message
+// The ladder of |g| / max|g| and the Round-to-Nearest ladder are launched from mlmc_vrtn.hip.
+#include "mlmc_extract.h"
 
 namespace mlmc {
 
@@ -31,311 +33,6 @@ __global__ __launch_bounds__(1024) void k_bits_prep(BitsArgs a) {
         a.level[row] = level;
         a.racc[row].rowmax_key = 0u;
         a.racc[row].smpmax_key = 0u;
-    }
-}
-
-// Largest |g| key of the sampled blocks of every row (block b of 1024 elements is sampled when b % S == S / 2,
-// S = 2^sample_shift; S = 1 reads the whole row and the result is the row maximum itself).
-constexpr int SMAX_THREADS = 512;
-template <int DT, bool VEC>
-__global__ __launch_bounds__(SMAX_THREADS) void k_bits_smax(BitsArgs a) {
-    const int row = blockIdx.y;
-    const int64_t S = (int64_t)1 << a.sample_shift, first = S >> 1;
-    const int64_t nblk = (a.d + 1023) / 1024;
-    const int64_t ns = nblk > first ? (nblk - first + S - 1) / S : 0;
-    RowLoader<DT, VEC> ld(a.g, a.ld, a.d, row);
-    const uint32_t lane = lane_id(), wave = (uint32_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    uint32_t maxkey = 0;
-    // a wave's blocks, the loads of the next one in flight while the current one is reduced
-    const int64_t i0 = (int64_t)blockIdx.x * (SMAX_THREADS / 64) + wave, istride = (int64_t)gridDim.x * (SMAX_THREADS / 64);
-    auto fetch = [&](int64_t i, uint32_t (&b)[4][4]) {
-        const int64_t blk = first + i * S;
-        const int64_t base = blk * 1024 + lane * 4;
-        if ((blk + 1) * 1024 <= a.d) {   // a whole block: four loads in flight
-#pragma unroll
-            for (int q = 0; q < 4; ++q) ld.load4_stream(base + q * 256, b[q]);
-        } else {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) ld.load4(base + q * 256, b[q]);   // past the end: +0
-        }
-    };
-    auto reduce = [&](const uint32_t (&b)[4][4]) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const uint32_t key = key_of_bits(b[q][c]);
-                maxkey = key > maxkey ? key : maxkey;
-            }
-    };
-    uint32_t b0[4][4], b1[4][4];
-    int64_t i = i0;
-    if (i < ns) fetch(i, b0);
-    for (; i < ns; i += 2 * istride) {
-        const bool more1 = i + istride < ns, more2 = i + 2 * istride < ns;   // uniform
-        if (more1) fetch(i + istride, b1);
-        reduce(b0);
-        if (more2) fetch(i + 2 * istride, b0);
-        if (more1) reduce(b1);
-    }
-    maxkey = wave_max(maxkey);
-    if (lane == 0 && maxkey) {
-        atomicMax(&a.racc[row].smpmax_key, maxkey);
-        if (maxkey >= 0x7F800000u) atomicOr(a.dev_status, MLMC_DEV_NONFINITE);
-    }
-}
-
-// v_writelane_b32 through its compiler intrinsic (this compiler has no builtin of that name): the result is `old`
-// with lane `lane` (uniform) replaced by the uniform value `sval`.  As an intrinsic, not inline assembly, so that
-// the compiler keeps the wait states the instruction needs after the compare that produced sval.
-extern "C" __device__ int mlmc_writelane_i32(int sval, int lane, int old) __asm("llvm.amdgcn.writelane.i32");
-__device__ __forceinline__ void put_lane(uint32_t& dst, uint32_t sval, int lane) {
-    dst = (uint32_t)mlmc_writelane_i32((int)sval, lane, (int)dst);
-}
-
-// One wave packs one tile of 4096 elements: iteration i covers elements [64 i, 64 i + 64) of the tile, so a
-// ballot is the plane word of those 64 elements; it is kept in lane i and the 64 words of a plane go out in one
-// store.  Emax is the exponent the scale is taken from.  NPC: compile-time bound on the planes of the row (np <= NPC);
-// BASE: the ladder has a base field (F_0 > 0).  Returns the largest key met, through maxkey.
-//
-// Digits (Sec. 3.1): |g| = sig * 2^(E' - 150), scale s = 2^(Emax - 126), so floor(|g| / s * 2^F) = sig >> (24 - F + Emax - E').
-// Bit b of (sig >> (24 - F_l + Emax - E')) for b < F_l - F_{l-1} is bit b of the level field.
-// MODE 0 / 1: fixed-point ladder without / with a base field (F_0 > 0); MODE 2: floating-point ladder (App. B);
-// MODE 3 / 4: fixed-point ladder of |g| / v, v the largest entry of the row (vd, as a double; vr = 1 / vd), without /
-// with a base field.  Its digits: m = min(floor(|g| 2^Q / v), 2^Q - 1), Q = F_L.  |g| 2^Q and v are exact doubles;
-// n = trunc(|g| 2^Q * vr) is off by at most one, and the remainder |g| 2^Q - n v, exact in one fused multiply-add
-// (n v has at most 48 bits), says which way.
-template <int DT, bool VEC, int NPC, int MODE>
-__device__ __forceinline__ void bits_extract_tiles(const BitsArgs& a, int row, int Emax, int level, int np, uint32_t& maxkey,
-                                                   uint32_t* slds, double vd = 0.0, double vr = 0.0) {
-    const uint32_t lane = lane_id(), wave = (uint32_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    RowLoader<DT, false> ld(a.g, a.ld, a.d, row);
-    RowLoader<DT, VEC> ld4(a.g, a.ld, a.d, row);
-    const int64_t ntiles = (a.d + TILE - 1) / TILE;
-    const int64_t nwhole = a.d / TILE;   // tiles with all 4096 elements
-    const int F0 = a.F[0];
-    constexpr bool BASE = MODE == 1 || MODE == 4;
-    const int Q = a.F[a.L];
-    const uint32_t vcap = vd > 0.0 ? (Q >= 32 ? 0xFFFFFFFFu : (1u << Q) - 1u) : 0u;   // a zero row has only zero digits
-    const uint32_t vsl = (uint32_t)(Q - a.F[level]), vs0 = (uint32_t)(Q - F0);
-    const uint32_t Cl = (uint32_t)(24 - a.F[level] + Emax), C0 = (uint32_t)(24 - F0 + Emax);
-    const uint32_t mask0 = BASE ? (1u << F0) - 1u : 0u;
-    const uint32_t fsl = (uint32_t)(23 - a.F[level]), fs0 = (uint32_t)(23 - F0);   // floating-point ladder: digit positions
-    uint32_t wlo[NPC], whi[NPC];   // lane i: word i of the tile's planes
-#pragma unroll
-    for (int p = 0; p < NPC; ++p) { wlo[p] = 0; whi[p] = 0; }
-    // plane p >= 1 <-> bit p - 1 of the value returned here (base field first, then the level field; for the
-    // floating-point ladder the eight exponent bits come first)
-    auto digits = [&](uint32_t bits) -> uint32_t {
-        const uint32_t key = key_of_bits(bits);
-        maxkey = key > maxkey ? key : maxkey;
-        const uint32_t E = key >> 23;
-        if (MODE == 2) {
-            // App. B: the digits m_1..m_F of the mantissa are the top F bits of the 23-bit fraction field
-            const uint32_t frac = key & 0x7FFFFFu;
-            const uint32_t base = F0 ? frac >> fs0 : 0u;
-            return E | ((base | ((frac >> fsl) << F0)) << 8);
-        }
-        const uint32_t hid = (key & 0x7FFFFFu) | 0x800000u;
-        const uint32_t sig = key < hid ? key : hid;       // exponent field 0: no hidden bit
-        const uint32_t Ec = E > 1u ? E : 1u;
-        if (MODE >= 3) {
-            const double xg = ldexp((double)sig, (int)Ec - 150 + Q);   // |g| 2^Q
-            uint32_t n = (uint32_t)__dmul_rn(xg, vr);
-            const double rem = __fma_rn(-(double)n, vd, xg);
-            n += rem >= vd ? 1u : 0u;
-            n -= rem < 0.0 ? 1u : 0u;
-            n = n < vcap ? n : vcap;
-            const uint32_t xv = n >> vsl;
-            if (!BASE) return xv;
-            return ((n >> vs0) & mask0) | (xv << F0);
-        }
-        const uint32_t sl = Cl - Ec;                      // >= 32 (also "negative"): every digit is zero
-        const uint32_t x = sig >> (sl < 31u ? sl : 31u);
-        if (!BASE) return x;
-        const uint32_t s0 = C0 - Ec;
-        const uint32_t x0 = sig >> (s0 < 31u ? s0 : 31u);
-        return (x0 & mask0) | (x << F0);
-    };
-    // the ballots of iteration i (elements 64 i .. 64 i + 63 of the tile, one per lane) go to lane i of the tile's words
-    auto pack16 = [&](int g4, const uint32_t (&v)[16]) {
-#pragma unroll
-        for (int u = 0; u < 16; ++u) {
-            const int i = g4 * 16 + u;
-            const uint32_t bits = v[u];
-            const uint32_t x = digits(bits);
-            {
-                const uint64_t w = __ballot((int32_t)bits < 0);
-                put_lane(wlo[0], (uint32_t)w, i);
-                put_lane(whi[0], (uint32_t)(w >> 32), i);
-            }
-#pragma unroll
-            for (int p = 1; p < NPC; ++p) {
-                if (p < np) {   // uniform
-                    const uint64_t w = __ballot((x & (1u << (p - 1))) != 0u);
-                    put_lane(wlo[p], (uint32_t)w, i);
-                    put_lane(whi[p], (uint32_t)(w >> 32), i);
-                }
-            }
-        }
-    };
-    auto store_words = [&](int64_t tile) {
-        const int64_t w0 = tile * 64 + lane;
-        if (w0 < a.nwords) {
-            uint64_t* dst = a.planes + (size_t)row * a.nplanes * a.nwords + w0;
-#pragma unroll
-            for (int p = 0; p < NPC; ++p)
-                if (p < np) dst[(size_t)p * a.nwords] = ((uint64_t)whi[p] << 32) | wlo[p];
-        }
-    };
-    const int64_t first = (int64_t)blockIdx.x * 4 + wave, stride = (int64_t)gridDim.x * 4;
-    int64_t tile = first;
-    if (VEC) {
-        // Whole tiles of an aligned row: sixteen 16-byte loads per lane and tile (a load covers 256 consecutive
-        // elements, four per lane), eight in flight, also across the wave's tiles.  Four loads at a time pass
-        // through the wave's LDS buffer, written as loaded and read back one element per lane, so that a ballot
-        // is a plane word.
-        uint32_t bufA[4][4], bufB[4][4];
-        auto fetch4 = [&](int64_t t, int l0, uint32_t (&buf)[4][4]) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) ld4.load4_stream(t * TILE + (int64_t)((l0 + q) * 256) + (int64_t)lane * 4, buf[q]);
-        };
-        auto transpose16 = [&](const uint32_t (&buf)[4][4], uint32_t (&v)[16]) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-                *(uint4*)(slds + q * 256 + lane * 4) = make_uint4(buf[q][0], buf[q][1], buf[q][2], buf[q][3]);
-            wave_lds_sync();
-#pragma unroll
-            for (int u = 0; u < 16; ++u) v[u] = slds[u * 64 + lane];
-            wave_lds_sync();   // the next writes come after these reads
-        };
-        if (tile < nwhole) {
-            fetch4(tile, 0, bufA);
-            fetch4(tile, 4, bufB);
-        }
-        for (; tile < nwhole; tile += stride) {
-            const bool more = tile + stride < nwhole;   // uniform
-            uint32_t v[16];
-            transpose16(bufA, v);
-            fetch4(tile, 8, bufA);
-            pack16(0, v);
-            transpose16(bufB, v);
-            fetch4(tile, 12, bufB);
-            pack16(1, v);
-            transpose16(bufA, v);
-            if (more) fetch4(tile + stride, 0, bufA);
-            pack16(2, v);
-            transpose16(bufB, v);
-            if (more) fetch4(tile + stride, 4, bufB);
-            pack16(3, v);
-            store_words(tile);
-        }
-    } else {
-        // a row that is not aligned for 16-byte loads: one element per lane and load, sixteen loads in flight
-        for (; tile < nwhole; tile += stride) {
-            for (int g4 = 0; g4 < 4; ++g4) {
-                uint32_t v[16];
-#pragma unroll
-                for (int u = 0; u < 16; ++u) v[u] = ld.load1_stream(tile * TILE + (g4 * 16 + u) * 64 + lane);
-                pack16(g4, v);
-            }
-            store_words(tile);
-        }
-    }
-    if (tile < ntiles) {   // the ragged last tile of the row (one wave of the row gets here)
-        const int64_t base = tile * TILE;
-#pragma unroll
-        for (int p = 0; p < NPC; ++p) { wlo[p] = 0; whi[p] = 0; }
-        for (int i = 0; i < 64; ++i) {
-            const int64_t j = base + i * 64 + lane;
-            const uint32_t bits = j < a.d ? ld.load1(j) : 0u;
-            const uint32_t x = digits(bits);
-            const bool me = (int)lane == i;
-            {
-                const uint64_t w = __ballot((int32_t)bits < 0);
-                wlo[0] = me ? (uint32_t)w : wlo[0];
-                whi[0] = me ? (uint32_t)(w >> 32) : whi[0];
-            }
-#pragma unroll
-            for (int p = 1; p < NPC; ++p) {
-                if (p < np) {   // uniform
-                    const uint64_t w = __ballot((x & (1u << (p - 1))) != 0u);
-                    wlo[p] = me ? (uint32_t)w : wlo[p];
-                    whi[p] = me ? (uint32_t)(w >> 32) : whi[p];
-                }
-            }
-        }
-        store_words(tile);
-    }
-}
-
-// The row's message under the scale taken from the sampled maximum; the true maximum of the row is tracked on the
-// way.  REDO (second launch, only when the maximum was sampled): rows whose true maximum has a larger exponent than
-// the sampled one are extracted again with the true one; every other row is already final and is skipped.
-// NPCMAX: bound on the planes of any row of the plan (the kernel holds only the variants it can need, so that a
-// plan with few planes is not charged the registers of the widest one).  FLT: floating-point ladder (no scale).
-// KIND 2: fixed-point ladder of |g| / v: the row maximum was read exactly beforehand (sample of every block).
-template <int DT, bool VEC, bool REDO, int NPCMAX, int KIND>
-__global__ __launch_bounds__(256) void k_bits_extract(BitsArgs a) {
-    constexpr bool FLT = KIND == 1;
-    __shared__ __align__(16) uint32_t s_tr[4][1024];   // per wave: four loads of 256 elements on their way from "four per lane" to "one per lane"
-    uint32_t* slds = s_tr[threadIdx.x >> 6];
-    const int row = blockIdx.y;
-    RowAcc* ra = a.racc + row;
-    const uint32_t Es = ra->smpmax_key >> 23;
-    uint32_t Ex = Es;
-    if (REDO) {
-        Ex = ra->rowmax_key >> 23;
-        if (Ex == Es) return;
-    }
-    const int Emax = Ex ? (int)Ex : 1;
-    const int level = a.rinfo[row].level;
-    const int F0 = a.F[0];
-    const int np = (FLT ? 9 : 1) + F0 + (a.F[level] - a.F[level - 1]);   // planes written for this row
-    if (KIND == 0 && blockIdx.x == 0 && threadIdx.x == 0) a.scale_exp[row] = Emax - 126;
-    uint32_t maxkey = 0;
-    if constexpr (KIND == 2) {
-        const uint32_t vkey = ra->smpmax_key;   // the largest |g| of the row
-        if (blockIdx.x == 0 && threadIdx.x == 0) a.scale_exp[row] = (int32_t)vkey;
-        const uint32_t vE = vkey >> 23;
-        const double vd = ldexp((double)(vE ? (vkey & 0x7FFFFFu) | 0x800000u : vkey), (int)(vE ? vE : 1u) - 150);
-        const double vr = vd > 0.0 ? __ddiv_rn(1.0, vd) : 0.0;
-        if (F0 == 0) {
-            if (np <= 9) bits_extract_tiles<DT, VEC, 9, 3>(a, row, Emax, level, np, maxkey, slds, vd, vr);
-            else if constexpr (NPCMAX > 9) bits_extract_tiles<DT, VEC, MAX_PLANES, 3>(a, row, Emax, level, np, maxkey, slds, vd, vr);
-        } else {
-            if (np <= 9) bits_extract_tiles<DT, VEC, 9, 4>(a, row, Emax, level, np, maxkey, slds, vd, vr);
-            else if constexpr (NPCMAX > 9) bits_extract_tiles<DT, VEC, MAX_PLANES, 4>(a, row, Emax, level, np, maxkey, slds, vd, vr);
-        }
-    } else if constexpr (FLT) {
-        if (np <= 11) bits_extract_tiles<DT, VEC, 11, 2>(a, row, Emax, level, np, maxkey, slds);
-        else if constexpr (NPCMAX > 11) {
-            if (np <= 17) bits_extract_tiles<DT, VEC, 17, 2>(a, row, Emax, level, np, maxkey, slds);
-            else if (np <= 25) bits_extract_tiles<DT, VEC, 25, 2>(a, row, Emax, level, np, maxkey, slds);
-            else bits_extract_tiles<DT, VEC, MAX_FPLANES, 2>(a, row, Emax, level, np, maxkey, slds);
-        }
-    } else if (F0 == 0) {
-        if (np <= 3) bits_extract_tiles<DT, VEC, 3, 0>(a, row, Emax, level, np, maxkey, slds);
-        else if (np <= 5) bits_extract_tiles<DT, VEC, 5, 0>(a, row, Emax, level, np, maxkey, slds);
-        else if (np <= 9) bits_extract_tiles<DT, VEC, 9, 0>(a, row, Emax, level, np, maxkey, slds);
-        else if constexpr (NPCMAX > 9) {
-            if (np <= 17) bits_extract_tiles<DT, VEC, 17, 0>(a, row, Emax, level, np, maxkey, slds);
-            else bits_extract_tiles<DT, VEC, MAX_PLANES, 0>(a, row, Emax, level, np, maxkey, slds);
-        }
-    } else {
-        if (np <= 5) bits_extract_tiles<DT, VEC, 5, 1>(a, row, Emax, level, np, maxkey, slds);
-        else if (np <= 9) bits_extract_tiles<DT, VEC, 9, 1>(a, row, Emax, level, np, maxkey, slds);
-        else if constexpr (NPCMAX > 9) {
-            if (np <= 17) bits_extract_tiles<DT, VEC, 17, 1>(a, row, Emax, level, np, maxkey, slds);
-            else bits_extract_tiles<DT, VEC, MAX_PLANES, 1>(a, row, Emax, level, np, maxkey, slds);
-        }
-    }
-    if (!REDO) {
-        maxkey = wave_max(maxkey);
-        if (lane_id() == 0 && maxkey) {
-            atomicMax(&ra->rowmax_key, maxkey);
-            if (maxkey >= 0x7F800000u) atomicOr(a.dev_status, MLMC_DEV_NONFINITE);
-        }
     }
 }
 
@@ -382,7 +79,16 @@ __global__ __launch_bounds__(256) void k_agg_bits(AggBitsArgs a, const uint64_t*
     const int F0 = b.F[0];
     for (int r = threadIdx.x; r < b.M; r += 256) {
         int lev = a.level[r];
+        lev = lev < 1 ? 1 : (lev > b.L ? b.L : lev);
         double pl = b.p_fixed[lev - 1];
+        if (b.rtn) {   // Round-to-Nearest: c_0 = fp32(2c / D_0); the coefficient comes with the message
+            const double c = key_to_double((uint32_t)a.scale_exp[2 * r] & 0x7FFFFFFFu);
+            s_c0[r] = F0 > 0 ? (float)__ddiv_rn(__dmul_rn(2.0, c), (double)((1 << F0) - 1)) : 0.0f;
+            s_cl[r] = __uint_as_float((uint32_t)a.scale_exp[2 * r + 1]);
+            s_w[r] = (uint8_t)b.F[lev];                          // width of the drawn level's code
+            s_fl[r] = (uint8_t)(lev > 1 ? b.F[lev - 1] : 0);     // width of the previous level's code when it is sent
+            continue;
+        }
         if (b.flt) {   // the level's weight fp32(1 / p_l)
             s_c0[r] = 0.0f;
             s_cl[r] = pl == 0.0 ? 0.0f : (float)__ddiv_rn(1.0, pl);
@@ -416,7 +122,44 @@ __global__ __launch_bounds__(256) void k_agg_bits(AggBitsArgs a, const uint64_t*
             const float cl = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(s_cl[r])));
             const uint64_t* rp = planes + (size_t)r * b.nplanes * nw + w0;
             const Words8 sg = load_words8(rp, nvalid);
-            if (b.flt) {
+            if (b.rtn) {
+                // codes n_{b_0} (if any), n_{b_{l-1}} (if sent) and n_{b_l} from their planes, sign-extended; the residual
+                // integer k = n_cur D' - n_prev D; value = fp32(n_0) c_0 + fp32(k) coefficient
+                const int bp = __builtin_amdgcn_readfirstlane((int)s_fl[r]);
+                const float c0 = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(s_c0[r])));
+                const int bprev = bp > 0 ? bp : F0;               // level 1: the previous code is the base code
+                const int D = (1 << wd) - 1, Dp = bprev > 0 ? (1 << bprev) - 1 : 1;
+                uint32_t u0[8], u1[8], u2[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) { u0[k] = 0; u1[k] = 0; u2[k] = 0; }
+                for (int q = 0; q < F0; ++q) {
+                    const Words8 pw = q == 0 ? sg : load_words8(rp + (size_t)q * nw, nvalid);
+                    const uint32_t bit = 1u << q;
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) u0[k] |= __builtin_amdgcn_inverse_ballot_w64(pw.w[k]) ? bit : 0u;
+                }
+                for (int q = 0; q < bp; ++q) {
+                    const Words8 pw = load_words8(rp + (size_t)(F0 + q) * nw, nvalid);
+                    const uint32_t bit = 1u << q;
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) u1[k] |= __builtin_amdgcn_inverse_ballot_w64(pw.w[k]) ? bit : 0u;
+                }
+                for (int q = 0; q < wd; ++q) {
+                    const Words8 pw = load_words8(rp + (size_t)(F0 + bp + q) * nw, nvalid);
+                    const uint32_t bit = 1u << q;
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) u2[k] |= __builtin_amdgcn_inverse_ballot_w64(pw.w[k]) ? bit : 0u;
+                }
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const int32_t n0 = F0 > 0 ? (int32_t)(u0[k] << (32 - F0)) >> (32 - F0) : 0;
+                    const int32_t np_ = bp > 0 ? (int32_t)(u1[k] << (32 - bp)) >> (32 - bp) : n0;
+                    const int32_t nc = (int32_t)(u2[k] << (32 - wd)) >> (32 - wd);
+                    float v = __fmul_rn((float)(nc * Dp - np_ * D), cl);
+                    if (F0 > 0) v = __fadd_rn(__fmul_rn((float)n0, c0), v);
+                    acc[k] = __fadd_rn(acc[k], v);
+                }
+            } else if (b.flt) {
                 // App. B: sign, exponent field and base digits give C^{F_0}; the level digits, placed under the same
                 // sign and exponent, minus the bare power of two give the residual (exact); weight, then one add
                 const int Fl = __builtin_amdgcn_readfirstlane((int)s_fl[r]);
@@ -635,6 +378,7 @@ __global__ __launch_bounds__(256) void k_message_bits(MsgBitsArgs a) {
     const int64_t width = s_lad[lev] - s_lad[lev - 1];
     if (a.kind == MLMC_TOPK) n = (unsigned long long)(s_lad[0] + width) * (unsigned long long)(32 + ceil_log2_dev(a.d));
     else if (a.kind == MLMC_FBITS) n = (unsigned long long)a.d * (unsigned long long)(9 + s_lad[0] + width);
+    else if (a.kind == MLMC_RTN) n = (unsigned long long)a.d * (unsigned long long)(s_lad[0] + (lev > 1 ? s_lad[lev - 1] : 0) + s_lad[lev]) + 64ull;
     else n = (unsigned long long)a.d * (unsigned long long)(1 + s_lad[0] + width) + 32ull;
     a.bits[r] = n + (unsigned long long)ceil_log2_dev(a.L);
 }
@@ -655,6 +399,8 @@ mlmc_status message_bits(const mlmc_plan_t* pl, const int32_t* level, unsigned l
 }
 
 // ---------------------------------------------------------------------------------------------------
+mlmc_status vbits_extract(const mlmc_plan_t* pl, const BitsArgs& a, bool vec, dim3 egrid, hipStream_t st);   // mlmc_vrtn.hip
+
 mlmc_status bits_compress(const mlmc_plan_t* pl, const BitsArgs& a, bool vec, hipStream_t st) {
     MLMC_LAUNCH(K_DRAW, st, k_bits_prep<<<1, 1024, 0, st>>>(a));
     // a wave takes about four tiles (its loads run ahead across tiles); at least some 2048 waves in all
@@ -702,10 +448,7 @@ mlmc_status bits_compress(const mlmc_plan_t* pl, const BitsArgs& a, bool vec, hi
         else MLMC_LAUNCH(K_BITS_MAX, st, k_bits_smax<MLMC_BF16, false><<<sgrid, SMAX_THREADS, 0, st>>>(a));
     }
     const bool small = pl->nplanes <= 9;
-    if (a.vmx) {   // the maxima above are exact (every block was read): one extraction
-        MLMC_EXTRACT(K_BITS_EXTRACT, false, 2, 9, MAX_PLANES);
-        return MLMC_OK;
-    }
+    if (a.vmx) return vbits_extract(pl, a, vec, egrid, st);   // the maxima above are exact (every block was read): one extraction
     MLMC_EXTRACT(K_BITS_EXTRACT, false, 0, 9, MAX_PLANES);
     if (a.sample_shift > 0) MLMC_EXTRACT(K_BITS_REDO, true, 0, 9, MAX_PLANES);   // rows whose sampled maximum fell short (returns at once for the others)
 #undef MLMC_EXTRACT_V

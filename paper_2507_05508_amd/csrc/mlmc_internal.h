@@ -19,7 +19,8 @@ constexpr int PMAX = 192;               // exact partial sums ("pieces") that th
 constexpr int PIECE_CLASSES = 96;       // (parts of a zone) x (exponents of a zone) handled by one finish workgroup
 constexpr int TILE = MLMC_TILE;
 constexpr int MAX_PLANES = 25;          // fixed-point messages: 1 sign + at most 24 field planes
-constexpr int MAX_FPLANES = 32;         // floating-point messages: 1 sign + 8 exponent + at most 23 mantissa planes
+constexpr int MAX_FPLANES = 32;         // also the bound on the code planes of a Round-to-Nearest message
+constexpr int RTN_LMAX = MLMC_MAX_RTN_LEVELS;         // floating-point messages: 1 sign + 8 exponent + at most 23 mantissa planes
 constexpr int CHUNK_MAX = 1 << 18;      // elements per workgroup chunk of the streaming kernels
 constexpr int CHUNKS_MAX = 8192;        // chunks per row
 constexpr int FH_BINS = 2048;           // bins of the zone-relative key histogram of the finish kernels
@@ -153,7 +154,12 @@ struct BitsArgs {
     double p_fixed[LMAX];
     int32_t flt;             // 1: floating-point ladder (App. B): F are mantissa digits, no scale
     int32_t vmx;             // 1: fixed-point ladder of |g| / max|g| (the scale field carries the bits of max|g|)
+    int32_t rtn;             // 1: Round-to-Nearest ladder: F are bit widths, the scale field is [M][2]: bits of c, bits of the coefficient
+    int32_t adaptive;        // RTN: 1 = probabilities from the row's residual norms (Lemma 3.4)
     int32_t pad_;
+    unsigned long long* rtn_sums;   // RTN: [M][L][2] sums of squared residual integers, low and high 32-bit halves (zeroed per call)
+    double* norms;           // RTN: [M][L]
+    double* norms_user;      // RTN: optional copy
     int32_t nplanes;         // planes per row in the message buffer
     int64_t nwords;          // ceil(d / 64)
     int32_t chunk;
@@ -202,7 +208,7 @@ struct StopkArgs {
 // ---- optional per-kernel timing with HIP events (host side, see mlmc_profile_* in mlmc.h) ----------
 enum KernelId {
     K_ZERO = 0, K_HIST, K_SCAN, K_MAIN, K_FHIST, K_FINISH, K_FINISH1, K_REDO, K_NORMS, K_DRAW, K_MSGPLAN, K_FILTER, K_WRITE,
-    K_BITS_MAX, K_BITS_EXTRACT, K_BITS_REDO, K_AGG_BITS, K_TILEOFF, K_AGG_SPARSE, K_MSGBITS,
+    K_BITS_MAX, K_BITS_EXTRACT, K_BITS_REDO, K_AGG_BITS, K_TILEOFF, K_AGG_SPARSE, K_MSGBITS, K_RTN_NORMS, K_RTN_DRAW,
     K_RS_HIST, K_RS_SCAN, K_RS_SCATTER, K_SB_NORMS, K_SB_DRAW, K_SB_MARK, K_SB_OFFSETS, K_SB_WRITE, K_NUM
 };
 extern bool g_prof_on;
@@ -242,4 +248,5 @@ struct mlmc_plan_s {
     int nblk;
     int64_t bm_words;
     size_t off_pa, off_pb, off_counts, off_bitmap, off_srow, off_bintot;
+    size_t off_rtn_sums;   // Round-to-Nearest plans
 };

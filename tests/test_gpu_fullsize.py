@@ -158,6 +158,31 @@ def test_vbits_full_size():
         assert np.array_equal(out.cpu().numpy().view(np.uint32), ref.view(np.uint32))
 
 
+def test_rtn_full_size():
+    w = W.WORKLOADS["resnet18_rtn"]
+    G = W.generate(w)
+    g = _upload(G)
+    plan = P.Plan(P.MLMC_RTN, w.M, w.d, P.MLMC_F32, w.ladder, None)
+    for step in (0, 1):
+        print(f"Round-to-Nearest full size step {step}", flush=True)
+        msg = P.mlmc_compress_rtn(plan, g, seed=w.seed, step=step)
+        out = P.mlmc_aggregate(plan, msg, 1.0 / w.M)
+        torch.cuda.synchronize()
+        assert plan.status() == 0
+        want = O.compress_rtn(G, w.ladder, None, w.seed, step)
+        planes = msg.planes.cpu().numpy().view(np.uint64)
+        scale = msg.scale_exp.cpu().numpy().view(np.uint32)
+        norms = msg.norms.cpu().numpy()
+        for i in range(w.M):
+            assert np.array_equal(norms[i].view(np.uint64), np.array(want[i]["norms"], dtype=np.float64).view(np.uint64))
+            assert int(msg.level[i]) == want[i]["level"]
+            assert scale[i, 0] == np.float32(want[i]["c"]).view(np.uint32) and scale[i, 1] == np.float32(want[i]["coef"]).view(np.uint32)
+            n = want[i]["planes"].shape[0]
+            assert np.array_equal(planes[i, :n], want[i]["planes"])
+        ref = O.aggregate_rtn(want, w.ladder, w.d, 1.0 / w.M)
+        assert np.array_equal(out.cpu().numpy().view(np.uint32), ref.view(np.uint32))
+
+
 def test_fbits_full_size():
     w = W.WORKLOADS["resnet18_fbits"]
     G = W.generate(w)
