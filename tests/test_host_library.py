@@ -50,6 +50,9 @@ def test_plan_validation():
         dict(kind=P.MLMC_BITS, M=1, d=10, ladder=[0, 8, 16], p=None),         # adaptive bits not defined
         dict(kind=P.MLMC_VBITS, M=1, d=10, ladder=[0, 8, 25], p=[0.5, 0.5]),  # more than 24 bits
         dict(kind=P.MLMC_VBITS, M=1, d=10, ladder=[0, 8, 16], p=None),        # adaptive not defined
+        dict(kind=P.MLMC_RTN, M=1, d=10, ladder=[0, 8, 17], p=None),          # codes wider than 16 bits
+        dict(kind=P.MLMC_RTN, M=1, d=10, ladder=list(range(10)), p=None),     # more than 8 levels
+        dict(kind=P.MLMC_RTN, M=1, d=10, ladder=[4, 14, 16], p=None),         # 4 + 14 + 16 code planes in one message
         dict(kind=P.MLMC_FBITS, M=1, d=10, ladder=[0, 8, 24], p=[0.5, 0.5]),  # more than 23 mantissa digits
         dict(kind=P.MLMC_FBITS, M=1, d=10, ladder=[0, 8, 16], p=None),        # adaptive not defined
         dict(kind=7, M=1, d=10, ladder=[0, 10], p=[1.0]),
@@ -65,5 +68,9 @@ def test_plan_validation():
     assert vb.num_planes == 1 + 2 + 5 and vb.sparse_capacity_worst == 0
     with pytest.raises(P.MlmcError):
         vb.set_sampling(2)   # the largest entry is read exactly
+    rt = P.Plan(P.MLMC_RTN, 8, 1000, P.MLMC_F32, [0, 2, 4, 8, 16], None, allocate=False)
+    assert rt.num_planes == 8 + 16 and rt.sparse_capacity_worst == 0     # the previous and the drawn level's codes
+    rt2 = P.Plan(P.MLMC_RTN, 8, 1000, P.MLMC_F32, [2, 3, 5, 9], P.mlmc_geometric_p(3), allocate=False)
+    assert rt2.num_planes == 2 + 5 + 9
     fb = P.Plan(P.MLMC_FBITS, 8, 1000, P.MLMC_F32, list(range(24)), P.mlmc_geometric_p(23), allocate=False)
     assert fb.num_planes == 10 and fb.sparse_capacity_worst == 0   # sign + 8 exponent bits + one mantissa digit (App. B)
