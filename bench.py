@@ -188,6 +188,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-staging", action="store_true",
                     help="Top-k: write every message by a second read of the rows (tuning hook off; same results)")
+    ap.add_argument("--no-overlap", action="store_true",
+                    help="Top-k: both message kernels on the caller's stream (tuning hook off; same results)")
     ap.add_argument("--fused-update", action="store_true",
                     help="server side as mlmc_aggregate_update: x <- x - eta * g~ inside the aggregate, g~ itself not written")
     ap.add_argument("--cpu-budget", type=float, default=25.0)
@@ -237,6 +239,8 @@ def main():
         msg = P.SparseMessage(plan, with_norms=w.adaptive)
         if args.no_staging:
             plan.set_staging(False)
+        if args.no_overlap:
+            plan.set_overlap(False)
     else:
         kind = {"bits": P.MLMC_BITS, "fbits": P.MLMC_FBITS, "vbits": P.MLMC_VBITS, "rtn": P.MLMC_RTN}[w.kind]
         plan = P.Plan(kind, w.M, w.d, P.MLMC_F32, w.ladder, None if w.adaptive else P.mlmc_geometric_p(w.L))

@@ -122,6 +122,16 @@ mlmc_status mlmc_plan_set_sampling(mlmc_plan_t *plan, int shift);
  */
 mlmc_status mlmc_plan_set_staging(mlmc_plan_t *plan, int enable);
 
+/*
+ * Tuning hook (MLMC_TOPK plans).  The message of Eq. (6) is written by two kernels that serve disjoint rows: one
+ * assembles it from what the selection read set aside, the other reads a row again.  With overlap on (the default for
+ * plans of 8 rows or more and 2^28 elements or more; the fork and the join cost more than they gain on smaller ones) the
+ * second runs on a stream the plan owns (default priority, created at the first call, destroyed with the plan), forked
+ * from and joined to `hip_stream` with events, so the caller's stream stays in order.
+ * Off: both run on `hip_stream`.  Run time only, never a result.
+ */
+mlmc_status mlmc_plan_set_overlap(mlmc_plan_t *plan, int enable);
+
 /* MLMC_TOPK plans: elements of a row that one workgroup of the selection read takes (a multiple of MLMC_TILE, at most
  * 2^18); 0 for other plans.  For tests and tuning: results never depend on it. */
 int64_t mlmc_plan_chunk(const mlmc_plan_t *plan);

@@ -24,7 +24,7 @@ MLMC_MAX_SLEVELS = 65536
 MLMC_TILE = 4096
 MLMC_MAX_LEVELS = 32
 
-EXPORTS = ["mlmc_plan", "mlmc_plan_destroy", "mlmc_plan_set_sampling", "mlmc_plan_set_staging", "mlmc_plan_num_tiles", "mlmc_plan_chunk", "mlmc_plan_num_planes", "mlmc_geometric_p",
+EXPORTS = ["mlmc_plan", "mlmc_plan_destroy", "mlmc_plan_set_sampling", "mlmc_plan_set_staging", "mlmc_plan_set_overlap", "mlmc_plan_num_tiles", "mlmc_plan_chunk", "mlmc_plan_num_planes", "mlmc_geometric_p",
            "mlmc_status_string", "mlmc_level_norms", "mlmc_compress_topk", "mlmc_compress_bits", "mlmc_compress_bits_static", "mlmc_compress_rtn", "mlmc_aggregate", "mlmc_aggregate_update", "mlmc_message_bits",
            "mlmc_profile_enable", "mlmc_profile_reset", "mlmc_profile_num_kernels", "mlmc_profile_kernel_name",
            "mlmc_profile_get"]
@@ -53,6 +53,8 @@ def lib():
         L.mlmc_plan_set_sampling.argtypes = [vp, i32]
         L.mlmc_plan_set_staging.restype = C.c_int
         L.mlmc_plan_set_staging.argtypes = [vp, i32]
+        L.mlmc_plan_set_overlap.restype = C.c_int
+        L.mlmc_plan_set_overlap.argtypes = [vp, i32]
         L.mlmc_plan_num_tiles.restype = i64
         L.mlmc_plan_num_tiles.argtypes = [vp]
         L.mlmc_plan_chunk.restype = i64
@@ -183,6 +185,11 @@ class Plan:
     def set_staging(self, enable: bool):
         """Stage the drawn band's members during the selection read (run time only, never results)."""
         _check(lib().mlmc_plan_set_staging(self.handle, int(bool(enable))), "mlmc_plan_set_staging")
+
+    def set_overlap(self, enable: bool):
+        """Run the second read of unstaged rows on the plan's side stream, beside the assembly of the other rows' messages
+        (run time only, never results)."""
+        _check(lib().mlmc_plan_set_overlap(self.handle, int(bool(enable))), "mlmc_plan_set_overlap")
 
     def status(self, informational: bool = False) -> int:
         """Device status bits of the last call (synchronises).  MLMC_DEV_REDONE is not an error and is only

@@ -84,6 +84,17 @@ __device__ __forceinline__ int32_t rtn_code_abs(double a, const RtnCode& k, doub
     if ((rem == c || rem == -c) && (ni & 1)) ni += rem > 0.0 ? 1 : -1;
     return ni < k.N ? ni : k.N;
 }
+// The same code as a double, the short way.  n = rint(a D / 2c) computed with the rounded reciprocal is the exact
+// round-to-nearest-even unless the exact quotient lies within 2^-37 of a half-integer; the remainder a D - n 2c, exact
+// in one fused multiply-add, tells: below c in magnitude, n is right (and, a being below c then, inside the code's
+// range); otherwise (a tie, a near tie, the largest entry itself, a non-finite c) the code is computed the long way.
+__device__ __forceinline__ double rtn_code_f64(double a, const RtnCode& k, double c, double den, double inv_den) {
+    const double num = __dmul_rn(a, k.D);
+    double n = rint(__dmul_rn(num, inv_den));
+    const double rem = __fma_rn(-n, den, num);
+    if (__builtin_expect(!(fabs(rem) < c), 0)) n = (double)rtn_code_abs(a, k, c, den, inv_den);
+    return n;
+}
 __device__ __forceinline__ RtnCode rtn_code_of(int b) {
     RtnCode k;
     k.b = b;
@@ -147,7 +158,7 @@ __device__ __forceinline__ void bits_extract_tiles(const BitsArgs& a, int row, i
             for (int q = 0; q < 3; ++q) {
                 const RtnCode kq = rr->code[q];
                 if (kq.b > 0) {   // uniform
-                    int32_t n = rr->c > 0.0 ? rtn_code_abs(av, kq, rr->c, rr->den, rr->inv_den) : 0;
+                    int32_t n = rr->c > 0.0 ? (int32_t)rtn_code_f64(av, kq, rr->c, rr->den, rr->inv_den) : 0;
                     n = (int32_t)bits < 0 ? -n : n;
                     x |= ((uint32_t)n & ((1u << kq.b) - 1u)) << at;
                     at += (uint32_t)kq.b;

@@ -25,9 +25,13 @@ constexpr int CHUNK_MAX = 1 << 18;      // elements per workgroup chunk of the s
 constexpr int CHUNKS_MAX = 8192;        // chunks per row
 constexpr int FH_BINS = 2048;           // bins of the zone-relative key histogram of the finish kernels
 constexpr int COLLECT_CAP = 2048;       // candidates of the thresholds' bins that are ranked in LDS
-constexpr int FIN_SLICES = 16;          // a zone's candidate list is worked on in up to this many slices ...
-constexpr int FIN_SLICE = 32768;        // ... of at least this many candidates
-constexpr int FIN_WGS = 32;             // workgroups per row that take the (zone, slice) items in turn
+// The zone passes: FIN_WGS workgroups per row take (zone, slice) items in turn, a zone's candidate list being cut into up
+// to FIN_SLICES slices of at least FIN_SLICE candidates.  These are the figures for 16 rows or more (512 workgroups in
+// all); with fewer rows there are more workgroups per row, up to FIN_WGS_MAX, and as many more, smaller slices.
+constexpr int FIN_SLICES = 16;
+constexpr int FIN_SLICE = 32768;
+constexpr int FIN_WGS = 32;
+constexpr int FIN_WGS_MAX = 128;
 // Slot of a part of a zone in the per-chunk table of zone entries: the part inside the top k_t but outside the
 // top k of the zone's previous threshold has slot t; the part below every threshold of zone z has slot TMAX + z.
 constexpr int ZPMAX = 2 * TMAX;
@@ -103,6 +107,7 @@ struct TopkArgs {
     const void* g;
     int64_t ld, d;
     int32_t M, L;
+    int32_t dtype;           // MLMC_F32 / MLMC_BF16 (the kernels that stream rows are compiled per type; this is for the few loads elsewhere)
     int64_t k[TMAX];
     int32_t all_thresholds;  // 1: every ladder threshold + band sums (adaptive); 0: thresholds 0, l-1, l only
     int32_t chunk;           // elements per workgroup chunk (multiple of TILE, <= CHUNK_MAX)
@@ -112,6 +117,7 @@ struct TopkArgs {
     int32_t cchunks_per_row;
     int32_t sample_shift;    // the first histogram reads one 1024-element block out of 2^sample_shift
     int32_t staging;         // 1: the selection read stages the members of the (predicted) drawn band
+    int32_t fin_wgs, fin_slice, fin_slices;   // zone passes: workgroups per row, least candidates per slice, most slices per zone
     int64_t ntiles;
     uint32_t* hist;          // [M][NB1] histogram of the sampled blocks
     uint32_t* hist2;         // [M][NB1] full histogram of the rows that are redone exactly
@@ -192,6 +198,8 @@ struct StopkArgs {
     uint32_t* counts;        // [M][256][nblk] digit counts / offsets of a sort pass
     uint32_t* bin_total;     // [M][256] elements of every digit bin
     uint32_t* bitmap;        // [M][bm_words] entries of the drawn segment
+    uint32_t* tile_cnt;      // [M][ntiles] entries of the drawn segment per tile of 4096 indices (right behind the bitmaps: cleared with them)
+    size_t clear_bytes;      // bitmaps + tile counts, a multiple of 16
     uint32_t* tile_off;      // [M][ntiles + 1]
     double* norms;           // [M][L]
     double* norms_user;
@@ -247,6 +255,14 @@ struct mlmc_plan_s {
     int64_t s;
     int nblk;
     int64_t bm_words;
-    size_t off_pa, off_pb, off_counts, off_bitmap, off_srow, off_bintot;
+    size_t off_pa, off_pb, off_counts, off_bitmap, off_tilecnt, off_clear_end, off_srow, off_bintot;
     size_t off_rtn_sums;   // Round-to-Nearest plans
+    // Side stream of the message step (MLMC_TOPK): the second read of the rows whose band was not staged runs beside the
+    // assembly of the other rows' messages from the staged lists.  Created at the first call that uses it, on the device
+    // current then; default priority.  Host objects only; destroyed with the plan.
+    mutable hipStream_t side_stream;
+    mutable hipEvent_t side_fork, side_join;
+    mutable int side_device;      // device the three objects belong to
+    mutable int side_state;       // 0: not created yet, 1: ready, -1: could not be created (the step then runs on one stream)
+    int side_enable;              // mlmc_plan_set_overlap
 };

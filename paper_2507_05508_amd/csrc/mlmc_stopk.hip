@@ -206,13 +206,16 @@ __global__ __launch_bounds__(SN_WAVES * 64) void k_sb_norms(StopkArgs a, const u
     }
 }
 
-// Level draw of every row (Alg. 3): p_l = Delta_l / (Delta_1 + ... + Delta_L), the sum and the running CDF taken in
-// level order by one thread (the order fixes the roundings); the norms pass through LDS in chunks.
+// Level draw of every row (Alg. 3): p_l = Delta_l / (Delta_1 + ... + Delta_L).  The sum and the running CDF are taken in
+// level order by one thread (the order fixes the roundings) - but only the additions: the quotients before them and the
+// integer thresholds and comparisons after them are independent per level and spread over the workgroup.  The norms
+// pass through LDS in chunks.
 constexpr int SD_CHUNK = 8192;
 __global__ __launch_bounds__(1024) void k_sb_draw(StopkArgs a) {
-    __shared__ double s_n[SD_CHUNK];
+    __shared__ double s_n[SD_CHUNK];     // norms, then probabilities, of the chunk
+    __shared__ double s_cdf[SD_CHUNK];   // running sums of the probabilities up to every level of the chunk
     __shared__ double s_tot;
-    __shared__ int32_t s_found;
+    __shared__ int32_t s_found;          // lowest level met so far whose threshold lies above the drawn word
     const int row = blockIdx.x, tid = threadIdx.x;
     const double* nr = a.norms + (size_t)row * a.L;
     const int L = a.L;
@@ -224,32 +227,40 @@ __global__ __launch_bounds__(1024) void k_sb_draw(StopkArgs a) {
         __syncthreads();
         if (tid == 0) for (int i = 0; i < n; ++i) tot = __dadd_rn(tot, s_n[i]);
     }
-    if (tid == 0) { s_tot = tot; s_found = 0; }
+    if (tid == 0) { s_tot = tot; s_found = 0x7FFFFFFF; }
     __syncthreads();
     tot = s_tot;
     const uint32_t x = philox_word0(a.seed, a.step, (uint32_t)row);
     const double uni = __ddiv_rn(1.0, (double)L);
     double c = 0.0, pl = 0.0;
     int level = L;
-    for (int c0 = 0; c0 < L && !s_found; c0 += SD_CHUNK) {
+    for (int c0 = 0; c0 < L; c0 += SD_CHUNK) {
         const int n = L - c0 < SD_CHUNK ? L - c0 : SD_CHUNK;
         __syncthreads();
-        for (int i = tid; i < n; i += 1024) s_n[i] = nr[c0 + i];
+        for (int i = tid; i < n; i += 1024) s_n[i] = tot == 0.0 ? uni : __ddiv_rn(nr[c0 + i], tot);
         __syncthreads();
         if (tid == 0) {
             for (int i = 0; i < n; ++i) {
-                const double p = tot == 0.0 ? uni : __ddiv_rn(s_n[i], tot);
-                c = __dadd_rn(c, p);
-                const double t = floor(__dmul_rn(c, 4294967296.0));
-                uint64_t T;
-                if (!(t > 0.0)) T = 0;
-                else if (t >= 4294967296.0) T = 4294967296ull;
-                else T = (uint64_t)t;
-                if (c0 + i == L - 1) T = 4294967296ull;
-                if ((uint64_t)x < T) { level = c0 + i + 1; pl = p; s_found = 1; break; }
+                c = __dadd_rn(c, s_n[i]);
+                s_cdf[i] = c;
             }
         }
         __syncthreads();
+        for (int i = tid; i < n; i += 1024) {
+            const double t = floor(__dmul_rn(s_cdf[i], 4294967296.0));
+            uint64_t T;
+            if (!(t > 0.0)) T = 0;
+            else if (t >= 4294967296.0) T = 4294967296ull;
+            else T = (uint64_t)t;
+            if (c0 + i == L - 1) T = 4294967296ull;
+            if ((uint64_t)x < T) atomicMin(&s_found, c0 + i + 1);
+        }
+        __syncthreads();
+        if (s_found != 0x7FFFFFFF) {   // uniform: the chunk holds the level, and s_n its probability
+            level = s_found;
+            pl = s_n[level - 1 - c0];
+            break;
+        }
     }
     if (tid == 0) {
         SRow* sr = a.srow + row;
@@ -268,7 +279,8 @@ __global__ __launch_bounds__(256) void k_sb_clear(uint4* p, size_t n16, int32_t*
     if (dev_status && blockIdx.x == 0 && threadIdx.x == 0) *dev_status = 0;
 }
 
-// The entries of the drawn segment, marked in the row's bitmap (bit j of the row: entry j is in the message).
+// The entries of the drawn segment, marked in the row's bitmap (bit j of the row: entry j is in the message) and counted
+// per tile of 4096 indices.
 __global__ __launch_bounds__(256) void k_sb_mark(StopkArgs a, const uint2* sorted) {
     const int row = blockIdx.y;
     const SRow sr = a.srow[row];
@@ -276,6 +288,7 @@ __global__ __launch_bounds__(256) void k_sb_mark(StopkArgs a, const uint2* sorte
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < sr.count; i += (int64_t)gridDim.x * 256) {
         const uint32_t j = sorted[(size_t)row * a.d + sr.lo + i].y;
         atomicOr(&bm[j >> 5], 1u << (j & 31u));
+        atomicAdd(&a.tile_cnt[(size_t)row * a.ntiles + (j >> 12)], 1u);   // indices are distinct: an entry counts once
     }
 }
 
@@ -283,29 +296,12 @@ __global__ __launch_bounds__(256) void k_sb_mark(StopkArgs a, const uint2* sorte
 __global__ __launch_bounds__(1024) void k_sb_offsets(StopkArgs a) {
     __shared__ uint32_t s_scan[1024 / 64 + 1];
     const int row = blockIdx.x, tid = threadIdx.x;
-    const uint32_t* bm = a.bitmap + (size_t)row * a.bm_words;
     uint32_t* to = a.tile_off + (size_t)row * (a.ntiles + 1);
-    // a thread counts one tile at a time (its 128 bitmap words with loads issued together), 1024 tiles per round
+    const uint32_t* tc = a.tile_cnt + (size_t)row * a.ntiles;
     uint32_t carry = 0;
     for (int64_t j0 = 0; j0 < a.ntiles; j0 += 1024) {
         const int64_t t = j0 + tid;
-        uint32_t c = 0;
-        if (t < a.ntiles) {
-            const int64_t wbase = t * (TILE / 32);
-            if (wbase + TILE / 32 <= a.bm_words && (a.bm_words % 4) == 0) {
-                const uint4* p4 = (const uint4*)(bm + wbase);
-                uint4 v[8];
-                for (int q0 = 0; q0 < TILE / 128; q0 += 8) {
-#pragma unroll
-                    for (int q = 0; q < 8; ++q) v[q] = p4[q0 + q];
-#pragma unroll
-                    for (int q = 0; q < 8; ++q) c += (uint32_t)(__popc(v[q].x) + __popc(v[q].y) + __popc(v[q].z) + __popc(v[q].w));
-                }
-            } else {
-                for (int w = 0; w < TILE / 32; ++w)
-                    if (wbase + w < a.bm_words) c += (uint32_t)__popc(bm[wbase + w]);
-            }
-        }
+        const uint32_t c = t < a.ntiles ? tc[t] : 0u;
         uint32_t round_total;
         const uint32_t ex = block_excl_scan<1024>(c, s_scan, round_total);
         if (t < a.ntiles) to[t] = carry + ex;
@@ -367,9 +363,9 @@ __global__ __launch_bounds__(256) void k_sb_write(StopkArgs a) {
 template <int DT>
 static mlmc_status launch_stopk(const mlmc_plan_t* pl, const StopkArgs& a, bool message, hipStream_t st) {
     const dim3 sgrid(a.nblk, pl->M);
-    // bitmap and device status start at zero
+    // bitmaps, tile counts and device status start at zero
     {
-        const size_t n16 = ((size_t)pl->M * a.bm_words * 4 + 15) / 16;
+        const size_t n16 = a.clear_bytes / 16;   // the bitmaps and, right behind them, the tile counts
         int blocks = (int)((n16 + 255) / 256);
         if (blocks > 2048) blocks = 2048;
         MLMC_LAUNCH(K_ZERO, st, k_sb_clear<<<blocks, 256, 0, st>>>((uint4*)a.bitmap, n16, a.dev_status));

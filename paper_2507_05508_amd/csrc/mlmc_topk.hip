@@ -714,10 +714,10 @@ __device__ __forceinline__ void wave_rank_search(const uint32_t* h, uint32_t r, 
 
 constexpr int ZC_CAP = 8192;         // (parts of the zone) x (chunks of the row) counters
 
-// A zone's candidate list is split over up to FIN_SLICES workgroups.
-__device__ __forceinline__ int finish_slices(uint32_t n) {
-    const uint32_t s = (n + (uint32_t)FIN_SLICE - 1u) / (uint32_t)FIN_SLICE;
-    return s < 1u ? 1 : (s > (uint32_t)FIN_SLICES ? FIN_SLICES : (int)s);
+// A zone's candidate list is split over up to a.fin_slices workgroups, a.fin_slice candidates or more each.
+__device__ __forceinline__ int finish_slices(const TopkArgs& a, uint32_t n) {
+    const uint32_t s = (n + (uint32_t)a.fin_slice - 1u) / (uint32_t)a.fin_slice;
+    return s < 1u ? 1 : (s > (uint32_t)a.fin_slices ? a.fin_slices : (int)s);
 }
 // Key range of a zone: its buckets, cut at the largest key of the row (the top zone of a small sample reaches up to
 // the highest bucket, which would otherwise stretch the zone over every exponent above the data).
@@ -735,7 +735,7 @@ __device__ __forceinline__ int finish_shift(uint32_t kmin, uint32_t kmax) {
 
 // The work of the finish kernels is a list of items (zone, slice) per row; the workgroups of a row take them in
 // turn.  Fills s_fill / s_rcnt (zone list lengths, region counts) and s_first (first item of every zone).
-__device__ __forceinline__ int finish_items(const RowInfo* ri, const RowAcc* ra, bool sliced, uint32_t* s_fill,
+__device__ __forceinline__ int finish_items(const TopkArgs& a, const RowInfo* ri, const RowAcc* ra, bool sliced, uint32_t* s_fill,
                                             uint32_t* s_rcnt, int32_t* s_first) {
     const int tid = threadIdx.x, nz = ri->n_zones;
     if (tid < nz) s_fill[tid] = ra->zone_fill[tid];
@@ -745,7 +745,7 @@ __device__ __forceinline__ int finish_items(const RowInfo* ri, const RowAcc* ra,
         int run = 0;
         for (int z = 0; z < nz; ++z) {
             s_first[z] = run;
-            run += sliced ? finish_slices(s_fill[z]) : 1;
+            run += sliced ? finish_slices(a, s_fill[z]) : 1;
         }
         s_first[nz] = run;
     }
@@ -765,9 +765,11 @@ __device__ __forceinline__ void count_greater2(const unsigned long long* v, uint
     const uint32_t n2 = n >> 1;
     if (t >= n) return;   // waves past the end of the list do not load the LDS pipe
     if (n <= (uint32_t)FN_THREADS) {   // uniform: one value per thread
+#pragma unroll 8
         for (uint32_t f = 0; f < n; ++f) r0 += v[f] > c0 ? 1u : 0u;
         return;
     }
+#pragma unroll 8
     for (uint32_t f = 0; f < n2; ++f) {
         const ulonglong2 x = v2[f];
         r0 += (x.x > c0 ? 1u : 0u) + (x.y > c0 ? 1u : 0u);
@@ -778,6 +780,29 @@ __device__ __forceinline__ void count_greater2(const unsigned long long* v, uint
         r0 += x > c0 ? 1u : 0u;
         r1 += x > c1 ? 1u : 0u;
     }
+}
+
+// Bitonic sort in LDS, descending, of n values (n a power of two, at most 2 * FN_THREADS) by a whole workgroup: a thread
+// takes one compare-exchange per stage.  (Ranking by counting costs n broadcast reads per thread, which the LDS serves no
+// faster than distinct ones: at 2048 values it took ten times as long.)
+__device__ __forceinline__ void bitonic_sort_desc(unsigned long long* v, uint32_t n, uint32_t t) {
+    __syncthreads();   // the values were written by other waves
+    for (uint32_t k = 2; k <= n; k <<= 1) {
+        for (uint32_t j = k >> 1; j > 0; j >>= 1) {
+            // With a stride below 64 the pairs of a wave's 64 threads lie inside the wave's own 128 values: such a stage
+            // needs the other waves only if the stage before it had a longer stride.
+            if (j >= 64u || (j == 32u && k >= 128u)) __syncthreads();
+            else wave_lds_sync();
+            if (t < (n >> 1)) {
+                const uint32_t i = ((t & ~(j - 1u)) << 1) | (t & (j - 1u));   // bit j clear
+                const uint32_t l = i | j;
+                const unsigned long long x = v[i], y = v[l];
+                const bool desc = (i & k) == 0u;
+                if ((x < y) == desc) { v[i] = y; v[l] = x; }
+            }
+        }
+    }
+    __syncthreads();
 }
 
 // Read 1 of a candidate list, one item per (zone, slice): histogram of (key - kmin) >> shift.
@@ -793,7 +818,7 @@ __global__ __launch_bounds__(FN_THREADS) void k_fhist(TopkArgs a, int exact_pass
     if (exact_pass && !ri->respec) return;
     if (!exact_pass && ri->respec) return;
     const int nz = ri->n_zones;
-    const int nitems = finish_items(ri, ra, true, s_fill, s_rcnt, s_first);
+    const int nitems = finish_items(a, ri, ra, true, s_fill, s_rcnt, s_first);
     for (int item = blockIdx.x; item < nitems; item += gridDim.x) {
         int z = 0;
         while (z + 1 < nz && s_first[z + 1] <= item) ++z;
@@ -804,7 +829,7 @@ __global__ __launch_bounds__(FN_THREADS) void k_fhist(TopkArgs a, int exact_pass
         }
         const uint32_t n = s_fill[z];
         if (n == 0 || n > ri->zone_cap[z]) continue;   // the finish kernel reports it
-        const int S = finish_slices(n);
+        const int S = finish_slices(a, n);
         uint32_t kmin, kmax;
         zone_key_range(ri, ra, z, kmin, kmax);
         if (kmin > kmax) continue;
@@ -871,11 +896,11 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
         if (fail_bit) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
         else atomicOr((int32_t*)&ri->respec, 1);
     };
-    const int nitems = finish_items(ri, ra, PHASE == 0, s_fill, s_rcnt, s_first);
+    const int nitems = finish_items(a, ri, ra, PHASE == 0, s_fill, s_rcnt, s_first);
 
     auto run_item = [&](const int z, const int slice) {
     const uint32_t n = s_fill[z];
-    const int S = finish_slices(n);
+    const int S = finish_slices(a, n);
     const uint2* kl = a.cand + (size_t)row * (size_t)a.d + ri->zone_off[z];   // {bits, index}
 
     if (tid == 0) {
@@ -1071,6 +1096,7 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
             uint32_t* s_ih = s_un;   // FH_BINS words: free on this path
             int ish = 0;
             while (((uint32_t)(a.d - 1) >> ish) >= (uint32_t)FH_BINS) ++ish;
+            const bool chunk_bins = nchunks <= FH_BINS;   // the bins are the row's count chunks when there are few enough
             for (int i = tid; i < FH_BINS; i += FN_THREADS) s_ih[i] = 0;
             if (tid == 0) { s_q[0] = 0u; s_eq[0] = 0u; }   // largest ~key, largest key
             __syncthreads();
@@ -1088,7 +1114,7 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
                     if (col) {
                         const uint32_t pos = base + mbcnt(m);
                         if (pos < zcap) c2l[pos] = e;
-                        atomicAdd(&s_ih[e.y >> ish], 1u);
+                        atomicAdd(&s_ih[chunk_bins ? chunk_of(e.y) : e.y >> ish], 1u);
                         kmx = key > kmx ? key : kmx;
                         kmn_inv = ~key > kmn_inv ? ~key : kmn_inv;
                     }
@@ -1151,14 +1177,18 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
             return;
         }
         __syncthreads();
-        // descending order of (key, lower index first) by counting: composites are distinct
-        {
+        // descending order of (key, lower index first): composites are distinct and non-zero, zeros pad the end
+        if (ncol <= 256u) {   // few: ranking by counting (a thread per value, every thread walks the list) is quicker than sorting
             uint32_t r0, r1;
             count_greater2(s_col, ncol, (uint32_t)tid, r0, r1);
             if ((uint32_t)tid < ncol) s_srt[r0] = s_col[tid];
-            if ((uint32_t)tid + FN_THREADS < ncol) s_srt[r1] = s_col[tid + FN_THREADS];
+            __syncthreads();
+        } else {
+            uint32_t np2 = 512;
+            while (np2 < ncol) np2 <<= 1;   // <= COLLECT_CAP = 2 * FN_THREADS
+            for (uint32_t e = tid; e < np2; e += FN_THREADS) s_srt[e] = e < ncol ? s_col[e] : 0ull;
+            bitonic_sort_desc(s_srt, np2, (uint32_t)tid);
         }
-        __syncthreads();
         if (tid < nthr) {
             const unsigned long long c = s_srt[s_pos[tid]];
             s_tau[tid] = (uint32_t)(c >> 32);
@@ -1192,6 +1222,12 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
         // the threshold, only the index cut is left: histogram of the indices, then the one bin ranked in LDS.
         if (tid == 0) { s_any = 0; s_nsub = 0; }
         __syncthreads();
+        // Bins of the index histogram that the sliced launch made: the row's count chunks when they are few enough.  Then
+        // the overflow list is not read here at all: the chunk that holds the index cut is read from the row itself
+        // (its entries equal to the key, in index order), and every other chunk lies wholly on one side of the cut.
+        const bool chunk_bins = nchunks <= FH_BINS;
+        bool single_key = false;
+        uint32_t cut_chunk = (uint32_t)nchunks, cut_inside = 0;   // count chunk of the cut, entries of it inside the top k
         if (par_big && nthr == 1) {
             // key range and index histogram of the overflow list: made by the sliced launch while it copied
             const uint32_t* zi = (const uint32_t*)zcol;
@@ -1202,6 +1238,7 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
             __syncthreads();
             const uint32_t key1 = s_q[0];
             const bool single = key1 == s_eq[0];
+            single_key = single;
             __syncthreads();
             if (single) {
                 const uint32_t q = s_res[0];   // the threshold is the q-th entry of the list by ascending index
@@ -1213,7 +1250,75 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
                         if (lane == 0) { s_bin[0] = (uint32_t)bin; s_rin[0] = rin; s_bcnt[0] = cnt; }
                     }
                     __syncthreads();
-                    if (s_bcnt[0] <= (uint32_t)COLLECT_CAP && s_bcnt[0] > 0) {
+                    if (chunk_bins) {
+                        const uint32_t cnt = s_bcnt[0], rin = s_rin[0];
+                        const uint32_t target = cnt - rin + 1u;   // the cut is the target-th of the chunk's entries equal to the key, by index
+                        cut_chunk = s_bin[0];
+                        cut_inside = target;
+                        const int64_t e0 = (int64_t)cut_chunk * a.cchunk;
+                        const int64_t e1 = e0 + a.cchunk < a.d ? e0 + a.cchunk : a.d;
+                        // wave w takes a run of whole 64-element groups of the chunk, in order
+                        const int64_t per = ((e1 - e0 + FN_THREADS - 1) / FN_THREADS) * 64;
+                        const int64_t w0 = e0 + (int64_t)wave * per, w1 = w0 + per < e1 ? w0 + per : e1;
+                        // sixteen groups at a time, their loads issued together (a load per group in turn would cost a
+                        // memory latency per 64 elements); a lane past the end of the wave's run reads the run's last element
+                        // (the element type is a compile-time tag: a run-time test inside the loop would split the loads up again)
+                        auto equal_masks = [&](auto is_bf16, int64_t j0, uint64_t (&m)[16]) {
+                            constexpr bool BF = decltype(is_bf16)::value;
+                            uint32_t v[16];
+#pragma unroll
+                            for (int u = 0; u < 16; ++u) {
+                                const int64_t j = j0 + u * 64 + lane;
+                                const int64_t jc = (int64_t)row * a.ld + (j < w1 ? j : w1 - 1);
+                                if (BF) v[u] = (uint32_t)((const uint16_t*)a.g)[jc] << 16;
+                                else v[u] = ((const uint32_t*)a.g)[jc];
+                            }
+#pragma unroll
+                            for (int u = 0; u < 16; ++u) m[u] = __ballot(j0 + u * 64 + lane < w1 && key_of_bits(v[u]) == key1);
+                        };
+                        auto scan_chunk = [&](auto is_bf16) {
+                        uint32_t mine = 0;
+                        for (int64_t j0 = w0; j0 < w1; j0 += 1024) {
+                            uint64_t m[16];
+                            equal_masks(is_bf16, j0, m);
+#pragma unroll
+                            for (int u = 0; u < 16; ++u) mine += (uint32_t)__popcll(m[u]);
+                        }
+                        if (lane == 0) s_subpfx[wave] = mine;
+                        __syncthreads();
+                        uint32_t before = 0, total = 0;
+                        for (uint32_t w2 = 0; w2 < (uint32_t)(FN_THREADS / 64); ++w2) {
+                            const uint32_t v = s_subpfx[w2];
+                            before += w2 < wave ? v : 0u;
+                            total += v;
+                        }
+                        // total != cnt cannot happen (every entry equal to the key is in the overflow list); if it did the
+                        // zone would be resolved the long way below
+                        if (total == cnt && rin >= 1u && rin <= cnt && before < target && target <= before + mine) {
+                            uint32_t run = before;
+                            bool found = false;
+                            for (int64_t j0 = w0; j0 < w1 && !found; j0 += 1024) {
+                                uint64_t m[16];
+                                equal_masks(is_bf16, j0, m);
+#pragma unroll
+                                for (int u = 0; u < 16; ++u) {
+                                    const uint32_t c = (uint32_t)__popcll(m[u]);
+                                    if (!found && run + c >= target) {
+                                        if (((m[u] >> lane) & 1ull) && run + mbcnt(m[u]) + 1u == target) {
+                                            s_tau[0] = key1;
+                                            s_jx[0] = (uint32_t)(j0 + u * 64 + lane) + 1u;
+                                            s_any = 1;
+                                        }
+                                        found = true;
+                                    }
+                                    run += c;
+                                }
+                            }
+                        }
+                        };   // scan_chunk
+                        if (a.dtype == MLMC_BF16) scan_chunk(std::true_type{});
+                        else scan_chunk(std::false_type{});
+                    } else if (s_bcnt[0] <= (uint32_t)COLLECT_CAP && s_bcnt[0] > 0) {
                         const uint32_t ibin = s_bin[0];
                         batched_loop<16, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return xl[i].y; }, [&](uint32_t, uint32_t j) {
                             if ((j >> ish) == ibin) {
@@ -1345,7 +1450,28 @@ __global__ __launch_bounds__(FN_THREADS, PHASE == 0 ? 8 : 4) void k_finish(TopkA
             }
         }
         // every candidate's part from the exact thresholds
-        if (count_fits || SUMS) {
+        if (resolved && single_key && chunk_bins) {
+            // one key, bins = count chunks: the histogram says how many entries every chunk has, the cut says which side
+            // they are on; their squares are all the same
+            const uint32_t key1 = s_tau[0];
+            const uint32_t inside_all = s_res[0] < xn ? s_res[0] : xn;   // entries of the list inside the top k
+            for (int c = tid; c < nchunks; c += FN_THREADS) {
+                const uint32_t h = s_fh[c];
+                const uint32_t p0 = (uint32_t)c < cut_chunk ? h : (uint32_t)c > cut_chunk ? 0u : cut_inside;
+                if (p0) atomicAdd(&zc[(size_t)slot_of(0) * nchunks + c], p0);
+                if (h - p0) atomicAdd(&zc[(size_t)slot_of(1) * nchunks + c], h - p0);
+            }
+            if (SUMS && tid < 2) {
+                const unsigned long long cntp = tid == 0 ? inside_all : xn - inside_all;
+                const int E = (int)(key1 >> 23) ? (int)(key1 >> 23) : 1;
+                const int cls = tid * span + (E - Elo);
+                const unsigned long long sq = sig_square(key1);
+                if (cntp) {
+                    atomicAdd(&zp[cls * 2], (sq & 0xFFFFFFFFull) * cntp);
+                    atomicAdd(&zp[cls * 2 + 1], (sq >> 32) * cntp);
+                }
+            }
+        } else if (count_fits || SUMS) {
             batched_loop<8, FN_THREADS>(0u, xn, (uint32_t)tid, [&](uint32_t i) { return xl[i]; },
                                         [&](uint32_t, uint2 e) {
                 const uint32_t key = key_of_bits(e.x), j = e.y;
@@ -1904,7 +2030,7 @@ __global__ __launch_bounds__(FL_THREADS) void k_filter(TopkArgs a) {
 // host-side launchers
 template <int DT, bool VEC>
 static mlmc_status launch_select(const mlmc_plan_t* pl, const TopkArgs& a, bool sums, hipStream_t st) {
-    const dim3 fgrid(FIN_WGS, pl->M);
+    const dim3 fgrid(a.fin_wgs, pl->M);
     const int rounds = pl->sample_shift > 0 ? 2 : 1;   // second round: rows whose sampled zones were refuted
     for (int exact_pass = 0; exact_pass < rounds; ++exact_pass) {
         // histogram workgroups per row: enough to spread the row, few enough that the 64 KB flushes stay cheap
@@ -1946,6 +2072,21 @@ static mlmc_status launch_select(const mlmc_plan_t* pl, const TopkArgs& a, bool 
     return MLMC_OK;
 }
 
+// The plan's side stream and its two events, created on first use (one plan is used from one host thread at a time).
+static bool side_stream_ready(const mlmc_plan_t* pl) {
+    if (!pl->side_enable || pl->side_state < 0) return false;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return false;
+    if (pl->side_state == 1) return dev == pl->side_device;   // a call on another device runs on one stream
+    pl->side_state = -1;
+    if (hipStreamCreateWithFlags(&pl->side_stream, hipStreamNonBlocking) != hipSuccess) { pl->side_stream = nullptr; return false; }
+    if (hipEventCreateWithFlags(&pl->side_fork, hipEventDisableTiming) != hipSuccess) { pl->side_fork = nullptr; return false; }
+    if (hipEventCreateWithFlags(&pl->side_join, hipEventDisableTiming) != hipSuccess) { pl->side_join = nullptr; return false; }
+    pl->side_device = dev;
+    pl->side_state = 1;
+    return true;
+}
+
 template <int DT, bool VEC>
 static mlmc_status launch_compact(const mlmc_plan_t* pl, const TopkArgs& a, hipStream_t st) {
     const dim3 grid(pl->chunks_per_row, pl->M), wgrid(pl->cchunks_per_row, pl->M);
@@ -1957,8 +2098,23 @@ static mlmc_status launch_compact(const mlmc_plan_t* pl, const TopkArgs& a, hipS
     if (fl_lds > 48 * 1024 &&
         hipFuncSetAttribute((const void*)k_filter, hipFuncAttributeMaxDynamicSharedMemorySize, (int)fl_lds) != hipSuccess)
         return MLMC_EHIP;
+    // The two message kernels serve disjoint sets of rows and write disjoint parts of the message, and neither fills
+    // the machine for its whole run (the second read has the workgroups of one or two rows, the assembly is bound by
+    // latency): the second read goes to the plan's side stream, forked from and joined to the caller's stream with
+    // events, so the caller still sees one in-order stream.
+    hipStream_t sw = st;
+    const bool fork = pl->M > 1 && side_stream_ready(pl);
+    if (fork) {
+        if (hipEventRecord(pl->side_fork, st) != hipSuccess || hipStreamWaitEvent(pl->side_stream, pl->side_fork, 0) != hipSuccess)
+            return MLMC_EHIP;
+        sw = pl->side_stream;
+    }
+    MLMC_LAUNCH(K_WRITE, sw, k_write<DT, VEC><<<wgrid, WR_THREADS, 0, sw>>>(a));
     MLMC_LAUNCH(K_FILTER, st, k_filter<<<grid, FL_THREADS, fl_lds, st>>>(a));
-    MLMC_LAUNCH(K_WRITE, st, k_write<DT, VEC><<<wgrid, WR_THREADS, 0, st>>>(a));
+    if (fork) {
+        if (hipEventRecord(pl->side_join, sw) != hipSuccess || hipStreamWaitEvent(st, pl->side_join, 0) != hipSuccess)
+            return MLMC_EHIP;
+    }
     return MLMC_OK;
 }
 

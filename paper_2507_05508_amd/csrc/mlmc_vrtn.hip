@@ -45,29 +45,29 @@ __global__ __launch_bounds__(256) void k_rtn_norms(BitsArgs a) {
     const double c = key_to_double(ckey), den = 2.0 * c, inv_den = __ddiv_rn(1.0, den);
     RowLoader<DT, VEC> ld(a.g, a.ld, a.d, row);
     const int L = a.L;
+    // Everything below is fp64 arithmetic on integers that fp64 holds exactly: |g| D has 40 bits, a code 16, a residual
+    // integer k fewer than 18, k^2 fewer than 36, and a thread adds far fewer than 2^17 of them per level.
     RtnCode code[RTN_LMAX + 1];
-    double Dprev[RTN_LMAX + 1];   // D' of level l (1 when the previous width is 0)
+    double Dcur[RTN_LMAX + 1], Dprev[RTN_LMAX + 1];   // D of level t; D' of level t (1 when the previous width is 0)
 #pragma unroll
     for (int t = 0; t <= RTN_LMAX; ++t) {
         code[t] = rtn_code_of(t <= L ? a.F[t] : 0);
+        Dcur[t] = code[t].D;
         Dprev[t] = t >= 1 && t <= L && a.F[t - 1] > 0 ? (double)((1 << a.F[t - 1]) - 1) : 1.0;
     }
-    unsigned long long acc[RTN_LMAX];
-    int32_t Dpi[RTN_LMAX + 1], Di[RTN_LMAX + 1];
+    double acc[RTN_LMAX];
 #pragma unroll
-    for (int l = 0; l < RTN_LMAX; ++l) acc[l] = 0ull;
-#pragma unroll
-    for (int t = 0; t <= RTN_LMAX; ++t) { Dpi[t] = (int32_t)Dprev[t]; Di[t] = (int32_t)code[t].D; }
+    for (int l = 0; l < RTN_LMAX; ++l) acc[l] = 0.0;
+    auto code_of = [&](double av, int t) -> double { return rtn_code_f64(av, code[t], c, den, inv_den); };
     auto one = [&](uint32_t bits) {
         const double av = key_to_double(key_of_bits(bits));
-        int32_t nprev = code[0].b > 0 ? rtn_code_abs(av, code[0], c, den, inv_den) : 0;
+        double nprev = code[0].b > 0 ? code_of(av, 0) : 0.0;
 #pragma unroll
         for (int l = 1; l <= RTN_LMAX; ++l) {
             if (l <= L) {   // uniform
-                const int32_t ncur = rtn_code_abs(av, code[l], c, den, inv_den);
-                const int32_t k = ncur * Dpi[l] - nprev * Di[l];   // |k| < 2^18
-                const uint32_t ka = (uint32_t)(k < 0 ? -k : k);
-                acc[l - 1] += (unsigned long long)ka * (unsigned long long)ka;
+                const double ncur = code_of(av, l);
+                const double k = __fma_rn(ncur, Dprev[l], -__dmul_rn(nprev, Dcur[l]));
+                acc[l - 1] = __fma_rn(k, k, acc[l - 1]);
                 nprev = ncur;
             }
         }
@@ -91,16 +91,26 @@ __global__ __launch_bounds__(256) void k_rtn_norms(BitsArgs a) {
         for (int u = 0; u < 4; ++u)
             if (u < nv) one(b[u]);
     }
+    // One pair of global atomics per workgroup and level (atomics of many waves on one address take turns): the waves'
+    // sums meet in LDS first.
+    __shared__ unsigned long long s_part[4][RTN_LMAX];
+    const uint32_t wave = threadIdx.x >> 6;
 #pragma unroll
     for (int l = 0; l < RTN_LMAX; ++l) {
         if (l < L) {
-            unsigned long long v = acc[l];
+            unsigned long long v = (unsigned long long)acc[l];
 #pragma unroll
             for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
-            if (lane_id() == 0 && v) {
-                atomicAdd(&a.rtn_sums[((size_t)row * L + l) * 2], v & 0xFFFFFFFFull);
-                atomicAdd(&a.rtn_sums[((size_t)row * L + l) * 2 + 1], v >> 32);
-            }
+            if (lane_id() == 0) s_part[wave][l] = v;
+        }
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < L) {
+        const int l = threadIdx.x;
+        const unsigned long long v = s_part[0][l] + s_part[1][l] + s_part[2][l] + s_part[3][l];   // < 2^53 + 2: no overflow
+        if (v) {
+            atomicAdd(&a.rtn_sums[((size_t)row * L + l) * 2], v & 0xFFFFFFFFull);
+            atomicAdd(&a.rtn_sums[((size_t)row * L + l) * 2 + 1], v >> 32);
         }
     }
 }
@@ -196,9 +206,11 @@ mlmc_status rtn_compress(const mlmc_plan_t* pl, const BitsArgs& a, bool vec, boo
     if (sw > scap) sw = scap;
     if (sw < 1) sw = 1;
     const dim3 sgrid((unsigned)sw, M);
-    int64_t nw = (pl->d + 4 * 256 * 8 - 1) / (4 * 256 * 8);   // a thread takes about eight groups of four elements
-    const int64_t ncap = 8192 / M > 0 ? 8192 / M : 1;
+    int64_t nw = (pl->d + 4 * 256 * 8 - 1) / (4 * 256 * 8);   // a thread takes at least about eight groups of four elements
+    const int64_t ncap = 2048 / M > 0 ? 2048 / M : 1;          // eight workgroups per CU in all: few atomics per sum
     if (nw > ncap) nw = ncap;
+    const int64_t nmin = (pl->d + ((int64_t)1 << 24) - 1) >> 24;   // a thread adds at most 2^16 squares below 2^36: exact in fp64
+    if (nw < nmin) nw = nmin;
     if (nw < 1) nw = 1;
     const dim3 ngrid((unsigned)nw, M);
     int64_t ntiles = pl->ntiles;

@@ -144,6 +144,33 @@ def test_message_from_second_read_equals_message_from_staged_lists(name, d, M):
                 assert np.array_equal(out.cpu().numpy().view(np.uint32), O.aggregate_sparse(want, w.d, 1.0 / M).view(np.uint32))
 
 
+def test_message_kernels_side_by_side_or_in_turn():
+    """The second read of unstaged rows runs on the plan's side stream beside the assembly from the staged lists
+    (overlap on, the default) or after it on the caller's stream (off).  Same message either way, also on a stream
+    other than the default one and with other work of the caller queued right behind the call."""
+    w = W.scaled(W.WORKLOADS["resnet50_adaptive_topk"], d=9 * 65536 + 4096 + 33, M=5)
+    G = W.generate(w)
+    g = to_device(G)
+    side = torch.cuda.Stream()
+    for overlap in (True, False):
+        plan = _plan_for(w, None)
+        plan.set_overlap(overlap)
+        for step in range(10):
+            print(f"overlap={overlap} step={step}", flush=True)
+            if step % 2:
+                side.wait_stream(torch.cuda.current_stream())
+                with torch.cuda.stream(side):
+                    msg = P.mlmc_compress_topk(plan, g, seed=5, step=step)
+                    out = P.mlmc_aggregate(plan, msg, 1.0 / w.M)   # reads the message right behind the join
+                torch.cuda.current_stream().wait_stream(side)
+            else:
+                msg = P.mlmc_compress_topk(plan, g, seed=5, step=step)
+                out = P.mlmc_aggregate(plan, msg, 1.0 / w.M)
+            want = check_topk_against_oracle(plan, G, 5, step, msg, adaptive=True)
+            assert plan.status() == 0
+            assert np.array_equal(out.cpu().numpy().view(np.uint32), O.aggregate_sparse(want, w.d, 1.0 / w.M).view(np.uint32))
+
+
 @pytest.mark.parametrize("shift", [0, 2])
 def test_adversarial_rows_ties_zeros_denormals(shift):
     d = 3 * 4096 + 517
@@ -173,6 +200,56 @@ def test_adversarial_rows_ties_zeros_denormals(shift):
         out = P.mlmc_aggregate(plan_a, msg, 0.125)
         torch.cuda.synchronize()
         assert np.array_equal(out.cpu().numpy().view(np.uint32), O.aggregate_sparse(want, d, 0.125).view(np.uint32))
+
+
+def _tie_rows(d, M, n_above, n_tie, bf16, seed):
+    """Rows with n_above entries larger than one value, n_tie entries equal to it in magnitude (random signs, random
+    places), the rest smaller: a rank threshold inside the tie block is decided by the index alone."""
+    rng = np.random.default_rng(seed)
+    rows = []
+    for i in range(M):
+        perm = rng.permutation(d)
+        x = np.empty(d, np.float32)
+        x[perm[:n_above]] = (2.0 + rng.random(n_above)).astype(np.float32)
+        x[perm[n_above:n_above + n_tie]] = np.float32(0.375)
+        x[perm[n_above + n_tie:]] = (0.25 * rng.random(d - n_above - n_tie)).astype(np.float32)
+        x *= rng.choice(np.array([-1.0, 1.0], np.float32), d)
+        rows.append(x)
+    G = np.stack(rows)
+    if bf16:   # every value above is a bf16 number after truncation of the random parts; the tie value is one exactly
+        G = (G.view(np.uint32) >> 16).astype(np.uint16)
+    return G
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_one_key_holds_the_threshold_massive_ties(bf16):
+    """A threshold whose key is shared by far more entries than a workgroup can rank: the index cut is found from the
+    per-chunk counts of the tie block and the one chunk that holds it.  Cases: the cut inside a chunk (first, middle,
+    ragged last chunk), the threshold being the last of its key, two thresholds inside the same key."""
+    d, M = 6 * 65536 + 3 * 4096 + 77, 3
+    n_above, n_tie = d // 5, (3 * d) // 5
+    G = _tie_rows(d, M, n_above, n_tie, bf16, 11)
+    g = to_device(G)
+    dt = P.MLMC_BF16 if bf16 else P.MLMC_F32
+    ladders = [[100, n_above + 5, d],                    # the cut right after the block's first entries
+               [100, n_above + n_tie // 2, d],           # in the middle
+               [100, n_above + n_tie - 3, d],            # near its end
+               [100, n_above + n_tie, d],                # the last of its key: every equal entry is inside
+               [n_above + 1000, n_above + n_tie // 3, n_above + n_tie - 1000, d]]   # several thresholds in one key
+    for ladder in ladders:
+        L = len(ladder) - 1
+        for pf in (None, O.geometric_p(L)):
+            plan = P.Plan(P.MLMC_TOPK, M, d, dt, ladder, pf)
+            if pf is None:
+                norms = P.mlmc_level_norms(plan, g).cpu().numpy()
+                for i in range(M):
+                    want, _ = O.level_norms_row(G[i], ladder)
+                    assert np.array_equal(norms[i].view(np.uint64), np.array(want).view(np.uint64)), (ladder, i)
+            for step in range(4):
+                print(f"massive ties bf16={bf16} ladder={ladder} adaptive={pf is None} step={step}", flush=True)
+                msg = P.mlmc_compress_topk(plan, g, seed=3, step=step)
+                check_topk_against_oracle(plan, G, 3, step, msg, adaptive=pf is None)
+                assert plan.status() == 0
 
 
 @pytest.mark.parametrize("ld_pad", [1, 2, 3, 8])
