@@ -75,19 +75,40 @@ __global__ __launch_bounds__(HIST_THREADS) void k_hist(TopkArgs a, int exact_pas
             }
         }
     };
-    for (int64_t i = i0 + wave; i < i1; i += HIST_THREADS / 64) {
+    // A wave's whole blocks, the four loads of the next one in flight while the current one is counted; the row's last
+    // block, when it is a partial one, comes after them (blocks ascend with i, so it is the last of its wave).
+    const int64_t nwhole = a.d >> 10, wstep = HIST_THREADS / 64;
+    auto fetch = [&](int64_t i, uint32_t (&b)[4][4]) {
         const int64_t base = (first + i * S) * 1024 + lane * 4;
-        uint32_t b[4][4];
-        if ((first + i * S + 1) * 1024 <= a.d) {   // a whole block: four loads in flight
 #pragma unroll
-            for (int q = 0; q < 4; ++q) ld.load4_full(base + q * 256, b[q]);
+        for (int q = 0; q < 4; ++q) ld.load4_full(base + q * 256, b[q]);
+    };
+    auto count = [&](const uint32_t (&b)[4][4]) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) count4(b[q], 4);
-        } else {
-            for (int q = 0; q < 4; ++q) {
-                const int nv = ld.load4(base + q * 256, b[q]);
-                count4(b[q], nv);
-            }
+        for (int q = 0; q < 4; ++q) count4(b[q], 4);
+    };
+    auto whole = [&](int64_t i) -> bool { return i < i1 && first + i * S < nwhole; };   // uniform
+    uint32_t b0[4][4], b1[4][4];
+    int64_t i = i0 + wave;
+    bool have = whole(i);
+    if (have) fetch(i, b0);
+    while (have) {
+        const bool more1 = whole(i + wstep);
+        if (more1) fetch(i + wstep, b1);
+        count(b0);
+        i += wstep;
+        if (!more1) break;
+        const bool more2 = whole(i + wstep);
+        if (more2) fetch(i + wstep, b0);
+        count(b1);
+        i += wstep;
+        have = more2;
+    }
+    if (i < i1) {   // the partial last block of the row
+        const int64_t base = (first + i * S) * 1024 + lane * 4;
+        for (int q = 0; q < 4; ++q) {
+            const int nv = ld.load4(base + q * 256, b0[q]);
+            count4(b0[q], nv);
         }
     }
     __syncthreads();
@@ -204,9 +225,15 @@ __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
     uint32_t sum = 0;
 #pragma unroll
     for (int i = 0; i < 16; ++i) sum += hv[i];
-    if (sum) {   // range of the occupied buckets (the prediction below walks only that range)
-        atomicMin(&s_bmin, (uint32_t)(NB1 - 16 - tid * 16));
-        atomicMax(&s_bmax, (uint32_t)(NB1 - 1 - tid * 16));
+    {   // range of the occupied buckets (the prediction below walks only that range): one pair of atomics per wave, from
+        // its first and last thread with a non-empty run of buckets (a thousand threads on one LDS word take turns)
+        const uint64_t occ = __ballot(sum != 0u);
+        if (occ) {
+            const int first = __builtin_ctzll(occ), last = 63 - __builtin_clzll(occ);
+            const int l = (int)lane_id();
+            if (l == last) atomicMin(&s_bmin, (uint32_t)(NB1 - 16 - tid * 16));   // buckets descend with the thread index
+            if (l == first) atomicMax(&s_bmax, (uint32_t)(NB1 - 1 - tid * 16));
+        }
     }
     uint32_t total;
     const uint32_t before = block_excl_scan<1024>(sum, s_scan, total);
