@@ -433,7 +433,7 @@ mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dty
         pl->off_cand2 = off;
         off = align_up(off + sizeof(uint2) * (size_t)d * M, 256);
         pl->off_cand_priv = off;
-        off = align_up(off + sizeof(uint2) * (size_t)pl->chunk * pl->chunks_per_row * M, 256);
+        off = align_up(off + sizeof(uint2) * 2 * (size_t)pl->chunk * pl->chunks_per_row * M, 256);   // room for twice a wave's even share
         pl->off_priv_cnt = off;
         off = align_up(off + sizeof(uint32_t) * 16 * (size_t)pl->chunks_per_row * M, 256);
         pl->off_chunk_base = off;

@@ -126,7 +126,7 @@ struct TopkArgs {
     RowAcc* racc;            // [M]
     uint2* cand;             // [M][d] candidate lists of the zones: {fp32 bit pattern, index}
     uint2* cand2;            // [M][d] overflow lists: candidates of threshold bins too full to rank in LDS
-    uint2* cand_priv;        // [M][chunks_per_row][chunk] staged {bits, offset in chunk << 6 | tag} as the waves met them
+    uint2* cand_priv;        // [M][chunks_per_row][16 waves][chunk / 8] staged {bits, offset in chunk << 6 | tag} as the waves met them
     uint32_t* priv_cnt;      // [M][chunks_per_row][16] entries of every wave's private list
     uint32_t* chunk_base;    // [M][cchunks_per_row + 1] message entries of the row before every count chunk
     int32_t* row_order;      // [M] rows by descending message length: the order in which the message kernels take them

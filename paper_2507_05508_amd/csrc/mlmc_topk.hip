@@ -487,7 +487,12 @@ static_assert(ZMAX <= 64 && RMAX <= 64 && GMAX <= 512, "field widths of the clas
 // LOOPED: a workgroup takes the chunks blockIdx.x, blockIdx.x + gridDim.x, ... of its row.  The redo round is launched
 // that way with a small grid, so that it costs little when, as nearly always, no row needs it; the first round has a
 // workgroup per chunk and no loop.
-template <int DT, bool VEC, bool SUMS, bool LOOPED>
+// DYN: the waves of a workgroup take the chunk in groups of MAIN_GROUP consecutive elements handed out by an LDS counter,
+// instead of a fixed interleaved share each.  The waves of a SIMD are served oldest first, so with fixed shares the oldest
+// is done when the youngest still has a third of its share left, and the workgroup (which holds all of the CU's LDS: no
+// other can start) ends at a fraction of its wave slots; with the counter all waves end within one group of each other.
+constexpr int MAIN_GROUP = 2048;   // eight loads of a wave
+template <int DT, bool VEC, bool SUMS, bool LOOPED, bool DYN>
 __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pass) {
     __shared__ __align__(16) unsigned char lm[lm_total<SUMS>()];
     uint32_t* s_cnt = (uint32_t*)(lm + LM_CNT);
@@ -530,7 +535,8 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
     const int64_t c1 = c0 + a.chunk < a.d ? c0 + a.chunk : a.d;
     RowLoader<DT, VEC> ld(a.g, a.ld, a.d, row);
     // this wave's private, worst-case sized part of the scratch list: its candidates in the order met
-    uint2* priv = a.cand_priv + ((size_t)row * a.chunks_per_row + chunk_id) * (size_t)a.chunk + (size_t)wave * (a.chunk / MAIN_WAVES);
+    // (room for twice the wave's even share of the chunk: with DYN a wave may take more than that share)
+    uint2* priv = a.cand_priv + ((size_t)row * a.chunks_per_row + chunk_id) * (size_t)(2 * a.chunk) + (size_t)wave * (a.chunk / (MAIN_WAVES / 2));
     // per-lane byte addresses of the replicated accumulators
     const uint32_t cnt_lane = (uint32_t)LM_CNT + (lane & 15u) * 4u;
     const uint32_t sum_lane = (uint32_t)LM_SUM + (lane & 15u) * 8u;
@@ -572,23 +578,88 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
         }
     };
 
+    const int span = (int)(c1 - c0);
+    const int tpc = a.cchunk / TILE;   // tiles per count chunk
+    // the counters of the count chunk that tile t of the chunk lies in
+    auto cnt_of = [&](int t) -> uint32_t {
+        const uint32_t sub = (t >= tpc ? 1u : 0u) + (t >= 2 * tpc ? 1u : 0u) + (t >= 3 * tpc ? 1u : 0u);
+        return cnt_lane + (a.csub > 1 ? sub : 0u) * (uint32_t)(128 * REP_CNT * 4);
+    };
+    uint32_t buf[8][4];
+    uint32_t cc[4], cn[4];
+    if constexpr (DYN) {
+        // Groups of MAIN_GROUP elements from the counter; a wave holds the group it works on and the next one, whose
+        // loads refill the ring as those of the current one are consumed.  A wave takes at most gmax groups, which with
+        // one piece of the chunk's ragged end is what its private list has room for; together the waves have room for
+        // twice the chunk, so the groups never go begging.
+        uint32_t* s_next = (uint32_t*)(lm + LM_ROWMAX + 8);   // cleared with the words around it
+        const int ngroups = span / MAIN_GROUP;
+        const int gmax = (a.chunk / (MAIN_WAVES / 2) - 256) / MAIN_GROUP;
+        int taken = 0;
+        auto grab = [&]() -> int {   // uniform
+            if (taken >= gmax) return -1;
+            uint32_t v = 0;
+            if (lane == 0) v = atomicAdd(s_next, 1u);
+            const int g = __builtin_amdgcn_readfirstlane((int)v);
+            if (g >= ngroups) return -1;
+            ++taken;
+            return g;
+        };
+        auto gissue = [&](int g, int q, uint32_t (&b)[4]) { ld.load4_stream(c0 + (int64_t)(g * MAIN_GROUP + q * 256) + (int64_t)lane * 4, b); };
+        int gc = grab(), gn = gc >= 0 ? grab() : -1;
+        if (gc >= 0) {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) gissue(gc, q, buf[q]);
+            lookup(buf[0], cn);
+            // steady state: every slot is refilled from the next group as soon as it has been consumed (no condition on
+            // the loads, so that the waits can count them), then the last group without refills
+            while (gn >= 0) {   // uniform
+                const uint32_t cb = cnt_of(gc / (TILE / MAIN_GROUP));
+                const uint32_t rel0 = (uint32_t)(gc * MAIN_GROUP) + lane * 4;
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) cc[c] = cn[c];
+                    lookup(buf[(q + 1) & 7], cn);   // q = 7: load 0 of the next group, issued at q = 0
+                    process(buf[q], cc, rel0 + (uint32_t)(q * 256), 15u, cb);
+                    gissue(gn, q, buf[q]);
+                }
+                gc = gn;
+                gn = grab();
+            }
+            {
+                const uint32_t cb = cnt_of(gc / (TILE / MAIN_GROUP));
+                const uint32_t rel0 = (uint32_t)(gc * MAIN_GROUP) + lane * 4;
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) cc[c] = cn[c];
+                    if (q < 7) lookup(buf[q + 1], cn);
+                    process(buf[q], cc, rel0 + (uint32_t)(q * 256), 15u, cb);
+                }
+            }
+        }
+        // what is left past the whole groups: up to eight pieces of 256 elements, the last one ragged; wave w takes piece w
+        const int tbase = ngroups * MAIN_GROUP;
+        if (tbase + (int)wave * 256 < span) {
+            const int pos = tbase + (int)wave * 256;
+            const int64_t j = c0 + pos + (int64_t)lane * 4;
+            const int nv = j < c1 ? ld.load4(j, buf[0]) : 0;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) if (c >= nv) buf[0][c] = 0u;
+            lookup(buf[0], cc);
+            process(buf[0], cc, (uint32_t)pos + lane * 4, (1u << nv) - 1u, cnt_of(pos / TILE));
+        }
+    } else {
     // Load n of a wave covers the 256 elements at c0 + (16 n + wave) * 256: the 16 waves read 16 KB side by
     // side.  Eight loads per lane stay in flight: a slot is refilled as soon as it has been processed.
-    const int span = (int)(c1 - c0);
     const int woff = (int)wave * 256;
     const int nfull = span >= woff + 256 ? (span - woff - 256) / 4096 + 1 : 0;   // loads with all 256 elements
     auto issue = [&](int n, uint32_t (&b)[4]) { ld.load4_stream(c0 + (int64_t)((n * 16 + (int)wave) * 256) + (int64_t)lane * 4, b); };
     auto rel_of = [&](int n) -> uint32_t { return (uint32_t)((n * 16 + (int)wave) * 256) + lane * 4; };
-    // load round n covers tile n of the chunk: its counters are those of the count chunk the tile lies in
-    const int tpc = a.cchunk / TILE;   // tiles per count chunk
-    auto cnt_of = [&](int n) -> uint32_t {
-        const uint32_t sub = (n >= tpc ? 1u : 0u) + (n >= 2 * tpc ? 1u : 0u) + (n >= 3 * tpc ? 1u : 0u);
-        return cnt_lane + (a.csub > 1 ? sub : 0u) * (uint32_t)(128 * REP_CNT * 4);
-    };
+    // load round n covers tile n of the chunk
     // The table look-ups of the next load are issued before the accumulators of the current one are updated, so
     // that their latency is covered.
-    uint32_t buf[8][4];
-    uint32_t cc[4], cn[4];
     int n = 0;
     if (nfull >= 8) {
 #pragma unroll
@@ -625,6 +696,7 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
         for (int c = 0; c < 4; ++c) if (c >= nv) buf[0][c] = 0u;
         lookup(buf[0], cc);
         process(buf[0], cc, rel_of(nfull), (1u << nv) - 1u, cnt_of(nfull));
+    }
     }
     if (__ballot(maxkey >= 0x7F800000u) && lane == 0) atomicOr(a.dev_status, MLMC_DEV_NONFINITE);
     maxkey = wave_max(maxkey);
@@ -1979,7 +2051,7 @@ __global__ __launch_bounds__(FL_THREADS) void k_filter(TopkArgs a) {
     const int64_t c1 = c0 + a.chunk < a.d ? c0 + a.chunk : a.d;
     const int nwords = (int)((c1 - c0 + 31) / 32);
     // wave w of this workgroup reads the private list of wave w of the selection read
-    const uint2* priv = a.cand_priv + ((size_t)row * nc + chunk_id) * (size_t)a.chunk + (size_t)wave * (a.chunk / 16);
+    const uint2* priv = a.cand_priv + ((size_t)row * nc + chunk_id) * (size_t)(2 * a.chunk) + (size_t)wave * (a.chunk / 8);
     const uint32_t cnt = a.priv_cnt[((size_t)row * nc + chunk_id) * 16 + wave];
     // The first FL_KEEP entries of every lane stay in registers for the second pass (a wave's list rarely holds
     // more than 64 * FL_KEEP).  They are loaded without waiting for the list's length: the list's memory is there
@@ -2076,11 +2148,19 @@ static mlmc_status launch_select(const mlmc_plan_t* pl, const TopkArgs& a, bool 
         MLMC_LAUNCH(kh, st, k_hist<DT, VEC><<<hgrid, HIST_THREADS, 0, st>>>(a, exact_pass));
         MLMC_LAUNCH(ks, st, k_scan<<<pl->M, 1024, 0, st>>>(a, exact_pass));
         if (exact_pass) {
-            if (sums) MLMC_LAUNCH(km, st, k_main<DT, VEC, true, true><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
-            else MLMC_LAUNCH(km, st, k_main<DT, VEC, false, true><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
+            if (sums) MLMC_LAUNCH(km, st, k_main<DT, VEC, true, true, false><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
+            else MLMC_LAUNCH(km, st, k_main<DT, VEC, false, true, false><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
         } else {
-            if (sums) MLMC_LAUNCH(km, st, k_main<DT, VEC, true, false><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
-            else MLMC_LAUNCH(km, st, k_main<DT, VEC, false, false><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
+            // chunks of 64 K elements or more: the waves share the chunk through a counter (shorter ones are not worth it,
+            // and their private lists would have no room for a whole group)
+            const bool dyn = pl->chunk >= 65536;
+            if (sums) {
+                if (dyn) MLMC_LAUNCH(km, st, k_main<DT, VEC, true, false, true><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
+                else MLMC_LAUNCH(km, st, k_main<DT, VEC, true, false, false><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
+            } else {
+                if (dyn) MLMC_LAUNCH(km, st, k_main<DT, VEC, false, false, true><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
+                else MLMC_LAUNCH(km, st, k_main<DT, VEC, false, false, false><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
+            }
         }
         // the redo round resolves every zone in the ranking launch alone (two launches fewer to pay for when, as
         // nearly always, no row needs it)
