@@ -74,7 +74,7 @@ def measured_traffic(workload, kernel):
         f = line.split()
         if line.startswith("kernel sources sha256:"):
             digest_prof = f[-1]
-        elif f and f[0].split("<")[0] == kernel and len(f) >= 3:
+        elif value is None and f and f[0].split("<")[0] == kernel and len(f) >= 3:   # first line of the kernel: its working launches
             try:
                 value = int((float(f[-2]) + float(f[-1])) * 1e6)
             except ValueError:
