@@ -134,6 +134,7 @@ static void fill_topk_args(const mlmc_plan_t* pl, TopkArgs& a, const void* g, in
     a.hist2 = (uint32_t*)(w + pl->off_hist2);
     a.rinfo = (RowInfo*)(w + pl->off_rinfo);
     a.table = (uint32_t*)(w + pl->off_table);
+    a.table8 = (uint8_t*)(w + pl->off_table8);
     a.chunk_cnt = (uint32_t*)(w + pl->off_chunk_cnt);
     a.chunk_zcnt = (uint32_t*)(w + pl->off_chunk_zcnt);
     a.zhist = (uint32_t*)(w + pl->off_zhist);
@@ -440,6 +441,8 @@ mlmc_status mlmc_plan(mlmc_plan_t** plan, int kind, int M, int64_t d, int in_dty
         off = align_up(off + sizeof(uint32_t) * (size_t)(pl->cchunks_per_row + 1) * M, 256);
         pl->off_row_order = off;
         off = align_up(off + sizeof(int32_t) * (size_t)M, 256);
+        pl->off_table8 = off;
+        off = align_up(off + (size_t)NB1 * M, 256);
     }
     pl->ws_bytes = off;
     if (workspace_bytes) *workspace_bytes = off;

@@ -122,6 +122,7 @@ struct TopkArgs {
     uint32_t* hist;          // [M][NB1] histogram of the sampled blocks
     uint32_t* hist2;         // [M][NB1] full histogram of the rows that are redone exactly
     uint32_t* table;         // [M][NB1]
+    uint8_t* table8;         // [M][NB1] the class table in one byte per bucket: counter | stage << 7
     RowInfo* rinfo;          // [M]
     RowAcc* racc;            // [M]
     uint2* cand;             // [M][d] candidate lists of the zones: {fp32 bit pattern, index}
@@ -249,7 +250,7 @@ struct mlmc_plan_s {
     int staging;
     // workspace byte offsets
     size_t off_racc, off_hist, off_hist2, off_chunk_zcnt, off_zhist, off_zpacc, zero_bytes;  // [0, zero_bytes) is cleared per call
-    size_t off_rinfo, off_table, off_chunk_cnt, off_zcol, off_tileoff, off_norms, off_cand, off_cand2, off_cand_priv, off_priv_cnt, off_chunk_base, off_row_order;
+    size_t off_rinfo, off_table, off_chunk_cnt, off_zcol, off_tileoff, off_norms, off_cand, off_cand2, off_cand_priv, off_priv_cnt, off_chunk_base, off_row_order, off_table8;
     size_t ws_bytes;
     // s-segmented Top-k plans
     int64_t s;

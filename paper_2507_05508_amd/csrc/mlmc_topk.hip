@@ -453,6 +453,19 @@ __global__ __launch_bounds__(1024) void k_scan(TopkArgs a, int exact_pass) {
         uint4* dst = (uint4*)(a.table + (size_t)row * NB1 + (NB1 - 16 - tid * 16));
 #pragma unroll
         for (int i = 0; i < 4; ++i) dst[i] = make_uint4(codes[4 * i], codes[4 * i + 1], codes[4 * i + 2], codes[4 * i + 3]);
+        // the same table in one byte per bucket (counter in bits 0..6, "stage" in bit 7), for the selection read that
+        // rebuilds the rest from the key: the sum group of a region is (255 - exponent) + region, the tag of a zone its index
+        uint32_t w8[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            w8[i] = 0;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint32_t c = codes[4 * i + k];
+                w8[i] |= (((c >> 6) & 0x7Fu) | ((c & CODE_STAGE) ? 0x80u : 0u)) << (8 * k);
+            }
+        }
+        *(uint4*)(a.table8 + (size_t)row * NB1 + (NB1 - 16 - tid * 16)) = make_uint4(w8[0], w8[1], w8[2], w8[3]);
     }
     __syncthreads();
     for (int g = tid; g < GMAX; g += 1024) {
@@ -772,6 +785,248 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
         else atomicOr((int32_t*)&a.rinfo[row].respec, 1);
     }
     } while (LOOPED && (chunk_id += (int)gridDim.x) < a.chunks_per_row);
+}
+
+// ---------------------------------------------------------------------------------------------------
+// The selection read with two workgroups per CU (plans whose chunks have four count chunks): a chunk is read by two
+// workgroups of 512 threads, two count chunks each, so that the table load, the flush and the move of the candidates of
+// one workgroup run beside the streaming of the other (with one workgroup per CU they overlap nothing: a tenth to a
+// quarter of its time).  What makes two fit: the class table in one byte per bucket (16 KB instead of 64: the sum
+// group and the tag follow from the key and the counter), counters for two count chunks.  Everything the workgroup
+// writes has the layout of k_main: sixteen private lists per chunk (this workgroup's eight waves use lists 8 h .. 8 h + 7),
+// entries {bits, offset in the CHUNK << 6 | tag}, counts per count chunk.
+constexpr int M2_THREADS = 512;
+constexpr int M2_WAVES = M2_THREADS / 64;
+constexpr int M2_CSUB = 2;                                   // count chunks per workgroup
+constexpr int M2_TAB = 0;                                    // uint8 [NB1]
+constexpr int M2_SUM = NB1;                                  // uint64 [GMAX][REP_SUM]
+constexpr int M2_ZCUR = M2_SUM + GMAX * REP_SUM * 8;         // uint32 [64]
+constexpr int M2_ROWMAX = M2_ZCUR + 64 * 4;                  // uint32 largest key, uint32 (at + 8) group counter
+constexpr int M2_ZOFF = M2_ROWMAX + 16;
+constexpr int M2_ZCAP = M2_ZOFF + 64 * 4;
+constexpr int M2_MISC_END = M2_ZCAP + 64 * 4;
+constexpr int M2_CNT = 56 * 1024;                            // uint32 [M2_CSUB][128][REP_CNT]
+constexpr int M2_END = M2_CNT + M2_CSUB * 128 * REP_CNT * 4;
+static_assert(M2_MISC_END <= M2_CNT && 2 * M2_END <= 160 * 1024 && M2_SUM % 16 == 0 && M2_ZCUR % 16 == 0, "LDS layout: two workgroups per CU");
+
+template <int DT, bool VEC, bool SUMS>
+__global__ __launch_bounds__(M2_THREADS, 4) void k_main2(TopkArgs a) {
+    __shared__ __align__(16) unsigned char lm[M2_END];
+    uint32_t* s_cnt = (uint32_t*)(lm + M2_CNT);
+    uint32_t* s_zcur = (uint32_t*)(lm + M2_ZCUR);
+    uint32_t* s_rowmax = (uint32_t*)(lm + M2_ROWMAX);
+    uint32_t* s_next = (uint32_t*)(lm + M2_ROWMAX + 8);
+    uint32_t* s_zoff = (uint32_t*)(lm + M2_ZOFF);
+    uint32_t* s_zcap = (uint32_t*)(lm + M2_ZCAP);
+
+    const int row = blockIdx.y, tid = threadIdx.x;
+    const RowInfo* ri = a.rinfo + row;
+    const uint32_t lane = lane_id();
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane(tid >> 6);
+    RowAcc* ra = a.racc + row;
+    const int nz = ri->n_zones;
+    const int chunk_id = blockIdx.x >> 1, half = blockIdx.x & 1;
+    {
+        const uint4* src = (const uint4*)(a.table8 + (size_t)row * NB1);
+        uint4* dst = (uint4*)(lm + M2_TAB);
+        for (int i = tid; i < NB1 / 16; i += M2_THREADS) dst[i] = src[i];
+        const uint4 zero = make_uint4(0, 0, 0, 0);
+        uint4* z = (uint4*)(lm + M2_CNT);
+        for (int i = tid; i < (M2_END - M2_CNT) / 16; i += M2_THREADS) z[i] = zero;
+        z = (uint4*)(lm + M2_ZCUR);
+        for (int i = tid; i < (M2_ZOFF - M2_ZCUR) / 16; i += M2_THREADS) z[i] = zero;
+        if (SUMS) {
+            z = (uint4*)(lm + M2_SUM);
+            for (int i = tid; i < GMAX * REP_SUM * 8 / 16; i += M2_THREADS) z[i] = zero;
+        }
+    }
+    if (tid < 64) {
+        s_zoff[tid] = tid < nz ? ri->zone_off[tid] : 0u;
+        s_zcap[tid] = tid < nz ? ri->zone_cap[tid] : 0u;
+    }
+    __syncthreads();
+
+    const int hlen = a.chunk / 2;   // elements of a workgroup: two count chunks
+    const int64_t cbase = (int64_t)chunk_id * a.chunk;
+    const int64_t c0 = cbase + (int64_t)half * hlen;
+    const int64_t c1 = c0 + hlen < a.d ? c0 + hlen : a.d;
+    const int span = c1 > c0 ? (int)(c1 - c0) : 0;   // the second half of a row's last chunk may be empty
+    const uint32_t relh = (uint32_t)(half * hlen);   // offsets in the entries count from the start of the chunk
+    RowLoader<DT, VEC> ld(a.g, a.ld, a.d, row);
+    uint2* priv = a.cand_priv + ((size_t)row * a.chunks_per_row + chunk_id) * (size_t)(2 * a.chunk) +
+                  (size_t)(half * M2_WAVES + (int)wave) * (a.chunk / 8);
+    const uint32_t cnt_lane = (uint32_t)M2_CNT + (lane & 15u) * 4u;
+    const uint32_t sum_lane = (uint32_t)M2_SUM + (lane & 15u) * 8u;
+    uint32_t head = 0;
+    uint32_t maxkey = 0;
+
+    auto lookup = [&](const uint32_t (&b)[4], uint32_t (&code)[4]) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) code[c] = lm[(b[c] >> B1_SHIFT) & (uint32_t)(NB1 - 1)];
+    };
+    auto process = [&](const uint32_t (&b)[4], uint32_t (&code)[4], uint32_t rel0, uint32_t vmask, uint32_t cnt_base) {
+        uint32_t anys = 0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if (!((vmask >> c) & 1u)) code[c] = 0x7Fu;   // past the end: an unused zone's counter, the dummy group, not staged
+            const uint32_t key = key_of_bits(b[c]);
+            const uint32_t cnt7 = code[c] & 0x7Fu;
+            if (SUMS) {
+                const uint32_t hid = (key & 0x7FFFFFu) | 0x800000u;
+                const uint32_t sig = key < hid ? key : hid;   // exponent field 0: no hidden bit, sig = key
+                const uint32_t gid = cnt7 < 64u ? 255u - (key >> 23) + cnt7 : (uint32_t)G_DUMMY;
+                atomicAdd((unsigned long long*)(lm + (gid * (uint32_t)(REP_SUM * 8) + sum_lane)),
+                          (unsigned long long)sig * (unsigned long long)sig);
+            }
+            atomicAdd((uint32_t*)(lm + (cnt7 * (uint32_t)(REP_CNT * 4) + cnt_base)), 1u);
+            maxkey = key > maxkey ? key : maxkey;
+            anys |= code[c];
+        }
+        if (__ballot(anys & 0x80u)) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint64_t m = __ballot(code[c] & 0x80u);
+                if (__builtin_amdgcn_inverse_ballot_w64(m)) {
+                    const uint32_t cnt7 = code[c] & 0x7Fu;
+                    const uint32_t tag = cnt7 >= 64u ? cnt7 & 63u : TAG_MEMBER;
+                    priv[head + mbcnt(m)] = make_uint2(b[c], ((rel0 + (uint32_t)c) << 6) | tag);
+                }
+                head += (uint32_t)__popcll(m);
+            }
+        }
+    };
+
+    const int tpc = a.cchunk / TILE;   // tiles per count chunk
+    auto cnt_of = [&](int t) -> uint32_t { return cnt_lane + (t >= tpc ? 1u : 0u) * (uint32_t)(128 * REP_CNT * 4); };
+    uint32_t buf[8][4];
+    uint32_t cc[4], cn[4];
+    {
+        // groups of MAIN_GROUP elements from the counter, as in k_main<..., DYN>
+        const int ngroups = span / MAIN_GROUP;
+        const int gmax = (a.chunk / 8 - 256) / MAIN_GROUP;
+        int taken = 0;
+        auto grab = [&]() -> int {   // uniform
+            if (taken >= gmax) return -1;
+            uint32_t v = 0;
+            if (lane == 0) v = atomicAdd(s_next, 1u);
+            const int g = __builtin_amdgcn_readfirstlane((int)v);
+            if (g >= ngroups) return -1;
+            ++taken;
+            return g;
+        };
+        auto gissue = [&](int g, int q, uint32_t (&b)[4]) { ld.load4_stream(c0 + (int64_t)(g * MAIN_GROUP + q * 256) + (int64_t)lane * 4, b); };
+        int gc = grab(), gn = gc >= 0 ? grab() : -1;
+        if (gc >= 0) {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) gissue(gc, q, buf[q]);
+            lookup(buf[0], cn);
+            while (gn >= 0) {   // uniform
+                const uint32_t cb = cnt_of(gc / (TILE / MAIN_GROUP));
+                const uint32_t rel0 = relh + (uint32_t)(gc * MAIN_GROUP) + lane * 4;
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) cc[c] = cn[c];
+                    lookup(buf[(q + 1) & 7], cn);
+                    process(buf[q], cc, rel0 + (uint32_t)(q * 256), 15u, cb);
+                    gissue(gn, q, buf[q]);
+                }
+                gc = gn;
+                gn = grab();
+            }
+            {
+                const uint32_t cb = cnt_of(gc / (TILE / MAIN_GROUP));
+                const uint32_t rel0 = relh + (uint32_t)(gc * MAIN_GROUP) + lane * 4;
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) cc[c] = cn[c];
+                    if (q < 7) lookup(buf[q + 1], cn);
+                    process(buf[q], cc, rel0 + (uint32_t)(q * 256), 15u, cb);
+                }
+            }
+        }
+        const int tbase = ngroups * MAIN_GROUP;   // up to eight pieces of 256 elements are left, the last one ragged: wave w takes piece w
+        if (tbase + (int)wave * 256 < span) {
+            const int pos = tbase + (int)wave * 256;
+            const int64_t j = c0 + pos + (int64_t)lane * 4;
+            const int nv = j < c1 ? ld.load4(j, buf[0]) : 0;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) if (c >= nv) buf[0][c] = 0u;
+            lookup(buf[0], cc);
+            process(buf[0], cc, relh + (uint32_t)pos + lane * 4, (1u << nv) - 1u, cnt_of(pos / TILE));
+        }
+    }
+    if (__ballot(maxkey >= 0x7F800000u) && lane == 0) atomicOr(a.dev_status, MLMC_DEV_NONFINITE);
+    maxkey = wave_max(maxkey);
+    if (lane == 0) atomicMax(s_rowmax, maxkey);
+
+    // ---- flush and move, as in k_main ----
+    constexpr int EP_KEEP = 16;
+    uint2 ent[EP_KEEP];
+    __threadfence_block();
+    if (head) {   // uniform
+#pragma unroll
+        for (int u = 0; u < EP_KEEP; ++u) {
+            const uint32_t i = lane + 64u * (uint32_t)u;
+            ent[u] = priv[i < head ? i : head - 1u];
+        }
+    }
+    if (lane == 0) a.priv_cnt[((size_t)row * a.chunks_per_row + chunk_id) * MAIN_WAVES + half * M2_WAVES + wave] = head;
+    __syncthreads();
+    if (tid < nz) {
+        uint32_t total = 0;
+        for (int r = 0; r < M2_CSUB * REP_CNT; ++r)
+            total += s_cnt[(r / REP_CNT) * (128 * REP_CNT) + (64 + tid) * REP_CNT + ((r + tid) & (REP_CNT - 1))];
+        s_zcur[tid] = total ? atomicAdd(&ra->zone_fill[tid], total) : 0u;
+    }
+    if (tid == 64) atomicMax(&ra->rowmax_key, s_rowmax[0]);
+    if (SUMS && tid >= 64) {
+        const unsigned long long* s_sum = (const unsigned long long*)(lm + M2_SUM);
+        for (int g = tid - 64; g < G_DUMMY; g += M2_THREADS - 64) {
+            unsigned long long lo = 0, hi = 0;
+#pragma unroll
+            for (int r = 0; r < REP_SUM; ++r) {
+                const unsigned long long v = s_sum[g * REP_SUM + ((r + tid) & (REP_SUM - 1))];
+                lo += v & 0xFFFFFFFFull;
+                hi += v >> 32;
+            }
+            if (lo) atomicAdd((unsigned long long*)&ra->gsum[g][0], lo);
+            if (hi) atomicAdd((unsigned long long*)&ra->gsum[g][1], hi);
+        }
+    }
+    if (tid >= M2_THREADS - RMAX * M2_CSUB) {   // per count chunk: the counters of region t % RMAX
+        const int t = tid - (M2_THREADS - RMAX * M2_CSUB);
+        const int r = t % RMAX, sub = t / RMAX;
+        uint32_t cnt = 0;
+        for (int k = 0; k < REP_CNT; ++k) cnt += s_cnt[sub * (128 * REP_CNT) + r * REP_CNT + ((k + t) & (REP_CNT - 1))];
+        const int64_t ccx = (int64_t)chunk_id * 4 + half * M2_CSUB + sub;
+        if (ccx < a.cchunks_per_row) a.chunk_cnt[((size_t)row * RMAX + r) * a.cchunks_per_row + ccx] = cnt;
+        if (cnt) atomicAdd(&ra->region_cnt[r], cnt);
+    }
+    __syncthreads();
+    uint2* cl = a.cand + (size_t)row * (size_t)a.d;
+    bool dropped = false;
+    auto move = [&](uint2 e) {
+        const uint32_t z = e.y & 63u;
+        if (z == TAG_MEMBER) return;   // staged for the message only
+        const uint32_t pos = atomicAdd(&s_zcur[z], 1u);
+        if (pos < s_zcap[z]) {
+            cl[(size_t)s_zoff[z] + pos] = make_uint2(e.x, (uint32_t)cbase + (e.y >> 6));
+        } else {
+            dropped = true;
+        }
+    };
+    if (head) {
+#pragma unroll
+        for (int u = 0; u < EP_KEEP; ++u)
+            if (lane + 64u * (uint32_t)u < head) move(ent[u]);
+    }
+    batched_loop<16, 64>(64u * EP_KEEP, head, lane, [&](uint32_t i) { return priv[i]; }, [&](uint32_t, uint2 e) { move(e); });
+    if (__ballot(dropped) && lane == 0) {
+        if (ri->exact) atomicOr(a.dev_status, MLMC_DEV_INTERNAL);
+        else atomicOr((int32_t*)&a.rinfo[row].respec, 1);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -2154,7 +2409,11 @@ static mlmc_status launch_select(const mlmc_plan_t* pl, const TopkArgs& a, bool 
             // chunks of 64 K elements or more: the waves share the chunk through a counter (shorter ones are not worth it,
             // and their private lists would have no room for a whole group)
             const bool dyn = pl->chunk >= 65536;
-            if (sums) {
+            if (dyn && pl->csub == 4) {   // two workgroups per chunk, two per CU
+                const dim3 grid2(2 * pl->chunks_per_row, pl->M);
+                if (sums) MLMC_LAUNCH(km, st, k_main2<DT, VEC, true><<<grid2, M2_THREADS, 0, st>>>(a));
+                else MLMC_LAUNCH(km, st, k_main2<DT, VEC, false><<<grid2, M2_THREADS, 0, st>>>(a));
+            } else if (sums) {
                 if (dyn) MLMC_LAUNCH(km, st, k_main<DT, VEC, true, false, true><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
                 else MLMC_LAUNCH(km, st, k_main<DT, VEC, true, false, false><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
             } else {
