@@ -500,12 +500,7 @@ static_assert(ZMAX <= 64 && RMAX <= 64 && GMAX <= 512, "field widths of the clas
 // LOOPED: a workgroup takes the chunks blockIdx.x, blockIdx.x + gridDim.x, ... of its row.  The redo round is launched
 // that way with a small grid, so that it costs little when, as nearly always, no row needs it; the first round has a
 // workgroup per chunk and no loop.
-// DYN: the waves of a workgroup take the chunk in groups of MAIN_GROUP consecutive elements handed out by an LDS counter,
-// instead of a fixed interleaved share each.  The waves of a SIMD are served oldest first, so with fixed shares the oldest
-// is done when the youngest still has a third of its share left, and the workgroup (which holds all of the CU's LDS: no
-// other can start) ends at a fraction of its wave slots; with the counter all waves end within one group of each other.
-constexpr int MAIN_GROUP = 2048;   // eight loads of a wave
-template <int DT, bool VEC, bool SUMS, bool LOOPED, bool DYN>
+template <int DT, bool VEC, bool SUMS, bool LOOPED>
 __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pass) {
     __shared__ __align__(16) unsigned char lm[lm_total<SUMS>()];
     uint32_t* s_cnt = (uint32_t*)(lm + LM_CNT);
@@ -548,7 +543,7 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
     const int64_t c1 = c0 + a.chunk < a.d ? c0 + a.chunk : a.d;
     RowLoader<DT, VEC> ld(a.g, a.ld, a.d, row);
     // this wave's private, worst-case sized part of the scratch list: its candidates in the order met
-    // (room for twice the wave's even share of the chunk: with DYN a wave may take more than that share)
+    // (room for twice the wave's even share of the chunk: the waves of k_main2 may take more than that share)
     uint2* priv = a.cand_priv + ((size_t)row * a.chunks_per_row + chunk_id) * (size_t)(2 * a.chunk) + (size_t)wave * (a.chunk / (MAIN_WAVES / 2));
     // per-lane byte addresses of the replicated accumulators
     const uint32_t cnt_lane = (uint32_t)LM_CNT + (lane & 15u) * 4u;
@@ -600,70 +595,6 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
     };
     uint32_t buf[8][4];
     uint32_t cc[4], cn[4];
-    if constexpr (DYN) {
-        // Groups of MAIN_GROUP elements from the counter; a wave holds the group it works on and the next one, whose
-        // loads refill the ring as those of the current one are consumed.  A wave takes at most gmax groups, which with
-        // one piece of the chunk's ragged end is what its private list has room for; together the waves have room for
-        // twice the chunk, so the groups never go begging.
-        uint32_t* s_next = (uint32_t*)(lm + LM_ROWMAX + 8);   // cleared with the words around it
-        const int ngroups = span / MAIN_GROUP;
-        const int gmax = (a.chunk / (MAIN_WAVES / 2) - 256) / MAIN_GROUP;
-        int taken = 0;
-        auto grab = [&]() -> int {   // uniform
-            if (taken >= gmax) return -1;
-            uint32_t v = 0;
-            if (lane == 0) v = atomicAdd(s_next, 1u);
-            const int g = __builtin_amdgcn_readfirstlane((int)v);
-            if (g >= ngroups) return -1;
-            ++taken;
-            return g;
-        };
-        auto gissue = [&](int g, int q, uint32_t (&b)[4]) { ld.load4_stream(c0 + (int64_t)(g * MAIN_GROUP + q * 256) + (int64_t)lane * 4, b); };
-        int gc = grab(), gn = gc >= 0 ? grab() : -1;
-        if (gc >= 0) {
-#pragma unroll
-            for (int q = 0; q < 8; ++q) gissue(gc, q, buf[q]);
-            lookup(buf[0], cn);
-            // steady state: every slot is refilled from the next group as soon as it has been consumed (no condition on
-            // the loads, so that the waits can count them), then the last group without refills
-            while (gn >= 0) {   // uniform
-                const uint32_t cb = cnt_of(gc / (TILE / MAIN_GROUP));
-                const uint32_t rel0 = (uint32_t)(gc * MAIN_GROUP) + lane * 4;
-#pragma unroll
-                for (int q = 0; q < 8; ++q) {
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) cc[c] = cn[c];
-                    lookup(buf[(q + 1) & 7], cn);   // q = 7: load 0 of the next group, issued at q = 0
-                    process(buf[q], cc, rel0 + (uint32_t)(q * 256), 15u, cb);
-                    gissue(gn, q, buf[q]);
-                }
-                gc = gn;
-                gn = grab();
-            }
-            {
-                const uint32_t cb = cnt_of(gc / (TILE / MAIN_GROUP));
-                const uint32_t rel0 = (uint32_t)(gc * MAIN_GROUP) + lane * 4;
-#pragma unroll
-                for (int q = 0; q < 8; ++q) {
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) cc[c] = cn[c];
-                    if (q < 7) lookup(buf[q + 1], cn);
-                    process(buf[q], cc, rel0 + (uint32_t)(q * 256), 15u, cb);
-                }
-            }
-        }
-        // what is left past the whole groups: up to eight pieces of 256 elements, the last one ragged; wave w takes piece w
-        const int tbase = ngroups * MAIN_GROUP;
-        if (tbase + (int)wave * 256 < span) {
-            const int pos = tbase + (int)wave * 256;
-            const int64_t j = c0 + pos + (int64_t)lane * 4;
-            const int nv = j < c1 ? ld.load4(j, buf[0]) : 0;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) if (c >= nv) buf[0][c] = 0u;
-            lookup(buf[0], cc);
-            process(buf[0], cc, (uint32_t)pos + lane * 4, (1u << nv) - 1u, cnt_of(pos / TILE));
-        }
-    } else {
     // Load n of a wave covers the 256 elements at c0 + (16 n + wave) * 256: the 16 waves read 16 KB side by
     // side.  Eight loads per lane stay in flight: a slot is refilled as soon as it has been processed.
     const int woff = (int)wave * 256;
@@ -709,7 +640,6 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
         for (int c = 0; c < 4; ++c) if (c >= nv) buf[0][c] = 0u;
         lookup(buf[0], cc);
         process(buf[0], cc, rel_of(nfull), (1u << nv) - 1u, cnt_of(nfull));
-    }
     }
     if (__ballot(maxkey >= 0x7F800000u) && lane == 0) atomicOr(a.dev_status, MLMC_DEV_NONFINITE);
     maxkey = wave_max(maxkey);
@@ -788,6 +718,7 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
 }
 
 // ---------------------------------------------------------------------------------------------------
+constexpr int MAIN_GROUP = 2048;   // elements a wave takes at a time: its eight loads in flight
 // The selection read with two workgroups per CU (plans whose chunks have four count chunks): a chunk is read by two
 // workgroups of 512 threads, two count chunks each, so that the table load, the flush and the move of the candidates of
 // one workgroup run beside the streaming of the other (with one workgroup per CU they overlap nothing: a tenth to a
@@ -795,6 +726,10 @@ __global__ __launch_bounds__(MAIN_THREADS) void k_main(TopkArgs a, int exact_pas
 // group and the tag follow from the key and the counter), counters for two count chunks.  Everything the workgroup
 // writes has the layout of k_main: sixteen private lists per chunk (this workgroup's eight waves use lists 8 h .. 8 h + 7),
 // entries {bits, offset in the CHUNK << 6 | tag}, counts per count chunk.
+// The waves take their workgroup's elements in groups of MAIN_GROUP consecutive ones handed out by an LDS counter, not in
+// fixed interleaved shares: the waves of a SIMD are served oldest first, so with fixed shares the oldest is done when the
+// youngest still has a third of its share left and the workgroup ends at a fraction of its wave slots; with the counter
+// all waves end within one group of each other.
 constexpr int M2_THREADS = 512;
 constexpr int M2_WAVES = M2_THREADS / 64;
 constexpr int M2_CSUB = 2;                                   // count chunks per workgroup
@@ -901,7 +836,10 @@ __global__ __launch_bounds__(M2_THREADS, 4) void k_main2(TopkArgs a) {
     uint32_t buf[8][4];
     uint32_t cc[4], cn[4];
     {
-        // groups of MAIN_GROUP elements from the counter, as in k_main<..., DYN>
+        // Groups of MAIN_GROUP elements from the counter; a wave holds the group it works on and the next one, whose
+        // loads refill the ring as those of the current one are consumed (no condition on a load of the steady-state
+        // loop, so that the waits can count them).  A wave takes at most gmax groups, which with one piece of the ragged
+        // end is what its private list has room for; together the waves have room for twice their elements.
         const int ngroups = span / MAIN_GROUP;
         const int gmax = (a.chunk / 8 - 256) / MAIN_GROUP;
         int taken = 0;
@@ -2403,22 +2341,18 @@ static mlmc_status launch_select(const mlmc_plan_t* pl, const TopkArgs& a, bool 
         MLMC_LAUNCH(kh, st, k_hist<DT, VEC><<<hgrid, HIST_THREADS, 0, st>>>(a, exact_pass));
         MLMC_LAUNCH(ks, st, k_scan<<<pl->M, 1024, 0, st>>>(a, exact_pass));
         if (exact_pass) {
-            if (sums) MLMC_LAUNCH(km, st, k_main<DT, VEC, true, true, false><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
-            else MLMC_LAUNCH(km, st, k_main<DT, VEC, false, true, false><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
+            if (sums) MLMC_LAUNCH(km, st, k_main<DT, VEC, true, true><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
+            else MLMC_LAUNCH(km, st, k_main<DT, VEC, false, true><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
         } else {
-            // chunks of 64 K elements or more: the waves share the chunk through a counter (shorter ones are not worth it,
-            // and their private lists would have no room for a whole group)
-            const bool dyn = pl->chunk >= 65536;
-            if (dyn && pl->csub == 4) {   // two workgroups per chunk, two per CU
+            // chunks of 64 K elements or more in four count chunks: two workgroups per chunk, two per CU
+            if (pl->chunk >= 65536 && pl->csub == 4) {
                 const dim3 grid2(2 * pl->chunks_per_row, pl->M);
                 if (sums) MLMC_LAUNCH(km, st, k_main2<DT, VEC, true><<<grid2, M2_THREADS, 0, st>>>(a));
                 else MLMC_LAUNCH(km, st, k_main2<DT, VEC, false><<<grid2, M2_THREADS, 0, st>>>(a));
             } else if (sums) {
-                if (dyn) MLMC_LAUNCH(km, st, k_main<DT, VEC, true, false, true><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
-                else MLMC_LAUNCH(km, st, k_main<DT, VEC, true, false, false><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
+                MLMC_LAUNCH(km, st, k_main<DT, VEC, true, false><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
             } else {
-                if (dyn) MLMC_LAUNCH(km, st, k_main<DT, VEC, false, false, true><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
-                else MLMC_LAUNCH(km, st, k_main<DT, VEC, false, false, false><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
+                MLMC_LAUNCH(km, st, k_main<DT, VEC, false, false><<<mgrid, MAIN_THREADS, 0, st>>>(a, exact_pass));
             }
         }
         // the redo round resolves every zone in the ranking launch alone (two launches fewer to pay for when, as
