@@ -61,6 +61,10 @@ def kernel_sources_digest():
     return h.hexdigest()
 
 
+# kernels that the library times under one name (mlmc_profile_*) and the kernel trace lists under their own
+_TRACE_NAME = {"k_main2": "k_main", "k_rtn_extract": "k_bits_extract", "k_sb_clear": "k_zero"}
+
+
 def measured_traffic(workload, kernel):
     """(HBM bytes per launch of `kernel`, provenance) from the committed rocprofv3 summary of this workload
     (FETCH_SIZE + WRITE_SIZE, scaled as the summary says).  The summary names the digest of the kernel sources it
@@ -74,7 +78,7 @@ def measured_traffic(workload, kernel):
         f = line.split()
         if line.startswith("kernel sources sha256:"):
             digest_prof = f[-1]
-        elif value is None and f and f[0].split("<")[0] == kernel and len(f) >= 3:   # first line of the kernel: its working launches
+        elif value is None and f and _TRACE_NAME.get(f[0].split("<")[0], f[0].split("<")[0]) == kernel and len(f) >= 3:   # first line of the kernel: its working launches
             try:
                 value = int((float(f[-2]) + float(f[-1])) * 1e6)
             except ValueError:
