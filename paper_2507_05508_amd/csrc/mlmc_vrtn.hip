@@ -220,10 +220,12 @@ mlmc_status rtn_compress(const mlmc_plan_t* pl, const BitsArgs& a, bool vec, boo
     if (gx > cap) gx = cap;
     if (gx < 1) gx = 1;
     const dim3 egrid(gx, M);
+    // with the plan's own probabilities the draw needs no norms: that read of the input is made only when they are asked for
+    const bool need_norms = pl->adaptive || !message || a.norms_user != nullptr;
 #define MLMC_RTN_STEPS(DT, VEC)                                                                                          \
     do {                                                                                                                \
         MLMC_LAUNCH(K_BITS_MAX, st, k_bits_smax<DT, VEC><<<sgrid, SMAX_THREADS, 0, st>>>(a));                            \
-        MLMC_LAUNCH(K_RTN_NORMS, st, k_rtn_norms<DT, VEC><<<ngrid, 256, 0, st>>>(a));                                     \
+        if (need_norms) MLMC_LAUNCH(K_RTN_NORMS, st, k_rtn_norms<DT, VEC><<<ngrid, 256, 0, st>>>(a));                     \
         MLMC_LAUNCH(K_RTN_DRAW, st, k_rtn_draw<<<(M + 63) / 64, 64, 0, st>>>(a, message ? 0 : 1));                        \
         if (message) MLMC_LAUNCH(K_BITS_EXTRACT, st, k_rtn_extract<DT, VEC><<<egrid, 256, 0, st>>>(a));                  \
     } while (0)

@@ -74,3 +74,9 @@ def test_plan_validation():
     assert rt2.num_planes == 2 + 5 + 9
     fb = P.Plan(P.MLMC_FBITS, 8, 1000, P.MLMC_F32, list(range(24)), P.mlmc_geometric_p(23), allocate=False)
     assert fb.num_planes == 10 and fb.sparse_capacity_worst == 0   # sign + 8 exponent bits + one mantissa digit (App. B)
+    # tuning hooks are refused for the kinds they do not apply to
+    tk = P.Plan(P.MLMC_TOPK, 4, 100_000, P.MLMC_F32, [10, 100, 100_000], None, allocate=False)
+    tk.set_overlap(True)
+    tk.set_overlap(False)
+    with pytest.raises(P.MlmcError):
+        bits.set_overlap(True)
