@@ -29,7 +29,8 @@ DEFAULT_WORKLOAD = "resnet50_adaptive_topk"
 
 
 def algorithmic_bytes(w, kernel, nnz_total, planes_bytes):
-    """Bytes the method itself has to move in one launch of `kernel` ('Kernels')."""
+    """Bytes the method itself has to move in one launch of `kernel`: one read of what it consumes, one write of what it
+    produces (no re-reads, no scratch lists)."""
     s_in = 2 if w.dtype == "bf16" else 4
     in_bytes = w.M * w.d * s_in
     if kernel in ("k_main", "k_bits_max", "k_bits_smax", "k_rtn_norms"):
