@@ -241,7 +241,7 @@ static mlmc_status plan_stopk(mlmc_plan_t** plan, int M, int64_t d, int in_dtype
     pl->s = s;
     pl->adaptive = true;
     pl->ntiles = (d + TILE - 1) / TILE;
-    pl->nblk = (int)((d + 8192 - 1) / 8192);
+    pl->nblk = (int)((d + 4096 - 1) / 4096);   // sort blocks: RS_TILE elements
     pl->bm_words = ((d + 31) / 32 + 3) / 4 * 4;   // whole 16-byte groups per row
     size_t off = 0;
     pl->off_bitmap = off;

@@ -15,8 +15,8 @@
 
 namespace mlmc {
 
-constexpr int RS_TILE = 8192;     // elements of one sort block
-constexpr int RS_THREADS = 256;   // four waves; wave w owns elements [2048 w, 2048 w + 2048) of the block, in order
+constexpr int RS_TILE = 4096;     // elements of one sort block
+constexpr int RS_THREADS = 256;   // four waves; wave w owns a quarter of the block, in order
 constexpr int RS_PER_WAVE = RS_TILE / (RS_THREADS / 64);
 constexpr int RS_GROUPS = RS_PER_WAVE / 64;   // 64-element groups of a wave
 
