@@ -40,11 +40,13 @@ __global__ __launch_bounds__(RS_THREADS) void k_rs_hist(StopkArgs a, const uint2
     const int64_t i0 = (int64_t)blk * RS_TILE;
     const int64_t i1 = i0 + RS_TILE < a.d ? i0 + RS_TILE : a.d;
     bool nonfinite = false;
-    for (int64_t i = i0 + tid; i < i1; i += RS_THREADS) {
-        const uint2 e = rs_load<DT, FIRST>(a, ld, src, row, i);
-        atomicAdd(&s_h[(e.x >> shift) & 255u], 1u);
-        if (FIRST) nonfinite |= e.x <= 0x7FFFFFFFu - 0x7F800000u;   // Inf / NaN keys (ordered by their bit pattern)
-    }
+    // the block's loads issued sixteen at a time per thread (a loop of single loads waits for each in turn)
+    batched_loop<RS_TILE / RS_THREADS, RS_THREADS>(0u, (uint32_t)(i1 - i0), (uint32_t)tid,
+        [&](uint32_t i) { return rs_load<DT, FIRST>(a, ld, src, row, i0 + i).x; },
+        [&](uint32_t, uint32_t key) {
+            atomicAdd(&s_h[(key >> shift) & 255u], 1u);
+            if (FIRST) nonfinite |= key <= 0x7FFFFFFFu - 0x7F800000u;   // Inf / NaN keys (ordered by their bit pattern)
+        });
     if (FIRST && __ballot(nonfinite) && lane_id() == 0) atomicOr(a.dev_status, MLMC_DEV_NONFINITE);
     __syncthreads();
     a.counts[((size_t)row * 256 + tid) * a.nblk + blk] = s_h[tid];
@@ -74,8 +76,8 @@ __global__ __launch_bounds__(1024) void k_rs_scan(StopkArgs a) {
 // addresses, so the writes come in runs instead of single 8-byte stores.
 template <int DT, bool FIRST>
 __global__ __launch_bounds__(RS_THREADS) void k_rs_scatter(StopkArgs a, const uint2* src, uint2* dst, int shift) {
-    __shared__ uint32_t s_hist[RS_THREADS / 64][256];
-    __shared__ uint32_t s_base[RS_THREADS / 64][256];   // slot in the block's digit-ordered staging area
+    __shared__ uint32_t s_hist[RS_THREADS / 64][256];   // per wave and digit: the count, then (in place) the slot in the block's digit-ordered staging area
+    uint32_t (*s_base)[256] = s_hist;
     __shared__ uint32_t s_gstart[256];                  // global position of the block's first pair of a digit minus its slot
     __shared__ uint32_t s_scan[RS_THREADS / 64 + 1];
     __shared__ uint2 s_stage[RS_TILE];
@@ -87,10 +89,15 @@ __global__ __launch_bounds__(RS_THREADS) void k_rs_scatter(StopkArgs a, const ui
     const int64_t b0 = (int64_t)blk * RS_TILE;
     const int64_t w0 = b0 + (int64_t)wave * RS_PER_WAVE;
     uint2 e[RS_GROUPS];
+    if (b0 + RS_TILE <= a.d) {   // a whole block (uniform): no bounds check between the loads, they are issued together
 #pragma unroll
-    for (int q = 0; q < RS_GROUPS; ++q) {
-        const int64_t i = w0 + q * 64 + lane;
-        e[q] = i < a.d ? rs_load<DT, FIRST>(a, ld, src, row, i) : make_uint2(0u, 0u);
+        for (int q = 0; q < RS_GROUPS; ++q) e[q] = rs_load<DT, FIRST>(a, ld, src, row, w0 + q * 64 + lane);
+    } else {
+#pragma unroll
+        for (int q = 0; q < RS_GROUPS; ++q) {
+            const int64_t i = w0 + q * 64 + lane;
+            e[q] = i < a.d ? rs_load<DT, FIRST>(a, ld, src, row, i) : make_uint2(0u, 0u);
+        }
     }
 #pragma unroll
     for (int q = 0; q < RS_GROUPS; ++q)
@@ -109,8 +116,9 @@ __global__ __launch_bounds__(RS_THREADS) void k_rs_scatter(StopkArgs a, const ui
         uint32_t run = slot0;
 #pragma unroll
         for (int w = 0; w < RS_THREADS / 64; ++w) {
+            const uint32_t c = s_hist[w][tid];
             s_base[w][tid] = run;
-            run += s_hist[w][tid];
+            run += c;
         }
     }
     __syncthreads();
@@ -174,18 +182,30 @@ __global__ __launch_bounds__(SN_WAVES * 64) void k_sb_norms(StopkArgs a, const u
         };
         uint32_t curE = 0xFFFFFFFFu;
         uint64_t slo = 0, shi = 0;
-        for (int64_t i = lo + lane; i < hi; i += 64) {
-            const uint32_t key = 0x7FFFFFFFu - sp[i].x;
-            const uint32_t E = key >> 23;
-            if (E != curE) {
-                if (curE != 0xFFFFFFFFu) flush(curE, slo, shi);
-                curE = E;
-                slo = 0;
-                shi = 0;
+        // eight loads of a lane in flight (past the segment's end: its last entry, ignored), consumed in order
+        for (int64_t i = lo + lane; i < hi; i += 64 * 8) {
+            uint32_t kx[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int64_t j = i + 64 * u;
+                kx[u] = sp[j < hi ? j : hi - 1].x;
             }
-            const uint64_t sq = sig_square(key);
-            slo += sq & 0xFFFFFFFFull;
-            shi += sq >> 32;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                if (i + 64 * u < hi) {
+                    const uint32_t key = 0x7FFFFFFFu - kx[u];
+                    const uint32_t E = key >> 23;
+                    if (E != curE) {
+                        if (curE != 0xFFFFFFFFu) flush(curE, slo, shi);
+                        curE = E;
+                        slo = 0;
+                        shi = 0;
+                    }
+                    const uint64_t sq = sig_square(key);
+                    slo += sq & 0xFFFFFFFFull;
+                    shi += sq >> 32;
+                }
+            }
         }
         if (curE != 0xFFFFFFFFu) flush(curE, slo, shi);
         wave_lds_sync();
