@@ -202,7 +202,8 @@ mlmc_status mlmc_compress_bits(const mlmc_plan_t *plan, const void *g, int64_t l
  * Worker side of Alg. 2 / Alg. 3 for the Round-to-Nearest ladder (MLMC_RTN plans; Sec. 3.3, App. G.2).  The residual of
  * level l is C^{b_l}(v) - C^{b_{l-1}}(v) = (2c / (D D')) k with the integers k_j = n_{b_l} D' - n_{b_{l-1}} D,
  * D = 2^{b_l} - 1, D' = 2^{b_{l-1}} - 1 (D' = 1, n = 0 for b_{l-1} = 0); Delta_l = (2c / (D D')) sqrt(sum_j k_j^2) with
- * the integer sum exact and rounded once to fp64 (Lemma 3.4).  Three reads of the input: largest entry, norms, codes.
+ * the integer sum exact and rounded once to fp64 (Lemma 3.4).  Three reads of the input: largest entry, norms, codes
+ * (two when the plan has its own probabilities and norms_out is NULL: the norms are then not computed).
  *   level: dev [M] int32 (out);  scale: dev [M][2] int32 (out): the bit patterns of c and of the coefficient
  *   fp32((2c / (D D')) / p_l) that the server multiplies k with;  planes: dev [M][num_planes][ceil(d/64)] uint64 (out):
  *   per row the planes of the codes n_{b_0} (b_0 of them, if b_0 > 0), n_{b_{l-1}} (if l > 1) and n_{b_l}, each code

@@ -9,7 +9,7 @@
 //                threshold that holds it with overwhelming probability; the buckets between zones are REGIONS whose
 //                elements lie wholly inside one band.  With known p the level is drawn here; with adaptive p it is
 //                predicted from the histogram.  Writes the class table: bucket -> {region, sum group, stage flag | zone}.
-//   k_main       the selection read: per region exact element counts (per chunk and per row) and exact sums of
+//   k_main2      (k_main for short rows and the redo round) the selection read: per region exact element counts (per chunk and per row) and exact sums of
 //                squared significands per (exponent, region); zone candidates and the members of the staged band
 //                go to per-wave private lists, the candidates from there to per-zone lists
 //   k_fhist      per (zone, slice): histogram of the candidates over the zone's own key range (that of its buckets,
