@@ -1,7 +1,7 @@
 // Bit-wise MLMC (Sec. 3.1 fixed point, App. B floating point) and the server aggregate (Alg. 2 / Alg. 3) on gfx950.
 //
-//   k_bits_prep     level draw of every row
-//   k_bits_smax     largest |g| key of a sample of every row (integer atomic max) -> predicted power-of-two scale   [mlmc_extract.h]
+//   k_bits_prep     level draw of every row (floating-point ladder; the other ladders draw in k_bits_smax)
+//   k_bits_smax     largest |g| key of a sample of every row -> predicted power-of-two scale; level draw             [mlmc_extract.h]
 //   k_bits_extract  the one full read: digits floor(|g_j| / s * 2^F), sign plane + field planes packed by wave      [mlmc_extract.h]
 //                   ballot, and the true row maximum; a row whose true maximum has a larger exponent than the
 //                   sampled one is extracted again by a second launch (which returns at once for every other row)
@@ -401,8 +401,9 @@ mlmc_status message_bits(const mlmc_plan_t* pl, const int32_t* level, unsigned l
 // ---------------------------------------------------------------------------------------------------
 mlmc_status vbits_extract(const mlmc_plan_t* pl, const BitsArgs& a, bool vec, dim3 egrid, hipStream_t st);   // mlmc_vrtn.hip
 
-mlmc_status bits_compress(const mlmc_plan_t* pl, const BitsArgs& a, bool vec, hipStream_t st) {
-    MLMC_LAUNCH(K_DRAW, st, k_bits_prep<<<1, 1024, 0, st>>>(a));
+mlmc_status bits_compress(const mlmc_plan_t* pl, const BitsArgs& a0, bool vec, hipStream_t st) {
+    BitsArgs a = a0;
+    if (a.flt) MLMC_LAUNCH(K_DRAW, st, k_bits_prep<<<1, 1024, 0, st>>>(a));
     // a wave takes about four tiles (its loads run ahead across tiles); at least some 2048 waves in all
     int64_t ntiles = pl->ntiles;
     int gx = (int)((ntiles + 15) / 16);
@@ -440,12 +441,15 @@ mlmc_status bits_compress(const mlmc_plan_t* pl, const BitsArgs& a, bool vec, hi
     if (sw > scap) sw = scap;
     if (sw < 1) sw = 1;
     const dim3 sgrid((unsigned)sw, pl->M);
+    // the first launch of the call: its workgroups leave one maximum each (nothing to clear beforehand) and draw the levels
+    static_assert(1024 <= SMAX_PARTS_MAX, "sw is at most 1024");
+    a.smax_parts = (int32_t)sw;
     if (pl->dtype == MLMC_F32) {
-        if (vec) MLMC_LAUNCH(K_BITS_MAX, st, k_bits_smax<MLMC_F32, true><<<sgrid, SMAX_THREADS, 0, st>>>(a));
-        else MLMC_LAUNCH(K_BITS_MAX, st, k_bits_smax<MLMC_F32, false><<<sgrid, SMAX_THREADS, 0, st>>>(a));
+        if (vec) MLMC_LAUNCH(K_BITS_MAX, st, k_bits_smax<MLMC_F32, true, true><<<sgrid, SMAX_THREADS, 0, st>>>(a));
+        else MLMC_LAUNCH(K_BITS_MAX, st, k_bits_smax<MLMC_F32, false, true><<<sgrid, SMAX_THREADS, 0, st>>>(a));
     } else {
-        if (vec) MLMC_LAUNCH(K_BITS_MAX, st, k_bits_smax<MLMC_BF16, true><<<sgrid, SMAX_THREADS, 0, st>>>(a));
-        else MLMC_LAUNCH(K_BITS_MAX, st, k_bits_smax<MLMC_BF16, false><<<sgrid, SMAX_THREADS, 0, st>>>(a));
+        if (vec) MLMC_LAUNCH(K_BITS_MAX, st, k_bits_smax<MLMC_BF16, true, true><<<sgrid, SMAX_THREADS, 0, st>>>(a));
+        else MLMC_LAUNCH(K_BITS_MAX, st, k_bits_smax<MLMC_BF16, false, true><<<sgrid, SMAX_THREADS, 0, st>>>(a));
     }
     const bool small = pl->nplanes <= 9;
     if (a.vmx) return vbits_extract(pl, a, vec, egrid, st);   // the maxima above are exact (every block was read): one extraction

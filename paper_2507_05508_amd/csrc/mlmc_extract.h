@@ -8,10 +8,30 @@ namespace mlmc {
 
 // Largest |g| key of the sampled blocks of every row (block b of 1024 elements is sampled when b % S == S / 2,
 // S = 2^sample_shift; S = 1 reads the whole row and the result is the row maximum itself).
+// PARTS: nothing is cleared beforehand, so no launch precedes this one: every workgroup stores its own maximum (the
+// readers take the largest of a row's, row_smpmax), and the first workgroup of a row draws the row's level (Alg. 2
+// "Sample l ~ p") and sets the state that the extraction accumulates into to its start values.
 constexpr int SMAX_THREADS = 512;
-template <int DT, bool VEC>
+template <int DT, bool VEC, bool PARTS>
 __global__ __launch_bounds__(SMAX_THREADS) void k_bits_smax(BitsArgs a) {
     const int row = blockIdx.y;
+    if (PARTS && blockIdx.x == 0) {   // uniform over the workgroup
+        __shared__ double s_p[LMAX];
+        if ((int)threadIdx.x < a.L) s_p[threadIdx.x] = a.p_fixed[threadIdx.x];
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            if (row == 0) *a.dev_status = 0;   // no workgroup of this launch reports through it
+            const uint32_t x = philox_word0(a.seed, a.step, (uint32_t)row);
+            const int level = draw_from_p(s_p, a.L, x);
+            const double pl = s_p[level - 1];
+            RowInfo* ri = a.rinfo + row;
+            ri->level = level;
+            ri->weight = pl == 0.0 ? 0.0f : (float)__ddiv_rn(1.0, pl);
+            ri->draw_x = x;
+            a.level[row] = level;
+            a.racc[row].rowmax_key = 0u;
+        }
+    }
     const int64_t S = (int64_t)1 << a.sample_shift, first = S >> 1;
     const int64_t nblk = (a.d + 1023) / 1024;
     const int64_t ns = nblk > first ? (nblk - first + S - 1) / S : 0;
@@ -51,10 +71,34 @@ __global__ __launch_bounds__(SMAX_THREADS) void k_bits_smax(BitsArgs a) {
         if (more1) reduce(b1);
     }
     maxkey = wave_max(maxkey);
-    if (lane == 0 && maxkey) {
+    if (PARTS) {
+        // a non-finite entry is reported by the extraction, which sees every entry
+        __shared__ uint32_t s_wmax[SMAX_THREADS / 64];
+        if (lane == 0) s_wmax[wave] = maxkey;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            uint32_t m = 0;
+#pragma unroll
+            for (int w = 0; w < SMAX_THREADS / 64; ++w) m = s_wmax[w] > m ? s_wmax[w] : m;
+            ((uint32_t*)a.racc[row].gsum)[blockIdx.x] = m;
+        }
+    } else if (lane == 0 && maxkey) {
         atomicMax(&a.racc[row].smpmax_key, maxkey);
         if (maxkey >= 0x7F800000u) atomicOr(a.dev_status, MLMC_DEV_NONFINITE);
     }
+}
+
+// The largest key k_bits_smax found in a row (every lane of the calling wave gets it).
+__device__ __forceinline__ uint32_t row_smpmax(const BitsArgs& a, int row) {
+    const RowAcc* ra = a.racc + row;
+    if (a.smax_parts == 0) return ra->smpmax_key;
+    const uint32_t* part = (const uint32_t*)ra->gsum;
+    uint32_t m = 0;
+    for (int i = (int)lane_id(); i < a.smax_parts; i += 64) {
+        const uint32_t v = part[i];
+        m = v > m ? v : m;
+    }
+    return wave_max(m);
 }
 
 // v_writelane_b32 through its compiler intrinsic (this compiler has no builtin of that name): the result is `old`
@@ -318,7 +362,8 @@ __global__ __launch_bounds__(256) void k_bits_extract(BitsArgs a) {
     uint32_t* slds = s_tr[threadIdx.x >> 6];
     const int row = blockIdx.y;
     RowAcc* ra = a.racc + row;
-    const uint32_t Es = ra->smpmax_key >> 23;
+    const uint32_t smpmax = row_smpmax(a, row);
+    const uint32_t Es = smpmax >> 23;
     uint32_t Ex = Es;
     if (REDO) {
         Ex = ra->rowmax_key >> 23;
@@ -331,7 +376,7 @@ __global__ __launch_bounds__(256) void k_bits_extract(BitsArgs a) {
     if (KIND == 0 && blockIdx.x == 0 && threadIdx.x == 0) a.scale_exp[row] = Emax - 126;
     uint32_t maxkey = 0;
     if constexpr (KIND == 2) {
-        const uint32_t vkey = ra->smpmax_key;   // the largest |g| of the row
+        const uint32_t vkey = smpmax;   // the largest |g| of the row
         if (blockIdx.x == 0 && threadIdx.x == 0) a.scale_exp[row] = (int32_t)vkey;
         const uint32_t vE = vkey >> 23;
         const double vd = ldexp((double)(vE ? (vkey & 0x7FFFFFu) | 0x800000u : vkey), (int)(vE ? vE : 1u) - 150);

@@ -102,6 +102,8 @@ struct RowAcc {  // per row, zeroed at the start of every call (and again before
     uint64_t gsum[GMAX][2];
     Piece pieces[PMAX];
 };
+constexpr int SMAX_PARTS_MAX = 1024;   // bit-wise path: per-workgroup maxima of a row, kept in the words of gsum (unused there)
+static_assert(sizeof(uint64_t) * GMAX * 2 >= sizeof(uint32_t) * SMAX_PARTS_MAX, "the per-workgroup maxima fit in gsum");
 
 struct TopkArgs {
     const void* g;
@@ -163,7 +165,8 @@ struct BitsArgs {
     int32_t vmx;             // 1: fixed-point ladder of |g| / max|g| (the scale field carries the bits of max|g|)
     int32_t rtn;             // 1: Round-to-Nearest ladder: F are bit widths, the scale field is [M][2]: bits of c, bits of the coefficient
     int32_t adaptive;        // RTN: 1 = probabilities from the row's residual norms (Lemma 3.4)
-    int32_t pad_;
+    int32_t smax_parts;      // > 0: k_bits_smax left the maxima of its workgroups (this many per row) in the row's gsum words instead of
+                             // one atomic maximum in smpmax_key, which would have to be cleared by a launch before it
     unsigned long long* rtn_sums;   // RTN: [M][L][2] sums of squared residual integers, low and high 32-bit halves (zeroed per call)
     double* norms;           // RTN: [M][L]
     double* norms_user;      // RTN: optional copy

@@ -224,7 +224,7 @@ mlmc_status rtn_compress(const mlmc_plan_t* pl, const BitsArgs& a, bool vec, boo
     const bool need_norms = pl->adaptive || !message || a.norms_user != nullptr;
 #define MLMC_RTN_STEPS(DT, VEC)                                                                                          \
     do {                                                                                                                \
-        MLMC_LAUNCH(K_BITS_MAX, st, k_bits_smax<DT, VEC><<<sgrid, SMAX_THREADS, 0, st>>>(a));                            \
+        MLMC_LAUNCH(K_BITS_MAX, st, k_bits_smax<DT, VEC, false><<<sgrid, SMAX_THREADS, 0, st>>>(a));                            \
         if (need_norms) MLMC_LAUNCH(K_RTN_NORMS, st, k_rtn_norms<DT, VEC><<<ngrid, 256, 0, st>>>(a));                     \
         MLMC_LAUNCH(K_RTN_DRAW, st, k_rtn_draw<<<(M + 63) / 64, 64, 0, st>>>(a, message ? 0 : 1));                        \
         if (message) MLMC_LAUNCH(K_BITS_EXTRACT, st, k_rtn_extract<DT, VEC><<<egrid, 256, 0, st>>>(a));                  \
