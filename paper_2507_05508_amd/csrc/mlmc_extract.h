@@ -70,21 +70,21 @@ __global__ __launch_bounds__(SMAX_THREADS) void k_bits_smax(BitsArgs a) {
         if (more2) fetch(i + 2 * istride, b0);
         if (more1) reduce(b1);
     }
+    // the waves' maxima meet in LDS: atomics of many waves on one address take turns
     maxkey = wave_max(maxkey);
-    if (PARTS) {
-        // a non-finite entry is reported by the extraction, which sees every entry
-        __shared__ uint32_t s_wmax[SMAX_THREADS / 64];
-        if (lane == 0) s_wmax[wave] = maxkey;
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            uint32_t m = 0;
+    __shared__ uint32_t s_wmax[SMAX_THREADS / 64];
+    if (lane == 0) s_wmax[wave] = maxkey;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t m = 0;
 #pragma unroll
-            for (int w = 0; w < SMAX_THREADS / 64; ++w) m = s_wmax[w] > m ? s_wmax[w] : m;
-            ((uint32_t*)a.racc[row].gsum)[blockIdx.x] = m;
+        for (int w = 0; w < SMAX_THREADS / 64; ++w) m = s_wmax[w] > m ? s_wmax[w] : m;
+        if (PARTS) {
+            ((uint32_t*)a.racc[row].gsum)[blockIdx.x] = m;   // a non-finite entry is reported by the extraction, which sees every entry
+        } else if (m) {
+            atomicMax(&a.racc[row].smpmax_key, m);
+            if (m >= 0x7F800000u) atomicOr(a.dev_status, MLMC_DEV_NONFINITE);
         }
-    } else if (lane == 0 && maxkey) {
-        atomicMax(&a.racc[row].smpmax_key, maxkey);
-        if (maxkey >= 0x7F800000u) atomicOr(a.dev_status, MLMC_DEV_NONFINITE);
     }
 }
 
@@ -412,10 +412,19 @@ __global__ __launch_bounds__(256) void k_bits_extract(BitsArgs a) {
         }
     }
     if (!REDO) {
+        // one atomic per workgroup (the workgroups of a launch end together, and atomics on one address take turns)
         maxkey = wave_max(maxkey);
-        if (lane_id() == 0 && maxkey) {
-            atomicMax(&ra->rowmax_key, maxkey);
-            if (maxkey >= 0x7F800000u) atomicOr(a.dev_status, MLMC_DEV_NONFINITE);
+        __syncthreads();   // every wave is done with its transposing buffer
+        if (lane_id() == 0) s_tr[0][threadIdx.x >> 6] = maxkey;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            uint32_t m = s_tr[0][0];
+#pragma unroll
+            for (int w = 1; w < 4; ++w) m = s_tr[0][w] > m ? s_tr[0][w] : m;
+            if (m) {
+                atomicMax(&ra->rowmax_key, m);
+                if (m >= 0x7F800000u) atomicOr(a.dev_status, MLMC_DEV_NONFINITE);
+            }
         }
     }
 }
