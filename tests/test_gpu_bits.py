@@ -142,3 +142,43 @@ def test_bits_sampled_scale_is_proven_or_redone(shift):
             out = P.mlmc_aggregate(plan, msg, 0.5)
             torch.cuda.synchronize()
             assert np.array_equal(out.cpu().numpy().view(np.uint32), O.aggregate_bits(want, Fl, d, 0.5).view(np.uint32))
+
+
+@pytest.mark.parametrize("kind", ["bits", "vbits", "fbits", "rtn"])
+@pytest.mark.parametrize("d", [100_003, (1 << 21) + 3 * 4096 + 77])
+def test_workspace_contents_on_entry_do_not_matter(kind, d):
+    """The calls expect nothing in the workspace: with every byte of it set to 0xFF or 0x5A beforehand the message,
+    the status word and the aggregate are those of a call on a workspace as allocated.  (The fixed-point kinds start
+    with the maximum kernel, no clearing launch before it; the longer rows take the sampled maximum.)"""
+    M = 3
+    w = W.scaled(W.WORKLOADS["resnet18_bits"], d=d, M=M)
+    G = W.generate(w)
+    G[1] *= np.float32(1e-3)
+    g = to_device(G)
+    if kind == "rtn":
+        plan = P.Plan(P.MLMC_RTN, M, d, P.MLMC_F32, [0, 2, 4, 8], None)
+        compress = P.mlmc_compress_rtn
+    else:
+        F = [0, 1, 2, 4, 8, 16] if kind != "fbits" else [0, 1, 2, 4, 8, 16, 23]
+        code = {"bits": P.MLMC_BITS, "vbits": P.MLMC_VBITS, "fbits": P.MLMC_FBITS}[kind]
+        plan = P.Plan(code, M, d, P.MLMC_F32, F, O.geometric_p(len(F) - 1))
+        compress = P.mlmc_compress_bits
+
+    def run(step):
+        msg = compress(plan, g, seed=21, step=step)
+        out = P.mlmc_aggregate(plan, msg, 1.0 / M)
+        torch.cuda.synchronize()
+        got = [msg.level.cpu().numpy(), msg.scale_exp.cpu().numpy(), msg.planes.cpu().numpy(), out.cpu().numpy().view(np.uint32)]
+        if msg.norms is not None:
+            got.append(msg.norms.cpu().numpy().view(np.uint64))
+        return got, plan.status(informational=True)
+
+    for step in range(3):
+        print(f"workspace {kind} d={d} step={step}", flush=True)
+        want, want_status = run(step)
+        for fill in (0xFF, 0x5A):
+            plan.ws.fill_(fill)
+            got, status = run(step)
+            assert status == want_status
+            for a, b in zip(got, want):
+                assert np.array_equal(a, b), (kind, step, hex(fill))
