@@ -182,3 +182,37 @@ def test_workspace_contents_on_entry_do_not_matter(kind, d):
             assert status == want_status
             for a, b in zip(got, want):
                 assert np.array_equal(a, b), (kind, step, hex(fill))
+
+
+@pytest.mark.parametrize("where", ["first", "middle", "last"])
+def test_bits_one_long_row_every_workgroup_maximum_counts(where):
+    """One worker and a row long enough that the maximum kernel runs with its largest grid (1024 workgroups for the
+    row, each leaving its own maximum): the row's largest entry sits in the first block, in a middle one or in the
+    ragged last one, and both fixed-point kinds (power-of-two scale from every block; largest entry itself) must find it."""
+    d = 8192 * 1024 + 3 * 1024 + 77
+    w = W.scaled(W.WORKLOADS["resnet18_bits"], d=d, M=1)
+    G = W.generate(w)
+    at = {"first": 3, "middle": 4099 * 1024 + 511, "last": d - 2}[where]
+    G[0, at] = np.float32(-7.25) * np.abs(G[0]).max()
+    g = to_device(G)
+    F = [0, 1, 2, 4, 8, 16]
+    p = O.geometric_p(5)
+    print(f"long row, maximum in the {where} block: bits", flush=True)
+    plan = P.Plan(P.MLMC_BITS, 1, d, P.MLMC_F32, F, p)
+    plan.set_sampling(0)
+    msg = P.mlmc_compress_bits(plan, g, seed=9, step=1)
+    want = _check_bits(plan, G, F, p, 9, 1, msg)
+    assert plan.status(informational=True) == 0   # every block was read: nothing to redo
+    out = P.mlmc_aggregate(plan, msg, 1.0)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy().view(np.uint32), O.aggregate_bits(want, F, d, 1.0).view(np.uint32))
+    print(f"long row, maximum in the {where} block: vbits", flush=True)
+    planv = P.Plan(P.MLMC_VBITS, 1, d, P.MLMC_F32, F, p)
+    msgv = P.mlmc_compress_bits(planv, g, seed=9, step=1)
+    torch.cuda.synchronize()
+    wantv = O.compress_vbits(G, F, p, 9, 1)
+    assert int(msgv.level.cpu().numpy()[0]) == wantv[0]["level"]
+    assert msgv.scale_exp.cpu().numpy().view(np.uint32)[0] == np.float32(wantv[0]["vmax"]).view(np.uint32)
+    n = wantv[0]["planes"].shape[0]
+    assert np.array_equal(msgv.planes.cpu().numpy().view(np.uint64)[0, :n], wantv[0]["planes"])
+    assert planv.status() == 0
